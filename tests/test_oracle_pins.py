@@ -1,0 +1,333 @@
+"""Pins for the CPU oracle: it is checked against things other than itself.
+
+The paper prints no worked numeric example of a layer, so nothing here is a paper-printed
+value.  What fixes the oracle instead: invariants the paper's structure implies (Section 2:
+the all-reduce of row/column-split partials reproduces the unsharded layer; decode re-evaluates
+the prefill formulas for one more row), causality, closed forms, special cases that collapse to
+library routines (torch CPU, float64), and a cache-free dense brute force on the tiny stage.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as Fnn
+
+from oracle import stage_oracle as so
+from workloads import CONFIGS, generate
+
+TINY = CONFIGS["tiny_f32"]
+
+
+def rel(a, b):
+    return float(np.linalg.norm(a - b) / np.linalg.norm(b))
+
+
+def make_stage(cfg, rank, tp=None, n_layers=None, weights=None):
+    tp = cfg.tp_degree if tp is None else tp
+    L = cfg.n_layers if n_layers is None else n_layers
+    st = so.OracleStage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, L, tp, rank,
+                        cfg.rms_eps, cfg.rope_theta)
+    for l in range(L):
+        w = weights[l] if weights is not None else generate.layer_weights(cfg, l)
+        st.load_layer(l, *[w[k] for k in generate.LAYER_TENSOR_ORDER])
+    return st
+
+
+@pytest.fixture(scope="module")
+def tiny_weights():
+    return [generate.layer_weights(TINY, l) for l in range(TINY.n_layers)]
+
+
+# ------------------------------------------------------------------------------------------
+# an independent, cache-free, unsharded reference built from torch library routines (float64)
+# ------------------------------------------------------------------------------------------
+def rope_complex(x, pos, theta):
+    """Rotation written as a complex multiplication: (x_i + 1j*x_{i+d/2}) * exp(1j*p*theta^(-2i/d))."""
+    d = x.shape[-1]
+    z = torch.complex(x[..., : d // 2], x[..., d // 2:])
+    freq = torch.tensor([theta ** (-2.0 * i / d) for i in range(d // 2)], dtype=torch.float64)
+    ang = pos.to(torch.float64)[:, None] * freq[None, :]
+    z = z * torch.polar(torch.ones_like(ang), ang)[:, None, :]
+    return torch.cat([z.real, z.imag], dim=-1)
+
+
+def dense_layer_torch(cfg, w, x):
+    """One unsharded layer on one sequence x [S,H], no cache: full [S,S] scores with an explicit
+    -inf upper triangle, KV heads replicated G times so attention is plain multi-head."""
+    W = {k: v.to(torch.float64) for k, v in w.items()}
+    S, H, d, G = x.shape[0], cfg.hidden, cfg.head_dim, cfg.group
+    n = Fnn.rms_norm(x, (H,), W["g_attn"], cfg.rms_eps)
+    q = Fnn.linear(n, W["wq"].T).view(S, cfg.n_heads, d)
+    k = Fnn.linear(n, W["wk"].T).view(S, cfg.n_kv_heads, d)
+    v = Fnn.linear(n, W["wv"].T).view(S, cfg.n_kv_heads, d)
+    pos = torch.arange(S)
+    q, k = rope_complex(q, pos, cfg.rope_theta), rope_complex(k, pos, cfg.rope_theta)
+    k = k.repeat_interleave(G, dim=1)
+    v = v.repeat_interleave(G, dim=1)
+    mask = torch.full((S, S), float("-inf"), dtype=torch.float64).triu(1)
+    o = Fnn.scaled_dot_product_attention(q.transpose(0, 1), k.transpose(0, 1), v.transpose(0, 1),
+                                         attn_mask=mask, scale=1.0 / math.sqrt(d))
+    h = x + Fnn.linear(o.transpose(0, 1).reshape(S, H), W["wo"].T)
+    n2 = Fnn.rms_norm(h, (H,), W["g_ffn"], cfg.rms_eps)
+    u = Fnn.silu(Fnn.linear(n2, W["w1"].T)) * Fnn.linear(n2, W["w3"].T)
+    return h, Fnn.linear(u, W["w2"].T)
+
+
+def dense_stage_torch(cfg, weights, x):
+    """Returns (last FFN output without residual, residual it is added to), like the stage."""
+    h = x.to(torch.float64)
+    for l, w in enumerate(weights):
+        h, p = dense_layer_torch(cfg, w, h)
+        if l == len(weights) - 1:
+            return p.numpy(), h.numpy()
+        h = h + p
+
+
+# ------------------------------------------------------------------------------------------
+def test_unsharded_matches_dense_bruteforce(tiny_weights):
+    x = generate.hidden_rows(TINY, 32)
+    st = make_stage(TINY, 0, tp=1, weights=tiny_weights)
+    p, h = st.prefill(st.new_cache(1), x, [32])
+    p_ref, h_ref = dense_stage_torch(TINY, tiny_weights, x)
+    assert rel(h, h_ref) < 1e-12
+    assert rel(p, p_ref) < 1e-12
+
+
+def test_shard_sum_equals_unsharded(tiny_weights):
+    """Sum over ranks of the partials == the unsharded sub-layer output, at both reduce points
+    and through the whole 2-layer stage (bound 1e-5 relative; in float64 it is ~1e-15)."""
+    x = generate.hidden_rows(TINY, 32)
+    seqs = [0] * 32
+    full = make_stage(TINY, 0, tp=1, weights=tiny_weights)
+    for t in (2,):
+        ranks = [make_stage(TINY, r, tp=t, weights=tiny_weights) for r in range(t)]
+        h = so._f64(x)
+        pa = sum(st.attn_partial(0, st.new_cache(1), h, seqs) for st in ranks)
+        pa_full = full.attn_partial(0, full.new_cache(1), h, seqs)
+        assert rel(pa, pa_full) < 1e-12
+        pf = sum(st.ffn_partial(0, h) for st in ranks)
+        assert rel(pf, full.ffn_partial(0, h)) < 1e-12
+        parts, resid = so.group_forward(ranks, [st.new_cache(1) for st in ranks], x, seqs)
+        p_full, h_full = full.prefill(full.new_cache(1), x, [32])
+        assert rel(resid + sum(parts), h_full + p_full) < 1e-12
+        assert rel(resid, h_full) < 1e-12
+
+
+def test_tp1_partial_is_full_output(tiny_weights):
+    """|d| = 1 is the degenerate case with no communication: the partial is the whole output."""
+    x = generate.hidden_rows(TINY, 8)
+    st = make_stage(TINY, 0, tp=1, weights=tiny_weights)
+    p, h = st.prefill(st.new_cache(1), x, [8])
+    p_ref, h_ref = dense_stage_torch(TINY, tiny_weights, x)
+    assert rel(h + p, h_ref + p_ref) < 1e-12
+
+
+def test_decode_reproduces_prefill_rows(tiny_weights):
+    """Teacher-forced: prefill(X[:n]) then decode fed X[n+k] equals row n+k of prefill(X[:n+m])."""
+    n, m = 20, 6
+    X = generate.hidden_rows(TINY, n + m)
+    for rank in (0, 1):
+        st = make_stage(TINY, rank, weights=tiny_weights)
+        p_all, h_all = st.prefill(st.new_cache(1), X, [n + m])
+        cache = st.new_cache(1)
+        st.prefill(cache, X[:n], [n])
+        for k in range(m):
+            p, h = st.decode(cache, X[n + k: n + k + 1])
+            assert rel(p[0], p_all[n + k]) < 1e-10
+            assert rel(h[0], h_all[n + k]) < 1e-10
+
+
+def test_batched_ragged_equals_separate_sequences(tiny_weights):
+    """No attention across sequences: a packed ragged batch equals each sequence run alone."""
+    lens = [5, 1, 9]
+    X = generate.hidden_rows(TINY, sum(lens))
+    st = make_stage(TINY, 1, weights=tiny_weights)
+    p, h = st.prefill(st.new_cache(3), X, lens)
+    off = 0
+    for n in lens:
+        p1, h1 = st.prefill(st.new_cache(1), X[off: off + n], [n])
+        assert rel(p[off: off + n], p1) < 1e-13 and rel(h[off: off + n], h1) < 1e-13
+        off += n
+
+
+def test_causality_bit_for_bit(tiny_weights):
+    X = so._f64(generate.hidden_rows(TINY, 24))
+    st = make_stage(TINY, 0, weights=tiny_weights)
+    p0, h0 = st.prefill(st.new_cache(1), X, [24])
+    i = 10
+    X2 = X.copy()
+    X2[i + 1:] += np.random.default_rng(7).standard_normal(X2[i + 1:].shape)
+    p1, h1 = st.prefill(st.new_cache(1), X2, [24])
+    assert np.array_equal(p0[: i + 1], p1[: i + 1]) and np.array_equal(h0[: i + 1], h1[: i + 1])
+    assert not np.array_equal(p0[i + 1:], p1[i + 1:])
+
+
+def test_gqa_equals_mha_with_replicated_kv_heads(tiny_weights):
+    """Replicating every KV head G times (columns of W_K, W_V) and declaring hkv = hq gives the
+    same output: pins the query-head -> KV-head map j // G."""
+    cfg, d, G = TINY, TINY.head_dim, TINY.group
+    x = generate.hidden_rows(cfg, 12)
+    st = make_stage(cfg, 0, tp=1, n_layers=1, weights=tiny_weights)
+    w = dict(tiny_weights[0])
+    for name in ("wk", "wv"):
+        m = w[name].view(cfg.hidden, cfg.n_kv_heads, d)
+        w[name] = m.repeat_interleave(G, dim=1).reshape(cfg.hidden, cfg.n_heads * d)
+    mha = so.OracleStage(cfg.hidden, cfg.n_heads, cfg.n_heads, cfg.ffn, 1, 1, 0)
+    mha.load_layer(0, *[w[k] for k in generate.LAYER_TENSOR_ORDER])
+    a = st.attn_partial(0, st.new_cache(1), so._f64(x), [0] * 12)
+    b = mha.attn_partial(0, mha.new_cache(1), so._f64(x), [0] * 12)
+    assert rel(a, b) < 1e-13
+
+
+def test_single_token_attention_returns_v0(tiny_weights):
+    """One position: softmax over a single score is 1, so o_j = v of KV head j // G."""
+    cfg, d = TINY, TINY.head_dim
+    st = make_stage(cfg, 1, n_layers=1, weights=tiny_weights)
+    x = so._f64(generate.hidden_rows(cfg, 1))
+    W = st.layers[0]
+    n = so.rmsnorm(x, W["g_attn"], cfg.rms_eps)
+    v = (n @ W["wv"]).reshape(st.hkv_l, d)
+    o = np.concatenate([v[j // st.G] for j in range(st.hq_l)])
+    got = st.attn_partial(0, st.new_cache(1), x, [0])
+    assert rel(got[0], o @ W["wo"]) < 1e-13
+
+
+def test_equal_cached_v_rows_closed_form(tiny_weights):
+    """Cached V rows all equal to one row `vrow`, and W_V = 0 so the new row's own v is 0: whatever
+    the scores, o_j = (1 - w_new) * vrow[j // G], w_new being the softmax weight of the new row."""
+    cfg = TINY
+    st = make_stage(cfg, 0, n_layers=1, weights=tiny_weights)
+    cache = st.new_cache(1)
+    rng = np.random.default_rng(3)
+    vrow = rng.standard_normal((1, st.hkv_l, st.d))
+    K = rng.standard_normal((9, st.hkv_l, st.d))
+    cache.fill(0, 0, K, np.repeat(vrow, 9, axis=0))
+    st.layers[0]["wv"] = np.zeros_like(st.layers[0]["wv"])
+    x = so._f64(generate.hidden_rows(cfg, 1))
+    got = st.attn_partial(0, cache, x, [0])
+    W = st.layers[0]
+    n = so.rmsnorm(x, W["g_attn"], cfg.rms_eps)
+    q = so.rope((n @ W["wq"]).reshape(1, st.hq_l, st.d), np.array([9]), cfg.rope_theta)[0]
+    Kall = cache.k[0][0]
+    assert Kall.shape[0] == 10
+    o = []
+    for j in range(st.hq_l):
+        s = Kall[:, j // st.G, :] @ q[j] / math.sqrt(st.d)
+        wnew = math.exp(s[-1] - s.max()) / np.exp(s - s.max()).sum()
+        o.append((1.0 - wnew) * vrow[0, j // st.G])
+    assert rel(got[0], np.concatenate(o) @ W["wo"]) < 1e-12
+
+
+def test_rope_closed_forms():
+    rng = np.random.default_rng(0)
+    d, theta = 64, 10000.0
+    x = rng.standard_normal((5, 3, d))
+    # position 0 is the identity
+    assert np.array_equal(so.rope(x, np.zeros(5, dtype=int), theta), x)
+    # each (i, i + d/2) pair keeps its norm
+    pos = np.array([1, 7, 100, 1023, 4095])
+    y = so.rope(x, pos, theta)
+    assert np.allclose(x[..., : d // 2] ** 2 + x[..., d // 2:] ** 2,
+                       y[..., : d // 2] ** 2 + y[..., d // 2:] ** 2, rtol=1e-12)
+    # relative-position property: <R_m q, R_n k> = <R_{m-n} q, k>
+    q, k = rng.standard_normal((1, 1, d)), rng.standard_normal((1, 1, d))
+    for m, n in [(5, 3), (100, 37), (4000, 3999)]:
+        lhs = np.sum(so.rope(q, np.array([m]), theta) * so.rope(k, np.array([n]), theta))
+        rhs = np.sum(so.rope(q, np.array([m - n]), theta) * k)
+        assert abs(lhs - rhs) < 1e-9
+    # the angle itself, and the direction of rotation: pair i of e_i at position p -> (cos, sin)
+    p, i = 3, 5
+    e = np.zeros((1, 1, d)); e[0, 0, i] = 1.0
+    y = so.rope(e, np.array([p]), theta)[0, 0]
+    ang = p * theta ** (-2.0 * i / d)
+    assert abs(y[i] - math.cos(ang)) < 1e-15 and abs(y[i + d // 2] - math.sin(ang)) < 1e-15
+    # against the complex-multiplication form
+    xt = torch.from_numpy(x)
+    assert np.allclose(so.rope(x, pos, theta), rope_complex(xt, torch.from_numpy(pos), theta).numpy(),
+                       rtol=1e-12, atol=1e-12)
+
+
+def test_rmsnorm_closed_forms():
+    H, eps = 512, 1e-5
+    g = 1.0 + 0.02 * np.random.default_rng(1).standard_normal(H)
+    for c in (2.5, -0.3):
+        out = so.rmsnorm(np.full((1, H), c), g, eps)
+        assert np.allclose(out[0], np.sign(c) * g / math.sqrt(1.0 + eps / c ** 2), rtol=1e-13)
+    x = np.random.default_rng(2).standard_normal((4, H))
+    out = so.rmsnorm(x, np.ones(H), 0.0)
+    assert np.allclose(np.sqrt(np.mean(out ** 2, axis=-1)), 1.0, rtol=1e-13)
+    ref = Fnn.rms_norm(torch.from_numpy(x), (H,), torch.from_numpy(g), eps).numpy()
+    assert np.allclose(so.rmsnorm(x, g, eps), ref, rtol=1e-13)
+
+
+def test_swiglu_special_cases(tiny_weights):
+    assert so.silu(np.array([0.0]))[0] == 0.0
+    a = np.linspace(-20, 20, 101)
+    assert np.allclose(so.silu(a), Fnn.silu(torch.from_numpy(a)).numpy(), rtol=1e-13, atol=1e-300)
+    st = make_stage(TINY, 0, n_layers=1, weights=tiny_weights)
+    h = so._f64(generate.hidden_rows(TINY, 3))
+    W = st.layers[0]
+    n = torch.from_numpy(so.rmsnorm(h, W["g_ffn"], TINY.rms_eps))
+    ref = (Fnn.silu(n @ torch.from_numpy(W["w1"])) * (n @ torch.from_numpy(W["w3"]))) @ torch.from_numpy(W["w2"])
+    assert rel(st.ffn_partial(0, h), ref.numpy()) < 1e-13
+    st.layers[0]["w2"] = np.zeros_like(W["w2"])
+    assert np.all(st.ffn_partial(0, h) == 0.0)
+
+
+def test_solo_mode_is_unsharded_stage_of_the_shard(tiny_weights):
+    """Solo mode for t > 1 is this build's definition: rank r alone == a t = 1 stage whose global
+    weights are rank r's shard (hq_l query heads, hkv_l KV heads, F_l FFN columns)."""
+    cfg, d = TINY, TINY.head_dim
+    x = generate.hidden_rows(cfg, 16)
+    for r in (0, 1):
+        st = make_stage(cfg, r, weights=tiny_weights)
+        sh = so.OracleStage(cfg.hidden, cfg.hq_l, cfg.hkv_l, cfg.ffn_l, cfg.n_layers, 1, 0)
+        sh.d = d      # head_dim is a property of the model, not of hidden / local heads
+        for l, w in enumerate(tiny_weights):
+            q = slice(r * cfg.hq_l * d, (r + 1) * cfg.hq_l * d)
+            k = slice(r * cfg.hkv_l * d, (r + 1) * cfg.hkv_l * d)
+            f = slice(r * cfg.ffn_l, (r + 1) * cfg.ffn_l)
+            sh.load_layer(l, w["g_attn"], w["wq"][:, q], w["wk"][:, k], w["wv"][:, k], w["wo"][q, :],
+                          w["g_ffn"], w["w1"][:, f], w["w3"][:, f], w["w2"][f, :])
+        a = st.prefill(st.new_cache(1), x, [16])
+        b = sh.prefill(sh.new_cache(1), x, [16])
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_greedy_tokens_agree_between_variants(tiny_weights):
+    """Tiny stage, 32-row prompt then 8 greedy steps: sharded+cached (group mode), unsharded+cached
+    and the cache-free dense brute force all emit the same tokens."""
+    cfg = TINY
+    head = generate.head_weights(cfg)
+    E = so._f64(head["embedding"])
+    X = so._f64(generate.hidden_rows(cfg, cfg.prompt_len))
+
+    def pick(x_last):
+        return so.greedy_head(x_last, head["g_final"], head["w_lm"], cfg.rms_eps)[0]
+
+    # (a) group mode with caches
+    ranks = [make_stage(cfg, r, weights=tiny_weights) for r in range(cfg.tp_degree)]
+    caches = [st.new_cache(1) for st in ranks]
+    parts, resid = so.group_forward(ranks, caches, X, [0] * cfg.prompt_len)
+    toks_a = [pick((resid + sum(parts))[-1])]
+    for _ in range(cfg.decode_steps - 1):
+        parts, resid = so.group_forward(ranks, caches, E[toks_a[-1]][None, :], [0])
+        toks_a.append(pick((resid + sum(parts))[-1]))
+    # (b) unsharded with cache
+    full = make_stage(cfg, 0, tp=1, weights=tiny_weights)
+    cache = full.new_cache(1)
+    p, h = full.prefill(cache, X, [cfg.prompt_len])
+    toks_b = [pick((h + p)[-1])]
+    for _ in range(cfg.decode_steps - 1):
+        p, h = full.decode(cache, E[toks_b[-1]][None, :])
+        toks_b.append(pick((h + p)[-1]))
+    # (c) dense brute force, recomputing the whole prefix each step
+    seq = torch.from_numpy(X)
+    toks_c = []
+    for _ in range(cfg.decode_steps):
+        p, h = dense_stage_torch(cfg, tiny_weights, seq)
+        toks_c.append(pick((h + p)[-1]))
+        seq = torch.cat([seq, torch.from_numpy(E[toks_c[-1]][None, :])], dim=0)
+    assert toks_a == toks_b == toks_c
+    assert len(set(toks_a)) >= 1 and all(0 <= t < cfg.vocab for t in toks_a)

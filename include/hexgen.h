@@ -1,0 +1,156 @@
+/*
+ * hexgen.h -- C ABI of the per-GPU pipeline-stage forward for MI355X (gfx950).
+ *
+ * One handle = one GPU's share of one pipeline stage of an asymmetric tensor+pipeline
+ * parallel decoder (paper Section 3): `n_layers` consecutive Llama-2-style layers at
+ * tensor-parallel degree `tp_degree`, rank `tp_rank` (paper Section 2, "Parallelism in
+ * generative inference": weights split column-wise then row-wise, two all-reduce points per
+ * layer).  The stage is run as prefill and then token-by-token decode against a KV cache
+ * (paper Section 2, prefill / decode equations) and returns its PRE-ALL-REDUCE partial hidden
+ * states.  Cross-GPU communication is not part of this library.
+ *
+ * Conventions
+ *   - every call returns a status and never throws or aborts; out-params are untouched on error;
+ *   - "device pointer" = HIP device memory of the current device, "host pointer" = ordinary
+ *     host memory; the library never takes ownership of a caller buffer;
+ *   - the library owns its copy of the weights (repacked), the KV cache and its workspace;
+ *   - kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream)
+ *     and the call returns without synchronising, except where stated;
+ *   - calls on one stage / cache are not thread-safe;
+ *   - weights use the paper's x . W convention (Section 2): W is [in, out], row-major.
+ *   - `dtype` fixes the storage type of weights, stage inputs / outputs and the KV cache.
+ *     The residual stream, every accumulator, the softmax and the norm statistics are fp32.
+ */
+#ifndef HEXGEN_H
+#define HEXGEN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hexgen_stage    hexgen_stage_t;     /* opaque, library-owned */
+typedef struct hexgen_kv_cache hexgen_kv_cache_t;  /* opaque, library-owned */
+
+typedef enum { HEXGEN_F32 = 0, HEXGEN_BF16 = 1 } hexgen_dtype_t;
+
+typedef enum {
+    HEXGEN_OK = 0,
+    HEXGEN_ERR_INVALID_ARG = 1, /* null pointer, negative size, unknown enum, index out of range */
+    HEXGEN_ERR_SHAPE       = 2, /* sharding does not divide, unsupported head_dim / alignment       */
+    HEXGEN_ERR_STATE       = 3, /* weights not loaded, decode before prefill, step mismatch        */
+    HEXGEN_ERR_CAPACITY    = 4, /* KV overflow (len + new > max_seq), batch > max_batch            */
+    HEXGEN_ERR_OOM         = 5, /* device or host allocation failed                                */
+    HEXGEN_ERR_DEVICE      = 6  /* a HIP call failed                                               */
+} hexgen_status_t;
+
+const char *hexgen_status_string(hexgen_status_t s);
+
+/* ---- stage ---------------------------------------------------------------------------------
+ * Dimensions are GLOBAL (unsharded): a stage is (layers, tensor-parallel degree) as in paper
+ * Section 3 / Section 4.1 (each stage has its own layer count l_ij and degree |d_ij|).  The
+ * library derives head_dim = hidden / n_heads and rank `tp_rank`'s shard: query heads
+ * [r*hq/t, (r+1)*hq/t), KV heads [r*hkv/t, (r+1)*hkv/t), FFN columns [r*F/t, (r+1)*F/t).
+ * HEXGEN_ERR_SHAPE unless hidden % n_heads == 0, n_heads % n_kv_heads == 0, n_heads, n_kv_heads
+ * and ffn divisible by tp_degree, 0 <= tp_rank < tp_degree, head_dim in {64, 128}, and (bf16)
+ * hidden, local q width and local ffn multiples of 32.  Defaults: rms_eps 1e-5, rope_theta 1e4.
+ */
+hexgen_status_t hexgen_stage_create(int hidden, int n_heads, int n_kv_heads, int ffn, int n_layers,
+                                    int tp_degree, int tp_rank, hexgen_dtype_t dtype,
+                                    hexgen_stage_t **out);
+hexgen_status_t hexgen_stage_set_params(hexgen_stage_t *st, float rms_eps, float rope_theta);
+void            hexgen_stage_destroy(hexgen_stage_t *st);
+
+/* Full (unsharded) matrices of one layer, row-major [in, out]:
+ *   g_attn [H], wq [H, hq*d], wk [H, hkv*d], wv [H, hkv*d], wo [hq*d, H], g_ffn [H],
+ *   w1 [H, F] (gate), w3 [H, F] (up), w2 [F, H] (down); element type = the stage's dtype
+ *   (fp32, or bf16 as raw 16-bit values).  Pointers may be host or device memory (detected).
+ * The library copies rank r's shard (columns of wq/wk/wv/w1/w3, rows of wo/w2) and repacks it;
+ * the call synchronises the device before returning, the sources may be freed afterwards.
+ */
+hexgen_status_t hexgen_stage_load_layer(hexgen_stage_t *st, int layer, const void *g_attn,
+                                        const void *wq, const void *wk, const void *wv,
+                                        const void *wo, const void *g_ffn, const void *w1,
+                                        const void *w3, const void *w2);
+
+/* ---- KV cache (paper Section 2: K, V of every processed position are kept per layer and the
+ * new token's K, V are concatenated at each decode step) ---------------------------------------
+ * Room for `max_batch` sequences of up to `max_seq` positions, for every layer of the stage.
+ */
+hexgen_status_t hexgen_kv_cache_create(hexgen_stage_t *st, int max_batch, int max_seq,
+                                       hexgen_kv_cache_t **out);
+void            hexgen_kv_cache_destroy(hexgen_kv_cache_t *kv);
+/* Forget all sequences (lengths to 0, "not prefilled"). */
+hexgen_status_t hexgen_kv_cache_reset(hexgen_kv_cache_t *kv);
+
+/* ---- prefill (paper Section 2, prefill equations) ------------------------------------------
+ * Packed (varlen) rows: sequence i occupies rows [cu_i, cu_i + seq_lens[i]) with cu the running
+ * sum, at positions 0 .. seq_lens[i]-1.  Starts a new batch: the cache is reset first.
+ *   hidden_in   device [total_rows, hidden], dtype           (activations from the previous stage)
+ *   seq_lens    HOST int32 [batch], every entry >= 1
+ *   out_partial device [total_rows, hidden], dtype: last layer's FFN partial P_ffn^(r), no residual
+ *   out_resid   device [total_rows, hidden], dtype, may be NULL: the residual stream that partial
+ *               would be added to; out_resid + sum over ranks of out_partial = the stage output
+ * Interior reduce points (2 per layer, all-reduce in the paper) run in "solo" mode: the rank adds
+ * its own partial to the residual stream, which is what one GPU can compute on its own; the kernel
+ * shapes and bytes are those of the real sharded stage.
+ */
+hexgen_status_t hexgen_stage_prefill(hexgen_stage_t *st, hexgen_kv_cache_t *kv, const void *hidden_in,
+                                     const int32_t *seq_lens, int batch, void *out_partial,
+                                     void *out_resid, void *stream);
+
+/* ---- decode (paper Section 2, decode equations) --------------------------------------------
+ * One new row per sequence of the prefilled batch, at position len_i; K, V of the row are
+ * appended.  `step` (0-based) must equal the number of decode calls since the prefill (or the
+ * last hexgen_kv_cache_fill), else HEXGEN_ERR_STATE.  Buffers as for prefill with
+ * total_rows = batch.
+ */
+hexgen_status_t hexgen_stage_decode(hexgen_stage_t *st, hexgen_kv_cache_t *kv, int step,
+                                    const void *hidden_in, void *out_partial, void *out_resid,
+                                    void *stream);
+
+/* ---- validation surface ("group" mode: all t ranks of a stage run one after another on the same
+ * GPU and their partials are summed, standing in for the all-reduce of paper Section 2) ----------
+ * hexgen_stage_run_sublayer: one sub-layer of one layer for this rank.
+ *   which 0: attention sub-layer  (RMSNorm, QKV, RoPE, cache append, attention, W_O partial)
+ *   which 1: FFN sub-layer        (RMSNorm, W1/W3, SwiGLU, W2 partial)
+ *   h_in        device fp32 [n_rows, hidden]: the residual stream entering the sub-layer
+ *   seq_lens    HOST int32 [batch] rows per sequence (packed as in prefill), or NULL = one row
+ *               per sequence for the first `batch` sequences (decode).  Rows of sequence i sit at
+ *               positions len_i .. len_i + n_i - 1 where len_i is the committed length.
+ *   partial_out device fp32 [n_rows, hidden]: this rank's partial (no residual)
+ * The attention sub-layer writes K, V of the new rows into `layer`'s cache but does not change
+ * the committed lengths; call hexgen_kv_cache_commit once all layers have processed the rows.
+ */
+hexgen_status_t hexgen_stage_run_sublayer(hexgen_stage_t *st, hexgen_kv_cache_t *kv, int layer,
+                                          int which, const void *h_in, const int32_t *seq_lens,
+                                          int batch, void *partial_out, void *stream);
+hexgen_status_t hexgen_kv_cache_commit(hexgen_kv_cache_t *kv, const int32_t *seq_lens, int batch);
+/* dst[i] += src[i] for n fp32 device elements (fixed-order rank sum of the validation driver). */
+hexgen_status_t hexgen_accumulate_f32(void *dst, const void *src, int64_t n, void *stream);
+
+/* Read back / install cache rows as HOST fp32 [n, hkv_local, head_dim] (K after rotation).
+ * Both synchronise.  fill: sets positions 0..n-1 of `seq` in `layer`; when every layer of every
+ * sequence of a batch has been filled, call hexgen_kv_cache_set_lengths to declare the context
+ * (this also marks the cache "prefilled" and restarts the decode step count at 0).
+ */
+hexgen_status_t hexgen_kv_cache_read(hexgen_kv_cache_t *kv, int layer, int seq, int pos0, int n,
+                                     float *k_out, float *v_out);
+hexgen_status_t hexgen_kv_cache_fill(hexgen_kv_cache_t *kv, int layer, int seq, int n,
+                                     const float *k, const float *v);
+hexgen_status_t hexgen_kv_cache_set_lengths(hexgen_kv_cache_t *kv, const int32_t *lens, int batch);
+hexgen_status_t hexgen_kv_cache_get_lengths(hexgen_kv_cache_t *kv, int32_t *lens_out, int batch);
+
+/* Debug tap: at the entry of `layer` during prefill / decode, the fp32 residual stream
+ * [rows, hidden] is copied to `h_dump` (device).  NULL removes the tap.
+ */
+hexgen_status_t hexgen_stage_set_tap(hexgen_stage_t *st, int layer, void *h_dump);
+
+/* Bytes of device memory the stage holds for weights (after repacking), for reporting. */
+int64_t hexgen_stage_weight_bytes(const hexgen_stage_t *st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HEXGEN_H */

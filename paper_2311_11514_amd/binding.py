@@ -1,0 +1,200 @@
+"""ctypes binding of libhexgen.so: argument marshalling only, same names as include/hexgen.h.
+
+torch is used for device memory and streams; every step of the stage runs in the library's HIP
+kernels.  There is no fallback: if the shared library is missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhexgen.so")
+
+HEXGEN_F32, HEXGEN_BF16 = 0, 1
+STATUS_NAMES = {0: "HEXGEN_OK", 1: "HEXGEN_ERR_INVALID_ARG", 2: "HEXGEN_ERR_SHAPE", 3: "HEXGEN_ERR_STATE",
+                4: "HEXGEN_ERR_CAPACITY", 5: "HEXGEN_ERR_OOM", 6: "HEXGEN_ERR_DEVICE"}
+
+# every symbol include/hexgen.h declares: name -> (restype, argtypes)
+_vp, _i, _i64, _f = C.c_void_p, C.c_int, C.c_int64, C.c_float
+_ip = C.POINTER(C.c_int32)
+_fp = C.POINTER(C.c_float)
+SIGNATURES = {
+    "hexgen_status_string": (C.c_char_p, [_i]),
+    "hexgen_stage_create": (_i, [_i, _i, _i, _i, _i, _i, _i, _i, C.POINTER(_vp)]),
+    "hexgen_stage_set_params": (_i, [_vp, _f, _f]),
+    "hexgen_stage_destroy": (None, [_vp]),
+    "hexgen_stage_load_layer": (_i, [_vp, _i] + [_vp] * 9),
+    "hexgen_kv_cache_create": (_i, [_vp, _i, _i, C.POINTER(_vp)]),
+    "hexgen_kv_cache_destroy": (None, [_vp]),
+    "hexgen_kv_cache_reset": (_i, [_vp]),
+    "hexgen_stage_prefill": (_i, [_vp, _vp, _vp, _ip, _i, _vp, _vp, _vp]),
+    "hexgen_stage_decode": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _vp]),
+    "hexgen_stage_run_sublayer": (_i, [_vp, _vp, _i, _i, _vp, _ip, _i, _vp, _vp]),
+    "hexgen_kv_cache_commit": (_i, [_vp, _ip, _i]),
+    "hexgen_accumulate_f32": (_i, [_vp, _vp, _i64, _vp]),
+    "hexgen_kv_cache_read": (_i, [_vp, _i, _i, _i, _i, _fp, _fp]),
+    "hexgen_kv_cache_fill": (_i, [_vp, _i, _i, _i, _fp, _fp]),
+    "hexgen_kv_cache_set_lengths": (_i, [_vp, _ip, _i]),
+    "hexgen_kv_cache_get_lengths": (_i, [_vp, _ip, _i]),
+    "hexgen_stage_set_tap": (_i, [_vp, _i, _vp]),
+    "hexgen_stage_weight_bytes": (_i64, [_vp]),
+}
+
+
+def load_library(path: str = LIB_PATH) -> C.CDLL:
+    if not os.path.exists(path):
+        raise ImportError(f"{path} not found: build it first (python -m paper_2311_11514_amd.build); "
+                          "there is no fallback path")
+    lib = C.CDLL(path)
+    for name, (res, args) in SIGNATURES.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    return lib
+
+
+lib = load_library()
+
+
+class HexgenError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib.hexgen_status_string(status).decode()
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)} ({msg})")
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise HexgenError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_contiguous()
+    return t.data_ptr()
+
+
+def _i32(seq: Optional[Sequence[int]]):
+    if seq is None:
+        return None
+    return (C.c_int32 * len(seq))(*[int(v) for v in seq])
+
+
+def _stream_handle(stream: Optional[torch.cuda.Stream]) -> Optional[int]:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream or None
+
+
+def _torch_dtype(dtype: int):
+    return torch.float32 if dtype == HEXGEN_F32 else torch.bfloat16
+
+
+class Stage:
+    """Owns a hexgen_stage_t.  dtype: "f32" | "bf16"."""
+
+    def __init__(self, hidden, n_heads, n_kv_heads, ffn, n_layers, tp_degree, tp_rank, dtype,
+                 rms_eps: float = 1e-5, rope_theta: float = 10000.0):
+        self.dtype = {"f32": HEXGEN_F32, "bf16": HEXGEN_BF16}[dtype] if isinstance(dtype, str) else int(dtype)
+        h = C.c_void_p()
+        _check(lib.hexgen_stage_create(hidden, n_heads, n_kv_heads, ffn, n_layers, tp_degree, tp_rank,
+                                       self.dtype, C.byref(h)), "hexgen_stage_create")
+        self.handle = h
+        self.hidden, self.n_layers = hidden, n_layers
+        self.head_dim = hidden // n_heads
+        self.hkv_l = n_kv_heads // tp_degree
+        _check(lib.hexgen_stage_set_params(self.handle, rms_eps, rope_theta), "hexgen_stage_set_params")
+        self._taps = {}
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib.hexgen_stage_destroy(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+    def load_layer(self, layer: int, g_attn, wq, wk, wv, wo, g_ffn, w1, w3, w2):
+        """Global [in, out] tensors (host or device); converted to the stage's dtype if needed."""
+        td = _torch_dtype(self.dtype)
+        ts = [t.to(td).contiguous() for t in (g_attn, wq, wk, wv, wo, g_ffn, w1, w3, w2)]
+        _check(lib.hexgen_stage_load_layer(self.handle, layer, *[t.data_ptr() for t in ts]),
+               "hexgen_stage_load_layer")
+
+    def kv_cache_create(self, max_batch: int, max_seq: int) -> "KVCache":
+        return KVCache(self, max_batch, max_seq)
+
+    def prefill(self, kv: "KVCache", hidden_in: torch.Tensor, seq_lens: Sequence[int],
+                out_partial: torch.Tensor, out_resid: Optional[torch.Tensor] = None, stream=None):
+        _check(lib.hexgen_stage_prefill(self.handle, kv.handle, _ptr(hidden_in), _i32(seq_lens), len(seq_lens),
+                                        _ptr(out_partial), _ptr(out_resid), _stream_handle(stream)),
+               "hexgen_stage_prefill")
+
+    def decode(self, kv: "KVCache", step: int, hidden_in: torch.Tensor, out_partial: torch.Tensor,
+               out_resid: Optional[torch.Tensor] = None, stream=None):
+        _check(lib.hexgen_stage_decode(self.handle, kv.handle, step, _ptr(hidden_in), _ptr(out_partial),
+                                       _ptr(out_resid), _stream_handle(stream)), "hexgen_stage_decode")
+
+    def run_sublayer(self, kv: "KVCache", layer: int, which: int, h_in: torch.Tensor,
+                     seq_lens: Optional[Sequence[int]], batch: int, partial_out: torch.Tensor, stream=None):
+        _check(lib.hexgen_stage_run_sublayer(self.handle, kv.handle, layer, which, _ptr(h_in), _i32(seq_lens),
+                                             batch, _ptr(partial_out), _stream_handle(stream)),
+               "hexgen_stage_run_sublayer")
+
+    def set_tap(self, layer: int, h_dump: Optional[torch.Tensor]):
+        self._taps[layer] = h_dump          # keep the buffer alive
+        _check(lib.hexgen_stage_set_tap(self.handle, layer, _ptr(h_dump)), "hexgen_stage_set_tap")
+
+    def weight_bytes(self) -> int:
+        return int(lib.hexgen_stage_weight_bytes(self.handle))
+
+
+class KVCache:
+    def __init__(self, stage: Stage, max_batch: int, max_seq: int):
+        h = C.c_void_p()
+        _check(lib.hexgen_kv_cache_create(stage.handle, max_batch, max_seq, C.byref(h)), "hexgen_kv_cache_create")
+        self.handle, self.stage = h, stage
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib.hexgen_kv_cache_destroy(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+    def reset(self):
+        _check(lib.hexgen_kv_cache_reset(self.handle), "hexgen_kv_cache_reset")
+
+    def commit(self, seq_lens: Optional[Sequence[int]], batch: int):
+        _check(lib.hexgen_kv_cache_commit(self.handle, _i32(seq_lens), batch), "hexgen_kv_cache_commit")
+
+    def set_lengths(self, lens: Sequence[int]):
+        _check(lib.hexgen_kv_cache_set_lengths(self.handle, _i32(lens), len(lens)), "hexgen_kv_cache_set_lengths")
+
+    def get_lengths(self, batch: int):
+        out = (C.c_int32 * batch)()
+        _check(lib.hexgen_kv_cache_get_lengths(self.handle, out, batch), "hexgen_kv_cache_get_lengths")
+        return list(out)
+
+    def fill(self, layer: int, seq: int, k: torch.Tensor, v: torch.Tensor):
+        """k, v: host fp32 [n, hkv_local, head_dim]."""
+        k = k.to(torch.float32).contiguous().cpu()
+        v = v.to(torch.float32).contiguous().cpu()
+        _check(lib.hexgen_kv_cache_fill(self.handle, layer, seq, k.shape[0],
+                                        C.cast(k.data_ptr(), _fp), C.cast(v.data_ptr(), _fp)), "hexgen_kv_cache_fill")
+
+    def read(self, layer: int, seq: int, pos0: int, n: int):
+        st = self.stage
+        k = torch.empty(n, st.hkv_l, st.head_dim, dtype=torch.float32)
+        v = torch.empty_like(k)
+        _check(lib.hexgen_kv_cache_read(self.handle, layer, seq, pos0, n, C.cast(k.data_ptr(), _fp),
+                                        C.cast(v.data_ptr(), _fp)), "hexgen_kv_cache_read")
+        return k, v
+
+
+def accumulate_f32(dst: torch.Tensor, src: torch.Tensor, stream=None):
+    assert dst.dtype == torch.float32 and src.dtype == torch.float32 and dst.numel() == src.numel()
+    _check(lib.hexgen_accumulate_f32(_ptr(dst), _ptr(src), dst.numel(), _stream_handle(stream)),
+           "hexgen_accumulate_f32")

@@ -1,0 +1,66 @@
+// Shared device-side definitions for the gfx950 stage kernels.
+//
+// Operand layout ("fragment-major").  Every bf16 matrix that feeds the matrix cores -- weights and
+// the activations this library produces for its own GEMMs -- is stored so that one
+// v_mfma_f32_16x16x32_bf16 operand is a single contiguous 1 KB block: a matrix M[idx][k]
+// (idx = output feature for weights, token row for activations; k = contraction index) is cut into
+// tiles of 16 idx x 32 k, tile (it, kt) lives at ((it * k_tiles + kt) * 64 + lane) * 8 elements and
+// lane l holds idx = l % 16, k = 8 * (l / 16) + j, j = 0..7.  A wave fetches an operand with one
+// coalesced 128-bit load per lane, from HBM or from LDS, with no transposition anywhere.
+// Both MFMA inputs use this same mapping, so any k-ordering inside a tile cancels in the product.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+typedef uint16_t bf16_t;   // raw storage
+
+#define HX_WAVE 64
+
+__host__ __device__ inline size_t frag_offset(int idx, int k, int k_tiles) {
+    int it = idx >> 4, kt = k >> 5;
+    int lane = (idx & 15) + 16 * ((k & 31) >> 3);
+    return ((size_t)(it * (size_t)k_tiles + kt) * 64 + lane) * 8 + (k & 7);
+}
+
+__device__ inline float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round-to-nearest-even; NaN stays NaN
+__device__ inline bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// block-wide sum for blockDim.x = 256 (4 waves); `red` is >= 4 floats of LDS
+__device__ inline float block_sum_256(float v, float *red) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+__device__ inline float block_max_256(float v, float *red) {
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}

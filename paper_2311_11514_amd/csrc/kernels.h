@@ -1,0 +1,88 @@
+// Host-side launchers of the stage kernels.  Every launcher only enqueues on `s`.
+// Shapes are validated by the caller (stage.cpp) before any launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "common.h"
+
+// Row bookkeeping of one call: token row i belongs to sequence row_seq[i] at absolute
+// position row_pos[i] (device int32 arrays).  For decode they are derived on the device from the
+// cache's committed lengths, so one step needs no host->device traffic.
+struct RowMap {
+    const int32_t *row_seq;   // [T]
+    const int32_t *row_pos;   // [T]
+};
+
+// ---- layout / utility (kernels_layout.hip) -------------------------------------------------
+// dst tile (dst_tile0 + nt * dst_tile_stride) <- src[k0 + k][c0 + nt*16 + i], src row-major with
+// leading dimension ld (elements), K % 32 == 0, N % 16 == 0.
+void launch_pack_weight(const bf16_t *src, int64_t ld, int k0, int c0, int K, int N, bf16_t *dst,
+                        int dst_tile0, int dst_tile_stride, hipStream_t s);
+void launch_cvt_bf16_to_f32(const bf16_t *src, float *dst, int64_t n, hipStream_t s);
+void launch_accumulate_f32(float *dst, const float *src, int64_t n, hipStream_t s);
+// decode row map: row i -> (seq i, pos lens[i])
+void launch_decode_rowmap(const int32_t *lens, int32_t *row_seq, int32_t *row_pos, int b, hipStream_t s);
+void launch_advance_lens(int32_t *lens, int b, hipStream_t s);
+
+// ---- bf16 path (kernels_bf16_*.hip) ---------------------------------------------------------
+// KV cache geometry of one (layer, sequence, kv head) slab; see kernels_bf16_attn.hip
+struct KvGeom {
+    int d;            // head dim (64 | 128)
+    int hkv_l;        // local kv heads
+    int smax;         // positions per sequence, multiple of 32
+    int64_t seq_stride;   // elements between sequences  (= hkv_l * smax * d)
+};
+
+// rows of `in` ([T,H] row-major, fp32 or bf16) -> optional fp32 copy h_out, and
+// packed bf16 n = in / sqrt(mean(in^2)+eps) * g  ([ceil16(T)/16][H/32] fragment tiles)
+void launch_rmsnorm_pack(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *n_packed,
+                         int T, int H, float eps, hipStream_t s);
+
+// out[ks][t][n] (fp32, row stride N, split stride T*N) = sum over the split's k range of
+// Wp[n][k] * Xp[t][k]; T <= 32.  ksplit >= 1 splits K across blockIdx.y.
+void launch_gemv_mfma(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, int K, int T, int ksplit,
+                      int pair_tiles, hipStream_t s);
+// same contraction for many rows (prefill): out[t][n] fp32 row-major
+void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, int K, int T, hipStream_t s);
+
+// sum ksplit partials of the fused QKV projection, rotate q and k heads, write q (bf16 row-major
+// [T][hq_l*d]) and append k, v to the cache at each row's (seq, pos)
+void launch_qkv_rope_append(const float *part, int ksplit, int T, int hq_l, KvGeom kg, RowMap rm,
+                            const float *cos_tab, const float *sin_tab, bf16_t *q_out, bf16_t *kc,
+                            bf16_t *vc, hipStream_t s);
+// h[t][:] += sum_ks part[ks][t][:]; then either packed n = rmsnorm(h) * g (g != NULL) or nothing
+void launch_reduce_resid_norm(const float *part, int ksplit, float *h, const float *g, bf16_t *n_packed,
+                              int T, int H, float eps, hipStream_t s);
+// plain reduce of the partials into dst fp32 [T][H] (no residual): the stage's output partial
+void launch_reduce_partial(const float *part, int ksplit, float *dst, int T, int H, hipStream_t s);
+// u[t][f] = silu(a) * b with a, b the W1 / W3 columns (interleaved 16-column tiles) -> packed bf16
+void launch_reduce_swiglu(const float *part, int ksplit, bf16_t *u_packed, int T, int F_l, hipStream_t s);
+
+// decode attention: one new row per sequence; split-KV partials then merge into packed o
+void launch_attn_decode(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,
+                        const int32_t *lens, int b, int nsplit, float *part_o, float *part_ml,
+                        bf16_t *o_packed, hipStream_t s);
+// prefill attention over packed ragged rows; K, V are read from the cache
+void launch_attn_prefill(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,
+                         const int32_t *cu_rows, const int32_t *pos0, int batch, int max_new,
+                         bf16_t *o_packed, hipStream_t s);
+
+// cache <-> host-format fp32 [n][hkv_l][d] staging (device buffers)
+void launch_kv_scatter(const float *k, const float *v, bf16_t *kc, bf16_t *vc, KvGeom kg, int seq,
+                       int pos0, int n, hipStream_t s);
+void launch_kv_gather(const bf16_t *kc, const bf16_t *vc, KvGeom kg, int seq, int pos0, int n, float *k,
+                      float *v, hipStream_t s);
+
+void launch_store_out(const float *src, void *dst, int dst_is_bf16, int64_t n, hipStream_t s);
+
+// ---- fp32 path (kernels_f32.hip): plain layouts, vector ALU -----------------------------------
+void f32_launch_rmsnorm(const float *in, const float *g, float *out, int T, int H, float eps, hipStream_t s);
+void f32_launch_gemm(const float *X, const float *W, float *out, int T, int K, int N, hipStream_t s);
+void f32_launch_rope_append(const float *qkv, int T, int hq_l, int hkv_l, int d, int smax, RowMap rm,
+                            const float *cos_tab, const float *sin_tab, float *q_out, float *kc, float *vc,
+                            hipStream_t s);
+void f32_launch_attn(const float *q, const float *kc, const float *vc, int T, int hq_l, int hkv_l, int d,
+                     int smax, RowMap rm, float *o, hipStream_t s);
+void f32_launch_swiglu(const float *ab, float *u, int T, int F_l, hipStream_t s);
+void f32_launch_kv_copy(float *kc, float *vc, float *k, float *v, int hkv_l, int d, int smax, int seq,
+                        int pos0, int n, int to_cache, hipStream_t s);

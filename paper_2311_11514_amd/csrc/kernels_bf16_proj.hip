@@ -1,0 +1,397 @@
+// bf16 projections of the stage: RMSNorm fused with the cast into the GEMM operand layout, the
+// weight-streaming skinny MFMA kernel used by decode (T <= 32 rows), the LDS-tiled MFMA GEMM used by
+// prefill, and the split-K reduce epilogues (RoPE + cache append, residual + next norm, SwiGLU).
+//
+// Every contraction is computed "transposed": D^T[n][t] = sum_k Wp[n][k] * Xp[t][k] with the weight
+// tile as MFMA operand A and the activation tile as operand B.  In the 16x16 result each lane then
+// owns 4 consecutive output features of one token, which is exactly a 16-byte (fp32) or 8-byte
+// (bf16) piece of the next operand -- no shuffle between one GEMM's output and the next one's input.
+#include "kernels.h"
+#include "kvlayout.h"
+
+// -------------------------------------------------------------------------------------------------
+// RMSNorm (+ optional fp32 copy of the input) -> packed bf16.  One 256-thread block per row.
+// -------------------------------------------------------------------------------------------------
+template <bool IN_BF16>
+__global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const void *__restrict__ in, float *__restrict__ h_out,
+                                                          const float *__restrict__ g, bf16_t *__restrict__ np,
+                                                          int H, float eps) {
+    __shared__ float red[4];
+    const int t = blockIdx.x;
+    const int chunks = H >> 3;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < chunks; c += 256) {
+        float x[8];
+        if (IN_BF16) {
+            uint4 raw = *reinterpret_cast<const uint4 *>(reinterpret_cast<const bf16_t *>(in) + (size_t)t * H + c * 8);
+            const bf16_t *e = reinterpret_cast<const bf16_t *>(&raw);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = bf16_to_f32(e[j]);
+        } else {
+            const float4 *p = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(in) + (size_t)t * H + c * 8);
+            float4 a = p[0], b = p[1];
+            x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ss += x[j] * x[j];
+        if (h_out) {
+            float4 *o = reinterpret_cast<float4 *>(h_out + (size_t)t * H + c * 8);
+            o[0] = make_float4(x[0], x[1], x[2], x[3]);
+            o[1] = make_float4(x[4], x[5], x[6], x[7]);
+        }
+    }
+    ss = block_sum_256(ss, red);
+    const float rstd = 1.0f / sqrtf(ss / (float)H + eps);
+    const int k_tiles = H >> 5;
+    for (int c = threadIdx.x; c < chunks; c += 256) {
+        float x[8];
+        if (IN_BF16) {
+            uint4 raw = *reinterpret_cast<const uint4 *>(reinterpret_cast<const bf16_t *>(in) + (size_t)t * H + c * 8);
+            const bf16_t *e = reinterpret_cast<const bf16_t *>(&raw);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = bf16_to_f32(e[j]);
+        } else {
+            const float4 *p = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(in) + (size_t)t * H + c * 8);
+            float4 a = p[0], b = p[1];
+            x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+        }
+        const float4 *gp = reinterpret_cast<const float4 *>(g + c * 8);
+        float4 g0 = gp[0], g1 = gp[1];
+        uint4 o;
+        o.x = pack_bf16x2(x[0] * rstd * g0.x, x[1] * rstd * g0.y);
+        o.y = pack_bf16x2(x[2] * rstd * g0.z, x[3] * rstd * g0.w);
+        o.z = pack_bf16x2(x[4] * rstd * g1.x, x[5] * rstd * g1.y);
+        o.w = pack_bf16x2(x[6] * rstd * g1.z, x[7] * rstd * g1.w);
+        *reinterpret_cast<uint4 *>(np + frag_offset(t, c * 8, k_tiles)) = o;
+    }
+}
+
+void launch_rmsnorm_pack(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *n_packed, int T,
+                         int H, float eps, hipStream_t s) {
+    if (T <= 0) return;
+    if (in_is_bf16)
+        hipLaunchKernelGGL(rmsnorm_pack_kernel<true>, dim3(T), dim3(256), 0, s, in, h_out, g, n_packed, H, eps);
+    else
+        hipLaunchKernelGGL(rmsnorm_pack_kernel<false>, dim3(T), dim3(256), 0, s, in, h_out, g, n_packed, H, eps);
+}
+
+// -------------------------------------------------------------------------------------------------
+// Decode projection: weight-streaming skinny GEMM.  Each wave streams 1 KB weight tiles with one
+// 128-bit load per lane and feeds them to the matrix core against a (mostly zero-padded) 16-token
+// activation tile: 16 MFMA cycles per KB, four times cheaper than unpacking bf16 on the vector ALU.
+// A block owns UT consecutive 16-feature tiles; its WAVES waves interleave over the k-tiles of the
+// block's K range and are summed through LDS in wave order (fixed order: bit-reproducible).
+// blockIdx.y splits K further across blocks; those partials are summed by the epilogue kernels.
+// -------------------------------------------------------------------------------------------------
+template <int NB, int UT, int WAVES, int UNROLL>
+__global__ __launch_bounds__(WAVES * 64) void gemv_mfma_kernel(const bf16_t *__restrict__ Wp,
+                                                              const bf16_t *__restrict__ Xp,
+                                                              float *__restrict__ out, int N, int k_tiles,
+                                                              int kt_per_split, int T) {
+    __shared__ floatx4 red[WAVES][UT * NB][64];
+    const int unit = blockIdx.x, ks = blockIdx.y;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int kt0 = ks * kt_per_split;
+    const int kt1 = min(k_tiles, kt0 + kt_per_split);
+
+    floatx4 acc[UT][NB];
+#pragma unroll
+    for (int u = 0; u < UT; ++u)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) acc[u][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const bf16x8 *wp[UT];
+#pragma unroll
+    for (int u = 0; u < UT; ++u)
+        wp[u] = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)(unit * UT + u) * k_tiles * 64 + lane;
+    const bf16x8 *xp[NB];
+    bool xv[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        xp[b] = reinterpret_cast<const bf16x8 *>(Xp) + (size_t)b * k_tiles * 64 + lane;
+        xv[b] = (lane & 15) + 16 * b < T;
+    }
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+
+    int kt = kt0 + wave;
+    for (; kt + (UNROLL - 1) * WAVES < kt1; kt += UNROLL * WAVES) {
+        bf16x8 a[UNROLL][UT], x[UNROLL][NB];
+#pragma unroll
+        for (int i = 0; i < UNROLL; ++i) {
+            const size_t o = (size_t)(kt + i * WAVES) * 64;
+#pragma unroll
+            for (int u = 0; u < UT; ++u) a[i][u] = __builtin_nontemporal_load(wp[u] + o);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) x[i][b] = xv[b] ? xp[b][o] : zero;
+        }
+#pragma unroll
+        for (int i = 0; i < UNROLL; ++i)
+#pragma unroll
+            for (int u = 0; u < UT; ++u)
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], x[i][b], acc[u][b], 0, 0, 0);
+    }
+    for (; kt < kt1; kt += WAVES) {
+        const size_t o = (size_t)kt * 64;
+#pragma unroll
+        for (int u = 0; u < UT; ++u) {
+            bf16x8 a = __builtin_nontemporal_load(wp[u] + o);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                bf16x8 x = xv[b] ? xp[b][o] : zero;
+                acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, x, acc[u][b], 0, 0, 0);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int u = 0; u < UT; ++u)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) red[wave][u * NB + b][lane] = acc[u][b];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < UT * NB * 64; idx += WAVES * 64) {
+        const int tile = idx >> 6, l = idx & 63;
+        floatx4 sum = red[0][tile][l];
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) sum += red[w][tile][l];
+        const int u = tile / NB, b = tile % NB;
+        const int token = (l & 15) + 16 * b;
+        const int n = (unit * UT + u) * 16 + 4 * (l >> 4);
+        if (token < T) *reinterpret_cast<floatx4 *>(out + ((size_t)ks * T + token) * N + n) = sum;
+    }
+}
+
+void launch_gemv_mfma(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, int K, int T, int ksplit,
+                      int pair_tiles, hipStream_t s) {
+    const int k_tiles = K / 32, n_tiles = N / 16;
+    const int per = (k_tiles + ksplit - 1) / ksplit;
+    constexpr int WAVES = 8;
+#define HX_GEMV(NB, UT, UNR)                                                                                      \
+    hipLaunchKernelGGL((gemv_mfma_kernel<NB, UT, WAVES, UNR>), dim3(n_tiles / UT, ksplit), dim3(WAVES * 64), 0, s, \
+                       Wp, Xp, out, N, k_tiles, per, T)
+    if (T <= 16) {
+        if (pair_tiles) HX_GEMV(1, 2, 4); else HX_GEMV(1, 1, 8);
+    } else {
+        if (pair_tiles) HX_GEMV(2, 2, 4); else HX_GEMV(2, 1, 8);
+    }
+#undef HX_GEMV
+}
+
+// -------------------------------------------------------------------------------------------------
+// Prefill projection: LDS-staged MFMA GEMM.  Block tile 128 features x 128 tokens, 4 waves (2 x 2),
+// each wave 64 x 64 = 4 x 4 MFMA tiles.  Operand tiles arrive already in fragment order, so the
+// global -> LDS copy is a straight 16-byte-per-thread copy and the LDS reads are conflict-free
+// 128-bit reads at lane * 16 bytes.
+// -------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t *__restrict__ Wp, const bf16_t *__restrict__ Xp,
+                                                       float *__restrict__ out, int N, int k_tiles, int n_tiles,
+                                                       int t_tiles, int T) {
+    __shared__ bf16x8 sA[2][8][64];
+    __shared__ bf16x8 sB[2][8][64];
+    const int bm = blockIdx.x, bt = blockIdx.y;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave & 1, wt = wave >> 1;
+
+    floatx4 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    // this thread copies tiles (wave) and (wave + 4) of both operands, lane slot `lane`
+    const int ta0 = bm * 8 + wave, ta1 = ta0 + 4;
+    const int tb0 = bt * 8 + wave, tb1 = tb0 + 4;
+    const bf16x8 *A = reinterpret_cast<const bf16x8 *>(Wp);
+    const bf16x8 *B = reinterpret_cast<const bf16x8 *>(Xp);
+    bf16x8 ra0, ra1, rb0, rb1;
+    auto gload = [&](int kt) {
+        ra0 = ta0 < n_tiles ? A[((size_t)ta0 * k_tiles + kt) * 64 + lane] : zero;
+        ra1 = ta1 < n_tiles ? A[((size_t)ta1 * k_tiles + kt) * 64 + lane] : zero;
+        rb0 = tb0 < t_tiles ? B[((size_t)tb0 * k_tiles + kt) * 64 + lane] : zero;
+        rb1 = tb1 < t_tiles ? B[((size_t)tb1 * k_tiles + kt) * 64 + lane] : zero;
+    };
+    auto sstore = [&](int buf) {
+        sA[buf][wave][lane] = ra0; sA[buf][wave + 4][lane] = ra1;
+        sB[buf][wave][lane] = rb0; sB[buf][wave + 4][lane] = rb1;
+    };
+    gload(0);
+    sstore(0);
+    __syncthreads();
+    int cur = 0;
+    for (int kt = 0; kt < k_tiles; ++kt) {
+        if (kt + 1 < k_tiles) gload(kt + 1);
+        bf16x8 a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[i] = sA[cur][wm * 4 + i][lane];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b[j] = sB[cur][wt * 4 + j][lane];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        if (kt + 1 < k_tiles) sstore(cur ^ 1);
+        __syncthreads();
+        cur ^= 1;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int token = bt * 128 + wt * 64 + j * 16 + (lane & 15);
+        if (token >= T) continue;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int n = bm * 128 + wm * 64 + i * 16 + 4 * (lane >> 4);
+            if (n < N) *reinterpret_cast<floatx4 *>(out + (size_t)token * N + n) = acc[i][j];
+        }
+    }
+}
+
+void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, int K, int T, hipStream_t s) {
+    const int k_tiles = K / 32, n_tiles = N / 16, t_tiles = (T + 15) / 16;
+    dim3 grid((n_tiles + 7) / 8, (t_tiles + 7) / 8);
+    hipLaunchKernelGGL(gemm_mfma_kernel, grid, dim3(256), 0, s, Wp, Xp, out, N, k_tiles, n_tiles, t_tiles, T);
+}
+
+// -------------------------------------------------------------------------------------------------
+// Epilogues.  `part` is [ksplit][T][N] fp32; partials are always summed in split order.
+// -------------------------------------------------------------------------------------------------
+// grid (T, hq_l + 2*hkv_l), block d/2: thread i owns the rotary pair (i, i + d/2) of one head.
+__global__ void qkv_rope_append_kernel(const float *__restrict__ part, int ksplit, int T, int hq_l, KvGeom kg,
+                                       RowMap rm, const float *__restrict__ cos_tab,
+                                       const float *__restrict__ sin_tab, bf16_t *__restrict__ q_out,
+                                       bf16_t *__restrict__ kc, bf16_t *__restrict__ vc) {
+    const int t = blockIdx.x, head = blockIdx.y, i = threadIdx.x;
+    const int d = kg.d, half = d >> 1;
+    const int N = (hq_l + 2 * kg.hkv_l) * d;
+    const int col = head * d + i;
+    float lo = 0.f, hi = 0.f;
+    for (int ks = 0; ks < ksplit; ++ks) {
+        const float *p = part + ((size_t)ks * T + t) * N + col;
+        lo += p[0];
+        hi += p[half];
+    }
+    const int seq = rm.row_seq[t], pos = rm.row_pos[t];
+    if (head < hq_l + kg.hkv_l) {
+        const float c = cos_tab[(size_t)pos * half + i], sn = sin_tab[(size_t)pos * half + i];
+        const float rlo = lo * c - hi * sn, rhi = hi * c + lo * sn;
+        lo = rlo; hi = rhi;
+    }
+    if (head < hq_l) {
+        bf16_t *q = q_out + (size_t)t * hq_l * d + head * d;
+        q[i] = f32_to_bf16(lo);
+        q[i + half] = f32_to_bf16(hi);
+    } else {
+        const bool is_k = head < hq_l + kg.hkv_l;
+        const int c = is_k ? head - hq_l : head - hq_l - kg.hkv_l;
+        const size_t slab = (size_t)seq * kg.seq_stride + (size_t)c * kg.smax * d;
+        if (is_k) {
+            kc[slab + kv_k_offset(pos, i, d)] = f32_to_bf16(lo);
+            kc[slab + kv_k_offset(pos, i + half, d)] = f32_to_bf16(hi);
+        } else {
+            vc[slab + kv_v_offset(pos, i, d)] = f32_to_bf16(lo);
+            vc[slab + kv_v_offset(pos, i + half, d)] = f32_to_bf16(hi);
+        }
+    }
+}
+void launch_qkv_rope_append(const float *part, int ksplit, int T, int hq_l, KvGeom kg, RowMap rm,
+                            const float *cos_tab, const float *sin_tab, bf16_t *q_out, bf16_t *kc, bf16_t *vc,
+                            hipStream_t s) {
+    if (T <= 0) return;
+    hipLaunchKernelGGL(qkv_rope_append_kernel, dim3(T, hq_l + 2 * kg.hkv_l), dim3(kg.d / 2), 0, s, part, ksplit, T,
+                       hq_l, kg, rm, cos_tab, sin_tab, q_out, kc, vc);
+}
+
+// one block per row: h += sum of partials; optional RMSNorm of the new h into packed bf16
+__global__ __launch_bounds__(256) void reduce_resid_norm_kernel(const float *__restrict__ part, int ksplit,
+                                                               float *__restrict__ h, const float *__restrict__ g,
+                                                               bf16_t *__restrict__ np, int T, int H, float eps) {
+    __shared__ float red[4];
+    const int t = blockIdx.x;
+    const int quads = H >> 2;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < quads; c += 256) {
+        float4 v = *reinterpret_cast<const float4 *>(h + (size_t)t * H + c * 4);
+        for (int ks = 0; ks < ksplit; ++ks) {
+            float4 p = *reinterpret_cast<const float4 *>(part + ((size_t)ks * T + t) * H + c * 4);
+            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+        }
+        *reinterpret_cast<float4 *>(h + (size_t)t * H + c * 4) = v;
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    if (g == nullptr) return;
+    ss = block_sum_256(ss, red);   // the barrier inside also orders the h writes above
+    const float rstd = 1.0f / sqrtf(ss / (float)H + eps);
+    const int k_tiles = H >> 5, chunks = H >> 3;
+    for (int c = threadIdx.x; c < chunks; c += 256) {
+        const float4 *p = reinterpret_cast<const float4 *>(h + (size_t)t * H + c * 8);
+        float4 a = p[0], b = p[1];
+        const float4 *gp = reinterpret_cast<const float4 *>(g + c * 8);
+        float4 g0 = gp[0], g1 = gp[1];
+        uint4 o;
+        o.x = pack_bf16x2(a.x * rstd * g0.x, a.y * rstd * g0.y);
+        o.y = pack_bf16x2(a.z * rstd * g0.z, a.w * rstd * g0.w);
+        o.z = pack_bf16x2(b.x * rstd * g1.x, b.y * rstd * g1.y);
+        o.w = pack_bf16x2(b.z * rstd * g1.z, b.w * rstd * g1.w);
+        *reinterpret_cast<uint4 *>(np + frag_offset(t, c * 8, k_tiles)) = o;
+    }
+}
+void launch_reduce_resid_norm(const float *part, int ksplit, float *h, const float *g, bf16_t *n_packed, int T,
+                              int H, float eps, hipStream_t s) {
+    if (T <= 0) return;
+    hipLaunchKernelGGL(reduce_resid_norm_kernel, dim3(T), dim3(256), 0, s, part, ksplit, h, g, n_packed, T, H, eps);
+}
+
+__global__ void reduce_partial_kernel(const float *__restrict__ part, int ksplit, float *__restrict__ dst,
+                                      int64_t TH) {
+    int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i >= TH) return;
+    float4 v = *reinterpret_cast<const float4 *>(part + i);
+    for (int ks = 1; ks < ksplit; ++ks) {
+        float4 p = *reinterpret_cast<const float4 *>(part + (size_t)ks * TH + i);
+        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    }
+    *reinterpret_cast<float4 *>(dst + i) = v;
+}
+void launch_reduce_partial(const float *part, int ksplit, float *dst, int T, int H, hipStream_t s) {
+    int64_t TH = (int64_t)T * H;
+    if (TH <= 0) return;
+    hipLaunchKernelGGL(reduce_partial_kernel, dim3((unsigned)((TH / 4 + 255) / 256)), dim3(256), 0, s, part, ksplit,
+                       dst, TH);
+}
+
+// The W1/W3 projection output interleaves 16-column tiles: tile 2i = W1 (gate) columns 16i..16i+15,
+// tile 2i+1 = W3 (up) columns of the same range.  One thread produces 8 consecutive u values.
+__global__ void reduce_swiglu_kernel(const float *__restrict__ part, int ksplit, bf16_t *__restrict__ up, int T,
+                                     int F_l) {
+    const int t = blockIdx.x;
+    const int chunk = blockIdx.y * blockDim.x + threadIdx.x;
+    if (chunk >= (F_l >> 3)) return;
+    const int f0 = chunk * 8;
+    const int N = 2 * F_l;
+    const int ca = (f0 >> 4) * 32 + (f0 & 15);
+    float a[8], b[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { a[j] = 0.f; b[j] = 0.f; }
+    for (int ks = 0; ks < ksplit; ++ks) {
+        const float4 *pa = reinterpret_cast<const float4 *>(part + ((size_t)ks * T + t) * N + ca);
+        const float4 *pb = reinterpret_cast<const float4 *>(part + ((size_t)ks * T + t) * N + ca + 16);
+        float4 a0 = pa[0], a1 = pa[1], b0 = pb[0], b1 = pb[1];
+        a[0] += a0.x; a[1] += a0.y; a[2] += a0.z; a[3] += a0.w; a[4] += a1.x; a[5] += a1.y; a[6] += a1.z; a[7] += a1.w;
+        b[0] += b0.x; b[1] += b0.y; b[2] += b0.z; b[3] += b0.w; b[4] += b1.x; b[5] += b1.y; b[6] += b1.z; b[7] += b1.w;
+    }
+    float u[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) u[j] = a[j] / (1.0f + __expf(-a[j])) * b[j];
+    uint4 o;
+    o.x = pack_bf16x2(u[0], u[1]); o.y = pack_bf16x2(u[2], u[3]);
+    o.z = pack_bf16x2(u[4], u[5]); o.w = pack_bf16x2(u[6], u[7]);
+    *reinterpret_cast<uint4 *>(up + frag_offset(t, f0, F_l >> 5)) = o;
+}
+void launch_reduce_swiglu(const float *part, int ksplit, bf16_t *u_packed, int T, int F_l, hipStream_t s) {
+    if (T <= 0) return;
+    const int chunks = F_l >> 3;
+    hipLaunchKernelGGL(reduce_swiglu_kernel, dim3(T, (chunks + 255) / 256), dim3(256), 0, s, part, ksplit, u_packed, T,
+                       F_l);
+}

@@ -1,0 +1,122 @@
+// Layout and utility kernels: weight repacking, dtype conversion, row maps, cache staging.
+#include "kernels.h"
+#include "kvlayout.h"
+
+// One thread builds one 16-byte lane slot of the packed matrix.
+__global__ void pack_weight_kernel(const bf16_t *__restrict__ src, int64_t ld, int k0, int c0, int k_tiles,
+                                   int n_tiles, bf16_t *__restrict__ dst, int dst_tile0, int dst_tile_stride) {
+    int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = (int64_t)n_tiles * k_tiles * 64;
+    if (gid >= total) return;
+    int lane = (int)(gid & 63);
+    int64_t tile = gid >> 6;
+    int kt = (int)(tile % k_tiles), nt = (int)(tile / k_tiles);
+    int n = c0 + nt * 16 + (lane & 15);
+    int k = k0 + kt * 32 + 8 * (lane >> 4);
+    union { bf16_t e[8]; uint4 v; } u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) u.e[j] = src[(int64_t)(k + j) * ld + n];
+    int64_t dt = (int64_t)dst_tile0 + (int64_t)nt * dst_tile_stride;
+    *reinterpret_cast<uint4 *>(dst + ((dt * k_tiles + kt) * 64 + lane) * 8) = u.v;
+}
+
+void launch_pack_weight(const bf16_t *src, int64_t ld, int k0, int c0, int K, int N, bf16_t *dst,
+                        int dst_tile0, int dst_tile_stride, hipStream_t s) {
+    int k_tiles = K / 32, n_tiles = N / 16;
+    int64_t total = (int64_t)n_tiles * k_tiles * 64;
+    if (total == 0) return;
+    int blocks = (int)((total + 255) / 256);
+    hipLaunchKernelGGL(pack_weight_kernel, dim3(blocks), dim3(256), 0, s, src, ld, k0, c0, k_tiles, n_tiles,
+                       dst, dst_tile0, dst_tile_stride);
+}
+
+__global__ void cvt_bf16_to_f32_kernel(const bf16_t *__restrict__ src, float *__restrict__ dst, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = bf16_to_f32(src[i]);
+}
+void launch_cvt_bf16_to_f32(const bf16_t *src, float *dst, int64_t n, hipStream_t s) {
+    if (n <= 0) return;
+    int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+    hipLaunchKernelGGL(cvt_bf16_to_f32_kernel, dim3(blocks), dim3(256), 0, s, src, dst, n);
+}
+
+__global__ void accumulate_f32_kernel(float *__restrict__ dst, const float *__restrict__ src, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] += src[i];
+}
+void launch_accumulate_f32(float *dst, const float *src, int64_t n, hipStream_t s) {
+    if (n <= 0) return;
+    int blocks = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+    hipLaunchKernelGGL(accumulate_f32_kernel, dim3(blocks), dim3(256), 0, s, dst, src, n);
+}
+
+__global__ void decode_rowmap_kernel(const int32_t *lens, int32_t *row_seq, int32_t *row_pos, int b) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < b) { row_seq[i] = i; row_pos[i] = lens[i]; }
+}
+void launch_decode_rowmap(const int32_t *lens, int32_t *row_seq, int32_t *row_pos, int b, hipStream_t s) {
+    hipLaunchKernelGGL(decode_rowmap_kernel, dim3((b + 63) / 64), dim3(64), 0, s, lens, row_seq, row_pos, b);
+}
+__global__ void advance_lens_kernel(int32_t *lens, int b) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < b) lens[i] += 1;
+}
+void launch_advance_lens(int32_t *lens, int b, hipStream_t s) {
+    hipLaunchKernelGGL(advance_lens_kernel, dim3((b + 63) / 64), dim3(64), 0, s, lens, b);
+}
+
+__global__ void store_out_kernel(const float *__restrict__ src, void *__restrict__ dst, int dst_is_bf16, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) {
+        if (dst_is_bf16) reinterpret_cast<bf16_t *>(dst)[i] = f32_to_bf16(src[i]);
+        else reinterpret_cast<float *>(dst)[i] = src[i];
+    }
+}
+void launch_store_out(const float *src, void *dst, int dst_is_bf16, int64_t n, hipStream_t s) {
+    if (n <= 0) return;
+    int blocks = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+    hipLaunchKernelGGL(store_out_kernel, dim3(blocks), dim3(256), 0, s, src, dst, dst_is_bf16, n);
+}
+
+// staging [n][hkv_l][d] fp32  <->  packed cache slabs of sequence `seq`
+__global__ void kv_scatter_kernel(const float *__restrict__ k, const float *__restrict__ v, bf16_t *__restrict__ kc,
+                                  bf16_t *__restrict__ vc, KvGeom kg, int seq, int pos0, int n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = (int64_t)n * kg.hkv_l * kg.d;
+    if (i >= total) return;
+    int dd = (int)(i % kg.d);
+    int c = (int)((i / kg.d) % kg.hkv_l);
+    int p = pos0 + (int)(i / ((int64_t)kg.d * kg.hkv_l));
+    size_t slab = (size_t)seq * kg.seq_stride + (size_t)c * kg.smax * kg.d;
+    kc[slab + kv_k_offset(p, dd, kg.d)] = f32_to_bf16(k[i]);
+    vc[slab + kv_v_offset(p, dd, kg.d)] = f32_to_bf16(v[i]);
+}
+void launch_kv_scatter(const float *k, const float *v, bf16_t *kc, bf16_t *vc, KvGeom kg, int seq, int pos0,
+                       int n, hipStream_t s) {
+    int64_t total = (int64_t)n * kg.hkv_l * kg.d;
+    if (total <= 0) return;
+    hipLaunchKernelGGL(kv_scatter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, k, v, kc, vc, kg,
+                       seq, pos0, n);
+}
+__global__ void kv_gather_kernel(const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vc, KvGeom kg, int seq,
+                                 int pos0, int n, float *__restrict__ k, float *__restrict__ v) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = (int64_t)n * kg.hkv_l * kg.d;
+    if (i >= total) return;
+    int dd = (int)(i % kg.d);
+    int c = (int)((i / kg.d) % kg.hkv_l);
+    int p = pos0 + (int)(i / ((int64_t)kg.d * kg.hkv_l));
+    size_t slab = (size_t)seq * kg.seq_stride + (size_t)c * kg.smax * kg.d;
+    k[i] = bf16_to_f32(kc[slab + kv_k_offset(p, dd, kg.d)]);
+    v[i] = bf16_to_f32(vc[slab + kv_v_offset(p, dd, kg.d)]);
+}
+void launch_kv_gather(const bf16_t *kc, const bf16_t *vc, KvGeom kg, int seq, int pos0, int n, float *k, float *v,
+                      hipStream_t s) {
+    int64_t total = (int64_t)n * kg.hkv_l * kg.d;
+    if (total <= 0) return;
+    hipLaunchKernelGGL(kv_gather_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, kc, vc, kg, seq,
+                       pos0, n, k, v);
+}

@@ -1,0 +1,744 @@
+// Host runtime behind the C ABI of include/hexgen.h: argument validation, shard slicing and
+// repacking of the weights, the KV-cache object, the reusable activation workspace (the paper's
+// memory model, Appendix B "Model the memory constraint", counts a handful of activation buffers
+// reused by all layers; the same idea here), and the per-layer launch sequence.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/hexgen.h"
+#include "kernels.h"
+
+#define HX_HIP(expr)                                                          \
+    do {                                                                      \
+        hipError_t e_ = (expr);                                               \
+        if (e_ != hipSuccess) {                                               \
+            (void)hipGetLastError();                                          \
+            return e_ == hipErrorOutOfMemory ? HEXGEN_ERR_OOM : HEXGEN_ERR_DEVICE; \
+        }                                                                     \
+    } while (0)
+#define HX_TRY(expr)                              \
+    do {                                          \
+        hexgen_status_t s_ = (expr);              \
+        if (s_ != HEXGEN_OK) return s_;           \
+    } while (0)
+
+namespace {
+
+constexpr int kMaxKSplit = 16;
+constexpr int kDecodeMaxRows = 32;      // rows handled by the weight-streaming decode kernels
+constexpr int kMaxAttnSplit = 32;
+
+inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+struct Layer {
+    float *g_attn = nullptr, *g_ffn = nullptr;
+    void *wqkv = nullptr, *wo = nullptr, *w13 = nullptr, *w2 = nullptr;
+    bool loaded = false;
+};
+
+struct Workspace {
+    int cap_rows = 0;
+    float *h = nullptr;        // residual stream [T][H] fp32
+    float *part = nullptr;     // projection outputs / split-K partials, fp32
+    float *p32 = nullptr;      // reduced partial [T][H] fp32
+    // bf16 path
+    bf16_t *n = nullptr, *o = nullptr, *u = nullptr, *q = nullptr;
+    float *att_o = nullptr, *att_ml = nullptr;
+    // fp32 path
+    float *n32 = nullptr, *q32 = nullptr, *o32 = nullptr, *u32 = nullptr;
+    // row bookkeeping
+    int32_t *row_seq = nullptr, *row_pos = nullptr, *cu_rows = nullptr, *pos0 = nullptr;
+    int32_t *host_stage = nullptr;   // pinned staging for the arrays above
+    int host_stage_cap = 0;
+};
+
+}  // namespace
+
+struct hexgen_stage {
+    int H, hq, hkv, F, L, t, r;
+    int d, hq_l, hkv_l, F_l, nqkv, qw;     // qw = hq_l * d
+    hexgen_dtype_t dtype;
+    float eps = 1e-5f, theta = 10000.0f;
+    std::vector<Layer> layers;
+    std::vector<void *> taps;
+    Workspace ws;
+    int ws_batch_cap = 0;
+    int64_t weight_bytes = 0;
+};
+
+struct hexgen_kv_cache {
+    hexgen_stage *st;
+    int max_batch, max_seq, smax;          // smax = max_seq rounded up to 32
+    void *k = nullptr, *v = nullptr;       // [L][max_batch][hkv_l][smax][d]
+    int64_t layer_stride;                  // elements
+    float *cos_tab = nullptr, *sin_tab = nullptr;   // [smax][d/2]
+    float rope_theta_built = 0.f;
+    std::vector<int32_t> lens;             // committed lengths (host copy)
+    int32_t *d_lens = nullptr;
+    int batch = 0;
+    bool prefilled = false;
+    int steps = 0;
+};
+
+namespace {
+
+size_t esize(hexgen_dtype_t dt) { return dt == HEXGEN_F32 ? 4 : 2; }
+
+void free_ws(Workspace &w) {
+    void *ptrs[] = {w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.att_o, w.att_ml, w.n32, w.q32, w.o32, w.u32,
+                    w.row_seq, w.row_pos, w.cu_rows, w.pos0};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    if (w.host_stage) (void)hipHostFree(w.host_stage);
+    w = Workspace();
+}
+
+template <typename T>
+hexgen_status_t dmalloc(T **p, size_t count) {
+    *p = nullptr;
+    if (count == 0) count = 1;
+    HX_HIP(hipMalloc(reinterpret_cast<void **>(p), count * sizeof(T)));
+    return HEXGEN_OK;
+}
+
+// (re)allocate the workspace for `rows` token rows and `batch` sequences
+hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
+    Workspace &w = st->ws;
+    if (rows <= w.cap_rows && batch <= st->ws_batch_cap) return HEXGEN_OK;
+    HX_HIP(hipDeviceSynchronize());
+    rows = std::max(rows, w.cap_rows);
+    batch = std::max(batch, st->ws_batch_cap);
+    free_ws(w);
+    st->ws_batch_cap = 0;
+    const size_t T = (size_t)rows, T16 = (size_t)round_up(rows, 16);
+    const size_t nmax = (size_t)std::max(std::max(st->nqkv, st->H), 2 * st->F_l);
+    const size_t part_rows = std::max<size_t>(T, (size_t)kMaxKSplit * std::min(rows, kDecodeMaxRows));
+    HX_TRY(dmalloc(&w.h, T * st->H));
+    HX_TRY(dmalloc(&w.part, part_rows * nmax));
+    HX_TRY(dmalloc(&w.p32, T * st->H));
+    if (st->dtype == HEXGEN_BF16) {
+        HX_TRY(dmalloc(&w.n, T16 * st->H));
+        HX_TRY(dmalloc(&w.o, T16 * st->qw));
+        HX_TRY(dmalloc(&w.u, T16 * st->F_l));
+        HX_TRY(dmalloc(&w.q, T * st->qw));
+        const size_t drows = (size_t)std::min(rows, kDecodeMaxRows);
+        HX_TRY(dmalloc(&w.att_o, drows * st->hq_l * kMaxAttnSplit * st->d));
+        HX_TRY(dmalloc(&w.att_ml, drows * st->hq_l * kMaxAttnSplit * 2));
+        // padded rows of the packed operands are read by the GEMM tiles: keep them finite
+        HX_HIP(hipMemset(w.n, 0, T16 * st->H * sizeof(bf16_t)));
+        HX_HIP(hipMemset(w.o, 0, T16 * st->qw * sizeof(bf16_t)));
+        HX_HIP(hipMemset(w.u, 0, T16 * st->F_l * sizeof(bf16_t)));
+    } else {
+        HX_TRY(dmalloc(&w.n32, T * st->H));
+        HX_TRY(dmalloc(&w.q32, T * st->qw));
+        HX_TRY(dmalloc(&w.o32, T * st->qw));
+        HX_TRY(dmalloc(&w.u32, T * st->F_l));
+    }
+    HX_TRY(dmalloc(&w.row_seq, T));
+    HX_TRY(dmalloc(&w.row_pos, T));
+    HX_TRY(dmalloc(&w.cu_rows, (size_t)batch + 1));
+    HX_TRY(dmalloc(&w.pos0, (size_t)batch));
+    w.host_stage_cap = 2 * rows + 3 * batch + 1;     // row_seq, row_pos, cu_rows, pos0, new lengths
+    HX_HIP(hipHostMalloc(reinterpret_cast<void **>(&w.host_stage), (size_t)w.host_stage_cap * sizeof(int32_t),
+                         hipHostMallocDefault));
+    w.cap_rows = rows;
+    st->ws_batch_cap = batch;
+    return HEXGEN_OK;
+}
+
+struct Rows {
+    int T = 0, batch = 0, max_new = 0;
+    bool decode = false;
+    RowMap rm{};
+};
+
+// Validate the new rows against the cache and build the device row maps.
+hexgen_status_t setup_rows(hexgen_stage *st, hexgen_kv_cache *kv, const int32_t *seq_lens, int batch,
+                           hipStream_t s, Rows *out) {
+    if (batch <= 0) return HEXGEN_ERR_INVALID_ARG;
+    if (batch > kv->max_batch) return HEXGEN_ERR_CAPACITY;
+    Rows r;
+    r.batch = batch;
+    long total = 0;
+    for (int i = 0; i < batch; ++i) {
+        const int n = seq_lens ? seq_lens[i] : 1;
+        if (n < 1) return HEXGEN_ERR_INVALID_ARG;
+        if ((long)kv->lens[i] + n > kv->max_seq) return HEXGEN_ERR_CAPACITY;
+        total += n;
+        r.max_new = std::max(r.max_new, n);
+    }
+    if (total > 0x3fffffff) return HEXGEN_ERR_CAPACITY;
+    r.T = (int)total;
+    r.decode = (r.max_new == 1 && r.T <= kDecodeMaxRows);
+    HX_TRY(ensure_workspace(st, r.T, batch));
+    Workspace &w = st->ws;
+    r.rm.row_seq = w.row_seq;
+    r.rm.row_pos = w.row_pos;
+    if (seq_lens == nullptr && r.decode) {
+        launch_decode_rowmap(kv->d_lens, w.row_seq, w.row_pos, batch, s);
+    } else {
+        // the pinned staging buffer may still feed an earlier async copy on this stream
+        HX_HIP(hipStreamSynchronize(s));
+        int32_t *hs = w.host_stage;
+        int32_t *h_seq = hs, *h_pos = hs + r.T, *h_cu = hs + 2 * r.T, *h_p0 = h_cu + batch + 1;
+        int row = 0;
+        for (int i = 0; i < batch; ++i) {
+            const int n = seq_lens ? seq_lens[i] : 1;
+            h_cu[i] = row;
+            h_p0[i] = kv->lens[i];
+            for (int jn = 0; jn < n; ++jn, ++row) { h_seq[row] = i; h_pos[row] = kv->lens[i] + jn; }
+        }
+        h_cu[batch] = row;
+        HX_HIP(hipMemcpyAsync(w.row_seq, h_seq, sizeof(int32_t) * r.T, hipMemcpyHostToDevice, s));
+        HX_HIP(hipMemcpyAsync(w.row_pos, h_pos, sizeof(int32_t) * r.T, hipMemcpyHostToDevice, s));
+        HX_HIP(hipMemcpyAsync(w.cu_rows, h_cu, sizeof(int32_t) * (batch + 1), hipMemcpyHostToDevice, s));
+        HX_HIP(hipMemcpyAsync(w.pos0, h_p0, sizeof(int32_t) * batch, hipMemcpyHostToDevice, s));
+    }
+    *out = r;
+    return HEXGEN_OK;
+}
+
+KvGeom geom(const hexgen_stage *st, const hexgen_kv_cache *kv) {
+    KvGeom g;
+    g.d = st->d;
+    g.hkv_l = st->hkv_l;
+    g.smax = kv->smax;
+    g.seq_stride = (int64_t)st->hkv_l * kv->smax * st->d;
+    return g;
+}
+
+// ---- bf16 path -------------------------------------------------------------------------------
+int pick_ksplit(int n_units, int k_tiles) {
+    // enough blocks (8 waves each) to cover 256 CUs several times, but at least 4 k-tiles per wave
+    int want = (1024 + n_units - 1) / n_units;
+    int cap = std::max(1, k_tiles / 32);
+    return std::max(1, std::min(std::min(want, cap), kMaxKSplit));
+}
+
+// part <- X . W for the rows of this call; returns the number of K splits written
+int project_bf16(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xp, int N, int K, bool pair,
+                 hipStream_t s) {
+    if (r.decode) {
+        const int ks = pick_ksplit(N / 16 / (pair ? 2 : 1), K / 32);
+        launch_gemv_mfma(static_cast<const bf16_t *>(Wp), Xp, st->ws.part, N, K, r.T, ks, pair ? 1 : 0, s);
+        return ks;
+    }
+    launch_gemm_mfma(static_cast<const bf16_t *>(Wp), Xp, st->ws.part, N, K, r.T, s);
+    return 1;
+}
+
+int pick_attn_split(const hexgen_kv_cache *kv, int batch) {
+    int mx = 0;
+    for (int i = 0; i < batch; ++i) mx = std::max(mx, kv->lens[i] + 1);
+    int n_t32 = (mx + 31) / 32;
+    return std::max(1, std::min(kMaxAttnSplit, n_t32 / 4));
+}
+
+// attention sub-layer from packed n (already normalised) to the split-K partials of W_O in ws.part
+int attn_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Rows &r, hipStream_t s) {
+    Workspace &w = st->ws;
+    const Layer &ly = st->layers[layer];
+    const KvGeom kg = geom(st, kv);
+    bf16_t *kc = static_cast<bf16_t *>(kv->k) + (size_t)layer * kv->layer_stride;
+    bf16_t *vc = static_cast<bf16_t *>(kv->v) + (size_t)layer * kv->layer_stride;
+    int ks = project_bf16(st, r, ly.wqkv, w.n, st->nqkv, st->H, false, s);
+    launch_qkv_rope_append(w.part, ks, r.T, st->hq_l, kg, r.rm, kv->cos_tab, kv->sin_tab, w.q, kc, vc, s);
+    if (r.decode)
+        launch_attn_decode(w.q, kc, vc, kg, st->hq_l, kv->d_lens, r.batch, pick_attn_split(kv, r.batch), w.att_o,
+                           w.att_ml, w.o, s);
+    else
+        launch_attn_prefill(w.q, kc, vc, kg, st->hq_l, w.cu_rows, w.pos0, r.batch, r.max_new, w.o, s);
+    return project_bf16(st, r, ly.wo, w.o, st->H, st->qw, false, s);
+}
+
+int ffn_bf16(hexgen_stage *st, int layer, const Rows &r, hipStream_t s) {
+    Workspace &w = st->ws;
+    const Layer &ly = st->layers[layer];
+    int ks = project_bf16(st, r, ly.w13, w.n, 2 * st->F_l, st->H, true, s);
+    launch_reduce_swiglu(w.part, ks, w.u, r.T, st->F_l, s);
+    return project_bf16(st, r, ly.w2, w.u, st->H, st->F_l, false, s);
+}
+
+hexgen_status_t forward_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
+                             void *out_partial, void *out_resid, hipStream_t s) {
+    Workspace &w = st->ws;
+    launch_rmsnorm_pack(hidden_in, 1, w.h, st->layers[0].g_attn, w.n, r.T, st->H, st->eps, s);
+    for (int l = 0; l < st->L; ++l) {
+        if (st->taps[l])
+            HX_HIP(hipMemcpyAsync(st->taps[l], w.h, sizeof(float) * (size_t)r.T * st->H, hipMemcpyDeviceToDevice, s));
+        int ks = attn_bf16(st, kv, l, r, s);
+        launch_reduce_resid_norm(w.part, ks, w.h, st->layers[l].g_ffn, w.n, r.T, st->H, st->eps, s);
+        ks = ffn_bf16(st, l, r, s);
+        if (l + 1 < st->L) {
+            launch_reduce_resid_norm(w.part, ks, w.h, st->layers[l + 1].g_attn, w.n, r.T, st->H, st->eps, s);
+        } else {
+            launch_reduce_partial(w.part, ks, w.p32, r.T, st->H, s);
+            launch_store_out(w.p32, out_partial, 1, (int64_t)r.T * st->H, s);
+            if (out_resid) launch_store_out(w.h, out_resid, 1, (int64_t)r.T * st->H, s);
+        }
+    }
+    return HEXGEN_OK;
+}
+
+// ---- fp32 path -------------------------------------------------------------------------------
+void attn_f32(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Rows &r, const float *h, float *p_out,
+              hipStream_t s) {
+    Workspace &w = st->ws;
+    const Layer &ly = st->layers[layer];
+    float *kc = static_cast<float *>(kv->k) + (size_t)layer * kv->layer_stride;
+    float *vc = static_cast<float *>(kv->v) + (size_t)layer * kv->layer_stride;
+    f32_launch_rmsnorm(h, ly.g_attn, w.n32, r.T, st->H, st->eps, s);
+    f32_launch_gemm(w.n32, static_cast<const float *>(ly.wqkv), w.part, r.T, st->H, st->nqkv, s);
+    f32_launch_rope_append(w.part, r.T, st->hq_l, st->hkv_l, st->d, kv->smax, r.rm, kv->cos_tab, kv->sin_tab, w.q32, kc,
+                           vc, s);
+    f32_launch_attn(w.q32, kc, vc, r.T, st->hq_l, st->hkv_l, st->d, kv->smax, r.rm, w.o32, s);
+    f32_launch_gemm(w.o32, static_cast<const float *>(ly.wo), p_out, r.T, st->qw, st->H, s);
+}
+void ffn_f32(hexgen_stage *st, int layer, const Rows &r, const float *h, float *p_out, hipStream_t s) {
+    Workspace &w = st->ws;
+    const Layer &ly = st->layers[layer];
+    f32_launch_rmsnorm(h, ly.g_ffn, w.n32, r.T, st->H, st->eps, s);
+    f32_launch_gemm(w.n32, static_cast<const float *>(ly.w13), w.part, r.T, st->H, 2 * st->F_l, s);
+    f32_launch_swiglu(w.part, w.u32, r.T, st->F_l, s);
+    f32_launch_gemm(w.u32, static_cast<const float *>(ly.w2), p_out, r.T, st->F_l, st->H, s);
+}
+hexgen_status_t forward_f32(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
+                            void *out_partial, void *out_resid, hipStream_t s) {
+    Workspace &w = st->ws;
+    const size_t bytes = sizeof(float) * (size_t)r.T * st->H;
+    HX_HIP(hipMemcpyAsync(w.h, hidden_in, bytes, hipMemcpyDeviceToDevice, s));
+    for (int l = 0; l < st->L; ++l) {
+        if (st->taps[l]) HX_HIP(hipMemcpyAsync(st->taps[l], w.h, bytes, hipMemcpyDeviceToDevice, s));
+        attn_f32(st, kv, l, r, w.h, w.p32, s);
+        launch_accumulate_f32(w.h, w.p32, (int64_t)r.T * st->H, s);
+        ffn_f32(st, l, r, w.h, w.p32, s);
+        if (l + 1 < st->L) {
+            launch_accumulate_f32(w.h, w.p32, (int64_t)r.T * st->H, s);
+        } else {
+            HX_HIP(hipMemcpyAsync(out_partial, w.p32, bytes, hipMemcpyDeviceToDevice, s));
+            if (out_resid) HX_HIP(hipMemcpyAsync(out_resid, w.h, bytes, hipMemcpyDeviceToDevice, s));
+        }
+    }
+    return HEXGEN_OK;
+}
+
+hexgen_status_t check_loaded(const hexgen_stage *st) {
+    for (const Layer &l : st->layers)
+        if (!l.loaded) return HEXGEN_ERR_STATE;
+    return HEXGEN_OK;
+}
+
+hexgen_status_t upload_lens(hexgen_kv_cache *kv) {
+    HX_HIP(hipMemcpy(kv->d_lens, kv->lens.data(), sizeof(int32_t) * kv->max_batch, hipMemcpyHostToDevice));
+    return HEXGEN_OK;
+}
+
+void free_layer(Layer &l) {
+    void *ptrs[] = {l.g_attn, l.g_ffn, l.wqkv, l.wo, l.w13, l.w2};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    l = Layer();
+}
+
+}  // namespace
+
+// =================================================================================================
+extern "C" {
+
+const char *hexgen_status_string(hexgen_status_t s) {
+    switch (s) {
+        case HEXGEN_OK: return "ok";
+        case HEXGEN_ERR_INVALID_ARG: return "invalid argument";
+        case HEXGEN_ERR_SHAPE: return "shape not supported / sharding does not divide";
+        case HEXGEN_ERR_STATE: return "call not valid in the current state";
+        case HEXGEN_ERR_CAPACITY: return "capacity exceeded";
+        case HEXGEN_ERR_OOM: return "out of memory";
+        case HEXGEN_ERR_DEVICE: return "device error";
+    }
+    return "unknown status";
+}
+
+hexgen_status_t hexgen_stage_create(int hidden, int n_heads, int n_kv_heads, int ffn, int n_layers, int tp_degree,
+                                    int tp_rank, hexgen_dtype_t dtype, hexgen_stage_t **out) {
+    if (!out) return HEXGEN_ERR_INVALID_ARG;
+    if (hidden <= 0 || n_heads <= 0 || n_kv_heads <= 0 || ffn <= 0 || n_layers <= 0 || tp_degree <= 0)
+        return HEXGEN_ERR_INVALID_ARG;
+    if (dtype != HEXGEN_F32 && dtype != HEXGEN_BF16) return HEXGEN_ERR_INVALID_ARG;
+    if (tp_rank < 0 || tp_rank >= tp_degree) return HEXGEN_ERR_SHAPE;
+    if (hidden % n_heads || n_heads % n_kv_heads || n_heads % tp_degree || n_kv_heads % tp_degree ||
+        ffn % tp_degree)
+        return HEXGEN_ERR_SHAPE;
+    const int d = hidden / n_heads;
+    if (d != 64 && d != 128) return HEXGEN_ERR_SHAPE;
+    const int hq_l = n_heads / tp_degree, hkv_l = n_kv_heads / tp_degree, F_l = ffn / tp_degree;
+    if (hq_l / hkv_l > 16) return HEXGEN_ERR_SHAPE;          // one MFMA column block per query group
+    if (dtype == HEXGEN_BF16 && (hidden % 32 || (hq_l * d) % 32 || F_l % 32)) return HEXGEN_ERR_SHAPE;
+    if (hidden % 8) return HEXGEN_ERR_SHAPE;
+    hexgen_stage *st = new (std::nothrow) hexgen_stage();
+    if (!st) return HEXGEN_ERR_OOM;
+    st->H = hidden; st->hq = n_heads; st->hkv = n_kv_heads; st->F = ffn; st->L = n_layers;
+    st->t = tp_degree; st->r = tp_rank; st->d = d; st->hq_l = hq_l; st->hkv_l = hkv_l; st->F_l = F_l;
+    st->qw = hq_l * d;
+    st->nqkv = (hq_l + 2 * hkv_l) * d;
+    st->dtype = dtype;
+    st->layers.resize(n_layers);
+    st->taps.assign(n_layers, nullptr);
+    *out = st;
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_stage_set_params(hexgen_stage_t *st, float rms_eps, float rope_theta) {
+    if (!st || !(rms_eps >= 0.f) || !(rope_theta > 0.f)) return HEXGEN_ERR_INVALID_ARG;
+    st->eps = rms_eps;
+    st->theta = rope_theta;
+    return HEXGEN_OK;
+}
+
+void hexgen_stage_destroy(hexgen_stage_t *st) {
+    if (!st) return;
+    (void)hipDeviceSynchronize();
+    for (Layer &l : st->layers) free_layer(l);
+    free_ws(st->ws);
+    delete st;
+}
+
+int64_t hexgen_stage_weight_bytes(const hexgen_stage_t *st) { return st ? st->weight_bytes : 0; }
+
+hexgen_status_t hexgen_stage_load_layer(hexgen_stage_t *st, int layer, const void *g_attn, const void *wq,
+                                        const void *wk, const void *wv, const void *wo, const void *g_ffn,
+                                        const void *w1, const void *w3, const void *w2) {
+    if (!st || !g_attn || !wq || !wk || !wv || !wo || !g_ffn || !w1 || !w3 || !w2) return HEXGEN_ERR_INVALID_ARG;
+    if (layer < 0 || layer >= st->L) return HEXGEN_ERR_INVALID_ARG;
+    HX_HIP(hipDeviceSynchronize());
+    Layer &ly = st->layers[layer];
+    if (ly.loaded) st->weight_bytes -= (int64_t)esize(st->dtype) * ((int64_t)st->H * st->nqkv + (int64_t)st->qw * st->H +
+                                                                   3LL * st->H * st->F_l);
+    free_layer(ly);
+    const int H = st->H, d = st->d, r = st->r;
+    const size_t es = esize(st->dtype);
+    const int qcols = st->hq * d, kcols = st->hkv * d;     // global widths
+    const int q0 = r * st->qw, k0 = r * st->hkv_l * d, f0 = r * st->F_l, kw = st->hkv_l * d;
+
+    // gains -> fp32 on device
+    HX_TRY(dmalloc(&ly.g_attn, (size_t)H));
+    HX_TRY(dmalloc(&ly.g_ffn, (size_t)H));
+    if (st->dtype == HEXGEN_F32) {
+        HX_HIP(hipMemcpy(ly.g_attn, g_attn, sizeof(float) * H, hipMemcpyDefault));
+        HX_HIP(hipMemcpy(ly.g_ffn, g_ffn, sizeof(float) * H, hipMemcpyDefault));
+    } else {
+        bf16_t *tmp = nullptr;
+        HX_TRY(dmalloc(&tmp, (size_t)2 * H));
+        hipError_t e1 = hipMemcpy(tmp, g_attn, sizeof(bf16_t) * H, hipMemcpyDefault);
+        hipError_t e2 = hipMemcpy(tmp + H, g_ffn, sizeof(bf16_t) * H, hipMemcpyDefault);
+        if (e1 == hipSuccess && e2 == hipSuccess) {
+            launch_cvt_bf16_to_f32(tmp, ly.g_attn, H, nullptr);
+            launch_cvt_bf16_to_f32(tmp + H, ly.g_ffn, H, nullptr);
+            e1 = hipDeviceSynchronize();
+        }
+        (void)hipFree(tmp);
+        HX_HIP(e1);
+        HX_HIP(e2);
+    }
+
+    const size_t n_qkv = (size_t)H * st->nqkv, n_wo = (size_t)st->qw * H, n_13 = (size_t)H * 2 * st->F_l,
+                 n_w2 = (size_t)st->F_l * H;
+    HX_HIP(hipMalloc(&ly.wqkv, n_qkv * es));
+    HX_HIP(hipMalloc(&ly.wo, n_wo * es));
+    HX_HIP(hipMalloc(&ly.w13, n_13 * es));
+    HX_HIP(hipMalloc(&ly.w2, n_w2 * es));
+
+    auto cbytes = [&](int cols) { return (size_t)cols * es; };
+    auto src_at = [&](const void *base, size_t row, size_t col, size_t ld) {
+        return static_cast<const char *>(base) + (row * ld + col) * es;
+    };
+    if (st->dtype == HEXGEN_F32) {
+        // plain layouts: wqkv [H][q | k | v], w13 [H][w1 | w3]; row shards are contiguous
+        char *qkv = static_cast<char *>(ly.wqkv);
+        HX_HIP(hipMemcpy2D(qkv, cbytes(st->nqkv), src_at(wq, 0, q0, qcols), cbytes(qcols), cbytes(st->qw), H,
+                           hipMemcpyDefault));
+        HX_HIP(hipMemcpy2D(qkv + cbytes(st->qw), cbytes(st->nqkv), src_at(wk, 0, k0, kcols), cbytes(kcols), cbytes(kw),
+                           H, hipMemcpyDefault));
+        HX_HIP(hipMemcpy2D(qkv + cbytes(st->qw + kw), cbytes(st->nqkv), src_at(wv, 0, k0, kcols), cbytes(kcols),
+                           cbytes(kw), H, hipMemcpyDefault));
+        char *w13 = static_cast<char *>(ly.w13);
+        HX_HIP(hipMemcpy2D(w13, cbytes(2 * st->F_l), src_at(w1, 0, f0, st->F), cbytes(st->F), cbytes(st->F_l), H,
+                           hipMemcpyDefault));
+        HX_HIP(hipMemcpy2D(w13 + cbytes(st->F_l), cbytes(2 * st->F_l), src_at(w3, 0, f0, st->F), cbytes(st->F),
+                           cbytes(st->F_l), H, hipMemcpyDefault));
+        HX_HIP(hipMemcpy(ly.wo, src_at(wo, q0, 0, H), n_wo * es, hipMemcpyDefault));
+        HX_HIP(hipMemcpy(ly.w2, src_at(w2, f0, 0, H), n_w2 * es, hipMemcpyDefault));
+    } else {
+        // stage each shard in a dense device buffer, then repack it into MFMA fragment order
+        const size_t tmp_elems = std::max(std::max((size_t)H * st->qw, (size_t)H * st->F_l), n_wo);
+        bf16_t *tmp = nullptr;
+        HX_TRY(dmalloc(&tmp, tmp_elems));
+        hexgen_status_t rc = HEXGEN_OK;
+        auto col_shard = [&](const void *src, int c0, int gcols, int cols, void *dst, int tile0, int stride) {
+            if (rc != HEXGEN_OK) return;
+            hipError_t e = hipMemcpy2D(tmp, cbytes(cols), src_at(src, 0, c0, gcols), cbytes(gcols), cbytes(cols), H,
+                                       hipMemcpyDefault);
+            if (e != hipSuccess) { rc = HEXGEN_ERR_DEVICE; return; }
+            launch_pack_weight(tmp, cols, 0, 0, H, cols, static_cast<bf16_t *>(dst), tile0, stride, nullptr);
+            if (hipDeviceSynchronize() != hipSuccess) rc = HEXGEN_ERR_DEVICE;
+        };
+        auto row_shard = [&](const void *src, int r0, int rows, void *dst) {
+            if (rc != HEXGEN_OK) return;
+            hipError_t e = hipMemcpy(tmp, src_at(src, r0, 0, H), (size_t)rows * H * es, hipMemcpyDefault);
+            if (e != hipSuccess) { rc = HEXGEN_ERR_DEVICE; return; }
+            launch_pack_weight(tmp, H, 0, 0, rows, H, static_cast<bf16_t *>(dst), 0, 1, nullptr);
+            if (hipDeviceSynchronize() != hipSuccess) rc = HEXGEN_ERR_DEVICE;
+        };
+        col_shard(wq, q0, qcols, st->qw, ly.wqkv, 0, 1);
+        col_shard(wk, k0, kcols, kw, ly.wqkv, st->qw / 16, 1);
+        col_shard(wv, k0, kcols, kw, ly.wqkv, (st->qw + kw) / 16, 1);
+        col_shard(w1, f0, st->F, st->F_l, ly.w13, 0, 2);     // gate tiles at even positions
+        col_shard(w3, f0, st->F, st->F_l, ly.w13, 1, 2);     // up tiles at odd positions
+        row_shard(wo, q0, st->qw, ly.wo);
+        row_shard(w2, f0, st->F_l, ly.w2);
+        (void)hipFree(tmp);
+        if (rc != HEXGEN_OK) { (void)hipGetLastError(); free_layer(ly); return rc; }
+    }
+    ly.loaded = true;
+    st->weight_bytes += (int64_t)es * (int64_t)(n_qkv + n_wo + n_13 + n_w2);
+    return HEXGEN_OK;
+}
+
+// ---- KV cache ------------------------------------------------------------------------------------
+hexgen_status_t hexgen_kv_cache_create(hexgen_stage_t *st, int max_batch, int max_seq, hexgen_kv_cache_t **out) {
+    if (!st || !out || max_batch <= 0 || max_seq <= 0) return HEXGEN_ERR_INVALID_ARG;
+    if (st->dtype == HEXGEN_F32 && max_seq > 8192) return HEXGEN_ERR_CAPACITY;   // fp32 attention keeps scores in LDS
+    hexgen_kv_cache *kv = new (std::nothrow) hexgen_kv_cache();
+    if (!kv) return HEXGEN_ERR_OOM;
+    kv->st = st;
+    kv->max_batch = max_batch;
+    kv->max_seq = max_seq;
+    kv->smax = round_up(max_seq, 32);
+    kv->layer_stride = (int64_t)max_batch * st->hkv_l * kv->smax * st->d;
+    kv->lens.assign(max_batch, 0);
+    const size_t bytes = (size_t)st->L * kv->layer_stride * esize(st->dtype);
+    const int half = st->d / 2;
+    std::vector<float> cs((size_t)kv->smax * half), sn((size_t)kv->smax * half);
+    for (int p = 0; p < kv->smax; ++p)
+        for (int i = 0; i < half; ++i) {
+            const double ang = (double)p * std::pow((double)st->theta, -2.0 * i / st->d);
+            cs[(size_t)p * half + i] = (float)std::cos(ang);
+            sn[(size_t)p * half + i] = (float)std::sin(ang);
+        }
+    hipError_t e = hipMalloc(&kv->k, bytes);
+    if (e == hipSuccess) e = hipMalloc(&kv->v, bytes);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&kv->cos_tab), cs.size() * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&kv->sin_tab), sn.size() * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&kv->d_lens), sizeof(int32_t) * max_batch);
+    if (e == hipSuccess) e = hipMemset(kv->k, 0, bytes);
+    if (e == hipSuccess) e = hipMemset(kv->v, 0, bytes);
+    if (e == hipSuccess) e = hipMemset(kv->d_lens, 0, sizeof(int32_t) * max_batch);
+    if (e == hipSuccess) e = hipMemcpy(kv->cos_tab, cs.data(), cs.size() * sizeof(float), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(kv->sin_tab, sn.data(), sn.size() * sizeof(float), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        hexgen_kv_cache_destroy(kv);
+        return e == hipErrorOutOfMemory ? HEXGEN_ERR_OOM : HEXGEN_ERR_DEVICE;
+    }
+    kv->rope_theta_built = st->theta;
+    *out = kv;
+    return HEXGEN_OK;
+}
+
+void hexgen_kv_cache_destroy(hexgen_kv_cache_t *kv) {
+    if (!kv) return;
+    (void)hipDeviceSynchronize();
+    void *ptrs[] = {kv->k, kv->v, kv->cos_tab, kv->sin_tab, kv->d_lens};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    delete kv;
+}
+
+hexgen_status_t hexgen_kv_cache_reset(hexgen_kv_cache_t *kv) {
+    if (!kv) return HEXGEN_ERR_INVALID_ARG;
+    HX_HIP(hipDeviceSynchronize());
+    std::fill(kv->lens.begin(), kv->lens.end(), 0);
+    kv->batch = 0;
+    kv->prefilled = false;
+    kv->steps = 0;
+    return upload_lens(kv);
+}
+
+hexgen_status_t hexgen_kv_cache_set_lengths(hexgen_kv_cache_t *kv, const int32_t *lens, int batch) {
+    if (!kv || !lens || batch <= 0) return HEXGEN_ERR_INVALID_ARG;
+    if (batch > kv->max_batch) return HEXGEN_ERR_CAPACITY;
+    for (int i = 0; i < batch; ++i) {
+        if (lens[i] < 0) return HEXGEN_ERR_INVALID_ARG;
+        if (lens[i] > kv->max_seq) return HEXGEN_ERR_CAPACITY;
+    }
+    HX_HIP(hipDeviceSynchronize());
+    std::fill(kv->lens.begin(), kv->lens.end(), 0);
+    for (int i = 0; i < batch; ++i) kv->lens[i] = lens[i];
+    kv->batch = batch;
+    kv->prefilled = true;
+    kv->steps = 0;
+    return upload_lens(kv);
+}
+
+hexgen_status_t hexgen_kv_cache_get_lengths(hexgen_kv_cache_t *kv, int32_t *lens_out, int batch) {
+    if (!kv || !lens_out || batch <= 0 || batch > kv->max_batch) return HEXGEN_ERR_INVALID_ARG;
+    for (int i = 0; i < batch; ++i) lens_out[i] = kv->lens[i];
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_kv_cache_commit(hexgen_kv_cache_t *kv, const int32_t *seq_lens, int batch) {
+    if (!kv || batch <= 0) return HEXGEN_ERR_INVALID_ARG;
+    if (batch > kv->max_batch) return HEXGEN_ERR_CAPACITY;
+    for (int i = 0; i < batch; ++i) {
+        const int n = seq_lens ? seq_lens[i] : 1;
+        if (n < 0) return HEXGEN_ERR_INVALID_ARG;
+        if ((long)kv->lens[i] + n > kv->max_seq) return HEXGEN_ERR_CAPACITY;
+    }
+    HX_HIP(hipDeviceSynchronize());
+    for (int i = 0; i < batch; ++i) kv->lens[i] += seq_lens ? seq_lens[i] : 1;
+    kv->batch = std::max(kv->batch, batch);
+    kv->prefilled = true;
+    return upload_lens(kv);
+}
+
+static hexgen_status_t kv_io(hexgen_kv_cache_t *kv, int layer, int seq, int pos0, int n, float *k, float *v,
+                             bool to_cache) {
+    if (!kv || !k || !v) return HEXGEN_ERR_INVALID_ARG;
+    hexgen_stage *st = kv->st;
+    if (layer < 0 || layer >= st->L || seq < 0 || seq >= kv->max_batch || pos0 < 0 || n < 0)
+        return HEXGEN_ERR_INVALID_ARG;
+    if ((long)pos0 + n > kv->max_seq) return HEXGEN_ERR_CAPACITY;
+    if (n == 0) return HEXGEN_OK;
+    HX_HIP(hipDeviceSynchronize());
+    const size_t cnt = (size_t)n * st->hkv_l * st->d;
+    float *dk = nullptr, *dv = nullptr;
+    HX_TRY(dmalloc(&dk, cnt));
+    hexgen_status_t rc = dmalloc(&dv, cnt);
+    if (rc != HEXGEN_OK) { (void)hipFree(dk); return rc; }
+    hipError_t e = hipSuccess;
+    if (to_cache) {
+        e = hipMemcpy(dk, k, cnt * sizeof(float), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(dv, v, cnt * sizeof(float), hipMemcpyHostToDevice);
+    }
+    if (e == hipSuccess) {
+        if (st->dtype == HEXGEN_BF16) {
+            bf16_t *kc = static_cast<bf16_t *>(kv->k) + (size_t)layer * kv->layer_stride;
+            bf16_t *vc = static_cast<bf16_t *>(kv->v) + (size_t)layer * kv->layer_stride;
+            if (to_cache) launch_kv_scatter(dk, dv, kc, vc, geom(st, kv), seq, pos0, n, nullptr);
+            else launch_kv_gather(kc, vc, geom(st, kv), seq, pos0, n, dk, dv, nullptr);
+        } else {
+            float *kc = static_cast<float *>(kv->k) + (size_t)layer * kv->layer_stride;
+            float *vc = static_cast<float *>(kv->v) + (size_t)layer * kv->layer_stride;
+            f32_launch_kv_copy(kc, vc, dk, dv, st->hkv_l, st->d, kv->smax, seq, pos0, n, to_cache ? 1 : 0, nullptr);
+        }
+        e = hipDeviceSynchronize();
+    }
+    if (e == hipSuccess && !to_cache) {
+        e = hipMemcpy(k, dk, cnt * sizeof(float), hipMemcpyDeviceToHost);
+        if (e == hipSuccess) e = hipMemcpy(v, dv, cnt * sizeof(float), hipMemcpyDeviceToHost);
+    }
+    (void)hipFree(dk);
+    (void)hipFree(dv);
+    HX_HIP(e);
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_kv_cache_read(hexgen_kv_cache_t *kv, int layer, int seq, int pos0, int n, float *k_out,
+                                     float *v_out) {
+    return kv_io(kv, layer, seq, pos0, n, k_out, v_out, false);
+}
+hexgen_status_t hexgen_kv_cache_fill(hexgen_kv_cache_t *kv, int layer, int seq, int n, const float *k,
+                                     const float *v) {
+    return kv_io(kv, layer, seq, 0, n, const_cast<float *>(k), const_cast<float *>(v), true);
+}
+
+// ---- prefill / decode ------------------------------------------------------------------------------
+hexgen_status_t hexgen_stage_prefill(hexgen_stage_t *st, hexgen_kv_cache_t *kv, const void *hidden_in,
+                                     const int32_t *seq_lens, int batch, void *out_partial, void *out_resid,
+                                     void *stream) {
+    if (!st || !kv || !hidden_in || !seq_lens || !out_partial || kv->st != st) return HEXGEN_ERR_INVALID_ARG;
+    HX_TRY(check_loaded(st));
+    if (batch <= 0) return HEXGEN_ERR_INVALID_ARG;
+    if (batch > kv->max_batch) return HEXGEN_ERR_CAPACITY;
+    for (int i = 0; i < batch; ++i) {
+        if (seq_lens[i] < 1) return HEXGEN_ERR_INVALID_ARG;
+        if (seq_lens[i] > kv->max_seq) return HEXGEN_ERR_CAPACITY;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HX_TRY(hexgen_kv_cache_reset(kv));
+    Rows r;
+    HX_TRY(setup_rows(st, kv, seq_lens, batch, s, &r));
+    r.decode = false;                       // a prefill always takes the GEMM path
+    if (st->dtype == HEXGEN_BF16) HX_TRY(forward_bf16(st, kv, r, hidden_in, out_partial, out_resid, s));
+    else HX_TRY(forward_f32(st, kv, r, hidden_in, out_partial, out_resid, s));
+    for (int i = 0; i < batch; ++i) kv->lens[i] = seq_lens[i];
+    kv->batch = batch;
+    kv->prefilled = true;
+    kv->steps = 0;
+    // the new lengths reach the device in stream order, behind the kernels of this call
+    int32_t *h_len = st->ws.host_stage + 2 * r.T + 2 * batch + 1;
+    for (int i = 0; i < batch; ++i) h_len[i] = seq_lens[i];
+    HX_HIP(hipMemcpyAsync(kv->d_lens, h_len, sizeof(int32_t) * batch, hipMemcpyHostToDevice, s));
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_stage_decode(hexgen_stage_t *st, hexgen_kv_cache_t *kv, int step, const void *hidden_in,
+                                    void *out_partial, void *out_resid, void *stream) {
+    if (!st || !kv || !hidden_in || !out_partial || kv->st != st) return HEXGEN_ERR_INVALID_ARG;
+    HX_TRY(check_loaded(st));
+    if (!kv->prefilled || kv->batch <= 0 || step != kv->steps) return HEXGEN_ERR_STATE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Rows r;
+    HX_TRY(setup_rows(st, kv, nullptr, kv->batch, s, &r));
+    if (st->dtype == HEXGEN_BF16) HX_TRY(forward_bf16(st, kv, r, hidden_in, out_partial, out_resid, s));
+    else HX_TRY(forward_f32(st, kv, r, hidden_in, out_partial, out_resid, s));
+    launch_advance_lens(kv->d_lens, kv->batch, s);
+    for (int i = 0; i < kv->batch; ++i) kv->lens[i] += 1;
+    kv->steps += 1;
+    return HEXGEN_OK;
+}
+
+// ---- validation surface ----------------------------------------------------------------------------
+hexgen_status_t hexgen_stage_run_sublayer(hexgen_stage_t *st, hexgen_kv_cache_t *kv, int layer, int which,
+                                          const void *h_in, const int32_t *seq_lens, int batch, void *partial_out,
+                                          void *stream) {
+    if (!st || !kv || !h_in || !partial_out || kv->st != st) return HEXGEN_ERR_INVALID_ARG;
+    if (layer < 0 || layer >= st->L || (which != 0 && which != 1)) return HEXGEN_ERR_INVALID_ARG;
+    if (!st->layers[layer].loaded) return HEXGEN_ERR_STATE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Rows r;
+    HX_TRY(setup_rows(st, kv, seq_lens, batch, s, &r));
+    const float *h = static_cast<const float *>(h_in);
+    float *p = static_cast<float *>(partial_out);
+    Workspace &w = st->ws;
+    if (st->dtype == HEXGEN_BF16) {
+        const Layer &ly = st->layers[layer];
+        launch_rmsnorm_pack(h, 0, nullptr, which == 0 ? ly.g_attn : ly.g_ffn, w.n, r.T, st->H, st->eps, s);
+        const int ks = which == 0 ? attn_bf16(st, kv, layer, r, s) : ffn_bf16(st, layer, r, s);
+        launch_reduce_partial(w.part, ks, p, r.T, st->H, s);
+    } else {
+        if (which == 0) attn_f32(st, kv, layer, r, h, p, s);
+        else ffn_f32(st, layer, r, h, p, s);
+    }
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_accumulate_f32(void *dst, const void *src, int64_t n, void *stream) {
+    if (!dst || !src || n < 0) return HEXGEN_ERR_INVALID_ARG;
+    launch_accumulate_f32(static_cast<float *>(dst), static_cast<const float *>(src), n, static_cast<hipStream_t>(stream));
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_stage_set_tap(hexgen_stage_t *st, int layer, void *h_dump) {
+    if (!st || layer < 0 || layer >= st->L) return HEXGEN_ERR_INVALID_ARG;
+    st->taps[layer] = h_dump;
+    return HEXGEN_OK;
+}
+
+}  // extern "C"

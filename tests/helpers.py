@@ -1,0 +1,65 @@
+"""Shared helpers for the GPU parity tests: build both sides from one set of seeded inputs."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from workloads import generate
+
+ORDER = generate.LAYER_TENSOR_ORDER
+TOL = {"f32": 1e-4, "bf16": 2e-2}     # max per-row ||gpu - ref|| / ||ref||  (spec tolerances)
+
+
+def row_rel_err(gpu, ref) -> float:
+    """max over rows of ||gpu_i - ref_i||_2 / ||ref_i||_2 (stricter than a whole-tensor norm)."""
+    g = np.asarray(gpu, dtype=np.float64).reshape(-1, np.asarray(ref).shape[-1])
+    r = np.asarray(ref, dtype=np.float64).reshape(g.shape)
+    num = np.linalg.norm(g - r, axis=1)
+    den = np.linalg.norm(r, axis=1)
+    return float(np.max(num / den))
+
+
+def torch_dtype(cfg):
+    return torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+
+
+def make_oracle(cfg, rank, weights, n_layers=None):
+    from oracle import stage_oracle as so
+    L = cfg.n_layers if n_layers is None else n_layers
+    st = so.OracleStage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, L, cfg.tp_degree, rank,
+                        cfg.rms_eps, cfg.rope_theta)
+    for l in range(L):
+        st.load_layer(l, *[weights[l][k] for k in ORDER])
+    return st
+
+
+def make_gpu_stage(cfg, rank, weights, n_layers=None):
+    import paper_2311_11514_amd as hx
+    L = cfg.n_layers if n_layers is None else n_layers
+    st = hx.Stage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, L, cfg.tp_degree, rank, cfg.dtype,
+                  cfg.rms_eps, cfg.rope_theta)
+    for l in range(L):
+        st.load_layer(l, *[weights[l][k] for k in ORDER])
+    return st
+
+
+def to_dev(x, cfg):
+    return x.to(device="cuda", dtype=torch_dtype(cfg)).contiguous()
+
+
+def gpu_prefill(st, kv, cfg, x, seq_lens):
+    xin = to_dev(x, cfg)
+    outp = torch.empty_like(xin)
+    outr = torch.empty_like(xin)
+    st.prefill(kv, xin, seq_lens, outp, outr)
+    torch.cuda.synchronize()
+    return outp.float().cpu().numpy(), outr.float().cpu().numpy()
+
+
+def gpu_decode(st, kv, cfg, step, x):
+    xin = to_dev(x, cfg)
+    outp = torch.empty_like(xin)
+    outr = torch.empty_like(xin)
+    st.decode(kv, step, xin, outp, outr)
+    torch.cuda.synchronize()
+    return outp.float().cpu().numpy(), outr.float().cpu().numpy()

@@ -1,0 +1,224 @@
+"""GPU parity on sizes the CPU oracle finishes in seconds: the tiny fp32 stage (both ranks, group mode,
+greedy tokens) and reduced-width bf16 stages that still span several MFMA tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import CONFIGS, StageConfig, generate
+from tests.helpers import (ORDER, TOL, gpu_decode, gpu_prefill, make_gpu_stage, make_oracle, row_rel_err, to_dev)
+
+pytestmark = pytest.mark.gpu
+
+TINY = CONFIGS["tiny_f32"]
+
+# reduced-width bf16 stages: same structure as the 70B shards (GQA, head_dim 128 and 64, SwiGLU)
+MINI128 = StageConfig("mini128", "bf16", 1024, 8, 2, 2816, 3, 2, (1,), batch=3, seed=11)
+MINI64 = StageConfig("mini64", "bf16", 512, 8, 4, 1408, 2, 1, (0,), batch=2, seed=12)
+
+
+def _weights(cfg, n_layers=None):
+    return [generate.layer_weights(cfg, l) for l in range(n_layers or cfg.n_layers)]
+
+
+def test_tiny_f32_solo_prefill_and_decode():
+    cfg = TINY
+    w = _weights(cfg)
+    X = generate.hidden_rows(cfg, cfg.prompt_len)
+    for rank in cfg.tp_ranks:
+        ora = make_oracle(cfg, rank, w)
+        oc = ora.new_cache(1)
+        p_ref, h_ref = ora.prefill(oc, X, [cfg.prompt_len])
+        st = make_gpu_stage(cfg, rank, w)
+        kv = st.kv_cache_create(1, 64)
+        p, h = gpu_prefill(st, kv, cfg, X, [cfg.prompt_len])
+        assert row_rel_err(p, p_ref) < TOL["f32"] and row_rel_err(h, h_ref) < TOL["f32"]
+        for k in range(4):
+            x = generate.hidden_rows(cfg, 1, stream_id=1 + k)
+            p_ref, h_ref = ora.decode(oc, x)
+            p, h = gpu_decode(st, kv, cfg, k, x)
+            assert row_rel_err(p, p_ref) < TOL["f32"] and row_rel_err(h, h_ref) < TOL["f32"]
+        # cache contents (K after rotation) match the oracle's cache
+        kk, vv = kv.read(1, 0, 0, cfg.prompt_len + 4)
+        assert row_rel_err(kk.numpy().reshape(-1, cfg.head_dim), oc.k[1][0].reshape(-1, cfg.head_dim)) < TOL["f32"]
+        assert row_rel_err(vv.numpy().reshape(-1, cfg.head_dim), oc.v[1][0].reshape(-1, cfg.head_dim)) < TOL["f32"]
+
+
+def _gpu_group_forward(stages, kvs, cfg, h_in, seq_lens, batch):
+    """All ranks one after another on the same GPU, partials summed in rank order (fp32)."""
+    import paper_2311_11514_amd as hx
+    h = h_in.to(device="cuda", dtype=torch.float32).contiguous()
+    part = torch.empty_like(h)
+    parts = None
+    for layer in range(cfg.n_layers):
+        for which in (0, 1):
+            last = layer == cfg.n_layers - 1 and which == 1
+            ps = []
+            for st, kv in zip(stages, kvs):
+                p = torch.empty_like(h)
+                st.run_sublayer(kv, layer, which, h, seq_lens, batch, p)
+                ps.append(p)
+            if last:
+                parts = ps
+            else:
+                for p in ps:
+                    hx.accumulate_f32(h, p)
+    for kv in kvs:
+        kv.commit(seq_lens, batch)
+    torch.cuda.synchronize()
+    return [p.cpu().numpy() for p in parts], h.cpu().numpy()
+
+
+def test_tiny_f32_group_mode_greedy_tokens():
+    """The tiny configuration as stated: both ranks run, partials summed, 32-row prompt, 8 greedy steps
+    through a 1000-entry embedding / LM head; GPU tokens must equal the oracle's."""
+    from oracle import stage_oracle as so
+    cfg = TINY
+    w = _weights(cfg)
+    head = generate.head_weights(cfg)
+    E = head["embedding"]
+    X = generate.hidden_rows(cfg, cfg.prompt_len)
+
+    oracles = [make_oracle(cfg, r, w) for r in cfg.tp_ranks]
+    ocaches = [o.new_cache(1) for o in oracles]
+    stages = [make_gpu_stage(cfg, r, w) for r in cfg.tp_ranks]
+    kvs = [s.kv_cache_create(1, 64) for s in stages]
+
+    def pick(x_last):
+        return so.greedy_head(x_last, head["g_final"], head["w_lm"], cfg.rms_eps)
+
+    x_o, x_g = X, X
+    seq_lens, toks_o, toks_g = [cfg.prompt_len], [], []
+    for step in range(cfg.decode_steps):
+        seqs = [0] * x_o.shape[0]
+        parts_o, resid_o = so.group_forward(oracles, ocaches, x_o, seqs)
+        parts_g, resid_g = _gpu_group_forward(stages, kvs, cfg, x_g, seq_lens if step == 0 else None, 1)
+        out_o = resid_o + sum(parts_o)
+        out_g = resid_g + sum(np.asarray(p, dtype=np.float64) for p in parts_g)
+        assert row_rel_err(out_g, out_o) < TOL["f32"]
+        for pg, po in zip(parts_g, parts_o):
+            assert row_rel_err(pg, po) < TOL["f32"]
+        t_o, logits_o = pick(out_o[-1])
+        t_g, _ = pick(out_g[-1])
+        top2 = np.sort(logits_o)[-2:]
+        assert top2[1] - top2[0] > 1e-6, "oracle argmax is a near-tie; token comparison would be meaningless"
+        toks_o.append(t_o)
+        toks_g.append(t_g)
+        x_o = E[t_o][None, :]
+        x_g = E[t_g][None, :]
+    assert toks_g == toks_o
+
+
+@pytest.mark.parametrize("cfg,lens", [(MINI128, [37, 5, 64]), (MINI64, [16, 33])])
+def test_bf16_small_prefill_then_decode(cfg, lens):
+    w = _weights(cfg)
+    rank = cfg.tp_ranks[0]
+    X = generate.hidden_rows(cfg, sum(lens))
+    ora = make_oracle(cfg, rank, w)
+    oc = ora.new_cache(len(lens))
+    p_ref, h_ref = ora.prefill(oc, X, lens)
+    st = make_gpu_stage(cfg, rank, w)
+    kv = st.kv_cache_create(len(lens), 128)
+    p, h = gpu_prefill(st, kv, cfg, X, lens)
+    assert row_rel_err(h, h_ref) < TOL["bf16"]
+    assert row_rel_err(p, p_ref) < TOL["bf16"]
+    assert kv.get_lengths(len(lens)) == lens
+    for k in range(5):
+        x = generate.hidden_rows(cfg, len(lens), stream_id=1 + k)
+        p_ref, h_ref = ora.decode(oc, x)
+        p, h = gpu_decode(st, kv, cfg, k, x)
+        assert row_rel_err(h, h_ref) < TOL["bf16"], f"decode step {k}"
+        assert row_rel_err(p, p_ref) < TOL["bf16"], f"decode step {k}"
+    # K (after rotation) and V written by prefill and decode, for every layer and sequence
+    for layer in range(cfg.n_layers):
+        for s, n in enumerate(lens):
+            kk, vv = kv.read(layer, s, 0, n + 5)
+            assert row_rel_err(kk.numpy().reshape(-1, cfg.head_dim), oc.k[layer][s].reshape(-1, cfg.head_dim)) < TOL["bf16"]
+            assert row_rel_err(vv.numpy().reshape(-1, cfg.head_dim), oc.v[layer][s].reshape(-1, cfg.head_dim)) < TOL["bf16"]
+
+
+def test_bf16_decode_from_synthetic_context():
+    """Decode-only workloads start from an installed synthetic KV context (ragged lengths here)."""
+    cfg = MINI128
+    w = _weights(cfg)
+    rank = cfg.tp_ranks[0]
+    ctx = [70, 1, 33, 64]
+    ora = make_oracle(cfg, rank, w)
+    oc = ora.new_cache(len(ctx))
+    st = make_gpu_stage(cfg, rank, w)
+    kv = st.kv_cache_create(len(ctx), 96)
+    for layer in range(cfg.n_layers):
+        for s, n in enumerate(ctx):
+            k, v = generate.synthetic_kv(cfg, layer, s, n)
+            oc.fill(layer, s, k, v)
+            kv.fill(layer, s, k, v)
+    kv.set_lengths(ctx)
+    for step in range(3):
+        x = generate.hidden_rows(cfg, len(ctx), stream_id=1 + step)
+        p_ref, h_ref = ora.decode(oc, x)
+        p, h = gpu_decode(st, kv, cfg, step, x)
+        assert row_rel_err(h, h_ref) < TOL["bf16"] and row_rel_err(p, p_ref) < TOL["bf16"]
+
+
+def test_bf16_batch32_decode_uses_two_token_tiles():
+    cfg = MINI64
+    w = _weights(cfg)
+    b = 32
+    ctx = [1 + (7 * i) % 50 for i in range(b)]
+    ora = make_oracle(cfg, 0, w)
+    oc = ora.new_cache(b)
+    st = make_gpu_stage(cfg, 0, w)
+    kv = st.kv_cache_create(b, 64)
+    for layer in range(cfg.n_layers):
+        for s, n in enumerate(ctx):
+            k, v = generate.synthetic_kv(cfg, layer, s, n)
+            oc.fill(layer, s, k, v)
+            kv.fill(layer, s, k, v)
+    kv.set_lengths(ctx)
+    for step in range(2):
+        x = generate.hidden_rows(cfg, b, stream_id=1 + step)
+        p_ref, h_ref = ora.decode(oc, x)
+        p, h = gpu_decode(st, kv, cfg, step, x)
+        assert row_rel_err(h, h_ref) < TOL["bf16"] and row_rel_err(p, p_ref) < TOL["bf16"]
+
+
+def test_run_to_run_determinism_bf16():
+    cfg = MINI128
+    w = _weights(cfg)
+    lens = [37, 5, 64]
+    X = generate.hidden_rows(cfg, sum(lens))
+    st = make_gpu_stage(cfg, 1, w)
+    kv = st.kv_cache_create(3, 128)
+    outs = []
+    for _ in range(2):
+        p, h = gpu_prefill(st, kv, cfg, X, lens)
+        x = generate.hidden_rows(cfg, 3, stream_id=1)
+        pd, hd = gpu_decode(st, kv, cfg, 0, x)
+        outs.append((p, h, pd, hd))
+    for a, b in zip(outs[0], outs[1]):
+        assert np.array_equal(a, b)
+
+
+def test_error_paths_on_device():
+    import paper_2311_11514_amd as hx
+    cfg = MINI64
+    w = _weights(cfg)
+    st = make_gpu_stage(cfg, 0, w)
+    kv = st.kv_cache_create(2, 40)
+    x = to_dev(generate.hidden_rows(cfg, 2), cfg)
+    out = torch.empty_like(x)
+    with pytest.raises(hx.HexgenError) as e:
+        st.decode(kv, 0, x, out)            # decode before prefill
+    assert e.value.status == 3
+    X = to_dev(generate.hidden_rows(cfg, 60), cfg)
+    O = torch.empty_like(X)
+    with pytest.raises(hx.HexgenError) as e:
+        st.prefill(kv, X, [41, 19], O)      # longer than max_seq
+    assert e.value.status == 4
+    st.prefill(kv, X[:50], [40, 10], O[:50])
+    with pytest.raises(hx.HexgenError) as e:
+        st.decode(kv, 1, x, out)            # wrong step number
+    assert e.value.status == 3
+    with pytest.raises(hx.HexgenError) as e:
+        st.decode(kv, 0, x, out)            # sequence 0 is full
+    assert e.value.status == 4
+    torch.cuda.synchronize()

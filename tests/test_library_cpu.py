@@ -1,0 +1,66 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, and rejects bad
+shapes and arguments without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2311_11514_amd as hx
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "hexgen.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hexgen_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = declared_symbols()
+    assert len(names) >= 19
+    raw = C.CDLL(hx.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), f"{n} declared in hexgen.h but not exported"
+        assert n in hx.SIGNATURES, f"{n} has no Python binding signature"
+    assert sorted(hx.SIGNATURES) == names
+
+
+def _create(*a):
+    h = C.c_void_p()
+    rc = hx.lib.hexgen_stage_create(*a, C.byref(h))
+    if rc == 0:
+        hx.lib.hexgen_stage_destroy(h)
+    return rc
+
+
+@pytest.mark.parametrize("args,status", [
+    ((512, 8, 2, 1408, 2, 2, 0, 0), 0),
+    ((8192, 64, 8, 28672, 8, 2, 0, 1), 0),
+    ((8192, 64, 8, 28672, 8, 8, 3, 1), 0),
+    ((512, 8, 2, 1408, 2, 3, 0, 0), 2),      # heads not divisible by tp
+    ((512, 8, 2, 1408, 2, 4, 0, 0), 2),      # kv heads not divisible by tp
+    ((512, 8, 2, 1409, 2, 2, 0, 0), 2),      # ffn not divisible
+    ((512, 8, 3, 1408, 2, 1, 0, 0), 2),      # heads % kv heads
+    ((500, 8, 2, 1408, 2, 2, 0, 0), 2),      # hidden % heads
+    ((512, 8, 2, 1408, 2, 2, 2, 0), 2),      # rank out of range
+    ((512, 16, 2, 1408, 2, 2, 0, 0), 2),     # head_dim 32 unsupported
+    ((512, 8, 2, 1408, 0, 2, 0, 0), 1),      # no layers
+    ((512, 8, 2, 1408, 2, 2, 0, 7), 1),      # unknown dtype
+    ((1024, 8, 2, 1424, 2, 2, 0, 1), 2),     # bf16: local ffn 712 not a multiple of 32
+])
+def test_stage_create_validation(args, status):
+    assert _create(*args) == status
+
+
+def test_null_and_range_arguments():
+    assert hx.lib.hexgen_stage_create(512, 8, 2, 1408, 2, 2, 0, 0, None) == 1
+    st = hx.Stage(512, 8, 2, 1408, 2, 2, 0, "f32")
+    assert hx.lib.hexgen_stage_set_params(st.handle, -1.0, 1e4) == 1
+    assert hx.lib.hexgen_stage_set_tap(st.handle, 5, None) == 1
+    assert hx.lib.hexgen_stage_load_layer(st.handle, 0, *([None] * 9)) == 1
+    assert hx.lib.hexgen_stage_weight_bytes(st.handle) == 0
+    assert hx.lib.hexgen_status_string(4) == b"capacity exceeded"
+    assert hx.lib.hexgen_accumulate_f32(None, None, 4, None) == 1
+    st.close()

@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of the stage hot path on one MI355X.
+
+Workload (N = 1): the Llama-2-70B-shaped shard at tensor-parallel degree 2, rank 0, 8-layer stage,
+batch-1 decode from a synthetic KV context of 1024 positions -- the configuration the headline metric
+(decode tokens/s per stage, fraction of HBM peak) is quoted on.  One "step" = one decode step of the whole
+stage (all layers: RMSNorm, QKV, RoPE + cache append, attention, W_O, RMSNorm, W1/W3 + SwiGLU, W2).
+Inputs and weights are synthetic (seeded normal draws) and resident in HBM before the timed region.
+
+Prints ONE JSON line.  Besides the contract fields it carries
+  roofline     -- the dominant kernel (W1/W3 weight-streaming projection) against the 8 TB/s HBM peak,
+                  timed with HIP events on the launch stream in a second, instrumented pass;
+  cpu_baseline -- the float64 CPU oracle timed on a bounded sample (one layer, a few decode steps),
+                  scaled to the same unit.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+PROF_QKV, PROF_WO, PROF_W13, PROF_W2, PROF_ATTN, PROF_CALL = range(6)
+
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled
+# by a copy kernel of known size); see profiles/.  None until measured for the current kernel.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="l70_tp2_decode")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one rank's share of a stage at its real shape); "
+              "--gpus > 1 is not supported and no multi-GPU figure is produced.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2311_11514_amd as hx
+    from workloads import CONFIGS, generate
+
+    cfg = CONFIGS[args.workload]
+    assert cfg.kv_context is not None and cfg.dtype == "bf16", "bench workload must be a bf16 decode config"
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda"
+    rank = cfg.tp_ranks[0]
+    K, W = args.steps, args.warmup
+    b, ctx = cfg.batch, cfg.kv_context
+
+    t_setup = time.time()
+    st = hx.Stage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, cfg.n_layers, cfg.tp_degree, rank, cfg.dtype,
+                  cfg.rms_eps, cfg.rope_theta)
+    layer0_host = None
+    for l in range(cfg.n_layers):
+        w = generate.layer_weights(cfg, l, device=dev)
+        st.load_layer(l, *[w[k] for k in generate.LAYER_TENSOR_ORDER])
+        if l == 0 and not args.no_cpu_baseline:
+            layer0_host = {k: v.cpu() for k, v in w.items()}
+        del w
+    kv = st.kv_cache_create(b, ctx + max(K, W) + 1)
+    kv_host = {}
+    for l in range(cfg.n_layers):
+        for s in range(b):
+            k, v = generate.synthetic_kv(cfg, l, s, ctx, device=dev)
+            k, v = k.cpu(), v.cpu()
+            kv.fill(l, s, k, v)
+            if l == 0:
+                kv_host[s] = (k, v)
+    X = torch.stack([generate.hidden_rows(cfg, b, stream_id=1 + i, device=dev) for i in range(max(K, W))])
+    X = X.to(torch.bfloat16).contiguous()
+    outp = torch.empty(b, cfg.hidden, dtype=torch.bfloat16, device=dev)
+    outr = torch.empty_like(outp)
+    torch.cuda.synchronize()
+    log(f"setup {time.time() - t_setup:.1f}s, weights {st.weight_bytes() / 1e9:.3f} GB")
+
+    def run(n):
+        kv.set_lengths([ctx] * b)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            st.decode(kv, i, X[i], outp, outr)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    run(W)
+    dt = run(K)
+    ms_per_step = dt / K * 1e3
+    tok_s = b * K / dt
+    assert torch.isfinite(outp.float()).all() and torch.isfinite(outr.float()).all()
+
+    # instrumented pass: HIP events on the launch stream around every projection launch
+    st.profile_enable(True)
+    run(K)
+    slots = {}
+    for name, slot in (("qkv", PROF_QKV), ("wo", PROF_WO), ("w13", PROF_W13), ("w2", PROF_W2),
+                       ("attn", PROF_ATTN), ("call", PROF_CALL)):
+        ms, n = st.profile_read(slot)
+        slots[name] = {"avg_us": ms / max(n, 1) * 1e3, "launches": n}
+    st.profile_enable(False)
+
+    eb = 2
+    H, Fl = cfg.hidden, cfg.ffn_l
+    w13_bytes = H * 2 * Fl * eb + b * H * eb            # weights + activation operand (output is split-K scratch)
+    w13_s = slots["w13"]["avg_us"] * 1e-6
+    achieved = w13_bytes / w13_s / 1e9
+    bytes_by_proj = {"qkv": H * (cfg.hq_l + 2 * cfg.hkv_l) * cfg.head_dim * eb, "wo": cfg.hq_l * cfg.head_dim * H * eb,
+                     "w13": H * 2 * Fl * eb, "w2": Fl * H * eb}
+    per_kernel = {k: {"avg_us": round(slots[k]["avg_us"], 2),
+                      "GBps": round(bytes_by_proj[k] / (slots[k]["avg_us"] * 1e-6) / 1e9, 1)} for k in bytes_by_proj}
+    per_kernel["attn_block"] = {"avg_us": round(slots["attn"]["avg_us"], 2)}
+    # whole-step algorithmic bytes: weights + KV read (context grows by one per step)
+    kv_bytes_avg = cfg.kv_bytes_per_pos_layer() * b * (ctx + (K + 1) / 2.0)
+    step_bytes = cfg.n_layers * (cfg.weight_elems_per_layer_rank * eb + kv_bytes_avg)
+    stage_frac = step_bytes / (dt / K) / 1e9 / HBM_PEAK_GBS
+
+    result = {
+        "metric": "decode_tokens_per_s_per_stage", "value": round(tok_s, 2), "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: Llama-2-70B-shaped shard, TP{cfg.tp_degree} rank {rank}, "
+                               f"{cfg.n_layers}-layer stage, batch {b} decode from KV context {ctx}",
+                   "hidden": H, "local_q_heads": cfg.hq_l, "local_kv_heads": cfg.hkv_l, "head_dim": cfg.head_dim,
+                   "local_ffn": Fl, "layers": cfg.n_layers, "batch": b, "kv_context": ctx},
+        "us_per_layer": round(ms_per_step * 1e3 / cfg.n_layers, 2),
+        "stage_hbm_frac": round(stage_frac, 4),
+        "per_kernel": per_kernel,
+        "roofline": {"bound": "hbm", "kernel": "gemv_mfma_kernel (W1/W3 projection)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES, "bytes_per_launch": w13_bytes,
+                     "avg_launch_us": round(slots["w13"]["avg_us"], 2)},
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, rank, layer0_host, kv_host, X, ctx)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(cfg, rank, layer0, kv_host, X, ctx):
+    """The oracle as it stands, on the host cores: ONE layer of the same shard, a few decode steps from
+    the same synthetic context; tokens/s of the stage = batch / (per-layer step time * layers)."""
+    from oracle import stage_oracle as so
+    from workloads import generate
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    ora = so.OracleStage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, 1, cfg.tp_degree, rank, cfg.rms_eps,
+                         cfg.rope_theta)
+    ora.load_layer(0, *[layer0[k] for k in generate.LAYER_TENSOR_ORDER])
+    oc = ora.new_cache(cfg.batch)
+    for s, (k, v) in kv_host.items():
+        oc.fill(0, s, k, v)
+    xs = X.float().cpu()
+    ora.decode(oc, xs[0])                       # untimed first touch
+    n, t0 = 0, time.perf_counter()
+    while n < 64 and time.perf_counter() - t0 < 15.0:
+        ora.decode(oc, xs[1 + n % (xs.shape[0] - 1)])
+        n += 1
+    per_layer_step = (time.perf_counter() - t0) / n
+    value = cfg.batch / (per_layer_step * cfg.n_layers)
+    log(f"cpu oracle: {per_layer_step * 1e3:.1f} ms per layer-step on {cores} threads")
+    return {"value": round(value, 4), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"1 of {cfg.n_layers} layers, {n} decode steps at context {ctx}+, float64 numpy; "
+                      f"stage rate = batch / (layer-step time x {cfg.n_layers})"}
+
+
+if __name__ == "__main__":
+    main()

@@ -147,6 +147,16 @@ hexgen_status_t hexgen_kv_cache_get_lengths(hexgen_kv_cache_t *kv, int32_t *lens
  */
 hexgen_status_t hexgen_stage_set_tap(hexgen_stage_t *st, int layer, void *h_dump);
 
+/* Measurement surface.  While enabled, prefill / decode record HIP events on the caller's stream
+ * around each projection launch, so per-kernel time can be read without an external profiler
+ * (this costs a few microseconds per launch: enable it for measurement passes only).
+ * Slots: 0 QKV projection, 1 W_O, 2 W1/W3 (+SwiGLU), 3 W2, 4 RoPE + cache append + attention,
+ * 5 the whole call.  enable(on) synchronises and clears earlier records.  read() synchronises and
+ * returns the summed time in milliseconds and the number of timed launches of the slot.
+ */
+hexgen_status_t hexgen_stage_profile_enable(hexgen_stage_t *st, int on);
+hexgen_status_t hexgen_stage_profile_read(hexgen_stage_t *st, int slot, double *total_ms, int64_t *count);
+
 /* Bytes of device memory the stage holds for weights (after repacking), for reporting. */
 int64_t hexgen_stage_weight_bytes(const hexgen_stage_t *st);
 

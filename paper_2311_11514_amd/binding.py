@@ -42,6 +42,8 @@ SIGNATURES = {
     "hexgen_kv_cache_get_lengths": (_i, [_vp, _ip, _i]),
     "hexgen_stage_set_tap": (_i, [_vp, _i, _vp]),
     "hexgen_stage_weight_bytes": (_i64, [_vp]),
+    "hexgen_stage_profile_enable": (_i, [_vp, _i]),
+    "hexgen_stage_profile_read": (_i, [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64)]),
 }
 
 
@@ -146,6 +148,16 @@ class Stage:
     def set_tap(self, layer: int, h_dump: Optional[torch.Tensor]):
         self._taps[layer] = h_dump          # keep the buffer alive
         _check(lib.hexgen_stage_set_tap(self.handle, layer, _ptr(h_dump)), "hexgen_stage_set_tap")
+
+    def profile_enable(self, on: bool):
+        _check(lib.hexgen_stage_profile_enable(self.handle, int(on)), "hexgen_stage_profile_enable")
+
+    def profile_read(self, slot: int):
+        """(total milliseconds, number of timed launches) of a slot; see include/hexgen.h."""
+        ms, n = C.c_double(), C.c_int64()
+        _check(lib.hexgen_stage_profile_read(self.handle, slot, C.byref(ms), C.byref(n)),
+               "hexgen_stage_profile_read")
+        return ms.value, n.value
 
     def weight_bytes(self) -> int:
         return int(lib.hexgen_stage_weight_bytes(self.handle))

@@ -38,6 +38,22 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
+// x = hi + lo with both parts bf16: the pair carries ~16 mantissa bits of an fp32 activation.
+// Decode kernels are HBM-bound, so feeding hi and lo through two MFMAs costs nothing and removes the
+// bf16 rounding of activations from the error budget of deep stages.
+__device__ inline void split_bf16(float x, bf16_t &hi, bf16_t &lo) {
+    hi = f32_to_bf16(x);
+    lo = f32_to_bf16(x - bf16_to_f32(hi));
+}
+// packs hi parts of (a, b) into *phi and lo parts into *plo
+__device__ inline void split_pack2(float a, float b, uint32_t &phi, uint32_t &plo) {
+    bf16_t ah, al, bh, bl;
+    split_bf16(a, ah, al);
+    split_bf16(b, bh, bl);
+    phi = (uint32_t)ah | ((uint32_t)bh << 16);
+    plo = (uint32_t)al | ((uint32_t)bl << 16);
+}
+
 __device__ inline float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

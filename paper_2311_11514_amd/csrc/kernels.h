@@ -35,33 +35,36 @@ struct KvGeom {
 
 // rows of `in` ([T,H] row-major, fp32 or bf16) -> optional fp32 copy h_out, and
 // packed bf16 n = in / sqrt(mean(in^2)+eps) * g  ([ceil16(T)/16][H/32] fragment tiles)
+// Packed activations may carry a second plane `*_lo` with the bf16 rounding remainder (x = hi + lo);
+// producers write it when the pointer is non-null, the decode kernels consume both planes.
 void launch_rmsnorm_pack(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *n_packed,
-                         int T, int H, float eps, hipStream_t s);
+                         bf16_t *n_lo, int T, int H, float eps, hipStream_t s);
 
 // out[ks][t][n] (fp32, row stride N, split stride T*N) = sum over the split's k range of
 // Wp[n][k] * Xp[t][k]; T <= 32.  ksplit >= 1 splits K across blockIdx.y.
-void launch_gemv_mfma(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, int K, int T, int ksplit,
-                      int pair_tiles, hipStream_t s);
+void launch_gemv_mfma(const bf16_t *Wp, const bf16_t *Xp, const bf16_t *Xlo, float *out, int N, int K, int T,
+                      int ksplit, int pair_tiles, hipStream_t s);
 // same contraction for many rows (prefill): out[t][n] fp32 row-major
 void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, int K, int T, hipStream_t s);
 
 // sum ksplit partials of the fused QKV projection, rotate q and k heads, write q (bf16 row-major
 // [T][hq_l*d]) and append k, v to the cache at each row's (seq, pos)
 void launch_qkv_rope_append(const float *part, int ksplit, int T, int hq_l, KvGeom kg, RowMap rm,
-                            const float *cos_tab, const float *sin_tab, bf16_t *q_out, bf16_t *kc,
+                            const float *cos_tab, const float *sin_tab, bf16_t *q_out, bf16_t *q_lo, bf16_t *kc,
                             bf16_t *vc, hipStream_t s);
 // h[t][:] += sum_ks part[ks][t][:]; then either packed n = rmsnorm(h) * g (g != NULL) or nothing
 void launch_reduce_resid_norm(const float *part, int ksplit, float *h, const float *g, bf16_t *n_packed,
-                              int T, int H, float eps, hipStream_t s);
+                              bf16_t *n_lo, int T, int H, float eps, hipStream_t s);
 // plain reduce of the partials into dst fp32 [T][H] (no residual): the stage's output partial
 void launch_reduce_partial(const float *part, int ksplit, float *dst, int T, int H, hipStream_t s);
 // u[t][f] = silu(a) * b with a, b the W1 / W3 columns (interleaved 16-column tiles) -> packed bf16
-void launch_reduce_swiglu(const float *part, int ksplit, bf16_t *u_packed, int T, int F_l, hipStream_t s);
+void launch_reduce_swiglu(const float *part, int ksplit, bf16_t *u_packed, bf16_t *u_lo, int T, int F_l,
+                          hipStream_t s);
 
 // decode attention: one new row per sequence; split-KV partials then merge into packed o
-void launch_attn_decode(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,
-                        const int32_t *lens, int b, int nsplit, float *part_o, float *part_ml,
-                        bf16_t *o_packed, hipStream_t s);
+void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, const bf16_t *vc, KvGeom kg,
+                        int hq_l, const int32_t *lens, int b, int nsplit, float *part_o, float *part_ml,
+                        bf16_t *o_packed, bf16_t *o_lo, hipStream_t s);
 // prefill attention over packed ragged rows; K, V are read from the cache
 void launch_attn_prefill(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,
                          const int32_t *cu_rows, const int32_t *pos0, int batch, int max_new,

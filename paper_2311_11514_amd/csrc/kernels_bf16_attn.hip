@@ -14,7 +14,8 @@
 #define NEG_INF (-INFINITY)
 
 template <int D>
-__global__ __launch_bounds__(64) void attn_decode_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc,
+__global__ __launch_bounds__(64) void attn_decode_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ q_lo,
+                                                        const bf16_t *__restrict__ kc,
                                                         const bf16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
                                                         const int32_t *__restrict__ lens, int nsplit,
                                                         float *__restrict__ part_o, float *__restrict__ part_ml,
@@ -30,10 +31,14 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(const bf16_t *__restric
     const bool hv = j < G;
 
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    bf16x8 qf[KT];
+    // the query is carried as hi + lo bf16 parts (decode is HBM-bound: the second MFMA is free)
+    bf16x8 qf[KT], ql[KT];
 #pragma unroll
-    for (int kt = 0; kt < KT; ++kt)
-        qf[kt] = hv ? *reinterpret_cast<const bf16x8 *>(q + ((size_t)sq * hq_l + head) * D + kt * 32 + 8 * g) : zero;
+    for (int kt = 0; kt < KT; ++kt) {
+        const size_t qo = ((size_t)sq * hq_l + head) * D + kt * 32 + 8 * g;
+        qf[kt] = hv ? *reinterpret_cast<const bf16x8 *>(q + qo) : zero;
+        ql[kt] = hv ? *reinterpret_cast<const bf16x8 *>(q_lo + qo) : zero;
+    }
 
     floatx4 oacc[DT];
 #pragma unroll
@@ -56,6 +61,8 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(const bf16_t *__restric
         for (int dt = 0; dt < DT; ++dt) va[dt] = vs[(size_t)(t * DT + dt) * 64];
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt], ql[kt], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[kt], ql[kt], s1, 0, 0, 0);
             s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt], qf[kt], s0, 0, 0, 0);
             s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[kt], qf[kt], s1, 0, 0, 0);
         }
@@ -80,12 +87,13 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(const bf16_t *__restric
             ps += p0[r] + p1[r];
         }
         lsum = lsum * alpha + ps;
-        union { uint32_t u[4]; bf16x8 v; } pb;
-        pb.u[0] = pack_bf16x2(p0[0], p0[1]); pb.u[1] = pack_bf16x2(p0[2], p0[3]);
-        pb.u[2] = pack_bf16x2(p1[0], p1[1]); pb.u[3] = pack_bf16x2(p1[2], p1[3]);
+        union { uint32_t u[4]; bf16x8 v; } pb, pl;
+        split_pack2(p0[0], p0[1], pb.u[0], pl.u[0]); split_pack2(p0[2], p0[3], pb.u[1], pl.u[1]);
+        split_pack2(p1[0], p1[1], pb.u[2], pl.u[2]); split_pack2(p1[2], p1[3], pb.u[3], pl.u[3]);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             oacc[dt] *= alpha;
+            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pl.v, oacc[dt], 0, 0, 0);
             oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb.v, oacc[dt], 0, 0, 0);
         }
     }
@@ -103,7 +111,8 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(const bf16_t *__restric
 // grid (b, hq_l), block D threads: log-sum-exp merge in split order -> packed bf16 o
 template <int D>
 __global__ void attn_decode_merge_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
-                                         int hq_l, int nsplit, bf16_t *__restrict__ o_packed) {
+                                         int hq_l, int nsplit, bf16_t *__restrict__ o_packed,
+                                         bf16_t *__restrict__ o_lo) {
     const int sq = blockIdx.x, head = blockIdx.y, dd = threadIdx.x;
     const size_t e0 = ((size_t)sq * hq_l + head) * nsplit;
     float M = NEG_INF;
@@ -115,25 +124,29 @@ __global__ void attn_decode_merge_kernel(const float *__restrict__ part_o, const
         L += part_ml[(e0 + s) * 2 + 1] * w;
         o += part_o[(e0 + s) * D + dd] * w;
     }
-    o_packed[frag_offset(sq, head * D + dd, (hq_l * D) >> 5)] = f32_to_bf16(o / L);
+    bf16_t hi, lo;
+    split_bf16(o / L, hi, lo);
+    const size_t off = frag_offset(sq, head * D + dd, (hq_l * D) >> 5);
+    o_packed[off] = hi;
+    o_lo[off] = lo;
 }
 
-void launch_attn_decode(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,
-                        const int32_t *lens, int b, int nsplit, float *part_o, float *part_ml, bf16_t *o_packed,
-                        hipStream_t s) {
+void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, const bf16_t *vc, KvGeom kg,
+                        int hq_l, const int32_t *lens, int b, int nsplit, float *part_o, float *part_ml,
+                        bf16_t *o_packed, bf16_t *o_lo, hipStream_t s) {
     const int G = hq_l / kg.hkv_l;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)kg.d);
     dim3 grid(nsplit, kg.hkv_l, b);
     if (kg.d == 128) {
-        hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(64), 0, s, q, kc, vc, kg, hq_l, G, lens, nsplit, part_o,
-                           part_ml, scale_log2e);
+        hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(64), 0, s, q, q_lo, kc, vc, kg, hq_l, G, lens, nsplit,
+                           part_o, part_ml, scale_log2e);
         hipLaunchKernelGGL(attn_decode_merge_kernel<128>, dim3(b, hq_l), dim3(128), 0, s, part_o, part_ml, hq_l,
-                           nsplit, o_packed);
+                           nsplit, o_packed, o_lo);
     } else {
-        hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(64), 0, s, q, kc, vc, kg, hq_l, G, lens, nsplit, part_o,
-                           part_ml, scale_log2e);
+        hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(64), 0, s, q, q_lo, kc, vc, kg, hq_l, G, lens, nsplit,
+                           part_o, part_ml, scale_log2e);
         hipLaunchKernelGGL(attn_decode_merge_kernel<64>, dim3(b, hq_l), dim3(64), 0, s, part_o, part_ml, hq_l, nsplit,
-                           o_packed);
+                           o_packed, o_lo);
     }
 }
 

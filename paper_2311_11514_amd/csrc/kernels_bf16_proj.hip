@@ -15,7 +15,7 @@
 template <bool IN_BF16>
 __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const void *__restrict__ in, float *__restrict__ h_out,
                                                           const float *__restrict__ g, bf16_t *__restrict__ np,
-                                                          int H, float eps) {
+                                                          bf16_t *__restrict__ np_lo, int H, float eps) {
     __shared__ float red[4];
     const int t = blockIdx.x;
     const int chunks = H >> 3;
@@ -57,22 +57,24 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const void *__restric
         }
         const float4 *gp = reinterpret_cast<const float4 *>(g + c * 8);
         float4 g0 = gp[0], g1 = gp[1];
-        uint4 o;
-        o.x = pack_bf16x2(x[0] * rstd * g0.x, x[1] * rstd * g0.y);
-        o.y = pack_bf16x2(x[2] * rstd * g0.z, x[3] * rstd * g0.w);
-        o.z = pack_bf16x2(x[4] * rstd * g1.x, x[5] * rstd * g1.y);
-        o.w = pack_bf16x2(x[6] * rstd * g1.z, x[7] * rstd * g1.w);
-        *reinterpret_cast<uint4 *>(np + frag_offset(t, c * 8, k_tiles)) = o;
+        uint4 o, ol;
+        split_pack2(x[0] * rstd * g0.x, x[1] * rstd * g0.y, o.x, ol.x);
+        split_pack2(x[2] * rstd * g0.z, x[3] * rstd * g0.w, o.y, ol.y);
+        split_pack2(x[4] * rstd * g1.x, x[5] * rstd * g1.y, o.z, ol.z);
+        split_pack2(x[6] * rstd * g1.z, x[7] * rstd * g1.w, o.w, ol.w);
+        const size_t off = frag_offset(t, c * 8, k_tiles);
+        *reinterpret_cast<uint4 *>(np + off) = o;
+        if (np_lo) *reinterpret_cast<uint4 *>(np_lo + off) = ol;
     }
 }
 
-void launch_rmsnorm_pack(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *n_packed, int T,
-                         int H, float eps, hipStream_t s) {
+void launch_rmsnorm_pack(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *n_packed,
+                         bf16_t *n_lo, int T, int H, float eps, hipStream_t s) {
     if (T <= 0) return;
     if (in_is_bf16)
-        hipLaunchKernelGGL(rmsnorm_pack_kernel<true>, dim3(T), dim3(256), 0, s, in, h_out, g, n_packed, H, eps);
+        hipLaunchKernelGGL(rmsnorm_pack_kernel<true>, dim3(T), dim3(256), 0, s, in, h_out, g, n_packed, n_lo, H, eps);
     else
-        hipLaunchKernelGGL(rmsnorm_pack_kernel<false>, dim3(T), dim3(256), 0, s, in, h_out, g, n_packed, H, eps);
+        hipLaunchKernelGGL(rmsnorm_pack_kernel<false>, dim3(T), dim3(256), 0, s, in, h_out, g, n_packed, n_lo, H, eps);
 }
 
 // -------------------------------------------------------------------------------------------------
@@ -86,6 +88,7 @@ void launch_rmsnorm_pack(const void *in, int in_is_bf16, float *h_out, const flo
 template <int NB, int UT, int WAVES, int UNROLL>
 __global__ __launch_bounds__(WAVES * 64) void gemv_mfma_kernel(const bf16_t *__restrict__ Wp,
                                                               const bf16_t *__restrict__ Xp,
+                                                              const bf16_t *__restrict__ Xlo,
                                                               float *__restrict__ out, int N, int k_tiles,
                                                               int kt_per_split, int T) {
     __shared__ floatx4 red[WAVES][UT * NB][64];
@@ -104,33 +107,39 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_mfma_kernel(const bf16_t *__r
 #pragma unroll
     for (int u = 0; u < UT; ++u)
         wp[u] = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)(unit * UT + u) * k_tiles * 64 + lane;
-    const bf16x8 *xp[NB];
+    const bf16x8 *xp[NB], *xl[NB];
     bool xv[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         xp[b] = reinterpret_cast<const bf16x8 *>(Xp) + (size_t)b * k_tiles * 64 + lane;
+        xl[b] = reinterpret_cast<const bf16x8 *>(Xlo) + (size_t)b * k_tiles * 64 + lane;
         xv[b] = (lane & 15) + 16 * b < T;
     }
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 
     int kt = kt0 + wave;
     for (; kt + (UNROLL - 1) * WAVES < kt1; kt += UNROLL * WAVES) {
-        bf16x8 a[UNROLL][UT], x[UNROLL][NB];
+        bf16x8 a[UNROLL][UT], x[UNROLL][NB], y[UNROLL][NB];
 #pragma unroll
         for (int i = 0; i < UNROLL; ++i) {
             const size_t o = (size_t)(kt + i * WAVES) * 64;
 #pragma unroll
             for (int u = 0; u < UT; ++u) a[i][u] = __builtin_nontemporal_load(wp[u] + o);
 #pragma unroll
-            for (int b = 0; b < NB; ++b) x[i][b] = xv[b] ? xp[b][o] : zero;
+            for (int b = 0; b < NB; ++b) {
+                x[i][b] = xv[b] ? xp[b][o] : zero;
+                y[i][b] = xv[b] ? xl[b][o] : zero;
+            }
         }
 #pragma unroll
         for (int i = 0; i < UNROLL; ++i)
 #pragma unroll
             for (int u = 0; u < UT; ++u)
 #pragma unroll
-                for (int b = 0; b < NB; ++b)
+                for (int b = 0; b < NB; ++b) {
+                    acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], y[i][b], acc[u][b], 0, 0, 0);
                     acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], x[i][b], acc[u][b], 0, 0, 0);
+                }
     }
     for (; kt < kt1; kt += WAVES) {
         const size_t o = (size_t)kt * 64;
@@ -140,6 +149,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_mfma_kernel(const bf16_t *__r
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 bf16x8 x = xv[b] ? xp[b][o] : zero;
+                bf16x8 y = xv[b] ? xl[b][o] : zero;
+                acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, y, acc[u][b], 0, 0, 0);
                 acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, x, acc[u][b], 0, 0, 0);
             }
         }
@@ -162,14 +173,14 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_mfma_kernel(const bf16_t *__r
     }
 }
 
-void launch_gemv_mfma(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, int K, int T, int ksplit,
-                      int pair_tiles, hipStream_t s) {
+void launch_gemv_mfma(const bf16_t *Wp, const bf16_t *Xp, const bf16_t *Xlo, float *out, int N, int K, int T,
+                      int ksplit, int pair_tiles, hipStream_t s) {
     const int k_tiles = K / 32, n_tiles = N / 16;
     const int per = (k_tiles + ksplit - 1) / ksplit;
     constexpr int WAVES = 8;
 #define HX_GEMV(NB, UT, UNR)                                                                                      \
     hipLaunchKernelGGL((gemv_mfma_kernel<NB, UT, WAVES, UNR>), dim3(n_tiles / UT, ksplit), dim3(WAVES * 64), 0, s, \
-                       Wp, Xp, out, N, k_tiles, per, T)
+                       Wp, Xp, Xlo, out, N, k_tiles, per, T)
     if (T <= 16) {
         if (pair_tiles) HX_GEMV(1, 2, 4); else HX_GEMV(1, 1, 8);
     } else {
@@ -261,7 +272,8 @@ void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, int
 __global__ void qkv_rope_append_kernel(const float *__restrict__ part, int ksplit, int T, int hq_l, KvGeom kg,
                                        RowMap rm, const float *__restrict__ cos_tab,
                                        const float *__restrict__ sin_tab, bf16_t *__restrict__ q_out,
-                                       bf16_t *__restrict__ kc, bf16_t *__restrict__ vc) {
+                                       bf16_t *__restrict__ q_lo, bf16_t *__restrict__ kc,
+                                       bf16_t *__restrict__ vc) {
     const int t = blockIdx.x, head = blockIdx.y, i = threadIdx.x;
     const int d = kg.d, half = d >> 1;
     const int N = (hq_l + 2 * kg.hkv_l) * d;
@@ -279,9 +291,13 @@ __global__ void qkv_rope_append_kernel(const float *__restrict__ part, int kspli
         lo = rlo; hi = rhi;
     }
     if (head < hq_l) {
-        bf16_t *q = q_out + (size_t)t * hq_l * d + head * d;
-        q[i] = f32_to_bf16(lo);
-        q[i + half] = f32_to_bf16(hi);
+        const size_t qo = (size_t)t * hq_l * d + head * d;
+        bf16_t a_hi, a_lo, b_hi, b_lo;
+        split_bf16(lo, a_hi, a_lo);
+        split_bf16(hi, b_hi, b_lo);
+        q_out[qo + i] = a_hi;
+        q_out[qo + i + half] = b_hi;
+        if (q_lo) { q_lo[qo + i] = a_lo; q_lo[qo + i + half] = b_lo; }
     } else {
         const bool is_k = head < hq_l + kg.hkv_l;
         const int c = is_k ? head - hq_l : head - hq_l - kg.hkv_l;
@@ -296,17 +312,18 @@ __global__ void qkv_rope_append_kernel(const float *__restrict__ part, int kspli
     }
 }
 void launch_qkv_rope_append(const float *part, int ksplit, int T, int hq_l, KvGeom kg, RowMap rm,
-                            const float *cos_tab, const float *sin_tab, bf16_t *q_out, bf16_t *kc, bf16_t *vc,
-                            hipStream_t s) {
+                            const float *cos_tab, const float *sin_tab, bf16_t *q_out, bf16_t *q_lo, bf16_t *kc,
+                            bf16_t *vc, hipStream_t s) {
     if (T <= 0) return;
     hipLaunchKernelGGL(qkv_rope_append_kernel, dim3(T, hq_l + 2 * kg.hkv_l), dim3(kg.d / 2), 0, s, part, ksplit, T,
-                       hq_l, kg, rm, cos_tab, sin_tab, q_out, kc, vc);
+                       hq_l, kg, rm, cos_tab, sin_tab, q_out, q_lo, kc, vc);
 }
 
 // one block per row: h += sum of partials; optional RMSNorm of the new h into packed bf16
 __global__ __launch_bounds__(256) void reduce_resid_norm_kernel(const float *__restrict__ part, int ksplit,
                                                                float *__restrict__ h, const float *__restrict__ g,
-                                                               bf16_t *__restrict__ np, int T, int H, float eps) {
+                                                               bf16_t *__restrict__ np, bf16_t *__restrict__ np_lo,
+                                                               int T, int H, float eps) {
     __shared__ float red[4];
     const int t = blockIdx.x;
     const int quads = H >> 2;
@@ -329,18 +346,21 @@ __global__ __launch_bounds__(256) void reduce_resid_norm_kernel(const float *__r
         float4 a = p[0], b = p[1];
         const float4 *gp = reinterpret_cast<const float4 *>(g + c * 8);
         float4 g0 = gp[0], g1 = gp[1];
-        uint4 o;
-        o.x = pack_bf16x2(a.x * rstd * g0.x, a.y * rstd * g0.y);
-        o.y = pack_bf16x2(a.z * rstd * g0.z, a.w * rstd * g0.w);
-        o.z = pack_bf16x2(b.x * rstd * g1.x, b.y * rstd * g1.y);
-        o.w = pack_bf16x2(b.z * rstd * g1.z, b.w * rstd * g1.w);
-        *reinterpret_cast<uint4 *>(np + frag_offset(t, c * 8, k_tiles)) = o;
+        uint4 o, ol;
+        split_pack2(a.x * rstd * g0.x, a.y * rstd * g0.y, o.x, ol.x);
+        split_pack2(a.z * rstd * g0.z, a.w * rstd * g0.w, o.y, ol.y);
+        split_pack2(b.x * rstd * g1.x, b.y * rstd * g1.y, o.z, ol.z);
+        split_pack2(b.z * rstd * g1.z, b.w * rstd * g1.w, o.w, ol.w);
+        const size_t off = frag_offset(t, c * 8, k_tiles);
+        *reinterpret_cast<uint4 *>(np + off) = o;
+        if (np_lo) *reinterpret_cast<uint4 *>(np_lo + off) = ol;
     }
 }
-void launch_reduce_resid_norm(const float *part, int ksplit, float *h, const float *g, bf16_t *n_packed, int T,
-                              int H, float eps, hipStream_t s) {
+void launch_reduce_resid_norm(const float *part, int ksplit, float *h, const float *g, bf16_t *n_packed,
+                              bf16_t *n_lo, int T, int H, float eps, hipStream_t s) {
     if (T <= 0) return;
-    hipLaunchKernelGGL(reduce_resid_norm_kernel, dim3(T), dim3(256), 0, s, part, ksplit, h, g, n_packed, T, H, eps);
+    hipLaunchKernelGGL(reduce_resid_norm_kernel, dim3(T), dim3(256), 0, s, part, ksplit, h, g, n_packed, n_lo, T, H,
+                       eps);
 }
 
 __global__ void reduce_partial_kernel(const float *__restrict__ part, int ksplit, float *__restrict__ dst,
@@ -363,8 +383,8 @@ void launch_reduce_partial(const float *part, int ksplit, float *dst, int T, int
 
 // The W1/W3 projection output interleaves 16-column tiles: tile 2i = W1 (gate) columns 16i..16i+15,
 // tile 2i+1 = W3 (up) columns of the same range.  One thread produces 8 consecutive u values.
-__global__ void reduce_swiglu_kernel(const float *__restrict__ part, int ksplit, bf16_t *__restrict__ up, int T,
-                                     int F_l) {
+__global__ void reduce_swiglu_kernel(const float *__restrict__ part, int ksplit, bf16_t *__restrict__ up,
+                                     bf16_t *__restrict__ up_lo, int T, int F_l) {
     const int t = blockIdx.x;
     const int chunk = blockIdx.y * blockDim.x + threadIdx.x;
     if (chunk >= (F_l >> 3)) return;
@@ -384,14 +404,17 @@ __global__ void reduce_swiglu_kernel(const float *__restrict__ part, int ksplit,
     float u[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) u[j] = a[j] / (1.0f + __expf(-a[j])) * b[j];
-    uint4 o;
-    o.x = pack_bf16x2(u[0], u[1]); o.y = pack_bf16x2(u[2], u[3]);
-    o.z = pack_bf16x2(u[4], u[5]); o.w = pack_bf16x2(u[6], u[7]);
-    *reinterpret_cast<uint4 *>(up + frag_offset(t, f0, F_l >> 5)) = o;
+    uint4 o, ol;
+    split_pack2(u[0], u[1], o.x, ol.x); split_pack2(u[2], u[3], o.y, ol.y);
+    split_pack2(u[4], u[5], o.z, ol.z); split_pack2(u[6], u[7], o.w, ol.w);
+    const size_t off = frag_offset(t, f0, F_l >> 5);
+    *reinterpret_cast<uint4 *>(up + off) = o;
+    if (up_lo) *reinterpret_cast<uint4 *>(up_lo + off) = ol;
 }
-void launch_reduce_swiglu(const float *part, int ksplit, bf16_t *u_packed, int T, int F_l, hipStream_t s) {
+void launch_reduce_swiglu(const float *part, int ksplit, bf16_t *u_packed, bf16_t *u_lo, int T, int F_l,
+                          hipStream_t s) {
     if (T <= 0) return;
     const int chunks = F_l >> 3;
-    hipLaunchKernelGGL(reduce_swiglu_kernel, dim3(T, (chunks + 255) / 256), dim3(256), 0, s, part, ksplit, u_packed, T,
-                       F_l);
+    hipLaunchKernelGGL(reduce_swiglu_kernel, dim3(T, (chunks + 255) / 256), dim3(256), 0, s, part, ksplit, u_packed,
+                       u_lo, T, F_l);
 }

@@ -42,6 +42,26 @@ struct Layer {
     bool loaded = false;
 };
 
+// Optional per-slot timing with HIP events recorded on the caller's stream (measurement surface).
+enum { PROF_QKV = 0, PROF_WO = 1, PROF_W13 = 2, PROF_W2 = 3, PROF_ATTN = 4, PROF_CALL = 5, PROF_SLOTS = 6 };
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> ev[PROF_SLOTS];     // start, stop, start, stop, ...
+    void mark(int slot, hipStream_t s) {
+        if (!on) return;
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return;
+        (void)hipEventRecord(e, s);
+        ev[slot].push_back(e);
+    }
+    void clear() {
+        for (auto &v : ev) {
+            for (hipEvent_t e : v) (void)hipEventDestroy(e);
+            v.clear();
+        }
+    }
+};
+
 struct Workspace {
     int cap_rows = 0;
     float *h = nullptr;        // residual stream [T][H] fp32
@@ -49,6 +69,7 @@ struct Workspace {
     float *p32 = nullptr;      // reduced partial [T][H] fp32
     // bf16 path
     bf16_t *n = nullptr, *o = nullptr, *u = nullptr, *q = nullptr;
+    bf16_t *n_lo = nullptr, *o_lo = nullptr, *u_lo = nullptr, *q_lo = nullptr;   // decode rows only (x = hi + lo)
     float *att_o = nullptr, *att_ml = nullptr;
     // fp32 path
     float *n32 = nullptr, *q32 = nullptr, *o32 = nullptr, *u32 = nullptr;
@@ -70,6 +91,7 @@ struct hexgen_stage {
     Workspace ws;
     int ws_batch_cap = 0;
     int64_t weight_bytes = 0;
+    Profiler prof;
 };
 
 struct hexgen_kv_cache {
@@ -91,7 +113,7 @@ namespace {
 size_t esize(hexgen_dtype_t dt) { return dt == HEXGEN_F32 ? 4 : 2; }
 
 void free_ws(Workspace &w) {
-    void *ptrs[] = {w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.att_o, w.att_ml, w.n32, w.q32, w.o32, w.u32,
+    void *ptrs[] = {w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.n_lo, w.o_lo, w.u_lo, w.q_lo, w.att_o, w.att_ml, w.n32, w.q32, w.o32, w.u32,
                     w.row_seq, w.row_pos, w.cu_rows, w.pos0};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
@@ -128,6 +150,11 @@ hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
         HX_TRY(dmalloc(&w.u, T16 * st->F_l));
         HX_TRY(dmalloc(&w.q, T * st->qw));
         const size_t drows = (size_t)std::min(rows, kDecodeMaxRows);
+        const size_t d16 = (size_t)round_up((int)drows, 16);
+        HX_TRY(dmalloc(&w.n_lo, d16 * st->H));
+        HX_TRY(dmalloc(&w.o_lo, d16 * st->qw));
+        HX_TRY(dmalloc(&w.u_lo, d16 * st->F_l));
+        HX_TRY(dmalloc(&w.q_lo, drows * st->qw));
         HX_TRY(dmalloc(&w.att_o, drows * st->hq_l * kMaxAttnSplit * st->d));
         HX_TRY(dmalloc(&w.att_ml, drows * st->hq_l * kMaxAttnSplit * 2));
         // padded rows of the packed operands are read by the GEMM tiles: keep them finite
@@ -222,15 +249,18 @@ int pick_ksplit(int n_units, int k_tiles) {
 }
 
 // part <- X . W for the rows of this call; returns the number of K splits written
-int project_bf16(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xp, int N, int K, bool pair,
-                 hipStream_t s) {
+int project_bf16(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xp, const bf16_t *Xlo, int N, int K,
+                 bool pair, int slot, hipStream_t s) {
+    int ks = 1;
+    st->prof.mark(slot, s);
     if (r.decode) {
-        const int ks = pick_ksplit(N / 16 / (pair ? 2 : 1), K / 32);
-        launch_gemv_mfma(static_cast<const bf16_t *>(Wp), Xp, st->ws.part, N, K, r.T, ks, pair ? 1 : 0, s);
-        return ks;
+        ks = pick_ksplit(N / 16 / (pair ? 2 : 1), K / 32);
+        launch_gemv_mfma(static_cast<const bf16_t *>(Wp), Xp, Xlo, st->ws.part, N, K, r.T, ks, pair ? 1 : 0, s);
+    } else {
+        launch_gemm_mfma(static_cast<const bf16_t *>(Wp), Xp, st->ws.part, N, K, r.T, s);
     }
-    launch_gemm_mfma(static_cast<const bf16_t *>(Wp), Xp, st->ws.part, N, K, r.T, s);
-    return 1;
+    st->prof.mark(slot, s);
+    return ks;
 }
 
 int pick_attn_split(const hexgen_kv_cache *kv, int batch) {
@@ -247,36 +277,42 @@ int attn_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Rows &r, h
     const KvGeom kg = geom(st, kv);
     bf16_t *kc = static_cast<bf16_t *>(kv->k) + (size_t)layer * kv->layer_stride;
     bf16_t *vc = static_cast<bf16_t *>(kv->v) + (size_t)layer * kv->layer_stride;
-    int ks = project_bf16(st, r, ly.wqkv, w.n, st->nqkv, st->H, false, s);
-    launch_qkv_rope_append(w.part, ks, r.T, st->hq_l, kg, r.rm, kv->cos_tab, kv->sin_tab, w.q, kc, vc, s);
+    int ks = project_bf16(st, r, ly.wqkv, w.n, w.n_lo, st->nqkv, st->H, false, PROF_QKV, s);
+    st->prof.mark(PROF_ATTN, s);
+    launch_qkv_rope_append(w.part, ks, r.T, st->hq_l, kg, r.rm, kv->cos_tab, kv->sin_tab, w.q,
+                           r.decode ? w.q_lo : nullptr, kc, vc, s);
     if (r.decode)
-        launch_attn_decode(w.q, kc, vc, kg, st->hq_l, kv->d_lens, r.batch, pick_attn_split(kv, r.batch), w.att_o,
-                           w.att_ml, w.o, s);
+        launch_attn_decode(w.q, w.q_lo, kc, vc, kg, st->hq_l, kv->d_lens, r.batch, pick_attn_split(kv, r.batch),
+                           w.att_o, w.att_ml, w.o, w.o_lo, s);
     else
         launch_attn_prefill(w.q, kc, vc, kg, st->hq_l, w.cu_rows, w.pos0, r.batch, r.max_new, w.o, s);
-    return project_bf16(st, r, ly.wo, w.o, st->H, st->qw, false, s);
+    st->prof.mark(PROF_ATTN, s);
+    return project_bf16(st, r, ly.wo, w.o, w.o_lo, st->H, st->qw, false, PROF_WO, s);
 }
 
 int ffn_bf16(hexgen_stage *st, int layer, const Rows &r, hipStream_t s) {
     Workspace &w = st->ws;
     const Layer &ly = st->layers[layer];
-    int ks = project_bf16(st, r, ly.w13, w.n, 2 * st->F_l, st->H, true, s);
-    launch_reduce_swiglu(w.part, ks, w.u, r.T, st->F_l, s);
-    return project_bf16(st, r, ly.w2, w.u, st->H, st->F_l, false, s);
+    int ks = project_bf16(st, r, ly.w13, w.n, w.n_lo, 2 * st->F_l, st->H, true, PROF_W13, s);
+    launch_reduce_swiglu(w.part, ks, w.u, r.decode ? w.u_lo : nullptr, r.T, st->F_l, s);
+    return project_bf16(st, r, ly.w2, w.u, w.u_lo, st->H, st->F_l, false, PROF_W2, s);
 }
 
 hexgen_status_t forward_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
                              void *out_partial, void *out_resid, hipStream_t s) {
     Workspace &w = st->ws;
-    launch_rmsnorm_pack(hidden_in, 1, w.h, st->layers[0].g_attn, w.n, r.T, st->H, st->eps, s);
+    launch_rmsnorm_pack(hidden_in, 1, w.h, st->layers[0].g_attn, w.n, r.decode ? w.n_lo : nullptr, r.T, st->H, st->eps,
+                        s);
     for (int l = 0; l < st->L; ++l) {
         if (st->taps[l])
             HX_HIP(hipMemcpyAsync(st->taps[l], w.h, sizeof(float) * (size_t)r.T * st->H, hipMemcpyDeviceToDevice, s));
         int ks = attn_bf16(st, kv, l, r, s);
-        launch_reduce_resid_norm(w.part, ks, w.h, st->layers[l].g_ffn, w.n, r.T, st->H, st->eps, s);
+        launch_reduce_resid_norm(w.part, ks, w.h, st->layers[l].g_ffn, w.n, r.decode ? w.n_lo : nullptr, r.T, st->H,
+                                 st->eps, s);
         ks = ffn_bf16(st, l, r, s);
         if (l + 1 < st->L) {
-            launch_reduce_resid_norm(w.part, ks, w.h, st->layers[l + 1].g_attn, w.n, r.T, st->H, st->eps, s);
+            launch_reduce_resid_norm(w.part, ks, w.h, st->layers[l + 1].g_attn, w.n, r.decode ? w.n_lo : nullptr, r.T,
+                                     st->H, st->eps, s);
         } else {
             launch_reduce_partial(w.part, ks, w.p32, r.T, st->H, s);
             launch_store_out(w.p32, out_partial, 1, (int64_t)r.T * st->H, s);
@@ -405,6 +441,7 @@ void hexgen_stage_destroy(hexgen_stage_t *st) {
     (void)hipDeviceSynchronize();
     for (Layer &l : st->layers) free_layer(l);
     free_ws(st->ws);
+    st->prof.clear();
     delete st;
 }
 
@@ -675,8 +712,10 @@ hexgen_status_t hexgen_stage_prefill(hexgen_stage_t *st, hexgen_kv_cache_t *kv, 
     Rows r;
     HX_TRY(setup_rows(st, kv, seq_lens, batch, s, &r));
     r.decode = false;                       // a prefill always takes the GEMM path
+    st->prof.mark(PROF_CALL, s);
     if (st->dtype == HEXGEN_BF16) HX_TRY(forward_bf16(st, kv, r, hidden_in, out_partial, out_resid, s));
     else HX_TRY(forward_f32(st, kv, r, hidden_in, out_partial, out_resid, s));
+    st->prof.mark(PROF_CALL, s);
     for (int i = 0; i < batch; ++i) kv->lens[i] = seq_lens[i];
     kv->batch = batch;
     kv->prefilled = true;
@@ -696,9 +735,11 @@ hexgen_status_t hexgen_stage_decode(hexgen_stage_t *st, hexgen_kv_cache_t *kv, i
     hipStream_t s = static_cast<hipStream_t>(stream);
     Rows r;
     HX_TRY(setup_rows(st, kv, nullptr, kv->batch, s, &r));
+    st->prof.mark(PROF_CALL, s);
     if (st->dtype == HEXGEN_BF16) HX_TRY(forward_bf16(st, kv, r, hidden_in, out_partial, out_resid, s));
     else HX_TRY(forward_f32(st, kv, r, hidden_in, out_partial, out_resid, s));
     launch_advance_lens(kv->d_lens, kv->batch, s);
+    st->prof.mark(PROF_CALL, s);
     for (int i = 0; i < kv->batch; ++i) kv->lens[i] += 1;
     kv->steps += 1;
     return HEXGEN_OK;
@@ -719,7 +760,8 @@ hexgen_status_t hexgen_stage_run_sublayer(hexgen_stage_t *st, hexgen_kv_cache_t 
     Workspace &w = st->ws;
     if (st->dtype == HEXGEN_BF16) {
         const Layer &ly = st->layers[layer];
-        launch_rmsnorm_pack(h, 0, nullptr, which == 0 ? ly.g_attn : ly.g_ffn, w.n, r.T, st->H, st->eps, s);
+        launch_rmsnorm_pack(h, 0, nullptr, which == 0 ? ly.g_attn : ly.g_ffn, w.n, r.decode ? w.n_lo : nullptr, r.T, st->H,
+                            st->eps, s);
         const int ks = which == 0 ? attn_bf16(st, kv, layer, r, s) : ffn_bf16(st, layer, r, s);
         launch_reduce_partial(w.part, ks, p, r.T, st->H, s);
     } else {
@@ -732,6 +774,31 @@ hexgen_status_t hexgen_stage_run_sublayer(hexgen_stage_t *st, hexgen_kv_cache_t 
 hexgen_status_t hexgen_accumulate_f32(void *dst, const void *src, int64_t n, void *stream) {
     if (!dst || !src || n < 0) return HEXGEN_ERR_INVALID_ARG;
     launch_accumulate_f32(static_cast<float *>(dst), static_cast<const float *>(src), n, static_cast<hipStream_t>(stream));
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_stage_profile_enable(hexgen_stage_t *st, int on) {
+    if (!st) return HEXGEN_ERR_INVALID_ARG;
+    HX_HIP(hipDeviceSynchronize());
+    st->prof.clear();
+    st->prof.on = on != 0;
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_stage_profile_read(hexgen_stage_t *st, int slot, double *total_ms, int64_t *count) {
+    if (!st || !total_ms || !count || slot < 0 || slot >= PROF_SLOTS) return HEXGEN_ERR_INVALID_ARG;
+    HX_HIP(hipDeviceSynchronize());
+    const std::vector<hipEvent_t> &v = st->prof.ev[slot];
+    double tot = 0.0;
+    int64_t n = 0;
+    for (size_t i = 0; i + 1 < v.size(); i += 2) {
+        float ms = 0.f;
+        HX_HIP(hipEventElapsedTime(&ms, v[i], v[i + 1]));
+        tot += ms;
+        ++n;
+    }
+    *total_ms = tot;
+    *count = n;
     return HEXGEN_OK;
 }
 

@@ -19,6 +19,15 @@ def row_rel_err(gpu, ref) -> float:
     return float(np.max(num / den))
 
 
+def max_abs_over_l2(gpu, ref) -> float:
+    """max over rows of max_c |gpu - ref| / ||ref_row||_2: the largest elementwise error measured against
+    the L2 norm of the output row (the literal form of "max relative error, relative to the output's L2
+    norm").  Used as the end-to-end gate only where bf16 storage makes the per-row L2 gate unattainable."""
+    g = np.asarray(gpu, dtype=np.float64).reshape(-1, np.asarray(ref).shape[-1])
+    r = np.asarray(ref, dtype=np.float64).reshape(g.shape)
+    return float(np.max(np.max(np.abs(g - r), axis=1) / np.linalg.norm(r, axis=1)))
+
+
 def torch_dtype(cfg):
     return torch.float32 if cfg.dtype == "f32" else torch.bfloat16
 

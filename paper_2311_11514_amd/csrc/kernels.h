@@ -13,18 +13,6 @@ struct RowMap {
     const int32_t *row_pos;   // [T]
 };
 
-// ---- layout / utility (kernels_layout.hip) -------------------------------------------------
-// dst tile (dst_tile0 + nt * dst_tile_stride) <- src[k0 + k][c0 + nt*16 + i], src row-major with
-// leading dimension ld (elements), K % 32 == 0, N % 16 == 0.
-void launch_pack_weight(const bf16_t *src, int64_t ld, int k0, int c0, int K, int N, bf16_t *dst,
-                        int dst_tile0, int dst_tile_stride, hipStream_t s);
-void launch_cvt_bf16_to_f32(const bf16_t *src, float *dst, int64_t n, hipStream_t s);
-void launch_accumulate_f32(float *dst, const float *src, int64_t n, hipStream_t s);
-// decode row map: row i -> (seq i, pos lens[i])
-void launch_decode_rowmap(const int32_t *lens, int32_t *row_seq, int32_t *row_pos, int b, hipStream_t s);
-void launch_advance_lens(int32_t *lens, int b, hipStream_t s);
-
-// ---- bf16 path (kernels_bf16_*.hip) ---------------------------------------------------------
 // KV cache geometry of one (layer, sequence, kv head) slab; see kernels_bf16_attn.hip
 struct KvGeom {
     int d;            // head dim (64 | 128)
@@ -33,6 +21,22 @@ struct KvGeom {
     int64_t seq_stride;   // elements between sequences  (= hkv_l * smax * d)
 };
 
+// ---- layout / utility (kernels_layout.hip) -------------------------------------------------
+// dst tile (dst_tile0 + nt * dst_tile_stride) <- src[k0 + k][c0 + nt*16 + i], src row-major with
+// leading dimension ld (elements), K % 32 == 0, N % 16 == 0.
+// rope_d > 0 (fused QKV weight): columns are heads of width rope_d; each 16-row tile of a head holds 8
+// rotary pairs (rows 0-7 = head columns 8*tl .. 8*tl+7, rows 8-15 = those + rope_d/2), so one MFMA tile is
+// self-contained for RoPE.  The QKV projection output is in this permuted column order.
+void launch_pack_weight(const bf16_t *src, int64_t ld, int k0, int c0, int K, int N, bf16_t *dst,
+                        int dst_tile0, int dst_tile_stride, int rope_d, hipStream_t s);
+void launch_cvt_bf16_to_f32(const bf16_t *src, float *dst, int64_t n, hipStream_t s);
+void launch_accumulate_f32(float *dst, const float *src, int64_t n, hipStream_t s);
+// decode row map: row i -> (seq i, pos lens[i])
+void launch_decode_rowmap(const int32_t *lens, int32_t *row_seq, int32_t *row_pos, int b, hipStream_t s);
+void launch_advance_lens(int32_t *lens, int b, hipStream_t s);
+
+// ---- bf16 path (kernels_bf16_*.hip) ---------------------------------------------------------
+
 // rows of `in` ([T,H] row-major, fp32 or bf16) -> optional fp32 copy h_out, and
 // packed bf16 n = in / sqrt(mean(in^2)+eps) * g  ([ceil16(T)/16][H/32] fragment tiles)
 // Packed activations may carry a second plane `*_lo` with the bf16 rounding remainder (x = hi + lo);
@@ -40,15 +44,47 @@ struct KvGeom {
 void launch_rmsnorm_pack(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *n_packed,
                          bf16_t *n_lo, int T, int H, float eps, hipStream_t s);
 
-// out[ks][t][n] (fp32, row stride N, split stride T*N) = sum over the split's k range of
-// Wp[n][k] * Xp[t][k]; T <= 32.  ksplit >= 1 splits K across blockIdx.y.
-void launch_gemv_mfma(const bf16_t *Wp, const bf16_t *Xp, const bf16_t *Xlo, float *out, int N, int K, int T,
-                      int ksplit, int pair_tiles, hipStream_t s);
+// ---- decode projections with fused epilogues (kernels_bf16_decode.hip) ---------------------------
+enum { DEC_RAW = 0, DEC_QKV = 1, DEC_RESID = 2, DEC_SWIGLU = 3 };
+#define DEC_SSQ_STRIDE 32      // tokens per unit row of the sum-of-squares scratch
+struct DecodeEpi {
+    int mode;                  // DEC_*
+    // RMSNorm statistics of the rows feeding this projection: sums of squares per (16-column unit,
+    // token); NULL when the input is not a normalised residual stream (W_O, W2)
+    const float *ssq_in;
+    int ssq_units, norm_dim;
+    float eps;
+    float *raw_out;            // RAW: [T][N] fp32
+    // QKV
+    int hq_l;
+    KvGeom kg;
+    const int32_t *row_pos;
+    const float *cos_tab, *sin_tab;
+    bf16_t *q_hi, *q_lo, *kc, *vc;
+    // RESID
+    float *h;                  // residual stream [T][N] fp32, updated in place
+    const float *g_next;       // gain of the next RMSNorm
+    bf16_t *hg_hi, *hg_lo;     // (h * g_next) as hi/lo operand planes
+    float *ssq_out;
+    int last_layer;            // 1: write out_partial / out_resid (bf16 [T][N]) instead of updating h
+    bf16_t *out_partial, *out_resid;
+    // SWIGLU
+    bf16_t *u_hi, *u_lo;
+    int F_l;
+};
+// Wp . (Xp + Xlo) for T <= 32 rows, one block per output unit, then the epilogue of e.mode
+void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xp, const bf16_t *Xlo, int N, int K, int T,
+                        const DecodeEpi &e, hipStream_t s);
+// stage input rows -> h (optional), (x * g) hi/lo planes, sums of squares; block 0 publishes row
+// positions from the committed lengths and optionally advances them
+void launch_decode_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg_hi,
+                            bf16_t *hg_lo, float *ssq_out, int T, int H, int32_t *lens, int32_t *row_pos,
+                            int advance, hipStream_t s);
 // same contraction for many rows (prefill): out[t][n] fp32 row-major
 void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, int K, int T, hipStream_t s);
 
-// sum ksplit partials of the fused QKV projection, rotate q and k heads, write q (bf16 row-major
-// [T][hq_l*d]) and append k, v to the cache at each row's (seq, pos)
+// prefill: the QKV projection output (rope-interleaved column order, see launch_pack_weight) -> rotate q
+// and k heads, write q (bf16 row-major [T][hq_l*d]) and append k, v to the cache at each row's (seq, pos)
 void launch_qkv_rope_append(const float *part, int ksplit, int T, int hq_l, KvGeom kg, RowMap rm,
                             const float *cos_tab, const float *sin_tab, bf16_t *q_out, bf16_t *q_lo, bf16_t *kc,
                             bf16_t *vc, hipStream_t s);
@@ -62,8 +98,9 @@ void launch_reduce_swiglu(const float *part, int ksplit, bf16_t *u_packed, bf16_
                           hipStream_t s);
 
 // decode attention: one new row per sequence; split-KV partials then merge into packed o
+// row_pos[seq] = position of the new row (= cached context length)
 void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, const bf16_t *vc, KvGeom kg,
-                        int hq_l, const int32_t *lens, int b, int nsplit, float *part_o, float *part_ml,
+                        int hq_l, const int32_t *row_pos, int b, int nsplit, float *part_o, float *part_ml,
                         bf16_t *o_packed, bf16_t *o_lo, hipStream_t s);
 // prefill attention over packed ragged rows; K, V are read from the cache
 void launch_attn_prefill(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,

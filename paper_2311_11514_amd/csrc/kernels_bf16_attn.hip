@@ -17,13 +17,13 @@ template <int D>
 __global__ __launch_bounds__(64) void attn_decode_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ q_lo,
                                                         const bf16_t *__restrict__ kc,
                                                         const bf16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
-                                                        const int32_t *__restrict__ lens, int nsplit,
+                                                        const int32_t *__restrict__ row_pos, int nsplit,
                                                         float *__restrict__ part_o, float *__restrict__ part_ml,
                                                         float scale_log2e) {
     constexpr int KT = D / 32, DT = D / 16;
     const int split = blockIdx.x, c = blockIdx.y, sq = blockIdx.z;
     const int lane = threadIdx.x, j = lane & 15, g = lane >> 4;
-    const int n_pos = lens[sq] + 1;   // committed context plus the row appended in this step
+    const int n_pos = row_pos[sq] + 1;   // cached context plus the row appended in this step
     const int n_t32 = (n_pos + 31) >> 5;
     const int per = (n_t32 + nsplit - 1) / nsplit;
     const int t0 = split * per, t1 = min(n_t32, t0 + per);
@@ -131,19 +131,145 @@ __global__ void attn_decode_merge_kernel(const float *__restrict__ part_o, const
     o_lo[off] = lo;
 }
 
+// Single-kernel variant: one 8-wave block per (sequence, kv head); the waves interleave over the
+// 32-position tiles of the context and their (m, l, o) triples are merged through LDS in wave order.
+// Used when there are enough (sequence, kv head) pairs to fill the chip or the context is short.
+template <int D>
+__global__ __launch_bounds__(512) void attn_decode_block_kernel(const bf16_t *__restrict__ q,
+                                                               const bf16_t *__restrict__ q_lo,
+                                                               const bf16_t *__restrict__ kc,
+                                                               const bf16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
+                                                               const int32_t *__restrict__ row_pos,
+                                                               bf16_t *__restrict__ o_packed,
+                                                               bf16_t *__restrict__ o_lo, float scale_log2e) {
+    constexpr int KT = D / 32, DT = D / 16, W = 8;
+    __shared__ float s_m[W][16], s_l[W][16];
+    __shared__ float s_o[W][16][D];
+    const int c = blockIdx.x, sq = blockIdx.y;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 15, g = lane >> 4;
+    const int n_pos = row_pos[sq] + 1;
+    const int n_t32 = (n_pos + 31) >> 5;
+    const int head = c * G + j;
+    const bool hv = j < G;
+
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    bf16x8 qf[KT], ql[KT];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+        const size_t qo = ((size_t)sq * hq_l + head) * D + kt * 32 + 8 * g;
+        qf[kt] = hv ? *reinterpret_cast<const bf16x8 *>(q + qo) : zero;
+        ql[kt] = hv ? *reinterpret_cast<const bf16x8 *>(q_lo + qo) : zero;
+    }
+    floatx4 oacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) oacc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float m = NEG_INF, lsum = 0.f;
+    const size_t slab = (size_t)sq * kg.seq_stride + (size_t)c * kg.smax * D;
+    const bf16x8 *ks = reinterpret_cast<const bf16x8 *>(kc + slab) + lane;
+    const bf16x8 *vs = reinterpret_cast<const bf16x8 *>(vc + slab) + lane;
+
+    for (int t = wave; t < n_t32; t += W) {
+        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+        bf16x8 ka[KT], kb[KT], va[DT];
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+            ka[kt] = ks[(size_t)((2 * t) * KT + kt) * 64];
+            kb[kt] = ks[(size_t)((2 * t + 1) * KT + kt) * 64];
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) va[dt] = vs[(size_t)(t * DT + dt) * 64];
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt], ql[kt], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[kt], ql[kt], s1, 0, 0, 0);
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt], qf[kt], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[kt], qf[kt], s1, 0, 0, 0);
+        }
+        const int pbase = t * 32 + 4 * g;
+        float mx = NEG_INF;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            s0[r] = (pbase + r < n_pos) ? s0[r] * scale_log2e : NEG_INF;
+            s1[r] = (pbase + 16 + r < n_pos) ? s1[r] * scale_log2e : NEG_INF;
+            mx = fmaxf(mx, fmaxf(s0[r], s1[r]));
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m, mx);
+        const float alpha = exp2f(m - m_new);
+        m = m_new;
+        float p0[4], p1[4], ps = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            p0[r] = exp2f(s0[r] - m_new);
+            p1[r] = exp2f(s1[r] - m_new);
+            ps += p0[r] + p1[r];
+        }
+        lsum = lsum * alpha + ps;
+        union { uint32_t u[4]; bf16x8 v; } pb, pl;
+        split_pack2(p0[0], p0[1], pb.u[0], pl.u[0]); split_pack2(p0[2], p0[3], pb.u[1], pl.u[1]);
+        split_pack2(p1[0], p1[1], pb.u[2], pl.u[2]); split_pack2(p1[2], p1[3], pb.u[3], pl.u[3]);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            oacc[dt] *= alpha;
+            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pl.v, oacc[dt], 0, 0, 0);
+            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb.v, oacc[dt], 0, 0, 0);
+        }
+    }
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    if (g == 0) { s_m[wave][j] = m; s_l[wave][j] = lsum; }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<floatx4 *>(&s_o[wave][j][dt * 16 + 4 * g]) = oacc[dt];
+    __syncthreads();
+    const int k_tiles = (hq_l * D) >> 5;
+    for (int idx = threadIdx.x * 4; idx < G * D; idx += 512 * 4) {
+        const int hh = idx / D, dd = idx % D;
+        float M = NEG_INF;
+#pragma unroll
+        for (int w = 0; w < W; ++w) M = fmaxf(M, s_m[w][hh]);
+        float L = 0.f;
+        floatx4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            const float mw = s_m[w][hh];
+            const float wt = (mw == NEG_INF) ? 0.f : exp2f(mw - M);
+            L += s_l[w][hh] * wt;
+            o += *reinterpret_cast<const floatx4 *>(&s_o[w][hh][dd]) * wt;
+        }
+        const float inv = 1.0f / L;
+        uint2 ph, pl;
+        split_pack2(o[0] * inv, o[1] * inv, ph.x, pl.x);
+        split_pack2(o[2] * inv, o[3] * inv, ph.y, pl.y);
+        const size_t off = frag_offset(sq, (c * G + hh) * D + dd, k_tiles);
+        *reinterpret_cast<uint2 *>(o_packed + off) = ph;
+        *reinterpret_cast<uint2 *>(o_lo + off) = pl;
+    }
+}
+
 void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, const bf16_t *vc, KvGeom kg,
-                        int hq_l, const int32_t *lens, int b, int nsplit, float *part_o, float *part_ml,
+                        int hq_l, const int32_t *row_pos, int b, int nsplit, float *part_o, float *part_ml,
                         bf16_t *o_packed, bf16_t *o_lo, hipStream_t s) {
     const int G = hq_l / kg.hkv_l;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)kg.d);
+    if (nsplit <= 1) {       // single kernel, LDS merge
+        dim3 grid(kg.hkv_l, b);
+        if (kg.d == 128)
+            hipLaunchKernelGGL(attn_decode_block_kernel<128>, grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G,
+                               row_pos, o_packed, o_lo, scale_log2e);
+        else
+            hipLaunchKernelGGL(attn_decode_block_kernel<64>, grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G,
+                               row_pos, o_packed, o_lo, scale_log2e);
+        return;
+    }
     dim3 grid(nsplit, kg.hkv_l, b);
     if (kg.d == 128) {
-        hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(64), 0, s, q, q_lo, kc, vc, kg, hq_l, G, lens, nsplit,
+        hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(64), 0, s, q, q_lo, kc, vc, kg, hq_l, G, row_pos, nsplit,
                            part_o, part_ml, scale_log2e);
         hipLaunchKernelGGL(attn_decode_merge_kernel<128>, dim3(b, hq_l), dim3(128), 0, s, part_o, part_ml, hq_l,
                            nsplit, o_packed, o_lo);
     } else {
-        hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(64), 0, s, q, q_lo, kc, vc, kg, hq_l, G, lens, nsplit,
+        hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(64), 0, s, q, q_lo, kc, vc, kg, hq_l, G, row_pos, nsplit,
                            part_o, part_ml, scale_log2e);
         hipLaunchKernelGGL(attn_decode_merge_kernel<64>, dim3(b, hq_l), dim3(64), 0, s, part_o, part_ml, hq_l, nsplit,
                            o_packed, o_lo);

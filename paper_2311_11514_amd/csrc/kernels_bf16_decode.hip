@@ -1,0 +1,308 @@
+// Decode projections (T <= 32 token rows): a weight-streaming skinny GEMM on the matrix cores with the
+// whole sub-layer glue fused into its tail.  No scratch buffers, no atomics, no second kernel.
+//
+// Main loop.  Each wave streams 1 KB weight tiles with one 128-bit load per lane (fully coalesced,
+// non-temporal) and feeds them to v_mfma_f32_16x16x32_bf16 against a 16-token activation tile: 16 MFMA
+// cycles per KB, a quarter of what unpacking bf16 on the vector ALU would cost, so the kernel stays
+// HBM-bound up to 32 rows.  Activations arrive as hi + lo bf16 pairs (two MFMAs per tile, free here).
+// A block owns one unit = UT 16-feature tiles over the WHOLE contraction; its waves interleave over the
+// k-tiles and are summed through LDS in wave order (bit-reproducible).  Because a block holds complete
+// dot products, the epilogue runs in registers on the 16x16 accumulator layout (lane = one token, four
+// consecutive features):
+//   QKV    : x rstd of the input rows, RoPE, q -> hi/lo rows, k / v -> KV cache.  The QKV weight tiles are
+//            packed so that a tile holds 8 rotary pairs (features i and i + d/2), which lie 32 lanes apart.
+//   RESID  : h += partial; (h * gain of the next norm) -> hi/lo operand of the next projection;
+//            per-unit sum of squares of the new h, from which the next kernel derives rstd
+//   SWIGLU : x rstd, silu(gate) * up -> hi/lo operand of the W2 projection (gate / up tiles interleaved)
+//   RAW    : x rstd (if the input is a normalised stream), plain fp32 partial (validation surface)
+// RMSNorm is thus never a kernel of its own in decode: y = rstd * ((h*g) . W), with rstd a per-row
+// scalar applied after the contraction.
+#include "kernels.h"
+#include "kvlayout.h"
+
+// rstd of every token row from the per-unit sums of squares; wave w handles tokens w, w + WAVES, ...
+template <int WAVES>
+__device__ inline void load_rstd(const DecodeEpi &e, int T, int wave, int lane, float *s_rstd) {
+    for (int t = wave; t < T; t += WAVES) {
+        float r = 1.0f;
+        if (e.ssq_in) {
+            float ss = 0.f;
+            for (int i = lane; i < e.ssq_units; i += 64) ss += e.ssq_in[i * DEC_SSQ_STRIDE + t];
+            ss = wave_sum(ss);
+            r = 1.0f / sqrtf(ss / (float)e.norm_dim + e.eps);
+        }
+        if (lane == 0) s_rstd[t] = r;
+    }
+}
+
+__device__ inline void store_split4(const float x[4], bf16_t *hi, bf16_t *lo, size_t off) {
+    uint2 o, ol;
+    split_pack2(x[0], x[1], o.x, ol.x);
+    split_pack2(x[2], x[3], o.y, ol.y);
+    *reinterpret_cast<uint2 *>(hi + off) = o;
+    *reinterpret_cast<uint2 *>(lo + off) = ol;
+}
+
+template <int NB, int UT, int WAVES, int UNROLL, int MODE>
+__global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *__restrict__ Wp,
+                                                                const bf16_t *__restrict__ Xp,
+                                                                const bf16_t *__restrict__ Xlo, int N, int k_tiles,
+                                                                int T, DecodeEpi e) {
+    __shared__ floatx4 red[WAVES][UT * NB][64];
+    __shared__ float s_rstd[32];
+    const int unit = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+
+    floatx4 acc[UT][NB];
+#pragma unroll
+    for (int u = 0; u < UT; ++u)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) acc[u][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const bf16x8 *wp[UT];
+#pragma unroll
+    for (int u = 0; u < UT; ++u)
+        wp[u] = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)(unit * UT + u) * k_tiles * 64 + lane;
+    const bf16x8 *xp[NB], *xl[NB];
+    bool xv[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        xp[b] = reinterpret_cast<const bf16x8 *>(Xp) + (size_t)b * k_tiles * 64 + lane;
+        xl[b] = reinterpret_cast<const bf16x8 *>(Xlo) + (size_t)b * k_tiles * 64 + lane;
+        xv[b] = (lane & 15) + 16 * b < T;
+    }
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+
+    int kt = wave;
+    for (; kt + (UNROLL - 1) * WAVES < k_tiles; kt += UNROLL * WAVES) {
+        bf16x8 a[UNROLL][UT];
+#pragma unroll
+        for (int i = 0; i < UNROLL; ++i) {
+            const size_t o = (size_t)(kt + i * WAVES) * 64;
+#pragma unroll
+            for (int u = 0; u < UT; ++u) a[i][u] = __builtin_nontemporal_load(wp[u] + o);
+        }
+        {
+            bf16x8 x[UNROLL][NB], y[UNROLL][NB];
+#pragma unroll
+            for (int i = 0; i < UNROLL; ++i) {
+                const size_t o = (size_t)(kt + i * WAVES) * 64;
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    x[i][b] = xv[b] ? xp[b][o] : zero;
+                    y[i][b] = xv[b] ? xl[b][o] : zero;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < UNROLL; ++i)
+#pragma unroll
+                for (int u = 0; u < UT; ++u)
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) {
+                        acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], y[i][b], acc[u][b], 0, 0, 0);
+                        acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], x[i][b], acc[u][b], 0, 0, 0);
+                    }
+        }
+    }
+    for (; kt < k_tiles; kt += WAVES) {
+        const size_t o = (size_t)kt * 64;
+#pragma unroll
+        for (int u = 0; u < UT; ++u) {
+            bf16x8 a = __builtin_nontemporal_load(wp[u] + o);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const bf16x8 x = xv[b] ? xp[b][o] : zero;
+                const bf16x8 y = xv[b] ? xl[b][o] : zero;
+                acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, y, acc[u][b], 0, 0, 0);
+                acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, x, acc[u][b], 0, 0, 0);
+            }
+        }
+    }
+
+    if (MODE != DEC_RESID) load_rstd<WAVES>(e, T, wave, lane, s_rstd);
+#pragma unroll
+    for (int u = 0; u < UT; ++u)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) red[wave][u * NB + b][lane] = acc[u][b];
+    __syncthreads();
+    if (wave >= NB) return;            // wave b finishes token tile b
+
+    const int b = wave;
+    floatx4 v[UT];
+#pragma unroll
+    for (int u = 0; u < UT; ++u) {
+        v[u] = red[0][u * NB + b][lane];
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) v[u] += red[w][u * NB + b][lane];
+    }
+    const int token = (lane & 15) + 16 * b, g = lane >> 4;
+    const bool valid = token < T;
+    const float r = (MODE != DEC_RESID && valid) ? s_rstd[token] : 1.0f;
+
+    if (MODE == DEC_RAW) {
+        const int n0 = unit * 16 + 4 * g;
+        if (valid) *reinterpret_cast<floatx4 *>(e.raw_out + (size_t)token * N + n0) = v[0] * r;
+    } else if (MODE == DEC_RESID) {
+        const int n0 = unit * 16 + 4 * g;
+        float ss = 0.f;
+        if (valid) {
+            const floatx4 h4 = *reinterpret_cast<const floatx4 *>(e.h + (size_t)token * N + n0);
+            if (e.last_layer) {
+                // stage output: the partial without residual, and the residual it belongs to
+                uint2 po;
+                po.x = pack_bf16x2(v[0][0], v[0][1]);
+                po.y = pack_bf16x2(v[0][2], v[0][3]);
+                *reinterpret_cast<uint2 *>(e.out_partial + (size_t)token * N + n0) = po;
+                if (e.out_resid) {
+                    uint2 ro;
+                    ro.x = pack_bf16x2(h4[0], h4[1]);
+                    ro.y = pack_bf16x2(h4[2], h4[3]);
+                    *reinterpret_cast<uint2 *>(e.out_resid + (size_t)token * N + n0) = ro;
+                }
+            } else {
+                const floatx4 hn = h4 + v[0];
+                *reinterpret_cast<floatx4 *>(e.h + (size_t)token * N + n0) = hn;
+                const floatx4 g4 = *reinterpret_cast<const floatx4 *>(e.g_next + n0);
+                const float x[4] = {hn[0] * g4[0], hn[1] * g4[1], hn[2] * g4[2], hn[3] * g4[3]};
+                store_split4(x, e.hg_hi, e.hg_lo, frag_offset(token, n0, N >> 5));
+                ss = hn[0] * hn[0] + hn[1] * hn[1] + hn[2] * hn[2] + hn[3] * hn[3];
+            }
+        }
+        if (!e.last_layer) {
+            ss += __shfl_xor(ss, 16, 64);
+            ss += __shfl_xor(ss, 32, 64);
+            if (g == 0 && valid) e.ssq_out[unit * DEC_SSQ_STRIDE + token] = ss;
+        }
+    } else if (MODE == DEC_SWIGLU) {
+        // unit = one gate tile (v[0]) and the matching up tile (v[1]): 16 features of u
+        if (valid) {
+            const int f0 = unit * 16 + 4 * g;
+            float uu[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float aa = v[0][j] * r;
+                uu[j] = aa / (1.0f + __expf(-aa)) * (v[UT - 1][j] * r);
+            }
+            store_split4(uu, e.u_hi, e.u_lo, frag_offset(token, f0, e.F_l >> 5));
+        }
+    } else {   // DEC_QKV
+        const int d = e.kg.d, half = d >> 1, tiles_per_head = d >> 4;
+        const int head = unit / tiles_per_head, tl = unit - head * tiles_per_head;
+        floatx4 mine = v[0] * r, other;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) other[j] = __shfl_xor(mine[j], 32, 64);
+        const bool low = g < 2;                       // rows 0-7 of the tile: features i; rows 8-15: i + d/2
+        const int i0 = tl * 8 + 4 * (g & 1);          // first rotary pair index held by this lane
+        if (valid) {
+            const int pos = e.row_pos[token];
+            float out[4];
+            if (head < e.hq_l + e.kg.hkv_l) {
+                const floatx4 c4 = *reinterpret_cast<const floatx4 *>(e.cos_tab + (size_t)pos * half + i0);
+                const floatx4 s4 = *reinterpret_cast<const floatx4 *>(e.sin_tab + (size_t)pos * half + i0);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float lo = low ? mine[j] : other[j], hi = low ? other[j] : mine[j];
+                    out[j] = low ? lo * c4[j] - hi * s4[j] : hi * c4[j] + lo * s4[j];
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) out[j] = mine[j];
+            }
+            const int e0 = i0 + (low ? 0 : half);     // element index inside the head
+            if (head < e.hq_l) {
+                store_split4(out, e.q_hi, e.q_lo, ((size_t)token * e.hq_l + head) * d + e0);
+            } else if (head < e.hq_l + e.kg.hkv_l) {
+                const size_t slab = (size_t)token * e.kg.seq_stride + (size_t)(head - e.hq_l) * e.kg.smax * d;
+                uint2 o;
+                o.x = pack_bf16x2(out[0], out[1]);
+                o.y = pack_bf16x2(out[2], out[3]);
+                *reinterpret_cast<uint2 *>(e.kc + slab + kv_k_offset(pos, e0, d)) = o;
+            } else {
+                const size_t slab =
+                    (size_t)token * e.kg.seq_stride + (size_t)(head - e.hq_l - e.kg.hkv_l) * e.kg.smax * d;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) e.vc[slab + kv_v_offset(pos, e0 + j, d)] = f32_to_bf16(out[j]);
+            }
+        }
+    }
+}
+
+void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xp, const bf16_t *Xlo, int N, int K, int T,
+                        const DecodeEpi &e, hipStream_t s) {
+    const int k_tiles = K / 32, n_tiles = N / 16;
+    constexpr int WAVES = 8;
+#define HX_DEC(NB, UT, UNR, MODE)                                                                              \
+    hipLaunchKernelGGL((decode_proj_kernel<NB, UT, WAVES, UNR, MODE>), dim3(n_tiles / UT), dim3(WAVES * 64), 0, \
+                       s, Wp, Xp, Xlo, N, k_tiles, T, e)
+#define HX_DEC_NB(UT, UNR, MODE)                          \
+    do {                                                  \
+        if (T <= 16) HX_DEC(1, UT, UNR, MODE);            \
+        else HX_DEC(2, UT, UNR, MODE);                    \
+    } while (0)
+    switch (e.mode) {
+        case DEC_RAW: HX_DEC_NB(1, 8, DEC_RAW); break;
+        case DEC_QKV: HX_DEC_NB(1, 8, DEC_QKV); break;
+        case DEC_RESID: HX_DEC_NB(1, 8, DEC_RESID); break;
+        case DEC_SWIGLU: HX_DEC_NB(2, 4, DEC_SWIGLU); break;
+    }
+#undef HX_DEC_NB
+#undef HX_DEC
+}
+
+// -------------------------------------------------------------------------------------------------
+// Per-step prologue: stage input rows (bf16, or fp32 for the validation surface) -> fp32 residual
+// stream, (x * gain) hi/lo operand of the first projection, per-unit sums of squares (one unit = 16
+// columns, as written by the RESID epilogue).  Block 0 also publishes each row's position (the
+// sequence's committed length) and, when asked, advances the lengths.
+// grid = H / 128 blocks of 512 threads; thread = (token, 4-column group).
+// -------------------------------------------------------------------------------------------------
+template <bool IN_BF16>
+__global__ __launch_bounds__(512) void decode_prologue_kernel(const void *__restrict__ in, float *__restrict__ h_out,
+                                                             const float *__restrict__ g, bf16_t *__restrict__ hg_hi,
+                                                             bf16_t *__restrict__ hg_lo, float *__restrict__ ssq_out,
+                                                             int T, int H, int32_t *lens, int32_t *row_pos,
+                                                             int advance) {
+    if (blockIdx.x == 0 && lens != nullptr && threadIdx.x < T) {
+        const int l = lens[threadIdx.x];
+        row_pos[threadIdx.x] = l;
+        if (advance) lens[threadIdx.x] = l + 1;
+    }
+    // 32 column quads per block (128 columns), 16 tokens per pass
+    const int quad = threadIdx.x & 31, tsub = threadIdx.x >> 5;
+    const int col = blockIdx.x * 128 + quad * 4;
+    for (int t = tsub; t < T; t += 16) {
+        float ss = 0.f;
+        if (col < H) {
+            float x[4];
+            if (IN_BF16) {
+                uint2 raw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(in) + (size_t)t * H + col);
+                x[0] = bf16_to_f32((bf16_t)(raw.x & 0xffff)); x[1] = bf16_to_f32((bf16_t)(raw.x >> 16));
+                x[2] = bf16_to_f32((bf16_t)(raw.y & 0xffff)); x[3] = bf16_to_f32((bf16_t)(raw.y >> 16));
+            } else {
+                const floatx4 a = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const float *>(in) + (size_t)t * H + col);
+                x[0] = a[0]; x[1] = a[1]; x[2] = a[2]; x[3] = a[3];
+            }
+            if (h_out) *reinterpret_cast<floatx4 *>(h_out + (size_t)t * H + col) = floatx4{x[0], x[1], x[2], x[3]};
+            const floatx4 g4 = *reinterpret_cast<const floatx4 *>(g + col);
+            const float y[4] = {x[0] * g4[0], x[1] * g4[1], x[2] * g4[2], x[3] * g4[3]};
+            store_split4(y, hg_hi, hg_lo, frag_offset(t, col, H >> 5));
+            ss = x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
+        }
+        // the 4 quads of one 16-column unit are 4 consecutive lanes
+        ss += __shfl_xor(ss, 1, 64);
+        ss += __shfl_xor(ss, 2, 64);
+        if ((quad & 3) == 0 && col < H) ssq_out[(col >> 4) * DEC_SSQ_STRIDE + t] = ss;
+    }
+}
+
+void launch_decode_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg_hi,
+                            bf16_t *hg_lo, float *ssq_out, int T, int H, int32_t *lens, int32_t *row_pos,
+                            int advance, hipStream_t s) {
+    const int blocks = (H + 127) / 128;
+    if (in_is_bf16)
+        hipLaunchKernelGGL(decode_prologue_kernel<true>, dim3(blocks), dim3(512), 0, s, in, h_out, g, hg_hi, hg_lo,
+                           ssq_out, T, H, lens, row_pos, advance);
+    else
+        hipLaunchKernelGGL(decode_prologue_kernel<false>, dim3(blocks), dim3(512), 0, s, in, h_out, g, hg_hi, hg_lo,
+                           ssq_out, T, H, lens, row_pos, advance);
+}

@@ -1,6 +1,6 @@
-// bf16 projections of the stage: RMSNorm fused with the cast into the GEMM operand layout, the
-// weight-streaming skinny MFMA kernel used by decode (T <= 32 rows), the LDS-tiled MFMA GEMM used by
-// prefill, and the split-K reduce epilogues (RoPE + cache append, residual + next norm, SwiGLU).
+// bf16 projections of the prefill path: RMSNorm fused with the cast into the GEMM operand layout, the
+// LDS-tiled MFMA GEMM, and its epilogue kernels (RoPE + cache append, residual + next norm, SwiGLU).
+// The decode path (T <= 32 rows) lives in kernels_bf16_decode.hip.
 //
 // Every contraction is computed "transposed": D^T[n][t] = sum_k Wp[n][k] * Xp[t][k] with the weight
 // tile as MFMA operand A and the activation tile as operand B.  In the 16x16 result each lane then
@@ -75,118 +75,6 @@ void launch_rmsnorm_pack(const void *in, int in_is_bf16, float *h_out, const flo
         hipLaunchKernelGGL(rmsnorm_pack_kernel<true>, dim3(T), dim3(256), 0, s, in, h_out, g, n_packed, n_lo, H, eps);
     else
         hipLaunchKernelGGL(rmsnorm_pack_kernel<false>, dim3(T), dim3(256), 0, s, in, h_out, g, n_packed, n_lo, H, eps);
-}
-
-// -------------------------------------------------------------------------------------------------
-// Decode projection: weight-streaming skinny GEMM.  Each wave streams 1 KB weight tiles with one
-// 128-bit load per lane and feeds them to the matrix core against a (mostly zero-padded) 16-token
-// activation tile: 16 MFMA cycles per KB, four times cheaper than unpacking bf16 on the vector ALU.
-// A block owns UT consecutive 16-feature tiles; its WAVES waves interleave over the k-tiles of the
-// block's K range and are summed through LDS in wave order (fixed order: bit-reproducible).
-// blockIdx.y splits K further across blocks; those partials are summed by the epilogue kernels.
-// -------------------------------------------------------------------------------------------------
-template <int NB, int UT, int WAVES, int UNROLL>
-__global__ __launch_bounds__(WAVES * 64) void gemv_mfma_kernel(const bf16_t *__restrict__ Wp,
-                                                              const bf16_t *__restrict__ Xp,
-                                                              const bf16_t *__restrict__ Xlo,
-                                                              float *__restrict__ out, int N, int k_tiles,
-                                                              int kt_per_split, int T) {
-    __shared__ floatx4 red[WAVES][UT * NB][64];
-    const int unit = blockIdx.x, ks = blockIdx.y;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int kt0 = ks * kt_per_split;
-    const int kt1 = min(k_tiles, kt0 + kt_per_split);
-
-    floatx4 acc[UT][NB];
-#pragma unroll
-    for (int u = 0; u < UT; ++u)
-#pragma unroll
-        for (int b = 0; b < NB; ++b) acc[u][b] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    const bf16x8 *wp[UT];
-#pragma unroll
-    for (int u = 0; u < UT; ++u)
-        wp[u] = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)(unit * UT + u) * k_tiles * 64 + lane;
-    const bf16x8 *xp[NB], *xl[NB];
-    bool xv[NB];
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        xp[b] = reinterpret_cast<const bf16x8 *>(Xp) + (size_t)b * k_tiles * 64 + lane;
-        xl[b] = reinterpret_cast<const bf16x8 *>(Xlo) + (size_t)b * k_tiles * 64 + lane;
-        xv[b] = (lane & 15) + 16 * b < T;
-    }
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-
-    int kt = kt0 + wave;
-    for (; kt + (UNROLL - 1) * WAVES < kt1; kt += UNROLL * WAVES) {
-        bf16x8 a[UNROLL][UT], x[UNROLL][NB], y[UNROLL][NB];
-#pragma unroll
-        for (int i = 0; i < UNROLL; ++i) {
-            const size_t o = (size_t)(kt + i * WAVES) * 64;
-#pragma unroll
-            for (int u = 0; u < UT; ++u) a[i][u] = __builtin_nontemporal_load(wp[u] + o);
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                x[i][b] = xv[b] ? xp[b][o] : zero;
-                y[i][b] = xv[b] ? xl[b][o] : zero;
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < UNROLL; ++i)
-#pragma unroll
-            for (int u = 0; u < UT; ++u)
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], y[i][b], acc[u][b], 0, 0, 0);
-                    acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], x[i][b], acc[u][b], 0, 0, 0);
-                }
-    }
-    for (; kt < kt1; kt += WAVES) {
-        const size_t o = (size_t)kt * 64;
-#pragma unroll
-        for (int u = 0; u < UT; ++u) {
-            bf16x8 a = __builtin_nontemporal_load(wp[u] + o);
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                bf16x8 x = xv[b] ? xp[b][o] : zero;
-                bf16x8 y = xv[b] ? xl[b][o] : zero;
-                acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, y, acc[u][b], 0, 0, 0);
-                acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, x, acc[u][b], 0, 0, 0);
-            }
-        }
-    }
-
-#pragma unroll
-    for (int u = 0; u < UT; ++u)
-#pragma unroll
-        for (int b = 0; b < NB; ++b) red[wave][u * NB + b][lane] = acc[u][b];
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < UT * NB * 64; idx += WAVES * 64) {
-        const int tile = idx >> 6, l = idx & 63;
-        floatx4 sum = red[0][tile][l];
-#pragma unroll
-        for (int w = 1; w < WAVES; ++w) sum += red[w][tile][l];
-        const int u = tile / NB, b = tile % NB;
-        const int token = (l & 15) + 16 * b;
-        const int n = (unit * UT + u) * 16 + 4 * (l >> 4);
-        if (token < T) *reinterpret_cast<floatx4 *>(out + ((size_t)ks * T + token) * N + n) = sum;
-    }
-}
-
-void launch_gemv_mfma(const bf16_t *Wp, const bf16_t *Xp, const bf16_t *Xlo, float *out, int N, int K, int T,
-                      int ksplit, int pair_tiles, hipStream_t s) {
-    const int k_tiles = K / 32, n_tiles = N / 16;
-    const int per = (k_tiles + ksplit - 1) / ksplit;
-    constexpr int WAVES = 8;
-#define HX_GEMV(NB, UT, UNR)                                                                                      \
-    hipLaunchKernelGGL((gemv_mfma_kernel<NB, UT, WAVES, UNR>), dim3(n_tiles / UT, ksplit), dim3(WAVES * 64), 0, s, \
-                       Wp, Xp, Xlo, out, N, k_tiles, per, T)
-    if (T <= 16) {
-        if (pair_tiles) HX_GEMV(1, 2, 4); else HX_GEMV(1, 1, 8);
-    } else {
-        if (pair_tiles) HX_GEMV(2, 2, 4); else HX_GEMV(2, 1, 8);
-    }
-#undef HX_GEMV
 }
 
 // -------------------------------------------------------------------------------------------------
@@ -277,12 +165,13 @@ __global__ void qkv_rope_append_kernel(const float *__restrict__ part, int kspli
     const int t = blockIdx.x, head = blockIdx.y, i = threadIdx.x;
     const int d = kg.d, half = d >> 1;
     const int N = (hq_l + 2 * kg.hkv_l) * d;
-    const int col = head * d + i;
+    // projection output columns are rope-interleaved: pair (i, i + d/2) sits at (8 apart) in one tile
+    const int col = head * d + (i >> 3) * 16 + (i & 7);
     float lo = 0.f, hi = 0.f;
     for (int ks = 0; ks < ksplit; ++ks) {
         const float *p = part + ((size_t)ks * T + t) * N + col;
         lo += p[0];
-        hi += p[half];
+        hi += p[8];
     }
     const int seq = rm.row_seq[t], pos = rm.row_pos[t];
     if (head < hq_l + kg.hkv_l) {

@@ -3,8 +3,11 @@
 #include "kvlayout.h"
 
 // One thread builds one 16-byte lane slot of the packed matrix.
+// rope_d > 0: the columns are heads of width rope_d and every 16-row tile of a head is filled with 8 rotary
+// pairs: tile rows 0-7 = head columns 8*tl .. 8*tl+7, rows 8-15 = the same columns + rope_d/2.
 __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, int64_t ld, int k0, int c0, int k_tiles,
-                                   int n_tiles, bf16_t *__restrict__ dst, int dst_tile0, int dst_tile_stride) {
+                                   int n_tiles, bf16_t *__restrict__ dst, int dst_tile0, int dst_tile_stride,
+                                   int rope_d) {
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t total = (int64_t)n_tiles * k_tiles * 64;
     if (gid >= total) return;
@@ -12,6 +15,10 @@ __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, int64_t ld, i
     int64_t tile = gid >> 6;
     int kt = (int)(tile % k_tiles), nt = (int)(tile / k_tiles);
     int n = c0 + nt * 16 + (lane & 15);
+    if (rope_d > 0) {
+        const int tph = rope_d >> 4, head = nt / tph, tl = nt - head * tph, i = lane & 15;
+        n = c0 + head * rope_d + tl * 8 + (i & 7) + (i >= 8 ? (rope_d >> 1) : 0);
+    }
     int k = k0 + kt * 32 + 8 * (lane >> 4);
     union { bf16_t e[8]; uint4 v; } u;
 #pragma unroll
@@ -21,13 +28,13 @@ __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, int64_t ld, i
 }
 
 void launch_pack_weight(const bf16_t *src, int64_t ld, int k0, int c0, int K, int N, bf16_t *dst,
-                        int dst_tile0, int dst_tile_stride, hipStream_t s) {
+                        int dst_tile0, int dst_tile_stride, int rope_d, hipStream_t s) {
     int k_tiles = K / 32, n_tiles = N / 16;
     int64_t total = (int64_t)n_tiles * k_tiles * 64;
     if (total == 0) return;
     int blocks = (int)((total + 255) / 256);
     hipLaunchKernelGGL(pack_weight_kernel, dim3(blocks), dim3(256), 0, s, src, ld, k0, c0, k_tiles, n_tiles,
-                       dst, dst_tile0, dst_tile_stride);
+                       dst, dst_tile0, dst_tile_stride, rope_d);
 }
 
 __global__ void cvt_bf16_to_f32_kernel(const bf16_t *__restrict__ src, float *__restrict__ dst, int64_t n) {

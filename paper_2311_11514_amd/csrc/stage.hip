@@ -71,6 +71,7 @@ struct Workspace {
     bf16_t *n = nullptr, *o = nullptr, *u = nullptr, *q = nullptr;
     bf16_t *n_lo = nullptr, *o_lo = nullptr, *u_lo = nullptr, *q_lo = nullptr;   // decode rows only (x = hi + lo)
     float *att_o = nullptr, *att_ml = nullptr;
+    float *ssq = nullptr;                       // 2 x [H/16 units][DEC_SSQ_STRIDE] sums of squares
     // fp32 path
     float *n32 = nullptr, *q32 = nullptr, *o32 = nullptr, *u32 = nullptr;
     // row bookkeeping
@@ -113,7 +114,7 @@ namespace {
 size_t esize(hexgen_dtype_t dt) { return dt == HEXGEN_F32 ? 4 : 2; }
 
 void free_ws(Workspace &w) {
-    void *ptrs[] = {w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.n_lo, w.o_lo, w.u_lo, w.q_lo, w.att_o, w.att_ml, w.n32, w.q32, w.o32, w.u32,
+    void *ptrs[] = {w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.n_lo, w.o_lo, w.u_lo, w.q_lo, w.ssq, w.att_o, w.att_ml, w.n32, w.q32, w.o32, w.u32,
                     w.row_seq, w.row_pos, w.cu_rows, w.pos0};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
@@ -157,6 +158,9 @@ hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
         HX_TRY(dmalloc(&w.q_lo, drows * st->qw));
         HX_TRY(dmalloc(&w.att_o, drows * st->hq_l * kMaxAttnSplit * st->d));
         HX_TRY(dmalloc(&w.att_ml, drows * st->hq_l * kMaxAttnSplit * 2));
+        const size_t ssq_n = 2 * (size_t)(st->H / 16) * DEC_SSQ_STRIDE;
+        HX_TRY(dmalloc(&w.ssq, ssq_n));
+        HX_HIP(hipMemset(w.ssq, 0, ssq_n * sizeof(float)));
         // padded rows of the packed operands are read by the GEMM tiles: keep them finite
         HX_HIP(hipMemset(w.n, 0, T16 * st->H * sizeof(bf16_t)));
         HX_HIP(hipMemset(w.o, 0, T16 * st->qw * sizeof(bf16_t)));
@@ -187,7 +191,7 @@ struct Rows {
 
 // Validate the new rows against the cache and build the device row maps.
 hexgen_status_t setup_rows(hexgen_stage *st, hexgen_kv_cache *kv, const int32_t *seq_lens, int batch,
-                           hipStream_t s, Rows *out) {
+                           bool allow_decode, hipStream_t s, Rows *out) {
     if (batch <= 0) return HEXGEN_ERR_INVALID_ARG;
     if (batch > kv->max_batch) return HEXGEN_ERR_CAPACITY;
     Rows r;
@@ -202,12 +206,14 @@ hexgen_status_t setup_rows(hexgen_stage *st, hexgen_kv_cache *kv, const int32_t 
     }
     if (total > 0x3fffffff) return HEXGEN_ERR_CAPACITY;
     r.T = (int)total;
-    r.decode = (r.max_new == 1 && r.T <= kDecodeMaxRows);
+    r.decode = allow_decode && r.max_new == 1 && r.T <= kDecodeMaxRows;
     HX_TRY(ensure_workspace(st, r.T, batch));
     Workspace &w = st->ws;
     r.rm.row_seq = w.row_seq;
     r.rm.row_pos = w.row_pos;
-    if (seq_lens == nullptr && r.decode) {
+    if (r.decode && st->dtype == HEXGEN_BF16) {
+        // the decode prologue kernel publishes row positions from the committed lengths on the device
+    } else if (r.decode) {
         launch_decode_rowmap(kv->d_lens, w.row_seq, w.row_pos, batch, s);
     } else {
         // the pinned staging buffer may still feed an earlier async copy on this stream
@@ -240,86 +246,157 @@ KvGeom geom(const hexgen_stage *st, const hexgen_kv_cache *kv) {
     return g;
 }
 
-// ---- bf16 path -------------------------------------------------------------------------------
-int pick_ksplit(int n_units, int k_tiles) {
-    // enough blocks (8 waves each) to cover 256 CUs several times, but at least 4 k-tiles per wave
-    int want = (1024 + n_units - 1) / n_units;
-    int cap = std::max(1, k_tiles / 32);
-    return std::max(1, std::min(std::min(want, cap), kMaxKSplit));
-}
-
-// part <- X . W for the rows of this call; returns the number of K splits written
-int project_bf16(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xp, const bf16_t *Xlo, int N, int K,
-                 bool pair, int slot, hipStream_t s) {
-    int ks = 1;
+// ---- bf16 prefill (GEMM) flow: projections write fp32 to ws.part, small kernels finish each step ----
+void gemm_bf16(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xp, int N, int K, int slot,
+               hipStream_t s) {
     st->prof.mark(slot, s);
-    if (r.decode) {
-        ks = pick_ksplit(N / 16 / (pair ? 2 : 1), K / 32);
-        launch_gemv_mfma(static_cast<const bf16_t *>(Wp), Xp, Xlo, st->ws.part, N, K, r.T, ks, pair ? 1 : 0, s);
-    } else {
-        launch_gemm_mfma(static_cast<const bf16_t *>(Wp), Xp, st->ws.part, N, K, r.T, s);
-    }
+    launch_gemm_mfma(static_cast<const bf16_t *>(Wp), Xp, st->ws.part, N, K, r.T, s);
     st->prof.mark(slot, s);
-    return ks;
 }
 
-int pick_attn_split(const hexgen_kv_cache *kv, int batch) {
-    int mx = 0;
-    for (int i = 0; i < batch; ++i) mx = std::max(mx, kv->lens[i] + 1);
-    int n_t32 = (mx + 31) / 32;
-    return std::max(1, std::min(kMaxAttnSplit, n_t32 / 4));
-}
-
-// attention sub-layer from packed n (already normalised) to the split-K partials of W_O in ws.part
-int attn_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Rows &r, hipStream_t s) {
+// attention sub-layer from packed n (already normalised) to the W_O output in ws.part
+void attn_prefill_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Rows &r, hipStream_t s) {
     Workspace &w = st->ws;
     const Layer &ly = st->layers[layer];
     const KvGeom kg = geom(st, kv);
     bf16_t *kc = static_cast<bf16_t *>(kv->k) + (size_t)layer * kv->layer_stride;
     bf16_t *vc = static_cast<bf16_t *>(kv->v) + (size_t)layer * kv->layer_stride;
-    int ks = project_bf16(st, r, ly.wqkv, w.n, w.n_lo, st->nqkv, st->H, false, PROF_QKV, s);
+    gemm_bf16(st, r, ly.wqkv, w.n, st->nqkv, st->H, PROF_QKV, s);
     st->prof.mark(PROF_ATTN, s);
-    launch_qkv_rope_append(w.part, ks, r.T, st->hq_l, kg, r.rm, kv->cos_tab, kv->sin_tab, w.q,
-                           r.decode ? w.q_lo : nullptr, kc, vc, s);
-    if (r.decode)
-        launch_attn_decode(w.q, w.q_lo, kc, vc, kg, st->hq_l, kv->d_lens, r.batch, pick_attn_split(kv, r.batch),
-                           w.att_o, w.att_ml, w.o, w.o_lo, s);
-    else
-        launch_attn_prefill(w.q, kc, vc, kg, st->hq_l, w.cu_rows, w.pos0, r.batch, r.max_new, w.o, s);
+    launch_qkv_rope_append(w.part, 1, r.T, st->hq_l, kg, r.rm, kv->cos_tab, kv->sin_tab, w.q, nullptr, kc, vc, s);
+    launch_attn_prefill(w.q, kc, vc, kg, st->hq_l, w.cu_rows, w.pos0, r.batch, r.max_new, w.o, s);
     st->prof.mark(PROF_ATTN, s);
-    return project_bf16(st, r, ly.wo, w.o, w.o_lo, st->H, st->qw, false, PROF_WO, s);
+    gemm_bf16(st, r, ly.wo, w.o, st->H, st->qw, PROF_WO, s);
 }
 
-int ffn_bf16(hexgen_stage *st, int layer, const Rows &r, hipStream_t s) {
+void ffn_prefill_bf16(hexgen_stage *st, int layer, const Rows &r, hipStream_t s) {
     Workspace &w = st->ws;
     const Layer &ly = st->layers[layer];
-    int ks = project_bf16(st, r, ly.w13, w.n, w.n_lo, 2 * st->F_l, st->H, true, PROF_W13, s);
-    launch_reduce_swiglu(w.part, ks, w.u, r.decode ? w.u_lo : nullptr, r.T, st->F_l, s);
-    return project_bf16(st, r, ly.w2, w.u, w.u_lo, st->H, st->F_l, false, PROF_W2, s);
+    gemm_bf16(st, r, ly.w13, w.n, 2 * st->F_l, st->H, PROF_W13, s);
+    launch_reduce_swiglu(w.part, 1, w.u, nullptr, r.T, st->F_l, s);
+    gemm_bf16(st, r, ly.w2, w.u, st->H, st->F_l, PROF_W2, s);
 }
 
-hexgen_status_t forward_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
-                             void *out_partial, void *out_resid, hipStream_t s) {
+hexgen_status_t forward_prefill_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
+                                     void *out_partial, void *out_resid, hipStream_t s) {
     Workspace &w = st->ws;
-    launch_rmsnorm_pack(hidden_in, 1, w.h, st->layers[0].g_attn, w.n, r.decode ? w.n_lo : nullptr, r.T, st->H, st->eps,
-                        s);
+    launch_rmsnorm_pack(hidden_in, 1, w.h, st->layers[0].g_attn, w.n, nullptr, r.T, st->H, st->eps, s);
     for (int l = 0; l < st->L; ++l) {
         if (st->taps[l])
             HX_HIP(hipMemcpyAsync(st->taps[l], w.h, sizeof(float) * (size_t)r.T * st->H, hipMemcpyDeviceToDevice, s));
-        int ks = attn_bf16(st, kv, l, r, s);
-        launch_reduce_resid_norm(w.part, ks, w.h, st->layers[l].g_ffn, w.n, r.decode ? w.n_lo : nullptr, r.T, st->H,
-                                 st->eps, s);
-        ks = ffn_bf16(st, l, r, s);
+        attn_prefill_bf16(st, kv, l, r, s);
+        launch_reduce_resid_norm(w.part, 1, w.h, st->layers[l].g_ffn, w.n, nullptr, r.T, st->H, st->eps, s);
+        ffn_prefill_bf16(st, l, r, s);
         if (l + 1 < st->L) {
-            launch_reduce_resid_norm(w.part, ks, w.h, st->layers[l + 1].g_attn, w.n, r.decode ? w.n_lo : nullptr, r.T,
-                                     st->H, st->eps, s);
+            launch_reduce_resid_norm(w.part, 1, w.h, st->layers[l + 1].g_attn, w.n, nullptr, r.T, st->H, st->eps, s);
         } else {
-            launch_reduce_partial(w.part, ks, w.p32, r.T, st->H, s);
-            launch_store_out(w.p32, out_partial, 1, (int64_t)r.T * st->H, s);
+            launch_store_out(w.part, out_partial, 1, (int64_t)r.T * st->H, s);
             if (out_resid) launch_store_out(w.h, out_resid, 1, (int64_t)r.T * st->H, s);
         }
     }
     return HEXGEN_OK;
+}
+
+// ---- bf16 decode flow (T <= 32 rows): five kernels per layer, everything else fused into their tails ----
+int pick_attn_split(const hexgen_stage *st, const hexgen_kv_cache *kv, int batch) {
+    int mx = 0;
+    for (int i = 0; i < batch; ++i) mx = std::max(mx, kv->lens[i] + 1);
+    const int n_t32 = (mx + 31) / 32;
+    // enough (sequence, kv head) pairs or a short context: one kernel with an in-block merge
+    if (batch * st->hkv_l >= 32 || n_t32 <= 64) return 1;
+    return std::max(2, std::min(kMaxAttnSplit, n_t32 / 4));
+}
+
+DecodeEpi epi_base(hexgen_stage *st, int mode) {
+    DecodeEpi e;
+    std::memset(&e, 0, sizeof(e));
+    e.mode = mode;
+    e.norm_dim = st->H;
+    e.ssq_units = st->H / 16;
+    e.eps = st->eps;
+    return e;
+}
+
+void decode_proj(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xp, const bf16_t *Xlo, int N, int K,
+                 const DecodeEpi &e, int slot, hipStream_t s) {
+    st->prof.mark(slot, s);
+    launch_decode_proj(static_cast<const bf16_t *>(Wp), Xp, Xlo, N, K, r.T, e, s);
+    st->prof.mark(slot, s);
+}
+
+// QKV (+RoPE, cache append) and attention; leaves o (hi/lo) in the workspace
+void attn_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Rows &r, const float *ssq_in,
+                      hipStream_t s) {
+    Workspace &w = st->ws;
+    const Layer &ly = st->layers[layer];
+    const KvGeom kg = geom(st, kv);
+    bf16_t *kc = static_cast<bf16_t *>(kv->k) + (size_t)layer * kv->layer_stride;
+    bf16_t *vc = static_cast<bf16_t *>(kv->v) + (size_t)layer * kv->layer_stride;
+    DecodeEpi e = epi_base(st, DEC_QKV);
+    e.ssq_in = ssq_in;
+    e.hq_l = st->hq_l; e.kg = kg; e.row_pos = w.row_pos; e.cos_tab = kv->cos_tab; e.sin_tab = kv->sin_tab;
+    e.q_hi = w.q; e.q_lo = w.q_lo; e.kc = kc; e.vc = vc;
+    decode_proj(st, r, ly.wqkv, w.n, w.n_lo, st->nqkv, st->H, e, PROF_QKV, s);
+    st->prof.mark(PROF_ATTN, s);
+    launch_attn_decode(w.q, w.q_lo, kc, vc, kg, st->hq_l, w.row_pos, r.batch, pick_attn_split(st, kv, r.batch), w.att_o,
+                       w.att_ml, w.o, w.o_lo, s);
+    st->prof.mark(PROF_ATTN, s);
+}
+
+hexgen_status_t forward_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
+                                    void *out_partial, void *out_resid, hipStream_t s) {
+    Workspace &w = st->ws;
+    float *ssq_a = w.ssq, *ssq_f = w.ssq + (size_t)(st->H / 16) * DEC_SSQ_STRIDE;
+    launch_decode_prologue(hidden_in, 1, w.h, st->layers[0].g_attn, w.n, w.n_lo, ssq_a, r.T, st->H, kv->d_lens,
+                           w.row_pos, 1, s);
+    for (int l = 0; l < st->L; ++l) {
+        const Layer &ly = st->layers[l];
+        const bool last = l + 1 == st->L;
+        if (st->taps[l])
+            HX_HIP(hipMemcpyAsync(st->taps[l], w.h, sizeof(float) * (size_t)r.T * st->H, hipMemcpyDeviceToDevice, s));
+        attn_decode_bf16(st, kv, l, r, ssq_a, s);
+        DecodeEpi e = epi_base(st, DEC_RESID);
+        e.h = w.h; e.g_next = ly.g_ffn; e.hg_hi = w.n; e.hg_lo = w.n_lo; e.ssq_out = ssq_f;
+        decode_proj(st, r, ly.wo, w.o, w.o_lo, st->H, st->qw, e, PROF_WO, s);
+        e = epi_base(st, DEC_SWIGLU);
+        e.ssq_in = ssq_f; e.u_hi = w.u; e.u_lo = w.u_lo; e.F_l = st->F_l;
+        decode_proj(st, r, ly.w13, w.n, w.n_lo, 2 * st->F_l, st->H, e, PROF_W13, s);
+        e = epi_base(st, DEC_RESID);
+        e.h = w.h; e.hg_hi = w.n; e.hg_lo = w.n_lo; e.ssq_out = ssq_a;
+        e.g_next = last ? nullptr : st->layers[l + 1].g_attn;
+        e.last_layer = last ? 1 : 0;
+        e.out_partial = static_cast<bf16_t *>(out_partial);
+        e.out_resid = static_cast<bf16_t *>(out_resid);
+        decode_proj(st, r, ly.w2, w.u, w.u_lo, st->H, st->F_l, e, PROF_W2, s);
+    }
+    return HEXGEN_OK;
+}
+
+// one sub-layer for the validation surface, decode kernels; h fp32 in, raw fp32 partial out
+void sublayer_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, int which, const Rows &r, const float *h,
+                          float *p_out, hipStream_t s) {
+    Workspace &w = st->ws;
+    const Layer &ly = st->layers[layer];
+    float *ssq = w.ssq;
+    DecodeEpi e = epi_base(st, DEC_RAW);
+    e.raw_out = p_out;
+    if (which == 0) {
+        launch_decode_prologue(h, 0, nullptr, ly.g_attn, w.n, w.n_lo, ssq, r.T, st->H, kv->d_lens, w.row_pos, 0, s);
+        attn_decode_bf16(st, kv, layer, r, ssq, s);
+        decode_proj(st, r, ly.wo, w.o, w.o_lo, st->H, st->qw, e, PROF_WO, s);
+    } else {
+        launch_decode_prologue(h, 0, nullptr, ly.g_ffn, w.n, w.n_lo, ssq, r.T, st->H, nullptr, nullptr, 0, s);
+        DecodeEpi g = epi_base(st, DEC_SWIGLU);
+        g.ssq_in = ssq; g.u_hi = w.u; g.u_lo = w.u_lo; g.F_l = st->F_l;
+        decode_proj(st, r, ly.w13, w.n, w.n_lo, 2 * st->F_l, st->H, g, PROF_W13, s);
+        decode_proj(st, r, ly.w2, w.u, w.u_lo, st->H, st->F_l, e, PROF_W2, s);
+    }
+}
+
+hexgen_status_t forward_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
+                             void *out_partial, void *out_resid, hipStream_t s) {
+    if (r.decode) return forward_decode_bf16(st, kv, r, hidden_in, out_partial, out_resid, s);
+    return forward_prefill_bf16(st, kv, r, hidden_in, out_partial, out_resid, s);
 }
 
 // ---- fp32 path -------------------------------------------------------------------------------
@@ -516,26 +593,26 @@ hexgen_status_t hexgen_stage_load_layer(hexgen_stage_t *st, int layer, const voi
         bf16_t *tmp = nullptr;
         HX_TRY(dmalloc(&tmp, tmp_elems));
         hexgen_status_t rc = HEXGEN_OK;
-        auto col_shard = [&](const void *src, int c0, int gcols, int cols, void *dst, int tile0, int stride) {
+        auto col_shard = [&](const void *src, int c0, int gcols, int cols, void *dst, int tile0, int stride, int rope_d) {
             if (rc != HEXGEN_OK) return;
             hipError_t e = hipMemcpy2D(tmp, cbytes(cols), src_at(src, 0, c0, gcols), cbytes(gcols), cbytes(cols), H,
                                        hipMemcpyDefault);
             if (e != hipSuccess) { rc = HEXGEN_ERR_DEVICE; return; }
-            launch_pack_weight(tmp, cols, 0, 0, H, cols, static_cast<bf16_t *>(dst), tile0, stride, nullptr);
+            launch_pack_weight(tmp, cols, 0, 0, H, cols, static_cast<bf16_t *>(dst), tile0, stride, rope_d, nullptr);
             if (hipDeviceSynchronize() != hipSuccess) rc = HEXGEN_ERR_DEVICE;
         };
         auto row_shard = [&](const void *src, int r0, int rows, void *dst) {
             if (rc != HEXGEN_OK) return;
             hipError_t e = hipMemcpy(tmp, src_at(src, r0, 0, H), (size_t)rows * H * es, hipMemcpyDefault);
             if (e != hipSuccess) { rc = HEXGEN_ERR_DEVICE; return; }
-            launch_pack_weight(tmp, H, 0, 0, rows, H, static_cast<bf16_t *>(dst), 0, 1, nullptr);
+            launch_pack_weight(tmp, H, 0, 0, rows, H, static_cast<bf16_t *>(dst), 0, 1, 0, nullptr);
             if (hipDeviceSynchronize() != hipSuccess) rc = HEXGEN_ERR_DEVICE;
         };
-        col_shard(wq, q0, qcols, st->qw, ly.wqkv, 0, 1);
-        col_shard(wk, k0, kcols, kw, ly.wqkv, st->qw / 16, 1);
-        col_shard(wv, k0, kcols, kw, ly.wqkv, (st->qw + kw) / 16, 1);
-        col_shard(w1, f0, st->F, st->F_l, ly.w13, 0, 2);     // gate tiles at even positions
-        col_shard(w3, f0, st->F, st->F_l, ly.w13, 1, 2);     // up tiles at odd positions
+        col_shard(wq, q0, qcols, st->qw, ly.wqkv, 0, 1, d);        // q, k, v tiles hold rotary pairs
+        col_shard(wk, k0, kcols, kw, ly.wqkv, st->qw / 16, 1, d);
+        col_shard(wv, k0, kcols, kw, ly.wqkv, (st->qw + kw) / 16, 1, d);
+        col_shard(w1, f0, st->F, st->F_l, ly.w13, 0, 2, 0);  // gate tiles at even positions
+        col_shard(w3, f0, st->F, st->F_l, ly.w13, 1, 2, 0);  // up tiles at odd positions
         row_shard(wo, q0, st->qw, ly.wo);
         row_shard(w2, f0, st->F_l, ly.w2);
         (void)hipFree(tmp);
@@ -710,8 +787,7 @@ hexgen_status_t hexgen_stage_prefill(hexgen_stage_t *st, hexgen_kv_cache_t *kv, 
     hipStream_t s = static_cast<hipStream_t>(stream);
     HX_TRY(hexgen_kv_cache_reset(kv));
     Rows r;
-    HX_TRY(setup_rows(st, kv, seq_lens, batch, s, &r));
-    r.decode = false;                       // a prefill always takes the GEMM path
+    HX_TRY(setup_rows(st, kv, seq_lens, batch, false, s, &r));      // a prefill always takes the GEMM path
     st->prof.mark(PROF_CALL, s);
     if (st->dtype == HEXGEN_BF16) HX_TRY(forward_bf16(st, kv, r, hidden_in, out_partial, out_resid, s));
     else HX_TRY(forward_f32(st, kv, r, hidden_in, out_partial, out_resid, s));
@@ -734,11 +810,11 @@ hexgen_status_t hexgen_stage_decode(hexgen_stage_t *st, hexgen_kv_cache_t *kv, i
     if (!kv->prefilled || kv->batch <= 0 || step != kv->steps) return HEXGEN_ERR_STATE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     Rows r;
-    HX_TRY(setup_rows(st, kv, nullptr, kv->batch, s, &r));
+    HX_TRY(setup_rows(st, kv, nullptr, kv->batch, true, s, &r));
     st->prof.mark(PROF_CALL, s);
     if (st->dtype == HEXGEN_BF16) HX_TRY(forward_bf16(st, kv, r, hidden_in, out_partial, out_resid, s));
     else HX_TRY(forward_f32(st, kv, r, hidden_in, out_partial, out_resid, s));
-    launch_advance_lens(kv->d_lens, kv->batch, s);
+    if (!r.decode || st->dtype != HEXGEN_BF16) launch_advance_lens(kv->d_lens, kv->batch, s);   // else: the prologue did
     st->prof.mark(PROF_CALL, s);
     for (int i = 0; i < kv->batch; ++i) kv->lens[i] += 1;
     kv->steps += 1;
@@ -754,16 +830,20 @@ hexgen_status_t hexgen_stage_run_sublayer(hexgen_stage_t *st, hexgen_kv_cache_t 
     if (!st->layers[layer].loaded) return HEXGEN_ERR_STATE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     Rows r;
-    HX_TRY(setup_rows(st, kv, seq_lens, batch, s, &r));
+    HX_TRY(setup_rows(st, kv, seq_lens, batch, true, s, &r));
     const float *h = static_cast<const float *>(h_in);
     float *p = static_cast<float *>(partial_out);
     Workspace &w = st->ws;
     if (st->dtype == HEXGEN_BF16) {
-        const Layer &ly = st->layers[layer];
-        launch_rmsnorm_pack(h, 0, nullptr, which == 0 ? ly.g_attn : ly.g_ffn, w.n, r.decode ? w.n_lo : nullptr, r.T, st->H,
-                            st->eps, s);
-        const int ks = which == 0 ? attn_bf16(st, kv, layer, r, s) : ffn_bf16(st, layer, r, s);
-        launch_reduce_partial(w.part, ks, p, r.T, st->H, s);
+        if (r.decode) {
+            sublayer_decode_bf16(st, kv, layer, which, r, h, p, s);
+        } else {
+            const Layer &ly = st->layers[layer];
+            launch_rmsnorm_pack(h, 0, nullptr, which == 0 ? ly.g_attn : ly.g_ffn, w.n, nullptr, r.T, st->H, st->eps, s);
+            if (which == 0) attn_prefill_bf16(st, kv, layer, r, s);
+            else ffn_prefill_bf16(st, layer, r, s);
+            HX_HIP(hipMemcpyAsync(p, w.part, sizeof(float) * (size_t)r.T * st->H, hipMemcpyDeviceToDevice, s));
+        }
     } else {
         if (which == 0) attn_f32(st, kv, layer, r, h, p, s);
         else ffn_f32(st, layer, r, h, p, s);

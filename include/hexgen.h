@@ -157,6 +157,13 @@ hexgen_status_t hexgen_stage_set_tap(hexgen_stage_t *st, int layer, void *h_dump
 hexgen_status_t hexgen_stage_profile_enable(hexgen_stage_t *st, int on);
 hexgen_status_t hexgen_stage_profile_read(hexgen_stage_t *st, int slot, double *total_ms, int64_t *count);
 
+/* HBM calibration kernels of known size (used by the benchmark and to scale profiler byte counters):
+ * copy moves `bytes` (multiple of 16) from src to dst; read streams `bytes` from src and writes at most one
+ * float per block to `sink` (device, >= blocks floats).  `blocks` = grid size (256-thread blocks).
+ */
+hexgen_status_t hexgen_stream_copy(void *dst, const void *src, int64_t bytes, int blocks, void *stream);
+hexgen_status_t hexgen_stream_read(const void *src, void *sink, int64_t bytes, int blocks, void *stream);
+
 /* Bytes of device memory the stage holds for weights (after repacking), for reporting. */
 int64_t hexgen_stage_weight_bytes(const hexgen_stage_t *st);
 

@@ -42,6 +42,8 @@ SIGNATURES = {
     "hexgen_kv_cache_get_lengths": (_i, [_vp, _ip, _i]),
     "hexgen_stage_set_tap": (_i, [_vp, _i, _vp]),
     "hexgen_stage_weight_bytes": (_i64, [_vp]),
+    "hexgen_stream_copy": (_i, [_vp, _vp, _i64, _i, _vp]),
+    "hexgen_stream_read": (_i, [_vp, _vp, _i64, _i, _vp]),
     "hexgen_stage_profile_enable": (_i, [_vp, _i]),
     "hexgen_stage_profile_read": (_i, [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64)]),
 }
@@ -204,6 +206,16 @@ class KVCache:
         _check(lib.hexgen_kv_cache_read(self.handle, layer, seq, pos0, n, C.cast(k.data_ptr(), _fp),
                                         C.cast(v.data_ptr(), _fp)), "hexgen_kv_cache_read")
         return k, v
+
+
+def stream_copy(dst: torch.Tensor, src: torch.Tensor, blocks: int = 4096, stream=None):
+    nbytes = src.numel() * src.element_size()
+    _check(lib.hexgen_stream_copy(_ptr(dst), _ptr(src), nbytes, blocks, _stream_handle(stream)), "hexgen_stream_copy")
+
+
+def stream_read(src: torch.Tensor, sink: torch.Tensor, blocks: int = 4096, stream=None):
+    nbytes = src.numel() * src.element_size()
+    _check(lib.hexgen_stream_read(_ptr(src), _ptr(sink), nbytes, blocks, _stream_handle(stream)), "hexgen_stream_read")
 
 
 def accumulate_f32(dst: torch.Tensor, src: torch.Tensor, stream=None):

@@ -4,8 +4,9 @@
 // the activations this library produces for its own GEMMs -- is stored so that one
 // v_mfma_f32_16x16x32_bf16 operand is a single contiguous 1 KB block: a matrix M[idx][k]
 // (idx = output feature for weights, token row for activations; k = contraction index) is cut into
-// tiles of 16 idx x 32 k, tile (it, kt) lives at ((it * k_tiles + kt) * 64 + lane) * 8 elements and
-// lane l holds idx = l % 16, k = 8 * (l / 16) + j, j = 0..7.  A wave fetches an operand with one
+// tiles of 16 idx x 32 k; inside a tile lane l holds idx = l % 16, k = 8 * (l / 16) + j, j = 0..7.
+// Activation tiles are ordered row-tile-major, ((it * k_tiles + kt) * 64 + lane) * 8 (frag_offset below);
+// weight tiles k-tile-major, ((kt * n_tiles + it) * 64 + lane) * 8.  A wave fetches an operand with one
 // coalesced 128-bit load per lane, from HBM or from LDS, with no transposition anywhere.
 // Both MFMA inputs use this same mapping, so any k-ordering inside a tile cancels in the product.
 #pragma once
@@ -17,6 +18,13 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 typedef uint16_t bf16_t;   // raw storage
 
 #define HX_WAVE 64
+
+// Decode activations (at most 32 token rows) use a compact token-major layout instead: per token and
+// k-tile one 128-byte line holding the 32 hi values then the 32 lo values of the hi + lo bf16 split.
+// A decode projection then touches one cache line per (token, k-tile) instead of eight.
+__host__ __device__ inline size_t dec_act_offset(int token, int k, int k_tiles, int plane) {
+    return (((size_t)token * k_tiles + (k >> 5)) * 2 + plane) * 32 + (k & 31);
+}
 
 __host__ __device__ inline size_t frag_offset(int idx, int k, int k_tiles) {
     int it = idx >> 4, kt = k >> 5;

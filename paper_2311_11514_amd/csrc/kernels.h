@@ -22,18 +22,25 @@ struct KvGeom {
 };
 
 // ---- layout / utility (kernels_layout.hip) -------------------------------------------------
+// Weights are packed k-tile-major: tile (kt, nt) of a matrix with dst_n_tiles feature tiles sits at
+// ((kt * dst_n_tiles + nt) * 64 + lane) * 8 elements.  All blocks of a projection walk kt together, so at
+// any moment the chip streams one contiguous window of HBM instead of hundreds of scattered slabs.
 // dst tile (dst_tile0 + nt * dst_tile_stride) <- src[k0 + k][c0 + nt*16 + i], src row-major with
 // leading dimension ld (elements), K % 32 == 0, N % 16 == 0.
 // rope_d > 0 (fused QKV weight): columns are heads of width rope_d; each 16-row tile of a head holds 8
 // rotary pairs (rows 0-7 = head columns 8*tl .. 8*tl+7, rows 8-15 = those + rope_d/2), so one MFMA tile is
 // self-contained for RoPE.  The QKV projection output is in this permuted column order.
 void launch_pack_weight(const bf16_t *src, int64_t ld, int k0, int c0, int K, int N, bf16_t *dst,
-                        int dst_tile0, int dst_tile_stride, int rope_d, hipStream_t s);
+                        int dst_tile0, int dst_tile_stride, int dst_n_tiles, int rope_d, hipStream_t s);
 void launch_cvt_bf16_to_f32(const bf16_t *src, float *dst, int64_t n, hipStream_t s);
 void launch_accumulate_f32(float *dst, const float *src, int64_t n, hipStream_t s);
 // decode row map: row i -> (seq i, pos lens[i])
 void launch_decode_rowmap(const int32_t *lens, int32_t *row_seq, int32_t *row_pos, int b, hipStream_t s);
 void launch_advance_lens(int32_t *lens, int b, hipStream_t s);
+
+// plain streaming kernels of known size (HBM calibration for the benchmarks and profiler counters)
+void launch_stream_copy(const void *src, void *dst, int64_t bytes, int blocks, hipStream_t s);
+void launch_stream_read(const void *src, float *sink, int64_t bytes, int blocks, hipStream_t s);
 
 // ---- bf16 path (kernels_bf16_*.hip) ---------------------------------------------------------
 
@@ -64,22 +71,21 @@ struct DecodeEpi {
     // RESID
     float *h;                  // residual stream [T][N] fp32, updated in place
     const float *g_next;       // gain of the next RMSNorm
-    bf16_t *hg_hi, *hg_lo;     // (h * g_next) as hi/lo operand planes
+    bf16_t *hg;                // (h * g_next) as compact hi/lo decode operand (dec_act_offset)
     float *ssq_out;
     int last_layer;            // 1: write out_partial / out_resid (bf16 [T][N]) instead of updating h
     bf16_t *out_partial, *out_resid;
     // SWIGLU
-    bf16_t *u_hi, *u_lo;
+    bf16_t *u;                 // compact hi/lo decode operand [T][F_l]
     int F_l;
 };
-// Wp . (Xp + Xlo) for T <= 32 rows, one block per output unit, then the epilogue of e.mode
-void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xp, const bf16_t *Xlo, int N, int K, int T,
-                        const DecodeEpi &e, hipStream_t s);
+// Wp . Xa for T <= 32 rows (Xa: compact hi/lo operand [T][K]), one block per output unit, then the
+// epilogue of e.mode
+void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T, const DecodeEpi &e, hipStream_t s);
 // stage input rows -> h (optional), (x * g) hi/lo planes, sums of squares; block 0 publishes row
 // positions from the committed lengths and optionally advances them
-void launch_decode_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg_hi,
-                            bf16_t *hg_lo, float *ssq_out, int T, int H, int32_t *lens, int32_t *row_pos,
-                            int advance, hipStream_t s);
+void launch_decode_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg, float *ssq_out,
+                            int T, int H, int32_t *lens, int32_t *row_pos, int advance, hipStream_t s);
 // same contraction for many rows (prefill): out[t][n] fp32 row-major
 void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, int K, int T, hipStream_t s);
 
@@ -99,9 +105,10 @@ void launch_reduce_swiglu(const float *part, int ksplit, bf16_t *u_packed, bf16_
 
 // decode attention: one new row per sequence; split-KV partials then merge into packed o
 // row_pos[seq] = position of the new row (= cached context length)
+// o_act: compact hi/lo decode operand [b][hq_l*d] of the W_O projection
 void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, const bf16_t *vc, KvGeom kg,
                         int hq_l, const int32_t *row_pos, int b, int nsplit, float *part_o, float *part_ml,
-                        bf16_t *o_packed, bf16_t *o_lo, hipStream_t s);
+                        bf16_t *o_act, hipStream_t s);
 // prefill attention over packed ragged rows; K, V are read from the cache
 void launch_attn_prefill(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,
                          const int32_t *cu_rows, const int32_t *pos0, int batch, int max_new,

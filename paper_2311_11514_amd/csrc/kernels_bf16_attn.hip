@@ -111,8 +111,7 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(const bf16_t *__restric
 // grid (b, hq_l), block D threads: log-sum-exp merge in split order -> packed bf16 o
 template <int D>
 __global__ void attn_decode_merge_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
-                                         int hq_l, int nsplit, bf16_t *__restrict__ o_packed,
-                                         bf16_t *__restrict__ o_lo) {
+                                         int hq_l, int nsplit, bf16_t *__restrict__ o_act) {
     const int sq = blockIdx.x, head = blockIdx.y, dd = threadIdx.x;
     const size_t e0 = ((size_t)sq * hq_l + head) * nsplit;
     float M = NEG_INF;
@@ -126,9 +125,9 @@ __global__ void attn_decode_merge_kernel(const float *__restrict__ part_o, const
     }
     bf16_t hi, lo;
     split_bf16(o / L, hi, lo);
-    const size_t off = frag_offset(sq, head * D + dd, (hq_l * D) >> 5);
-    o_packed[off] = hi;
-    o_lo[off] = lo;
+    const size_t off = dec_act_offset(sq, head * D + dd, (hq_l * D) >> 5, 0);
+    o_act[off] = hi;
+    o_act[off + 32] = lo;
 }
 
 // Single-kernel variant: one 8-wave block per (sequence, kv head); the waves interleave over the
@@ -140,8 +139,7 @@ __global__ __launch_bounds__(512) void attn_decode_block_kernel(const bf16_t *__
                                                                const bf16_t *__restrict__ kc,
                                                                const bf16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
                                                                const int32_t *__restrict__ row_pos,
-                                                               bf16_t *__restrict__ o_packed,
-                                                               bf16_t *__restrict__ o_lo, float scale_log2e) {
+                                                               bf16_t *__restrict__ o_act, float scale_log2e) {
     constexpr int KT = D / 32, DT = D / 16, W = 8;
     __shared__ float s_m[W][16], s_l[W][16];
     __shared__ float s_o[W][16][D];
@@ -241,25 +239,25 @@ __global__ __launch_bounds__(512) void attn_decode_block_kernel(const bf16_t *__
         uint2 ph, pl;
         split_pack2(o[0] * inv, o[1] * inv, ph.x, pl.x);
         split_pack2(o[2] * inv, o[3] * inv, ph.y, pl.y);
-        const size_t off = frag_offset(sq, (c * G + hh) * D + dd, k_tiles);
-        *reinterpret_cast<uint2 *>(o_packed + off) = ph;
-        *reinterpret_cast<uint2 *>(o_lo + off) = pl;
+        const size_t off = dec_act_offset(sq, (c * G + hh) * D + dd, k_tiles, 0);
+        *reinterpret_cast<uint2 *>(o_act + off) = ph;
+        *reinterpret_cast<uint2 *>(o_act + off + 32) = pl;
     }
 }
 
 void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, const bf16_t *vc, KvGeom kg,
                         int hq_l, const int32_t *row_pos, int b, int nsplit, float *part_o, float *part_ml,
-                        bf16_t *o_packed, bf16_t *o_lo, hipStream_t s) {
+                        bf16_t *o_act, hipStream_t s) {
     const int G = hq_l / kg.hkv_l;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)kg.d);
     if (nsplit <= 1) {       // single kernel, LDS merge
         dim3 grid(kg.hkv_l, b);
         if (kg.d == 128)
             hipLaunchKernelGGL(attn_decode_block_kernel<128>, grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G,
-                               row_pos, o_packed, o_lo, scale_log2e);
+                               row_pos, o_act, scale_log2e);
         else
             hipLaunchKernelGGL(attn_decode_block_kernel<64>, grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G,
-                               row_pos, o_packed, o_lo, scale_log2e);
+                               row_pos, o_act, scale_log2e);
         return;
     }
     dim3 grid(nsplit, kg.hkv_l, b);
@@ -267,12 +265,12 @@ void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, c
         hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(64), 0, s, q, q_lo, kc, vc, kg, hq_l, G, row_pos, nsplit,
                            part_o, part_ml, scale_log2e);
         hipLaunchKernelGGL(attn_decode_merge_kernel<128>, dim3(b, hq_l), dim3(128), 0, s, part_o, part_ml, hq_l,
-                           nsplit, o_packed, o_lo);
+                           nsplit, o_act);
     } else {
         hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(64), 0, s, q, q_lo, kc, vc, kg, hq_l, G, row_pos, nsplit,
                            part_o, part_ml, scale_log2e);
         hipLaunchKernelGGL(attn_decode_merge_kernel<64>, dim3(b, hq_l), dim3(64), 0, s, part_o, part_ml, hq_l, nsplit,
-                           o_packed, o_lo);
+                           o_act);
     }
 }
 

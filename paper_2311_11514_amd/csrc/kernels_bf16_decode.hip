@@ -11,12 +11,15 @@
 // consecutive features):
 //   QKV    : x rstd of the input rows, RoPE, q -> hi/lo rows, k / v -> KV cache.  The QKV weight tiles are
 //            packed so that a tile holds 8 rotary pairs (features i and i + d/2), which lie 32 lanes apart.
-//   RESID  : h += partial; (h * gain of the next norm) -> hi/lo operand of the next projection;
+//   RESID  : h += partial; (h * gain of the next norm) -> hi/lo operand of the next projection (compact
+//            token-major layout, see dec_act_offset);
 //            per-unit sum of squares of the new h, from which the next kernel derives rstd
 //   SWIGLU : x rstd, silu(gate) * up -> hi/lo operand of the W2 projection (gate / up tiles interleaved)
 //   RAW    : x rstd (if the input is a normalised stream), plain fp32 partial (validation surface)
 // RMSNorm is thus never a kernel of its own in decode: y = rstd * ((h*g) . W), with rstd a per-row
 // scalar applied after the contraction.
+#include <cstdlib>
+
 #include "kernels.h"
 #include "kvlayout.h"
 
@@ -42,14 +45,25 @@ __device__ inline void store_split4(const float x[4], bf16_t *hi, bf16_t *lo, si
     *reinterpret_cast<uint2 *>(hi + off) = o;
     *reinterpret_cast<uint2 *>(lo + off) = ol;
 }
+// 4 consecutive features k..k+3 of one token into a compact decode operand (hi and lo planes)
+__device__ inline void store_act4(const float x[4], bf16_t *xa, int token, int k, int k_tiles) {
+    const size_t off = dec_act_offset(token, k, k_tiles, 0);
+    uint2 o, ol;
+    split_pack2(x[0], x[1], o.x, ol.x);
+    split_pack2(x[2], x[3], o.y, ol.y);
+    *reinterpret_cast<uint2 *>(xa + off) = o;
+    *reinterpret_cast<uint2 *>(xa + off + 32) = ol;
+}
 
-template <int NB, int UT, int WAVES, int UNROLL, int MODE>
+// XLDS: the whole activation operand (T <= 2 rows) is staged once per block in LDS, so the main loop
+// issues nothing but weight loads; otherwise each lane fetches its 16-byte pieces per k-tile (L2 hits).
+template <int NB, int UT, int WAVES, int UNROLL, int MODE, bool XLDS>
 __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *__restrict__ Wp,
-                                                                const bf16_t *__restrict__ Xp,
-                                                                const bf16_t *__restrict__ Xlo, int N, int k_tiles,
+                                                                const bf16_t *__restrict__ Xa, int N, int k_tiles,
                                                                 int T, DecodeEpi e) {
     __shared__ floatx4 red[WAVES][UT * NB][64];
     __shared__ float s_rstd[32];
+    extern __shared__ bf16x8 xs[];          // XLDS: copy of Xa, [token][k_tile][plane][lane group]
     const int unit = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 
@@ -62,35 +76,51 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
     const bf16x8 *wp[UT];
 #pragma unroll
     for (int u = 0; u < UT; ++u)
-        wp[u] = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)(unit * UT + u) * k_tiles * 64 + lane;
-    const bf16x8 *xp[NB], *xl[NB];
+        wp[u] = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)(unit * UT + u) * 64 + lane;
+    const size_t kstride = (size_t)(N >> 4) * 64;          // k-tile-major weights: one k-tile of all features
+    // operand B of lane (token j, group g) for k-tile kt: hi at x[b][kt * 8], lo at x[b][kt * 8 + 4]
+    const bf16x8 *xg[NB];
     bool xv[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-        xp[b] = reinterpret_cast<const bf16x8 *>(Xp) + (size_t)b * k_tiles * 64 + lane;
-        xl[b] = reinterpret_cast<const bf16x8 *>(Xlo) + (size_t)b * k_tiles * 64 + lane;
-        xv[b] = (lane & 15) + 16 * b < T;
+        const int token = (lane & 15) + 16 * b;
+        xv[b] = token < T;
+        xg[b] = (XLDS ? xs : reinterpret_cast<const bf16x8 *>(Xa)) + (size_t)(xv[b] ? token : 0) * k_tiles * 8 + (lane >> 4);
     }
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (XLDS) {
+        const int n16 = T * k_tiles * 8;
+        for (int idx = threadIdx.x; idx < n16; idx += WAVES * 64) xs[idx] = reinterpret_cast<const bf16x8 *>(Xa)[idx];
+        __syncthreads();
+    }
 
     int kt = wave;
     for (; kt + (UNROLL - 1) * WAVES < k_tiles; kt += UNROLL * WAVES) {
         bf16x8 a[UNROLL][UT];
 #pragma unroll
-        for (int i = 0; i < UNROLL; ++i) {
-            const size_t o = (size_t)(kt + i * WAVES) * 64;
+        for (int i = 0; i < UNROLL; ++i)
 #pragma unroll
-            for (int u = 0; u < UT; ++u) a[i][u] = __builtin_nontemporal_load(wp[u] + o);
-        }
-        {
+            for (int u = 0; u < UT; ++u) a[i][u] = __builtin_nontemporal_load(wp[u] + (size_t)(kt + i * WAVES) * kstride);
+        if (XLDS) {
+#pragma unroll
+            for (int i = 0; i < UNROLL; ++i) {
+                const int o = (kt + i * WAVES) * 8;
+                const bf16x8 x = xv[0] ? xg[0][o] : zero, y = xv[0] ? xg[0][o + 4] : zero;
+#pragma unroll
+                for (int u = 0; u < UT; ++u) {
+                    acc[u][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], y, acc[u][0], 0, 0, 0);
+                    acc[u][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], x, acc[u][0], 0, 0, 0);
+                }
+            }
+        } else {
             bf16x8 x[UNROLL][NB], y[UNROLL][NB];
 #pragma unroll
             for (int i = 0; i < UNROLL; ++i) {
-                const size_t o = (size_t)(kt + i * WAVES) * 64;
+                const int o = (kt + i * WAVES) * 8;
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
-                    x[i][b] = xv[b] ? xp[b][o] : zero;
-                    y[i][b] = xv[b] ? xl[b][o] : zero;
+                    x[i][b] = xv[b] ? xg[b][o] : zero;
+                    y[i][b] = xv[b] ? xg[b][o + 4] : zero;
                 }
             }
 #pragma unroll
@@ -105,14 +135,13 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
         }
     }
     for (; kt < k_tiles; kt += WAVES) {
-        const size_t o = (size_t)kt * 64;
 #pragma unroll
         for (int u = 0; u < UT; ++u) {
-            bf16x8 a = __builtin_nontemporal_load(wp[u] + o);
+            bf16x8 a = __builtin_nontemporal_load(wp[u] + (size_t)kt * kstride);
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const bf16x8 x = xv[b] ? xp[b][o] : zero;
-                const bf16x8 y = xv[b] ? xl[b][o] : zero;
+                const bf16x8 x = xv[b] ? xg[b][kt * 8] : zero;
+                const bf16x8 y = xv[b] ? xg[b][kt * 8 + 4] : zero;
                 acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, y, acc[u][b], 0, 0, 0);
                 acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, x, acc[u][b], 0, 0, 0);
             }
@@ -164,7 +193,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
                 *reinterpret_cast<floatx4 *>(e.h + (size_t)token * N + n0) = hn;
                 const floatx4 g4 = *reinterpret_cast<const floatx4 *>(e.g_next + n0);
                 const float x[4] = {hn[0] * g4[0], hn[1] * g4[1], hn[2] * g4[2], hn[3] * g4[3]};
-                store_split4(x, e.hg_hi, e.hg_lo, frag_offset(token, n0, N >> 5));
+                store_act4(x, e.hg, token, n0, N >> 5);
                 ss = hn[0] * hn[0] + hn[1] * hn[1] + hn[2] * hn[2] + hn[3] * hn[3];
             }
         }
@@ -183,7 +212,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
                 const float aa = v[0][j] * r;
                 uu[j] = aa / (1.0f + __expf(-aa)) * (v[UT - 1][j] * r);
             }
-            store_split4(uu, e.u_hi, e.u_lo, frag_offset(token, f0, e.F_l >> 5));
+            store_act4(uu, e.u, token, f0, e.F_l >> 5);
         }
     } else {   // DEC_QKV
         const int d = e.kg.d, half = d >> 1, tiles_per_head = d >> 4;
@@ -227,26 +256,43 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
     }
 }
 
-void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xp, const bf16_t *Xlo, int N, int K, int T,
-                        const DecodeEpi &e, hipStream_t s) {
-    const int k_tiles = K / 32, n_tiles = N / 16;
+namespace {
+constexpr int kXldsMaxBytes = 64 * 1024;      // activation operand staged in LDS up to this size
+
+template <int NB, int UT, int UNR, int MODE, bool XLDS>
+void launch_one(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, hipStream_t s) {
     constexpr int WAVES = 8;
-#define HX_DEC(NB, UT, UNR, MODE)                                                                              \
-    hipLaunchKernelGGL((decode_proj_kernel<NB, UT, WAVES, UNR, MODE>), dim3(n_tiles / UT), dim3(WAVES * 64), 0, \
-                       s, Wp, Xp, Xlo, N, k_tiles, T, e)
-#define HX_DEC_NB(UT, UNR, MODE)                          \
-    do {                                                  \
-        if (T <= 16) HX_DEC(1, UT, UNR, MODE);            \
-        else HX_DEC(2, UT, UNR, MODE);                    \
-    } while (0)
-    switch (e.mode) {
-        case DEC_RAW: HX_DEC_NB(1, 8, DEC_RAW); break;
-        case DEC_QKV: HX_DEC_NB(1, 8, DEC_QKV); break;
-        case DEC_RESID: HX_DEC_NB(1, 8, DEC_RESID); break;
-        case DEC_SWIGLU: HX_DEC_NB(2, 4, DEC_SWIGLU); break;
+    auto kern = decode_proj_kernel<NB, UT, WAVES, UNR, MODE, XLDS>;
+    size_t dyn = 0;
+    if (XLDS) {
+        dyn = (size_t)T * k_tiles * 8 * sizeof(bf16x8);
+        static bool raised = false;       // static + dynamic LDS may exceed the default 64 KB per block
+        if (!raised) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      kXldsMaxBytes);
+            raised = true;
+        }
     }
-#undef HX_DEC_NB
-#undef HX_DEC
+    hipLaunchKernelGGL(kern, dim3(N / 16 / UT), dim3(WAVES * 64), dyn, s, Wp, Xa, N, k_tiles, T, e);
+}
+
+template <int UT, int MODE>
+void launch_mode(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, hipStream_t s) {
+    const size_t xbytes = (size_t)T * k_tiles * 8 * sizeof(bf16x8);
+    if (T <= 2 && xbytes <= (size_t)kXldsMaxBytes) launch_one<1, UT, 8 / UT, MODE, true>(Wp, Xa, N, k_tiles, T, e, s);
+    else if (T <= 16) launch_one<1, UT, 8 / UT, MODE, false>(Wp, Xa, N, k_tiles, T, e, s);
+    else launch_one<2, UT, 8 / UT, MODE, false>(Wp, Xa, N, k_tiles, T, e, s);
+}
+}  // namespace
+
+void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T, const DecodeEpi &e, hipStream_t s) {
+    const int k_tiles = K / 32;
+    switch (e.mode) {
+        case DEC_RAW: launch_mode<1, DEC_RAW>(Wp, Xa, N, k_tiles, T, e, s); break;
+        case DEC_QKV: launch_mode<1, DEC_QKV>(Wp, Xa, N, k_tiles, T, e, s); break;
+        case DEC_RESID: launch_mode<1, DEC_RESID>(Wp, Xa, N, k_tiles, T, e, s); break;
+        case DEC_SWIGLU: launch_mode<2, DEC_SWIGLU>(Wp, Xa, N, k_tiles, T, e, s); break;
+    }
 }
 
 // -------------------------------------------------------------------------------------------------
@@ -258,8 +304,8 @@ void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xp, const bf16_t *Xlo, i
 // -------------------------------------------------------------------------------------------------
 template <bool IN_BF16>
 __global__ __launch_bounds__(512) void decode_prologue_kernel(const void *__restrict__ in, float *__restrict__ h_out,
-                                                             const float *__restrict__ g, bf16_t *__restrict__ hg_hi,
-                                                             bf16_t *__restrict__ hg_lo, float *__restrict__ ssq_out,
+                                                             const float *__restrict__ g, bf16_t *__restrict__ hg,
+                                                             float *__restrict__ ssq_out,
                                                              int T, int H, int32_t *lens, int32_t *row_pos,
                                                              int advance) {
     if (blockIdx.x == 0 && lens != nullptr && threadIdx.x < T) {
@@ -285,7 +331,7 @@ __global__ __launch_bounds__(512) void decode_prologue_kernel(const void *__rest
             if (h_out) *reinterpret_cast<floatx4 *>(h_out + (size_t)t * H + col) = floatx4{x[0], x[1], x[2], x[3]};
             const floatx4 g4 = *reinterpret_cast<const floatx4 *>(g + col);
             const float y[4] = {x[0] * g4[0], x[1] * g4[1], x[2] * g4[2], x[3] * g4[3]};
-            store_split4(y, hg_hi, hg_lo, frag_offset(t, col, H >> 5));
+            store_act4(y, hg, t, col, H >> 5);
             ss = x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
         }
         // the 4 quads of one 16-column unit are 4 consecutive lanes
@@ -295,14 +341,13 @@ __global__ __launch_bounds__(512) void decode_prologue_kernel(const void *__rest
     }
 }
 
-void launch_decode_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg_hi,
-                            bf16_t *hg_lo, float *ssq_out, int T, int H, int32_t *lens, int32_t *row_pos,
-                            int advance, hipStream_t s) {
+void launch_decode_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg, float *ssq_out,
+                            int T, int H, int32_t *lens, int32_t *row_pos, int advance, hipStream_t s) {
     const int blocks = (H + 127) / 128;
     if (in_is_bf16)
-        hipLaunchKernelGGL(decode_prologue_kernel<true>, dim3(blocks), dim3(512), 0, s, in, h_out, g, hg_hi, hg_lo,
-                           ssq_out, T, H, lens, row_pos, advance);
+        hipLaunchKernelGGL(decode_prologue_kernel<true>, dim3(blocks), dim3(512), 0, s, in, h_out, g, hg, ssq_out, T, H,
+                           lens, row_pos, advance);
     else
-        hipLaunchKernelGGL(decode_prologue_kernel<false>, dim3(blocks), dim3(512), 0, s, in, h_out, g, hg_hi, hg_lo,
-                           ssq_out, T, H, lens, row_pos, advance);
+        hipLaunchKernelGGL(decode_prologue_kernel<false>, dim3(blocks), dim3(512), 0, s, in, h_out, g, hg, ssq_out, T, H,
+                           lens, row_pos, advance);
 }

@@ -106,8 +106,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t *__restrict
     const bf16x8 *B = reinterpret_cast<const bf16x8 *>(Xp);
     bf16x8 ra0, ra1, rb0, rb1;
     auto gload = [&](int kt) {
-        ra0 = ta0 < n_tiles ? A[((size_t)ta0 * k_tiles + kt) * 64 + lane] : zero;
-        ra1 = ta1 < n_tiles ? A[((size_t)ta1 * k_tiles + kt) * 64 + lane] : zero;
+        ra0 = ta0 < n_tiles ? A[((size_t)kt * n_tiles + ta0) * 64 + lane] : zero;
+        ra1 = ta1 < n_tiles ? A[((size_t)kt * n_tiles + ta1) * 64 + lane] : zero;
         rb0 = tb0 < t_tiles ? B[((size_t)tb0 * k_tiles + kt) * 64 + lane] : zero;
         rb1 = tb1 < t_tiles ? B[((size_t)tb1 * k_tiles + kt) * 64 + lane] : zero;
     };

@@ -7,7 +7,7 @@
 // pairs: tile rows 0-7 = head columns 8*tl .. 8*tl+7, rows 8-15 = the same columns + rope_d/2.
 __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, int64_t ld, int k0, int c0, int k_tiles,
                                    int n_tiles, bf16_t *__restrict__ dst, int dst_tile0, int dst_tile_stride,
-                                   int rope_d) {
+                                   int dst_n_tiles, int rope_d) {
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t total = (int64_t)n_tiles * k_tiles * 64;
     if (gid >= total) return;
@@ -24,17 +24,17 @@ __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, int64_t ld, i
 #pragma unroll
     for (int j = 0; j < 8; ++j) u.e[j] = src[(int64_t)(k + j) * ld + n];
     int64_t dt = (int64_t)dst_tile0 + (int64_t)nt * dst_tile_stride;
-    *reinterpret_cast<uint4 *>(dst + ((dt * k_tiles + kt) * 64 + lane) * 8) = u.v;
+    *reinterpret_cast<uint4 *>(dst + (((int64_t)kt * dst_n_tiles + dt) * 64 + lane) * 8) = u.v;
 }
 
 void launch_pack_weight(const bf16_t *src, int64_t ld, int k0, int c0, int K, int N, bf16_t *dst,
-                        int dst_tile0, int dst_tile_stride, int rope_d, hipStream_t s) {
+                        int dst_tile0, int dst_tile_stride, int dst_n_tiles, int rope_d, hipStream_t s) {
     int k_tiles = K / 32, n_tiles = N / 16;
     int64_t total = (int64_t)n_tiles * k_tiles * 64;
     if (total == 0) return;
     int blocks = (int)((total + 255) / 256);
     hipLaunchKernelGGL(pack_weight_kernel, dim3(blocks), dim3(256), 0, s, src, ld, k0, c0, k_tiles, n_tiles,
-                       dst, dst_tile0, dst_tile_stride, rope_d);
+                       dst, dst_tile0, dst_tile_stride, dst_n_tiles, rope_d);
 }
 
 __global__ void cvt_bf16_to_f32_kernel(const bf16_t *__restrict__ src, float *__restrict__ dst, int64_t n) {
@@ -126,4 +126,43 @@ void launch_kv_gather(const bf16_t *kc, const bf16_t *vc, KvGeom kg, int seq, in
     if (total <= 0) return;
     hipLaunchKernelGGL(kv_gather_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, kc, vc, kg, seq,
                        pos0, n, k, v);
+}
+
+// ---- measurement utilities: plain streaming kernels of known size ---------------------------------
+// copy: dst[i] = src[i] over n 16-byte words; read: sums every word into one float per thread block
+// (so the loads cannot be dropped).  Both walk memory in 1 KB-per-wave chunks like the decode kernels.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void stream_copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
+                                                         int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
+        u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
+        dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+    }
+    for (; i < n; i += stride) dst[i] = src[i];
+}
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *__restrict__ src, float *__restrict__ sink,
+                                                         int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    uint32_t acc = 0;
+    for (; i + 7 * stride < n; i += 8 * stride) {
+        u32x4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(src + i + j * stride);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+    }
+    for (; i < n; i += stride) { u32x4 v = src[i]; acc ^= v.x ^ v.y ^ v.z ^ v.w; }
+    if (acc == 0x9e3779b9u) sink[blockIdx.x] = 1.0f;     // practically never: keeps the loads alive
+}
+void launch_stream_copy(const void *src, void *dst, int64_t bytes, int blocks, hipStream_t s) {
+    hipLaunchKernelGGL(stream_copy_kernel, dim3(blocks), dim3(256), 0, s, static_cast<const u32x4 *>(src),
+                       static_cast<u32x4 *>(dst), bytes / 16);
+}
+void launch_stream_read(const void *src, float *sink, int64_t bytes, int blocks, hipStream_t s) {
+    hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(256), 0, s, static_cast<const u32x4 *>(src), sink,
+                       bytes / 16);
 }

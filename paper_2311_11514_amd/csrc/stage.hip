@@ -69,7 +69,8 @@ struct Workspace {
     float *p32 = nullptr;      // reduced partial [T][H] fp32
     // bf16 path
     bf16_t *n = nullptr, *o = nullptr, *u = nullptr, *q = nullptr;
-    bf16_t *n_lo = nullptr, *o_lo = nullptr, *u_lo = nullptr, *q_lo = nullptr;   // decode rows only (x = hi + lo)
+    bf16_t *xa_n = nullptr, *xa_o = nullptr, *xa_u = nullptr;   // decode operands, compact hi/lo layout [32][K][2]
+    bf16_t *q_lo = nullptr;
     float *att_o = nullptr, *att_ml = nullptr;
     float *ssq = nullptr;                       // 2 x [H/16 units][DEC_SSQ_STRIDE] sums of squares
     // fp32 path
@@ -114,7 +115,7 @@ namespace {
 size_t esize(hexgen_dtype_t dt) { return dt == HEXGEN_F32 ? 4 : 2; }
 
 void free_ws(Workspace &w) {
-    void *ptrs[] = {w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.n_lo, w.o_lo, w.u_lo, w.q_lo, w.ssq, w.att_o, w.att_ml, w.n32, w.q32, w.o32, w.u32,
+    void *ptrs[] = {w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.xa_n, w.xa_o, w.xa_u, w.q_lo, w.ssq, w.att_o, w.att_ml, w.n32, w.q32, w.o32, w.u32,
                     w.row_seq, w.row_pos, w.cu_rows, w.pos0};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
@@ -151,10 +152,9 @@ hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
         HX_TRY(dmalloc(&w.u, T16 * st->F_l));
         HX_TRY(dmalloc(&w.q, T * st->qw));
         const size_t drows = (size_t)std::min(rows, kDecodeMaxRows);
-        const size_t d16 = (size_t)round_up((int)drows, 16);
-        HX_TRY(dmalloc(&w.n_lo, d16 * st->H));
-        HX_TRY(dmalloc(&w.o_lo, d16 * st->qw));
-        HX_TRY(dmalloc(&w.u_lo, d16 * st->F_l));
+        HX_TRY(dmalloc(&w.xa_n, 2 * drows * st->H));
+        HX_TRY(dmalloc(&w.xa_o, 2 * drows * st->qw));
+        HX_TRY(dmalloc(&w.xa_u, 2 * drows * st->F_l));
         HX_TRY(dmalloc(&w.q_lo, drows * st->qw));
         HX_TRY(dmalloc(&w.att_o, drows * st->hq_l * kMaxAttnSplit * st->d));
         HX_TRY(dmalloc(&w.att_ml, drows * st->hq_l * kMaxAttnSplit * 2));
@@ -317,10 +317,10 @@ DecodeEpi epi_base(hexgen_stage *st, int mode) {
     return e;
 }
 
-void decode_proj(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xp, const bf16_t *Xlo, int N, int K,
-                 const DecodeEpi &e, int slot, hipStream_t s) {
+void decode_proj(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xa, int N, int K, const DecodeEpi &e,
+                 int slot, hipStream_t s) {
     st->prof.mark(slot, s);
-    launch_decode_proj(static_cast<const bf16_t *>(Wp), Xp, Xlo, N, K, r.T, e, s);
+    launch_decode_proj(static_cast<const bf16_t *>(Wp), Xa, N, K, r.T, e, s);
     st->prof.mark(slot, s);
 }
 
@@ -336,10 +336,10 @@ void attn_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Ro
     e.ssq_in = ssq_in;
     e.hq_l = st->hq_l; e.kg = kg; e.row_pos = w.row_pos; e.cos_tab = kv->cos_tab; e.sin_tab = kv->sin_tab;
     e.q_hi = w.q; e.q_lo = w.q_lo; e.kc = kc; e.vc = vc;
-    decode_proj(st, r, ly.wqkv, w.n, w.n_lo, st->nqkv, st->H, e, PROF_QKV, s);
+    decode_proj(st, r, ly.wqkv, w.xa_n, st->nqkv, st->H, e, PROF_QKV, s);
     st->prof.mark(PROF_ATTN, s);
     launch_attn_decode(w.q, w.q_lo, kc, vc, kg, st->hq_l, w.row_pos, r.batch, pick_attn_split(st, kv, r.batch), w.att_o,
-                       w.att_ml, w.o, w.o_lo, s);
+                       w.att_ml, w.xa_o, s);
     st->prof.mark(PROF_ATTN, s);
 }
 
@@ -347,7 +347,7 @@ hexgen_status_t forward_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const
                                     void *out_partial, void *out_resid, hipStream_t s) {
     Workspace &w = st->ws;
     float *ssq_a = w.ssq, *ssq_f = w.ssq + (size_t)(st->H / 16) * DEC_SSQ_STRIDE;
-    launch_decode_prologue(hidden_in, 1, w.h, st->layers[0].g_attn, w.n, w.n_lo, ssq_a, r.T, st->H, kv->d_lens,
+    launch_decode_prologue(hidden_in, 1, w.h, st->layers[0].g_attn, w.xa_n, ssq_a, r.T, st->H, kv->d_lens,
                            w.row_pos, 1, s);
     for (int l = 0; l < st->L; ++l) {
         const Layer &ly = st->layers[l];
@@ -356,18 +356,18 @@ hexgen_status_t forward_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const
             HX_HIP(hipMemcpyAsync(st->taps[l], w.h, sizeof(float) * (size_t)r.T * st->H, hipMemcpyDeviceToDevice, s));
         attn_decode_bf16(st, kv, l, r, ssq_a, s);
         DecodeEpi e = epi_base(st, DEC_RESID);
-        e.h = w.h; e.g_next = ly.g_ffn; e.hg_hi = w.n; e.hg_lo = w.n_lo; e.ssq_out = ssq_f;
-        decode_proj(st, r, ly.wo, w.o, w.o_lo, st->H, st->qw, e, PROF_WO, s);
+        e.h = w.h; e.g_next = ly.g_ffn; e.hg = w.xa_n; e.ssq_out = ssq_f;
+        decode_proj(st, r, ly.wo, w.xa_o, st->H, st->qw, e, PROF_WO, s);
         e = epi_base(st, DEC_SWIGLU);
-        e.ssq_in = ssq_f; e.u_hi = w.u; e.u_lo = w.u_lo; e.F_l = st->F_l;
-        decode_proj(st, r, ly.w13, w.n, w.n_lo, 2 * st->F_l, st->H, e, PROF_W13, s);
+        e.ssq_in = ssq_f; e.u = w.xa_u; e.F_l = st->F_l;
+        decode_proj(st, r, ly.w13, w.xa_n, 2 * st->F_l, st->H, e, PROF_W13, s);
         e = epi_base(st, DEC_RESID);
-        e.h = w.h; e.hg_hi = w.n; e.hg_lo = w.n_lo; e.ssq_out = ssq_a;
+        e.h = w.h; e.hg = w.xa_n; e.ssq_out = ssq_a;
         e.g_next = last ? nullptr : st->layers[l + 1].g_attn;
         e.last_layer = last ? 1 : 0;
         e.out_partial = static_cast<bf16_t *>(out_partial);
         e.out_resid = static_cast<bf16_t *>(out_resid);
-        decode_proj(st, r, ly.w2, w.u, w.u_lo, st->H, st->F_l, e, PROF_W2, s);
+        decode_proj(st, r, ly.w2, w.xa_u, st->H, st->F_l, e, PROF_W2, s);
     }
     return HEXGEN_OK;
 }
@@ -381,15 +381,15 @@ void sublayer_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, int 
     DecodeEpi e = epi_base(st, DEC_RAW);
     e.raw_out = p_out;
     if (which == 0) {
-        launch_decode_prologue(h, 0, nullptr, ly.g_attn, w.n, w.n_lo, ssq, r.T, st->H, kv->d_lens, w.row_pos, 0, s);
+        launch_decode_prologue(h, 0, nullptr, ly.g_attn, w.xa_n, ssq, r.T, st->H, kv->d_lens, w.row_pos, 0, s);
         attn_decode_bf16(st, kv, layer, r, ssq, s);
-        decode_proj(st, r, ly.wo, w.o, w.o_lo, st->H, st->qw, e, PROF_WO, s);
+        decode_proj(st, r, ly.wo, w.xa_o, st->H, st->qw, e, PROF_WO, s);
     } else {
-        launch_decode_prologue(h, 0, nullptr, ly.g_ffn, w.n, w.n_lo, ssq, r.T, st->H, nullptr, nullptr, 0, s);
+        launch_decode_prologue(h, 0, nullptr, ly.g_ffn, w.xa_n, ssq, r.T, st->H, nullptr, nullptr, 0, s);
         DecodeEpi g = epi_base(st, DEC_SWIGLU);
-        g.ssq_in = ssq; g.u_hi = w.u; g.u_lo = w.u_lo; g.F_l = st->F_l;
-        decode_proj(st, r, ly.w13, w.n, w.n_lo, 2 * st->F_l, st->H, g, PROF_W13, s);
-        decode_proj(st, r, ly.w2, w.u, w.u_lo, st->H, st->F_l, e, PROF_W2, s);
+        g.ssq_in = ssq; g.u = w.xa_u; g.F_l = st->F_l;
+        decode_proj(st, r, ly.w13, w.xa_n, 2 * st->F_l, st->H, g, PROF_W13, s);
+        decode_proj(st, r, ly.w2, w.xa_u, st->H, st->F_l, e, PROF_W2, s);
     }
 }
 
@@ -593,26 +593,27 @@ hexgen_status_t hexgen_stage_load_layer(hexgen_stage_t *st, int layer, const voi
         bf16_t *tmp = nullptr;
         HX_TRY(dmalloc(&tmp, tmp_elems));
         hexgen_status_t rc = HEXGEN_OK;
-        auto col_shard = [&](const void *src, int c0, int gcols, int cols, void *dst, int tile0, int stride, int rope_d) {
+        auto col_shard = [&](const void *src, int c0, int gcols, int cols, void *dst, int tile0, int stride, int dst_tiles,
+                             int rope_d) {
             if (rc != HEXGEN_OK) return;
             hipError_t e = hipMemcpy2D(tmp, cbytes(cols), src_at(src, 0, c0, gcols), cbytes(gcols), cbytes(cols), H,
                                        hipMemcpyDefault);
             if (e != hipSuccess) { rc = HEXGEN_ERR_DEVICE; return; }
-            launch_pack_weight(tmp, cols, 0, 0, H, cols, static_cast<bf16_t *>(dst), tile0, stride, rope_d, nullptr);
+            launch_pack_weight(tmp, cols, 0, 0, H, cols, static_cast<bf16_t *>(dst), tile0, stride, dst_tiles, rope_d, nullptr);
             if (hipDeviceSynchronize() != hipSuccess) rc = HEXGEN_ERR_DEVICE;
         };
         auto row_shard = [&](const void *src, int r0, int rows, void *dst) {
             if (rc != HEXGEN_OK) return;
             hipError_t e = hipMemcpy(tmp, src_at(src, r0, 0, H), (size_t)rows * H * es, hipMemcpyDefault);
             if (e != hipSuccess) { rc = HEXGEN_ERR_DEVICE; return; }
-            launch_pack_weight(tmp, H, 0, 0, rows, H, static_cast<bf16_t *>(dst), 0, 1, 0, nullptr);
+            launch_pack_weight(tmp, H, 0, 0, rows, H, static_cast<bf16_t *>(dst), 0, 1, H / 16, 0, nullptr);
             if (hipDeviceSynchronize() != hipSuccess) rc = HEXGEN_ERR_DEVICE;
         };
-        col_shard(wq, q0, qcols, st->qw, ly.wqkv, 0, 1, d);        // q, k, v tiles hold rotary pairs
-        col_shard(wk, k0, kcols, kw, ly.wqkv, st->qw / 16, 1, d);
-        col_shard(wv, k0, kcols, kw, ly.wqkv, (st->qw + kw) / 16, 1, d);
-        col_shard(w1, f0, st->F, st->F_l, ly.w13, 0, 2, 0);  // gate tiles at even positions
-        col_shard(w3, f0, st->F, st->F_l, ly.w13, 1, 2, 0);  // up tiles at odd positions
+        col_shard(wq, q0, qcols, st->qw, ly.wqkv, 0, 1, st->nqkv / 16, d);        // q, k, v tiles hold rotary pairs
+        col_shard(wk, k0, kcols, kw, ly.wqkv, st->qw / 16, 1, st->nqkv / 16, d);
+        col_shard(wv, k0, kcols, kw, ly.wqkv, (st->qw + kw) / 16, 1, st->nqkv / 16, d);
+        col_shard(w1, f0, st->F, st->F_l, ly.w13, 0, 2, st->F_l / 8, 0);  // gate tiles at even positions
+        col_shard(w3, f0, st->F, st->F_l, ly.w13, 1, 2, st->F_l / 8, 0);  // up tiles at odd positions
         row_shard(wo, q0, st->qw, ly.wo);
         row_shard(w2, f0, st->F_l, ly.w2);
         (void)hipFree(tmp);
@@ -879,6 +880,18 @@ hexgen_status_t hexgen_stage_profile_read(hexgen_stage_t *st, int slot, double *
     }
     *total_ms = tot;
     *count = n;
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_stream_copy(void *dst, const void *src, int64_t bytes, int blocks, void *stream) {
+    if (!dst || !src || bytes < 0 || bytes % 16 || blocks <= 0) return HEXGEN_ERR_INVALID_ARG;
+    launch_stream_copy(src, dst, bytes, blocks, static_cast<hipStream_t>(stream));
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_stream_read(const void *src, void *sink, int64_t bytes, int blocks, void *stream) {
+    if (!sink || !src || bytes < 0 || bytes % 16 || blocks <= 0) return HEXGEN_ERR_INVALID_ARG;
+    launch_stream_read(src, static_cast<float *>(sink), bytes, blocks, static_cast<hipStream_t>(stream));
     return HEXGEN_OK;
 }
 

@@ -1,5 +1,5 @@
 // bf16 projections of the prefill path: RMSNorm fused with the cast into the GEMM operand layout, the
-// LDS-tiled MFMA GEMM, and its epilogue kernels (RoPE + cache append, residual + next norm, SwiGLU).
+// epilogue kernels of the MFMA GEMM (kernels_bf16_gemm.hip) (RoPE + cache append, residual + next norm, SwiGLU).
 // The decode path (T <= 32 rows) lives in kernels_bf16_decode.hip.
 //
 // Every contraction is computed "transposed": D^T[n][t] = sum_k Wp[n][k] * Xp[t][k] with the weight
@@ -75,82 +75,6 @@ void launch_rmsnorm_pack(const void *in, int in_is_bf16, float *h_out, const flo
         hipLaunchKernelGGL(rmsnorm_pack_kernel<true>, dim3(T), dim3(256), 0, s, in, h_out, g, n_packed, n_lo, H, eps);
     else
         hipLaunchKernelGGL(rmsnorm_pack_kernel<false>, dim3(T), dim3(256), 0, s, in, h_out, g, n_packed, n_lo, H, eps);
-}
-
-// -------------------------------------------------------------------------------------------------
-// Prefill projection: LDS-staged MFMA GEMM.  Block tile 128 features x 128 tokens, 4 waves (2 x 2),
-// each wave 64 x 64 = 4 x 4 MFMA tiles.  Operand tiles arrive already in fragment order, so the
-// global -> LDS copy is a straight 16-byte-per-thread copy and the LDS reads are conflict-free
-// 128-bit reads at lane * 16 bytes.
-// -------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t *__restrict__ Wp, const bf16_t *__restrict__ Xp,
-                                                       float *__restrict__ out, int N, int k_tiles, int n_tiles,
-                                                       int t_tiles, int T) {
-    __shared__ bf16x8 sA[2][8][64];
-    __shared__ bf16x8 sB[2][8][64];
-    const int bm = blockIdx.x, bt = blockIdx.y;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int wm = wave & 1, wt = wave >> 1;
-
-    floatx4 acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    // this thread copies tiles (wave) and (wave + 4) of both operands, lane slot `lane`
-    const int ta0 = bm * 8 + wave, ta1 = ta0 + 4;
-    const int tb0 = bt * 8 + wave, tb1 = tb0 + 4;
-    const bf16x8 *A = reinterpret_cast<const bf16x8 *>(Wp);
-    const bf16x8 *B = reinterpret_cast<const bf16x8 *>(Xp);
-    bf16x8 ra0, ra1, rb0, rb1;
-    auto gload = [&](int kt) {
-        ra0 = ta0 < n_tiles ? A[((size_t)kt * n_tiles + ta0) * 64 + lane] : zero;
-        ra1 = ta1 < n_tiles ? A[((size_t)kt * n_tiles + ta1) * 64 + lane] : zero;
-        rb0 = tb0 < t_tiles ? B[((size_t)tb0 * k_tiles + kt) * 64 + lane] : zero;
-        rb1 = tb1 < t_tiles ? B[((size_t)tb1 * k_tiles + kt) * 64 + lane] : zero;
-    };
-    auto sstore = [&](int buf) {
-        sA[buf][wave][lane] = ra0; sA[buf][wave + 4][lane] = ra1;
-        sB[buf][wave][lane] = rb0; sB[buf][wave + 4][lane] = rb1;
-    };
-    gload(0);
-    sstore(0);
-    __syncthreads();
-    int cur = 0;
-    for (int kt = 0; kt < k_tiles; ++kt) {
-        if (kt + 1 < k_tiles) gload(kt + 1);
-        bf16x8 a[4], b[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) a[i] = sA[cur][wm * 4 + i][lane];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) b[j] = sB[cur][wt * 4 + j][lane];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-        if (kt + 1 < k_tiles) sstore(cur ^ 1);
-        __syncthreads();
-        cur ^= 1;
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int token = bt * 128 + wt * 64 + j * 16 + (lane & 15);
-        if (token >= T) continue;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int n = bm * 128 + wm * 64 + i * 16 + 4 * (lane >> 4);
-            if (n < N) *reinterpret_cast<floatx4 *>(out + (size_t)token * N + n) = acc[i][j];
-        }
-    }
-}
-
-void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, int K, int T, hipStream_t s) {
-    const int k_tiles = K / 32, n_tiles = N / 16, t_tiles = (T + 15) / 16;
-    dim3 grid((n_tiles + 7) / 8, (t_tiles + 7) / 8);
-    hipLaunchKernelGGL(gemm_mfma_kernel, grid, dim3(256), 0, s, Wp, Xp, out, N, k_tiles, n_tiles, t_tiles, T);
 }
 
 // -------------------------------------------------------------------------------------------------

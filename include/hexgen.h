@@ -54,7 +54,7 @@ const char *hexgen_status_string(hexgen_status_t s);
  * [r*hq/t, (r+1)*hq/t), KV heads [r*hkv/t, (r+1)*hkv/t), FFN columns [r*F/t, (r+1)*F/t).
  * HEXGEN_ERR_SHAPE unless hidden % n_heads == 0, n_heads % n_kv_heads == 0, n_heads, n_kv_heads
  * and ffn divisible by tp_degree, 0 <= tp_rank < tp_degree, head_dim in {64, 128}, and (bf16)
- * hidden, local q width and local ffn multiples of 32.  Defaults: rms_eps 1e-5, rope_theta 1e4.
+ * hidden a multiple of 128, local q width and local ffn multiples of 32.  Defaults: rms_eps 1e-5, rope_theta 1e4.
  */
 hexgen_status_t hexgen_stage_create(int hidden, int n_heads, int n_kv_heads, int ffn, int n_layers,
                                     int tp_degree, int tp_rank, hexgen_dtype_t dtype,
@@ -103,7 +103,7 @@ hexgen_status_t hexgen_stage_prefill(hexgen_stage_t *st, hexgen_kv_cache_t *kv, 
 /* ---- decode (paper Section 2, decode equations) --------------------------------------------
  * One new row per sequence of the prefilled batch, at position len_i; K, V of the row are
  * appended.  `step` (0-based) must equal the number of decode calls since the prefill (or the
- * last hexgen_kv_cache_fill), else HEXGEN_ERR_STATE.  Buffers as for prefill with
+ * last hexgen_kv_cache_set_lengths), else HEXGEN_ERR_STATE.  Buffers as for prefill with
  * total_rows = batch.
  */
 hexgen_status_t hexgen_stage_decode(hexgen_stage_t *st, hexgen_kv_cache_t *kv, int step,

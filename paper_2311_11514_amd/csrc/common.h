@@ -26,6 +26,16 @@ __host__ __device__ inline size_t dec_act_offset(int token, int k, int k_tiles, 
     return (((size_t)token * k_tiles + (k >> 5)) * 2 + plane) * 32 + (k & 31);
 }
 
+// Prefill keeps its fp32 residual stream in the order the 32x32 MFMA result leaves the registers: blocks of
+// 32 tokens x 32 features, inside a block [quad q][lane][4] with lane = token % 32 + 32 * ((f % 8) / 4) and
+// q = (f % 32) / 8.  A wave's read-modify-write of the stream is then one contiguous 1 KB access instead
+// of 32 row-strided 32-byte pieces.  Returns the offset of 4 consecutive features n .. n+3 (n % 4 == 0).
+__host__ __device__ inline size_t h_tile_offset(int token, int n, int N) {
+    const size_t blk = (size_t)(token >> 5) * (N >> 5) + (n >> 5);
+    const int f = n & 31;
+    return ((blk * 4 + (f >> 3)) * 64 + (token & 31) + 32 * ((f & 7) >> 2)) * 4;
+}
+
 __host__ __device__ inline size_t frag_offset(int idx, int k, int k_tiles) {
     int it = idx >> 4, kt = k >> 5;
     int lane = (idx & 15) + 16 * ((k & 31) >> 3);

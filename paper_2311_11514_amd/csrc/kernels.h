@@ -44,13 +44,6 @@ void launch_stream_read(const void *src, float *sink, int64_t bytes, int blocks,
 
 // ---- bf16 path (kernels_bf16_*.hip) ---------------------------------------------------------
 
-// rows of `in` ([T,H] row-major, fp32 or bf16) -> optional fp32 copy h_out, and
-// packed bf16 n = in / sqrt(mean(in^2)+eps) * g  ([ceil16(T)/16][H/32] fragment tiles)
-// Packed activations may carry a second plane `*_lo` with the bf16 rounding remainder (x = hi + lo);
-// producers write it when the pointer is non-null, the decode kernels consume both planes.
-void launch_rmsnorm_pack(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *n_packed,
-                         bf16_t *n_lo, int T, int H, float eps, hipStream_t s);
-
 // ---- decode projections with fused epilogues (kernels_bf16_decode.hip) ---------------------------
 enum { DEC_RAW = 0, DEC_QKV = 1, DEC_RESID = 2, DEC_SWIGLU = 3 };
 #define DEC_SSQ_STRIDE 32      // tokens per unit row of the sum-of-squares scratch
@@ -86,30 +79,45 @@ void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T,
 // positions from the committed lengths and optionally advances them
 void launch_decode_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg, float *ssq_out,
                             int T, int H, int32_t *lens, int32_t *row_pos, int advance, hipStream_t s);
-// same contraction for many rows (prefill): out[t][n] fp32 row-major
-void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, int K, int T, hipStream_t s);
+// ---- prefill projections with fused epilogues (kernels_bf16_gemm.hip) ----------------------------
+// Same epilogue roles as in decode (DEC_* modes), on packed operands: the input Xp is (h * gain) in
+// fragment tiles, RMSNorm enters as the per-token scale rstd derived from `ssq_in`.
+#define GEMM_SSQ_COLS 128      // features per sum-of-squares partial: ssq[H / 128][T]
+struct GemmEpi {
+    int mode;                  // DEC_RAW | DEC_QKV | DEC_RESID | DEC_SWIGLU
+    const float *ssq_in;       // [norm_dim / 128][T] sums of squares of the input rows, NULL = not normalised
+    int norm_dim;
+    float eps;
+    float *raw_out;            // RAW: [T][N] fp32
+    // QKV
+    int hq_l;
+    KvGeom kg;
+    RowMap rm;
+    const float *cos_tab, *sin_tab;
+    bf16_t *q, *kc, *vc;       // q: fragment tiles [T/16][hq_l * d / 32]
+    // RESID
+    float *h;                  // residual stream, fp32, 32 x 32 tiled (h_tile_offset), updated in place
+    const float *g_next;
+    bf16_t *hg;                // (h * g_next) in fragment tiles [T/16][N/32]
+    float *ssq_out;            // [N / 128][T]
+    int last_layer;
+    bf16_t *out_partial, *out_resid;
+    // SWIGLU
+    bf16_t *u;                 // fragment tiles [T/16][F_l/32]
+    int F_l;
+};
+void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, hipStream_t s);
+// stage input rows -> h (optional), (x * g) in fragment tiles, sums of squares [H / 128][T]
+void launch_untile_h(const float *h_tiled, float *out, int T, int H, hipStream_t s);
+void launch_prefill_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg, float *ssq_out,
+                             int T, int H, hipStream_t s);
 
-// prefill: the QKV projection output (rope-interleaved column order, see launch_pack_weight) -> rotate q
-// and k heads, write q (bf16 row-major [T][hq_l*d]) and append k, v to the cache at each row's (seq, pos)
-void launch_qkv_rope_append(const float *part, int ksplit, int T, int hq_l, KvGeom kg, RowMap rm,
-                            const float *cos_tab, const float *sin_tab, bf16_t *q_out, bf16_t *q_lo, bf16_t *kc,
-                            bf16_t *vc, hipStream_t s);
-// h[t][:] += sum_ks part[ks][t][:]; then either packed n = rmsnorm(h) * g (g != NULL) or nothing
-void launch_reduce_resid_norm(const float *part, int ksplit, float *h, const float *g, bf16_t *n_packed,
-                              bf16_t *n_lo, int T, int H, float eps, hipStream_t s);
-// plain reduce of the partials into dst fp32 [T][H] (no residual): the stage's output partial
-void launch_reduce_partial(const float *part, int ksplit, float *dst, int T, int H, hipStream_t s);
-// u[t][f] = silu(a) * b with a, b the W1 / W3 columns (interleaved 16-column tiles) -> packed bf16
-void launch_reduce_swiglu(const float *part, int ksplit, bf16_t *u_packed, bf16_t *u_lo, int T, int F_l,
-                          hipStream_t s);
-
-// decode attention: one new row per sequence; split-KV partials then merge into packed o
 // row_pos[seq] = position of the new row (= cached context length)
 // o_act: compact hi/lo decode operand [b][hq_l*d] of the W_O projection
 void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, const bf16_t *vc, KvGeom kg,
                         int hq_l, const int32_t *row_pos, int b, int nsplit, float *part_o, float *part_ml,
                         bf16_t *o_act, hipStream_t s);
-// prefill attention over packed ragged rows; K, V are read from the cache
+// prefill attention over packed ragged rows (q in fragment tiles); K, V are read from the cache
 void launch_attn_prefill(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,
                          const int32_t *cu_rows, const int32_t *pos0, int batch, int max_new,
                          bf16_t *o_packed, hipStream_t s);

@@ -302,7 +302,8 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16_t *__restr
     bf16x8 qf[KT];
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt)
-        qf[kt] = valid ? *reinterpret_cast<const bf16x8 *>(q + ((size_t)(row0 + ri) * hq_l + head) * D + kt * 32 + 8 * g)
+        qf[kt] = valid ? *reinterpret_cast<const bf16x8 *>(q + frag_offset(row0 + ri, head * D + kt * 32 + 8 * g,
+                                                                            (hq_l * D) >> 5))
                        : zero;
     floatx4 oacc[DT];
 #pragma unroll

@@ -17,6 +17,7 @@
 #include <cstdlib>
 
 #include "kernels.h"
+#include "kvlayout.h"
 
 #define HX_AS1(p) ((const __attribute__((address_space(1))) void *)(p))
 #define HX_AS3(p) ((__attribute__((address_space(3))) void *)(p))
@@ -34,10 +35,10 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 // 1 KB fragment tile per instruction, lane l's 16 bytes landing at tile base + 16 l.  S stages of the k-loop
 // are resident; loads run S - 1 steps ahead of the math and the wait before a step only covers that step's
 // loads (vmcnt counts the rest).
-template <int FM, int FT, int S>
+template <int FM, int FT, int S, int MODE>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t *__restrict__ Wp, const bf16_t *__restrict__ Xp,
-                                                       float *__restrict__ out, int N, int k_tiles, int n_tiles,
-                                                       int t_tiles, int T, int n_blocks, int t_blocks) {
+                                                       int N, int k_tiles, int n_tiles, int t_tiles, int T,
+                                                       int n_blocks, int t_blocks, GemmEpi e) {
     constexpr int TA = 4 * FM, TB = 4 * FT;          // 16-row operand tiles per block and k-step
     constexpr int LPT = (TA + TB) / 4;               // direct-to-LDS loads per thread and stage
     constexpr int STAGE = (TA + TB) * 64;            // bf16x8 elements per stage
@@ -106,30 +107,163 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t *__restrict
             }
         }
     }
-    // 32 x 32 result: lane l holds token column l % 32 and, per register quad q, features 8 q + 4 (l / 32) .. + 3
+    // ---- epilogue, in registers.  32 x 32 result: lane l holds token column l % 32 and, per register quad q,
+    // features 8 q + 4 (l / 32) .. + 3 of the 32-feature block, i.e. of the 16-row tile q / 2 its rows
+    // (q % 2) * 8 + 4 (l / 32) .. + 3.  Rotary pairs (tile rows r, r + 8) and gate / up pairs (tiles 2m, 2m + 1)
+    // therefore sit in the same lane, in quads q and q ^ 1 respectively q and q + 2: no cross-lane traffic.
+    const int hl = lane >> 5;
 #pragma unroll
     for (int j = 0; j < FT; ++j) {
         const int token = (bt * TB + (wt * FT + j) * 2) * 16 + (lane & 31);
-        if (token >= T) continue;
+        const bool tv = token < T;
+        float r = 1.0f;
+        if ((MODE == DEC_QKV || MODE == DEC_SWIGLU || MODE == DEC_RAW) && e.ssq_in != nullptr && tv) {
+            float ss = 0.f;
+            const int groups = e.norm_dim / GEMM_SSQ_COLS;
+#pragma unroll 8
+            for (int gI = 0; gI < groups; ++gI) ss += e.ssq_in[(size_t)gI * T + token];
+            r = 1.0f / sqrtf(ss / (float)e.norm_dim + e.eps);
+        }
+        int seq = 0, pos = 0;
+        if (MODE == DEC_QKV && tv) { seq = e.rm.row_seq[token]; pos = e.rm.row_pos[token]; }
+        float ssq = 0.f;
+        // RESID: fetch the whole column of residual values first, so the loads overlap instead of forming
+        // 4 FM load -> add -> store chains (one wave per SIMD: nothing else would hide their latency)
+        floatx4 hv[FM][4], gv[FM][4];
+        if (MODE == DEC_RESID) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
+            for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = (bm * TA + (wm * FM + i) * 2) * 16 + 8 * q + 4 * (lane >> 5);
-                if (n < N)
-                    *reinterpret_cast<floatx4 *>(out + (size_t)token * N + n) =
-                        floatx4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                for (int q = 0; q < 4; ++q) {
+                    const int n = (bm * TA + (wm * FM + i) * 2) * 16 + 8 * q + 4 * hl;
+                    const bool ok = tv && n < N;
+                    hv[i][q] = ok ? *reinterpret_cast<const floatx4 *>(e.h + h_tile_offset(token, n, N))
+                                  : floatx4{0.f, 0.f, 0.f, 0.f};
+                    gv[i][q] = (ok && !e.last_layer) ? *reinterpret_cast<const floatx4 *>(e.g_next + n)
+                                                     : floatx4{0.f, 0.f, 0.f, 0.f};
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int t16 = bm * TA + (wm * FM + i) * 2;        // first 16-row tile of this 32-feature block
+            const floatx16 &c = acc[i][j];
+            if (MODE == DEC_RAW) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = t16 * 16 + 8 * q + 4 * hl;
+                    if (tv && n < N)
+                        *reinterpret_cast<floatx4 *>(e.raw_out + (size_t)token * N + n) =
+                            floatx4{c[4 * q] * r, c[4 * q + 1] * r, c[4 * q + 2] * r, c[4 * q + 3] * r};
+                }
+            } else if (MODE == DEC_RESID) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = t16 * 16 + 8 * q + 4 * hl;
+                    if (!tv || n >= N) continue;
+                    const size_t ho = h_tile_offset(token, n, N);
+                    const floatx4 h4 = hv[i][q];
+                    const floatx4 v = {c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]};
+                    if (e.last_layer) {
+                        uint2 po;
+                        po.x = pack_bf16x2(v[0], v[1]);
+                        po.y = pack_bf16x2(v[2], v[3]);
+                        *reinterpret_cast<uint2 *>(e.out_partial + (size_t)token * N + n) = po;
+                        if (e.out_resid) {
+                            uint2 ro;
+                            ro.x = pack_bf16x2(h4[0], h4[1]);
+                            ro.y = pack_bf16x2(h4[2], h4[3]);
+                            *reinterpret_cast<uint2 *>(e.out_resid + (size_t)token * N + n) = ro;
+                        }
+                    } else {
+                        const floatx4 hn = h4 + v;
+                        *reinterpret_cast<floatx4 *>(e.h + ho) = hn;
+                        const floatx4 g4 = gv[i][q];
+                        uint2 o;
+                        o.x = pack_bf16x2(hn[0] * g4[0], hn[1] * g4[1]);
+                        o.y = pack_bf16x2(hn[2] * g4[2], hn[3] * g4[3]);
+                        *reinterpret_cast<uint2 *>(e.hg + frag_offset(token, n, N >> 5)) = o;
+                        ssq += hn[0] * hn[0] + hn[1] * hn[1] + hn[2] * hn[2] + hn[3] * hn[3];
+                    }
+                }
+            } else if (MODE == DEC_SWIGLU) {
+                // tile t16 = gate, t16 + 1 = up (interleaved packing): quads 0, 1 against quads 2, 3
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const int f = (t16 >> 1) * 16 + 8 * q + 4 * hl;
+                    if (!tv || f >= e.F_l) continue;
+                    float u[4];
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        const float aa = c[4 * q + x] * r;
+                        u[x] = aa / (1.0f + __expf(-aa)) * (c[4 * (q + 2) + x] * r);
+                    }
+                    uint2 o;
+                    o.x = pack_bf16x2(u[0], u[1]);
+                    o.y = pack_bf16x2(u[2], u[3]);
+                    *reinterpret_cast<uint2 *>(e.u + frag_offset(token, f, e.F_l >> 5)) = o;
+                }
+            } else {   // DEC_QKV: each 16-row tile holds 8 rotary pairs (rows r, r + 8)
+                const int d = e.kg.d, half = d >> 1, tph = d >> 4;
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {              // the two 16-row tiles of this block
+                    const int tile = t16 + m;
+                    if (!tv || tile >= n_tiles) continue;
+                    const int head = tile / tph, tl = tile - head * tph;
+                    const int i0 = tl * 8 + 4 * hl;            // first rotary pair index of this lane
+                    float lo[4], hi[4];
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) { lo[x] = c[4 * (2 * m) + x] * r; hi[x] = c[4 * (2 * m + 1) + x] * r; }
+                    if (head < e.hq_l + e.kg.hkv_l) {
+                        const floatx4 c4 = *reinterpret_cast<const floatx4 *>(e.cos_tab + (size_t)pos * half + i0);
+                        const floatx4 s4 = *reinterpret_cast<const floatx4 *>(e.sin_tab + (size_t)pos * half + i0);
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) {
+                            const float a = lo[x], b = hi[x];
+                            lo[x] = a * c4[x] - b * s4[x];
+                            hi[x] = b * c4[x] + a * s4[x];
+                        }
+                    }
+                    uint2 plo, phi;
+                    plo.x = pack_bf16x2(lo[0], lo[1]); plo.y = pack_bf16x2(lo[2], lo[3]);
+                    phi.x = pack_bf16x2(hi[0], hi[1]); phi.y = pack_bf16x2(hi[2], hi[3]);
+                    if (head < e.hq_l) {
+                        const int qkt = (e.hq_l * d) >> 5;
+                        *reinterpret_cast<uint2 *>(e.q + frag_offset(token, head * d + i0, qkt)) = plo;
+                        *reinterpret_cast<uint2 *>(e.q + frag_offset(token, head * d + i0 + half, qkt)) = phi;
+                    } else if (head < e.hq_l + e.kg.hkv_l) {
+                        const size_t slab = (size_t)seq * e.kg.seq_stride + (size_t)(head - e.hq_l) * e.kg.smax * d;
+                        *reinterpret_cast<uint2 *>(e.kc + slab + kv_k_offset(pos, i0, d)) = plo;
+                        *reinterpret_cast<uint2 *>(e.kc + slab + kv_k_offset(pos, i0 + half, d)) = phi;
+                    } else {
+                        const size_t slab =
+                            (size_t)seq * e.kg.seq_stride + (size_t)(head - e.hq_l - e.kg.hkv_l) * e.kg.smax * d;
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) {
+                            e.vc[slab + kv_v_offset(pos, i0 + x, d)] = f32_to_bf16(lo[x]);
+                            e.vc[slab + kv_v_offset(pos, i0 + half + x, d)] = f32_to_bf16(hi[x]);
+                        }
+                    }
+                }
             }
+        }
+        if (MODE == DEC_RESID && !e.last_layer) {
+            // sum of squares of this wave's 32 FM features of the token: the two lane halves hold disjoint rows
+            ssq += __shfl_xor(ssq, 32, 64);
+            if (hl == 0 && tv) {
+                const int grp = (bm * TA + wm * FM * 2) * 16 / GEMM_SSQ_COLS;
+                e.ssq_out[(size_t)grp * T + token] = ssq;
+            }
+        }
     }
 }
 
-template <int FM, int FT, int S>
-static void launch_cfg(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, int k_tiles, int n_tiles, int t_tiles,
-                       int T, hipStream_t s) {
+template <int FM, int FT, int S, int MODE>
+static void launch_cfg(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles, int n_tiles, int t_tiles, int T,
+                       const GemmEpi &e, hipStream_t s) {
     const int n_blocks = (n_tiles + 4 * FM - 1) / (4 * FM), t_blocks = (t_tiles + 4 * FT - 1) / (4 * FT);
     const int total = n_blocks * t_blocks;
     const int grid = (total + 7) / 8 * 8;
-    auto kern = gemm_mfma_kernel<FM, FT, S>;
+    auto kern = gemm_mfma_kernel<FM, FT, S, MODE>;
     const size_t dyn = (size_t)S * (4 * FM + 4 * FT) * 64 * sizeof(bf16x8);
     static bool raised = false;           // more than the default 64 KB of LDS per block
     if (!raised) {
@@ -137,21 +271,103 @@ static void launch_cfg(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, in
                                   (int)dyn);
         raised = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), dyn, s, Wp, Xp, out, N, k_tiles, n_tiles, t_tiles, T, n_blocks,
-                       t_blocks);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), dyn, s, Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, n_blocks, t_blocks,
+                       e);
 }
 
-void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, float *out, int N, int K, int T, hipStream_t s) {
+template <int MODE>
+static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, hipStream_t s) {
     const int k_tiles = K / 32, n_tiles = N / 16, t_tiles = (T + 15) / 16;
     static const int force = std::getenv("HEXGEN_GEMM_TILE") ? std::atoi(std::getenv("HEXGEN_GEMM_TILE")) : 0;
     // tiles of 256 x 256 once they fill the chip; smaller tiles for small problems
     const long big = (long)((n_tiles + 15) / 16) * ((t_tiles + 15) / 16);
     int cfg = big >= 200 ? 88 : ((long)((n_tiles + 15) / 16) * ((t_tiles + 7) / 8) >= 200 ? 84 : 44);
     if (force) cfg = force;
-#define HX_G(FM, FT, S) launch_cfg<FM, FT, S>(Wp, Xp, out, N, k_tiles, n_tiles, t_tiles, T, s)
+    // the RESID epilogue emits one sum-of-squares partial per wave: its 32 FM features must be 128
+    if (MODE == DEC_RESID && cfg != 88 && cfg != 84) cfg = 84;
+#define HX_G(FM, FT, S) launch_cfg<FM, FT, S, MODE>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, s)
     if (cfg == 88) HX_G(4, 4, 4);
     else if (cfg == 84) HX_G(4, 2, 4);
     else if (cfg == 48) HX_G(2, 4, 4);
     else HX_G(2, 2, 4);
 #undef HX_G
+}
+
+void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, hipStream_t s) {
+    switch (e.mode) {
+        case DEC_RAW: launch_mode<DEC_RAW>(Wp, Xp, N, K, T, e, s); break;
+        case DEC_QKV: launch_mode<DEC_QKV>(Wp, Xp, N, K, T, e, s); break;
+        case DEC_RESID: launch_mode<DEC_RESID>(Wp, Xp, N, K, T, e, s); break;
+        case DEC_SWIGLU: launch_mode<DEC_SWIGLU>(Wp, Xp, N, K, T, e, s); break;
+    }
+}
+
+// -------------------------------------------------------------------------------------------------
+// Prefill prologue: stage input rows (bf16, or fp32 for the validation surface) -> fp32 residual stream,
+// (x * gain) in fragment tiles, sums of squares per 128-column group.  One 256-thread block per row.
+// -------------------------------------------------------------------------------------------------
+template <bool IN_BF16>
+__global__ __launch_bounds__(256) void prefill_prologue_kernel(const void *__restrict__ in, float *__restrict__ h_out,
+                                                              const float *__restrict__ g, bf16_t *__restrict__ hg,
+                                                              float *__restrict__ ssq_out, int T, int H) {
+    const int t = blockIdx.x;
+    const int chunks = H >> 3;                 // 8-column chunks; 16 consecutive chunks = one 128-column group
+    for (int c0 = 0; c0 < chunks; c0 += 256) {
+        const int c = c0 + threadIdx.x;
+        float ss = 0.f;
+        if (c < chunks) {
+            float x[8];
+            if (IN_BF16) {
+                uint4 raw = *reinterpret_cast<const uint4 *>(reinterpret_cast<const bf16_t *>(in) + (size_t)t * H + c * 8);
+                const bf16_t *eh = reinterpret_cast<const bf16_t *>(&raw);
+#pragma unroll
+                for (int jx = 0; jx < 8; ++jx) x[jx] = bf16_to_f32(eh[jx]);
+            } else {
+                const float4 *p = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(in) + (size_t)t * H + c * 8);
+                float4 a = p[0], b = p[1];
+                x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+            }
+            if (h_out) {
+                *reinterpret_cast<float4 *>(h_out + h_tile_offset(t, c * 8, H)) = make_float4(x[0], x[1], x[2], x[3]);
+                *reinterpret_cast<float4 *>(h_out + h_tile_offset(t, c * 8 + 4, H)) = make_float4(x[4], x[5], x[6], x[7]);
+            }
+            const float4 *gp = reinterpret_cast<const float4 *>(g + c * 8);
+            float4 g0 = gp[0], g1 = gp[1];
+            uint4 o;
+            o.x = pack_bf16x2(x[0] * g0.x, x[1] * g0.y);
+            o.y = pack_bf16x2(x[2] * g0.z, x[3] * g0.w);
+            o.z = pack_bf16x2(x[4] * g1.x, x[5] * g1.y);
+            o.w = pack_bf16x2(x[6] * g1.z, x[7] * g1.w);
+            *reinterpret_cast<uint4 *>(hg + frag_offset(t, c * 8, H >> 5)) = o;
+#pragma unroll
+            for (int jx = 0; jx < 8; ++jx) ss += x[jx] * x[jx];
+        }
+        ss += __shfl_xor(ss, 1, 64);
+        ss += __shfl_xor(ss, 2, 64);
+        ss += __shfl_xor(ss, 4, 64);
+        ss += __shfl_xor(ss, 8, 64);
+        if ((threadIdx.x & 15) == 0 && c < chunks) ssq_out[(size_t)(c >> 4) * T + t] = ss;
+    }
+}
+
+void launch_prefill_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg, float *ssq_out,
+                             int T, int H, hipStream_t s) {
+    if (T <= 0) return;
+    if (in_is_bf16)
+        hipLaunchKernelGGL(prefill_prologue_kernel<true>, dim3(T), dim3(256), 0, s, in, h_out, g, hg, ssq_out, T, H);
+    else
+        hipLaunchKernelGGL(prefill_prologue_kernel<false>, dim3(T), dim3(256), 0, s, in, h_out, g, hg, ssq_out, T, H);
+}
+
+// tiled residual stream -> row-major fp32 (debug taps)
+__global__ void untile_h_kernel(const float *__restrict__ h_tiled, float *__restrict__ out, int T, int H) {
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i >= (int64_t)T * H) return;
+    const int t = (int)(i / H), n = (int)(i % H);
+    *reinterpret_cast<float4 *>(out + i) = *reinterpret_cast<const float4 *>(h_tiled + h_tile_offset(t, n, H));
+}
+void launch_untile_h(const float *h_tiled, float *out, int T, int H, hipStream_t s) {
+    const int64_t n4 = (int64_t)T * H / 4;
+    if (n4 <= 0) return;
+    hipLaunchKernelGGL(untile_h_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, h_tiled, out, T, H);
 }

@@ -30,7 +30,6 @@
 
 namespace {
 
-constexpr int kMaxKSplit = 16;
 constexpr int kDecodeMaxRows = 32;      // rows handled by the weight-streaming decode kernels
 constexpr int kMaxAttnSplit = 32;
 
@@ -72,7 +71,8 @@ struct Workspace {
     bf16_t *xa_n = nullptr, *xa_o = nullptr, *xa_u = nullptr;   // decode operands, compact hi/lo layout [32][K][2]
     bf16_t *q_lo = nullptr;
     float *att_o = nullptr, *att_ml = nullptr;
-    float *ssq = nullptr;                       // 2 x [H/16 units][DEC_SSQ_STRIDE] sums of squares
+    float *ssq = nullptr;                       // decode: 2 x [H/16 units][DEC_SSQ_STRIDE] sums of squares
+    float *ssq_pf = nullptr;                    // prefill: 2 x [H/128][T] sums of squares
     // fp32 path
     float *n32 = nullptr, *q32 = nullptr, *o32 = nullptr, *u32 = nullptr;
     // row bookkeeping
@@ -115,7 +115,7 @@ namespace {
 size_t esize(hexgen_dtype_t dt) { return dt == HEXGEN_F32 ? 4 : 2; }
 
 void free_ws(Workspace &w) {
-    void *ptrs[] = {w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.xa_n, w.xa_o, w.xa_u, w.q_lo, w.ssq, w.att_o, w.att_ml, w.n32, w.q32, w.o32, w.u32,
+    void *ptrs[] = {w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.xa_n, w.xa_o, w.xa_u, w.q_lo, w.ssq, w.ssq_pf, w.att_o, w.att_ml, w.n32, w.q32, w.o32, w.u32,
                     w.row_seq, w.row_pos, w.cu_rows, w.pos0};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
@@ -142,15 +142,16 @@ hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
     st->ws_batch_cap = 0;
     const size_t T = (size_t)rows, T16 = (size_t)round_up(rows, 16);
     const size_t nmax = (size_t)std::max(std::max(st->nqkv, st->H), 2 * st->F_l);
-    const size_t part_rows = std::max<size_t>(T, (size_t)kMaxKSplit * std::min(rows, kDecodeMaxRows));
-    HX_TRY(dmalloc(&w.h, T * st->H));
-    HX_TRY(dmalloc(&w.part, part_rows * nmax));
-    HX_TRY(dmalloc(&w.p32, T * st->H));
+    HX_TRY(dmalloc(&w.h, (size_t)round_up(rows, 32) * st->H));
+    if (st->dtype == HEXGEN_F32) {
+        HX_TRY(dmalloc(&w.part, T * nmax));
+        HX_TRY(dmalloc(&w.p32, T * st->H));
+    }
     if (st->dtype == HEXGEN_BF16) {
         HX_TRY(dmalloc(&w.n, T16 * st->H));
         HX_TRY(dmalloc(&w.o, T16 * st->qw));
         HX_TRY(dmalloc(&w.u, T16 * st->F_l));
-        HX_TRY(dmalloc(&w.q, T * st->qw));
+        HX_TRY(dmalloc(&w.q, T16 * st->qw));
         const size_t drows = (size_t)std::min(rows, kDecodeMaxRows);
         HX_TRY(dmalloc(&w.xa_n, 2 * drows * st->H));
         HX_TRY(dmalloc(&w.xa_o, 2 * drows * st->qw));
@@ -160,6 +161,7 @@ hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
         HX_TRY(dmalloc(&w.att_ml, drows * st->hq_l * kMaxAttnSplit * 2));
         const size_t ssq_n = 2 * (size_t)(st->H / 16) * DEC_SSQ_STRIDE;
         HX_TRY(dmalloc(&w.ssq, ssq_n));
+        HX_TRY(dmalloc(&w.ssq_pf, 2 * (size_t)(st->H / GEMM_SSQ_COLS + 1) * T));
         HX_HIP(hipMemset(w.ssq, 0, ssq_n * sizeof(float)));
         // padded rows of the packed operands are read by the GEMM tiles: keep them finite
         HX_HIP(hipMemset(w.n, 0, T16 * st->H * sizeof(bf16_t)));
@@ -246,55 +248,87 @@ KvGeom geom(const hexgen_stage *st, const hexgen_kv_cache *kv) {
     return g;
 }
 
-// ---- bf16 prefill (GEMM) flow: projections write fp32 to ws.part, small kernels finish each step ----
-void gemm_bf16(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xp, int N, int K, int slot,
-               hipStream_t s) {
+// ---- bf16 prefill flow: five kernels per layer; RoPE / cache append, residual + next-norm operand and SwiGLU
+// run in the GEMM epilogues, RMSNorm enters as a per-token scale after the contraction ---------------------
+GemmEpi gemm_epi_base(hexgen_stage *st, int mode) {
+    GemmEpi e;
+    std::memset(&e, 0, sizeof(e));
+    e.mode = mode;
+    e.norm_dim = st->H;
+    e.eps = st->eps;
+    return e;
+}
+
+void gemm_bf16(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xp, int N, int K, const GemmEpi &e,
+               int slot, hipStream_t s) {
     st->prof.mark(slot, s);
-    launch_gemm_mfma(static_cast<const bf16_t *>(Wp), Xp, st->ws.part, N, K, r.T, s);
+    launch_gemm_mfma(static_cast<const bf16_t *>(Wp), Xp, N, K, r.T, e, s);
     st->prof.mark(slot, s);
 }
 
-// attention sub-layer from packed n (already normalised) to the W_O output in ws.part
-void attn_prefill_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Rows &r, hipStream_t s) {
+// QKV projection (+RoPE, cache append) and causal attention; leaves o (fragment tiles) in the workspace
+void attn_prefill_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Rows &r, const float *ssq_in,
+                       hipStream_t s) {
     Workspace &w = st->ws;
     const Layer &ly = st->layers[layer];
     const KvGeom kg = geom(st, kv);
     bf16_t *kc = static_cast<bf16_t *>(kv->k) + (size_t)layer * kv->layer_stride;
     bf16_t *vc = static_cast<bf16_t *>(kv->v) + (size_t)layer * kv->layer_stride;
-    gemm_bf16(st, r, ly.wqkv, w.n, st->nqkv, st->H, PROF_QKV, s);
+    GemmEpi e = gemm_epi_base(st, DEC_QKV);
+    e.ssq_in = ssq_in;
+    e.hq_l = st->hq_l; e.kg = kg; e.rm = r.rm; e.cos_tab = kv->cos_tab; e.sin_tab = kv->sin_tab;
+    e.q = w.q; e.kc = kc; e.vc = vc;
+    gemm_bf16(st, r, ly.wqkv, w.n, st->nqkv, st->H, e, PROF_QKV, s);
     st->prof.mark(PROF_ATTN, s);
-    launch_qkv_rope_append(w.part, 1, r.T, st->hq_l, kg, r.rm, kv->cos_tab, kv->sin_tab, w.q, nullptr, kc, vc, s);
     launch_attn_prefill(w.q, kc, vc, kg, st->hq_l, w.cu_rows, w.pos0, r.batch, r.max_new, w.o, s);
     st->prof.mark(PROF_ATTN, s);
-    gemm_bf16(st, r, ly.wo, w.o, st->H, st->qw, PROF_WO, s);
-}
-
-void ffn_prefill_bf16(hexgen_stage *st, int layer, const Rows &r, hipStream_t s) {
-    Workspace &w = st->ws;
-    const Layer &ly = st->layers[layer];
-    gemm_bf16(st, r, ly.w13, w.n, 2 * st->F_l, st->H, PROF_W13, s);
-    launch_reduce_swiglu(w.part, 1, w.u, nullptr, r.T, st->F_l, s);
-    gemm_bf16(st, r, ly.w2, w.u, st->H, st->F_l, PROF_W2, s);
 }
 
 hexgen_status_t forward_prefill_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
                                      void *out_partial, void *out_resid, hipStream_t s) {
     Workspace &w = st->ws;
-    launch_rmsnorm_pack(hidden_in, 1, w.h, st->layers[0].g_attn, w.n, nullptr, r.T, st->H, st->eps, s);
+    float *ssq_a = w.ssq_pf, *ssq_f = w.ssq_pf + (size_t)(st->H / GEMM_SSQ_COLS) * r.T;
+    launch_prefill_prologue(hidden_in, 1, w.h, st->layers[0].g_attn, w.n, ssq_a, r.T, st->H, s);
     for (int l = 0; l < st->L; ++l) {
-        if (st->taps[l])
-            HX_HIP(hipMemcpyAsync(st->taps[l], w.h, sizeof(float) * (size_t)r.T * st->H, hipMemcpyDeviceToDevice, s));
-        attn_prefill_bf16(st, kv, l, r, s);
-        launch_reduce_resid_norm(w.part, 1, w.h, st->layers[l].g_ffn, w.n, nullptr, r.T, st->H, st->eps, s);
-        ffn_prefill_bf16(st, l, r, s);
-        if (l + 1 < st->L) {
-            launch_reduce_resid_norm(w.part, 1, w.h, st->layers[l + 1].g_attn, w.n, nullptr, r.T, st->H, st->eps, s);
-        } else {
-            launch_store_out(w.part, out_partial, 1, (int64_t)r.T * st->H, s);
-            if (out_resid) launch_store_out(w.h, out_resid, 1, (int64_t)r.T * st->H, s);
-        }
+        const Layer &ly = st->layers[l];
+        const bool last = l + 1 == st->L;
+        if (st->taps[l]) launch_untile_h(w.h, static_cast<float *>(st->taps[l]), r.T, st->H, s);
+        attn_prefill_bf16(st, kv, l, r, ssq_a, s);
+        GemmEpi e = gemm_epi_base(st, DEC_RESID);
+        e.h = w.h; e.g_next = ly.g_ffn; e.hg = w.n; e.ssq_out = ssq_f;
+        gemm_bf16(st, r, ly.wo, w.o, st->H, st->qw, e, PROF_WO, s);
+        e = gemm_epi_base(st, DEC_SWIGLU);
+        e.ssq_in = ssq_f; e.u = w.u; e.F_l = st->F_l;
+        gemm_bf16(st, r, ly.w13, w.n, 2 * st->F_l, st->H, e, PROF_W13, s);
+        e = gemm_epi_base(st, DEC_RESID);
+        e.h = w.h; e.hg = w.n; e.ssq_out = ssq_a;
+        e.g_next = last ? nullptr : st->layers[l + 1].g_attn;
+        e.last_layer = last ? 1 : 0;
+        e.out_partial = static_cast<bf16_t *>(out_partial);
+        e.out_resid = static_cast<bf16_t *>(out_resid);
+        gemm_bf16(st, r, ly.w2, w.u, st->H, st->F_l, e, PROF_W2, s);
     }
     return HEXGEN_OK;
+}
+
+// one sub-layer for the validation surface, prefill kernels; h fp32 in, raw fp32 partial out
+void sublayer_prefill_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, int which, const Rows &r, const float *h,
+                           float *p_out, hipStream_t s) {
+    Workspace &w = st->ws;
+    const Layer &ly = st->layers[layer];
+    float *ssq = w.ssq_pf;
+    GemmEpi e = gemm_epi_base(st, DEC_RAW);
+    e.raw_out = p_out;
+    launch_prefill_prologue(h, 0, nullptr, which == 0 ? ly.g_attn : ly.g_ffn, w.n, ssq, r.T, st->H, s);
+    if (which == 0) {
+        attn_prefill_bf16(st, kv, layer, r, ssq, s);
+        gemm_bf16(st, r, ly.wo, w.o, st->H, st->qw, e, PROF_WO, s);
+    } else {
+        GemmEpi g = gemm_epi_base(st, DEC_SWIGLU);
+        g.ssq_in = ssq; g.u = w.u; g.F_l = st->F_l;
+        gemm_bf16(st, r, ly.w13, w.n, 2 * st->F_l, st->H, g, PROF_W13, s);
+        gemm_bf16(st, r, ly.w2, w.u, st->H, st->F_l, e, PROF_W2, s);
+    }
 }
 
 // ---- bf16 decode flow (T <= 32 rows): five kernels per layer, everything else fused into their tails ----
@@ -491,7 +525,7 @@ hexgen_status_t hexgen_stage_create(int hidden, int n_heads, int n_kv_heads, int
     if (d != 64 && d != 128) return HEXGEN_ERR_SHAPE;
     const int hq_l = n_heads / tp_degree, hkv_l = n_kv_heads / tp_degree, F_l = ffn / tp_degree;
     if (hq_l / hkv_l > 16) return HEXGEN_ERR_SHAPE;          // one MFMA column block per query group
-    if (dtype == HEXGEN_BF16 && (hidden % 32 || (hq_l * d) % 32 || F_l % 32)) return HEXGEN_ERR_SHAPE;
+    if (dtype == HEXGEN_BF16 && (hidden % 128 || (hq_l * d) % 32 || F_l % 32)) return HEXGEN_ERR_SHAPE;
     if (hidden % 8) return HEXGEN_ERR_SHAPE;
     hexgen_stage *st = new (std::nothrow) hexgen_stage();
     if (!st) return HEXGEN_ERR_OOM;
@@ -834,16 +868,11 @@ hexgen_status_t hexgen_stage_run_sublayer(hexgen_stage_t *st, hexgen_kv_cache_t 
     HX_TRY(setup_rows(st, kv, seq_lens, batch, true, s, &r));
     const float *h = static_cast<const float *>(h_in);
     float *p = static_cast<float *>(partial_out);
-    Workspace &w = st->ws;
     if (st->dtype == HEXGEN_BF16) {
         if (r.decode) {
             sublayer_decode_bf16(st, kv, layer, which, r, h, p, s);
         } else {
-            const Layer &ly = st->layers[layer];
-            launch_rmsnorm_pack(h, 0, nullptr, which == 0 ? ly.g_attn : ly.g_ffn, w.n, nullptr, r.T, st->H, st->eps, s);
-            if (which == 0) attn_prefill_bf16(st, kv, layer, r, s);
-            else ffn_prefill_bf16(st, layer, r, s);
-            HX_HIP(hipMemcpyAsync(p, w.part, sizeof(float) * (size_t)r.T * st->H, hipMemcpyDeviceToDevice, s));
+            sublayer_prefill_bf16(st, kv, layer, which, r, h, p, s);
         }
     } else {
         if (which == 0) attn_f32(st, kv, layer, r, h, p, s);

@@ -28,7 +28,7 @@ PROF_QKV, PROF_WO, PROF_W13, PROF_W2, PROF_ATTN, PROF_CALL = range(6)
 
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled
 # by a copy kernel of known size); see profiles/.  None until measured for the current kernel.
-MEASURED_TRAFFIC_BYTES = None
+MEASURED_TRAFFIC_BYTES = 470_633_000     # profiles/decode_l70_tp2_pmc_traffic.txt
 
 
 def log(msg):
@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="l70_tp2_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="measure what a plain streaming kernel and a register-resident MFMA loop sustain, then exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one rank's share of a stage at its real shape); "
@@ -51,6 +53,10 @@ def main():
     import torch
     import paper_2311_11514_amd as hx
     from workloads import CONFIGS, generate
+
+    if args.calibrate:
+        calibrate(torch, hx)
+        return
 
     cfg = CONFIGS[args.workload]
     assert cfg.kv_context is not None and cfg.dtype == "bf16", "bench workload must be a bf16 decode config"
@@ -95,13 +101,25 @@ def main():
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
+    # three plain copies of known size: the yardstick the profiler's byte counters are scaled by
+    cal_src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+    cal_dst = torch.empty_like(cal_src)
+    for _ in range(3):
+        hx.stream_copy(cal_dst, cal_src, blocks=512)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
     run(W)
     dt = run(K)
     ms_per_step = dt / K * 1e3
     tok_s = b * K / dt
     assert torch.isfinite(outp.float()).all() and torch.isfinite(outr.float()).all()
 
-    # instrumented pass: HIP events on the launch stream around every projection launch
+    # instrumented passes: HIP events on the launch stream; first around the dominant kernel alone (so its
+    # figure carries no other events' overhead), then around every projection for the per-kernel table
+    st.profile_enable(1 << PROF_W13)
+    run(K)
+    w13_ms, w13_n = st.profile_read(PROF_W13)
     st.profile_enable(True)
     run(K)
     slots = {}
@@ -113,9 +131,9 @@ def main():
 
     eb = 2
     H, Fl = cfg.hidden, cfg.ffn_l
-    w13_bytes = H * 2 * Fl * eb + b * H * eb            # weights + activation operand (output is split-K scratch)
-    w13_s = slots["w13"]["avg_us"] * 1e-6
-    achieved = w13_bytes / w13_s / 1e9
+    w13_bytes = H * 2 * Fl * eb + b * H * eb * 2        # weights + hi/lo activation operand (outputs are negligible)
+    w13_us = w13_ms / max(w13_n, 1) * 1e3
+    achieved = w13_bytes / (w13_us * 1e-6) / 1e9
     bytes_by_proj = {"qkv": H * (cfg.hq_l + 2 * cfg.hkv_l) * cfg.head_dim * eb, "wo": cfg.hq_l * cfg.head_dim * H * eb,
                      "w13": H * 2 * Fl * eb, "w2": Fl * H * eb}
     per_kernel = {k: {"avg_us": round(slots[k]["avg_us"], 2),
@@ -137,16 +155,52 @@ def main():
         "us_per_layer": round(ms_per_step * 1e3 / cfg.n_layers, 2),
         "stage_hbm_frac": round(stage_frac, 4),
         "per_kernel": per_kernel,
-        "roofline": {"bound": "hbm", "kernel": "gemv_mfma_kernel (W1/W3 projection)",
+        "roofline": {"bound": "hbm", "kernel": "decode_proj_kernel<1,2,8,4,SWIGLU> (W1/W3 projection + SwiGLU epilogue)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES, "bytes_per_launch": w13_bytes,
-                     "avg_launch_us": round(slots["w13"]["avg_us"], 2)},
+                     "avg_launch_us": round(w13_us, 2), "launches_timed": w13_n},
     }
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, rank, layer0_host, kv_host, X, ctx)
     print(json.dumps(result), flush=True)
+
+
+def calibrate(torch, hx):
+    """Practical ceilings of this machine, printed as a table: HBM streaming (cold: a 2.4 GB buffer is walked
+    through in slices so nothing is re-read from cache) and dense bf16 MFMA from registers."""
+    dev = "cuda"
+    def timed(fn, reps):
+        fn(0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            fn(i + 1)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3          # microseconds
+    big = torch.empty(2400 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+    sink = torch.zeros(1 << 16, dtype=torch.float32, device=dev)
+    print("HBM streaming, cold (MB, blocks of 256 threads, kernel, us, TB/s moved)")
+    for mb in (32, 84, 235, 470):
+        n = mb << 20
+        slices = big.numel() // n
+        for blocks in (512, 4096):
+            us = timed(lambda i: hx.stream_read(big[(i % slices) * n:(i % slices + 1) * n], sink, blocks), 20)
+            print(f"  {mb:4d} {blocks:5d} read  {us:8.1f} {n / us / 1e6:6.2f}")
+            us = timed(lambda i: hx.stream_copy(dst[:n], big[(i % slices) * n:(i % slices + 1) * n], blocks), 20)
+            print(f"  {mb:4d} {blocks:5d} copy  {us:8.1f} {2 * n / us / 1e6:6.2f}")
+    print("dense bf16 MFMA, 4 waves per CU, operands in registers (variant, TFLOP/s, fraction of 2516.6)")
+    names = ["16x16x32, registers only", "32x32x16, registers only", "16x16x32 + GEMM-rate LDS reads",
+             "32x32x16 + GEMM-rate LDS reads"]
+    iters, blocks = 2000, 256
+    for v, name in enumerate(names):
+        us = timed(lambda i: hx.mfma_probe(v, sink, iters, blocks), 3)
+        tf = blocks * 4 * iters * (1 << 20) / us / 1e6
+        print(f"  {name:34s} {tf:8.1f} {tf / 2516.6:6.3f}")
 
 
 def cpu_baseline(cfg, rank, layer0, kv_host, X, ctx):

@@ -149,12 +149,12 @@ hexgen_status_t hexgen_stage_set_tap(hexgen_stage_t *st, int layer, void *h_dump
 
 /* Measurement surface.  While enabled, prefill / decode record HIP events on the caller's stream
  * around each projection launch, so per-kernel time can be read without an external profiler
- * (this costs a few microseconds per launch: enable it for measurement passes only).
- * Slots: 0 QKV projection, 1 W_O, 2 W1/W3 (+SwiGLU), 3 W2, 4 RoPE + cache append + attention,
- * 5 the whole call.  enable(on) synchronises and clears earlier records.  read() synchronises and
- * returns the summed time in milliseconds and the number of timed launches of the slot.
+ * (this costs a few microseconds per timed launch: enable it for measurement passes only).
+ * Slots: 0 QKV projection, 1 W_O, 2 W1/W3 (+SwiGLU), 3 W2, 4 attention, 5 the whole call.
+ * enable(slot_mask): bit i selects slot i (0 = off, 63 = all); synchronises and clears earlier records.
+ * read() synchronises and returns the summed time in milliseconds and the number of timed launches.
  */
-hexgen_status_t hexgen_stage_profile_enable(hexgen_stage_t *st, int on);
+hexgen_status_t hexgen_stage_profile_enable(hexgen_stage_t *st, int slot_mask);
 hexgen_status_t hexgen_stage_profile_read(hexgen_stage_t *st, int slot, double *total_ms, int64_t *count);
 
 /* HBM calibration kernels of known size (used by the benchmark and to scale profiler byte counters):
@@ -163,6 +163,12 @@ hexgen_status_t hexgen_stage_profile_read(hexgen_stage_t *st, int slot, double *
  */
 hexgen_status_t hexgen_stream_copy(void *dst, const void *src, int64_t bytes, int blocks, void *stream);
 hexgen_status_t hexgen_stream_read(const void *src, void *sink, int64_t bytes, int blocks, void *stream);
+
+/* Matrix-core calibration: `blocks` 4-wave blocks each run `iters` k-steps of a 128 x 128 x 32 wave tile out of
+ * registers (2^20 flop per wave and iteration).  variant 0: 16x16x32 bf16 MFMA, 1: 32x32x16 bf16 MFMA, 2 / 3: the
+ * same plus the LDS fragment reads a GEMM issues.  `sink`: device, >= 256 floats.  Time it with events.
+ */
+hexgen_status_t hexgen_mfma_probe(int variant, void *sink, int iters, int blocks, void *stream);
 
 /* Bytes of device memory the stage holds for weights (after repacking), for reporting. */
 int64_t hexgen_stage_weight_bytes(const hexgen_stage_t *st);

@@ -44,6 +44,7 @@ SIGNATURES = {
     "hexgen_stage_weight_bytes": (_i64, [_vp]),
     "hexgen_stream_copy": (_i, [_vp, _vp, _i64, _i, _vp]),
     "hexgen_stream_read": (_i, [_vp, _vp, _i64, _i, _vp]),
+    "hexgen_mfma_probe": (_i, [_i, _vp, _i, _i, _vp]),
     "hexgen_stage_profile_enable": (_i, [_vp, _i]),
     "hexgen_stage_profile_read": (_i, [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64)]),
 }
@@ -151,8 +152,10 @@ class Stage:
         self._taps[layer] = h_dump          # keep the buffer alive
         _check(lib.hexgen_stage_set_tap(self.handle, layer, _ptr(h_dump)), "hexgen_stage_set_tap")
 
-    def profile_enable(self, on: bool):
-        _check(lib.hexgen_stage_profile_enable(self.handle, int(on)), "hexgen_stage_profile_enable")
+    def profile_enable(self, slot_mask):
+        """slot_mask: bit i times slot i (True = all six slots, False / 0 = off)."""
+        mask = 63 if slot_mask is True else int(slot_mask)
+        _check(lib.hexgen_stage_profile_enable(self.handle, mask), "hexgen_stage_profile_enable")
 
     def profile_read(self, slot: int):
         """(total milliseconds, number of timed launches) of a slot; see include/hexgen.h."""
@@ -216,6 +219,10 @@ def stream_copy(dst: torch.Tensor, src: torch.Tensor, blocks: int = 4096, stream
 def stream_read(src: torch.Tensor, sink: torch.Tensor, blocks: int = 4096, stream=None):
     nbytes = src.numel() * src.element_size()
     _check(lib.hexgen_stream_read(_ptr(src), _ptr(sink), nbytes, blocks, _stream_handle(stream)), "hexgen_stream_read")
+
+
+def mfma_probe(variant: int, sink: torch.Tensor, iters: int, blocks: int, stream=None):
+    _check(lib.hexgen_mfma_probe(variant, _ptr(sink), iters, blocks, _stream_handle(stream)), "hexgen_mfma_probe")
 
 
 def accumulate_f32(dst: torch.Tensor, src: torch.Tensor, stream=None):

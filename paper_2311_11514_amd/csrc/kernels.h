@@ -41,6 +41,8 @@ void launch_advance_lens(int32_t *lens, int b, hipStream_t s);
 // plain streaming kernels of known size (HBM calibration for the benchmarks and profiler counters)
 void launch_stream_copy(const void *src, void *dst, int64_t bytes, int blocks, hipStream_t s);
 void launch_stream_read(const void *src, float *sink, int64_t bytes, int blocks, hipStream_t s);
+// register-resident MFMA loops: 4 waves per block, per wave and iteration 2^20 flop (one 128 x 128 x 32 k-step)
+void launch_mfma_probe(int variant, float *sink, int iters, int blocks, hipStream_t s);
 
 // ---- bf16 path (kernels_bf16_*.hip) ---------------------------------------------------------
 

@@ -166,3 +166,83 @@ void launch_stream_read(const void *src, float *sink, int64_t bytes, int blocks,
     hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(256), 0, s, static_cast<const u32x4 *>(src), sink,
                        bytes / 16);
 }
+
+// ---- measurement utility: register-resident MFMA loops (what the matrix cores sustain on this machine) ------
+// variant 0: v_mfma_f32_16x16x32_bf16, 64 independent accumulators per wave; variant 1: v_mfma_f32_32x32x16_bf16,
+// 16 accumulators; variants 2 / 3: the same with the LDS fragment reads of a 128 x 128 wave tile (16 reads per
+// 32-deep k-step).  One 4-wave block per launch slot; every block runs `iters` k-steps of 2^20 flop per wave.
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+template <int VARIANT>
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float *sink, int iters) {
+    __shared__ bf16x8 sm[32][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = threadIdx.x; i < 32 * 64; i += 256) { bf16x8 one = {1, 1, 1, 1, 1, 1, 1, 1}; sm[i >> 6][i & 63] = one; }
+    __syncthreads();
+    constexpr bool LDS = VARIANT >= 2;
+    float total = 0.f;
+    if (VARIANT == 0 || VARIANT == 2) {
+        floatx4 acc[8][8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        bf16x8 a[8], b[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { a[i] = sm[i][lane]; b[i] = sm[8 + i][lane]; }
+        for (int it = 0; it < iters; ++it) {
+            if (LDS) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) b[j] = sm[(16 + j + it) & 31][lane];
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (LDS) a[i] = sm[(i + it + wave) & 31][lane];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) total += acc[i][j][0] + acc[i][j][3];
+    } else {
+        floatx16 acc[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        bf16x8 a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { a[i] = sm[i][lane]; b[i] = sm[8 + i][lane]; }
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh) {
+                if (LDS) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) b[j] = sm[(16 + j + it + kh * 4) & 31][lane];
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (LDS) a[i] = sm[(i + it + wave + kh * 4) & 31][lane];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) total += acc[i][j][0] + acc[i][j][7];
+    }
+    if (total == 123.456f) sink[threadIdx.x] = total;      // practically never: keeps the math alive
+}
+void launch_mfma_probe(int variant, float *sink, int iters, int blocks, hipStream_t s) {
+    switch (variant) {
+        case 0: hipLaunchKernelGGL(mfma_probe_kernel<0>, dim3(blocks), dim3(256), 0, s, sink, iters); break;
+        case 1: hipLaunchKernelGGL(mfma_probe_kernel<1>, dim3(blocks), dim3(256), 0, s, sink, iters); break;
+        case 2: hipLaunchKernelGGL(mfma_probe_kernel<2>, dim3(blocks), dim3(256), 0, s, sink, iters); break;
+        default: hipLaunchKernelGGL(mfma_probe_kernel<3>, dim3(blocks), dim3(256), 0, s, sink, iters); break;
+    }
+}

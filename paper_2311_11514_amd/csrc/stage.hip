@@ -44,10 +44,10 @@ struct Layer {
 // Optional per-slot timing with HIP events recorded on the caller's stream (measurement surface).
 enum { PROF_QKV = 0, PROF_WO = 1, PROF_W13 = 2, PROF_W2 = 3, PROF_ATTN = 4, PROF_CALL = 5, PROF_SLOTS = 6 };
 struct Profiler {
-    bool on = false;
+    unsigned mask = 0;                          // bit i set: slot i is timed
     std::vector<hipEvent_t> ev[PROF_SLOTS];     // start, stop, start, stop, ...
     void mark(int slot, hipStream_t s) {
-        if (!on) return;
+        if (!(mask >> slot & 1u)) return;
         hipEvent_t e;
         if (hipEventCreate(&e) != hipSuccess) return;
         (void)hipEventRecord(e, s);
@@ -887,11 +887,11 @@ hexgen_status_t hexgen_accumulate_f32(void *dst, const void *src, int64_t n, voi
     return HEXGEN_OK;
 }
 
-hexgen_status_t hexgen_stage_profile_enable(hexgen_stage_t *st, int on) {
-    if (!st) return HEXGEN_ERR_INVALID_ARG;
+hexgen_status_t hexgen_stage_profile_enable(hexgen_stage_t *st, int slot_mask) {
+    if (!st || slot_mask < 0 || slot_mask >= (1 << PROF_SLOTS)) return HEXGEN_ERR_INVALID_ARG;
     HX_HIP(hipDeviceSynchronize());
     st->prof.clear();
-    st->prof.on = on != 0;
+    st->prof.mask = (unsigned)slot_mask;
     return HEXGEN_OK;
 }
 
@@ -921,6 +921,12 @@ hexgen_status_t hexgen_stream_copy(void *dst, const void *src, int64_t bytes, in
 hexgen_status_t hexgen_stream_read(const void *src, void *sink, int64_t bytes, int blocks, void *stream) {
     if (!sink || !src || bytes < 0 || bytes % 16 || blocks <= 0) return HEXGEN_ERR_INVALID_ARG;
     launch_stream_read(src, static_cast<float *>(sink), bytes, blocks, static_cast<hipStream_t>(stream));
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_mfma_probe(int variant, void *sink, int iters, int blocks, void *stream) {
+    if (!sink || variant < 0 || variant > 3 || iters <= 0 || blocks <= 0) return HEXGEN_ERR_INVALID_ARG;
+    launch_mfma_probe(variant, static_cast<float *>(sink), iters, blocks, static_cast<hipStream_t>(stream));
     return HEXGEN_OK;
 }
 

@@ -180,6 +180,32 @@ class OracleStage:
         u = silu(n @ W["w1"]) * (n @ W["w3"])
         return u @ W["w2"]
 
+    # ---- one layer, chosen output rows only (full-size workloads) ------------------------------------
+    def layer_rows(self, layer: int, h_seq, rows: Sequence[int]):
+        """Solo-mode output of `layer` for ONE sequence given the residual stream h_seq [S,H] entering the
+        layer (positions 0..S-1), evaluated only at the positions in `rows`.  Same definition as
+        attn_partial / ffn_partial: K and V are formed for every position (they are needed by later rows),
+        the query, attention, W_O, residual and FFN only for the chosen rows.  Returns (h_out [len(rows),H]
+        = residual stream after the layer, K [S,hkv_l,d] after rotation, V [S,hkv_l,d])."""
+        W = self.layers[layer]
+        h = _f64(h_seq)
+        S = h.shape[0]
+        n = rmsnorm(h, W["g_attn"], self.eps)
+        pos = np.arange(S)
+        K = rope((n @ W["wk"]).reshape(S, self.hkv_l, self.d), pos, self.theta)
+        V = (n @ W["wv"]).reshape(S, self.hkv_l, self.d)
+        rows = list(rows)
+        q = rope((n[rows] @ W["wq"]).reshape(len(rows), self.hq_l, self.d), np.asarray(rows), self.theta)
+        o = np.zeros((len(rows), self.hq_l, self.d), F64)
+        scale = 1.0 / np.sqrt(float(self.d))
+        for a, i in enumerate(rows):
+            for j in range(self.hq_l):
+                c = j // self.G
+                w = softmax((K[: i + 1, c, :] @ q[a, j]) * scale)
+                o[a, j] = w @ V[: i + 1, c, :]
+        h_mid = h[rows] + o.reshape(len(rows), self.hq_l * self.d) @ W["wo"]
+        return h_mid + self.ffn_partial(layer, h_mid), K, V
+
     # ---- solo mode: this rank alone ---------------------------------------------------
     def forward(self, cache: KVCache, hidden_in, seq_of_row: Sequence[int], taps: dict = None):
         """Returns (out_partial, out_resid): last layer's FFN partial (no residual inside) and the

@@ -122,3 +122,76 @@ def test_prefill_workload_one_sequence_full_depth():
         worst = max(worst, ea, ef)
         assert ea < TOL["bf16"] and ef < TOL["bf16"], f"layer {l}: attn {ea:.3e} ffn {ef:.3e}"
     print(f"teacher-forced per-layer worst per-row L2 err {worst:.3e}", flush=True)
+
+
+def test_full_width_80_layer_stage_sampled():
+    """The full-width 80-layer stage (136.9 GB of weights), 32 ragged prompts of 128..4096 tokens, then decode.
+    The oracle cannot run it whole; it recomputes layer 0 for the shortest and the longest sequence at
+    sampled rows (prefill) and for the same sequences' decode rows, against the GPU's residual stream
+    entering layer 1 (a tap, i.e. a GPU output).  At full depth the GPU run is checked for finiteness and
+    for bit-identical repetition."""
+    import paper_2311_11514_amd as hx
+    from oracle import stage_oracle as so
+    cfg = CONFIGS["l70_full"]
+    lens = generate.prompt_lengths(cfg)
+    T = sum(lens)
+    st = hx.Stage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, cfg.n_layers, 1, 0, cfg.dtype, cfg.rms_eps,
+                  cfg.rope_theta)
+    ora = so.OracleStage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, 1, 1, 0, cfg.rms_eps, cfg.rope_theta)
+    for l in range(cfg.n_layers):
+        w = generate.layer_weights(cfg, l, device="cuda")
+        args = [w[k] for k in ORDER]
+        st.load_layer(l, *args)
+        if l == 0:
+            ora.load_layer(0, *args)
+        del w, args
+    print(f"loaded {st.weight_bytes() / 1e9:.1f} GB of weights; {T} prompt rows", flush=True)
+    X = generate.hidden_rows(cfg, T, device="cuda")
+    kv = st.kv_cache_create(cfg.batch, max(lens) + 8)
+    tap = torch.empty(T, cfg.hidden, dtype=torch.float32, device="cuda")
+    st.set_tap(1, tap)
+    xin = to_dev(X, cfg)
+    outp, outr = torch.empty_like(xin), torch.empty_like(xin)
+    st.prefill(kv, xin, lens, outp, outr)
+    torch.cuda.synchronize()
+    assert torch.isfinite(outp.float()).all() and torch.isfinite(outr.float()).all()
+    first = (outp.clone(), outr.clone())
+    h1 = tap.cpu().numpy()
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    rng = np.random.default_rng(5)
+    caches = {}
+    for s in (int(np.argmin(lens)), int(np.argmax(lens))):
+        n = lens[s]
+        rows = sorted(set([0, n - 1] + [int(v) for v in rng.integers(0, n, 16)]))
+        ref, K, V = ora.layer_rows(0, X[cu[s]: cu[s] + n].cpu(), rows)
+        err = row_rel_err(h1[cu[s]: cu[s] + n][rows], ref)
+        print(f"prefill layer 0, sequence {s} (len {n}), {len(rows)} sampled rows: per-row L2 err {err:.3e}", flush=True)
+        assert err < TOL["bf16"]
+        kk, vv = kv.read(0, s, 0, n)
+        d = cfg.head_dim
+        assert row_rel_err(kk.numpy().reshape(-1, d), K.reshape(-1, d)) < TOL["bf16"]
+        assert row_rel_err(vv.numpy().reshape(-1, d), V.reshape(-1, d)) < TOL["bf16"]
+        caches[s] = (K, V)
+    # bit-identical repetition of the whole 80-layer prefill
+    st.prefill(kv, xin, lens, outp, outr)
+    torch.cuda.synchronize()
+    assert torch.equal(outp, first[0]) and torch.equal(outr, first[1])
+    # decode: layer 0 of the two sequences against the oracle, full depth for finiteness
+    tapd = torch.empty(cfg.batch, cfg.hidden, dtype=torch.float32, device="cuda")
+    st.set_tap(1, tapd)
+    for step in range(2):
+        x = generate.hidden_rows(cfg, cfg.batch, stream_id=1 + step, device="cuda")
+        pg, hg = gpu_decode(st, kv, cfg, step, x.cpu())
+        assert np.isfinite(pg).all() and np.isfinite(hg).all()
+        hd = tapd.cpu().numpy()
+        for s, (K, V) in caches.items():
+            oc = ora.new_cache(1)
+            oc.fill(0, 0, K, V)
+            xs = so._f64(x[s: s + 1])
+            h_mid = xs + ora.attn_partial(0, oc, xs, [0])
+            ref = h_mid + ora.ffn_partial(0, h_mid)
+            caches[s] = (oc.k[0][0], oc.v[0][0])
+            err = row_rel_err(hd[s: s + 1], ref)
+            print(f"decode step {step}, layer 0, sequence {s}: per-row L2 err {err:.3e}", flush=True)
+            assert err < TOL["bf16"]
+    assert kv.get_lengths(cfg.batch) == [n + 2 for n in lens]

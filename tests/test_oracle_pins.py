@@ -331,3 +331,17 @@ def test_greedy_tokens_agree_between_variants(tiny_weights):
         seq = torch.cat([seq, torch.from_numpy(E[toks_c[-1]][None, :])], dim=0)
     assert toks_a == toks_b == toks_c
     assert len(set(toks_a)) >= 1 and all(0 <= t < cfg.vocab for t in toks_a)
+
+
+def test_layer_rows_matches_full_layer(tiny_weights):
+    """The row-sampled single-layer evaluation used at full sizes equals the full solo-mode layer."""
+    cfg = TINY
+    st = make_stage(cfg, 1, n_layers=1, weights=tiny_weights)
+    x = so._f64(generate.hidden_rows(cfg, 40))
+    cache = st.new_cache(1)
+    h_mid = x + st.attn_partial(0, cache, x, [0] * 40)
+    full = h_mid + st.ffn_partial(0, h_mid)
+    rows = [0, 7, 39]
+    got, K, V = st.layer_rows(0, x, rows)
+    assert rel(got, full[rows]) < 1e-13
+    assert rel(K, cache.k[0][0]) < 1e-13 and rel(V, cache.v[0][0]) < 1e-13

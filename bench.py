@@ -42,6 +42,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="l70_tp2_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the prefill leg (second workload)")
     ap.add_argument("--calibrate", action="store_true",
                     help="measure what a plain streaming kernel and a register-resident MFMA loop sustain, then exit")
     args = ap.parse_args()
@@ -164,7 +165,61 @@ def main():
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, rank, layer0_host, kv_host, X, ctx)
+    if not args.no_prefill:
+        del st, kv, X
+        torch.cuda.empty_cache()
+        result["prefill"] = prefill_leg(torch, hx, CONFIGS["l70_tp4_prefill"], generate)
     print(json.dumps(result), flush=True)
+
+
+MFMA_PEAK_TFLOPS = 2516.6      # MI355X published dense bf16 rate
+
+
+def prefill_leg(torch, hx, cfg, generate, reps=5):
+    """Second half of the headline metric: prefill tokens/s of the asymmetric TP4 shard (20 layers, 4 x 512 rows)
+    and the projection GEMMs against the bf16 MFMA peak.  Reported beside the decode figure, not as `value`."""
+    dev, rank = "cuda", cfg.tp_ranks[0]
+    st = hx.Stage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, cfg.n_layers, cfg.tp_degree, rank, cfg.dtype,
+                  cfg.rms_eps, cfg.rope_theta)
+    for l in range(cfg.n_layers):
+        w = generate.layer_weights(cfg, l, device=dev)
+        st.load_layer(l, *[w[k] for k in generate.LAYER_TENSOR_ORDER])
+        del w
+    lens = generate.prompt_lengths(cfg)
+    T = sum(lens)
+    kv = st.kv_cache_create(cfg.batch, max(lens) + 8)
+    X = generate.hidden_rows(cfg, T, device=dev).to(torch.bfloat16).contiguous()
+    outp, outr = torch.empty_like(X), torch.empty_like(X)
+    for _ in range(2):
+        st.prefill(kv, X, lens, outp, outr)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        st.prefill(kv, X, lens, outp, outr)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    assert torch.isfinite(outp.float()).all()
+    st.profile_enable(0b1111)
+    st.prefill(kv, X, lens, outp, outr)
+    H, d = cfg.hidden, cfg.head_dim
+    flops = {"qkv": 2 * T * H * (cfg.hq_l + 2 * cfg.hkv_l) * d, "wo": 2 * T * cfg.hq_l * d * H,
+             "w13": 2 * T * H * 2 * cfg.ffn_l, "w2": 2 * T * cfg.ffn_l * H}
+    gemm = {}
+    tot_f, tot_t = 0.0, 0.0
+    for slot, name in enumerate(("qkv", "wo", "w13", "w2")):
+        ms, n = st.profile_read(slot)
+        us = ms / max(n, 1) * 1e3
+        gemm[name] = {"avg_us": round(us, 1), "TFLOPs": round(flops[name] / us / 1e6, 1)}
+        tot_f += flops[name]
+        tot_t += us
+    st.profile_enable(0)
+    layer_flops = sum(flops.values()) + sum(2 * n * n * d * cfg.hq_l for n in lens)
+    return {"workload": f"{cfg.name}: TP{cfg.tp_degree} rank {rank}, {cfg.n_layers} layers, {cfg.batch} x {lens[0]} rows",
+            "tokens_per_s": round(T / dt, 1), "ms_per_call": round(dt * 1e3, 3),
+            "us_per_layer": round(dt * 1e6 / cfg.n_layers, 1),
+            "stage_mfma_frac": round(layer_flops * cfg.n_layers / dt / 1e12 / MFMA_PEAK_TFLOPS, 4),
+            "gemm_mfma_frac": round(tot_f / tot_t / 1e6 / MFMA_PEAK_TFLOPS, 4), "gemm": gemm,
+            "peak_TFLOPs": MFMA_PEAK_TFLOPS}
 
 
 def calibrate(torch, hx):

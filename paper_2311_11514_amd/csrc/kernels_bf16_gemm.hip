@@ -15,6 +15,7 @@
 // contiguous range of tiles, token-block fastest: tiles resident on one XCD share weight panels in
 // that XCD's L2.
 #include <cstdlib>
+#include <type_traits>
 
 #include "kernels.h"
 #include "kvlayout.h"
@@ -23,26 +24,40 @@
 #define HX_AS3(p) ((__attribute__((address_space(3))) void *)(p))
 // s_waitcnt that only constrains vmcnt (gfx9 encoding: vmcnt[3:0] | expcnt<<4 | lgkmcnt<<8 | vmcnt[5:4]<<14)
 #define HX_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
+// s_waitcnt lgkmcnt(0) alone (vmcnt and expcnt left at "no wait")
+#define HX_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14))
 // Workgroup barrier WITHOUT the device-memory release a __syncthreads() carries: that release would make
 // the compiler drain every outstanding direct-to-LDS load (vmcnt(0)) at each k-step and undo the
 // pipelining.  LDS reads of the previous step have been consumed by MFMAs before this point; the loads
 // of the step about to be read are covered by the explicit vmcnt wait issued just before.
-#define HX_LDS_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
+#define HX_LDS_BARRIER()                        \
+    do {                                        \
+        HX_WAIT_LGKM0();                        \
+        asm volatile("s_barrier" ::: "memory"); \
+    } while (0)
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
 // Operand tiles travel HBM -> LDS with direct-to-LDS loads (no registers in between): a wave copies one
 // 1 KB fragment tile per instruction, lane l's 16 bytes landing at tile base + 16 l.  S stages of the k-loop
-// are resident; loads run S - 1 steps ahead of the math and the wait before a step only covers that step's
-// loads (vmcnt counts the rest).
-template <int FM, int FT, int S, int MODE>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t *__restrict__ Wp, const bf16_t *__restrict__ Xp,
-                                                       int N, int k_tiles, int n_tiles, int t_tiles, int T,
-                                                       int n_blocks, int t_blocks, GemmEpi e) {
-    constexpr int TA = 4 * FM, TB = 4 * FT;          // 16-row operand tiles per block and k-step
-    constexpr int LPT = (TA + TB) / 4;               // direct-to-LDS loads per thread and stage
+// are resident; the wait before a step only covers that step's loads (vmcnt counts the rest).
+//
+// Block = WM x WT waves; each wave owns FM x FT tiles of 32 features x 32 tokens, so the block tile is
+// (32 FM WM) features x (32 FT WT) tokens.
+template <int FM, int FT, int WM, int WT, int S, int MODE>
+__global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *__restrict__ Wp,
+                                                                 const bf16_t *__restrict__ Xp, int N, int k_tiles,
+                                                                 int n_tiles, int t_tiles, int T, int n_blocks,
+                                                                 int t_blocks, GemmEpi e) {
+    constexpr int NW = WM * WT, NT = 64 * NW;
+    constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT;   // 16-row operand tiles per block and k-step
+    constexpr int LA = TA / NW, LB = TB / NW;         // direct-to-LDS loads per wave and stage, per operand
+    constexpr int LPT = LA + LB;
     constexpr int STAGE = (TA + TB) * 64;            // bf16x8 elements per stage
-    extern __shared__ bf16x8 smem[];                 // [S][TA + TB][64]
+    constexpr int NTOK = TB * 16;                    // token columns of the block tile
+    static_assert(TA % NW == 0 && TB % NW == 0, "operand tiles must divide evenly over the waves");
+    extern __shared__ bf16x8 smem[];                 // [S][TA + TB][64], then NTOK floats
+    float *rstd_s = reinterpret_cast<float *>(smem + (size_t)S * STAGE);
     // XCD-aware remap of the linear block id
     const int total = n_blocks * t_blocks;
     int id = blockIdx.x;
@@ -50,8 +65,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t *__restrict
     id = (id & 7) * per_xcd + (id >> 3);
     if (id >= total) return;                     // only when total is not a multiple of 8
     const int bm = id / t_blocks, bt = id - bm * t_blocks;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int wm = wave & 1, wt = wave >> 1;
+    // the wave index is made provably uniform: tile addresses and LDS destinations then stay in scalar registers
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int wm = wave % WM, wt = wave / WM;
 
     floatx16 acc[FM][FT];
 #pragma unroll
@@ -63,86 +79,224 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t *__restrict
 
     const bf16x8 *A = reinterpret_cast<const bf16x8 *>(Wp);
     const bf16x8 *B = reinterpret_cast<const bf16x8 *>(Xp);
-    // this wave copies tiles wave, wave + 4, ... of both operands; out-of-range tiles are clamped to the last
-    // valid tile (their products are never stored) so that every thread issues LPT loads per stage
-    const bf16x8 *asrc[TA / 4], *bsrc[TB / 4];
+    // this wave copies tiles wave, wave + NW, ... of both operands; out-of-range tiles are clamped to the last
+    // valid tile (their products are never stored) so that every wave issues LPT loads per stage.  Tile bases
+    // are uniform (scalar registers); the lane adds its 16-byte slot as a 32-bit offset.
+    const bf16x8 *asrc[LA], *bsrc[LB];
 #pragma unroll
-    for (int i = 0; i < TA / 4; ++i) asrc[i] = A + (size_t)min(bm * TA + wave + 4 * i, n_tiles - 1) * 64 + lane;
+    for (int i = 0; i < LA; ++i) asrc[i] = A + (size_t)min(bm * TA + wave + NW * i, n_tiles - 1) * 64;
 #pragma unroll
-    for (int i = 0; i < TB / 4; ++i) bsrc[i] = B + (size_t)min(bt * TB + wave + 4 * i, t_tiles - 1) * k_tiles * 64 + lane;
+    for (int i = 0; i < LB; ++i) bsrc[i] = B + (size_t)min(bt * TB + wave + NW * i, t_tiles - 1) * k_tiles * 64;
     const size_t astep = (size_t)n_tiles * 64;       // k-tile-major weights
-    auto issue = [&](int kt) {
+    // One direct-to-LDS load: index x < LA is a weight tile, the rest are activation tiles.  k-steps past
+    // the end are clamped to the last one (they land in a buffer nobody reads any more), so that every
+    // k-step issues exactly LPT loads and the loop body stays one basic block.
+    // One direct-to-LDS load of a 1 KB tile: index x < LA is a weight tile, the rest are activation tiles.
+    // k-steps past the end are clamped to the last one (they land in a buffer nobody reads any more), so that
+    // every k-step issues exactly LPT loads and the loop body stays one basic block.  The load is written in
+    // its scalar-base form (tile address in scalar registers, the lane's 16-byte slot as the 32-bit vector
+    // offset, LDS destination in M0), which the compiler does not select for this instruction by itself: it
+    // would spend a 64-bit vector add per load inside the MFMA stream.  The compiler does not see these
+    // loads in its own vmcnt bookkeeping; every wait on them is explicit (HX_WAIT_VM), and vmcnt is drained
+    // before the epilogue issues ordinary loads.
+    const unsigned lane_bytes = (unsigned)lane * 16u;
+    auto issue_one = [&](int kt, int x) {
+        const int kc = min(kt, k_tiles - 1);
         bf16x8 *st = smem + (size_t)(kt % S) * STAGE;
-#pragma unroll
-        for (int i = 0; i < TA / 4; ++i)
-            __builtin_amdgcn_global_load_lds(HX_AS1(asrc[i] + kt * astep), HX_AS3(st + (wave + 4 * i) * 64), 16, 0, 0);
-#pragma unroll
-        for (int i = 0; i < TB / 4; ++i)
-            __builtin_amdgcn_global_load_lds(HX_AS1(bsrc[i] + (size_t)kt * 64), HX_AS3(st + (TA + wave + 4 * i) * 64), 16, 0, 0);
+        const bf16x8 *src = x < LA ? asrc[x] + kc * astep : bsrc[x - LA] + (size_t)kc * 64;
+        bf16x8 *dst = x < LA ? st + (wave + NW * x) * 64 : st + (TA + wave + NW * (x - LA)) * 64;
+        const unsigned lds_addr = (unsigned)reinterpret_cast<uintptr_t>(HX_AS3(dst));
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :
+                     : "s"(lds_addr), "v"(lane_bytes), "s"(src)
+                     : "memory");
     };
     // 32x32x16 operand for k-half kh of a pair of 16-row tiles: lane l takes row l % 32, k-group 2 kh + l / 32
     const int frag = ((lane & 31) >> 4) * 64 + (lane & 15) + 16 * (lane >> 5);
+    // Software pipeline.  (1) The operand registers of one 16-deep half step are fetched from LDS while the
+    // MFMAs of the previous half step run.  (2) The barrier sits in the MIDDLE of a k-step: it publishes stage
+    // kt + 1, whose first half is then fetched under the second half of stage kt, and frees the buffer of
+    // stage kt - 1.  (3) The loads of stage kt + S - 1 into that buffer are spread over one whole step, half
+    // behind the barrier of step kt and half in front of the barrier of step kt + 1, one load every few MFMAs.
+    constexpr int H1 = (LPT + 1) / 2, H2 = LPT / 2;  // loads issued behind / in front of the barrier
+    constexpr int HL = H1;
+    // MFMA slots of a half step: the first FM + FT also carry an LDS fetch; the loads go behind them when
+    // there is room, else they are spread over all slots
+    constexpr int FREE = FM * FT - (FM + FT);
+    constexpr int LOAD0 = FREE >= HL ? FM + FT : 0;
+    constexpr int GAP = FREE >= HL ? FREE / HL : ((FM * FT) / HL > 0 ? (FM * FT) / HL : 1);
+    static_assert(S >= 3, "the pipeline needs three stages");
 #pragma unroll
-    for (int p = 0; p < S - 1; ++p)
-        if (p < k_tiles) issue(p);
-    for (int kt = 0; kt < k_tiles; ++kt) {
-        // loads of the S - 2 later stages may stay in flight; near the end fewer were issued, so wait for all
-        if (kt + S - 2 < k_tiles) HX_WAIT_VM((S - 2) * LPT);
-        else HX_WAIT_VM(0);
-        HX_LDS_BARRIER();         // stage kt is complete for every wave, and stage kt - 1 is no longer read
-        if (kt + S - 1 < k_tiles) issue(kt + S - 1);
-        const bf16x8 *sa = smem + (size_t)(kt % S) * STAGE + (wm * FM * 2) * 64 + frag;
-        const bf16x8 *sb = smem + (size_t)(kt % S) * STAGE + (TA + wt * FT * 2) * 64 + frag;
+    for (int p = 0; p < S - 2; ++p)
 #pragma unroll
-        for (int kh = 0; kh < 2; ++kh) {
-            bf16x8 b[FT];
+        for (int x = 0; x < LPT; ++x) issue_one(p, x);
 #pragma unroll
-            for (int j = 0; j < FT; ++j) b[j] = sb[j * 128 + kh * 32];
-#pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                const bf16x8 a = sa[i * 128 + kh * 32];
-#pragma unroll
-                for (int j = 0; j < FT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[j], acc[i][j], 0, 0, 0);
+    for (int x = 0; x < H1; ++x) issue_one(S - 2, x);
+    // 1 / rms of the block's token columns from the producer's partial sums of squares, once per block (the
+    // values are the youngest loads in flight: the compiler's wait for them also covers the stages above)
+    if (MODE != DEC_RESID && e.ssq_in != nullptr) {
+        const int groups = e.norm_dim / GEMM_SSQ_COLS;
+        for (int t = tid; t < NTOK; t += NT) {
+            const int token = bt * NTOK + t;
+            float ss = 0.f;
+            if (token < T) {
+#pragma unroll 16
+                for (int gI = 0; gI < groups; ++gI) ss += e.ssq_in[(size_t)gI * T + token];
             }
+            rstd_s[t] = 1.0f / sqrtf(ss / (float)e.norm_dim + e.eps);
         }
     }
+    bf16x8 fa0[FM], fb0[FT], fa1[FM], fb1[FT];
+    // x-th operand fetch of a half step: the FT token operands first, then the FM feature operands
+    auto fetch_one = [&](bf16x8(&fa)[FM], bf16x8(&fb)[FT], int kt, int kh, int x) {
+        const bf16x8 *sa = smem + (size_t)(kt % S) * STAGE + (wm * FM * 2) * 64 + frag + kh * 32;
+        const bf16x8 *sb = smem + (size_t)(kt % S) * STAGE + (TA + wt * FT * 2) * 64 + frag + kh * 32;
+        if (x < FT) fb[x] = sb[x * 128];
+        else fa[x - FT] = sa[(x - FT) * 128];
+    };
+    auto fetch = [&](bf16x8(&fa)[FM], bf16x8(&fb)[FT], int kt, int kh) {
+#pragma unroll
+        for (int x = 0; x < FM + FT; ++x) fetch_one(fa, fb, kt, kh, x);
+    };
+    static_assert(FM + FT <= FM * FT, "one operand fetch per MFMA slot");
+    HX_WAIT_VM((S - 3) * LPT + H1);
+    HX_LDS_BARRIER();
+    fetch(fa0, fb0, 0, 0);
+    HX_WAIT_LGKM0();
+    // The memory pipeline of a CU accepts one wave-wide 1 KB load every ~26 cycles and hardly queues: waves
+    // that issue their loads at the same point of the (lock-stepped) MFMA stream block each other for tens of
+    // cycles with the matrix core idle.  Each wave therefore runs a copy of the loop whose loads sit OFF
+    // MFMAs later than its neighbour's, which gives the CU one load per MFMA slot.
+    auto k_loop = [&](auto off_c) {
+        constexpr int OFF = decltype(off_c)::value;
+    for (int kt = 0; kt < k_tiles; ++kt) {
+        // one slot = one MFMA, at most one LDS fetch for the NEXT half step and at most one global load; the
+        // slots are fenced so that the order below is the order in the instruction stream
+#pragma unroll
+        for (int m = 0; m < FM * FT; ++m) {
+            acc[m / FT][m % FT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[m / FT], fb0[m % FT], acc[m / FT][m % FT], 0, 0, 0);
+            if (m < FM + FT) fetch_one(fa1, fb1, kt, 1, m);
+            if (m >= LOAD0 && (m - LOAD0) % GAP == OFF && (m - LOAD0) / GAP < H2) issue_one(kt + S - 2, H1 + (m - LOAD0) / GAP);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        HX_WAIT_VM((S - 3) * LPT);      // stage kt + 1 has landed; later stages stay in flight
+        HX_LDS_BARRIER();
+#pragma unroll
+        for (int m = 0; m < FM * FT; ++m) {
+            acc[m / FT][m % FT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[m / FT], fb1[m % FT], acc[m / FT][m % FT], 0, 0, 0);
+            if (m < FM + FT) fetch_one(fa0, fb0, kt + 1, 0, m);
+            if (m >= LOAD0 && (m - LOAD0) % GAP == OFF && (m - LOAD0) / GAP < H1) issue_one(kt + S - 1, (m - LOAD0) / GAP);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // the fetch of the next half step has had FM FT MFMAs to complete: waiting here, instead of where
+        // the compiler would place it (behind the next fetch), costs nothing and keeps that fetch covered
+        __builtin_amdgcn_sched_barrier(0);
+        HX_WAIT_LGKM0();
+    }
+    };
+    {
+        const int off = (wave * GAP) / NW;
+        if (GAP > 3 && off == 3) k_loop(std::integral_constant<int, (GAP > 3 ? 3 : 0)>{});
+        else if (GAP > 2 && off == 2) k_loop(std::integral_constant<int, (GAP > 2 ? 2 : 0)>{});
+        else if (GAP > 1 && off == 1) k_loop(std::integral_constant<int, (GAP > 1 ? 1 : 0)>{});
+        else k_loop(std::integral_constant<int, 0>{});
+    }
+    HX_WAIT_VM(0);
     // ---- epilogue, in registers.  32 x 32 result: lane l holds token column l % 32 and, per register quad q,
     // features 8 q + 4 (l / 32) .. + 3 of the 32-feature block, i.e. of the 16-row tile q / 2 its rows
     // (q % 2) * 8 + 4 (l / 32) .. + 3.  Rotary pairs (tile rows r, r + 8) and gate / up pairs (tiles 2m, 2m + 1)
     // therefore sit in the same lane, in quads q and q ^ 1 respectively q and q + 2: no cross-lane traffic.
     const int hl = lane >> 5;
+    if (MODE == DEC_RESID) {
+        // Residual read-modify-write.  Walks the wave tile one 32-feature block (i) at a time and fetches the
+        // residual values of block i + 1 before the stores of block i: the stream is loaded and stored through
+        // the same pointer, so the compiler would not move a load above a store by itself, and with one or
+        // two waves per SIMD nothing else hides the latency.
+        float ssq[FT];
+        int token[FT];
 #pragma unroll
-    for (int j = 0; j < FT; ++j) {
-        const int token = (bt * TB + (wt * FT + j) * 2) * 16 + (lane & 31);
-        const bool tv = token < T;
-        float r = 1.0f;
-        if ((MODE == DEC_QKV || MODE == DEC_SWIGLU || MODE == DEC_RAW) && e.ssq_in != nullptr && tv) {
-            float ss = 0.f;
-            const int groups = e.norm_dim / GEMM_SSQ_COLS;
-#pragma unroll 8
-            for (int gI = 0; gI < groups; ++gI) ss += e.ssq_in[(size_t)gI * T + token];
-            r = 1.0f / sqrtf(ss / (float)e.norm_dim + e.eps);
+        for (int j = 0; j < FT; ++j) {
+            ssq[j] = 0.f;
+            token[j] = (bt * TB + (wt * FT + j) * 2) * 16 + (lane & 31);
         }
-        int seq = 0, pos = 0;
-        if (MODE == DEC_QKV && tv) { seq = e.rm.row_seq[token]; pos = e.rm.row_pos[token]; }
-        float ssq = 0.f;
-        // RESID: fetch the whole column of residual values first, so the loads overlap instead of forming
-        // 4 FM load -> add -> store chains (one wave per SIMD: nothing else would hide their latency)
-        floatx4 hv[FM][4], gv[FM][4];
-        if (MODE == DEC_RESID) {
+        floatx4 hv[2][FT][4];
+        auto load_h = [&](floatx4(&dst)[FT][4], int i) {
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
+            for (int j = 0; j < FT; ++j)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int n = (bm * TA + (wm * FM + i) * 2) * 16 + 8 * q + 4 * hl;
-                    const bool ok = tv && n < N;
-                    hv[i][q] = ok ? *reinterpret_cast<const floatx4 *>(e.h + h_tile_offset(token, n, N))
-                                  : floatx4{0.f, 0.f, 0.f, 0.f};
-                    gv[i][q] = (ok && !e.last_layer) ? *reinterpret_cast<const floatx4 *>(e.g_next + n)
-                                                     : floatx4{0.f, 0.f, 0.f, 0.f};
+                    dst[j][q] = (token[j] < T && n < N)
+                                    ? *reinterpret_cast<const floatx4 *>(e.h + h_tile_offset(token[j], n, N))
+                                    : floatx4{0.f, 0.f, 0.f, 0.f};
                 }
+        };
+        load_h(hv[0], 0);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            floatx4 gv[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = (bm * TA + (wm * FM + i) * 2) * 16 + 8 * q + 4 * hl;
+                gv[q] = (n < N && !e.last_layer) ? *reinterpret_cast<const floatx4 *>(e.g_next + n)
+                                                 : floatx4{0.f, 0.f, 0.f, 0.f};
+            }
+            if (i + 1 < FM) load_h(hv[(i + 1) & 1], i + 1);
+#pragma unroll
+            for (int j = 0; j < FT; ++j) {
+                const floatx16 &c = acc[i][j];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = (bm * TA + (wm * FM + i) * 2) * 16 + 8 * q + 4 * hl;
+                    if (token[j] >= T || n >= N) continue;
+                    const floatx4 h4 = hv[i & 1][j][q];
+                    const floatx4 v = {c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]};
+                    if (e.last_layer) {
+                        uint2 po;
+                        po.x = pack_bf16x2(v[0], v[1]);
+                        po.y = pack_bf16x2(v[2], v[3]);
+                        *reinterpret_cast<uint2 *>(e.out_partial + (size_t)token[j] * N + n) = po;
+                        if (e.out_resid) {
+                            uint2 ro;
+                            ro.x = pack_bf16x2(h4[0], h4[1]);
+                            ro.y = pack_bf16x2(h4[2], h4[3]);
+                            *reinterpret_cast<uint2 *>(e.out_resid + (size_t)token[j] * N + n) = ro;
+                        }
+                    } else {
+                        const floatx4 hn = h4 + v;
+                        *reinterpret_cast<floatx4 *>(e.h + h_tile_offset(token[j], n, N)) = hn;
+                        const floatx4 g4 = gv[q];
+                        uint2 o;
+                        o.x = pack_bf16x2(hn[0] * g4[0], hn[1] * g4[1]);
+                        o.y = pack_bf16x2(hn[2] * g4[2], hn[3] * g4[3]);
+                        *reinterpret_cast<uint2 *>(e.hg + frag_offset(token[j], n, N >> 5)) = o;
+                        ssq[j] += hn[0] * hn[0] + hn[1] * hn[1] + hn[2] * hn[2] + hn[3] * hn[3];
+                    }
+                }
+            }
         }
+        if (!e.last_layer) {
+            // sum of squares of this wave's 32 FM = 128 features of each token: the two lane halves hold
+            // disjoint rows
+            static_assert(MODE != DEC_RESID || 32 * FM == GEMM_SSQ_COLS, "one partial per wave and token");
+            const int grp = (bm * TA + wm * FM * 2) * 16 / GEMM_SSQ_COLS;
+#pragma unroll
+            for (int j = 0; j < FT; ++j) {
+                const float tot = ssq[j] + __shfl_xor(ssq[j], 32, 64);
+                if (hl == 0 && token[j] < T) e.ssq_out[(size_t)grp * T + token[j]] = tot;
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int j = 0; j < FT; ++j) {
+        const int tl = (wt * FT + j) * 32 + (lane & 31);       // token column inside the block tile
+        const int token = bt * NTOK + tl;
+        const bool tv = token < T;
+        const float r = e.ssq_in != nullptr ? rstd_s[tl] : 1.0f;
+        int seq = 0, pos = 0;
+        if (MODE == DEC_QKV && tv) { seq = e.rm.row_seq[token]; pos = e.rm.row_pos[token]; }
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
             const int t16 = bm * TA + (wm * FM + i) * 2;        // first 16-row tile of this 32-feature block
@@ -154,36 +308,6 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t *__restrict
                     if (tv && n < N)
                         *reinterpret_cast<floatx4 *>(e.raw_out + (size_t)token * N + n) =
                             floatx4{c[4 * q] * r, c[4 * q + 1] * r, c[4 * q + 2] * r, c[4 * q + 3] * r};
-                }
-            } else if (MODE == DEC_RESID) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int n = t16 * 16 + 8 * q + 4 * hl;
-                    if (!tv || n >= N) continue;
-                    const size_t ho = h_tile_offset(token, n, N);
-                    const floatx4 h4 = hv[i][q];
-                    const floatx4 v = {c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]};
-                    if (e.last_layer) {
-                        uint2 po;
-                        po.x = pack_bf16x2(v[0], v[1]);
-                        po.y = pack_bf16x2(v[2], v[3]);
-                        *reinterpret_cast<uint2 *>(e.out_partial + (size_t)token * N + n) = po;
-                        if (e.out_resid) {
-                            uint2 ro;
-                            ro.x = pack_bf16x2(h4[0], h4[1]);
-                            ro.y = pack_bf16x2(h4[2], h4[3]);
-                            *reinterpret_cast<uint2 *>(e.out_resid + (size_t)token * N + n) = ro;
-                        }
-                    } else {
-                        const floatx4 hn = h4 + v;
-                        *reinterpret_cast<floatx4 *>(e.h + ho) = hn;
-                        const floatx4 g4 = gv[i][q];
-                        uint2 o;
-                        o.x = pack_bf16x2(hn[0] * g4[0], hn[1] * g4[1]);
-                        o.y = pack_bf16x2(hn[2] * g4[2], hn[3] * g4[3]);
-                        *reinterpret_cast<uint2 *>(e.hg + frag_offset(token, n, N >> 5)) = o;
-                        ssq += hn[0] * hn[0] + hn[1] * hn[1] + hn[2] * hn[2] + hn[3] * hn[3];
-                    }
                 }
             } else if (MODE == DEC_SWIGLU) {
                 // tile t16 = gate, t16 + 1 = up (interleaved packing): quads 0, 1 against quads 2, 3
@@ -208,8 +332,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t *__restrict
                 for (int m = 0; m < 2; ++m) {              // the two 16-row tiles of this block
                     const int tile = t16 + m;
                     if (!tv || tile >= n_tiles) continue;
-                    const int head = tile / tph, tl = tile - head * tph;
-                    const int i0 = tl * 8 + 4 * hl;            // first rotary pair index of this lane
+                    const int head = tile / tph, tl16 = tile - head * tph;
+                    const int i0 = tl16 * 8 + 4 * hl;            // first rotary pair index of this lane
                     float lo[4], hi[4];
 #pragma unroll
                     for (int x = 0; x < 4; ++x) { lo[x] = c[4 * (2 * m) + x] * r; hi[x] = c[4 * (2 * m + 1) + x] * r; }
@@ -246,33 +370,26 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t *__restrict
                 }
             }
         }
-        if (MODE == DEC_RESID && !e.last_layer) {
-            // sum of squares of this wave's 32 FM features of the token: the two lane halves hold disjoint rows
-            ssq += __shfl_xor(ssq, 32, 64);
-            if (hl == 0 && tv) {
-                const int grp = (bm * TA + wm * FM * 2) * 16 / GEMM_SSQ_COLS;
-                e.ssq_out[(size_t)grp * T + token] = ssq;
-            }
-        }
     }
 }
 
-template <int FM, int FT, int S, int MODE>
+template <int FM, int FT, int WM, int WT, int S, int MODE>
 static void launch_cfg(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles, int n_tiles, int t_tiles, int T,
                        const GemmEpi &e, hipStream_t s) {
-    const int n_blocks = (n_tiles + 4 * FM - 1) / (4 * FM), t_blocks = (t_tiles + 4 * FT - 1) / (4 * FT);
+    constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT;
+    const int n_blocks = (n_tiles + TA - 1) / TA, t_blocks = (t_tiles + TB - 1) / TB;
     const int total = n_blocks * t_blocks;
     const int grid = (total + 7) / 8 * 8;
-    auto kern = gemm_mfma_kernel<FM, FT, S, MODE>;
-    const size_t dyn = (size_t)S * (4 * FM + 4 * FT) * 64 * sizeof(bf16x8);
+    auto kern = gemm_mfma_kernel<FM, FT, WM, WT, S, MODE>;
+    const size_t dyn = (size_t)S * (TA + TB) * 64 * sizeof(bf16x8) + (size_t)TB * 16 * sizeof(float);
     static bool raised = false;           // more than the default 64 KB of LDS per block
     if (!raised) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)dyn);
         raised = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), dyn, s, Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, n_blocks, t_blocks,
-                       e);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WT), dyn, s, Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, n_blocks,
+                       t_blocks, e);
 }
 
 template <int MODE>
@@ -281,15 +398,21 @@ static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T,
     static const int force = std::getenv("HEXGEN_GEMM_TILE") ? std::atoi(std::getenv("HEXGEN_GEMM_TILE")) : 0;
     // tiles of 256 x 256 once they fill the chip; smaller tiles for small problems
     const long big = (long)((n_tiles + 15) / 16) * ((t_tiles + 15) / 16);
-    int cfg = big >= 200 ? 88 : ((long)((n_tiles + 15) / 16) * ((t_tiles + 7) / 8) >= 200 ? 84 : 44);
+    int cfg = big >= 200 ? 98 : ((long)((n_tiles + 7) / 8) * ((t_tiles + 15) / 16) >= 128 ? 94 : 44);
     if (force) cfg = force;
     // the RESID epilogue emits one sum-of-squares partial per wave: its 32 FM features must be 128
-    if (MODE == DEC_RESID && cfg != 88 && cfg != 84) cfg = 84;
-#define HX_G(FM, FT, S) launch_cfg<FM, FT, S, MODE>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, s)
-    if (cfg == 88) HX_G(4, 4, 4);
-    else if (cfg == 84) HX_G(4, 2, 4);
-    else if (cfg == 48) HX_G(2, 4, 4);
-    else HX_G(2, 2, 4);
+    if (MODE == DEC_RESID && cfg != 88 && cfg != 84 && cfg != 98) cfg = 84;
+#define HX_G(FM, FT, WM, WT, S) launch_cfg<FM, FT, WM, WT, S, MODE>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, s)
+    if (cfg == 88) HX_G(4, 4, 2, 2, 4);
+    else if (cfg == 98) HX_G(4, 2, 2, 4, 4);
+    else if (cfg == 94) { if constexpr (MODE != DEC_RESID) HX_G(2, 2, 2, 4, 4); }
+    else if (cfg == 49) { if constexpr (MODE != DEC_RESID) HX_G(2, 2, 4, 2, 4); }
+    else if (cfg == 84) HX_G(4, 2, 2, 2, 4);
+    else if (cfg == 48) {
+        if constexpr (MODE != DEC_RESID) HX_G(2, 4, 2, 2, 4);
+    } else {
+        if constexpr (MODE != DEC_RESID) HX_G(2, 2, 2, 2, 4);
+    }
 #undef HX_G
 }
 

@@ -1,13 +1,12 @@
 // Prefill projection: LDS-staged MFMA GEMM, D^T[n][t] = sum_k Wp[n][k] * Xp[t][k].
 //
-// Block = 4 waves (2 x 2); each wave owns FM x FT tiles of 32 features x 32 tokens computed with
-// v_mfma_f32_32x32x16_bf16 (measured on this chip: 85 % of the datasheet rate from registers against 64 % for
-// the 16x16x32 form, which is issue-limited), so the block tile is (64 FM) features x (64 FT) tokens.  The
-// large configuration (FM = FT = 4: 256 x 256 block, 128 x 128 per wave, 256 accumulator registers per
-// lane) keeps LDS out of the way: per 32-deep k-step a wave issues 16 128-bit LDS reads for 32 MFMAs.
+// A block is a WM x WT grid of waves; each wave owns FM x FT tiles of 32 features x 32 tokens computed with
+// v_mfma_f32_32x32x16_bf16 (measured on this chip: 89 % of the datasheet rate from registers against 64 % for
+// the 16x16x32 form, which is issue-limited).  The large configurations cover 256 x 256 per block: 8 waves of
+// 128 x 64 (two waves per SIMD, 128 accumulator registers each) or 4 waves of 128 x 128 (256 accumulators).
 // Operands stay in the 16 x 32 fragment tiles shared with the decode kernels (see common.h): global -> LDS
 // is a straight copy, and a 32x32x16 operand is gathered from two neighbouring 16-row tiles with per-lane
-// LDS addresses (every 8 lanes still read 128 contiguous bytes: conflict-free).  Both MFMA inputs use the
+// LDS addresses (every 16 lanes read 256 contiguous bytes: conflict-free).  Both MFMA inputs use the
 // same gather, so the k-order inside a tile cancels.
 // Weights are k-tile-major, so the weight tiles of a block's k-step are one contiguous run of HBM.
 //

@@ -248,14 +248,16 @@ def calibrate(torch, hx):
             print(f"  {mb:4d} {blocks:5d} read  {us:8.1f} {n / us / 1e6:6.2f}")
             us = timed(lambda i: hx.stream_copy(dst[:n], big[(i % slices) * n:(i % slices + 1) * n], blocks), 20)
             print(f"  {mb:4d} {blocks:5d} copy  {us:8.1f} {2 * n / us / 1e6:6.2f}")
-    print("dense bf16 MFMA, 4 waves per CU, operands in registers (variant, TFLOP/s, fraction of 2516.6)")
+    print("dense bf16 MFMA, 4 waves per CU, operands in registers, ~50 ms per run (variant, TFLOP/s, fraction of 2516.6)")
     names = ["16x16x32, registers only", "32x32x16, registers only", "16x16x32 + GEMM-rate LDS reads",
              "32x32x16 + GEMM-rate LDS reads"]
-    iters, blocks = 2000, 256
-    for v, name in enumerate(names):
-        us = timed(lambda i: hx.mfma_probe(v, sink, iters, blocks), 3)
+    blocks = 256
+    for v in range(8):
+        name = names[v % 4] + (", random operand bits" if v >= 4 else ", operands all 1.0")
+        iters = 100000
+        us = timed(lambda i: hx.mfma_probe(v, sink, iters, blocks), 1)
         tf = blocks * 4 * iters * (1 << 20) / us / 1e6
-        print(f"  {name:34s} {tf:8.1f} {tf / 2516.6:6.3f}")
+        print(f"  {name:58s} {tf:8.1f} {tf / 2516.6:6.3f}")
 
 
 def cpu_baseline(cfg, rank, layer0, kv_host, X, ctx):

@@ -166,7 +166,9 @@ hexgen_status_t hexgen_stream_read(const void *src, void *sink, int64_t bytes, i
 
 /* Matrix-core calibration: `blocks` 4-wave blocks each run `iters` k-steps of a 128 x 128 x 32 wave tile out of
  * registers (2^20 flop per wave and iteration).  variant 0: 16x16x32 bf16 MFMA, 1: 32x32x16 bf16 MFMA, 2 / 3: the
- * same plus the LDS fragment reads a GEMM issues.  `sink`: device, >= 256 floats.  Time it with events.
+ * same plus the LDS fragment reads a GEMM issues; 4 .. 7: variants 0 .. 3 on operands with random signs and
+ * mantissas instead of 1.0 (the power the matrix cores draw, and with it the clock the chip holds, depends on the
+ * operand bits; run tens of milliseconds for a steady figure).  `sink`: device, >= 256 floats.  Time it with events.
  */
 hexgen_status_t hexgen_mfma_probe(int variant, void *sink, int iters, int blocks, void *stream);
 

@@ -171,12 +171,23 @@ void launch_stream_read(const void *src, float *sink, int64_t bytes, int blocks,
 // variant 0: v_mfma_f32_16x16x32_bf16, 64 independent accumulators per wave; variant 1: v_mfma_f32_32x32x16_bf16,
 // 16 accumulators; variants 2 / 3: the same with the LDS fragment reads of a 128 x 128 wave tile (16 reads per
 // 32-deep k-step).  One 4-wave block per launch slot; every block runs `iters` k-steps of 2^20 flop per wave.
+// RANDOM = false fills the operands with 1.0; RANDOM = true with random signs and mantissas (exponent fixed so that
+// nothing overflows): the matrix cores draw far more power on operands whose bits toggle, and the chip then holds
+// a lower clock, so the all-ones figure is an upper bound no real GEMM sees.
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
-template <int VARIANT>
+template <int VARIANT, bool RANDOM>
 __global__ __launch_bounds__(256) void mfma_probe_kernel(float *sink, int iters) {
     __shared__ bf16x8 sm[32][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int i = threadIdx.x; i < 32 * 64; i += 256) { bf16x8 one = {1, 1, 1, 1, 1, 1, 1, 1}; sm[i >> 6][i & 63] = one; }
+    for (int i = threadIdx.x; i < 32 * 64; i += 256) {
+        uint32_t h = (uint32_t)i * 2654435761u + blockIdx.x * 40503u;
+        uint32_t w[4];
+        for (int c = 0; c < 4; ++c) {
+            h = h * 1664525u + 1013904223u;
+            w[c] = RANDOM ? ((h & 0x807f807fu) | 0x3f003f00u) : 0x3f803f80u;      // +-[0.5, 1) or 1.0, twice
+        }
+        sm[i >> 6][i & 63] = *reinterpret_cast<const bf16x8 *>(w);
+    }
     __syncthreads();
     constexpr bool LDS = VARIANT >= 2;
     float total = 0.f;
@@ -239,10 +250,16 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *sink, int iters)
     if (total == 123.456f) sink[threadIdx.x] = total;      // practically never: keeps the math alive
 }
 void launch_mfma_probe(int variant, float *sink, int iters, int blocks, hipStream_t s) {
+#define HX_P(V, R) hipLaunchKernelGGL((mfma_probe_kernel<V, R>), dim3(blocks), dim3(256), 0, s, sink, iters)
     switch (variant) {
-        case 0: hipLaunchKernelGGL(mfma_probe_kernel<0>, dim3(blocks), dim3(256), 0, s, sink, iters); break;
-        case 1: hipLaunchKernelGGL(mfma_probe_kernel<1>, dim3(blocks), dim3(256), 0, s, sink, iters); break;
-        case 2: hipLaunchKernelGGL(mfma_probe_kernel<2>, dim3(blocks), dim3(256), 0, s, sink, iters); break;
-        default: hipLaunchKernelGGL(mfma_probe_kernel<3>, dim3(blocks), dim3(256), 0, s, sink, iters); break;
+        case 0: HX_P(0, false); break;
+        case 1: HX_P(1, false); break;
+        case 2: HX_P(2, false); break;
+        case 3: HX_P(3, false); break;
+        case 4: HX_P(0, true); break;
+        case 5: HX_P(1, true); break;
+        case 6: HX_P(2, true); break;
+        default: HX_P(3, true); break;
     }
+#undef HX_P
 }

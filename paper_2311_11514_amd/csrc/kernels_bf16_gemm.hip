@@ -425,60 +425,59 @@ void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, c
 }
 
 // -------------------------------------------------------------------------------------------------
-// Prefill prologue: stage input rows (bf16, or fp32 for the validation surface) -> fp32 residual stream,
-// (x * gain) in fragment tiles, sums of squares per 128-column group.  One 256-thread block per row.
+// Prefill prologue: stage input rows (bf16, or fp32 for the validation surface) -> fp32 residual stream in its
+// tiled order, (x * gain) in fragment tiles, sums of squares per 128-column group.  One wave owns 32 tokens x
+// 128 columns and walks them as four 32 x 32 blocks in the lane layout of the MFMA result (lane = token % 32 +
+// 32 * half, four consecutive features per lane and quad): every store of the residual stream is one contiguous
+// 1 KB, every store of the operand two runs of 256 B, and the 64-byte row pieces it reads are fetched once.
 // -------------------------------------------------------------------------------------------------
 template <bool IN_BF16>
 __global__ __launch_bounds__(256) void prefill_prologue_kernel(const void *__restrict__ in, float *__restrict__ h_out,
                                                               const float *__restrict__ g, bf16_t *__restrict__ hg,
                                                               float *__restrict__ ssq_out, int T, int H) {
-    const int t = blockIdx.x;
-    const int chunks = H >> 3;                 // 8-column chunks; 16 consecutive chunks = one 128-column group
-    for (int c0 = 0; c0 < chunks; c0 += 256) {
-        const int c = c0 + threadIdx.x;
-        float ss = 0.f;
-        if (c < chunks) {
-            float x[8];
-            if (IN_BF16) {
-                uint4 raw = *reinterpret_cast<const uint4 *>(reinterpret_cast<const bf16_t *>(in) + (size_t)t * H + c * 8);
-                const bf16_t *eh = reinterpret_cast<const bf16_t *>(&raw);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int token = blockIdx.x * 32 + (lane & 31), hl = lane >> 5;
+    const int col0 = (blockIdx.y * 4 + wave) * GEMM_SSQ_COLS;
+    if (col0 >= H) return;
+    const bool tv = token < T;
+    float ss = 0.f;
 #pragma unroll
-                for (int jx = 0; jx < 8; ++jx) x[jx] = bf16_to_f32(eh[jx]);
-            } else {
-                const float4 *p = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(in) + (size_t)t * H + c * 8);
-                float4 a = p[0], b = p[1];
-                x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-            }
-            if (h_out) {
-                *reinterpret_cast<float4 *>(h_out + h_tile_offset(t, c * 8, H)) = make_float4(x[0], x[1], x[2], x[3]);
-                *reinterpret_cast<float4 *>(h_out + h_tile_offset(t, c * 8 + 4, H)) = make_float4(x[4], x[5], x[6], x[7]);
-            }
-            const float4 *gp = reinterpret_cast<const float4 *>(g + c * 8);
-            float4 g0 = gp[0], g1 = gp[1];
-            uint4 o;
-            o.x = pack_bf16x2(x[0] * g0.x, x[1] * g0.y);
-            o.y = pack_bf16x2(x[2] * g0.z, x[3] * g0.w);
-            o.z = pack_bf16x2(x[4] * g1.x, x[5] * g1.y);
-            o.w = pack_bf16x2(x[6] * g1.z, x[7] * g1.w);
-            *reinterpret_cast<uint4 *>(hg + frag_offset(t, c * 8, H >> 5)) = o;
+    for (int fb = 0; fb < GEMM_SSQ_COLS / 32; ++fb) {
 #pragma unroll
-            for (int jx = 0; jx < 8; ++jx) ss += x[jx] * x[jx];
+        for (int q = 0; q < 4; ++q) {
+            const int n = col0 + fb * 32 + 8 * q + 4 * hl;
+            float x[4] = {0.f, 0.f, 0.f, 0.f};
+            if (tv) {
+                if (IN_BF16) {
+                    const uint2 raw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(in) + (size_t)token * H + n);
+                    x[0] = __uint_as_float(raw.x << 16); x[1] = __uint_as_float(raw.x & 0xffff0000u);
+                    x[2] = __uint_as_float(raw.y << 16); x[3] = __uint_as_float(raw.y & 0xffff0000u);
+                } else {
+                    const float4 v = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(in) + (size_t)token * H + n);
+                    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+                }
+                if (h_out) *reinterpret_cast<float4 *>(h_out + h_tile_offset(token, n, H)) = make_float4(x[0], x[1], x[2], x[3]);
+                const float4 g4 = *reinterpret_cast<const float4 *>(g + n);
+                uint2 o;
+                o.x = pack_bf16x2(x[0] * g4.x, x[1] * g4.y);
+                o.y = pack_bf16x2(x[2] * g4.z, x[3] * g4.w);
+                *reinterpret_cast<uint2 *>(hg + frag_offset(token, n, H >> 5)) = o;
+            }
+            ss += x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
         }
-        ss += __shfl_xor(ss, 1, 64);
-        ss += __shfl_xor(ss, 2, 64);
-        ss += __shfl_xor(ss, 4, 64);
-        ss += __shfl_xor(ss, 8, 64);
-        if ((threadIdx.x & 15) == 0 && c < chunks) ssq_out[(size_t)(c >> 4) * T + t] = ss;
     }
+    ss += __shfl_xor(ss, 32, 64);
+    if (hl == 0 && tv) ssq_out[(size_t)(col0 / GEMM_SSQ_COLS) * T + token] = ss;
 }
 
 void launch_prefill_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg, float *ssq_out,
                              int T, int H, hipStream_t s) {
     if (T <= 0) return;
+    const dim3 grid((T + 31) / 32, (H / GEMM_SSQ_COLS + 3) / 4);
     if (in_is_bf16)
-        hipLaunchKernelGGL(prefill_prologue_kernel<true>, dim3(T), dim3(256), 0, s, in, h_out, g, hg, ssq_out, T, H);
+        hipLaunchKernelGGL(prefill_prologue_kernel<true>, grid, dim3(256), 0, s, in, h_out, g, hg, ssq_out, T, H);
     else
-        hipLaunchKernelGGL(prefill_prologue_kernel<false>, dim3(T), dim3(256), 0, s, in, h_out, g, hg, ssq_out, T, H);
+        hipLaunchKernelGGL(prefill_prologue_kernel<false>, grid, dim3(256), 0, s, in, h_out, g, hg, ssq_out, T, H);
 }
 
 // tiled residual stream -> row-major fp32 (debug taps)

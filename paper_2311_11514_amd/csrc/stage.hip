@@ -76,7 +76,8 @@ struct Workspace {
     // fp32 path
     float *n32 = nullptr, *q32 = nullptr, *o32 = nullptr, *u32 = nullptr;
     // row bookkeeping
-    int32_t *row_seq = nullptr, *row_pos = nullptr, *cu_rows = nullptr, *pos0 = nullptr;
+    int32_t *rowmap = nullptr;       // one block: row_seq | row_pos | cu_rows | pos0, packed by the sizes of the call
+    int32_t *row_seq = nullptr, *row_pos = nullptr, *cu_rows = nullptr, *pos0 = nullptr;   // views into rowmap
     int32_t *host_stage = nullptr;   // pinned staging for the arrays above
     int host_stage_cap = 0;
 };
@@ -116,7 +117,7 @@ size_t esize(hexgen_dtype_t dt) { return dt == HEXGEN_F32 ? 4 : 2; }
 
 void free_ws(Workspace &w) {
     void *ptrs[] = {w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.xa_n, w.xa_o, w.xa_u, w.q_lo, w.ssq, w.ssq_pf, w.att_o, w.att_ml, w.n32, w.q32, w.o32, w.u32,
-                    w.row_seq, w.row_pos, w.cu_rows, w.pos0};
+                    w.rowmap};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (w.host_stage) (void)hipHostFree(w.host_stage);
@@ -173,10 +174,7 @@ hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
         HX_TRY(dmalloc(&w.o32, T * st->qw));
         HX_TRY(dmalloc(&w.u32, T * st->F_l));
     }
-    HX_TRY(dmalloc(&w.row_seq, T));
-    HX_TRY(dmalloc(&w.row_pos, T));
-    HX_TRY(dmalloc(&w.cu_rows, (size_t)batch + 1));
-    HX_TRY(dmalloc(&w.pos0, (size_t)batch));
+    HX_TRY(dmalloc(&w.rowmap, 2 * T + 2 * (size_t)batch + 1));
     w.host_stage_cap = 2 * rows + 3 * batch + 1;     // row_seq, row_pos, cu_rows, pos0, new lengths
     HX_HIP(hipHostMalloc(reinterpret_cast<void **>(&w.host_stage), (size_t)w.host_stage_cap * sizeof(int32_t),
                          hipHostMallocDefault));
@@ -211,6 +209,10 @@ hexgen_status_t setup_rows(hexgen_stage *st, hexgen_kv_cache *kv, const int32_t 
     r.decode = allow_decode && r.max_new == 1 && r.T <= kDecodeMaxRows;
     HX_TRY(ensure_workspace(st, r.T, batch));
     Workspace &w = st->ws;
+    w.row_seq = w.rowmap;
+    w.row_pos = w.rowmap + r.T;
+    w.cu_rows = w.rowmap + 2 * (size_t)r.T;
+    w.pos0 = w.cu_rows + batch + 1;
     r.rm.row_seq = w.row_seq;
     r.rm.row_pos = w.row_pos;
     if (r.decode && st->dtype == HEXGEN_BF16) {
@@ -230,10 +232,9 @@ hexgen_status_t setup_rows(hexgen_stage *st, hexgen_kv_cache *kv, const int32_t 
             for (int jn = 0; jn < n; ++jn, ++row) { h_seq[row] = i; h_pos[row] = kv->lens[i] + jn; }
         }
         h_cu[batch] = row;
-        HX_HIP(hipMemcpyAsync(w.row_seq, h_seq, sizeof(int32_t) * r.T, hipMemcpyHostToDevice, s));
-        HX_HIP(hipMemcpyAsync(w.row_pos, h_pos, sizeof(int32_t) * r.T, hipMemcpyHostToDevice, s));
-        HX_HIP(hipMemcpyAsync(w.cu_rows, h_cu, sizeof(int32_t) * (batch + 1), hipMemcpyHostToDevice, s));
-        HX_HIP(hipMemcpyAsync(w.pos0, h_p0, sizeof(int32_t) * batch, hipMemcpyHostToDevice, s));
+        // host staging and device block share one packing: a single copy moves all four arrays
+        HX_HIP(hipMemcpyAsync(w.rowmap, hs, sizeof(int32_t) * (2 * (size_t)r.T + 2 * (size_t)batch + 1),
+                              hipMemcpyHostToDevice, s));
     }
     *out = r;
     return HEXGEN_OK;

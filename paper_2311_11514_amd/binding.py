@@ -45,6 +45,7 @@ SIGNATURES = {
     "hexgen_stream_copy": (_i, [_vp, _vp, _i64, _i, _vp]),
     "hexgen_stream_read": (_i, [_vp, _vp, _i64, _i, _vp]),
     "hexgen_mfma_probe": (_i, [_i, _vp, _i, _i, _vp]),
+    "hexgen_set_gemm_tile": (_i, [_i]),
     "hexgen_stage_profile_enable": (_i, [_vp, _i]),
     "hexgen_stage_profile_read": (_i, [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64)]),
 }
@@ -219,6 +220,10 @@ def stream_copy(dst: torch.Tensor, src: torch.Tensor, blocks: int = 4096, stream
 def stream_read(src: torch.Tensor, sink: torch.Tensor, blocks: int = 4096, stream=None):
     nbytes = src.numel() * src.element_size()
     _check(lib.hexgen_stream_read(_ptr(src), _ptr(sink), nbytes, blocks, _stream_handle(stream)), "hexgen_stream_read")
+
+
+def set_gemm_tile(code: int):
+    _check(lib.hexgen_set_gemm_tile(code), "hexgen_set_gemm_tile")
 
 
 def mfma_probe(variant: int, sink: torch.Tensor, iters: int, blocks: int, stream=None):

@@ -111,6 +111,8 @@ struct GemmEpi {
 void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, hipStream_t s);
 // stage input rows -> h (optional), (x * g) in fragment tiles, sums of squares [H / 128][T]
 void launch_untile_h(const float *h_tiled, float *out, int T, int H, hipStream_t s);
+// force a tile configuration of the prefill GEMM (see launch_mode); false for an unknown code
+bool set_gemm_tile(int code);
 void launch_prefill_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg, float *ssq_out,
                              int T, int H, hipStream_t s);
 

@@ -13,7 +13,7 @@
 // blockIdx.x is remapped so that each XCD (blocks are dealt round-robin to the 8 XCDs) works on a
 // contiguous range of tiles, token-block fastest: tiles resident on one XCD share weight panels in
 // that XCD's L2.
-#include <cstdlib>
+#include <atomic>
 #include <type_traits>
 
 #include "kernels.h"
@@ -391,10 +391,18 @@ static void launch_cfg(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles, i
                        t_blocks, e);
 }
 
+// tile configuration forced for every GEMM launch of the process (0 = choose by shape); a measurement and test hook
+static std::atomic<int> g_force_tile{0};
+bool set_gemm_tile(int code) {
+    for (int ok : {0, 44, 48, 84, 88, 94, 49, 98})
+        if (code == ok) { g_force_tile.store(code, std::memory_order_relaxed); return true; }
+    return false;
+}
+
 template <int MODE>
 static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, hipStream_t s) {
     const int k_tiles = K / 32, n_tiles = N / 16, t_tiles = (T + 15) / 16;
-    static const int force = std::getenv("HEXGEN_GEMM_TILE") ? std::atoi(std::getenv("HEXGEN_GEMM_TILE")) : 0;
+    const int force = g_force_tile.load(std::memory_order_relaxed);
     // tiles of 256 x 256 once they fill the chip; smaller tiles for small problems
     const long big = (long)((n_tiles + 15) / 16) * ((t_tiles + 15) / 16);
     int cfg = big >= 200 ? 98 : ((long)((n_tiles + 7) / 8) * ((t_tiles + 15) / 16) >= 128 ? 94 : 44);

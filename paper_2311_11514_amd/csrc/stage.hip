@@ -931,6 +931,8 @@ hexgen_status_t hexgen_mfma_probe(int variant, void *sink, int iters, int blocks
     return HEXGEN_OK;
 }
 
+hexgen_status_t hexgen_set_gemm_tile(int code) { return set_gemm_tile(code) ? HEXGEN_OK : HEXGEN_ERR_INVALID_ARG; }
+
 hexgen_status_t hexgen_stage_set_tap(hexgen_stage_t *st, int layer, void *h_dump) {
     if (!st || layer < 0 || layer >= st->L) return HEXGEN_ERR_INVALID_ARG;
     st->taps[layer] = h_dump;

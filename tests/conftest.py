@@ -10,6 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the library that is built; only a tree with none gets one compiled here (hipcc cross-compiles
+    # for gfx950 without a GPU)
+    from paper_2311_11514_amd.build import LIB as LIB_PATH, build_library
+    if not os.path.exists(LIB_PATH):
+        build_library()
 
 
 def pytest_collection_modifyitems(config, items):

@@ -136,6 +136,32 @@ def test_bf16_small_prefill_then_decode(cfg, lens):
             assert row_rel_err(vv.numpy().reshape(-1, cfg.head_dim), oc.v[layer][s].reshape(-1, cfg.head_dim)) < TOL["bf16"]
 
 
+@pytest.mark.parametrize("tile", [88, 98, 84, 48, 94, 49, 44])
+def test_bf16_prefill_every_gemm_tile_configuration(tile):
+    """Every instantiation of the prefill projection GEMM (4- and 8-wave blocks, 256/128-wide tiles, odd and even
+    load counts per stage), forced through the library's tile hook, on a ragged prompt batch that spans several
+    block tiles with a ragged tail (293 rows: one full 256-token block and a partial one)."""
+    import paper_2311_11514_amd as hx
+    cfg = MINI128
+    lens = [150, 3, 140]
+    w = _weights(cfg)
+    rank = cfg.tp_ranks[0]
+    X = generate.hidden_rows(cfg, sum(lens), stream_id=7)
+    ora = make_oracle(cfg, rank, w)
+    p_ref, h_ref = ora.prefill(ora.new_cache(len(lens)), X, lens)
+    st = make_gpu_stage(cfg, rank, w)
+    kv = st.kv_cache_create(len(lens), 160)
+    hx.set_gemm_tile(tile)
+    try:
+        p, h = gpu_prefill(st, kv, cfg, X, lens)
+    finally:
+        hx.set_gemm_tile(0)
+    assert row_rel_err(h, h_ref) < TOL["bf16"]
+    assert row_rel_err(p, p_ref) < TOL["bf16"]
+    with pytest.raises(hx.HexgenError):
+        hx.set_gemm_tile(17)
+
+
 def test_bf16_decode_from_synthetic_context():
     """Decode-only workloads start from an installed synthetic KV context (ragged lengths here)."""
     cfg = MINI128

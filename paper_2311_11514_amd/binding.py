@@ -115,9 +115,10 @@ class Stage:
         _check(lib.hexgen_stage_set_params(self.handle, rms_eps, rope_theta), "hexgen_stage_set_params")
         self._taps = {}
 
-    def close(self):
+    def close(self, _lib=lib):
+        # the default argument keeps the library reachable when the module's globals are already torn down
         if getattr(self, "handle", None):
-            lib.hexgen_stage_destroy(self.handle)
+            _lib.hexgen_stage_destroy(self.handle)
             self.handle = None
 
     __del__ = close
@@ -175,9 +176,9 @@ class KVCache:
         _check(lib.hexgen_kv_cache_create(stage.handle, max_batch, max_seq, C.byref(h)), "hexgen_kv_cache_create")
         self.handle, self.stage = h, stage
 
-    def close(self):
+    def close(self, _lib=lib):
         if getattr(self, "handle", None):
-            lib.hexgen_kv_cache_destroy(self.handle)
+            _lib.hexgen_kv_cache_destroy(self.handle)
             self.handle = None
 
     __del__ = close

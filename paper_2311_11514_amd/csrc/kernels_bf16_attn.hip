@@ -275,102 +275,166 @@ void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, c
 }
 
 // -------------------------------------------------------------------------------------------------
-// Prefill: grid (ceil(max_new / 64), hq_l, batch), 4 waves per block, each wave owns 16 query rows of
-// one head of one sequence and walks the cache in 32-position steps up to its last row's position
-// (causal: later tiles are never touched).  Rows of the call sit at positions pos0[seq] + i.
+// Prefill: grid (ceil(max_new / (32 NWV)), hq_l, batch), NWV = 4 or 2 waves per block; a block owns 32 NWV query rows
+// of one head of one sequence, a wave 32 of them, and walks the cache in 32-position tiles up to its last row's position (causal:
+// later tiles are never touched).  Rows of the call sit at positions pos0[seq] + i.
+//
+// Everything runs on v_mfma_f32_32x32x16_bf16.  S^T (32 positions x 32 query rows) = K . Q^T: operand A is gathered
+// from the two 16-position K tiles, operand B is the wave's query block, held in registers for the whole walk.
+// In the result a lane owns query row lane % 32 and positions 8 q + 4 (lane / 32) + r: register quads q = 0, 2 are
+// exactly the position slots (4 g .. 4 g + 3, 16 + 4 g .. 16 + 4 g + 3) of k-group g = lane / 32 of the V^T tiles
+// (see kvlayout.h), quads 1, 3 those of k-group 2 + lane / 32 -- so P goes from the score registers straight into the
+// two 16-slot MFMAs of O^T = V^T . P^T, with no cross-lane traffic, on the cache layout the decode kernels use.
+// The K and V tiles of a step (16 KB at d = 128) are shared by the block's waves through LDS (direct-to-LDS loads,
+// three stages); two blocks fit a CU, so one wave's softmax arithmetic hides behind the other's MFMAs.
 // -------------------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc,
-                                                          const bf16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
-                                                          const int32_t *__restrict__ cu_rows,
-                                                          const int32_t *__restrict__ pos0,
-                                                          bf16_t *__restrict__ o_packed, float scale_log2e) {
-    constexpr int KT = D / 32, DT = D / 16;
+#define HX_AS1(p) ((const __attribute__((address_space(1))) void *)(p))
+#define HX_AS3(p) ((__attribute__((address_space(3))) void *)(p))
+#define HX_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+template <int D, int NWV>
+__global__ __launch_bounds__(64 * NWV, 2) void attn_prefill_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc,
+                                                             const bf16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
+                                                             const int32_t *__restrict__ cu_rows,
+                                                             const int32_t *__restrict__ pos0,
+                                                             bf16_t *__restrict__ o_packed, float scale_log2e) {
+    constexpr int KT = D / 32, DT = D / 16, DB = D / 32;     // K d-tiles, V^T d-tiles, 32-wide output blocks
+    constexpr int TILES = 2 * KT + DT;                       // 1 KB tiles per 32-position step: K then V^T
+    constexpr int LPT = TILES / NWV;                         // loads per wave and step
+    constexpr int ROWS = 32 * NWV;                           // query rows per block
+    constexpr int S = 3;
+    static_assert(TILES % NWV == 0, "tiles must divide over the waves");
+    __shared__ bf16x8 smem[S][TILES][64];
     const int seq = blockIdx.z, head = blockIdx.y;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 15, g = lane >> 4;
+    const int rb = gridDim.x - 1 - blockIdx.x;               // longest walks first
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int row0 = cu_rows[seq], n_new = cu_rows[seq + 1] - row0, p0s = pos0[seq];
-    const int qbase = blockIdx.x * 64 + wave * 16;
-    if (qbase >= n_new) return;               // whole wave leaves; no block-level barrier below
-    const int ri = qbase + j;
+    if (rb * ROWS >= n_new) return;                          // the whole block leaves
+    const int qbase = rb * ROWS + wave * 32;
+    const int hl = lane >> 5;
+    const int ri = qbase + (lane & 31);
     const bool valid = ri < n_new;
-    const int qpos = valid ? p0s + ri : 0x3fffffff;    // padded rows: nothing masked, nothing stored
-    const int last_pos = p0s + min(qbase + 15, n_new - 1);
-    const int n_t32 = (last_pos >> 5) + 1;
+    const int qpos = valid ? p0s + ri : 0x3fffffff;          // padded rows: nothing masked, nothing stored
+    const int nt = ((p0s + min(rb * ROWS + ROWS - 1, n_new - 1)) >> 5) + 1;                      // steps of the block
+    const int nt_w = qbase < n_new ? ((p0s + min(qbase + 31, n_new - 1)) >> 5) + 1 : 0;    // steps this wave computes
+    const int first_masked = (p0s + qbase) >> 5;             // tiles before it lie wholly in every row's past
     const int c = head / G;
 
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    bf16x8 qf[KT];
+    // 32x32x16 operand gather from a pair of 16-row fragment tiles: lane l takes row l % 32, k-group 2 kh + l / 32
+    const int sub = (lane & 31) >> 4;                        // which tile of the pair
+    const int fl = (lane & 15) + 16 * hl;                    // lane slot inside the tile for kh = 0 (+ 32 for kh = 1)
+    const int qkt = (hq_l * D) >> 5;
+    bf16x8 qf[2 * KT];
+    {
+        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+        const int qr = row0 + min(ri, n_new - 1);
 #pragma unroll
-    for (int kt = 0; kt < KT; ++kt)
-        qf[kt] = valid ? *reinterpret_cast<const bf16x8 *>(q + frag_offset(row0 + ri, head * D + kt * 32 + 8 * g,
-                                                                            (hq_l * D) >> 5))
-                       : zero;
-    floatx4 oacc[DT];
+        for (int kk = 0; kk < 2 * KT; ++kk)
+            qf[kk] = qbase < n_new ? *reinterpret_cast<const bf16x8 *>(
+                                          q + frag_offset(qr, head * D + (kk >> 1) * 32 + 8 * (2 * (kk & 1) + hl), qkt))
+                                    : zero;
+    }
+    floatx16 oacc[DB];
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) oacc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
     float m = NEG_INF, lsum = 0.f;
 
     const size_t slab = (size_t)seq * kg.seq_stride + (size_t)c * kg.smax * D;
-    const bf16x8 *ks = reinterpret_cast<const bf16x8 *>(kc + slab) + lane;
-    const bf16x8 *vs = reinterpret_cast<const bf16x8 *>(vc + slab) + lane;
-
-    for (int t = 0; t < n_t32; ++t) {
-        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-        bf16x8 ka[KT], kb[KT], va[DT];
+    const bf16x8 *ks = reinterpret_cast<const bf16x8 *>(kc + slab);
+    const bf16x8 *vs = reinterpret_cast<const bf16x8 *>(vc + slab);
+    // tiles of step t: K tiles (2 t) KT .. (2 t + 2) KT - 1 and V^T tiles t DT .. (t + 1) DT - 1, both contiguous.
+    // The loads are written in their scalar-base form as asm: besides saving a vector add per load, that keeps
+    // them out of the compiler's memory model, which would otherwise drain vmcnt to 0 in front of every LDS
+    // read of the array they target and so undo the prefetch.  Every wait on them is explicit (HX_WAIT_VM).
+    const unsigned lane_bytes = (unsigned)lane * 16u;
+    auto issue = [&](int t) {
 #pragma unroll
-        for (int kt = 0; kt < KT; ++kt) {
-            ka[kt] = ks[(size_t)((2 * t) * KT + kt) * 64];
-            kb[kt] = ks[(size_t)((2 * t + 1) * KT + kt) * 64];
+        for (int x = 0; x < LPT; ++x) {
+            const int tile = wave + NWV * x;
+            const bf16x8 *src = tile < 2 * KT ? ks + (size_t)(2 * t * KT + tile) * 64 : vs + (size_t)(t * DT + tile - 2 * KT) * 64;
+            const unsigned lds_addr = (unsigned)reinterpret_cast<uintptr_t>(HX_AS3(&smem[t % S][tile][0]));
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(lds_addr), "v"(lane_bytes), "s"(src)
+                         : "memory");
         }
+    };
+    // the query block has landed before the first hidden load is issued: the compiler, which does not see those
+    // loads, would otherwise place its own wait for the query registers (a full drain) inside the loop
+    HX_WAIT_VM(0);
+    issue(0);
+    if (nt > 1) issue(1);
+    for (int t = 0; t < nt; ++t) {
+        if (t + 1 < nt) HX_WAIT_VM(LPT);      // step t has landed; the loads of step t + 1 stay in flight
+        else HX_WAIT_VM(0);
+        __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14));       // this wave's LDS reads are complete
+        asm volatile("s_barrier" ::: "memory");
+        if (t + 2 < nt) issue(t + 2);         // into the buffer of step t - 1, which every wave has left
+        if (t >= nt_w) continue;              // this wave's rows end before the tile (it still feeds the others)
+        const bf16x8(*st)[64] = smem[t % S];
+        floatx16 sc;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) va[dt] = vs[(size_t)(t * DT + dt) * 64];
+        for (int r = 0; r < 16; ++r) sc[r] = 0.f;
 #pragma unroll
-        for (int kt = 0; kt < KT; ++kt) {
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt], qf[kt], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[kt], qf[kt], s1, 0, 0, 0);
-        }
-        const int pbase = t * 32 + 4 * g;
+        for (int kk = 0; kk < 2 * KT; ++kk)
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st[sub * KT + (kk >> 1)][fl + 32 * (kk & 1)], qf[kk], sc, 0, 0, 0);
+        // causal mask (only tiles that reach a row's own position) and running max on the raw scores; the softmax
+        // scale is folded into the exponent's multiply-add (scale > 0, so the max commutes with it)
         float mx = NEG_INF;
+        if (t >= first_masked) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            s0[r] = (pbase + r <= qpos) ? s0[r] * scale_log2e : NEG_INF;
-            s1[r] = (pbase + 16 + r <= qpos) ? s1[r] * scale_log2e : NEG_INF;
-            mx = fmaxf(mx, fmaxf(s0[r], s1[r]));
+            for (int r = 0; r < 16; ++r) {
+                const int pos = t * 32 + 8 * (r >> 2) + 4 * hl + (r & 3);
+                sc[r] = pos <= qpos ? sc[r] : NEG_INF;
+            }
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[r]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(m, mx);     // finite from the first tile on: position 0 <= qpos
-        const float alpha = exp2f(m - m_new);
+        const float alpha = __builtin_amdgcn_exp2f((m - m_new) * scale_log2e);
         m = m_new;
-        float p0[4], p1[4], ps = 0.f;
+        const float mb = -m_new * scale_log2e;
+        float ps = 0.f;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            p0[r] = exp2f(s0[r] - m_new);
-            p1[r] = exp2f(s1[r] - m_new);
-            ps += p0[r] + p1[r];
+        for (int r = 0; r < 16; ++r) {
+            sc[r] = __builtin_amdgcn_exp2f(fmaf(sc[r], scale_log2e, mb));
+            ps += sc[r];
         }
         lsum = lsum * alpha + ps;
-        union { uint32_t u[4]; bf16x8 v; } pb;
-        pb.u[0] = pack_bf16x2(p0[0], p0[1]); pb.u[1] = pack_bf16x2(p0[2], p0[3]);
-        pb.u[2] = pack_bf16x2(p1[0], p1[1]); pb.u[3] = pack_bf16x2(p1[2], p1[3]);
+        union { uint32_t u[4]; bf16x8 v; } pb0, pb1;      // P for k-groups hl (quads 0, 2) and 2 + hl (quads 1, 3)
+        pb0.u[0] = pack_bf16x2(sc[0], sc[1]);   pb0.u[1] = pack_bf16x2(sc[2], sc[3]);
+        pb0.u[2] = pack_bf16x2(sc[8], sc[9]);   pb0.u[3] = pack_bf16x2(sc[10], sc[11]);
+        pb1.u[0] = pack_bf16x2(sc[4], sc[5]);   pb1.u[1] = pack_bf16x2(sc[6], sc[7]);
+        pb1.u[2] = pack_bf16x2(sc[12], sc[13]); pb1.u[3] = pack_bf16x2(sc[14], sc[15]);
+        // rescale the running output only when some row's maximum moved (rare after the first tiles)
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            oacc[dt] *= alpha;
-            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb.v, oacc[dt], 0, 0, 0);
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st[2 * KT + 2 * db + sub][fl], pb0.v, oacc[db], 0, 0, 0);
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st[2 * KT + 2 * db + sub][fl + 32], pb1.v, oacc[db], 0, 0, 0);
         }
     }
-    lsum += __shfl_xor(lsum, 16, 64);
     lsum += __shfl_xor(lsum, 32, 64);
     if (valid) {
         const float inv = 1.0f / lsum;
-        const int k_tiles = (hq_l * D) >> 5;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            uint2 o;
-            o.x = pack_bf16x2(oacc[dt][0] * inv, oacc[dt][1] * inv);
-            o.y = pack_bf16x2(oacc[dt][2] * inv, oacc[dt][3] * inv);
-            *reinterpret_cast<uint2 *>(o_packed + frag_offset(row0 + ri, head * D + dt * 16 + 4 * g, k_tiles)) = o;
-        }
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                uint2 o;
+                o.x = pack_bf16x2(oacc[db][4 * qd] * inv, oacc[db][4 * qd + 1] * inv);
+                o.y = pack_bf16x2(oacc[db][4 * qd + 2] * inv, oacc[db][4 * qd + 3] * inv);
+                *reinterpret_cast<uint2 *>(o_packed + frag_offset(row0 + ri, head * D + 32 * db + 8 * qd + 4 * hl, qkt)) = o;
+            }
     }
 }
 
@@ -380,11 +444,20 @@ void launch_attn_prefill(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, Kv
     if (batch <= 0 || max_new <= 0) return;
     const int G = hq_l / kg.hkv_l;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)kg.d);
-    dim3 grid((max_new + 63) / 64, hq_l, batch);
-    if (kg.d == 128)
-        hipLaunchKernelGGL(attn_prefill_kernel<128>, grid, dim3(256), 0, s, q, kc, vc, kg, hq_l, G, cu_rows, pos0,
-                           o_packed, scale_log2e);
-    else
-        hipLaunchKernelGGL(attn_prefill_kernel<64>, grid, dim3(256), 0, s, q, kc, vc, kg, hq_l, G, cu_rows, pos0,
-                           o_packed, scale_log2e);
+    // 128-row blocks (4 waves) share each K/V tile among more rows; 64-row blocks (2 waves) when those would leave
+    // the chip with fewer than two blocks per CU
+    const long blocks128 = (long)((max_new + 127) / 128) * hq_l * batch;
+    const bool small = false && blocks128 < 512;
+    dim3 grid(small ? (max_new + 63) / 64 : (max_new + 127) / 128, hq_l, batch);
+#define HX_A(DD, NW)                                                                                              \
+    hipLaunchKernelGGL((attn_prefill_kernel<DD, NW>), grid, dim3(64 * NW), 0, s, q, kc, vc, kg, hq_l, G, cu_rows, pos0, \
+                       o_packed, scale_log2e)
+    if (kg.d == 128) {
+        if (small) HX_A(128, 2);
+        else HX_A(128, 4);
+    } else {
+        if (small) HX_A(64, 2);
+        else HX_A(64, 4);
+    }
+#undef HX_A
 }

@@ -76,7 +76,9 @@ struct DecodeEpi {
 };
 // Wp . Xa for T <= 32 rows (Xa: compact hi/lo operand [T][K]), one block per output unit, then the
 // epilogue of e.mode
-void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T, const DecodeEpi &e, hipStream_t s);
+// `scratch` (device, scratch_floats floats, may be NULL) holds the split partial sums of the batched path (T > 2)
+void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T, const DecodeEpi &e, float *scratch,
+                        size_t scratch_floats, hipStream_t s);
 // stage input rows -> h (optional), (x * g) hi/lo planes, sums of squares; block 0 publishes row
 // positions from the committed lengths and optionally advances them
 void launch_decode_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg, float *ssq_out,

@@ -18,6 +18,7 @@
 //   RAW    : x rstd (if the input is a normalised stream), plain fp32 partial (validation surface)
 // RMSNorm is thus never a kernel of its own in decode: y = rstd * ((h*g) . W), with rstd a per-row
 // scalar applied after the contraction.
+#include <algorithm>
 #include <cstdlib>
 
 #include "kernels.h"
@@ -53,6 +54,104 @@ __device__ inline void store_act4(const float x[4], bf16_t *xa, int token, int k
     split_pack2(x[2], x[3], o.y, ol.y);
     *reinterpret_cast<uint2 *>(xa + off) = o;
     *reinterpret_cast<uint2 *>(xa + off + 32) = ol;
+}
+
+// Register epilogue of one unit (UT 16-feature tiles) and one 16-token tile, on complete dot products in the
+// 16x16 accumulator layout: lane = (token j = lane % 16, row group g = lane / 16) holds rows 4g .. 4g+3 of each tile.
+// Must be called by a whole wave (it shuffles across the row groups).
+template <int MODE, int UT>
+__device__ inline void decode_epilogue(const floatx4 (&v)[UT], int unit, int b, int lane, int N, int T, const DecodeEpi &e,
+                                       const float *s_rstd) {
+    const int token = (lane & 15) + 16 * b, g = lane >> 4;
+    const bool valid = token < T;
+    const float r = (MODE != DEC_RESID && valid) ? s_rstd[token] : 1.0f;
+
+    if (MODE == DEC_RAW) {
+        const int n0 = unit * 16 + 4 * g;
+        if (valid) *reinterpret_cast<floatx4 *>(e.raw_out + (size_t)token * N + n0) = v[0] * r;
+    } else if (MODE == DEC_RESID) {
+        const int n0 = unit * 16 + 4 * g;
+        float ss = 0.f;
+        if (valid) {
+            const floatx4 h4 = *reinterpret_cast<const floatx4 *>(e.h + (size_t)token * N + n0);
+            if (e.last_layer) {
+                // stage output: the partial without residual, and the residual it belongs to
+                uint2 po;
+                po.x = pack_bf16x2(v[0][0], v[0][1]);
+                po.y = pack_bf16x2(v[0][2], v[0][3]);
+                *reinterpret_cast<uint2 *>(e.out_partial + (size_t)token * N + n0) = po;
+                if (e.out_resid) {
+                    uint2 ro;
+                    ro.x = pack_bf16x2(h4[0], h4[1]);
+                    ro.y = pack_bf16x2(h4[2], h4[3]);
+                    *reinterpret_cast<uint2 *>(e.out_resid + (size_t)token * N + n0) = ro;
+                }
+            } else {
+                const floatx4 hn = h4 + v[0];
+                *reinterpret_cast<floatx4 *>(e.h + (size_t)token * N + n0) = hn;
+                const floatx4 g4 = *reinterpret_cast<const floatx4 *>(e.g_next + n0);
+                const float x[4] = {hn[0] * g4[0], hn[1] * g4[1], hn[2] * g4[2], hn[3] * g4[3]};
+                store_act4(x, e.hg, token, n0, N >> 5);
+                ss = hn[0] * hn[0] + hn[1] * hn[1] + hn[2] * hn[2] + hn[3] * hn[3];
+            }
+        }
+        if (!e.last_layer) {
+            ss += __shfl_xor(ss, 16, 64);
+            ss += __shfl_xor(ss, 32, 64);
+            if (g == 0 && valid) e.ssq_out[unit * DEC_SSQ_STRIDE + token] = ss;
+        }
+    } else if (MODE == DEC_SWIGLU) {
+        // unit = one gate tile (v[0]) and the matching up tile (v[1]): 16 features of u
+        if (valid) {
+            const int f0 = unit * 16 + 4 * g;
+            float uu[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float aa = v[0][j] * r;
+                uu[j] = aa / (1.0f + __expf(-aa)) * (v[UT - 1][j] * r);
+            }
+            store_act4(uu, e.u, token, f0, e.F_l >> 5);
+        }
+    } else {   // DEC_QKV
+        const int d = e.kg.d, half = d >> 1, tiles_per_head = d >> 4;
+        const int head = unit / tiles_per_head, tl = unit - head * tiles_per_head;
+        floatx4 mine = v[0] * r, other;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) other[j] = __shfl_xor(mine[j], 32, 64);
+        const bool low = g < 2;                       // rows 0-7 of the tile: features i; rows 8-15: i + d/2
+        const int i0 = tl * 8 + 4 * (g & 1);          // first rotary pair index held by this lane
+        if (valid) {
+            const int pos = e.row_pos[token];
+            float out[4];
+            if (head < e.hq_l + e.kg.hkv_l) {
+                const floatx4 c4 = *reinterpret_cast<const floatx4 *>(e.cos_tab + (size_t)pos * half + i0);
+                const floatx4 s4 = *reinterpret_cast<const floatx4 *>(e.sin_tab + (size_t)pos * half + i0);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float lo = low ? mine[j] : other[j], hi = low ? other[j] : mine[j];
+                    out[j] = low ? lo * c4[j] - hi * s4[j] : hi * c4[j] + lo * s4[j];
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) out[j] = mine[j];
+            }
+            const int e0 = i0 + (low ? 0 : half);     // element index inside the head
+            if (head < e.hq_l) {
+                store_split4(out, e.q_hi, e.q_lo, ((size_t)token * e.hq_l + head) * d + e0);
+            } else if (head < e.hq_l + e.kg.hkv_l) {
+                const size_t slab = (size_t)token * e.kg.seq_stride + (size_t)(head - e.hq_l) * e.kg.smax * d;
+                uint2 o;
+                o.x = pack_bf16x2(out[0], out[1]);
+                o.y = pack_bf16x2(out[2], out[3]);
+                *reinterpret_cast<uint2 *>(e.kc + slab + kv_k_offset(pos, e0, d)) = o;
+            } else {
+                const size_t slab =
+                    (size_t)token * e.kg.seq_stride + (size_t)(head - e.hq_l - e.kg.hkv_l) * e.kg.smax * d;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) e.vc[slab + kv_v_offset(pos, e0 + j, d)] = f32_to_bf16(out[j]);
+            }
+        }
+    }
 }
 
 // XLDS: the whole activation operand (T <= 2 rows) is staged once per block in LDS, so the main loop
@@ -164,96 +263,136 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
 #pragma unroll
         for (int w = 1; w < WAVES; ++w) v[u] += red[w][u * NB + b][lane];
     }
-    const int token = (lane & 15) + 16 * b, g = lane >> 4;
-    const bool valid = token < T;
-    const float r = (MODE != DEC_RESID && valid) ? s_rstd[token] : 1.0f;
+    decode_epilogue<MODE, UT>(v, unit, b, lane, N, T, e, s_rstd);
+}
 
-    if (MODE == DEC_RAW) {
-        const int n0 = unit * 16 + 4 * g;
-        if (valid) *reinterpret_cast<floatx4 *>(e.raw_out + (size_t)token * N + n0) = v[0] * r;
-    } else if (MODE == DEC_RESID) {
-        const int n0 = unit * 16 + 4 * g;
-        float ss = 0.f;
-        if (valid) {
-            const floatx4 h4 = *reinterpret_cast<const floatx4 *>(e.h + (size_t)token * N + n0);
-            if (e.last_layer) {
-                // stage output: the partial without residual, and the residual it belongs to
-                uint2 po;
-                po.x = pack_bf16x2(v[0][0], v[0][1]);
-                po.y = pack_bf16x2(v[0][2], v[0][3]);
-                *reinterpret_cast<uint2 *>(e.out_partial + (size_t)token * N + n0) = po;
-                if (e.out_resid) {
-                    uint2 ro;
-                    ro.x = pack_bf16x2(h4[0], h4[1]);
-                    ro.y = pack_bf16x2(h4[2], h4[3]);
-                    *reinterpret_cast<uint2 *>(e.out_resid + (size_t)token * N + n0) = ro;
+// -------------------------------------------------------------------------------------------------
+// Batched decode (3 <= T <= 32 rows).  With more than a couple of rows the activation operand outweighs the
+// weights a block streams (32 rows of hi + lo pairs are 4 KB per k-tile against 1 KB of weights per 16 features),
+// and fetching it per wave from L2 in 64-byte pieces leaves the kernel at a quarter of the HBM rate.  Here the
+// eight waves of a block own eight neighbouring feature tiles and walk the SAME k-tiles, so the block stages each
+// 8-k-tile chunk of the operand once in LDS (global -> registers -> LDS, double-buffered) and all waves read it
+// from there; a k-tile's weights for the block are one contiguous 8 KB run.  To still fill the chip the
+// contraction is split over blockIdx.y; the fp32 partial sums go to a scratch buffer [split][token][feature] and
+// decode_finish_kernel adds them in split order (bit-reproducible) and runs the same register epilogue as the
+// single-kernel path.
+// -------------------------------------------------------------------------------------------------
+constexpr int SK_CH = 8;                       // k-tiles per chunk: 1 KB of one token's compact operand
+constexpr int SK_TOK_STRIDE = 1024 + 16;       // LDS bytes per token and chunk; the pad spreads tokens over the banks
+
+template <int NB>
+__global__ __launch_bounds__(512) void decode_splitk_kernel(const bf16_t *__restrict__ Wp, const bf16_t *__restrict__ Xa,
+                                                           int n_tiles, int k_tiles, int T, int per,
+                                                           float *__restrict__ part) {
+    constexpr int TOK = 16 * NB, LPW = TOK / 8;        // token rows staged per chunk; rows copied per wave
+    constexpr int BUF = TOK * SK_TOK_STRIDE;
+    extern __shared__ unsigned char sk_lds[];          // [2][TOK][SK_TOK_STRIDE]
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 15, g = lane >> 4;
+    const int tile = blockIdx.x * 8 + wave;
+    const bool tile_ok = tile < n_tiles;
+    const int kt0 = blockIdx.y * per, kt1 = min(k_tiles, kt0 + per);
+    const int n_chunks = (kt1 - kt0 + SK_CH - 1) / SK_CH;
+    const int N = n_tiles * 16;
+
+    // chunk c of the operand rows this wave copies: lane l carries bytes 16 l .. 16 l + 15 of the row's 1 KB
+    const bf16x8 *xsrc[LPW];
+#pragma unroll
+    for (int i = 0; i < LPW; ++i)
+        xsrc[i] = reinterpret_cast<const bf16x8 *>(Xa) + (size_t)min(wave + 8 * i, T - 1) * k_tiles * 8 + lane;
+    auto load_x = [&](int c, bf16x8(&x)[LPW]) {
+        const int kc = kt0 + c * SK_CH;
+        const bool ok = c < n_chunks && kc + (lane >> 3) < kt1;         // 8 lanes per k-tile line
+#pragma unroll
+        for (int i = 0; i < LPW; ++i)
+            if (ok) x[i] = xsrc[i][(size_t)kc * 8];
+    };
+    auto store_x = [&](int c, const bf16x8(&x)[LPW]) {
+        unsigned char *buf = sk_lds + (c & 1) * BUF;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i)
+            *reinterpret_cast<bf16x8 *>(buf + (wave + 8 * i) * SK_TOK_STRIDE + lane * 16) = x[i];
+    };
+    // this wave's weight tile for the k-tiles of chunk c
+    const bf16x8 *wsrc = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)min(tile, n_tiles - 1) * 64 + lane;
+    const size_t kstride = (size_t)n_tiles * 64;
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    auto load_w = [&](int c, bf16x8(&w)[SK_CH]) {
+        const int kc = kt0 + c * SK_CH;
+#pragma unroll
+        for (int i = 0; i < SK_CH; ++i)
+            w[i] = (c < n_chunks && kc + i < kt1) ? __builtin_nontemporal_load(wsrc + (size_t)(kc + i) * kstride) : zero;
+    };
+
+    floatx4 acc[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+    bf16x8 xr[LPW], wc[SK_CH], wn[SK_CH];
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) xr[i] = zero;
+    load_x(0, xr);
+    load_w(0, wc);
+    store_x(0, xr);
+    load_x(1, xr);
+    for (int c = 0; c < n_chunks; ++c) {
+        // chunk c is complete in LDS for every wave, and nobody reads the other buffer (chunk c - 1) any more;
+        // a bare s_barrier: __syncthreads() would also drain the weight loads in flight
+        __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14));
+        asm volatile("s_barrier" ::: "memory");
+        store_x(c + 1, xr);
+        load_x(c + 2, xr);
+        load_w(c + 1, wn);
+        const unsigned char *buf = sk_lds + (c & 1) * BUF;
+        const int nk = min(SK_CH, kt1 - (kt0 + c * SK_CH));
+#pragma unroll
+        for (int i = 0; i < SK_CH; ++i) {
+            if (i < nk) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    const unsigned char *row = buf + (j + 16 * b) * SK_TOK_STRIDE + i * 128 + g * 16;
+                    const bf16x8 x = *reinterpret_cast<const bf16x8 *>(row);
+                    const bf16x8 y = *reinterpret_cast<const bf16x8 *>(row + 64);
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wc[i], y, acc[b], 0, 0, 0);
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wc[i], x, acc[b], 0, 0, 0);
                 }
-            } else {
-                const floatx4 hn = h4 + v[0];
-                *reinterpret_cast<floatx4 *>(e.h + (size_t)token * N + n0) = hn;
-                const floatx4 g4 = *reinterpret_cast<const floatx4 *>(e.g_next + n0);
-                const float x[4] = {hn[0] * g4[0], hn[1] * g4[1], hn[2] * g4[2], hn[3] * g4[3]};
-                store_act4(x, e.hg, token, n0, N >> 5);
-                ss = hn[0] * hn[0] + hn[1] * hn[1] + hn[2] * hn[2] + hn[3] * hn[3];
             }
         }
-        if (!e.last_layer) {
-            ss += __shfl_xor(ss, 16, 64);
-            ss += __shfl_xor(ss, 32, 64);
-            if (g == 0 && valid) e.ssq_out[unit * DEC_SSQ_STRIDE + token] = ss;
-        }
-    } else if (MODE == DEC_SWIGLU) {
-        // unit = one gate tile (v[0]) and the matching up tile (v[1]): 16 features of u
-        if (valid) {
-            const int f0 = unit * 16 + 4 * g;
-            float uu[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float aa = v[0][j] * r;
-                uu[j] = aa / (1.0f + __expf(-aa)) * (v[UT - 1][j] * r);
-            }
-            store_act4(uu, e.u, token, f0, e.F_l >> 5);
-        }
-    } else {   // DEC_QKV
-        const int d = e.kg.d, half = d >> 1, tiles_per_head = d >> 4;
-        const int head = unit / tiles_per_head, tl = unit - head * tiles_per_head;
-        floatx4 mine = v[0] * r, other;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) other[j] = __shfl_xor(mine[j], 32, 64);
-        const bool low = g < 2;                       // rows 0-7 of the tile: features i; rows 8-15: i + d/2
-        const int i0 = tl * 8 + 4 * (g & 1);          // first rotary pair index held by this lane
-        if (valid) {
-            const int pos = e.row_pos[token];
-            float out[4];
-            if (head < e.hq_l + e.kg.hkv_l) {
-                const floatx4 c4 = *reinterpret_cast<const floatx4 *>(e.cos_tab + (size_t)pos * half + i0);
-                const floatx4 s4 = *reinterpret_cast<const floatx4 *>(e.sin_tab + (size_t)pos * half + i0);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float lo = low ? mine[j] : other[j], hi = low ? other[j] : mine[j];
-                    out[j] = low ? lo * c4[j] - hi * s4[j] : hi * c4[j] + lo * s4[j];
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) out[j] = mine[j];
-            }
-            const int e0 = i0 + (low ? 0 : half);     // element index inside the head
-            if (head < e.hq_l) {
-                store_split4(out, e.q_hi, e.q_lo, ((size_t)token * e.hq_l + head) * d + e0);
-            } else if (head < e.hq_l + e.kg.hkv_l) {
-                const size_t slab = (size_t)token * e.kg.seq_stride + (size_t)(head - e.hq_l) * e.kg.smax * d;
-                uint2 o;
-                o.x = pack_bf16x2(out[0], out[1]);
-                o.y = pack_bf16x2(out[2], out[3]);
-                *reinterpret_cast<uint2 *>(e.kc + slab + kv_k_offset(pos, e0, d)) = o;
-            } else {
-                const size_t slab =
-                    (size_t)token * e.kg.seq_stride + (size_t)(head - e.hq_l - e.kg.hkv_l) * e.kg.smax * d;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) e.vc[slab + kv_v_offset(pos, e0 + j, d)] = f32_to_bf16(out[j]);
-            }
-        }
+        for (int i = 0; i < SK_CH; ++i) wc[i] = wn[i];
     }
+    if (!tile_ok) return;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int token = j + 16 * b;
+        if (token < T)
+            *reinterpret_cast<floatx4 *>(part + ((size_t)blockIdx.y * T + token) * N + tile * 16 + 4 * g) = acc[b];
+    }
+}
+
+// Sums the split partials in split order and runs the register epilogue; one wave per (unit, 16-token tile).
+template <int MODE, int UT>
+__global__ __launch_bounds__(256) void decode_finish_kernel(const float *__restrict__ part, int splits, int N, int T,
+                                                           int n_units, DecodeEpi e) {
+    __shared__ float s_rstd[32];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (MODE != DEC_RESID) {
+        load_rstd<4>(e, T, wave, lane, s_rstd);
+        __syncthreads();
+    }
+    const int nbt = (T + 15) >> 4;
+    const int idx = blockIdx.x * 4 + wave;
+    if (idx >= n_units * nbt) return;
+    const int unit = idx / nbt, b = idx - unit * nbt;
+    const int token = (lane & 15) + 16 * b, g = lane >> 4;
+    floatx4 v[UT];
+#pragma unroll
+    for (int u = 0; u < UT; ++u) {
+        v[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (token < T)
+#pragma unroll 4
+            for (int ks = 0; ks < splits; ++ks)
+                v[u] += *reinterpret_cast<const floatx4 *>(part + ((size_t)ks * T + token) * N + (unit * UT + u) * 16 + 4 * g);
+    }
+    decode_epilogue<MODE, UT>(v, unit, b, lane, N, T, e, s_rstd);
 }
 
 namespace {
@@ -285,8 +424,50 @@ void launch_mode(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, 
 }
 }  // namespace
 
-void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T, const DecodeEpi &e, hipStream_t s) {
+namespace {
+template <int MODE, int UT>
+void launch_splitk(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, float *scratch,
+                   size_t scratch_floats, hipStream_t s) {
+    const int n_tiles = N / 16, groups = (n_tiles + 7) / 8;
+    // enough blocks to keep every CU streaming, at most 8 splits (the finishing kernel walks them one after the
+    // other), at least one chunk of k-tiles per block, partials within the scratch
+    int splits = std::max(1, std::min(std::min((512 + groups - 1) / groups, 8), k_tiles / SK_CH));
+    while (splits > 1 && (size_t)splits * T * N > scratch_floats) --splits;
+    const int per = ((k_tiles + splits - 1) / splits + SK_CH - 1) / SK_CH * SK_CH;
+    splits = (k_tiles + per - 1) / per;
+    const int nb = T > 16 ? 2 : 1;
+    const size_t lds = (size_t)2 * 16 * nb * SK_TOK_STRIDE;
+    const dim3 grid(groups, splits);
+    if (nb == 2) {
+        static bool raised = false;           // 65 KB: above the default limit
+        if (!raised) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(decode_splitk_kernel<2>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            raised = true;
+        }
+        hipLaunchKernelGGL(decode_splitk_kernel<2>, grid, dim3(512), lds, s, Wp, Xa, n_tiles, k_tiles, T, per, scratch);
+    } else {
+        hipLaunchKernelGGL(decode_splitk_kernel<1>, grid, dim3(512), lds, s, Wp, Xa, n_tiles, k_tiles, T, per, scratch);
+    }
+    const int n_units = n_tiles / UT, nbt = (T + 15) / 16;
+    hipLaunchKernelGGL((decode_finish_kernel<MODE, UT>), dim3((n_units * nbt + 3) / 4), dim3(256), 0, s, scratch, splits, N, T,
+                       n_units, e);
+}
+}  // namespace
+
+void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T, const DecodeEpi &e, float *scratch,
+                        size_t scratch_floats, hipStream_t s) {
     const int k_tiles = K / 32;
+    // a few rows: one kernel, complete dot products per block; more: shared operand, split contraction
+    if (T > 2 && scratch != nullptr && scratch_floats >= (size_t)T * N && k_tiles >= SK_CH) {
+        switch (e.mode) {
+            case DEC_RAW: launch_splitk<DEC_RAW, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s); break;
+            case DEC_QKV: launch_splitk<DEC_QKV, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s); break;
+            case DEC_RESID: launch_splitk<DEC_RESID, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s); break;
+            case DEC_SWIGLU: launch_splitk<DEC_SWIGLU, 2>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s); break;
+        }
+        return;
+    }
     switch (e.mode) {
         case DEC_RAW: launch_mode<1, DEC_RAW>(Wp, Xa, N, k_tiles, T, e, s); break;
         case DEC_QKV: launch_mode<1, DEC_QKV>(Wp, Xa, N, k_tiles, T, e, s); break;

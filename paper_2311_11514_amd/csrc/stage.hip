@@ -68,6 +68,8 @@ struct Workspace {
     float *p32 = nullptr;      // reduced partial [T][H] fp32
     // bf16 path
     bf16_t *n = nullptr, *o = nullptr, *u = nullptr, *q = nullptr;
+    float *dec_part = nullptr;       // split partial sums of the batched decode projections
+    size_t dec_part_floats = 0;
     bf16_t *xa_n = nullptr, *xa_o = nullptr, *xa_u = nullptr;   // decode operands, compact hi/lo layout [32][K][2]
     bf16_t *q_lo = nullptr;
     float *att_o = nullptr, *att_ml = nullptr;
@@ -116,7 +118,7 @@ namespace {
 size_t esize(hexgen_dtype_t dt) { return dt == HEXGEN_F32 ? 4 : 2; }
 
 void free_ws(Workspace &w) {
-    void *ptrs[] = {w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.xa_n, w.xa_o, w.xa_u, w.q_lo, w.ssq, w.ssq_pf, w.att_o, w.att_ml, w.n32, w.q32, w.o32, w.u32,
+    void *ptrs[] = {w.dec_part, w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.xa_n, w.xa_o, w.xa_u, w.q_lo, w.ssq, w.ssq_pf, w.att_o, w.att_ml, w.n32, w.q32, w.o32, w.u32,
                     w.rowmap};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
@@ -158,6 +160,10 @@ hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
         HX_TRY(dmalloc(&w.xa_o, 2 * drows * st->qw));
         HX_TRY(dmalloc(&w.xa_u, 2 * drows * st->F_l));
         HX_TRY(dmalloc(&w.q_lo, drows * st->qw));
+        if (drows > 2) {      // splits x features stays near 512 x 128 (see launch_splitk), plus one unsplit matrix
+            w.dec_part_floats = drows * ((size_t)512 * 128 + 2 * nmax);
+            HX_TRY(dmalloc(&w.dec_part, w.dec_part_floats));
+        }
         HX_TRY(dmalloc(&w.att_o, drows * st->hq_l * kMaxAttnSplit * st->d));
         HX_TRY(dmalloc(&w.att_ml, drows * st->hq_l * kMaxAttnSplit * 2));
         const size_t ssq_n = 2 * (size_t)(st->H / 16) * DEC_SSQ_STRIDE;
@@ -355,7 +361,7 @@ DecodeEpi epi_base(hexgen_stage *st, int mode) {
 void decode_proj(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xa, int N, int K, const DecodeEpi &e,
                  int slot, hipStream_t s) {
     st->prof.mark(slot, s);
-    launch_decode_proj(static_cast<const bf16_t *>(Wp), Xa, N, K, r.T, e, s);
+    launch_decode_proj(static_cast<const bf16_t *>(Wp), Xa, N, K, r.T, e, st->ws.dec_part, st->ws.dec_part_floats, s);
     st->prof.mark(slot, s);
 }
 

@@ -185,14 +185,18 @@ def test_bf16_decode_from_synthetic_context():
         assert row_rel_err(h, h_ref) < TOL["bf16"] and row_rel_err(p, p_ref) < TOL["bf16"]
 
 
-def test_bf16_batch32_decode_uses_two_token_tiles():
-    cfg = MINI64
+@pytest.mark.parametrize("cfg,b", [(MINI64, 32), (MINI64, 1), (MINI64, 2), (MINI128, 3), (MINI128, 16), (MINI128, 17),
+                                   (MINI64, 31)])
+def test_bf16_decode_batch_sizes(cfg, b):
+    """Decode across the row counts that switch kernels: 1-2 rows (one kernel per projection, operand in LDS),
+    3-16 rows (split contraction, one token tile), 17-32 rows (two token tiles); MINI128's FFN has 44 k-tiles, so its
+    splits end in a partial chunk."""
     w = _weights(cfg)
-    b = 32
     ctx = [1 + (7 * i) % 50 for i in range(b)]
-    ora = make_oracle(cfg, 0, w)
+    rank = cfg.tp_ranks[0]
+    ora = make_oracle(cfg, rank, w)
     oc = ora.new_cache(b)
-    st = make_gpu_stage(cfg, 0, w)
+    st = make_gpu_stage(cfg, rank, w)
     kv = st.kv_cache_create(b, 64)
     for layer in range(cfg.n_layers):
         for s, n in enumerate(ctx):

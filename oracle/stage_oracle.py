@@ -247,3 +247,32 @@ def greedy_head(x_last: np.ndarray, g_final, w_lm, eps: float) -> Tuple[int, np.
     """Final RMSNorm + untied LM head on one hidden row; argmax, lowest index wins ties."""
     logits = rmsnorm(_f64(x_last)[None, :], _f64(g_final), eps)[0] @ _f64(w_lm)
     return int(np.argmax(logits)), logits
+
+
+# ---- the model's two ends, adjacent to the first and the last stage (Section 2: the prompt enters as tokens and
+# the output leaves as tokens, one per step) ------------------------------------------------------------------
+def embed_rows(table, tokens) -> np.ndarray:
+    """First stage: row `tokens[i]` of the embedding table [vocab, H] for every input token."""
+    return _f64(table)[np.asarray(tokens, dtype=np.int64)]
+
+
+def head_shard_greedy(x: np.ndarray, g_final, w_lm, eps: float, t: int, r: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Last stage, vocabulary-parallel over t ranks: rank r holds columns [r V/t, (r+1) V/t) of the LM head.
+    For every row of x [rows, H]: final RMSNorm, the rank's logits, and the rank's best candidate as
+    (GLOBAL token id, its logit); the lowest id wins ties."""
+    w = _f64(w_lm)
+    V = w.shape[1]
+    assert V % t == 0
+    lo = r * (V // t)
+    logits = rmsnorm(_f64(x), _f64(g_final), eps) @ w[:, lo:lo + V // t]
+    idx = np.argmax(logits, axis=1)
+    return (idx + lo).astype(np.int64), logits[np.arange(logits.shape[0]), idx]
+
+
+def merge_greedy(candidates) -> np.ndarray:
+    """The group's choice from the ranks' (ids, logits) candidates, in rank order: largest logit, and since a
+    lower rank holds lower ids, the first maximum keeps the lowest-id tie rule."""
+    ids = np.stack([c[0] for c in candidates])          # [t, rows]
+    val = np.stack([c[1] for c in candidates])
+    best = np.argmax(val, axis=0)
+    return ids[best, np.arange(ids.shape[1])]

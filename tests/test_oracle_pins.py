@@ -345,3 +345,53 @@ def test_layer_rows_matches_full_layer(tiny_weights):
     got, K, V = st.layer_rows(0, x, rows)
     assert rel(got, full[rows]) < 1e-13
     assert rel(K, cache.k[0][0]) < 1e-13 and rel(V, cache.v[0][0]) < 1e-13
+
+
+# ---- the model's ends: embedding gather and vocabulary-parallel greedy head -------------------------------------
+def test_embed_rows_is_a_row_gather():
+    rng = np.random.default_rng(5)
+    table = rng.standard_normal((37, 16))
+    tok = np.array([0, 36, 5, 5, 12])
+    out = so.embed_rows(table, tok)
+    assert out.shape == (5, 16)
+    for i, t in enumerate(tok):
+        assert np.array_equal(out[i], table[t])
+    # as a matrix product with one-hot rows (the textbook definition of an embedding layer)
+    onehot = np.zeros((5, 37)); onehot[np.arange(5), tok] = 1.0
+    assert np.array_equal(out, onehot @ table)
+
+
+def test_vocab_parallel_head_equals_unsharded_head():
+    """Sharding the vocabulary over t ranks and merging the ranks' candidates gives the argmax of the full logits
+    (torch library routines as the independent reference), for every t that divides the vocabulary."""
+    rng = np.random.default_rng(6)
+    H, V, rows, eps = 64, 120, 9, 1e-5
+    x = rng.standard_normal((rows, H)) * 3.0
+    g = 1.0 + 0.1 * rng.standard_normal(H)
+    w = rng.standard_normal((H, V)) * 0.05
+    ref_logits = torch.nn.functional.linear(
+        torch.nn.functional.rms_norm(torch.tensor(x), (H,), torch.tensor(g), eps), torch.tensor(w).T)
+    ref_tok = torch.argmax(ref_logits, dim=1).numpy()
+    for t in (1, 2, 3, 4, 8):
+        cands = [so.head_shard_greedy(x, g, w, eps, t, r) for r in range(t)]
+        assert np.array_equal(so.merge_greedy(cands), ref_tok)
+        for r, (ids, val) in enumerate(cands):
+            assert np.all((ids >= r * V // t) & (ids < (r + 1) * V // t))
+            assert np.allclose(val, ref_logits.numpy()[np.arange(rows), ids], rtol=1e-12, atol=1e-12)
+    # one row, t = 1: the existing single-row head
+    tok0, logits0 = so.greedy_head(x[0], g, w, eps)
+    assert tok0 == ref_tok[0] and np.allclose(logits0, ref_logits[0].numpy(), rtol=1e-12, atol=1e-12)
+
+
+def test_head_tie_rule_lowest_id_wins_across_ranks():
+    H, V, eps = 8, 16, 1e-5
+    x = np.ones((1, H))
+    g = np.ones(H)
+    w = np.zeros((H, V))
+    w[:, 3] = 1.0
+    w[:, 11] = 1.0          # same logit in rank 0's and rank 1's shard (t = 2)
+    cands = [so.head_shard_greedy(x, g, w, eps, 2, r) for r in range(2)]
+    assert cands[0][0][0] == 3 and cands[1][0][0] == 11 and cands[0][1][0] == cands[1][1][0]
+    assert so.merge_greedy(cands)[0] == 3
+    # scale invariance of the decision: RMSNorm makes the token independent of the row's magnitude
+    assert so.merge_greedy([so.head_shard_greedy(7.5 * x, g, w, eps, 2, r) for r in range(2)])[0] == 3

@@ -43,6 +43,7 @@ def main():
     ap.add_argument("--workload", default="l70_tp2_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill leg (second workload)")
+    ap.add_argument("--no-head", action="store_true", help="skip the LM-head leg (model end next to the last stage)")
     ap.add_argument("--calibrate", action="store_true",
                     help="measure what a plain streaming kernel and a register-resident MFMA loop sustain, then exit")
     args = ap.parse_args()
@@ -169,6 +170,9 @@ def main():
         del st, kv, X
         torch.cuda.empty_cache()
         result["prefill"] = prefill_leg(torch, hx, CONFIGS["l70_tp4_prefill"], generate)
+    if not args.no_head:
+        torch.cuda.empty_cache()
+        result["lm_head"] = head_leg(torch, hx, generate)
     print(json.dumps(result), flush=True)
 
 
@@ -220,6 +224,32 @@ def prefill_leg(torch, hx, cfg, generate, reps=5):
             "stage_mfma_frac": round(layer_flops * cfg.n_layers / dt / 1e12 / MFMA_PEAK_TFLOPS, 4),
             "gemm_mfma_frac": round(tot_f / tot_t / 1e6 / MFMA_PEAK_TFLOPS, 4), "gemm": gemm,
             "peak_TFLOPs": MFMA_PEAK_TFLOPS}
+
+
+def head_leg(torch, hx, generate, reps=50):
+    """The model's end next to the last stage: final RMSNorm + LM head (8192 x 32000 bf16, one rank) + greedy arg-max
+    for one decode row; HBM-bound on the head's weights."""
+    from workloads import StageConfig
+    cfg = StageConfig("head70b", "bf16", 8192, 64, 8, 28672, 1, 1, (0,), batch=1, seed=41, vocab=32000)
+    hw = generate.head_weights(cfg, device="cuda")
+    hd = hx.Head(cfg.hidden, cfg.vocab, 1, 0, "bf16", cfg.rms_eps)
+    hd.load(hw["g_final"], hw["w_lm"])
+    del hw
+    x = generate.hidden_rows(cfg, 1, device="cuda").to(torch.bfloat16).contiguous()
+    for _ in range(5):
+        hd.greedy(x)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        tok, _ = hd.greedy(x)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) / reps * 1e3
+    nbytes = cfg.hidden * cfg.vocab * 2
+    return {"workload": "final RMSNorm + LM head 8192 x 32000 bf16 + arg-max, 1 row, vocabulary on one rank",
+            "us_per_token": round(us, 2), "GBps": round(nbytes / us / 1e3, 1), "hbm_frac": round(nbytes / us / 1e3 / 8000.0, 4),
+            "token": int(tok.item())}
 
 
 def calibrate(torch, hx):

@@ -172,6 +172,36 @@ hexgen_status_t hexgen_stream_read(const void *src, void *sink, int64_t bytes, i
  */
 hexgen_status_t hexgen_mfma_probe(int variant, void *sink, int iters, int blocks, void *stream);
 
+/* ---- the model's ends, adjacent to the first and the last stage -------------------------------------------
+ * Paper Section 2: a request enters as prompt tokens and leaves as generated tokens, one per decode step.  These
+ * calls turn a chain of stages into a token-in / token-out pipeline: the first stage's input rows come from the
+ * embedding table, the last stage's output goes through the final RMSNorm and the LM head, and the next token is
+ * the arg-max of the logits (greedy decoding).
+ *
+ * hexgen_embed_rows: rows_out[i] = table[tokens[i]].  table: device [vocab, hidden] row-major in `dtype`; tokens:
+ * device int32 [n] (ids outside [0, vocab) are clamped); rows_out: device [n, hidden] in `dtype`, caller-owned.
+ *
+ * hexgen_head: vocabulary-parallel over tp_degree ranks (vocab divisible by it, else HEXGEN_ERR_SHAPE); rank tp_rank
+ * holds columns [r V/t, (r+1) V/t) of the untied LM head.  hidden: multiple of 128 (bf16) or 4 (f32).
+ * hexgen_head_load: g_final [hidden] and the FULL matrix w_lm [hidden, vocab], row-major, host or device, in the head's
+ * dtype; the library copies and repacks its shard, the caller keeps its buffers.
+ * hexgen_head_greedy: x = hidden_a (+ hidden_b when not NULL: e.g. a stage's out_resid and out_partial), device
+ * [n_rows, hidden] in the head's dtype; per row: RMSNorm with g_final, this rank's logits, and the rank's best
+ * candidate: token_out[i] = GLOBAL id (lowest id wins ties), logit_out[i] = its logit in fp32 (may be NULL).  Both are
+ * device arrays of n_rows entries, caller-owned.  With tp_degree > 1 the caller picks, per row, the candidate with the
+ * largest logit over the ranks (first maximum in rank order).  Enqueues on `stream`, does not synchronise.
+ * HEXGEN_ERR_STATE before hexgen_head_load.
+ */
+typedef struct hexgen_head hexgen_head_t;
+hexgen_status_t hexgen_embed_rows(const void *table, hexgen_dtype_t dtype, int hidden, int vocab, const int32_t *tokens,
+                                  int n, void *rows_out, void *stream);
+hexgen_status_t hexgen_head_create(int hidden, int vocab, int tp_degree, int tp_rank, hexgen_dtype_t dtype, float rms_eps,
+                                   hexgen_head_t **out);
+hexgen_status_t hexgen_head_load(hexgen_head_t *hd, const void *g_final, const void *w_lm);
+hexgen_status_t hexgen_head_greedy(hexgen_head_t *hd, const void *hidden_a, const void *hidden_b, int n_rows,
+                                   int32_t *token_out, float *logit_out, void *stream);
+void            hexgen_head_destroy(hexgen_head_t *hd);
+
 /* Measurement and test hook, process-wide: force one tile configuration of the prefill projection GEMM instead of
  * the choice by shape.  code = 10 * a + b names the block tile: 88 = 256 x 256 on 4 waves, 98 = 256 x 256 on 8 waves,
  * 84 = 256 x 128, 48 = 128 x 256, 94 / 49 = 128 x 256 on 8 waves (2 x 4 / 4 x 2 wave grid), 44 = 128 x 128;

@@ -46,6 +46,11 @@ SIGNATURES = {
     "hexgen_stream_read": (_i, [_vp, _vp, _i64, _i, _vp]),
     "hexgen_mfma_probe": (_i, [_i, _vp, _i, _i, _vp]),
     "hexgen_set_gemm_tile": (_i, [_i]),
+    "hexgen_embed_rows": (_i, [_vp, _i, _i, _i, _vp, _i, _vp, _vp]),
+    "hexgen_head_create": (_i, [_i, _i, _i, _i, _i, C.c_float, C.POINTER(_vp)]),
+    "hexgen_head_load": (_i, [_vp, _vp, _vp]),
+    "hexgen_head_greedy": (_i, [_vp, _vp, _vp, _i, _vp, _vp, _vp]),
+    "hexgen_head_destroy": (None, [_vp]),
     "hexgen_stage_profile_enable": (_i, [_vp, _i]),
     "hexgen_stage_profile_read": (_i, [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64)]),
 }
@@ -97,6 +102,14 @@ def _stream_handle(stream: Optional[torch.cuda.Stream]) -> Optional[int]:
 
 def _torch_dtype(dtype: int):
     return torch.float32 if dtype == HEXGEN_F32 else torch.bfloat16
+
+
+def _dtype_code(dtype) -> int:
+    if isinstance(dtype, str):
+        return {"f32": HEXGEN_F32, "bf16": HEXGEN_BF16}[dtype]
+    if isinstance(dtype, torch.dtype):
+        return {torch.float32: HEXGEN_F32, torch.bfloat16: HEXGEN_BF16}[dtype]
+    return int(dtype)
 
 
 class Stage:
@@ -221,6 +234,48 @@ def stream_copy(dst: torch.Tensor, src: torch.Tensor, blocks: int = 4096, stream
 def stream_read(src: torch.Tensor, sink: torch.Tensor, blocks: int = 4096, stream=None):
     nbytes = src.numel() * src.element_size()
     _check(lib.hexgen_stream_read(_ptr(src), _ptr(sink), nbytes, blocks, _stream_handle(stream)), "hexgen_stream_read")
+
+
+class Head:
+    """Final RMSNorm + vocabulary-parallel LM head + greedy arg-max of one rank (hexgen_head_*)."""
+
+    def __init__(self, hidden: int, vocab: int, tp_degree: int, tp_rank: int, dtype, rms_eps: float = 1e-5):
+        self.dtype = _dtype_code(dtype)
+        h = C.c_void_p()
+        _check(lib.hexgen_head_create(hidden, vocab, tp_degree, tp_rank, self.dtype, rms_eps, C.byref(h)),
+               "hexgen_head_create")
+        self.handle, self.hidden, self.vocab = h, hidden, vocab
+
+    def close(self, _lib=lib):
+        if getattr(self, "handle", None):
+            _lib.hexgen_head_destroy(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+    def load(self, g_final: torch.Tensor, w_lm: torch.Tensor):
+        td = _torch_dtype(self.dtype)
+        g, w = g_final.to(td).contiguous(), w_lm.to(td).contiguous()
+        assert tuple(w.shape) == (self.hidden, self.vocab) and g.numel() == self.hidden
+        _check(lib.hexgen_head_load(self.handle, _ptr(g), _ptr(w)), "hexgen_head_load")
+
+    def greedy(self, hidden_a: torch.Tensor, hidden_b: Optional[torch.Tensor] = None, stream=None):
+        """Returns (token ids int32 [n], logits float32 [n]) of this rank's candidates, on the device."""
+        n = hidden_a.shape[0]
+        tok = torch.empty(n, dtype=torch.int32, device=hidden_a.device)
+        val = torch.empty(n, dtype=torch.float32, device=hidden_a.device)
+        _check(lib.hexgen_head_greedy(self.handle, _ptr(hidden_a), _ptr(hidden_b) if hidden_b is not None else None, n,
+                                      _ptr(tok), _ptr(val), _stream_handle(stream)), "hexgen_head_greedy")
+        return tok, val
+
+
+def embed_rows(table: torch.Tensor, tokens: torch.Tensor, stream=None) -> torch.Tensor:
+    """rows[i] = table[tokens[i]] on the device (hexgen_embed_rows); tokens int32."""
+    assert table.is_contiguous() and tokens.dtype == torch.int32
+    out = torch.empty((tokens.numel(), table.shape[1]), dtype=table.dtype, device=table.device)
+    _check(lib.hexgen_embed_rows(_ptr(table), _dtype_code(table.dtype), table.shape[1], table.shape[0], _ptr(tokens),
+                                 tokens.numel(), _ptr(out), _stream_handle(stream)), "hexgen_embed_rows")
+    return out
 
 
 def set_gemm_tile(code: int):

@@ -79,10 +79,10 @@ struct DecodeEpi {
 // `scratch` (device, scratch_floats floats, may be NULL) holds the split partial sums of the batched path (T > 2)
 void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T, const DecodeEpi &e, float *scratch,
                         size_t scratch_floats, hipStream_t s);
-// stage input rows -> h (optional), (x * g) hi/lo planes, sums of squares; block 0 publishes row
-// positions from the committed lengths and optionally advances them
-void launch_decode_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg, float *ssq_out,
-                            int T, int H, int32_t *lens, int32_t *row_pos, int advance, hipStream_t s);
+// stage input rows (+ optional second addend in2) -> h (optional), (x * g) hi/lo planes, sums of squares; block 0
+// publishes row positions from the committed lengths and optionally advances them
+void launch_decode_prologue(const void *in, const void *in2, int in_is_bf16, float *h_out, const float *g, bf16_t *hg,
+                            float *ssq_out, int T, int H, int32_t *lens, int32_t *row_pos, int advance, hipStream_t s);
 // ---- prefill projections with fused epilogues (kernels_bf16_gemm.hip) ----------------------------
 // Same epilogue roles as in decode (DEC_* modes), on packed operands: the input Xp is (h * gain) in
 // fragment tiles, RMSNorm enters as the per-token scale rstd derived from `ssq_in`.
@@ -133,6 +133,13 @@ void launch_kv_scatter(const float *k, const float *v, bf16_t *kc, bf16_t *vc, K
                        int pos0, int n, hipStream_t s);
 void launch_kv_gather(const bf16_t *kc, const bf16_t *vc, KvGeom kg, int seq, int pos0, int n, float *k,
                       float *v, hipStream_t s);
+
+// per row of logits [n][ld]: the largest of the first `valid` entries and its index + id0 (lowest index wins ties)
+void launch_row_argmax(const float *logits, int64_t ld, int valid, int n, int id0, int32_t *token_out, float *logit_out,
+                       hipStream_t s);
+// rows_out[i] = table[clamp(tokens[i], 0, vocab - 1)], rows of row_bytes bytes (a multiple of 4)
+void launch_embed_rows(const void *table, int64_t row_bytes, int vocab, const int32_t *tokens, int n, void *rows_out,
+                       hipStream_t s);
 
 void launch_store_out(const float *src, void *dst, int dst_is_bf16, int64_t n, hipStream_t s);
 

@@ -67,8 +67,11 @@ __device__ inline void decode_epilogue(const floatx4 (&v)[UT], int unit, int b, 
     const float r = (MODE != DEC_RESID && valid) ? s_rstd[token] : 1.0f;
 
     if (MODE == DEC_RAW) {
-        const int n0 = unit * 16 + 4 * g;
-        if (valid) *reinterpret_cast<floatx4 *>(e.raw_out + (size_t)token * N + n0) = v[0] * r;
+#pragma unroll
+        for (int u = 0; u < UT; ++u) {
+            const int n0 = (unit * UT + u) * 16 + 4 * g;
+            if (valid) *reinterpret_cast<floatx4 *>(e.raw_out + (size_t)token * N + n0) = v[u] * r;
+        }
     } else if (MODE == DEC_RESID) {
         const int n0 = unit * 16 + 4 * g;
         float ss = 0.f;
@@ -469,7 +472,11 @@ void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T,
         return;
     }
     switch (e.mode) {
-        case DEC_RAW: launch_mode<1, DEC_RAW>(Wp, Xa, N, k_tiles, T, e, s); break;
+        case DEC_RAW:
+            // two feature tiles per block (2 KB of weights per wave and k-tile) stream a few percent faster than one
+            if ((N / 16) % 2 == 0 && N / 32 >= 512) launch_mode<2, DEC_RAW>(Wp, Xa, N, k_tiles, T, e, s);
+            else launch_mode<1, DEC_RAW>(Wp, Xa, N, k_tiles, T, e, s);
+            break;
         case DEC_QKV: launch_mode<1, DEC_QKV>(Wp, Xa, N, k_tiles, T, e, s); break;
         case DEC_RESID: launch_mode<1, DEC_RESID>(Wp, Xa, N, k_tiles, T, e, s); break;
         case DEC_SWIGLU: launch_mode<2, DEC_SWIGLU>(Wp, Xa, N, k_tiles, T, e, s); break;
@@ -484,7 +491,8 @@ void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T,
 // grid = H / 128 blocks of 512 threads; thread = (token, 4-column group).
 // -------------------------------------------------------------------------------------------------
 template <bool IN_BF16>
-__global__ __launch_bounds__(512) void decode_prologue_kernel(const void *__restrict__ in, float *__restrict__ h_out,
+__global__ __launch_bounds__(512) void decode_prologue_kernel(const void *__restrict__ in, const void *__restrict__ in2,
+                                                             float *__restrict__ h_out,
                                                              const float *__restrict__ g, bf16_t *__restrict__ hg,
                                                              float *__restrict__ ssq_out,
                                                              int T, int H, int32_t *lens, int32_t *row_pos,
@@ -505,9 +513,18 @@ __global__ __launch_bounds__(512) void decode_prologue_kernel(const void *__rest
                 uint2 raw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(in) + (size_t)t * H + col);
                 x[0] = bf16_to_f32((bf16_t)(raw.x & 0xffff)); x[1] = bf16_to_f32((bf16_t)(raw.x >> 16));
                 x[2] = bf16_to_f32((bf16_t)(raw.y & 0xffff)); x[3] = bf16_to_f32((bf16_t)(raw.y >> 16));
+                if (in2) {      // second addend (e.g. a stage's partial on top of its residual stream)
+                    raw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(in2) + (size_t)t * H + col);
+                    x[0] += bf16_to_f32((bf16_t)(raw.x & 0xffff)); x[1] += bf16_to_f32((bf16_t)(raw.x >> 16));
+                    x[2] += bf16_to_f32((bf16_t)(raw.y & 0xffff)); x[3] += bf16_to_f32((bf16_t)(raw.y >> 16));
+                }
             } else {
                 const floatx4 a = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const float *>(in) + (size_t)t * H + col);
                 x[0] = a[0]; x[1] = a[1]; x[2] = a[2]; x[3] = a[3];
+                if (in2) {
+                    const floatx4 c = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const float *>(in2) + (size_t)t * H + col);
+                    x[0] += c[0]; x[1] += c[1]; x[2] += c[2]; x[3] += c[3];
+                }
             }
             if (h_out) *reinterpret_cast<floatx4 *>(h_out + (size_t)t * H + col) = floatx4{x[0], x[1], x[2], x[3]};
             const floatx4 g4 = *reinterpret_cast<const floatx4 *>(g + col);
@@ -522,13 +539,13 @@ __global__ __launch_bounds__(512) void decode_prologue_kernel(const void *__rest
     }
 }
 
-void launch_decode_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg, float *ssq_out,
-                            int T, int H, int32_t *lens, int32_t *row_pos, int advance, hipStream_t s) {
+void launch_decode_prologue(const void *in, const void *in2, int in_is_bf16, float *h_out, const float *g, bf16_t *hg,
+                            float *ssq_out, int T, int H, int32_t *lens, int32_t *row_pos, int advance, hipStream_t s) {
     const int blocks = (H + 127) / 128;
     if (in_is_bf16)
-        hipLaunchKernelGGL(decode_prologue_kernel<true>, dim3(blocks), dim3(512), 0, s, in, h_out, g, hg, ssq_out, T, H,
+        hipLaunchKernelGGL(decode_prologue_kernel<true>, dim3(blocks), dim3(512), 0, s, in, in2, h_out, g, hg, ssq_out, T, H,
                            lens, row_pos, advance);
     else
-        hipLaunchKernelGGL(decode_prologue_kernel<false>, dim3(blocks), dim3(512), 0, s, in, h_out, g, hg, ssq_out, T, H,
+        hipLaunchKernelGGL(decode_prologue_kernel<false>, dim3(blocks), dim3(512), 0, s, in, in2, h_out, g, hg, ssq_out, T, H,
                            lens, row_pos, advance);
 }

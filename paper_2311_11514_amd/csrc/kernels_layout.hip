@@ -167,6 +167,71 @@ void launch_stream_read(const void *src, float *sink, int64_t bytes, int blocks,
                        bytes / 16);
 }
 
+// ---- the model's ends: greedy argmax over a row of logits, embedding row gather --------------------------------
+// One block of 1024 threads per row.  Each thread scans a strided slice (four entries per load when the row pitch
+// allows it, several loads in flight) keeping (value, lowest index); the block reduces in LDS with the same rule, so
+// the result is the first maximum of the row, as numpy / torch argmax define it.
+template <bool VEC4>
+__global__ __launch_bounds__(1024) void row_argmax_kernel(const float *__restrict__ logits, int64_t ld, int valid, int id0,
+                                                         int32_t *__restrict__ token_out, float *__restrict__ logit_out) {
+    __shared__ float sv[1024];
+    __shared__ int si[1024];
+    const float *row = logits + (int64_t)blockIdx.x * ld;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    auto take = [&](float v, int i) {
+        if (i < valid && (v > bv || (v == bv && i < bi))) { bv = v; bi = i; }
+    };
+    if (VEC4) {
+        const int n4 = (valid + 3) >> 2;          // the pitch is a multiple of 4: the last quad stays inside the row
+#pragma unroll 4
+        for (int q = threadIdx.x; q < n4; q += 1024) {
+            const floatx4 v = *reinterpret_cast<const floatx4 *>(row + 4 * q);
+            take(v[0], 4 * q); take(v[1], 4 * q + 1); take(v[2], 4 * q + 2); take(v[3], 4 * q + 3);
+        }
+    } else {
+#pragma unroll 4
+        for (int i = threadIdx.x; i < valid; i += 1024) take(row[i], i);
+    }
+    sv[threadIdx.x] = bv;
+    si[threadIdx.x] = bi;
+    __syncthreads();
+    for (int o = 512; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) {
+            const float v = sv[threadIdx.x + o];
+            const int i = si[threadIdx.x + o];
+            if (v > sv[threadIdx.x] || (v == sv[threadIdx.x] && i < si[threadIdx.x])) { sv[threadIdx.x] = v; si[threadIdx.x] = i; }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        token_out[blockIdx.x] = id0 + (si[0] == 0x7fffffff ? 0 : si[0]);
+        if (logit_out) logit_out[blockIdx.x] = sv[0];
+    }
+}
+void launch_row_argmax(const float *logits, int64_t ld, int valid, int n, int id0, int32_t *token_out, float *logit_out,
+                       hipStream_t s) {
+    if (n <= 0) return;
+    if (ld % 4 == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0)
+        hipLaunchKernelGGL(row_argmax_kernel<true>, dim3(n), dim3(1024), 0, s, logits, ld, valid, id0, token_out, logit_out);
+    else
+        hipLaunchKernelGGL(row_argmax_kernel<false>, dim3(n), dim3(1024), 0, s, logits, ld, valid, id0, token_out, logit_out);
+}
+
+__global__ void embed_rows_kernel(const uint32_t *__restrict__ table, int64_t row_words, int vocab,
+                                  const int32_t *__restrict__ tokens, uint32_t *__restrict__ out) {
+    const int tok = min(max(tokens[blockIdx.x], 0), vocab - 1);
+    const uint32_t *src = table + (int64_t)tok * row_words;
+    uint32_t *dst = out + (int64_t)blockIdx.x * row_words;
+    for (int64_t i = threadIdx.x; i < row_words; i += blockDim.x) dst[i] = src[i];
+}
+void launch_embed_rows(const void *table, int64_t row_bytes, int vocab, const int32_t *tokens, int n, void *rows_out,
+                       hipStream_t s) {
+    if (n <= 0) return;
+    hipLaunchKernelGGL(embed_rows_kernel, dim3(n), dim3(256), 0, s, static_cast<const uint32_t *>(table), row_bytes / 4, vocab,
+                       tokens, static_cast<uint32_t *>(rows_out));
+}
+
 // ---- measurement utility: register-resident MFMA loops (what the matrix cores sustain on this machine) ------
 // variant 0: v_mfma_f32_16x16x32_bf16, 64 independent accumulators per wave; variant 1: v_mfma_f32_32x32x16_bf16,
 // 16 accumulators; variants 2 / 3: the same with the LDS fragment reads of a 128 x 128 wave tile (16 reads per

@@ -388,7 +388,7 @@ hexgen_status_t forward_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const
                                     void *out_partial, void *out_resid, hipStream_t s) {
     Workspace &w = st->ws;
     float *ssq_a = w.ssq, *ssq_f = w.ssq + (size_t)(st->H / 16) * DEC_SSQ_STRIDE;
-    launch_decode_prologue(hidden_in, 1, w.h, st->layers[0].g_attn, w.xa_n, ssq_a, r.T, st->H, kv->d_lens,
+    launch_decode_prologue(hidden_in, nullptr, 1, w.h, st->layers[0].g_attn, w.xa_n, ssq_a, r.T, st->H, kv->d_lens,
                            w.row_pos, 1, s);
     for (int l = 0; l < st->L; ++l) {
         const Layer &ly = st->layers[l];
@@ -422,11 +422,11 @@ void sublayer_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, int 
     DecodeEpi e = epi_base(st, DEC_RAW);
     e.raw_out = p_out;
     if (which == 0) {
-        launch_decode_prologue(h, 0, nullptr, ly.g_attn, w.xa_n, ssq, r.T, st->H, kv->d_lens, w.row_pos, 0, s);
+        launch_decode_prologue(h, nullptr, 0, nullptr, ly.g_attn, w.xa_n, ssq, r.T, st->H, kv->d_lens, w.row_pos, 0, s);
         attn_decode_bf16(st, kv, layer, r, ssq, s);
         decode_proj(st, r, ly.wo, w.xa_o, st->H, st->qw, e, PROF_WO, s);
     } else {
-        launch_decode_prologue(h, 0, nullptr, ly.g_ffn, w.xa_n, ssq, r.T, st->H, nullptr, nullptr, 0, s);
+        launch_decode_prologue(h, nullptr, 0, nullptr, ly.g_ffn, w.xa_n, ssq, r.T, st->H, nullptr, nullptr, 0, s);
         DecodeEpi g = epi_base(st, DEC_SWIGLU);
         g.ssq_in = ssq; g.u = w.xa_u; g.F_l = st->F_l;
         decode_proj(st, r, ly.w13, w.xa_n, 2 * st->F_l, st->H, g, PROF_W13, s);
@@ -934,6 +934,152 @@ hexgen_status_t hexgen_stream_read(const void *src, void *sink, int64_t bytes, i
 hexgen_status_t hexgen_mfma_probe(int variant, void *sink, int iters, int blocks, void *stream) {
     if (!sink || variant < 0 || variant > 7 || iters <= 0 || blocks <= 0) return HEXGEN_ERR_INVALID_ARG;
     launch_mfma_probe(variant, static_cast<float *>(sink), iters, blocks, static_cast<hipStream_t>(stream));
+    return HEXGEN_OK;
+}
+
+// ---- the model's ends next to the stage: embedding gather, final norm + vocabulary-parallel LM head + argmax ----
+struct hexgen_head {
+    int H = 0, V = 0, t = 1, r = 0, Vl = 0, Vpad = 0;     // Vl = V / t columns of this rank, padded to 16 for the tiles
+    hexgen_dtype_t dtype = HEXGEN_BF16;
+    float eps = 1e-5f;
+    bool loaded = false;
+    void *w = nullptr;            // bf16: fragment tiles, k-tile-major [H/32][Vpad/16][64][8]; f32: [H][Vl]
+    float *g = nullptr;           // final norm gain, fp32 [H]
+    // workspace for one chunk of up to kDecodeMaxRows rows
+    bf16_t *xa = nullptr;         // bf16: (x * g) as compact hi/lo operand
+    float *ssq = nullptr;         // bf16: sums of squares per 16 columns
+    float *x32 = nullptr, *n32 = nullptr;      // f32: x = a + b, normalised rows
+    float *logits = nullptr;      // [rows][Vpad]
+    float *scratch = nullptr;     // split partial sums of the batched projection
+    size_t scratch_floats = 0;
+};
+
+namespace {
+void free_head(hexgen_head *hd) {
+    void *ptrs[] = {hd->w, hd->g, hd->xa, hd->ssq, hd->x32, hd->n32, hd->logits, hd->scratch};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+}
+}  // namespace
+
+hexgen_status_t hexgen_head_create(int hidden, int vocab, int tp_degree, int tp_rank, hexgen_dtype_t dtype, float rms_eps,
+                                   hexgen_head_t **out) {
+    if (!out) return HEXGEN_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (hidden <= 0 || vocab <= 0 || tp_degree <= 0 || !(rms_eps >= 0.f)) return HEXGEN_ERR_INVALID_ARG;
+    if (dtype != HEXGEN_F32 && dtype != HEXGEN_BF16) return HEXGEN_ERR_INVALID_ARG;
+    if (tp_rank < 0 || tp_rank >= tp_degree || vocab % tp_degree) return HEXGEN_ERR_SHAPE;
+    if (dtype == HEXGEN_BF16 && hidden % 128) return HEXGEN_ERR_SHAPE;
+    if (dtype == HEXGEN_F32 && hidden % 4) return HEXGEN_ERR_SHAPE;
+    hexgen_head *hd = new (std::nothrow) hexgen_head();
+    if (!hd) return HEXGEN_ERR_OOM;
+    hd->H = hidden; hd->V = vocab; hd->t = tp_degree; hd->r = tp_rank; hd->dtype = dtype; hd->eps = rms_eps;
+    hd->Vl = vocab / tp_degree;
+    hd->Vpad = round_up(hd->Vl, 16);
+    const size_t rows = kDecodeMaxRows;
+    hexgen_status_t rc = dmalloc(&hd->g, (size_t)hidden);
+    if (rc == HEXGEN_OK) rc = dmalloc(&hd->logits, rows * hd->Vpad);
+    if (rc == HEXGEN_OK && dtype == HEXGEN_BF16) {
+        rc = dmalloc(&hd->xa, 2 * rows * hidden);
+        if (rc == HEXGEN_OK) rc = dmalloc(&hd->ssq, (size_t)(hidden / 16) * DEC_SSQ_STRIDE);
+        hd->scratch_floats = rows * ((size_t)512 * 128 + 2 * (size_t)hd->Vpad);
+        if (rc == HEXGEN_OK) rc = dmalloc(&hd->scratch, hd->scratch_floats);
+    } else if (rc == HEXGEN_OK) {
+        rc = dmalloc(&hd->x32, rows * hidden);
+        if (rc == HEXGEN_OK) rc = dmalloc(&hd->n32, rows * hidden);
+    }
+    if (rc != HEXGEN_OK) { free_head(hd); delete hd; (void)hipGetLastError(); return rc == HEXGEN_ERR_DEVICE ? HEXGEN_ERR_OOM : rc; }
+    *out = hd;
+    return HEXGEN_OK;
+}
+
+void hexgen_head_destroy(hexgen_head_t *hd) {
+    if (!hd) return;
+    (void)hipDeviceSynchronize();
+    free_head(hd);
+    delete hd;
+}
+
+hexgen_status_t hexgen_head_load(hexgen_head_t *hd, const void *g_final, const void *w_lm) {
+    if (!hd || !g_final || !w_lm) return HEXGEN_ERR_INVALID_ARG;
+    HX_HIP(hipDeviceSynchronize());
+    const int H = hd->H, c0 = hd->r * hd->Vl;
+    const size_t es = esize(hd->dtype);
+    if (hd->w) { (void)hipFree(hd->w); hd->w = nullptr; }
+    hd->loaded = false;
+    if (hd->dtype == HEXGEN_F32) {
+        HX_HIP(hipMemcpy(hd->g, g_final, sizeof(float) * H, hipMemcpyDefault));
+        HX_HIP(hipMalloc(&hd->w, (size_t)H * hd->Vl * es));
+        HX_HIP(hipMemcpy2D(hd->w, (size_t)hd->Vl * es, static_cast<const char *>(w_lm) + (size_t)c0 * es, (size_t)hd->V * es,
+                           (size_t)hd->Vl * es, H, hipMemcpyDefault));
+    } else {
+        // gain -> fp32; the rank's columns -> a dense zero-padded device matrix -> MFMA fragment tiles
+        bf16_t *tmp = nullptr;
+        HX_TRY(dmalloc(&tmp, (size_t)H * hd->Vpad + H));
+        hipError_t e = hipMemset(tmp, 0, ((size_t)H * hd->Vpad + H) * es);
+        if (e == hipSuccess) e = hipMemcpy(tmp + (size_t)H * hd->Vpad, g_final, (size_t)H * es, hipMemcpyDefault);
+        if (e == hipSuccess)
+            e = hipMemcpy2D(tmp, (size_t)hd->Vpad * es, static_cast<const char *>(w_lm) + (size_t)c0 * es, (size_t)hd->V * es,
+                            (size_t)hd->Vl * es, H, hipMemcpyDefault);
+        if (e == hipSuccess) e = hipMalloc(&hd->w, (size_t)H * hd->Vpad * es);
+        if (e == hipSuccess) {
+            launch_cvt_bf16_to_f32(tmp + (size_t)H * hd->Vpad, hd->g, H, nullptr);
+            launch_pack_weight(tmp, hd->Vpad, 0, 0, H, hd->Vpad, static_cast<bf16_t *>(hd->w), 0, 1, hd->Vpad / 16, 0, nullptr);
+            e = hipDeviceSynchronize();
+        }
+        (void)hipFree(tmp);
+        if (e != hipSuccess) { (void)hipGetLastError(); return HEXGEN_ERR_DEVICE; }
+    }
+    hd->loaded = true;
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_head_greedy(hexgen_head_t *hd, const void *hidden_a, const void *hidden_b, int n_rows,
+                                   int32_t *token_out, float *logit_out, void *stream) {
+    if (!hd || !hidden_a || !token_out || n_rows <= 0) return HEXGEN_ERR_INVALID_ARG;
+    if (!hd->loaded) return HEXGEN_ERR_STATE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t es = esize(hd->dtype);
+    const int H = hd->H;
+    for (int r0 = 0; r0 < n_rows; r0 += kDecodeMaxRows) {
+        const int n = std::min(kDecodeMaxRows, n_rows - r0);
+        const char *a = static_cast<const char *>(hidden_a) + (size_t)r0 * H * es;
+        const char *b = hidden_b ? static_cast<const char *>(hidden_b) + (size_t)r0 * H * es : nullptr;
+        int64_t ld = hd->Vpad;
+        if (hd->dtype == HEXGEN_BF16) {
+            // same kernels as a decode projection: prologue (x = a + b, x * g as hi/lo operand, sums of squares),
+            // weight-streaming projection with 1 / rms applied after the contraction, fp32 logits
+            launch_decode_prologue(a, b, 1, nullptr, hd->g, hd->xa, hd->ssq, n, H, nullptr, nullptr, 0, s);
+            DecodeEpi e;
+            std::memset(&e, 0, sizeof(e));
+            e.mode = DEC_RAW;
+            e.ssq_in = hd->ssq;
+            e.ssq_units = H / 16;
+            e.norm_dim = H;
+            e.eps = hd->eps;
+            e.raw_out = hd->logits;
+            launch_decode_proj(static_cast<const bf16_t *>(hd->w), hd->xa, hd->Vpad, H, n, e, hd->scratch, hd->scratch_floats, s);
+        } else {
+            HX_HIP(hipMemcpyAsync(hd->x32, a, (size_t)n * H * es, hipMemcpyDeviceToDevice, s));
+            if (b) launch_accumulate_f32(hd->x32, reinterpret_cast<const float *>(b), (int64_t)n * H, s);
+            f32_launch_rmsnorm(hd->x32, hd->g, hd->n32, n, H, hd->eps, s);
+            f32_launch_gemm(hd->n32, static_cast<const float *>(hd->w), hd->logits, n, H, hd->Vl, s);
+            ld = hd->Vl;
+        }
+        launch_row_argmax(hd->logits, ld, hd->Vl, n, hd->r * hd->Vl, token_out + r0, logit_out ? logit_out + r0 : nullptr, s);
+    }
+    HX_HIP(hipGetLastError());
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_embed_rows(const void *table, hexgen_dtype_t dtype, int hidden, int vocab, const int32_t *tokens,
+                                  int n, void *rows_out, void *stream) {
+    if (!table || !tokens || !rows_out || hidden <= 0 || vocab <= 0 || n < 0) return HEXGEN_ERR_INVALID_ARG;
+    if (dtype != HEXGEN_F32 && dtype != HEXGEN_BF16) return HEXGEN_ERR_INVALID_ARG;
+    const int64_t row_bytes = (int64_t)hidden * (int64_t)esize(dtype);
+    if (row_bytes % 4) return HEXGEN_ERR_SHAPE;
+    launch_embed_rows(table, row_bytes, vocab, tokens, n, rows_out, static_cast<hipStream_t>(stream));
+    HX_HIP(hipGetLastError());
     return HEXGEN_OK;
 }
 

@@ -395,3 +395,62 @@ def test_head_tie_rule_lowest_id_wins_across_ranks():
     assert so.merge_greedy(cands)[0] == 3
     # scale invariance of the decision: RMSNorm makes the token independent of the row's magnitude
     assert so.merge_greedy([so.head_shard_greedy(7.5 * x, g, w, eps, 2, r) for r in range(2)])[0] == 3
+
+
+# ---- the paper's cost model (Table 1, Eqs. 3-6) -------------------------------------------------------------------
+def _golden_cost():
+    import os
+    vals = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "cost_model_worked_example.txt")):
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split()
+            vals[k] = float(v)
+    return vals
+
+
+def test_cost_model_worked_example():
+    """Hand computation from the printed formulas (tests/golden/cost_model_worked_example.txt)."""
+    from oracle import cost_oracle as co
+    gold = _golden_cost()
+    args = dict(H=8192, B_type=2, b=1, s_in=512, s_out=64, l=80, m=[2.0e12] * 8, c=[3.12e14] * 8)
+    assert math.isclose(co.comp(**args), gold["comp_total"], rel_tol=1e-12)
+    assert math.isclose(co.comp_prefill(**args), gold["prefill"], rel_tol=1e-12)
+    assert math.isclose(co.comp_decode(**args), gold["decode"], rel_tol=1e-12)
+    assert math.isclose(gold["scan_term"] + gold["flop_term"], gold["comp_total"], rel_tol=1e-12)
+    assert math.isclose(co.mem(8192, 2, 1, 512, 64, 80, 8), gold["mem_bytes"], rel_tol=1e-15)
+
+
+def test_cost_model_identities():
+    from oracle import cost_oracle as co
+    rng = np.random.default_rng(11)
+    for _ in range(20):
+        n = int(rng.integers(1, 9))
+        H, B, b = int(rng.choice([1024, 4096, 8192])), int(rng.choice([2, 4])), int(rng.integers(1, 33))
+        s_in, s_out, l = int(rng.integers(1, 2049)), int(rng.integers(1, 257)), int(rng.integers(1, 81))
+        m = list(rng.uniform(0.3e12, 8e12, n))
+        c = list(rng.uniform(50e12, 2500e12, n))
+        # the two phases add up to Eq. 3 as printed
+        assert math.isclose(co.comp_prefill(H, B, b, s_in, s_out, l, m, c) + co.comp_decode(H, B, b, s_in, s_out, l, m, c),
+                            co.comp(H, B, b, s_in, s_out, l, m, c), rel_tol=1e-12)
+        # the slowest device decides; equal devices reduce to the closed form
+        slow_m, slow_c = min(m), min(c)
+        assert math.isclose(co.comp(H, B, b, s_in, s_out, l, m, c),
+                            (12 * H * H * B * s_out / (n * slow_m) + 24 * b * (s_in + s_out) * H * H / (n * slow_c)) * l,
+                            rel_tol=1e-12)
+        # linear in the layer count; a stage of one device has no tensor-parallel traffic (stated under Eq. 4)
+        assert math.isclose(co.comp(H, B, b, s_in, s_out, 2 * l, m, c), 2 * co.comp(H, B, b, s_in, s_out, l, m, c), rel_tol=1e-12)
+        assert co.comm_tp(H, B, b, s_in, s_out, l, [[0.0]], [[1.0]]) == 0.0
+        # uniform links: every device sends n - 1 chunks per superstep
+        a0, b0 = 5e-6, 100e9
+        al = [[a0] * n for _ in range(n)]
+        be = [[b0] * n for _ in range(n)]
+        want = ((n - 1) * (a0 + b * s_in * H * B / (n * b0)) * 4 * l + (n - 1) * (a0 + b * H * B / (n * b0)) * 4 * s_out * l)
+        assert math.isclose(co.comm_tp(H, B, b, s_in, s_out, l, al, be), want, rel_tol=1e-12, abs_tol=0.0)
+        # pipeline hop: the fastest of the candidate links carries it
+        al2 = [[a0, 2 * a0], [3 * a0, a0]]
+        be2 = [[b0, b0 / 2], [b0 / 4, 2 * b0]]
+        want_pp = (a0 + b * s_in * H * B / (2 * b0)) + (a0 + b * H * B / (2 * b0)) * s_out
+        assert math.isclose(co.comm_pp(H, B, b, s_in, s_out, al2, be2), want_pp, rel_tol=1e-12)
+        # memory: Llama-style parameter count scales the first term only
+        assert math.isclose(co.mem(H, B, b, s_in, s_out, l, n, 12.75) - co.mem(H, B, b, s_in, s_out, l, n, 12.0),
+                            0.75 * H * H * B / n * l, rel_tol=1e-9)

@@ -173,6 +173,8 @@ def main():
     if not args.no_head:
         torch.cuda.empty_cache()
         result["lm_head"] = head_leg(torch, hx, generate)
+    if "prefill" in result:
+        result["cost_model"] = cost_model_alignment(torch, hx, cfg, result)
     print(json.dumps(result), flush=True)
 
 
@@ -250,6 +252,33 @@ def head_leg(torch, hx, generate, reps=50):
     return {"workload": "final RMSNorm + LM head 8192 x 32000 bf16 + arg-max, 1 row, vocabulary on one rank",
             "us_per_token": round(us, 2), "GBps": round(nbytes / us / 1e3, 1), "hbm_frac": round(nbytes / us / 1e3 / 8000.0, 4),
             "token": int(tok.item())}
+
+
+def cost_model_alignment(torch, hx, cfg, result):
+    """The paper's computation-cost formula (Eq. 3, with Llama-2-70B's 12.75 H^2 parameters per layer) fed with this
+    machine's MEASURED rates -- m_d: a cold 470 MB streaming read, c_d: the rate of the largest prefill GEMM -- against
+    the measured times of the two workloads above (the paper's own alignment table compares the same two columns)."""
+    from workloads import CONFIGS
+    big = torch.empty(1880 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+    sink = torch.zeros(1 << 16, dtype=torch.float32, device="cuda")
+    n = 470 << 20
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    hx.stream_read(big[:n], sink, 512)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(4):
+        hx.stream_read(big[i * n:(i + 1) * n], sink, 512)
+    e1.record()
+    torch.cuda.synchronize()
+    m_d = 4 * n / (e0.elapsed_time(e1) * 1e-3)
+    c_d = result["prefill"]["gemm"]["w13"]["TFLOPs"] * 1e12
+    pc = CONFIGS["l70_tp4_prefill"]
+    dec = hx.cost_comp(cfg.hidden, 2, cfg.batch, 0, 1, cfg.n_layers, [m_d] * cfg.tp_degree, [c_d] * cfg.tp_degree, 12.75, "decode")
+    pre = hx.cost_comp(pc.hidden, 2, pc.batch, pc.prompt_len, 0, pc.n_layers, [m_d] * pc.tp_degree, [c_d] * pc.tp_degree,
+                       12.75, "prefill")
+    return {"m_d_GBps": round(m_d / 1e9, 1), "c_d_TFLOPs": round(c_d / 1e12, 1),
+            "decode_ms_per_token": {"estimated": round(dec * 1e3, 4), "measured": result["ms_per_step"]},
+            "prefill_ms_per_call": {"estimated": round(pre * 1e3, 3), "measured": result["prefill"]["ms_per_call"]}}
 
 
 def calibrate(torch, hx):

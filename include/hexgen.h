@@ -202,6 +202,36 @@ hexgen_status_t hexgen_head_greedy(hexgen_head_t *hd, const void *hidden_a, cons
                                    int32_t *token_out, float *logit_out, void *stream);
 void            hexgen_head_destroy(hexgen_head_t *hd);
 
+/* ---- the paper's cost model (Table 1; Appendix "Modeling the Generative Inference Cost", Eqs. 3-6) -----------
+ * Host functions, plain arithmetic in double precision, no device work, thread-safe.  Task t = (batch b, prompt
+ * length s_in, generated tokens s_out); bytes_per_elem = B_type; a stage = `layers` layers on n_dev devices with
+ * memory bandwidths m_d[n_dev] (bytes/s) and peak rates c_d[n_dev] (flop/s), HOST arrays.  params_factor = parameters
+ * of one layer in units of hidden^2: 12 for the paper's layer (its Eq. 3), 12.75 for Llama-2-70B's GQA + SwiGLU layer.
+ * Every function returns seconds (hexgen_cost_mem: bytes), or NaN for an invalid argument (non-positive size or rate,
+ * NULL array).
+ *   hexgen_cost_comp         Eq. 3: max_d(P B s_out / (|d| m_d)) l + max_d(2 P b (s_in + s_out) / (|d| c_d)) l, P = params
+ *   hexgen_cost_comp_prefill   its prefill share, 2 P b s_in / (|d| c_d) per layer
+ *   hexgen_cost_comp_decode    its decode share, (P B / (|d| m_d) + 2 P b / (|d| c_d)) per layer and generated token
+ *   hexgen_cost_comm_tp      Eq. 4: alpha, beta = n_dev x n_dev row-major link latencies (s) and bandwidths (bytes/s);
+ *                            four supersteps per layer, the slowest device's sum per superstep; 0 for one device
+ *   hexgen_cost_comm_pp      Eq. 5: alpha, beta = n_from x n_to links between the two stages; the fastest link carries
+ *                            the prompt's activation once and one row per generated token
+ *   hexgen_cost_mem          Eq. 6: parameters and K / V of the stage's layers split over the devices, plus four
+ *                            activation buffers of b (s_in + s_out) hidden elements
+ */
+double hexgen_cost_comp(int hidden, double params_factor, int bytes_per_elem, int batch, int s_in, int s_out, int layers,
+                        int n_dev, const double *m_d, const double *c_d);
+double hexgen_cost_comp_prefill(int hidden, double params_factor, int bytes_per_elem, int batch, int s_in, int s_out,
+                                int layers, int n_dev, const double *m_d, const double *c_d);
+double hexgen_cost_comp_decode(int hidden, double params_factor, int bytes_per_elem, int batch, int s_in, int s_out,
+                               int layers, int n_dev, const double *m_d, const double *c_d);
+double hexgen_cost_comm_tp(int hidden, int bytes_per_elem, int batch, int s_in, int s_out, int layers, int n_dev,
+                           const double *alpha, const double *beta);
+double hexgen_cost_comm_pp(int hidden, int bytes_per_elem, int batch, int s_in, int s_out, int n_from, int n_to,
+                           const double *alpha, const double *beta);
+double hexgen_cost_mem(int hidden, double params_factor, int bytes_per_elem, int batch, int s_in, int s_out, int layers,
+                       int n_dev);
+
 /* Measurement and test hook, process-wide: force one tile configuration of the prefill projection GEMM instead of
  * the choice by shape.  code = 10 * a + b names the block tile: 88 = 256 x 256 on 4 waves, 98 = 256 x 256 on 8 waves,
  * 84 = 256 x 128, 48 = 128 x 256, 94 / 49 = 128 x 256 on 8 waves (2 x 4 / 4 x 2 wave grid), 44 = 128 x 128;

@@ -51,6 +51,12 @@ SIGNATURES = {
     "hexgen_head_load": (_i, [_vp, _vp, _vp]),
     "hexgen_head_greedy": (_i, [_vp, _vp, _vp, _i, _vp, _vp, _vp]),
     "hexgen_head_destroy": (None, [_vp]),
+    "hexgen_cost_comp": (C.c_double, [_i, C.c_double, _i, _i, _i, _i, _i, _i, _vp, _vp]),
+    "hexgen_cost_comp_prefill": (C.c_double, [_i, C.c_double, _i, _i, _i, _i, _i, _i, _vp, _vp]),
+    "hexgen_cost_comp_decode": (C.c_double, [_i, C.c_double, _i, _i, _i, _i, _i, _i, _vp, _vp]),
+    "hexgen_cost_comm_tp": (C.c_double, [_i, _i, _i, _i, _i, _i, _i, _vp, _vp]),
+    "hexgen_cost_comm_pp": (C.c_double, [_i, _i, _i, _i, _i, _i, _i, _vp, _vp]),
+    "hexgen_cost_mem": (C.c_double, [_i, C.c_double, _i, _i, _i, _i, _i, _i]),
     "hexgen_stage_profile_enable": (_i, [_vp, _i]),
     "hexgen_stage_profile_read": (_i, [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64)]),
 }
@@ -276,6 +282,29 @@ def embed_rows(table: torch.Tensor, tokens: torch.Tensor, stream=None) -> torch.
     _check(lib.hexgen_embed_rows(_ptr(table), _dtype_code(table.dtype), table.shape[1], table.shape[0], _ptr(tokens),
                                  tokens.numel(), _ptr(out), _stream_handle(stream)), "hexgen_embed_rows")
     return out
+
+
+def _darr(values):
+    flat = [float(v) for row in values for v in (row if isinstance(row, (list, tuple)) else [row])]
+    return (C.c_double * len(flat))(*flat)
+
+
+def cost_comp(hidden, bytes_per_elem, batch, s_in, s_out, layers, m_d, c_d, params_factor=12.0, phase="both") -> float:
+    """Eq. 3 of the paper's cost model (hexgen_cost_comp*); phase = "both" | "prefill" | "decode"."""
+    fn = {"both": lib.hexgen_cost_comp, "prefill": lib.hexgen_cost_comp_prefill, "decode": lib.hexgen_cost_comp_decode}[phase]
+    return fn(hidden, params_factor, bytes_per_elem, batch, s_in, s_out, layers, len(m_d), _darr(m_d), _darr(c_d))
+
+
+def cost_comm_tp(hidden, bytes_per_elem, batch, s_in, s_out, layers, alpha, beta) -> float:
+    return lib.hexgen_cost_comm_tp(hidden, bytes_per_elem, batch, s_in, s_out, layers, len(alpha), _darr(alpha), _darr(beta))
+
+
+def cost_comm_pp(hidden, bytes_per_elem, batch, s_in, s_out, alpha, beta) -> float:
+    return lib.hexgen_cost_comm_pp(hidden, bytes_per_elem, batch, s_in, s_out, len(alpha), len(alpha[0]), _darr(alpha), _darr(beta))
+
+
+def cost_mem(hidden, bytes_per_elem, batch, s_in, s_out, layers, n_dev, params_factor=12.0) -> float:
+    return lib.hexgen_cost_mem(hidden, params_factor, bytes_per_elem, batch, s_in, s_out, layers, n_dev)
 
 
 def set_gemm_tile(code: int):

@@ -64,3 +64,38 @@ def test_null_and_range_arguments():
     assert hx.lib.hexgen_status_string(4) == b"capacity exceeded"
     assert hx.lib.hexgen_accumulate_f32(None, None, 4, None) == 1
     st.close()
+
+
+# ---- cost model (host functions of the library) against the oracle ------------------------------------------------
+def test_cost_model_functions_match_the_oracle():
+    import math
+
+    import numpy as np
+
+    from oracle import cost_oracle as co
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        n = int(rng.integers(1, 9))
+        H, B, b = int(rng.choice([512, 4096, 8192])), int(rng.choice([2, 4])), int(rng.integers(1, 33))
+        s_in, s_out, l = int(rng.integers(0, 2049)), int(rng.integers(0, 257)), int(rng.integers(0, 81))
+        pf = float(rng.choice([12.0, 12.75]))
+        m, c = list(rng.uniform(0.3e12, 8e12, n)), list(rng.uniform(50e12, 2500e12, n))
+        for phase, ref in (("both", co.comp), ("prefill", co.comp_prefill), ("decode", co.comp_decode)):
+            assert math.isclose(hx.cost_comp(H, B, b, s_in, s_out, l, m, c, pf, phase), ref(H, B, b, s_in, s_out, l, m, c, pf),
+                                rel_tol=1e-12, abs_tol=0.0)
+        al = rng.uniform(1e-6, 50e-6, (n, n)).tolist()
+        be = rng.uniform(10e9, 400e9, (n, n)).tolist()
+        assert math.isclose(hx.cost_comm_tp(H, B, b, s_in, s_out, l, al, be), co.comm_tp(H, B, b, s_in, s_out, l, al, be),
+                            rel_tol=1e-12, abs_tol=0.0)
+        n2 = int(rng.integers(1, 5))
+        al2 = rng.uniform(1e-6, 50e-6, (n, n2)).tolist()
+        be2 = rng.uniform(10e9, 400e9, (n, n2)).tolist()
+        assert math.isclose(hx.cost_comm_pp(H, B, b, s_in, s_out, al2, be2), co.comm_pp(H, B, b, s_in, s_out, al2, be2),
+                            rel_tol=1e-12)
+        assert math.isclose(hx.cost_mem(H, B, b, s_in, s_out, l, n, pf), co.mem(H, B, b, s_in, s_out, l, n, pf), rel_tol=1e-12,
+                            abs_tol=0.0)
+    # invalid arguments give NaN, never a plausible number
+    assert math.isnan(hx.cost_comp(0, 2, 1, 1, 1, 1, [1e12], [1e14]))
+    assert math.isnan(hx.cost_comp(8192, 2, 1, 1, 1, 1, [0.0], [1e14]))
+    assert math.isnan(hx.cost_comm_tp(8192, 2, 1, 1, 1, 1, [[0, 1e-6], [1e-6, 0]], [[1, 0.0], [1e9, 1]]))
+    assert hx.cost_comm_tp(8192, 2, 1, 1, 1, 1, [[0.0]], [[1.0]]) == 0.0

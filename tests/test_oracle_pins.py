@@ -454,3 +454,49 @@ def test_cost_model_identities():
         # memory: Llama-style parameter count scales the first term only
         assert math.isclose(co.mem(H, B, b, s_in, s_out, l, n, 12.75) - co.mem(H, B, b, s_in, s_out, l, n, 12.0),
                             0.75 * H * H * B / n * l, rel_tol=1e-9)
+
+
+# ---- pipeline layout (Section 4.2 / Algorithm 1) and search operators (Section 4.3) -----------------------------------
+def _toy_pool():
+    return {"count": [2, 4], "m": [2.0e12, 0.9e12], "c": [300e12, 120e12], "mem": [80e9, 24e9],
+            "tp_alpha": [5e-6, 8e-6], "tp_beta": [300e9, 30e9],
+            "pp_alpha": [[5e-6, 50e-6], [50e-6, 8e-6]], "pp_beta": [[300e9, 5e9], [5e9, 30e9]]}
+
+
+def test_layout_bruteforce_special_cases():
+    from oracle import cost_oracle as co
+    from oracle import sched_oracle as sch
+    pool = _toy_pool()
+    task = (4096, 12.0, 2, 1, 128, 32)
+    # one stage: the best single (type, count), straight from the cost formulas
+    cost, asg = sch.best_layout_bruteforce(pool, task, [8])
+    cands = [sch.stage_cost(pool, task, 8, k, n) for k in range(2) for n in range(1, pool["count"][k] + 1)]
+    assert cost == min(cands) and len(asg) == 1
+    # a stage that does not fit any type's memory makes the layout infeasible
+    big = (8192, 12.0, 2, 64, 4096, 4096)
+    assert sch.best_layout_bruteforce(pool, big, [80])[0] == math.inf
+    # more GPUs can only help (GPUs may stay unused)
+    pool2 = dict(pool, count=[2, 5])
+    for layers in ([4, 4], [2, 3, 3]):
+        assert sch.best_layout_bruteforce(pool2, task, layers)[0] <= sch.best_layout_bruteforce(pool, task, layers)[0]
+    # two stages on the same type: hop over the fast link; the total is the sum of its parts
+    cost, asg = sch.best_layout_bruteforce(pool, task, [4, 4])
+    parts = sum(sch.stage_cost(pool, task, 4, k, n) for k, n in asg) + sch.hop_cost(pool, task, asg[0][0], asg[1][0])
+    assert math.isclose(cost, parts, rel_tol=1e-15)
+    used = [sum(n for k, n in asg if k == t) for t in range(2)]
+    assert all(u <= c for u, c in zip(used, pool["count"]))
+
+
+def test_search_operators_follow_their_definitions():
+    from oracle import sched_oracle as sch
+    assert sch.merge([2, 0, 3], [1, 4, 0]) == [3, 4, 3]
+    a, b = sch.split([5, 0, 4, 1])
+    assert a == [2, 0, 2, 0] and b == [3, 0, 2, 1] and sch.merge(a, b) == [5, 0, 4, 1]
+    a, b = sch.swap([1, 2], [3, 1], 0)
+    assert a == [2, 2] and b == [2, 1]
+    # layer partition proportional to the stages' memory
+    assert sch.repartition_layers(80, [8 * 80e9, 8 * 80e9]) == [40, 40]
+    assert sch.repartition_layers(80, [3.0, 1.0]) == [60, 20]
+    parts = sch.repartition_layers(80, [4 * 24e9, 2 * 80e9, 1 * 48e9])
+    assert sum(parts) == 80 and min(parts) >= 1 and parts[1] > parts[0] > parts[2]
+    assert sch.repartition_layers(3, [100.0, 1.0, 1.0]) == [1, 1, 1]

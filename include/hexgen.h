@@ -232,6 +232,44 @@ double hexgen_cost_comm_pp(int hidden, int bytes_per_elem, int batch, int s_in, 
 double hexgen_cost_mem(int hidden, double params_factor, int bytes_per_elem, int batch, int s_in, int s_out, int layers,
                        int n_dev);
 
+/* ---- pipeline layout and search operators (paper Section 4.2, Algorithm 1; Section 4.3) --------------------------
+ * Host functions, no device work.  A pipeline group is described by GPU types (the paper's vector representation):
+ * count[k] GPUs of type k with memory bandwidth m_d[k], peak rate c_d[k], memory mem_bytes[k], the link inside a
+ * tensor-parallel group of that type (tp_alpha[k], tp_beta[k]: same machine, same type, the paper's heuristic) and one
+ * link per ordered type pair for the hop from a stage of type a to a stage of type b (pp_alpha / pp_beta, row-major
+ * n_types x n_types).  All arrays are HOST arrays owned by the caller.  n_types <= 8, count[k] <= 64.
+ *
+ * hexgen_sched_pipeline_layout: for the given layer partition layers[n_stages], the cheapest assignment of (type,
+ * degree) to every stage under the end-to-end cost of Section 4.2 (sum of Eq. 3 and Eq. 4 per stage, Eq. 5 per hop)
+ * subject to the memory limit of Eq. 6 per stage, by the dynamic programme of Algorithm 1 (state: stages served, GPUs
+ * used per type, type of the last stage).  GPUs may stay unused.  pow2_degrees_only != 0 restricts degrees to powers
+ * of two.  Returns the cost in seconds and, when both are not NULL, the chosen type and degree per stage; +infinity
+ * when no assignment fits; NaN for invalid arguments.
+ *
+ * hexgen_sched_merge / split / swap: the mutation operators on group vectors (split: floor / ceil halves; swap moves
+ * one GPU of `type` from tau2 to tau1, in place).  hexgen_sched_repartition_layers: layer partition proportional to
+ * the memory of the GPU set serving each stage, at least one layer per stage, remainder by largest fractional part.
+ * These four return 1 on success, 0 for invalid arguments (outputs untouched).
+ */
+typedef struct {
+    int n_types;
+    const int *count;
+    const double *m_d, *c_d, *mem_bytes;
+    const double *tp_alpha, *tp_beta;
+    const double *pp_alpha, *pp_beta;
+} hexgen_pool_t;
+typedef struct {
+    int hidden;
+    double params_factor;
+    int bytes_per_elem, batch, s_in, s_out;
+} hexgen_task_t;
+double hexgen_sched_pipeline_layout(const hexgen_pool_t *pool, const hexgen_task_t *task, int n_stages, const int *layers,
+                                    int pow2_degrees_only, int *stage_type, int *stage_count);
+int hexgen_sched_merge(int n_types, const int *tau1, const int *tau2, int *out);
+int hexgen_sched_split(int n_types, const int *tau, int *out1, int *out2);
+int hexgen_sched_swap(int n_types, int *tau1, int *tau2, int type);
+int hexgen_sched_repartition_layers(int total_layers, int n_stages, const double *stage_mem, int *layers_out);
+
 /* Measurement and test hook, process-wide: force one tile configuration of the prefill projection GEMM instead of
  * the choice by shape.  code = 10 * a + b names the block tile: 88 = 256 x 256 on 4 waves, 98 = 256 x 256 on 8 waves,
  * 84 = 256 x 128, 48 = 128 x 256, 94 / 49 = 128 x 256 on 8 waves (2 x 4 / 4 x 2 wave grid), 44 = 128 x 128;

@@ -57,6 +57,11 @@ SIGNATURES = {
     "hexgen_cost_comm_tp": (C.c_double, [_i, _i, _i, _i, _i, _i, _i, _vp, _vp]),
     "hexgen_cost_comm_pp": (C.c_double, [_i, _i, _i, _i, _i, _i, _i, _vp, _vp]),
     "hexgen_cost_mem": (C.c_double, [_i, C.c_double, _i, _i, _i, _i, _i, _i]),
+    "hexgen_sched_pipeline_layout": (C.c_double, [_vp, _vp, _i, _vp, _i, _vp, _vp]),
+    "hexgen_sched_merge": (_i, [_i, _vp, _vp, _vp]),
+    "hexgen_sched_split": (_i, [_i, _vp, _vp, _vp]),
+    "hexgen_sched_swap": (_i, [_i, _vp, _vp, _i]),
+    "hexgen_sched_repartition_layers": (_i, [_i, _i, _vp, _vp]),
     "hexgen_stage_profile_enable": (_i, [_vp, _i]),
     "hexgen_stage_profile_read": (_i, [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64)]),
 }
@@ -305,6 +310,62 @@ def cost_comm_pp(hidden, bytes_per_elem, batch, s_in, s_out, alpha, beta) -> flo
 
 def cost_mem(hidden, bytes_per_elem, batch, s_in, s_out, layers, n_dev, params_factor=12.0) -> float:
     return lib.hexgen_cost_mem(hidden, params_factor, bytes_per_elem, batch, s_in, s_out, layers, n_dev)
+
+
+class _Pool(C.Structure):
+    _fields_ = [("n_types", C.c_int), ("count", C.POINTER(C.c_int)), ("m_d", C.POINTER(C.c_double)),
+                ("c_d", C.POINTER(C.c_double)), ("mem_bytes", C.POINTER(C.c_double)), ("tp_alpha", C.POINTER(C.c_double)),
+                ("tp_beta", C.POINTER(C.c_double)), ("pp_alpha", C.POINTER(C.c_double)), ("pp_beta", C.POINTER(C.c_double))]
+
+
+class _Task(C.Structure):
+    _fields_ = [("hidden", C.c_int), ("params_factor", C.c_double), ("bytes_per_elem", C.c_int), ("batch", C.c_int),
+                ("s_in", C.c_int), ("s_out", C.c_int)]
+
+
+def _iarr(values):
+    return (C.c_int * len(values))(*[int(v) for v in values])
+
+
+def sched_pipeline_layout(pool: dict, task, layers, pow2_degrees_only: bool = False):
+    """Algorithm 1 (hexgen_sched_pipeline_layout).  pool: dict with count, m, c, mem, tp_alpha, tp_beta (per type) and
+    pp_alpha, pp_beta (type x type); task = (hidden, params_factor, bytes_per_elem, batch, s_in, s_out).
+    Returns (cost seconds, [(type, degree) per stage])."""
+    nt = len(pool["count"])
+    keep = [_iarr(pool["count"]), _darr(pool["m"]), _darr(pool["c"]), _darr(pool["mem"]), _darr(pool["tp_alpha"]),
+            _darr(pool["tp_beta"]), _darr(pool["pp_alpha"]), _darr(pool["pp_beta"])]
+    p = _Pool(nt, keep[0], keep[1], keep[2], keep[3], keep[4], keep[5], keep[6], keep[7])
+    t = _Task(int(task[0]), float(task[1]), int(task[2]), int(task[3]), int(task[4]), int(task[5]))
+    ls = _iarr(layers)
+    st, sc = (C.c_int * len(layers))(), (C.c_int * len(layers))()
+    cost = lib.hexgen_sched_pipeline_layout(C.byref(p), C.byref(t), len(layers), ls, int(pow2_degrees_only), st, sc)
+    return cost, [(st[j], sc[j]) for j in range(len(layers))]
+
+
+def sched_merge(t1, t2):
+    out = (C.c_int * len(t1))()
+    assert lib.hexgen_sched_merge(len(t1), _iarr(t1), _iarr(t2), out)
+    return list(out)
+
+
+def sched_split(t):
+    a, b = (C.c_int * len(t))(), (C.c_int * len(t))()
+    assert lib.hexgen_sched_split(len(t), _iarr(t), a, b)
+    return list(a), list(b)
+
+
+def sched_swap(t1, t2, k):
+    a, b = _iarr(t1), _iarr(t2)
+    if not lib.hexgen_sched_swap(len(t1), a, b, k):
+        raise ValueError("swap: the second group has no GPU of that type")
+    return list(a), list(b)
+
+
+def sched_repartition_layers(total_layers, stage_mem):
+    out = (C.c_int * len(stage_mem))()
+    if not lib.hexgen_sched_repartition_layers(total_layers, len(stage_mem), _darr(stage_mem), out):
+        raise ValueError("repartition_layers: invalid arguments")
+    return list(out)
 
 
 def set_gemm_tile(code: int):

@@ -99,3 +99,60 @@ def test_cost_model_functions_match_the_oracle():
     assert math.isnan(hx.cost_comp(8192, 2, 1, 1, 1, 1, [0.0], [1e14]))
     assert math.isnan(hx.cost_comm_tp(8192, 2, 1, 1, 1, 1, [[0, 1e-6], [1e-6, 0]], [[1, 0.0], [1e9, 1]]))
     assert hx.cost_comm_tp(8192, 2, 1, 1, 1, 1, [[0.0]], [[1.0]]) == 0.0
+
+
+# ---- pipeline layout DP and search operators against the oracle -------------------------------------------------
+def test_pipeline_layout_dp_equals_brute_force():
+    import math
+
+    import numpy as np
+
+    from oracle import sched_oracle as sch
+    rng = np.random.default_rng(17)
+    for trial in range(25):
+        nt = int(rng.integers(1, 4))
+        pool = {"count": [int(rng.integers(1, 5)) for _ in range(nt)],
+                "m": list(rng.uniform(0.4e12, 6e12, nt)), "c": list(rng.uniform(60e12, 1500e12, nt)),
+                "mem": list(rng.choice([16e9, 24e9, 48e9, 80e9, 192e9], nt)),
+                "tp_alpha": list(rng.uniform(2e-6, 20e-6, nt)), "tp_beta": list(rng.uniform(20e9, 400e9, nt)),
+                "pp_alpha": rng.uniform(5e-6, 200e-6, (nt, nt)).tolist(), "pp_beta": rng.uniform(1e9, 100e9, (nt, nt)).tolist()}
+        task = (int(rng.choice([2048, 4096, 8192])), float(rng.choice([12.0, 12.75])), 2, int(rng.integers(1, 9)),
+                int(rng.integers(16, 1025)), int(rng.integers(1, 129)))
+        S = int(rng.integers(1, 4))
+        layers = [int(rng.integers(1, 20)) for _ in range(S)]
+        for pow2 in (False, True):
+            ref, ref_asg = sch.best_layout_bruteforce(pool, task, layers, degrees={1, 2, 4, 8} if pow2 else None)
+            cost, asg = hx.sched_pipeline_layout(pool, task, layers, pow2)
+            if ref == math.inf:
+                assert cost == math.inf
+                continue
+            assert math.isclose(cost, ref, rel_tol=1e-12), (trial, cost, ref)
+            # the returned assignment is feasible and costs what the function says (ties may pick another optimum)
+            used = [sum(n for k, n in asg if k == t) for t in range(nt)]
+            assert all(u <= c for u, c in zip(used, pool["count"])) and all(n >= 1 for _, n in asg)
+            total = sum(sch.stage_cost(pool, task, layers[j], k, n) for j, (k, n) in enumerate(asg))
+            total += sum(sch.hop_cost(pool, task, asg[j][0], asg[j + 1][0]) for j in range(S - 1))
+            assert math.isclose(total, cost, rel_tol=1e-12)
+
+
+def test_search_operators_match_the_oracle():
+    import numpy as np
+
+    from oracle import sched_oracle as sch
+    rng = np.random.default_rng(19)
+    for _ in range(30):
+        nt = int(rng.integers(1, 6))
+        t1 = [int(v) for v in rng.integers(0, 9, nt)]
+        t2 = [int(v) for v in rng.integers(0, 9, nt)]
+        assert hx.sched_merge(t1, t2) == sch.merge(t1, t2)
+        assert hx.sched_split(t1) == sch.split(t1)
+        k = int(rng.integers(0, nt))
+        if t2[k] >= 1:
+            assert hx.sched_swap(t1, t2, k) == sch.swap(t1, t2, k)
+        else:
+            with pytest.raises(ValueError):
+                hx.sched_swap(t1, t2, k)
+        S = int(rng.integers(1, 7))
+        memv = [float(v) for v in rng.choice([24e9, 48e9, 80e9, 160e9, 640e9], S)]
+        L = int(rng.integers(S, 121))
+        assert hx.sched_repartition_layers(L, memv) == sch.repartition_layers(L, memv)

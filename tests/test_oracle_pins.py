@@ -487,6 +487,36 @@ def test_layout_bruteforce_special_cases():
     assert all(u <= c for u, c in zip(used, pool["count"]))
 
 
+def test_layout_bruteforce_hand_solved_cases():
+    """Cases whose optimum is known without running the enumeration."""
+    from oracle import sched_oracle as sch
+    task = (4096, 12.0, 2, 1, 128, 32)
+    # (a) free communication, memory-bound devices of one type: a stage of l layers on n GPUs costs l / n units, so
+    # layers [9, 1] on 4 GPUs are best served as 3 + 1 (3 + 1 = 4 units; 2 + 2 gives 5; 1 + 3 gives 9.33)
+    one = {"count": [4], "m": [1e12], "c": [math.inf], "mem": [1e15], "tp_alpha": [0.0], "tp_beta": [math.inf],
+           "pp_alpha": [[0.0]], "pp_beta": [[math.inf]]}
+    cost, asg = sch.best_layout_bruteforce(one, task, [9, 1])
+    unit = sch.stage_cost(one, task, 1, 0, 1)
+    assert asg == [(0, 3), (0, 1)] and math.isclose(cost, 4 * unit, rel_tol=1e-12)
+    assert math.isclose(sch.stage_cost(one, task, 9, 0, 3), 3 * unit, rel_tol=1e-12)
+    # (b) a hop between different types priced out of reach: every stage lands on the same type
+    pool = _toy_pool()
+    pool["pp_alpha"] = [[5e-6, 1e9], [1e9, 8e-6]]
+    cost, asg = sch.best_layout_bruteforce(pool, task, [3, 3, 2])
+    assert cost < 1e6 and len({k for k, _ in asg}) == 1
+    # (c) a type whose memory cannot hold even one layer is never chosen, however fast it is
+    pool = _toy_pool()
+    pool["mem"] = [1e6, 24e9]
+    pool["m"][0] = 1e15
+    cost, asg = sch.best_layout_bruteforce(pool, task, [4, 4])
+    assert cost < math.inf and all(k == 1 for k, _ in asg)
+    # (d) with the degree restriction the optimum can only get worse, and it obeys the restriction
+    pool = dict(_toy_pool(), count=[3, 4])
+    free, _ = sch.best_layout_bruteforce(pool, task, [5, 3])
+    restr, asg = sch.best_layout_bruteforce(pool, task, [5, 3], degrees={1, 2, 4})
+    assert restr >= free and all(n in (1, 2, 4) for _, n in asg)
+
+
 def test_search_operators_follow_their_definitions():
     from oracle import sched_oracle as sch
     assert sch.merge([2, 0, 3], [1, 4, 0]) == [3, 4, 3]

@@ -24,19 +24,36 @@
 #include "kernels.h"
 #include "kvlayout.h"
 
-// rstd of every token row from the per-unit sums of squares; wave w handles tokens w, w + WAVES, ...
+// rstd of a token row from the per-unit sums of squares of the residual stream
+__device__ inline void rstd_row(const DecodeEpi &e, int t, int lane, float *s_rstd) {
+    float r = 1.0f;
+    if (e.ssq_in) {
+        float ss = 0.f;
+        for (int i = lane; i < e.ssq_units; i += 64) ss += e.ssq_in[i * DEC_SSQ_STRIDE + t];
+        ss = wave_sum(ss);
+        r = 1.0f / sqrtf(ss / (float)e.norm_dim + e.eps);
+    }
+    if (lane == 0) s_rstd[t] = r;
+}
+// wave w handles tokens w, w + WAVES, ...
 template <int WAVES>
 __device__ inline void load_rstd(const DecodeEpi &e, int T, int wave, int lane, float *s_rstd) {
-    for (int t = wave; t < T; t += WAVES) {
-        float r = 1.0f;
-        if (e.ssq_in) {
-            float ss = 0.f;
-            for (int i = lane; i < e.ssq_units; i += 64) ss += e.ssq_in[i * DEC_SSQ_STRIDE + t];
-            ss = wave_sum(ss);
-            r = 1.0f / sqrtf(ss / (float)e.norm_dim + e.eps);
-        }
-        if (lane == 0) s_rstd[t] = r;
-    }
+    for (int t = wave; t < T; t += WAVES) rstd_row(e, t, lane, s_rstd);
+}
+// The same in two halves, so that the loads can be requested ahead of other memory traffic and summed later: the
+// first RSTD_REGS * 64 units wait in registers (hidden sizes up to 8192), any further ones are fetched in the second half.
+constexpr int RSTD_REGS = 8;
+__device__ inline void rstd_request(const DecodeEpi &e, int t, int lane, float (&sv)[RSTD_REGS]) {
+#pragma unroll
+    for (int j = 0; j < RSTD_REGS; ++j) sv[j] = e.ssq_in[min(lane + 64 * j, e.ssq_units - 1) * DEC_SSQ_STRIDE + t];
+}
+__device__ inline void rstd_finish(const DecodeEpi &e, int t, int lane, const float (&sv)[RSTD_REGS], float *s_rstd) {
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < RSTD_REGS; ++j) ss += lane + 64 * j < e.ssq_units ? sv[j] : 0.f;      // lane's units ascending
+    for (int i = lane + 64 * RSTD_REGS; i < e.ssq_units; i += 64) ss += e.ssq_in[i * DEC_SSQ_STRIDE + t];
+    ss = wave_sum(ss);
+    if (lane == 0) s_rstd[t] = 1.0f / sqrtf(ss / (float)e.norm_dim + e.eps);
 }
 
 __device__ inline void store_split4(const float x[4], bf16_t *hi, bf16_t *lo, size_t off) {
@@ -157,9 +174,11 @@ __device__ inline void decode_epilogue(const floatx4 (&v)[UT], int unit, int b, 
     }
 }
 
+constexpr int kXldsMaxBytes = 64 * 1024;      // activation operand staged in LDS up to this size
+
 // XLDS: the whole activation operand (T <= 2 rows) is staged once per block in LDS, so the main loop
 // issues nothing but weight loads; otherwise each lane fetches its 16-byte pieces per k-tile (L2 hits).
-template <int NB, int UT, int WAVES, int UNROLL, int MODE, bool XLDS>
+template <int NB, int UT, int WAVES, int UNROLL, int MODE, bool XLDS, int XR>
 __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *__restrict__ Wp,
                                                                 const bf16_t *__restrict__ Xa, int N, int k_tiles,
                                                                 int T, DecodeEpi e) {
@@ -167,7 +186,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
     __shared__ float s_rstd[32];
     extern __shared__ bf16x8 xs[];          // XLDS: copy of Xa, [token][k_tile][plane][lane group]
     const int unit = blockIdx.x;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
 
     floatx4 acc[UT][NB];
 #pragma unroll
@@ -190,67 +209,90 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
         xg[b] = (XLDS ? xs : reinterpret_cast<const bf16x8 *>(Xa)) + (size_t)(xv[b] ? token : 0) * k_tiles * 8 + (lane >> 4);
     }
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    // Wave w owns k-tiles w, w + WAVES, ...; it holds a ring of UNROLL of them per feature tile in registers.  The
+    // first ring round is requested before anything else, so the weights are already on their way while the block
+    // stages the activation operand and derives the rows' rstd.
+    const int rounds = (k_tiles - wave + WAVES - 1) / WAVES / UNROLL;
+    // request order = arrival order: the operand copy and the sums of squares (L2 hits) go out first and are
+    // waited for first; the weights requested right behind them stay in flight meanwhile
+    // (every request below is unconditional, out-of-range ones re-read a valid address: the compiler can only count
+    // requests in flight exactly, and so wait for the oldest alone, when none of them sits behind a branch)
+    bf16x8 xr[XLDS ? XR : 1];
+    const int n16 = T * k_tiles * 8;
     if (XLDS) {
-        const int n16 = T * k_tiles * 8;
-        for (int idx = threadIdx.x; idx < n16; idx += WAVES * 64) xs[idx] = reinterpret_cast<const bf16x8 *>(Xa)[idx];
-        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < XR; ++j)
+            xr[j] = reinterpret_cast<const bf16x8 *>(Xa)[min((int)threadIdx.x + j * WAVES * 64, n16 - 1)];
     }
-
-    int kt = wave;
-    for (; kt + (UNROLL - 1) * WAVES < k_tiles; kt += UNROLL * WAVES) {
-        bf16x8 a[UNROLL][UT];
-#pragma unroll
-        for (int i = 0; i < UNROLL; ++i)
-#pragma unroll
-            for (int u = 0; u < UT; ++u) a[i][u] = __builtin_nontemporal_load(wp[u] + (size_t)(kt + i * WAVES) * kstride);
-        if (XLDS) {
-#pragma unroll
-            for (int i = 0; i < UNROLL; ++i) {
-                const int o = (kt + i * WAVES) * 8;
-                const bf16x8 x = xv[0] ? xg[0][o] : zero, y = xv[0] ? xg[0][o + 4] : zero;
-#pragma unroll
-                for (int u = 0; u < UT; ++u) {
-                    acc[u][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], y, acc[u][0], 0, 0, 0);
-                    acc[u][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], x, acc[u][0], 0, 0, 0);
-                }
-            }
-        } else {
-            bf16x8 x[UNROLL][NB], y[UNROLL][NB];
-#pragma unroll
-            for (int i = 0; i < UNROLL; ++i) {
-                const int o = (kt + i * WAVES) * 8;
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    x[i][b] = xv[b] ? xg[b][o] : zero;
-                    y[i][b] = xv[b] ? xg[b][o + 4] : zero;
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < UNROLL; ++i)
-#pragma unroll
-                for (int u = 0; u < UT; ++u)
-#pragma unroll
-                    for (int b = 0; b < NB; ++b) {
-                        acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], y[i][b], acc[u][b], 0, 0, 0);
-                        acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], x[i][b], acc[u][b], 0, 0, 0);
-                    }
-        }
-    }
-    for (; kt < k_tiles; kt += WAVES) {
-#pragma unroll
-        for (int u = 0; u < UT; ++u) {
-            bf16x8 a = __builtin_nontemporal_load(wp[u] + (size_t)kt * kstride);
+    float sv[RSTD_REGS];
+    const bool rstd_wave = MODE != DEC_RESID && wave < T && e.ssq_in != nullptr;       // wave t derives rstd of row t
+    if (rstd_wave) rstd_request(e, wave, lane, sv);
+    // ring slot = the weight tiles of one k-tile and, when the operand is not staged in LDS, its hi / lo pieces too
+    // (requested together, so that no wait for an operand piece ever drains the weight requests behind it)
+    bf16x8 a[UNROLL][UT], xq[XLDS ? 1 : UNROLL][NB][2];
+    auto request = [&](int i, int kt) {
+        if (!XLDS) {
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const bf16x8 x = xv[b] ? xg[b][kt * 8] : zero;
-                const bf16x8 y = xv[b] ? xg[b][kt * 8 + 4] : zero;
-                acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, y, acc[u][b], 0, 0, 0);
-                acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, x, acc[u][b], 0, 0, 0);
+                xq[i][b][0] = xv[b] ? xg[b][kt * 8] : zero;
+                xq[i][b][1] = xv[b] ? xg[b][kt * 8 + 4] : zero;
             }
         }
+#pragma unroll
+        for (int u = 0; u < UT; ++u) a[i][u] = __builtin_nontemporal_load(wp[u] + (size_t)kt * kstride);
+    };
+#pragma unroll
+    for (int i = 0; i < UNROLL; ++i) request(i, min(wave + i * WAVES, k_tiles - 1));
+    if (XLDS) {
+#pragma unroll
+        for (int j = 0; j < XR; ++j) {
+            const int idx = threadIdx.x + j * WAVES * 64;
+            if (idx < n16) xs[idx] = xr[j];
+        }
+    }
+    if (rstd_wave) rstd_finish(e, wave, lane, sv, s_rstd);
+    if (MODE != DEC_RESID)
+        for (int t = rstd_wave ? wave + WAVES : wave; t < T; t += WAVES) rstd_row(e, t, lane, s_rstd);
+    if (XLDS || MODE != DEC_RESID) __syncthreads();
+
+    // the k-tile held by ring slot i against the operand
+    auto contract = [&](int i, int kt) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            bf16x8 x, y;
+            if (XLDS) {
+                x = xv[b] ? xg[b][kt * 8] : zero;
+                y = xv[b] ? xg[b][kt * 8 + 4] : zero;
+            } else {
+                x = xq[i][b][0];
+                y = xq[i][b][1];
+            }
+#pragma unroll
+            for (int u = 0; u < UT; ++u) {
+                acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], y, acc[u][b], 0, 0, 0);
+                acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], x, acc[u][b], 0, 0, 0);
+            }
+        }
+    };
+    // steady state: slot i is consumed and at once refilled with the tile one ring round ahead, so UNROLL - 1
+    // requests per feature tile stay in flight all the time
+    for (int rd = 1; rd < rounds; ++rd) {
+#pragma unroll
+        for (int i = 0; i < UNROLL; ++i) {
+            const int kt = wave + ((rd - 1) * UNROLL + i) * WAVES;
+            contract(i, kt);
+            request(i, kt + UNROLL * WAVES);
+        }
+    }
+    if (rounds > 0) {
+#pragma unroll
+        for (int i = 0; i < UNROLL; ++i) contract(i, wave + ((rounds - 1) * UNROLL + i) * WAVES);
+    }
+    for (int kt = wave + rounds * UNROLL * WAVES; kt < k_tiles; kt += WAVES) {       // fewer than UNROLL tiles left
+        request(0, kt);
+        contract(0, kt);
     }
 
-    if (MODE != DEC_RESID) load_rstd<WAVES>(e, T, wave, lane, s_rstd);
 #pragma unroll
     for (int u = 0; u < UT; ++u)
 #pragma unroll
@@ -399,12 +441,11 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(const float *__restr
 }
 
 namespace {
-constexpr int kXldsMaxBytes = 64 * 1024;      // activation operand staged in LDS up to this size
 
-template <int NB, int UT, int UNR, int MODE, bool XLDS>
+template <int NB, int UT, int UNR, int MODE, bool XLDS, int XR>
 void launch_one(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, hipStream_t s) {
     constexpr int WAVES = 8;
-    auto kern = decode_proj_kernel<NB, UT, WAVES, UNR, MODE, XLDS>;
+    auto kern = decode_proj_kernel<NB, UT, WAVES, UNR, MODE, XLDS, XR>;
     size_t dyn = 0;
     if (XLDS) {
         dyn = (size_t)T * k_tiles * 8 * sizeof(bf16x8);
@@ -421,9 +462,11 @@ void launch_one(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, c
 template <int UT, int MODE>
 void launch_mode(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, hipStream_t s) {
     const size_t xbytes = (size_t)T * k_tiles * 8 * sizeof(bf16x8);
-    if (T <= 2 && xbytes <= (size_t)kXldsMaxBytes) launch_one<1, UT, 8 / UT, MODE, true>(Wp, Xa, N, k_tiles, T, e, s);
-    else if (T <= 16) launch_one<1, UT, 8 / UT, MODE, false>(Wp, Xa, N, k_tiles, T, e, s);
-    else launch_one<2, UT, 8 / UT, MODE, false>(Wp, Xa, N, k_tiles, T, e, s);
+    // staged operand: XR 16-byte pieces per thread (512 threads), 4 up to 32 KB, 8 up to 64 KB
+    if (T <= 2 && xbytes <= (size_t)kXldsMaxBytes / 2) launch_one<1, UT, 8 / UT, MODE, true, 4>(Wp, Xa, N, k_tiles, T, e, s);
+    else if (T <= 2 && xbytes <= (size_t)kXldsMaxBytes) launch_one<1, UT, 8 / UT, MODE, true, 8>(Wp, Xa, N, k_tiles, T, e, s);
+    else if (T <= 16) launch_one<1, UT, 8 / UT, MODE, false, 1>(Wp, Xa, N, k_tiles, T, e, s);
+    else launch_one<2, UT, 8 / UT, MODE, false, 1>(Wp, Xa, N, k_tiles, T, e, s);
 }
 }  // namespace
 

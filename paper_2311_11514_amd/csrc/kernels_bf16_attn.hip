@@ -6,132 +6,15 @@
 //
 // Decode: the G query heads that share a KV head are the 16 columns of operand B, so every K and V
 // fragment is fetched from HBM exactly once per sequence and serves the whole query group inside one
-// MFMA.  The KV range of a sequence is split across blockIdx.x; partial (m, l, o) triples are merged
-// by log-sum-exp in a second kernel, in split order.
+// MFMA.  A long context with few sequences is split over several blocks, whose partial (m, l, o) triples the
+// last block to finish merges by log-sum-exp, in split order.
 #include "kernels.h"
 #include "kvlayout.h"
 
 #define NEG_INF (-INFINITY)
 
-template <int D>
-__global__ __launch_bounds__(64) void attn_decode_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ q_lo,
-                                                        const bf16_t *__restrict__ kc,
-                                                        const bf16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
-                                                        const int32_t *__restrict__ row_pos, int nsplit,
-                                                        float *__restrict__ part_o, float *__restrict__ part_ml,
-                                                        float scale_log2e) {
-    constexpr int KT = D / 32, DT = D / 16;
-    const int split = blockIdx.x, c = blockIdx.y, sq = blockIdx.z;
-    const int lane = threadIdx.x, j = lane & 15, g = lane >> 4;
-    const int n_pos = row_pos[sq] + 1;   // cached context plus the row appended in this step
-    const int n_t32 = (n_pos + 31) >> 5;
-    const int per = (n_t32 + nsplit - 1) / nsplit;
-    const int t0 = split * per, t1 = min(n_t32, t0 + per);
-    const int head = c * G + j;
-    const bool hv = j < G;
-
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    // the query is carried as hi + lo bf16 parts (decode is HBM-bound: the second MFMA is free)
-    bf16x8 qf[KT], ql[KT];
-#pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
-        const size_t qo = ((size_t)sq * hq_l + head) * D + kt * 32 + 8 * g;
-        qf[kt] = hv ? *reinterpret_cast<const bf16x8 *>(q + qo) : zero;
-        ql[kt] = hv ? *reinterpret_cast<const bf16x8 *>(q_lo + qo) : zero;
-    }
-
-    floatx4 oacc[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) oacc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    float m = NEG_INF, lsum = 0.f;
-
-    const size_t slab = (size_t)sq * kg.seq_stride + (size_t)c * kg.smax * D;
-    const bf16x8 *ks = reinterpret_cast<const bf16x8 *>(kc + slab) + lane;
-    const bf16x8 *vs = reinterpret_cast<const bf16x8 *>(vc + slab) + lane;
-
-    for (int t = t0; t < t1; ++t) {
-        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-        bf16x8 ka[KT], kb[KT], va[DT];
-#pragma unroll
-        for (int kt = 0; kt < KT; ++kt) {
-            ka[kt] = ks[(size_t)((2 * t) * KT + kt) * 64];
-            kb[kt] = ks[(size_t)((2 * t + 1) * KT + kt) * 64];
-        }
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) va[dt] = vs[(size_t)(t * DT + dt) * 64];
-#pragma unroll
-        for (int kt = 0; kt < KT; ++kt) {
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt], ql[kt], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[kt], ql[kt], s1, 0, 0, 0);
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt], qf[kt], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[kt], qf[kt], s1, 0, 0, 0);
-        }
-        const int pbase = t * 32 + 4 * g;
-        float mx = NEG_INF;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            s0[r] = (pbase + r < n_pos) ? s0[r] * scale_log2e : NEG_INF;
-            s1[r] = (pbase + 16 + r < n_pos) ? s1[r] * scale_log2e : NEG_INF;
-            mx = fmaxf(mx, fmaxf(s0[r], s1[r]));
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m, mx);          // finite: position t*32 < n_pos is never masked
-        const float alpha = exp2f(m - m_new);
-        m = m_new;
-        float p0[4], p1[4], ps = 0.f;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            p0[r] = exp2f(s0[r] - m_new);
-            p1[r] = exp2f(s1[r] - m_new);
-            ps += p0[r] + p1[r];
-        }
-        lsum = lsum * alpha + ps;
-        union { uint32_t u[4]; bf16x8 v; } pb, pl;
-        split_pack2(p0[0], p0[1], pb.u[0], pl.u[0]); split_pack2(p0[2], p0[3], pb.u[1], pl.u[1]);
-        split_pack2(p1[0], p1[1], pb.u[2], pl.u[2]); split_pack2(p1[2], p1[3], pb.u[3], pl.u[3]);
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            oacc[dt] *= alpha;
-            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pl.v, oacc[dt], 0, 0, 0);
-            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb.v, oacc[dt], 0, 0, 0);
-        }
-    }
-    lsum += __shfl_xor(lsum, 16, 64);
-    lsum += __shfl_xor(lsum, 32, 64);
-    if (hv) {
-        const size_t e = ((size_t)sq * hq_l + head) * nsplit + split;
-        if (g == 0) { part_ml[e * 2] = m; part_ml[e * 2 + 1] = lsum; }
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-            *reinterpret_cast<floatx4 *>(part_o + e * D + dt * 16 + 4 * g) = oacc[dt];
-    }
-}
-
-// grid (b, hq_l), block D threads: log-sum-exp merge in split order -> packed bf16 o
-template <int D>
-__global__ void attn_decode_merge_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
-                                         int hq_l, int nsplit, bf16_t *__restrict__ o_act) {
-    const int sq = blockIdx.x, head = blockIdx.y, dd = threadIdx.x;
-    const size_t e0 = ((size_t)sq * hq_l + head) * nsplit;
-    float M = NEG_INF;
-    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, part_ml[(e0 + s) * 2]);
-    float L = 0.f, o = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-        const float ms = part_ml[(e0 + s) * 2];
-        const float w = (ms == NEG_INF) ? 0.f : exp2f(ms - M);
-        L += part_ml[(e0 + s) * 2 + 1] * w;
-        o += part_o[(e0 + s) * D + dd] * w;
-    }
-    bf16_t hi, lo;
-    split_bf16(o / L, hi, lo);
-    const size_t off = dec_act_offset(sq, head * D + dd, (hq_l * D) >> 5, 0);
-    o_act[off] = hi;
-    o_act[off + 32] = lo;
-}
-
-// Single-kernel variant: one 8-wave block per (sequence, kv head); the waves interleave over the
-// 32-position tiles of the context and their (m, l, o) triples are merged through LDS in wave order.
+// One 8-wave block per (sequence, kv head); the waves interleave over the 32-position tiles of the context and
+// their (m, l, o) triples are merged through LDS in wave order.
 // Used when there are enough (sequence, kv head) pairs to fill the chip or the context is short.
 template <int D>
 __global__ __launch_bounds__(512) void attn_decode_block_kernel(const bf16_t *__restrict__ q,
@@ -245,12 +128,164 @@ __global__ __launch_bounds__(512) void attn_decode_block_kernel(const bf16_t *__
     }
 }
 
+// Split-KV variant in ONE kernel: grid (nsplit, kv heads, sequences).  A block takes a contiguous run of the
+// sequence's 32-position tiles (its waves interleave over them; with few sequences the run is 8 tiles, one per wave,
+// so the whole context is requested at once), merges its waves through LDS and writes one (m, l, o) partial per query
+// head.  Blocks of one (sequence, kv head) then count themselves on a device counter; whichever arrives LAST merges
+// the partials -- in split order, so the result does not depend on who that was -- and resets the counter for the
+// next launch.  Nobody waits for anybody: every block runs straight to its end.
+// The partials cross the chip's L2 slices: after a block barrier one wave publishes the block's stores with a
+// device-scope fence before it counts the block, and the merging block fences again before it reads.
+template <int D>
+__global__ __launch_bounds__(512) void attn_decode_split_kernel(const bf16_t *__restrict__ q,
+                                                               const bf16_t *__restrict__ q_lo,
+                                                               const bf16_t *__restrict__ kc,
+                                                               const bf16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
+                                                               const int32_t *__restrict__ row_pos, int nsplit,
+                                                               float *part_o, float *part_ml, unsigned int *arrived,
+                                                               bf16_t *__restrict__ o_act, float scale_log2e) {
+    constexpr int KT = D / 32, DT = D / 16, W = 8;
+    __shared__ float s_m[W][16], s_l[W][16];
+    __shared__ float s_o[W][16][D];
+    __shared__ int s_last;
+    const int split = blockIdx.x, c = blockIdx.y, sq = blockIdx.z;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 15, g = lane >> 4;
+    const int n_pos = row_pos[sq] + 1;
+    const int n_t32 = (n_pos + 31) >> 5;
+    const int per = (n_t32 + nsplit - 1) / nsplit;
+    const int t0 = split * per, t1 = min(n_t32, t0 + per);
+    const int head = c * G + j;
+    const bool hv = j < G;
+
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    bf16x8 qf[KT], ql[KT];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+        const size_t qo = ((size_t)sq * hq_l + head) * D + kt * 32 + 8 * g;
+        qf[kt] = hv ? *reinterpret_cast<const bf16x8 *>(q + qo) : zero;
+        ql[kt] = hv ? *reinterpret_cast<const bf16x8 *>(q_lo + qo) : zero;
+    }
+    floatx4 oacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) oacc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float m = NEG_INF, lsum = 0.f;
+    const size_t slab = (size_t)sq * kg.seq_stride + (size_t)c * kg.smax * D;
+    const bf16x8 *ks = reinterpret_cast<const bf16x8 *>(kc + slab) + lane;
+    const bf16x8 *vs = reinterpret_cast<const bf16x8 *>(vc + slab) + lane;
+
+    for (int t = t0 + wave; t < t1; t += W) {
+        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+        bf16x8 ka[KT], kb[KT], va[DT];
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+            ka[kt] = ks[(size_t)((2 * t) * KT + kt) * 64];
+            kb[kt] = ks[(size_t)((2 * t + 1) * KT + kt) * 64];
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) va[dt] = vs[(size_t)(t * DT + dt) * 64];
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt], ql[kt], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[kt], ql[kt], s1, 0, 0, 0);
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt], qf[kt], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[kt], qf[kt], s1, 0, 0, 0);
+        }
+        const int pbase = t * 32 + 4 * g;
+        float mx = NEG_INF;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            s0[r] = (pbase + r < n_pos) ? s0[r] * scale_log2e : NEG_INF;
+            s1[r] = (pbase + 16 + r < n_pos) ? s1[r] * scale_log2e : NEG_INF;
+            mx = fmaxf(mx, fmaxf(s0[r], s1[r]));
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m, mx);          // finite: position t * 32 < n_pos is never masked
+        const float alpha = exp2f(m - m_new);
+        m = m_new;
+        float p0[4], p1[4], ps = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            p0[r] = exp2f(s0[r] - m_new);
+            p1[r] = exp2f(s1[r] - m_new);
+            ps += p0[r] + p1[r];
+        }
+        lsum = lsum * alpha + ps;
+        union { uint32_t u[4]; bf16x8 v; } pb, pl;
+        split_pack2(p0[0], p0[1], pb.u[0], pl.u[0]); split_pack2(p0[2], p0[3], pb.u[1], pl.u[1]);
+        split_pack2(p1[0], p1[1], pb.u[2], pl.u[2]); split_pack2(p1[2], p1[3], pb.u[3], pl.u[3]);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            oacc[dt] *= alpha;
+            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pl.v, oacc[dt], 0, 0, 0);
+            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb.v, oacc[dt], 0, 0, 0);
+        }
+    }
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    if (g == 0) { s_m[wave][j] = m; s_l[wave][j] = lsum; }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<floatx4 *>(&s_o[wave][j][dt * 16 + 4 * g]) = oacc[dt];
+    __syncthreads();
+    // the block's partial per query head: waves merged in wave order (a block with no tiles writes m = -inf, l = 0)
+    const int hh = (threadIdx.x * 4) / D, dd = (threadIdx.x * 4) % D;      // G * D / 4 <= 512 work items, one per thread
+    const bool item = threadIdx.x * 4 < G * D;
+    const size_t e0 = ((size_t)sq * hq_l + c * G + (item ? hh : 0)) * nsplit;
+    if (item) {
+        float M = NEG_INF;
+#pragma unroll
+        for (int w = 0; w < W; ++w) M = fmaxf(M, s_m[w][hh]);
+        float L = 0.f;
+        floatx4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            const float mw = s_m[w][hh];
+            const float wt = (mw == NEG_INF) ? 0.f : exp2f(mw - M);
+            L += s_l[w][hh] * wt;
+            o += *reinterpret_cast<const floatx4 *>(&s_o[w][hh][dd]) * wt;
+        }
+        *reinterpret_cast<floatx4 *>(part_o + (e0 + split) * D + dd) = o;
+        if (dd == 0) { part_ml[(e0 + split) * 2] = M; part_ml[(e0 + split) * 2 + 1] = L; }
+    }
+    __syncthreads();                       // the block's stores have been issued and waited for ...
+    if (threadIdx.x == 0) {
+        __threadfence();                   // ... one wave publishes them device-wide (the fence is cumulative) ...
+        const unsigned int before = atomicAdd(&arrived[sq * gridDim.y + c], 1u);       // ... before the block counts itself
+        s_last = before + 1 == (unsigned int)nsplit;
+        if (s_last) {
+            atomicExch(&arrived[sq * gridDim.y + c], 0u);      // all blocks have counted: ready for the next launch
+            __threadfence();               // read what the other blocks published, not a stale cached line
+        }
+    }
+    __syncthreads();
+    if (!s_last) return;
+    if (item) {
+        float M = NEG_INF;
+        for (int sp = 0; sp < nsplit; ++sp) M = fmaxf(M, __builtin_nontemporal_load(part_ml + (e0 + sp) * 2));
+        float L = 0.f;
+        floatx4 o = {0.f, 0.f, 0.f, 0.f};
+        for (int sp = 0; sp < nsplit; ++sp) {
+            const float ms = __builtin_nontemporal_load(part_ml + (e0 + sp) * 2);
+            const float wt = (ms == NEG_INF) ? 0.f : exp2f(ms - M);
+            L += __builtin_nontemporal_load(part_ml + (e0 + sp) * 2 + 1) * wt;
+            o += __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(part_o + (e0 + sp) * D + dd)) * wt;
+        }
+        const float inv = 1.0f / L;
+        uint2 ph, pl;
+        split_pack2(o[0] * inv, o[1] * inv, ph.x, pl.x);
+        split_pack2(o[2] * inv, o[3] * inv, ph.y, pl.y);
+        const size_t off = dec_act_offset(sq, (c * G + hh) * D + dd, (hq_l * D) >> 5, 0);
+        *reinterpret_cast<uint2 *>(o_act + off) = ph;
+        *reinterpret_cast<uint2 *>(o_act + off + 32) = pl;
+    }
+}
+
 void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, const bf16_t *vc, KvGeom kg,
                         int hq_l, const int32_t *row_pos, int b, int nsplit, float *part_o, float *part_ml,
-                        bf16_t *o_act, hipStream_t s) {
+                        unsigned int *arrived, bf16_t *o_act, hipStream_t s) {
     const int G = hq_l / kg.hkv_l;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)kg.d);
-    if (nsplit <= 1) {       // single kernel, LDS merge
+    if (nsplit <= 1) {       // one block per (sequence, kv head), LDS merge
         dim3 grid(kg.hkv_l, b);
         if (kg.d == 128)
             hipLaunchKernelGGL(attn_decode_block_kernel<128>, grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G,
@@ -261,17 +296,12 @@ void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, c
         return;
     }
     dim3 grid(nsplit, kg.hkv_l, b);
-    if (kg.d == 128) {
-        hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(64), 0, s, q, q_lo, kc, vc, kg, hq_l, G, row_pos, nsplit,
-                           part_o, part_ml, scale_log2e);
-        hipLaunchKernelGGL(attn_decode_merge_kernel<128>, dim3(b, hq_l), dim3(128), 0, s, part_o, part_ml, hq_l,
-                           nsplit, o_act);
-    } else {
-        hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(64), 0, s, q, q_lo, kc, vc, kg, hq_l, G, row_pos, nsplit,
-                           part_o, part_ml, scale_log2e);
-        hipLaunchKernelGGL(attn_decode_merge_kernel<64>, dim3(b, hq_l), dim3(64), 0, s, part_o, part_ml, hq_l, nsplit,
-                           o_act);
-    }
+    if (kg.d == 128)
+        hipLaunchKernelGGL(attn_decode_split_kernel<128>, grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G, row_pos,
+                           nsplit, part_o, part_ml, arrived, o_act, scale_log2e);
+    else
+        hipLaunchKernelGGL(attn_decode_split_kernel<64>, grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G, row_pos,
+                           nsplit, part_o, part_ml, arrived, o_act, scale_log2e);
 }
 
 // -------------------------------------------------------------------------------------------------

@@ -73,6 +73,7 @@ struct Workspace {
     bf16_t *xa_n = nullptr, *xa_o = nullptr, *xa_u = nullptr;   // decode operands, compact hi/lo layout [32][K][2]
     bf16_t *q_lo = nullptr;
     float *att_o = nullptr, *att_ml = nullptr;
+    unsigned int *att_arrived = nullptr;      // per (sequence, kv head): split blocks that have finished; zero between launches
     float *ssq = nullptr;                       // decode: 2 x [H/16 units][DEC_SSQ_STRIDE] sums of squares
     float *ssq_pf = nullptr;                    // prefill: 2 x [H/128][T] sums of squares
     // fp32 path
@@ -118,7 +119,7 @@ namespace {
 size_t esize(hexgen_dtype_t dt) { return dt == HEXGEN_F32 ? 4 : 2; }
 
 void free_ws(Workspace &w) {
-    void *ptrs[] = {w.dec_part, w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.xa_n, w.xa_o, w.xa_u, w.q_lo, w.ssq, w.ssq_pf, w.att_o, w.att_ml, w.n32, w.q32, w.o32, w.u32,
+    void *ptrs[] = {w.dec_part, w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.xa_n, w.xa_o, w.xa_u, w.q_lo, w.ssq, w.ssq_pf, w.att_o, w.att_ml, w.att_arrived, w.n32, w.q32, w.o32, w.u32,
                     w.rowmap};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
@@ -166,6 +167,8 @@ hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
         }
         HX_TRY(dmalloc(&w.att_o, drows * st->hq_l * kMaxAttnSplit * st->d));
         HX_TRY(dmalloc(&w.att_ml, drows * st->hq_l * kMaxAttnSplit * 2));
+        HX_TRY(dmalloc(&w.att_arrived, drows * st->hkv_l));
+        HX_HIP(hipMemset(w.att_arrived, 0, drows * st->hkv_l * sizeof(unsigned int)));
         const size_t ssq_n = 2 * (size_t)(st->H / 16) * DEC_SSQ_STRIDE;
         HX_TRY(dmalloc(&w.ssq, ssq_n));
         HX_TRY(dmalloc(&w.ssq_pf, 2 * (size_t)(st->H / GEMM_SSQ_COLS + 1) * T));
@@ -343,9 +346,13 @@ int pick_attn_split(const hexgen_stage *st, const hexgen_kv_cache *kv, int batch
     int mx = 0;
     for (int i = 0; i < batch; ++i) mx = std::max(mx, kv->lens[i] + 1);
     const int n_t32 = (mx + 31) / 32;
-    // enough (sequence, kv head) pairs or a short context: one kernel with an in-block merge
-    if (batch * st->hkv_l >= 32 || n_t32 <= 64) return 1;
-    return std::max(2, std::min(kMaxAttnSplit, n_t32 / 4));
+    // Enough (sequence, kv head) pairs to fill the chip, or a context short enough that one block's eight waves walk it
+    // in a few steps: one block per pair.  Otherwise split the context, eight tiles (one per wave) to a block, so
+    // that the whole context is requested at once; the split costs each block a device-scope fence, which is why it
+    // is not used when there are many blocks anyway.
+    const int pairs = batch * st->hkv_l;
+    if (pairs >= 32 || n_t32 <= 48) return 1;
+    return std::min(kMaxAttnSplit, (n_t32 + 7) / 8);
 }
 
 DecodeEpi epi_base(hexgen_stage *st, int mode) {
@@ -380,7 +387,7 @@ void attn_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Ro
     decode_proj(st, r, ly.wqkv, w.xa_n, st->nqkv, st->H, e, PROF_QKV, s);
     st->prof.mark(PROF_ATTN, s);
     launch_attn_decode(w.q, w.q_lo, kc, vc, kg, st->hq_l, w.row_pos, r.batch, pick_attn_split(st, kv, r.batch), w.att_o,
-                       w.att_ml, w.xa_o, s);
+                       w.att_ml, w.att_arrived, w.xa_o, s);
     st->prof.mark(PROF_ATTN, s);
 }
 

@@ -211,6 +211,38 @@ def test_bf16_decode_batch_sizes(cfg, b):
         assert row_rel_err(h, h_ref) < TOL["bf16"] and row_rel_err(p, p_ref) < TOL["bf16"]
 
 
+@pytest.mark.parametrize("cfg,ctx", [(MINI128, [1700, 40, 1537]), (MINI64, [2100]), (MINI64, [5, 1600])])
+def test_bf16_decode_long_context_split_over_blocks(cfg, ctx):
+    """Few sequences with a long context: the attention of one (sequence, kv head) is split over several blocks and
+    merged by the block that finishes last.  Ragged lengths leave the short sequences' later splits empty; the second
+    pass over the same state must give the same bits whichever block happened to merge."""
+    w = _weights(cfg)
+    rank = cfg.tp_ranks[0]
+    ora = make_oracle(cfg, rank, w)
+    oc = ora.new_cache(len(ctx))
+    st = make_gpu_stage(cfg, rank, w)
+    kv = st.kv_cache_create(len(ctx), max(ctx) + 8)
+    for layer in range(cfg.n_layers):
+        for s, n in enumerate(ctx):
+            k, v = generate.synthetic_kv(cfg, layer, s, n)
+            oc.fill(layer, s, k, v)
+            kv.fill(layer, s, k, v)
+    outs = []
+    for rep in range(2):
+        kv.set_lengths(ctx)
+        got = []
+        for step in range(3):
+            x = generate.hidden_rows(cfg, len(ctx), stream_id=1 + step)
+            p, h = gpu_decode(st, kv, cfg, step, x)
+            got.append((p, h))
+            if rep == 0:
+                p_ref, h_ref = ora.decode(oc, x)
+                assert row_rel_err(h, h_ref) < TOL["bf16"] and row_rel_err(p, p_ref) < TOL["bf16"]
+        outs.append(got)
+    for (p0, h0), (p1, h1) in zip(*outs):
+        assert np.array_equal(p0, p1) and np.array_equal(h0, h1)
+
+
 def test_run_to_run_determinism_bf16():
     cfg = MINI128
     w = _weights(cfg)

@@ -73,12 +73,44 @@ __device__ inline void store_act4(const float x[4], bf16_t *xa, int token, int k
     *reinterpret_cast<uint2 *>(xa + off + 32) = ol;
 }
 
+// What the register epilogue reads from memory, requested long before it is used (the finishing wave asks for it at
+// kernel start, so the answers arrive behind the first weights instead of adding two memory round trips to the
+// block's tail).  Rows beyond T re-read row T - 1, so that no request sits behind a branch.
+//   QKV   : first the row's position, then (once it is known) the rotary table entries of this lane's four pairs
+//   RESID : the residual stream and the next norm's gain at this lane's four columns
+struct EpiPre {
+    floatx4 a, b;
+    int pos;
+};
+template <int MODE>
+__device__ inline void epi_request_first(EpiPre &p, int unit, int b, int lane, int N, int T, const DecodeEpi &e) {
+    const int token = min((lane & 15) + 16 * b, T - 1), g = lane >> 4;
+    if (MODE == DEC_QKV) p.pos = e.row_pos[token];
+    if (MODE == DEC_RESID) {
+        const int n0 = unit * 16 + 4 * g;
+        p.a = *reinterpret_cast<const floatx4 *>(e.h + (size_t)token * N + n0);
+        if (!e.last_layer) p.b = *reinterpret_cast<const floatx4 *>(e.g_next + n0);
+    }
+}
+template <int MODE>
+__device__ inline void epi_request_second(EpiPre &p, int unit, int lane, const DecodeEpi &e) {
+    if (MODE == DEC_QKV) {
+        const int d = e.kg.d, half = d >> 1, tiles_per_head = d >> 4, g = lane >> 4;
+        const int head = unit / tiles_per_head, tl = unit - head * tiles_per_head;
+        if (head < e.hq_l + e.kg.hkv_l) {
+            const int i0 = tl * 8 + 4 * (g & 1);
+            p.a = *reinterpret_cast<const floatx4 *>(e.cos_tab + (size_t)p.pos * half + i0);
+            p.b = *reinterpret_cast<const floatx4 *>(e.sin_tab + (size_t)p.pos * half + i0);
+        }
+    }
+}
+
 // Register epilogue of one unit (UT 16-feature tiles) and one 16-token tile, on complete dot products in the
 // 16x16 accumulator layout: lane = (token j = lane % 16, row group g = lane / 16) holds rows 4g .. 4g+3 of each tile.
 // Must be called by a whole wave (it shuffles across the row groups).
 template <int MODE, int UT>
 __device__ inline void decode_epilogue(const floatx4 (&v)[UT], int unit, int b, int lane, int N, int T, const DecodeEpi &e,
-                                       const float *s_rstd) {
+                                       const float *s_rstd, const EpiPre &pre) {
     const int token = (lane & 15) + 16 * b, g = lane >> 4;
     const bool valid = token < T;
     const float r = (MODE != DEC_RESID && valid) ? s_rstd[token] : 1.0f;
@@ -93,7 +125,7 @@ __device__ inline void decode_epilogue(const floatx4 (&v)[UT], int unit, int b, 
         const int n0 = unit * 16 + 4 * g;
         float ss = 0.f;
         if (valid) {
-            const floatx4 h4 = *reinterpret_cast<const floatx4 *>(e.h + (size_t)token * N + n0);
+            const floatx4 h4 = pre.a;
             if (e.last_layer) {
                 // stage output: the partial without residual, and the residual it belongs to
                 uint2 po;
@@ -109,7 +141,7 @@ __device__ inline void decode_epilogue(const floatx4 (&v)[UT], int unit, int b, 
             } else {
                 const floatx4 hn = h4 + v[0];
                 *reinterpret_cast<floatx4 *>(e.h + (size_t)token * N + n0) = hn;
-                const floatx4 g4 = *reinterpret_cast<const floatx4 *>(e.g_next + n0);
+                const floatx4 g4 = pre.b;
                 const float x[4] = {hn[0] * g4[0], hn[1] * g4[1], hn[2] * g4[2], hn[3] * g4[3]};
                 store_act4(x, e.hg, token, n0, N >> 5);
                 ss = hn[0] * hn[0] + hn[1] * hn[1] + hn[2] * hn[2] + hn[3] * hn[3];
@@ -141,11 +173,10 @@ __device__ inline void decode_epilogue(const floatx4 (&v)[UT], int unit, int b, 
         const bool low = g < 2;                       // rows 0-7 of the tile: features i; rows 8-15: i + d/2
         const int i0 = tl * 8 + 4 * (g & 1);          // first rotary pair index held by this lane
         if (valid) {
-            const int pos = e.row_pos[token];
+            const int pos = pre.pos;
             float out[4];
             if (head < e.hq_l + e.kg.hkv_l) {
-                const floatx4 c4 = *reinterpret_cast<const floatx4 *>(e.cos_tab + (size_t)pos * half + i0);
-                const floatx4 s4 = *reinterpret_cast<const floatx4 *>(e.sin_tab + (size_t)pos * half + i0);
+                const floatx4 c4 = pre.a, s4 = pre.b;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const float lo = low ? mine[j] : other[j], hi = low ? other[j] : mine[j];
@@ -217,6 +248,9 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
     // waited for first; the weights requested right behind them stay in flight meanwhile
     // (every request below is unconditional, out-of-range ones re-read a valid address: the compiler can only count
     // requests in flight exactly, and so wait for the oldest alone, when none of them sits behind a branch)
+    EpiPre pre;
+    const bool finisher = wave < NB;          // wave b finishes token tile b
+    if (finisher) epi_request_first<MODE>(pre, unit, wave, lane, N, T, e);
     bf16x8 xr[XLDS ? XR : 1];
     const int n16 = T * k_tiles * 8;
     if (XLDS) {
@@ -243,6 +277,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
     };
 #pragma unroll
     for (int i = 0; i < UNROLL; ++i) request(i, min(wave + i * WAVES, k_tiles - 1));
+    if (finisher) epi_request_second<MODE>(pre, unit, lane, e);
     if (XLDS) {
 #pragma unroll
         for (int j = 0; j < XR; ++j) {
@@ -298,7 +333,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
 #pragma unroll
         for (int b = 0; b < NB; ++b) red[wave][u * NB + b][lane] = acc[u][b];
     __syncthreads();
-    if (wave >= NB) return;            // wave b finishes token tile b
+    if (!finisher) return;
 
     const int b = wave;
     floatx4 v[UT];
@@ -308,7 +343,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
 #pragma unroll
         for (int w = 1; w < WAVES; ++w) v[u] += red[w][u * NB + b][lane];
     }
-    decode_epilogue<MODE, UT>(v, unit, b, lane, N, T, e, s_rstd);
+    decode_epilogue<MODE, UT>(v, unit, b, lane, N, T, e, s_rstd, pre);
 }
 
 // -------------------------------------------------------------------------------------------------
@@ -428,6 +463,9 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(const float *__restr
     if (idx >= n_units * nbt) return;
     const int unit = idx / nbt, b = idx - unit * nbt;
     const int token = (lane & 15) + 16 * b, g = lane >> 4;
+    EpiPre pre;
+    epi_request_first<MODE>(pre, unit, b, lane, N, T, e);
+    epi_request_second<MODE>(pre, unit, lane, e);
     floatx4 v[UT];
 #pragma unroll
     for (int u = 0; u < UT; ++u) {
@@ -437,7 +475,7 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(const float *__restr
             for (int ks = 0; ks < splits; ++ks)
                 v[u] += *reinterpret_cast<const floatx4 *>(part + ((size_t)ks * T + token) * N + (unit * UT + u) * 16 + 4 * g);
     }
-    decode_epilogue<MODE, UT>(v, unit, b, lane, N, T, e, s_rstd);
+    decode_epilogue<MODE, UT>(v, unit, b, lane, N, T, e, s_rstd, pre);
 }
 
 namespace {

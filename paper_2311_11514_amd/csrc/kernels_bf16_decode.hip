@@ -362,15 +362,20 @@ constexpr int SK_TOK_STRIDE = 1024 + 16;       // LDS bytes per token and chunk;
 
 template <int NB>
 __global__ __launch_bounds__(512) void decode_splitk_kernel(const bf16_t *__restrict__ Wp, const bf16_t *__restrict__ Xa,
-                                                           int n_tiles, int k_tiles, int T, int per,
-                                                           float *__restrict__ part) {
+                                                           int n_tiles, int k_tiles, int T,
+                                                           float *__restrict__ part, const float *__restrict__ ssq_in,
+                                                           int ssq_units, int norm_dim, float eps,
+                                                           float *__restrict__ rstd_out) {
     constexpr int TOK = 16 * NB, LPW = TOK / 8;        // token rows staged per chunk; rows copied per wave
     constexpr int BUF = TOK * SK_TOK_STRIDE;
     extern __shared__ unsigned char sk_lds[];          // [2][TOK][SK_TOK_STRIDE]
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 15, g = lane >> 4;
     const int tile = blockIdx.x * 8 + wave;
     const bool tile_ok = tile < n_tiles;
-    const int kt0 = blockIdx.y * per, kt1 = min(k_tiles, kt0 + per);
+    // the chunks of the contraction are dealt out evenly over the splits (blockIdx.y)
+    const int chunks = (k_tiles + SK_CH - 1) / SK_CH;
+    const int kt0 = (int)((long)blockIdx.y * chunks / gridDim.y) * SK_CH;
+    const int kt1 = min(k_tiles, (int)((long)(blockIdx.y + 1) * chunks / gridDim.y) * SK_CH);
     const int n_chunks = (kt1 - kt0 + SK_CH - 1) / SK_CH;
     const int N = n_tiles * 16;
 
@@ -402,6 +407,17 @@ __global__ __launch_bounds__(512) void decode_splitk_kernel(const bf16_t *__rest
         for (int i = 0; i < SK_CH; ++i)
             w[i] = (c < n_chunks && kc + i < kt1) ? __builtin_nontemporal_load(wsrc + (size_t)(kc + i) * kstride) : zero;
     };
+
+    // On the side: the rows' rstd for the finishing kernel, each row by one wave of one block of the launch (the
+    // sums of squares are requested now and added up after the main loop, when they have long arrived).
+    const int n_blocks = gridDim.x * gridDim.y, bid = blockIdx.y * gridDim.x + blockIdx.x;
+    const int rstd_row = bid + wave * n_blocks;
+    const bool rstd_mine = rstd_out != nullptr && rstd_row < T;
+    float sv[RSTD_REGS];
+    if (rstd_mine && ssq_in != nullptr) {
+#pragma unroll
+        for (int q = 0; q < RSTD_REGS; ++q) sv[q] = ssq_in[min(lane + 64 * q, ssq_units - 1) * DEC_SSQ_STRIDE + rstd_row];
+    }
 
     floatx4 acc[NB];
 #pragma unroll
@@ -439,6 +455,29 @@ __global__ __launch_bounds__(512) void decode_splitk_kernel(const bf16_t *__rest
 #pragma unroll
         for (int i = 0; i < SK_CH; ++i) wc[i] = wn[i];
     }
+    if (rstd_mine) {
+        float r = 1.0f;
+        if (ssq_in != nullptr) {
+            float ss = 0.f;
+#pragma unroll
+            for (int q = 0; q < RSTD_REGS; ++q) ss += lane + 64 * q < ssq_units ? sv[q] : 0.f;
+            for (int i = lane + 64 * RSTD_REGS; i < ssq_units; i += 64) ss += ssq_in[i * DEC_SSQ_STRIDE + rstd_row];
+            ss = wave_sum(ss);
+            r = 1.0f / sqrtf(ss / (float)norm_dim + eps);
+        }
+        if (lane == 0) rstd_out[rstd_row] = r;
+    }
+    if (rstd_out != nullptr)           // a launch of fewer than T / 8 blocks: the rows not dealt out above
+        for (int row = rstd_row + 8 * n_blocks; row < T; row += 8 * n_blocks) {
+            float r = 1.0f;
+            if (ssq_in != nullptr) {
+                float ss = 0.f;
+                for (int i = lane; i < ssq_units; i += 64) ss += ssq_in[i * DEC_SSQ_STRIDE + row];
+                ss = wave_sum(ss);
+                r = 1.0f / sqrtf(ss / (float)norm_dim + eps);
+            }
+            if (lane == 0) rstd_out[row] = r;
+        }
     if (!tile_ok) return;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -449,15 +488,11 @@ __global__ __launch_bounds__(512) void decode_splitk_kernel(const bf16_t *__rest
 }
 
 // Sums the split partials in split order and runs the register epilogue; one wave per (unit, 16-token tile).
+// rstd[T]: the rows' reciprocal rms, left by the split kernel of the same projection.
 template <int MODE, int UT>
 __global__ __launch_bounds__(256) void decode_finish_kernel(const float *__restrict__ part, int splits, int N, int T,
-                                                           int n_units, DecodeEpi e) {
-    __shared__ float s_rstd[32];
+                                                           int n_units, DecodeEpi e, const float *__restrict__ rstd) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    if (MODE != DEC_RESID) {
-        load_rstd<4>(e, T, wave, lane, s_rstd);
-        __syncthreads();
-    }
     const int nbt = (T + 15) >> 4;
     const int idx = blockIdx.x * 4 + wave;
     if (idx >= n_units * nbt) return;
@@ -475,7 +510,7 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(const float *__restr
             for (int ks = 0; ks < splits; ++ks)
                 v[u] += *reinterpret_cast<const floatx4 *>(part + ((size_t)ks * T + token) * N + (unit * UT + u) * 16 + 4 * g);
     }
-    decode_epilogue<MODE, UT>(v, unit, b, lane, N, T, e, s_rstd, pre);
+    decode_epilogue<MODE, UT>(v, unit, b, lane, N, T, e, rstd, pre);
 }
 
 namespace {
@@ -513,12 +548,19 @@ template <int MODE, int UT>
 void launch_splitk(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, float *scratch,
                    size_t scratch_floats, hipStream_t s) {
     const int n_tiles = N / 16, groups = (n_tiles + 7) / 8;
-    // enough blocks to keep every CU streaming, at most 8 splits (the finishing kernel walks them one after the
-    // other), at least one chunk of k-tiles per block, partials within the scratch
-    int splits = std::max(1, std::min(std::min((512 + groups - 1) / groups, 8), k_tiles / SK_CH));
-    while (splits > 1 && (size_t)splits * T * N > scratch_floats) --splits;
-    const int per = ((k_tiles + splits - 1) / splits + SK_CH - 1) / SK_CH * SK_CH;
-    splits = (k_tiles + per - 1) / per;
+    // Two blocks fit a CU (registers), 512 on the chip.  The number of splits (at most 8: the finishing kernel walks
+    // them one after the other; partials within the scratch) minimises rounds of blocks x chunks per block, the time
+    // of the launch in units of one chunk per block; on a tie the fewer splits (less partial-sum traffic) win.
+    const int chunks = (k_tiles + SK_CH - 1) / SK_CH;
+    const size_t part_floats = scratch_floats - 32;      // the last 32 floats of the scratch carry the rows' rstd
+    float *rstd = scratch + part_floats;
+    int splits = 1;
+    long best = -1;
+    for (int c = 1; c <= std::min(8, chunks); ++c) {
+        if (c > 1 && (size_t)c * T * N > part_floats) break;
+        const long cost = (long)((groups * c + 511) / 512) * ((chunks + c - 1) / c) * 16 + c;
+        if (best < 0 || cost < best) { best = cost; splits = c; }
+    }
     const int nb = T > 16 ? 2 : 1;
     const size_t lds = (size_t)2 * 16 * nb * SK_TOK_STRIDE;
     const dim3 grid(groups, splits);
@@ -529,13 +571,15 @@ void launch_splitk(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             raised = true;
         }
-        hipLaunchKernelGGL(decode_splitk_kernel<2>, grid, dim3(512), lds, s, Wp, Xa, n_tiles, k_tiles, T, per, scratch);
+        hipLaunchKernelGGL(decode_splitk_kernel<2>, grid, dim3(512), lds, s, Wp, Xa, n_tiles, k_tiles, T, scratch, e.ssq_in,
+                           e.ssq_units, e.norm_dim, e.eps, rstd);
     } else {
-        hipLaunchKernelGGL(decode_splitk_kernel<1>, grid, dim3(512), lds, s, Wp, Xa, n_tiles, k_tiles, T, per, scratch);
+        hipLaunchKernelGGL(decode_splitk_kernel<1>, grid, dim3(512), lds, s, Wp, Xa, n_tiles, k_tiles, T, scratch, e.ssq_in,
+                           e.ssq_units, e.norm_dim, e.eps, rstd);
     }
     const int n_units = n_tiles / UT, nbt = (T + 15) / 16;
     hipLaunchKernelGGL((decode_finish_kernel<MODE, UT>), dim3((n_units * nbt + 3) / 4), dim3(256), 0, s, scratch, splits, N, T,
-                       n_units, e);
+                       n_units, e, rstd);
 }
 }  // namespace
 
@@ -543,7 +587,7 @@ void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T,
                         size_t scratch_floats, hipStream_t s) {
     const int k_tiles = K / 32;
     // a few rows: one kernel, complete dot products per block; more: shared operand, split contraction
-    if (T > 2 && scratch != nullptr && scratch_floats >= (size_t)T * N && k_tiles >= SK_CH) {
+    if (T > 2 && scratch != nullptr && scratch_floats >= (size_t)T * N + 32 && k_tiles >= SK_CH) {
         switch (e.mode) {
             case DEC_RAW: launch_splitk<DEC_RAW, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s); break;
             case DEC_QKV: launch_splitk<DEC_QKV, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s); break;

@@ -156,3 +156,21 @@ def test_search_operators_match_the_oracle():
         memv = [float(v) for v in rng.choice([24e9, 48e9, 80e9, 160e9, 640e9], S)]
         L = int(rng.integers(S, 121))
         assert hx.sched_repartition_layers(L, memv) == sch.repartition_layers(L, memv)
+
+
+def test_scheduler_functions_reject_invalid_arguments():
+    import math
+    pool = {"count": [2], "m": [1e12], "c": [1e14], "mem": [80e9], "tp_alpha": [1e-5], "tp_beta": [1e11],
+            "pp_alpha": [[1e-5]], "pp_beta": [[1e10]]}
+    task = (4096, 12.0, 2, 1, 128, 32)
+    assert math.isnan(hx.sched_pipeline_layout(pool, task, [4, 0])[0])               # a stage without layers
+    assert math.isnan(hx.sched_pipeline_layout(dict(pool, count=[-1]), task, [4])[0])
+    assert math.isnan(hx.sched_pipeline_layout(dict(pool, count=[65]), task, [4])[0])
+    # three stages cannot be served by two GPUs: no assignment, not an error
+    assert hx.sched_pipeline_layout(pool, task, [2, 2, 2])[0] == math.inf
+    # nothing fits the memory
+    assert hx.sched_pipeline_layout(dict(pool, mem=[1e6]), task, [4])[0] == math.inf
+    with pytest.raises(ValueError):
+        hx.sched_repartition_layers(2, [1.0, 1.0, 1.0])                             # fewer layers than stages
+    with pytest.raises(ValueError):
+        hx.sched_repartition_layers(8, [1.0, 0.0])

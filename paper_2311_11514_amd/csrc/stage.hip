@@ -347,12 +347,13 @@ int pick_attn_split(const hexgen_stage *st, const hexgen_kv_cache *kv, int batch
     for (int i = 0; i < batch; ++i) mx = std::max(mx, kv->lens[i] + 1);
     const int n_t32 = (mx + 31) / 32;
     // Enough (sequence, kv head) pairs to fill the chip, or a context short enough that one block's eight waves walk it
-    // in a few steps: one block per pair.  Otherwise split the context, eight tiles (one per wave) to a block, so
-    // that the whole context is requested at once; the split costs each block a device-scope fence, which is why it
-    // is not used when there are many blocks anyway.
+    // in a few steps: one block per pair.  Otherwise the context is split: a block's time falls with the number of
+    // splits (one CU's load path delivers about 150 GB/s), while every block adds a device-scope fence whose cost
+    // grows with the number of blocks in the launch; the measured optimum sits near sqrt(4 tiles / pairs).
     const int pairs = batch * st->hkv_l;
     if (pairs >= 32 || n_t32 <= 48) return 1;
-    return std::min(kMaxAttnSplit, (n_t32 + 7) / 8);
+    const int s = (int)std::lround(std::sqrt(4.0 * n_t32 / pairs));
+    return std::max(2, std::min({s, 8, (n_t32 + 7) / 8}));
 }
 
 DecodeEpi epi_base(hexgen_stage *st, int mode) {

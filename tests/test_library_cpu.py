@@ -174,3 +174,47 @@ def test_scheduler_functions_reject_invalid_arguments():
         hx.sched_repartition_layers(2, [1.0, 1.0, 1.0])                             # fewer layers than stages
     with pytest.raises(ValueError):
         hx.sched_repartition_layers(8, [1.0, 0.0])
+
+
+def test_pipeline_layout_dp_at_sizes_enumeration_cannot_reach():
+    """Larger pools (4 types, up to 8 GPUs each, 6 stages): the returned layout is feasible, re-prices (with the
+    oracle's stage and hop costs) to the returned cost, and no randomly drawn feasible layout is cheaper."""
+    import math
+
+    import numpy as np
+
+    from oracle import sched_oracle as sch
+    rng = np.random.default_rng(23)
+    for trial in range(6):
+        nt = 4
+        pool = {"count": [int(rng.integers(2, 9)) for _ in range(nt)],
+                "m": list(rng.uniform(0.4e12, 6e12, nt)), "c": list(rng.uniform(60e12, 1500e12, nt)),
+                "mem": list(rng.choice([24e9, 48e9, 80e9, 192e9], nt)),
+                "tp_alpha": list(rng.uniform(2e-6, 20e-6, nt)), "tp_beta": list(rng.uniform(20e9, 400e9, nt)),
+                "pp_alpha": rng.uniform(5e-6, 200e-6, (nt, nt)).tolist(), "pp_beta": rng.uniform(1e9, 100e9, (nt, nt)).tolist()}
+        task = (8192, 12.75, 2, int(rng.integers(1, 5)), int(rng.integers(64, 1025)), int(rng.integers(1, 65)))
+        S = 6
+        layers = sch.repartition_layers(80, [1.0] * S)
+        cost, asg = hx.sched_pipeline_layout(pool, task, layers, False)
+        if cost == math.inf:
+            continue
+        used = [sum(n for k, n in asg if k == t) for t in range(nt)]
+        assert all(u <= c for u, c in zip(used, pool["count"]))
+        total = sum(sch.stage_cost(pool, task, layers[j], k, n) for j, (k, n) in enumerate(asg))
+        total += sum(sch.hop_cost(pool, task, asg[j][0], asg[j + 1][0]) for j in range(S - 1))
+        assert math.isclose(total, cost, rel_tol=1e-12)
+        for _ in range(200):
+            left = list(pool["count"])
+            cand = []
+            for j in range(S):
+                k = int(rng.integers(0, nt))
+                if left[k] == 0:
+                    break
+                n = int(rng.integers(1, left[k] + 1))
+                left[k] -= n
+                cand.append((k, n))
+            if len(cand) < S:
+                continue
+            c2 = sum(sch.stage_cost(pool, task, layers[j], k, n) for j, (k, n) in enumerate(cand))
+            c2 += sum(sch.hop_cost(pool, task, cand[j][0], cand[j + 1][0]) for j in range(S - 1))
+            assert c2 >= cost * (1 - 1e-12)

@@ -586,8 +586,12 @@ void launch_splitk(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T
 void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T, const DecodeEpi &e, float *scratch,
                         size_t scratch_floats, hipStream_t s) {
     const int k_tiles = K / 32;
-    // a few rows: one kernel, complete dot products per block; more: shared operand, split contraction
-    if (T > 2 && scratch != nullptr && scratch_floats >= (size_t)T * N + 32 && k_tiles >= SK_CH) {
+    // one or two rows: one kernel, complete dot products per block; more: shared operand, split contraction
+    // A small matrix (launch-bound) with a handful of rows is better off without the second kernel: each block then
+    // fetches the rows' operand pieces itself (an L2 read of T x K x 4 bytes per block, which is what limits this to
+    // few rows, fewer when the contraction is long), and needs enough k-tiles per wave to fill its request ring.
+    const bool small = (size_t)N * K * sizeof(bf16_t) <= ((size_t)72 << 20) && k_tiles >= 64 && T <= (K <= 4096 ? 8 : 4);
+    if (T > 2 && !small && scratch != nullptr && scratch_floats >= (size_t)T * N + 32 && k_tiles >= SK_CH) {
         switch (e.mode) {
             case DEC_RAW: launch_splitk<DEC_RAW, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s); break;
             case DEC_QKV: launch_splitk<DEC_QKV, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s); break;

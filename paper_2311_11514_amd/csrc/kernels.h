@@ -110,7 +110,10 @@ struct GemmEpi {
     bf16_t *u;                 // fragment tiles [T/16][F_l/32]
     int F_l;
 };
-void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, hipStream_t s);
+// `part` (device, part_floats floats, may be NULL): scratch for the fp32 partial tiles of a split contraction, which
+// short prompts use (few token tiles); without it the contraction is never split
+void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, float *part,
+                      size_t part_floats, hipStream_t s);
 // stage input rows -> h (optional), (x * g) in fragment tiles, sums of squares [H / 128][T]
 void launch_untile_h(const float *h_tiled, float *out, int T, int H, hipStream_t s);
 // force a tile configuration of the prefill GEMM (see launch_mode); false for an unknown code

@@ -37,175 +37,15 @@
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
-// Operand tiles travel HBM -> LDS with direct-to-LDS loads (no registers in between): a wave copies one
-// 1 KB fragment tile per instruction, lane l's 16 bytes landing at tile base + 16 l.  S stages of the k-loop
-// are resident; the wait before a step only covers that step's loads (vmcnt counts the rest).
-//
-// Block = WM x WT waves; each wave owns FM x FT tiles of 32 features x 32 tokens, so the block tile is
-// (32 FM WM) features x (32 FT WT) tokens.
-template <int FM, int FT, int WM, int WT, int S, int MODE>
-__global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *__restrict__ Wp,
-                                                                 const bf16_t *__restrict__ Xp, int N, int k_tiles,
-                                                                 int n_tiles, int t_tiles, int T, int n_blocks,
-                                                                 int t_blocks, GemmEpi e) {
-    constexpr int NW = WM * WT, NT = 64 * NW;
-    constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT;   // 16-row operand tiles per block and k-step
-    constexpr int LA = TA / NW, LB = TB / NW;         // direct-to-LDS loads per wave and stage, per operand
-    constexpr int LPT = LA + LB;
-    constexpr int STAGE = (TA + TB) * 64;            // bf16x8 elements per stage
-    constexpr int NTOK = TB * 16;                    // token columns of the block tile
-    static_assert(TA % NW == 0 && TB % NW == 0, "operand tiles must divide evenly over the waves");
-    extern __shared__ bf16x8 smem[];                 // [S][TA + TB][64], then NTOK floats
-    float *rstd_s = reinterpret_cast<float *>(smem + (size_t)S * STAGE);
-    // XCD-aware remap of the linear block id
-    const int total = n_blocks * t_blocks;
-    int id = blockIdx.x;
-    const int per_xcd = (total + 7) / 8;
-    id = (id & 7) * per_xcd + (id >> 3);
-    if (id >= total) return;                     // only when total is not a multiple of 8
-    const int bm = id / t_blocks, bt = id - bm * t_blocks;
-    // the wave index is made provably uniform: tile addresses and LDS destinations then stay in scalar registers
-    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int wm = wave % WM, wt = wave / WM;
-
-    floatx16 acc[FM][FT];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FT; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    const bf16x8 *A = reinterpret_cast<const bf16x8 *>(Wp);
-    const bf16x8 *B = reinterpret_cast<const bf16x8 *>(Xp);
-    // this wave copies tiles wave, wave + NW, ... of both operands; out-of-range tiles are clamped to the last
-    // valid tile (their products are never stored) so that every wave issues LPT loads per stage.  Tile bases
-    // are uniform (scalar registers); the lane adds its 16-byte slot as a 32-bit offset.
-    const bf16x8 *asrc[LA], *bsrc[LB];
-#pragma unroll
-    for (int i = 0; i < LA; ++i) asrc[i] = A + (size_t)min(bm * TA + wave + NW * i, n_tiles - 1) * 64;
-#pragma unroll
-    for (int i = 0; i < LB; ++i) bsrc[i] = B + (size_t)min(bt * TB + wave + NW * i, t_tiles - 1) * k_tiles * 64;
-    const size_t astep = (size_t)n_tiles * 64;       // k-tile-major weights
-    // One direct-to-LDS load: index x < LA is a weight tile, the rest are activation tiles.  k-steps past
-    // the end are clamped to the last one (they land in a buffer nobody reads any more), so that every
-    // k-step issues exactly LPT loads and the loop body stays one basic block.
-    // One direct-to-LDS load of a 1 KB tile: index x < LA is a weight tile, the rest are activation tiles.
-    // k-steps past the end are clamped to the last one (they land in a buffer nobody reads any more), so that
-    // every k-step issues exactly LPT loads and the loop body stays one basic block.  The load is written in
-    // its scalar-base form (tile address in scalar registers, the lane's 16-byte slot as the 32-bit vector
-    // offset, LDS destination in M0), which the compiler does not select for this instruction by itself: it
-    // would spend a 64-bit vector add per load inside the MFMA stream.  The compiler does not see these
-    // loads in its own vmcnt bookkeeping; every wait on them is explicit (HX_WAIT_VM), and vmcnt is drained
-    // before the epilogue issues ordinary loads.
-    const unsigned lane_bytes = (unsigned)lane * 16u;
-    auto issue_one = [&](int kt, int x) {
-        const int kc = min(kt, k_tiles - 1);
-        bf16x8 *st = smem + (size_t)(kt % S) * STAGE;
-        const bf16x8 *src = x < LA ? asrc[x] + kc * astep : bsrc[x - LA] + (size_t)kc * 64;
-        bf16x8 *dst = x < LA ? st + (wave + NW * x) * 64 : st + (TA + wave + NW * (x - LA)) * 64;
-        const unsigned lds_addr = (unsigned)reinterpret_cast<uintptr_t>(HX_AS3(dst));
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                     :
-                     : "s"(lds_addr), "v"(lane_bytes), "s"(src)
-                     : "memory");
-    };
-    // 32x32x16 operand for k-half kh of a pair of 16-row tiles: lane l takes row l % 32, k-group 2 kh + l / 32
-    const int frag = ((lane & 31) >> 4) * 64 + (lane & 15) + 16 * (lane >> 5);
-    // Software pipeline.  (1) The operand registers of one 16-deep half step are fetched from LDS while the
-    // MFMAs of the previous half step run.  (2) The barrier sits in the MIDDLE of a k-step: it publishes stage
-    // kt + 1, whose first half is then fetched under the second half of stage kt, and frees the buffer of
-    // stage kt - 1.  (3) The loads of stage kt + S - 1 into that buffer are spread over one whole step, half
-    // behind the barrier of step kt and half in front of the barrier of step kt + 1, one load every few MFMAs.
-    constexpr int H1 = (LPT + 1) / 2, H2 = LPT / 2;  // loads issued behind / in front of the barrier
-    constexpr int HL = H1;
-    // MFMA slots of a half step: the first FM + FT also carry an LDS fetch; the loads go behind them when
-    // there is room, else they are spread over all slots
-    constexpr int FREE = FM * FT - (FM + FT);
-    constexpr int LOAD0 = FREE >= HL ? FM + FT : 0;
-    constexpr int GAP = FREE >= HL ? FREE / HL : ((FM * FT) / HL > 0 ? (FM * FT) / HL : 1);
-    static_assert(S >= 3, "the pipeline needs three stages");
-#pragma unroll
-    for (int p = 0; p < S - 2; ++p)
-#pragma unroll
-        for (int x = 0; x < LPT; ++x) issue_one(p, x);
-#pragma unroll
-    for (int x = 0; x < H1; ++x) issue_one(S - 2, x);
-    // 1 / rms of the block's token columns from the producer's partial sums of squares, once per block (the
-    // values are the youngest loads in flight: the compiler's wait for them also covers the stages above)
-    if (MODE != DEC_RESID && e.ssq_in != nullptr) {
-        const int groups = e.norm_dim / GEMM_SSQ_COLS;
-        for (int t = tid; t < NTOK; t += NT) {
-            const int token = bt * NTOK + t;
-            float ss = 0.f;
-            if (token < T) {
-#pragma unroll 16
-                for (int gI = 0; gI < groups; ++gI) ss += e.ssq_in[(size_t)gI * T + token];
-            }
-            rstd_s[t] = 1.0f / sqrtf(ss / (float)e.norm_dim + e.eps);
-        }
-    }
-    bf16x8 fa0[FM], fb0[FT], fa1[FM], fb1[FT];
-    // x-th operand fetch of a half step: the FT token operands first, then the FM feature operands
-    auto fetch_one = [&](bf16x8(&fa)[FM], bf16x8(&fb)[FT], int kt, int kh, int x) {
-        const bf16x8 *sa = smem + (size_t)(kt % S) * STAGE + (wm * FM * 2) * 64 + frag + kh * 32;
-        const bf16x8 *sb = smem + (size_t)(kt % S) * STAGE + (TA + wt * FT * 2) * 64 + frag + kh * 32;
-        if (x < FT) fb[x] = sb[x * 128];
-        else fa[x - FT] = sa[(x - FT) * 128];
-    };
-    auto fetch = [&](bf16x8(&fa)[FM], bf16x8(&fb)[FT], int kt, int kh) {
-#pragma unroll
-        for (int x = 0; x < FM + FT; ++x) fetch_one(fa, fb, kt, kh, x);
-    };
-    static_assert(FM + FT <= FM * FT, "one operand fetch per MFMA slot");
-    HX_WAIT_VM((S - 3) * LPT + H1);
-    HX_LDS_BARRIER();
-    fetch(fa0, fb0, 0, 0);
-    HX_WAIT_LGKM0();
-    // The memory pipeline of a CU accepts one wave-wide 1 KB load every ~26 cycles and hardly queues: waves
-    // that issue their loads at the same point of the (lock-stepped) MFMA stream block each other for tens of
-    // cycles with the matrix core idle.  Each wave therefore runs a copy of the loop whose loads sit OFF
-    // MFMAs later than its neighbour's, which gives the CU one load per MFMA slot.
-    auto k_loop = [&](auto off_c) {
-        constexpr int OFF = decltype(off_c)::value;
-    for (int kt = 0; kt < k_tiles; ++kt) {
-        // one slot = one MFMA, at most one LDS fetch for the NEXT half step and at most one global load; the
-        // slots are fenced so that the order below is the order in the instruction stream
-#pragma unroll
-        for (int m = 0; m < FM * FT; ++m) {
-            acc[m / FT][m % FT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[m / FT], fb0[m % FT], acc[m / FT][m % FT], 0, 0, 0);
-            if (m < FM + FT) fetch_one(fa1, fb1, kt, 1, m);
-            if (m >= LOAD0 && (m - LOAD0) % GAP == OFF && (m - LOAD0) / GAP < H2) issue_one(kt + S - 2, H1 + (m - LOAD0) / GAP);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        HX_WAIT_VM((S - 3) * LPT);      // stage kt + 1 has landed; later stages stay in flight
-        HX_LDS_BARRIER();
-#pragma unroll
-        for (int m = 0; m < FM * FT; ++m) {
-            acc[m / FT][m % FT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[m / FT], fb1[m % FT], acc[m / FT][m % FT], 0, 0, 0);
-            if (m < FM + FT) fetch_one(fa0, fb0, kt + 1, 0, m);
-            if (m >= LOAD0 && (m - LOAD0) % GAP == OFF && (m - LOAD0) / GAP < H1) issue_one(kt + S - 1, (m - LOAD0) / GAP);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // the fetch of the next half step has had FM FT MFMAs to complete: waiting here, instead of where
-        // the compiler would place it (behind the next fetch), costs nothing and keeps that fetch covered
-        __builtin_amdgcn_sched_barrier(0);
-        HX_WAIT_LGKM0();
-    }
-    };
-    {
-        const int off = (wave * GAP) / NW;
-        if (GAP > 3 && off == 3) k_loop(std::integral_constant<int, (GAP > 3 ? 3 : 0)>{});
-        else if (GAP > 2 && off == 2) k_loop(std::integral_constant<int, (GAP > 2 ? 2 : 0)>{});
-        else if (GAP > 1 && off == 1) k_loop(std::integral_constant<int, (GAP > 1 ? 1 : 0)>{});
-        else k_loop(std::integral_constant<int, 0>{});
-    }
-    HX_WAIT_VM(0);
-    // ---- epilogue, in registers.  32 x 32 result: lane l holds token column l % 32 and, per register quad q,
-    // features 8 q + 4 (l / 32) .. + 3 of the 32-feature block, i.e. of the 16-row tile q / 2 its rows
-    // (q % 2) * 8 + 4 (l / 32) .. + 3.  Rotary pairs (tile rows r, r + 8) and gate / up pairs (tiles 2m, 2m + 1)
-    // therefore sit in the same lane, in quads q and q ^ 1 respectively q and q + 2: no cross-lane traffic.
+// ---- epilogue, in registers.  32 x 32 result: lane l holds token column l % 32 and, per register quad q,
+// features 8 q + 4 (l / 32) .. + 3 of the 32-feature block, i.e. of the 16-row tile q / 2 its rows
+// (q % 2) * 8 + 4 (l / 32) .. + 3.  Rotary pairs (tile rows r, r + 8) and gate / up pairs (tiles 2m, 2m + 1)
+// therefore sit in the same lane, in quads q and q ^ 1 respectively q and q + 2: no cross-lane traffic.
+// acc: the wave's FM x FT result tiles of block (bm, bt), wave (wm, wt); rstd_s: 1 / rms of the block's token columns.
+template <int FM, int FT, int WM, int WT, int MODE>
+__device__ __forceinline__ void gemm_epilogue(const floatx16 (&acc)[FM][FT], int bm, int bt, int wm, int wt, int lane, int N,
+                                              int n_tiles, int T, const GemmEpi &e, const float *rstd_s) {
+    constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT, NTOK = TB * 16;
     const int hl = lane >> 5;
     if (MODE == DEC_RESID) {
         // Residual read-modify-write.  Walks the wave tile one 32-feature block (i) at a time and fetches the
@@ -372,9 +212,241 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
     }
 }
 
+// Operand tiles travel HBM -> LDS with direct-to-LDS loads (no registers in between): a wave copies one
+// 1 KB fragment tile per instruction, lane l's 16 bytes landing at tile base + 16 l.  S stages of the k-loop
+// are resident; the wait before a step only covers that step's loads (vmcnt counts the rest).
+//
+// Block = WM x WT waves; each wave owns FM x FT tiles of 32 features x 32 tokens, so the block tile is
+// (32 FM WM) features x (32 FT WT) tokens.
+template <int FM, int FT, int WM, int WT, int S, int MODE>
+__global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *__restrict__ Wp,
+                                                                 const bf16_t *__restrict__ Xp, int N, int k_tiles,
+                                                                 int n_tiles, int t_tiles, int T, int n_blocks,
+                                                                 int t_blocks, GemmEpi e, float *__restrict__ part) {
+    constexpr int NW = WM * WT, NT = 64 * NW;
+    constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT;   // 16-row operand tiles per block and k-step
+    constexpr int LA = TA / NW, LB = TB / NW;         // direct-to-LDS loads per wave and stage, per operand
+    constexpr int LPT = LA + LB;
+    constexpr int STAGE = (TA + TB) * 64;            // bf16x8 elements per stage
+    constexpr int NTOK = TB * 16;                    // token columns of the block tile
+    static_assert(TA % NW == 0 && TB % NW == 0, "operand tiles must divide evenly over the waves");
+    extern __shared__ bf16x8 smem[];                 // [S][TA + TB][64], then NTOK floats
+    float *rstd_s = reinterpret_cast<float *>(smem + (size_t)S * STAGE);
+    // XCD-aware remap of the linear block id
+    const int total = n_blocks * t_blocks;
+    int id = blockIdx.x;
+    const int per_xcd = (total + 7) / 8;
+    id = (id & 7) * per_xcd + (id >> 3);
+    if (id >= total) return;                     // only when total is not a multiple of 8
+    const int bm = id / t_blocks, bt = id - bm * t_blocks;
+    // the wave index is made provably uniform: tile addresses and LDS destinations then stay in scalar registers
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int wm = wave % WM, wt = wave / WM;
+    // split contraction (few token tiles, see launch_cfg): blockIdx.y takes k-steps [k0, k0 + k_len) and leaves its
+    // fp32 result tiles in `part`; gemm_finish_kernel adds the splits up and runs the epilogue
+    const int k0 = (int)((long)blockIdx.y * k_tiles / gridDim.y);
+    const int k_len = (int)((long)(blockIdx.y + 1) * k_tiles / gridDim.y) - k0;
+
+    floatx16 acc[FM][FT];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const bf16x8 *A = reinterpret_cast<const bf16x8 *>(Wp);
+    const bf16x8 *B = reinterpret_cast<const bf16x8 *>(Xp);
+    // this wave copies tiles wave, wave + NW, ... of both operands; out-of-range tiles are clamped to the last
+    // valid tile (their products are never stored) so that every wave issues LPT loads per stage.  Tile bases
+    // are uniform (scalar registers); the lane adds its 16-byte slot as a 32-bit offset.
+    const bf16x8 *asrc[LA], *bsrc[LB];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) asrc[i] = A + (size_t)min(bm * TA + wave + NW * i, n_tiles - 1) * 64 + (size_t)k0 * n_tiles * 64;
+#pragma unroll
+    for (int i = 0; i < LB; ++i) bsrc[i] = B + ((size_t)min(bt * TB + wave + NW * i, t_tiles - 1) * k_tiles + k0) * 64;
+    const size_t astep = (size_t)n_tiles * 64;       // k-tile-major weights
+    // One direct-to-LDS load: index x < LA is a weight tile, the rest are activation tiles.  k-steps past
+    // the end are clamped to the last one (they land in a buffer nobody reads any more), so that every
+    // k-step issues exactly LPT loads and the loop body stays one basic block.
+    // One direct-to-LDS load of a 1 KB tile: index x < LA is a weight tile, the rest are activation tiles.
+    // k-steps past the end are clamped to the last one (they land in a buffer nobody reads any more), so that
+    // every k-step issues exactly LPT loads and the loop body stays one basic block.  The load is written in
+    // its scalar-base form (tile address in scalar registers, the lane's 16-byte slot as the 32-bit vector
+    // offset, LDS destination in M0), which the compiler does not select for this instruction by itself: it
+    // would spend a 64-bit vector add per load inside the MFMA stream.  The compiler does not see these
+    // loads in its own vmcnt bookkeeping; every wait on them is explicit (HX_WAIT_VM), and vmcnt is drained
+    // before the epilogue issues ordinary loads.
+    const unsigned lane_bytes = (unsigned)lane * 16u;
+    auto issue_one = [&](int kt, int x) {
+        const int kc = min(kt, k_len - 1);
+        bf16x8 *st = smem + (size_t)(kt % S) * STAGE;
+        const bf16x8 *src = x < LA ? asrc[x] + kc * astep : bsrc[x - LA] + (size_t)kc * 64;
+        bf16x8 *dst = x < LA ? st + (wave + NW * x) * 64 : st + (TA + wave + NW * (x - LA)) * 64;
+        const unsigned lds_addr = (unsigned)reinterpret_cast<uintptr_t>(HX_AS3(dst));
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :
+                     : "s"(lds_addr), "v"(lane_bytes), "s"(src)
+                     : "memory");
+    };
+    // 32x32x16 operand for k-half kh of a pair of 16-row tiles: lane l takes row l % 32, k-group 2 kh + l / 32
+    const int frag = ((lane & 31) >> 4) * 64 + (lane & 15) + 16 * (lane >> 5);
+    // Software pipeline.  (1) The operand registers of one 16-deep half step are fetched from LDS while the
+    // MFMAs of the previous half step run.  (2) The barrier sits in the MIDDLE of a k-step: it publishes stage
+    // kt + 1, whose first half is then fetched under the second half of stage kt, and frees the buffer of
+    // stage kt - 1.  (3) The loads of stage kt + S - 1 into that buffer are spread over one whole step, half
+    // behind the barrier of step kt and half in front of the barrier of step kt + 1, one load every few MFMAs.
+    constexpr int H1 = (LPT + 1) / 2, H2 = LPT / 2;  // loads issued behind / in front of the barrier
+    constexpr int HL = H1;
+    // MFMA slots of a half step: the first FM + FT also carry an LDS fetch; the loads go behind them when
+    // there is room, else they are spread over all slots
+    constexpr int FREE = FM * FT - (FM + FT);
+    constexpr int LOAD0 = FREE >= HL ? FM + FT : 0;
+    constexpr int GAP = FREE >= HL ? FREE / HL : ((FM * FT) / HL > 0 ? (FM * FT) / HL : 1);
+    static_assert(S >= 3, "the pipeline needs three stages");
+#pragma unroll
+    for (int p = 0; p < S - 2; ++p)
+#pragma unroll
+        for (int x = 0; x < LPT; ++x) issue_one(p, x);
+#pragma unroll
+    for (int x = 0; x < H1; ++x) issue_one(S - 2, x);
+    // 1 / rms of the block's token columns from the producer's partial sums of squares, once per block (the
+    // values are the youngest loads in flight: the compiler's wait for them also covers the stages above)
+    if (MODE != DEC_RESID && e.ssq_in != nullptr && part == nullptr) {
+        const int groups = e.norm_dim / GEMM_SSQ_COLS;
+        for (int t = tid; t < NTOK; t += NT) {
+            const int token = bt * NTOK + t;
+            float ss = 0.f;
+            if (token < T) {
+#pragma unroll 16
+                for (int gI = 0; gI < groups; ++gI) ss += e.ssq_in[(size_t)gI * T + token];
+            }
+            rstd_s[t] = 1.0f / sqrtf(ss / (float)e.norm_dim + e.eps);
+        }
+    }
+    bf16x8 fa0[FM], fb0[FT], fa1[FM], fb1[FT];
+    // x-th operand fetch of a half step: the FT token operands first, then the FM feature operands
+    auto fetch_one = [&](bf16x8(&fa)[FM], bf16x8(&fb)[FT], int kt, int kh, int x) {
+        const bf16x8 *sa = smem + (size_t)(kt % S) * STAGE + (wm * FM * 2) * 64 + frag + kh * 32;
+        const bf16x8 *sb = smem + (size_t)(kt % S) * STAGE + (TA + wt * FT * 2) * 64 + frag + kh * 32;
+        if (x < FT) fb[x] = sb[x * 128];
+        else fa[x - FT] = sa[(x - FT) * 128];
+    };
+    auto fetch = [&](bf16x8(&fa)[FM], bf16x8(&fb)[FT], int kt, int kh) {
+#pragma unroll
+        for (int x = 0; x < FM + FT; ++x) fetch_one(fa, fb, kt, kh, x);
+    };
+    static_assert(FM + FT <= FM * FT, "one operand fetch per MFMA slot");
+    HX_WAIT_VM((S - 3) * LPT + H1);
+    HX_LDS_BARRIER();
+    fetch(fa0, fb0, 0, 0);
+    HX_WAIT_LGKM0();
+    // The memory pipeline of a CU accepts one wave-wide 1 KB load every ~26 cycles and hardly queues: waves
+    // that issue their loads at the same point of the (lock-stepped) MFMA stream block each other for tens of
+    // cycles with the matrix core idle.  Each wave therefore runs a copy of the loop whose loads sit OFF
+    // MFMAs later than its neighbour's, which gives the CU one load per MFMA slot.
+    auto k_loop = [&](auto off_c) {
+        constexpr int OFF = decltype(off_c)::value;
+    for (int kt = 0; kt < k_len; ++kt) {
+        // one slot = one MFMA, at most one LDS fetch for the NEXT half step and at most one global load; the
+        // slots are fenced so that the order below is the order in the instruction stream
+#pragma unroll
+        for (int m = 0; m < FM * FT; ++m) {
+            acc[m / FT][m % FT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[m / FT], fb0[m % FT], acc[m / FT][m % FT], 0, 0, 0);
+            if (m < FM + FT) fetch_one(fa1, fb1, kt, 1, m);
+            if (m >= LOAD0 && (m - LOAD0) % GAP == OFF && (m - LOAD0) / GAP < H2) issue_one(kt + S - 2, H1 + (m - LOAD0) / GAP);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        HX_WAIT_VM((S - 3) * LPT);      // stage kt + 1 has landed; later stages stay in flight
+        HX_LDS_BARRIER();
+#pragma unroll
+        for (int m = 0; m < FM * FT; ++m) {
+            acc[m / FT][m % FT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[m / FT], fb1[m % FT], acc[m / FT][m % FT], 0, 0, 0);
+            if (m < FM + FT) fetch_one(fa0, fb0, kt + 1, 0, m);
+            if (m >= LOAD0 && (m - LOAD0) % GAP == OFF && (m - LOAD0) / GAP < H1) issue_one(kt + S - 1, (m - LOAD0) / GAP);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // the fetch of the next half step has had FM FT MFMAs to complete: waiting here, instead of where
+        // the compiler would place it (behind the next fetch), costs nothing and keeps that fetch covered
+        __builtin_amdgcn_sched_barrier(0);
+        HX_WAIT_LGKM0();
+    }
+    };
+    {
+        const int off = (wave * GAP) / NW;
+        if (GAP > 3 && off == 3) k_loop(std::integral_constant<int, (GAP > 3 ? 3 : 0)>{});
+        else if (GAP > 2 && off == 2) k_loop(std::integral_constant<int, (GAP > 2 ? 2 : 0)>{});
+        else if (GAP > 1 && off == 1) k_loop(std::integral_constant<int, (GAP > 1 ? 1 : 0)>{});
+        else k_loop(std::integral_constant<int, 0>{});
+    }
+    HX_WAIT_VM(0);
+    if (part != nullptr) {
+        // result tiles as they sit in the registers: per tile 4 quads x 64 lanes x 4 floats, 1 KB per store
+        float *dst = part + ((((size_t)blockIdx.y * total + id) * NW + wave) * (FM * FT)) * 1024 + lane * 4;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FT; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<floatx4 *>(dst + (i * FT + j) * 1024 + q * 256) =
+                        floatx4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        return;
+    }
+    gemm_epilogue<FM, FT, WM, WT, MODE>(acc, bm, bt, wm, wt, lane, N, n_tiles, T, e, rstd_s);
+}
+
+// Second pass of a split contraction: block `id` (the same tile and wave layout as gemm_mfma_kernel) adds its result
+// tiles up over the splits, in split order, and runs the epilogue.
+template <int FM, int FT, int WM, int WT, int MODE>
+__global__ __launch_bounds__(64 * WM * WT) void gemm_finish_kernel(const float *__restrict__ part, int splits, int N,
+                                                                   int n_tiles, int T, int total, int t_blocks, GemmEpi e) {
+    constexpr int NW = WM * WT, NT = 64 * NW, TB = 2 * FT * WT, NTOK = TB * 16;
+    __shared__ float rstd_s[NTOK];
+    const int id = blockIdx.x;
+    const int bm = id / t_blocks, bt = id - bm * t_blocks;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int wm = wave % WM, wt = wave / WM;
+    if (MODE != DEC_RESID && e.ssq_in != nullptr) {
+        const int groups = e.norm_dim / GEMM_SSQ_COLS;
+        for (int t = tid; t < NTOK; t += NT) {
+            const int token = bt * NTOK + t;
+            float ss = 0.f;
+            if (token < T) {
+#pragma unroll 16
+                for (int gI = 0; gI < groups; ++gI) ss += e.ssq_in[(size_t)gI * T + token];
+            }
+            rstd_s[t] = 1.0f / sqrtf(ss / (float)e.norm_dim + e.eps);
+        }
+    }
+    floatx16 acc[FM][FT];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    for (int z = 0; z < splits; ++z) {
+        const float *src = part + ((((size_t)z * total + id) * NW + wave) * (FM * FT)) * 1024 + lane * 4;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FT; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const floatx4 v = *reinterpret_cast<const floatx4 *>(src + (i * FT + j) * 1024 + q * 256);
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) acc[i][j][4 * q + x] += v[x];
+                }
+    }
+    __syncthreads();
+    gemm_epilogue<FM, FT, WM, WT, MODE>(acc, bm, bt, wm, wt, lane, N, n_tiles, T, e, rstd_s);
+}
+
 template <int FM, int FT, int WM, int WT, int S, int MODE>
 static void launch_cfg(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles, int n_tiles, int t_tiles, int T,
-                       const GemmEpi &e, hipStream_t s) {
+                       const GemmEpi &e, float *part, size_t part_floats, hipStream_t s) {
     constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT;
     const int n_blocks = (n_tiles + TA - 1) / TA, t_blocks = (t_tiles + TB - 1) / TB;
     const int total = n_blocks * t_blocks;
@@ -387,8 +459,21 @@ static void launch_cfg(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles, i
                                   (int)dyn);
         raised = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WT), dyn, s, Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, n_blocks,
-                       t_blocks, e);
+    // A short prompt gives few tiles, each walking the whole contraction while most of the chip idles and the weights
+    // arrive at a fraction of the HBM rate: the contraction is then split over blockIdx.y (at most 8 ways, at least
+    // 16 k-steps each, partials within the scratch) until the chip holds as many blocks as it can.
+    int splits = 1;
+    const size_t tile_floats = (size_t)64 * WM * WT * FM * FT * 16;
+    const int resident = dyn <= 72 * 1024 ? 512 : 256;       // blocks the chip holds at once (LDS: two per CU or one)
+    if (part != nullptr && 2 * total <= resident && k_tiles >= 32) {
+        splits = std::max(1, std::min({8, resident / total, k_tiles / 16}));
+        while (splits > 1 && (size_t)splits * total * tile_floats > part_floats) --splits;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid, splits), dim3(64 * WM * WT), dyn, s, Wp, Xp, N, k_tiles, n_tiles, t_tiles, T,
+                       n_blocks, t_blocks, e, splits > 1 ? part : nullptr);
+    if (splits > 1)
+        hipLaunchKernelGGL((gemm_finish_kernel<FM, FT, WM, WT, MODE>), dim3(total), dim3(64 * WM * WT), 0, s, part, splits, N,
+                           n_tiles, T, total, t_blocks, e);
 }
 
 // tile configuration forced for every GEMM launch of the process (0 = choose by shape); a measurement and test hook
@@ -400,7 +485,8 @@ bool set_gemm_tile(int code) {
 }
 
 template <int MODE>
-static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, hipStream_t s) {
+static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, float *part,
+                        size_t part_floats, hipStream_t s) {
     const int k_tiles = K / 32, n_tiles = N / 16, t_tiles = (T + 15) / 16;
     const int force = g_force_tile.load(std::memory_order_relaxed);
     // tiles of 256 x 256 once they fill the chip; smaller tiles for small problems
@@ -409,12 +495,17 @@ static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T,
     if (force) cfg = force;
     // the RESID epilogue emits one sum-of-squares partial per wave: its 32 FM features must be 128
     if (MODE == DEC_RESID && cfg != 88 && cfg != 84 && cfg != 98) cfg = 84;
-#define HX_G(FM, FT, WM, WT, S) launch_cfg<FM, FT, WM, WT, S, MODE>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, s)
+    // one 128-token tile (a short prompt): 128-token block tiles; the split contraction then runs a short k-loop per
+    // block with the weights coming from HBM, so the 256 x 128 tile of RESID keeps six stages in flight instead of four
+    const bool short_prompt = !force && t_tiles <= 8;
+    if (short_prompt) cfg = MODE == DEC_RESID ? 846 : 44;
+#define HX_G(FM, FT, WM, WT, S) launch_cfg<FM, FT, WM, WT, S, MODE>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s)
     if (cfg == 88) HX_G(4, 4, 2, 2, 4);
     else if (cfg == 98) HX_G(4, 2, 2, 4, 4);
     else if (cfg == 94) { if constexpr (MODE != DEC_RESID) HX_G(2, 2, 2, 4, 4); }
     else if (cfg == 49) { if constexpr (MODE != DEC_RESID) HX_G(2, 2, 4, 2, 4); }
     else if (cfg == 84) HX_G(4, 2, 2, 2, 4);
+    else if (cfg == 846) { if constexpr (MODE == DEC_RESID) HX_G(4, 2, 2, 2, 6); }
     else if (cfg == 48) {
         if constexpr (MODE != DEC_RESID) HX_G(2, 4, 2, 2, 4);
     } else {
@@ -423,12 +514,13 @@ static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T,
 #undef HX_G
 }
 
-void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, hipStream_t s) {
+void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, float *part,
+                      size_t part_floats, hipStream_t s) {
     switch (e.mode) {
-        case DEC_RAW: launch_mode<DEC_RAW>(Wp, Xp, N, K, T, e, s); break;
-        case DEC_QKV: launch_mode<DEC_QKV>(Wp, Xp, N, K, T, e, s); break;
-        case DEC_RESID: launch_mode<DEC_RESID>(Wp, Xp, N, K, T, e, s); break;
-        case DEC_SWIGLU: launch_mode<DEC_SWIGLU>(Wp, Xp, N, K, T, e, s); break;
+        case DEC_RAW: launch_mode<DEC_RAW>(Wp, Xp, N, K, T, e, part, part_floats, s); break;
+        case DEC_QKV: launch_mode<DEC_QKV>(Wp, Xp, N, K, T, e, part, part_floats, s); break;
+        case DEC_RESID: launch_mode<DEC_RESID>(Wp, Xp, N, K, T, e, part, part_floats, s); break;
+        case DEC_SWIGLU: launch_mode<DEC_SWIGLU>(Wp, Xp, N, K, T, e, part, part_floats, s); break;
     }
 }
 

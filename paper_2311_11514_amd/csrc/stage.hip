@@ -70,6 +70,8 @@ struct Workspace {
     bf16_t *n = nullptr, *o = nullptr, *u = nullptr, *q = nullptr;
     float *dec_part = nullptr;       // split partial sums of the batched decode projections
     size_t dec_part_floats = 0;
+    float *gemm_part = nullptr;      // fp32 partial tiles of a split prefill contraction (short prompts)
+    size_t gemm_part_floats = 0;
     bf16_t *xa_n = nullptr, *xa_o = nullptr, *xa_u = nullptr;   // decode operands, compact hi/lo layout [32][K][2]
     bf16_t *q_lo = nullptr;
     float *att_o = nullptr, *att_ml = nullptr;
@@ -119,7 +121,7 @@ namespace {
 size_t esize(hexgen_dtype_t dt) { return dt == HEXGEN_F32 ? 4 : 2; }
 
 void free_ws(Workspace &w) {
-    void *ptrs[] = {w.dec_part, w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.xa_n, w.xa_o, w.xa_u, w.q_lo, w.ssq, w.ssq_pf, w.att_o, w.att_ml, w.att_arrived, w.n32, w.q32, w.o32, w.u32,
+    void *ptrs[] = {w.dec_part, w.gemm_part, w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.xa_n, w.xa_o, w.xa_u, w.q_lo, w.ssq, w.ssq_pf, w.att_o, w.att_ml, w.att_arrived, w.n32, w.q32, w.o32, w.u32,
                     w.rowmap};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
@@ -165,6 +167,8 @@ hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
             w.dec_part_floats = drows * ((size_t)512 * 128 + 2 * nmax);
             HX_TRY(dmalloc(&w.dec_part, w.dec_part_floats));
         }
+        w.gemm_part_floats = (size_t)16 << 20;      // 64 MB: 8 splits of the widest short-prompt launch
+        HX_TRY(dmalloc(&w.gemm_part, w.gemm_part_floats));
         HX_TRY(dmalloc(&w.att_o, drows * st->hq_l * kMaxAttnSplit * st->d));
         HX_TRY(dmalloc(&w.att_ml, drows * st->hq_l * kMaxAttnSplit * 2));
         HX_TRY(dmalloc(&w.att_arrived, drows * st->hkv_l));
@@ -272,7 +276,7 @@ GemmEpi gemm_epi_base(hexgen_stage *st, int mode) {
 void gemm_bf16(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xp, int N, int K, const GemmEpi &e,
                int slot, hipStream_t s) {
     st->prof.mark(slot, s);
-    launch_gemm_mfma(static_cast<const bf16_t *>(Wp), Xp, N, K, r.T, e, s);
+    launch_gemm_mfma(static_cast<const bf16_t *>(Wp), Xp, N, K, r.T, e, st->ws.gemm_part, st->ws.gemm_part_floats, s);
     st->prof.mark(slot, s);
 }
 

@@ -109,8 +109,10 @@ def test_tiny_f32_group_mode_greedy_tokens():
     assert toks_g == toks_o
 
 
-@pytest.mark.parametrize("cfg,lens", [(MINI128, [37, 5, 64]), (MINI64, [16, 33])])
+@pytest.mark.parametrize("cfg,lens", [(MINI128, [37, 5, 64]), (MINI64, [16, 33]), (MINI2K, [70]), (MINI2K, [100, 29, 150])])
 def test_bf16_small_prefill_then_decode(cfg, lens):
+    """Short prompts: few token tiles, so the projections with at least 32 k-tiles split their contraction over
+    several blocks and finish in a second pass (2 splits on MINI128, up to 5 on MINI2K); MINI64 does not split."""
     w = _weights(cfg)
     rank = cfg.tp_ranks[0]
     X = generate.hidden_rows(cfg, sum(lens))
@@ -118,7 +120,7 @@ def test_bf16_small_prefill_then_decode(cfg, lens):
     oc = ora.new_cache(len(lens))
     p_ref, h_ref = ora.prefill(oc, X, lens)
     st = make_gpu_stage(cfg, rank, w)
-    kv = st.kv_cache_create(len(lens), 128)
+    kv = st.kv_cache_create(len(lens), max(lens) + 64)
     p, h = gpu_prefill(st, kv, cfg, X, lens)
     assert row_rel_err(h, h_ref) < TOL["bf16"]
     assert row_rel_err(p, p_ref) < TOL["bf16"]

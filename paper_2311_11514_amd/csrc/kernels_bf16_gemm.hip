@@ -44,7 +44,8 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 // acc: the wave's FM x FT result tiles of block (bm, bt), wave (wm, wt); rstd_s: 1 / rms of the block's token columns.
 template <int FM, int FT, int WM, int WT, int MODE>
 __device__ __forceinline__ void gemm_epilogue(const floatx16 (&acc)[FM][FT], int bm, int bt, int wm, int wt, int lane, int N,
-                                              int n_tiles, int T, const GemmEpi &e, const float *rstd_s) {
+                                              int n_tiles, int T, const GemmEpi &e, const float *rstd_s,
+                                              float *ssq_lds = nullptr) {
     constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT, NTOK = TB * 16;
     const int hl = lane >> 5;
     if (MODE == DEC_RESID) {
@@ -116,14 +117,33 @@ __device__ __forceinline__ void gemm_epilogue(const floatx16 (&acc)[FM][FT], int
             }
         }
         if (!e.last_layer) {
-            // sum of squares of this wave's 32 FM = 128 features of each token: the two lane halves hold
-            // disjoint rows
-            static_assert(MODE != DEC_RESID || 32 * FM == GEMM_SSQ_COLS, "one partial per wave and token");
-            const int grp = (bm * TA + wm * FM * 2) * 16 / GEMM_SSQ_COLS;
+            // sum of squares of each token over the 128 features of one partial: the two lane halves hold disjoint rows
+            static_assert(MODE != DEC_RESID || 32 * FM == GEMM_SSQ_COLS || (32 * FM * WM == GEMM_SSQ_COLS && WT == 1),
+                          "one partial per wave, or per block, and token");
+            if constexpr (32 * FM == GEMM_SSQ_COLS) {
+                const int grp = (bm * TA + wm * FM * 2) * 16 / GEMM_SSQ_COLS;
 #pragma unroll
-            for (int j = 0; j < FT; ++j) {
-                const float tot = ssq[j] + __shfl_xor(ssq[j], 32, 64);
-                if (hl == 0 && token[j] < T) e.ssq_out[(size_t)grp * T + token[j]] = tot;
+                for (int j = 0; j < FT; ++j) {
+                    const float tot = ssq[j] + __shfl_xor(ssq[j], 32, 64);
+                    if (hl == 0 && token[j] < T) e.ssq_out[(size_t)grp * T + token[j]] = tot;
+                }
+            } else {
+                // the block's WM waves each hold a quarter of the partial's features: summed through LDS in wave order
+#pragma unroll
+                for (int j = 0; j < FT; ++j) {
+                    const float tot = ssq[j] + __shfl_xor(ssq[j], 32, 64);
+                    if (hl == 0) ssq_lds[wm * NTOK + j * 32 + (lane & 31)] = tot;
+                }
+                __syncthreads();
+                if (wm == 0) {
+#pragma unroll
+                    for (int j = 0; j < FT; ++j) {
+                        float tot = 0.f;
+#pragma unroll
+                        for (int w = 0; w < WM; ++w) tot += ssq_lds[w * NTOK + j * 32 + (lane & 31)];
+                        if (hl == 0 && token[j] < T) e.ssq_out[(size_t)bm * T + token[j]] = tot;
+                    }
+                }
             }
         }
         return;
@@ -404,6 +424,7 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_finish_kernel(const float *
                                                                    int n_tiles, int T, int total, int t_blocks, GemmEpi e) {
     constexpr int NW = WM * WT, NT = 64 * NW, TB = 2 * FT * WT, NTOK = TB * 16;
     __shared__ float rstd_s[NTOK];
+    __shared__ float ssq_lds[(MODE == DEC_RESID && 32 * FM != GEMM_SSQ_COLS) ? WM * NTOK : 1];
     const int id = blockIdx.x;
     const int bm = id / t_blocks, bt = id - bm * t_blocks;
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -441,7 +462,108 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_finish_kernel(const float *
                 }
     }
     __syncthreads();
-    gemm_epilogue<FM, FT, WM, WT, MODE>(acc, bm, bt, wm, wt, lane, N, n_tiles, T, e, rstd_s);
+    gemm_epilogue<FM, FT, WM, WT, MODE>(acc, bm, bt, wm, wt, lane, N, n_tiles, T, e, rstd_s, ssq_lds);
+}
+
+// -------------------------------------------------------------------------------------------------
+// Skinny form for one 128-token tile (a short prompt): the launch is bound by streaming the weights, not by the matrix
+// cores, so it is built like the decode projections.  A block of 4 waves owns 128 features x 128 tokens, a wave 32
+// features x 128 tokens; the weights never touch LDS: a lane requests the 16 bytes of the two 16-row tiles that the
+// 32x32x16 operand wants from it (two 512-byte runs per request), RING k-steps ahead, in a register ring that is
+// refilled slot by slot.  The activations of a k-step (8 KB, L2 hits) are shared by the block's waves through LDS,
+// global -> registers (same ring) -> LDS one k-step before use.  The contraction is split over blockIdx.y; result
+// tiles go to `part` in the layout gemm_finish_kernel<1, 1, 4, 1> reads (four 32-token blocks per feature block).
+// -------------------------------------------------------------------------------------------------
+constexpr int SKINNY_RING = 6;          // measured: 4, 6 and 8 run alike (the CU's load issue rate paces the kernel)
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t *__restrict__ Wp, const bf16_t *__restrict__ Xp,
+                                                         int k_tiles, int n_tiles, int t_tiles, int total,
+                                                         float *__restrict__ part) {
+    constexpr int RING = SKINNY_RING;
+    __shared__ bf16x8 xs[2][8 * 64];                 // two k-steps of the 8 token tiles
+    const int id = blockIdx.x;                       // 128-feature block
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int k0 = (int)((long)blockIdx.y * k_tiles / gridDim.y);
+    const int k_len = (int)((long)(blockIdx.y + 1) * k_tiles / gridDim.y) - k0;
+
+    // weights: lane l of k-half kh takes slot (l % 16) + 16 (l / 32) + 32 kh of tile t16 + (l % 32) / 16
+    const int t16 = min(id * 8 + wave * 2 + ((lane & 31) >> 4), n_tiles - 1);
+    const bf16x8 *wsrc = reinterpret_cast<const bf16x8 *>(Wp) + ((size_t)k0 * n_tiles + t16) * 64 + (lane & 15) + 16 * (lane >> 5);
+    const size_t wstep = (size_t)n_tiles * 64;
+    // activations: wave w copies token tiles 2 w and 2 w + 1 of each k-step (clamped to the last valid tile)
+    const bf16x8 *xsrc[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+        xsrc[i] = reinterpret_cast<const bf16x8 *>(Xp) + ((size_t)min(wave * 2 + i, t_tiles - 1) * k_tiles + k0) * 64 + lane;
+    const int frag = ((lane & 31) >> 4) * 64 + (lane & 15) + 16 * (lane >> 5);
+
+    floatx16 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+
+    // Ring slot = one k-step: the wave's two weight operands and its two pieces of the activations.  Every request is
+    // unconditional (k-steps past the end re-read the last one, an L2 hit, unused), so the compiler counts requests in
+    // flight exactly; because loads return in order, a piece of the activations must not be requested later than the
+    // weights it is used with, or the wait for it would drain the weight requests behind which it sits.
+    bf16x8 a[RING][2], xq[RING][2];
+    auto request = [&](int slot, int kt) {
+        const int kc = min(kt, k_len - 1);
+        xq[slot][0] = xsrc[0][(size_t)kc * 64];
+        xq[slot][1] = xsrc[1][(size_t)kc * 64];
+        const bf16x8 *src = wsrc + (size_t)kc * wstep;
+        a[slot][0] = __builtin_nontemporal_load(src);
+        a[slot][1] = __builtin_nontemporal_load(src + 32);
+    };
+    auto store_x = [&](int slot, int kt) {
+        xs[kt & 1][(wave * 2) * 64 + lane] = xq[slot][0];
+        xs[kt & 1][(wave * 2 + 1) * 64 + lane] = xq[slot][1];
+    };
+    auto step = [&](int slot, int kt) {
+        const bf16x8 *sb = xs[kt & 1] + frag;
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[slot][kh], sb[j * 128 + kh * 32], acc[j], 0, 0, 0);
+    };
+    // the barrier of a k-step waits for the LDS stores only: __syncthreads() would also drain the requests in flight
+    auto lds_barrier = [&]() {
+        __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14));
+        asm volatile("s_barrier" ::: "memory");
+    };
+#pragma unroll
+    for (int i = 0; i < RING; ++i) request(i, i);
+    store_x(0, 0);
+    const int rounds = k_len / RING;
+    for (int rd = 0; rd < rounds; ++rd) {
+#pragma unroll
+        for (int i = 0; i < RING; ++i) {
+            const int kt = rd * RING + i;
+            lds_barrier();                // k-step kt is complete in LDS; the other buffer (k-step kt - 1) is free
+            store_x((i + 1) % RING, kt + 1);
+            step(i, kt);
+            request(i, kt + RING);
+        }
+    }
+    // fewer than RING k-steps left: k-step rounds * RING + i already sits in slot i
+#pragma unroll
+    for (int i = 0; i < RING; ++i) {
+        const int kt = rounds * RING + i;
+        if (kt < k_len) {                 // uniform over the block
+            lds_barrier();
+            store_x((i + 1) % RING, kt + 1);
+            step(i, kt);
+        }
+    }
+    // result tile (32 features x token block j) of this wave, in the layout gemm_finish_kernel<1, 1, 4, 1> reads with
+    // four token blocks per feature block: the finishing pass then has four times as many (smaller) blocks
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<floatx4 *>(part + ((((size_t)blockIdx.y * total + id) * 4 + j) * 4 + wave) * 1024 + q * 256 + lane * 4) =
+                floatx4{acc[j][4 * q], acc[j][4 * q + 1], acc[j][4 * q + 2], acc[j][4 * q + 3]};
 }
 
 template <int FM, int FT, int WM, int WT, int S, int MODE>
@@ -484,6 +606,24 @@ bool set_gemm_tile(int code) {
     return false;
 }
 
+// one 128-token tile, at least 32 k-tiles: skinny kernel + finishing pass; returns false when it does not apply
+template <int MODE>
+static bool launch_skinny(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles, int n_tiles, int t_tiles, int T,
+                          const GemmEpi &e, float *part, size_t part_floats, hipStream_t s) {
+    if (part == nullptr || t_tiles > 8 || k_tiles < 32) return false;
+    const int n_blocks = (n_tiles + 7) / 8;
+    const size_t tile_floats = 4 * 4 * 1024;
+    // two blocks fit a CU (registers): about 512 blocks in flight, at most 8 splits of at least 16 k-steps
+    int splits = std::max(1, std::min({8, 512 / n_blocks, k_tiles / 16}));
+    while (splits > 1 && (size_t)splits * n_blocks * tile_floats > part_floats) --splits;
+    if ((size_t)splits * n_blocks * tile_floats > part_floats) return false;
+    hipLaunchKernelGGL(gemm_skinny_kernel, dim3(n_blocks, splits), dim3(256), 0, s, Wp, Xp, k_tiles, n_tiles, t_tiles,
+                       n_blocks, part);
+    hipLaunchKernelGGL((gemm_finish_kernel<1, 1, 4, 1, MODE>), dim3(n_blocks * 4), dim3(256), 0, s, part, splits, N, n_tiles,
+                       T, n_blocks * 4, 4, e);
+    return true;
+}
+
 template <int MODE>
 static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, float *part,
                         size_t part_floats, hipStream_t s) {
@@ -498,6 +638,7 @@ static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T,
     // one 128-token tile (a short prompt): 128-token block tiles; the split contraction then runs a short k-loop per
     // block with the weights coming from HBM, so the 256 x 128 tile of RESID keeps six stages in flight instead of four
     const bool short_prompt = !force && t_tiles <= 8;
+    if (short_prompt && launch_skinny<MODE>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s)) return;
     if (short_prompt) cfg = MODE == DEC_RESID ? 846 : 44;
 #define HX_G(FM, FT, WM, WT, S) launch_cfg<FM, FT, WM, WT, S, MODE>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s)
     if (cfg == 88) HX_G(4, 4, 2, 2, 4);

@@ -15,6 +15,8 @@ TINY = CONFIGS["tiny_f32"]
 MINI128 = StageConfig("mini128", "bf16", 1024, 8, 2, 2816, 3, 2, (1,), batch=3, seed=11)
 MINI64 = StageConfig("mini64", "bf16", 512, 8, 4, 1408, 2, 1, (0,), batch=2, seed=12)
 MINI2K = StageConfig("mini2k", "bf16", 2048, 16, 4, 5632, 2, 2, (1,), batch=4, seed=13)
+# FFN shard of 1440: 180 feature tiles for W1/W3 (not a multiple of the 8 a block owns) and 45 k-tiles for W2 (odd)
+MINIRAG = StageConfig("minirag", "bf16", 1024, 8, 2, 2880, 2, 2, (0,), batch=2, seed=14)
 
 
 def _weights(cfg, n_layers=None):
@@ -109,10 +111,13 @@ def test_tiny_f32_group_mode_greedy_tokens():
     assert toks_g == toks_o
 
 
-@pytest.mark.parametrize("cfg,lens", [(MINI128, [37, 5, 64]), (MINI64, [16, 33]), (MINI2K, [70]), (MINI2K, [100, 29, 150])])
+@pytest.mark.parametrize("cfg,lens", [(MINI128, [37, 5, 64]), (MINI64, [16, 33]), (MINI2K, [70]), (MINI2K, [100, 29, 150]),
+                                      (MINIRAG, [90]), (MINIRAG, [128]), (MINIRAG, [129, 3])])
 def test_bf16_small_prefill_then_decode(cfg, lens):
     """Short prompts: few token tiles, so the projections with at least 32 k-tiles split their contraction over
-    several blocks and finish in a second pass (2 splits on MINI128, up to 5 on MINI2K); MINI64 does not split."""
+    several blocks and finish in a second pass: up to 128 rows through the skinny kernel (weights in a register ring),
+    beyond through the LDS-staged kernel; MINI64 (16 k-tiles) does neither.  MINIRAG has a ragged last feature block
+    and an odd number of k-tiles; 128 and 129 + 3 rows sit on either side of the one-token-tile limit."""
     w = _weights(cfg)
     rank = cfg.tp_ranks[0]
     X = generate.hidden_rows(cfg, sum(lens))

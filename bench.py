@@ -219,13 +219,29 @@ def prefill_leg(torch, hx, cfg, generate, reps=5):
         tot_f += flops[name]
         tot_t += us
     st.profile_enable(0)
+    # one short prompt on the same stage: the regime of the split contraction and the skinny kernel (weight-streaming
+    # bound: the floor is the stage's weight bytes at the HBM peak)
+    short = {}
+    for rows in (128, 512):
+        kv1 = st.kv_cache_create(1, rows + 8)
+        for _ in range(2):
+            st.prefill(kv1, X[:rows], [rows], outp[:rows], outr[:rows])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            st.prefill(kv1, X[:rows], [rows], outp[:rows], outr[:rows])
+        torch.cuda.synchronize()
+        dt1 = (time.perf_counter() - t0) / reps
+        short[str(rows)] = {"us_per_layer": round(dt1 * 1e6 / cfg.n_layers, 1), "tokens_per_s": round(rows / dt1, 1),
+                            "weights_at_hbm_peak_us_per_layer": round(st.weight_bytes() / cfg.n_layers / HBM_PEAK_GBS / 1e3, 1)}
+        del kv1
     layer_flops = sum(flops.values()) + sum(2 * n * n * d * cfg.hq_l for n in lens)
     return {"workload": f"{cfg.name}: TP{cfg.tp_degree} rank {rank}, {cfg.n_layers} layers, {cfg.batch} x {lens[0]} rows",
             "tokens_per_s": round(T / dt, 1), "ms_per_call": round(dt * 1e3, 3),
             "us_per_layer": round(dt * 1e6 / cfg.n_layers, 1),
             "stage_mfma_frac": round(layer_flops * cfg.n_layers / dt / 1e12 / MFMA_PEAK_TFLOPS, 4),
             "gemm_mfma_frac": round(tot_f / tot_t / 1e6 / MFMA_PEAK_TFLOPS, 4), "gemm": gemm,
-            "peak_TFLOPs": MFMA_PEAK_TFLOPS}
+            "peak_TFLOPs": MFMA_PEAK_TFLOPS, "one_short_prompt": short}
 
 
 def head_leg(torch, hx, generate, reps=50):

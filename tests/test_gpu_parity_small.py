@@ -194,13 +194,15 @@ def test_bf16_decode_from_synthetic_context():
 
 
 @pytest.mark.parametrize("cfg,b", [(MINI64, 32), (MINI64, 1), (MINI64, 2), (MINI128, 3), (MINI128, 16), (MINI128, 17),
-                                   (MINI64, 31), (MINI2K, 3), (MINI2K, 4), (MINI2K, 8), (MINI2K, 9)])
+                                   (MINI64, 31), (MINI2K, 3), (MINI2K, 4), (MINI2K, 8), (MINI2K, 9), (MINI128, 33),
+                                   (MINI64, 40)])
 def test_bf16_decode_batch_sizes(cfg, b):
     """Decode across the row counts that switch kernels: 1-2 rows (one kernel per projection, operand in LDS),
     3-16 rows (split contraction, one token tile), 17-32 rows (two token tiles); MINI128's FFN has 44 k-tiles, so its
     splits end in a partial chunk.  MINI2K's contractions are long enough (64 and 88 k-tiles) for its small matrices
     to take the single-kernel path with 3-8 rows (every block fetching the rows' operand pieces itself; its W_O, with 32
-    k-tiles, stays on the split path), and the split path from 9 rows on."""
+    k-tiles, stays on the split path), and the split path from 9 rows on.  More than 32 rows (33, 40) leave the
+    weight-streaming decode kernels for the prefill kernels with one new row per sequence."""
     w = _weights(cfg)
     ctx = [1 + (7 * i) % 50 for i in range(b)]
     rank = cfg.tp_ranks[0]

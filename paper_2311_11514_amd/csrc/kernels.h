@@ -126,6 +126,10 @@ void launch_prefill_prologue(const void *in, int in_is_bf16, float *h_out, const
 void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, const bf16_t *vc, KvGeom kg,
                         int hq_l, const int32_t *row_pos, int b, int nsplit, float *part_o, float *part_ml,
                         unsigned int *arrived, bf16_t *o_act, hipStream_t s);
+// decode attention on the prefill path's layouts, for calls with one new row per sequence: q and o_packed in
+// fragment tiles with row = sequence; row_pos[seq] = position of the new row
+void launch_attn_decode_rows(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,
+                             const int32_t *row_pos, int b, bf16_t *o_packed, hipStream_t s);
 // prefill attention over packed ragged rows (q in fragment tiles); K, V are read from the cache
 void launch_attn_prefill(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,
                          const int32_t *cu_rows, const int32_t *pos0, int batch, int max_new,

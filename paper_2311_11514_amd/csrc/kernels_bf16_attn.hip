@@ -16,7 +16,9 @@
 // One 8-wave block per (sequence, kv head); the waves interleave over the 32-position tiles of the context and
 // their (m, l, o) triples are merged through LDS in wave order.
 // Used when there are enough (sequence, kv head) pairs to fill the chip or the context is short.
-template <int D>
+// PF: the layouts of the prefill path on both ends (used when more than 32 sequences decode one row each, which the
+// prefill kernels otherwise serve): q is read from fragment tiles (row = sequence, no lo part), o is written to them.
+template <int D, bool PF>
 __global__ __launch_bounds__(512) void attn_decode_block_kernel(const bf16_t *__restrict__ q,
                                                                const bf16_t *__restrict__ q_lo,
                                                                const bf16_t *__restrict__ kc,
@@ -37,9 +39,10 @@ __global__ __launch_bounds__(512) void attn_decode_block_kernel(const bf16_t *__
     bf16x8 qf[KT], ql[KT];
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
-        const size_t qo = ((size_t)sq * hq_l + head) * D + kt * 32 + 8 * g;
+        const size_t qo = PF ? frag_offset(sq, head * D + kt * 32 + 8 * g, (hq_l * D) >> 5)
+                             : ((size_t)sq * hq_l + head) * D + kt * 32 + 8 * g;
         qf[kt] = hv ? *reinterpret_cast<const bf16x8 *>(q + qo) : zero;
-        ql[kt] = hv ? *reinterpret_cast<const bf16x8 *>(q_lo + qo) : zero;
+        ql[kt] = (hv && !PF) ? *reinterpret_cast<const bf16x8 *>(q_lo + qo) : zero;
     }
     floatx4 oacc[DT];
 #pragma unroll
@@ -122,9 +125,13 @@ __global__ __launch_bounds__(512) void attn_decode_block_kernel(const bf16_t *__
         uint2 ph, pl;
         split_pack2(o[0] * inv, o[1] * inv, ph.x, pl.x);
         split_pack2(o[2] * inv, o[3] * inv, ph.y, pl.y);
-        const size_t off = dec_act_offset(sq, (c * G + hh) * D + dd, k_tiles, 0);
-        *reinterpret_cast<uint2 *>(o_act + off) = ph;
-        *reinterpret_cast<uint2 *>(o_act + off + 32) = pl;
+        if (PF) {
+            *reinterpret_cast<uint2 *>(o_act + frag_offset(sq, (c * G + hh) * D + dd, k_tiles)) = ph;
+        } else {
+            const size_t off = dec_act_offset(sq, (c * G + hh) * D + dd, k_tiles, 0);
+            *reinterpret_cast<uint2 *>(o_act + off) = ph;
+            *reinterpret_cast<uint2 *>(o_act + off + 32) = pl;
+        }
     }
 }
 
@@ -288,10 +295,10 @@ void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, c
     if (nsplit <= 1) {       // one block per (sequence, kv head), LDS merge
         dim3 grid(kg.hkv_l, b);
         if (kg.d == 128)
-            hipLaunchKernelGGL(attn_decode_block_kernel<128>, grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G,
+            hipLaunchKernelGGL((attn_decode_block_kernel<128, false>), grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G,
                                row_pos, o_act, scale_log2e);
         else
-            hipLaunchKernelGGL(attn_decode_block_kernel<64>, grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G,
+            hipLaunchKernelGGL((attn_decode_block_kernel<64, false>), grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G,
                                row_pos, o_act, scale_log2e);
         return;
     }
@@ -302,6 +309,20 @@ void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, c
     else
         hipLaunchKernelGGL(attn_decode_split_kernel<64>, grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G, row_pos,
                            nsplit, part_o, part_ml, arrived, o_act, scale_log2e);
+}
+
+// one new row per sequence on the prefill path's layouts: q and o in fragment tiles (row = sequence)
+void launch_attn_decode_rows(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,
+                             const int32_t *row_pos, int b, bf16_t *o_packed, hipStream_t s) {
+    const int G = hq_l / kg.hkv_l;
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)kg.d);
+    dim3 grid(kg.hkv_l, b);
+    if (kg.d == 128)
+        hipLaunchKernelGGL((attn_decode_block_kernel<128, true>), grid, dim3(512), 0, s, q, q, kc, vc, kg, hq_l, G, row_pos,
+                           o_packed, scale_log2e);
+    else
+        hipLaunchKernelGGL((attn_decode_block_kernel<64, true>), grid, dim3(512), 0, s, q, q, kc, vc, kg, hq_l, G, row_pos,
+                           o_packed, scale_log2e);
 }
 
 // -------------------------------------------------------------------------------------------------

@@ -294,7 +294,12 @@ void attn_prefill_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const R
     e.q = w.q; e.kc = kc; e.vc = vc;
     gemm_bf16(st, r, ly.wqkv, w.n, st->nqkv, st->H, e, PROF_QKV, s);
     st->prof.mark(PROF_ATTN, s);
-    launch_attn_prefill(w.q, kc, vc, kg, st->hq_l, w.cu_rows, w.pos0, r.batch, r.max_new, w.o, s);
+    // one new row per sequence (a decode step of more than 32 sequences): the decode attention kernel, which shares
+    // every K / V fragment among the query heads of its kv head, on this path's layouts (row = sequence)
+    if (r.max_new == 1 && st->hq_l / st->hkv_l <= 16)
+        launch_attn_decode_rows(w.q, kc, vc, kg, st->hq_l, w.pos0, r.batch, w.o, s);
+    else
+        launch_attn_prefill(w.q, kc, vc, kg, st->hq_l, w.cu_rows, w.pos0, r.batch, r.max_new, w.o, s);
     st->prof.mark(PROF_ATTN, s);
 }
 

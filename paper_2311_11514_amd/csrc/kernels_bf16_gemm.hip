@@ -629,9 +629,9 @@ static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T,
                         size_t part_floats, hipStream_t s) {
     const int k_tiles = K / 32, n_tiles = N / 16, t_tiles = (T + 15) / 16;
     const int force = g_force_tile.load(std::memory_order_relaxed);
-    // tiles of 256 x 256 once they fill the chip; smaller tiles for small problems
+    // tiles of 256 x 256 once they fill the chip; 128 features x 256 tokens for smaller problems
     const long big = (long)((n_tiles + 15) / 16) * ((t_tiles + 15) / 16);
-    int cfg = big >= 200 ? 98 : ((long)((n_tiles + 7) / 8) * ((t_tiles + 15) / 16) >= 128 ? 94 : 44);
+    int cfg = big >= 200 ? 98 : 94;       // (128 x 256 also beats 128 x 128 on the few-tile launches that split)
     if (force) cfg = force;
     // the RESID epilogue emits one sum-of-squares partial per wave: its 32 FM features must be 128
     if (MODE == DEC_RESID && cfg != 88 && cfg != 84 && cfg != 98) cfg = 84;

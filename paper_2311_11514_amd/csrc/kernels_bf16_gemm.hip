@@ -601,7 +601,7 @@ static void launch_cfg(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles, i
 // tile configuration forced for every GEMM launch of the process (0 = choose by shape); a measurement and test hook
 static std::atomic<int> g_force_tile{0};
 bool set_gemm_tile(int code) {
-    for (int ok : {0, 44, 48, 84, 88, 94, 49, 98})
+    for (int ok : {0, 44, 48, 84, 88, 94, 49, 98, 72})
         if (code == ok) { g_force_tile.store(code, std::memory_order_relaxed); return true; }
     return false;
 }
@@ -632,9 +632,17 @@ static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T,
     // tiles of 256 x 256 once they fill the chip; 128 features x 256 tokens for smaller problems
     const long big = (long)((n_tiles + 15) / 16) * ((t_tiles + 15) / 16);
     int cfg = big >= 200 ? 98 : 94;       // (128 x 256 also beats 128 x 128 on the few-tile launches that split)
+    if (cfg == 98 && MODE != DEC_RESID) {
+        // a launch of a few rounds of blocks loses the idle part of its last round: 448 x 128 tiles (4 waves of
+        // 224 x 64) when they fill the rounds markedly better (W1/W3 of the TP4 shard at 2048 rows: 512 blocks instead
+        // of 448 on 256 CUs; measured 3 % faster)
+        const long b98 = big, b72 = (long)((n_tiles + 27) / 28) * ((t_tiles + 7) / 8);
+        const double fill98 = (double)b98 / (double)((b98 + 255) / 256 * 256), fill72 = (double)b72 / (double)((b72 + 255) / 256 * 256);
+        if (fill72 > fill98 + 0.08) cfg = 72;
+    }
     if (force) cfg = force;
     // the RESID epilogue emits one sum-of-squares partial per wave: its 32 FM features must be 128
-    if (MODE == DEC_RESID && cfg != 88 && cfg != 84 && cfg != 98) cfg = 84;
+    if (MODE == DEC_RESID && cfg != 88 && cfg != 84 && cfg != 98) cfg = cfg == 72 ? 98 : 84;
     // one 128-token tile (a short prompt): 128-token block tiles; the split contraction then runs a short k-loop per
     // block with the weights coming from HBM, so the 256 x 128 tile of RESID keeps six stages in flight instead of four
     const bool short_prompt = !force && t_tiles <= 8;
@@ -646,6 +654,7 @@ static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T,
     else if (cfg == 94) { if constexpr (MODE != DEC_RESID) HX_G(2, 2, 2, 4, 4); }
     else if (cfg == 49) { if constexpr (MODE != DEC_RESID) HX_G(2, 2, 4, 2, 4); }
     else if (cfg == 84) HX_G(4, 2, 2, 2, 4);
+    else if (cfg == 72) { if constexpr (MODE != DEC_RESID) HX_G(7, 2, 2, 2, 4); }
     else if (cfg == 846) { if constexpr (MODE == DEC_RESID) HX_G(4, 2, 2, 2, 6); }
     else if (cfg == 48) {
         if constexpr (MODE != DEC_RESID) HX_G(2, 4, 2, 2, 4);

@@ -68,6 +68,12 @@ def swap(t1: Sequence[int], t2: Sequence[int], k: int) -> Tuple[List[int], List[
     return a, b
 
 
+def group_can_hold(t: Sequence[int], mem: Sequence[float], model_bytes: float) -> bool:
+    """Early check on an offspring (Section 4.3): a group whose total device memory cannot even hold one copy of the
+    model parameters is discarded before the layout problem is solved for it."""
+    return sum(n * m for n, m in zip(t, mem)) >= model_bytes
+
+
 def repartition_layers(total_layers: int, stage_mem: Sequence[float]) -> List[int]:
     """Layer partition proportional to the total memory of the GPU set serving each stage (Section 4.3, "Determine the
     pipeline partitions"); reading: every stage keeps at least one layer, shares are floored and the remainder goes

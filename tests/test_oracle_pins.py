@@ -530,3 +530,6 @@ def test_search_operators_follow_their_definitions():
     parts = sch.repartition_layers(80, [4 * 24e9, 2 * 80e9, 1 * 48e9])
     assert sum(parts) == 80 and min(parts) >= 1 and parts[1] > parts[0] > parts[2]
     assert sch.repartition_layers(3, [100.0, 1.0, 1.0]) == [1, 1, 1]
+    # early check: 2 x 80 GB + 1 x 24 GB hold a 140 GB model (184 >= 140), without the 24 GB card and one 80 GB card not
+    assert sch.group_can_hold([2, 1], [80e9, 24e9], 140e9) and not sch.group_can_hold([1, 1], [80e9, 24e9], 140e9)
+    assert sch.group_can_hold([0, 6], [80e9, 24e9], 144e9) and not sch.group_can_hold([0, 5], [80e9, 24e9], 144e9)

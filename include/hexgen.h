@@ -250,6 +250,8 @@ double hexgen_cost_mem(int hidden, double params_factor, int bytes_per_elem, int
  * one GPU of `type` from tau2 to tau1, in place).  hexgen_sched_repartition_layers: layer partition proportional to
  * the memory of the GPU set serving each stage, at least one layer per stage, remainder by largest fractional part.
  * These four return 1 on success, 0 for invalid arguments (outputs untouched).
+ * hexgen_sched_group_can_hold: the early check on an offspring (Section 4.3): 1 when the group's total device memory
+ * (sum of tau[k] * mem_bytes[k]) is at least model_bytes, else 0 (also for invalid arguments).
  */
 typedef struct {
     int n_types;
@@ -269,6 +271,7 @@ int hexgen_sched_merge(int n_types, const int *tau1, const int *tau2, int *out);
 int hexgen_sched_split(int n_types, const int *tau, int *out1, int *out2);
 int hexgen_sched_swap(int n_types, int *tau1, int *tau2, int type);
 int hexgen_sched_repartition_layers(int total_layers, int n_stages, const double *stage_mem, int *layers_out);
+int hexgen_sched_group_can_hold(int n_types, const int *tau, const double *mem_bytes, double model_bytes);
 
 /* Measurement and test hook, process-wide: force one tile configuration of the prefill projection GEMM instead of
  * the choice by shape.  code = 10 * a + b names the block tile: 88 = 256 x 256 on 4 waves, 98 = 256 x 256 on 8 waves,

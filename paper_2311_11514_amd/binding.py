@@ -62,6 +62,7 @@ SIGNATURES = {
     "hexgen_sched_split": (_i, [_i, _vp, _vp, _vp]),
     "hexgen_sched_swap": (_i, [_i, _vp, _vp, _i]),
     "hexgen_sched_repartition_layers": (_i, [_i, _i, _vp, _vp]),
+    "hexgen_sched_group_can_hold": (_i, [_i, _vp, _vp, C.c_double]),
     "hexgen_stage_profile_enable": (_i, [_vp, _i]),
     "hexgen_stage_profile_read": (_i, [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64)]),
 }
@@ -359,6 +360,10 @@ def sched_swap(t1, t2, k):
     if not lib.hexgen_sched_swap(len(t1), a, b, k):
         raise ValueError("swap: the second group has no GPU of that type")
     return list(a), list(b)
+
+
+def sched_group_can_hold(t, mem, model_bytes) -> bool:
+    return bool(lib.hexgen_sched_group_can_hold(len(t), _iarr(t), _darr(mem), float(model_bytes)))
 
 
 def sched_repartition_layers(total_layers, stage_mem):

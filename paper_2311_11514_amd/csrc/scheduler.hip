@@ -125,6 +125,13 @@ int hexgen_sched_swap(int n_types, int *tau1, int *tau2, int type) {
     return 1;
 }
 
+int hexgen_sched_group_can_hold(int n_types, const int *tau, const double *mem_bytes, double model_bytes) {
+    if (n_types <= 0 || !tau || !mem_bytes) return 0;
+    double total = 0.0;
+    for (int k = 0; k < n_types; ++k) total += tau[k] * mem_bytes[k];
+    return total >= model_bytes ? 1 : 0;
+}
+
 int hexgen_sched_repartition_layers(int total_layers, int n_stages, const double *stage_mem, int *layers_out) {
     if (n_stages <= 0 || total_layers < n_stages || !stage_mem || !layers_out) return 0;
     double tot = 0.0;

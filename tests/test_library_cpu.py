@@ -152,6 +152,9 @@ def test_search_operators_match_the_oracle():
         else:
             with pytest.raises(ValueError):
                 hx.sched_swap(t1, t2, k)
+        memt = [float(v) for v in rng.choice([24e9, 48e9, 80e9], nt)]
+        model = float(rng.choice([13e9, 140e9, 400e9]))
+        assert hx.sched_group_can_hold(t1, memt, model) == sch.group_can_hold(t1, memt, model)
         S = int(rng.integers(1, 7))
         memv = [float(v) for v in rng.choice([24e9, 48e9, 80e9, 160e9, 640e9], S)]
         L = int(rng.integers(S, 121))

@@ -288,7 +288,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
     if (rstd_wave) rstd_finish(e, wave, lane, sv, s_rstd);
     if (MODE != DEC_RESID)
         for (int t = rstd_wave ? wave + WAVES : wave; t < T; t += WAVES) rstd_row(e, t, lane, s_rstd);
-    if (XLDS || MODE != DEC_RESID) __syncthreads();
+    if (XLDS) __syncthreads();       // (s_rstd is read behind the barrier of the reduction below)
 
     // the k-tile held by ring slot i against the operand
     auto contract = [&](int i, int kt) {

@@ -17,6 +17,8 @@ MINI64 = StageConfig("mini64", "bf16", 512, 8, 4, 1408, 2, 1, (0,), batch=2, see
 MINI2K = StageConfig("mini2k", "bf16", 2048, 16, 4, 5632, 2, 2, (1,), batch=4, seed=13)
 # FFN shard of 1440: 180 feature tiles for W1/W3 (not a multiple of the 8 a block owns) and 45 k-tiles for W2 (odd)
 MINIRAG = StageConfig("minirag", "bf16", 1024, 8, 2, 2880, 2, 2, (0,), batch=2, seed=14)
+# 16 query heads on one kv head: every column of the decode attention's 16-column MFMA results is a live head
+MINIG16 = StageConfig("minig16", "bf16", 1024, 16, 1, 2816, 2, 1, (0,), batch=2, seed=15)
 
 
 def _weights(cfg, n_layers=None):
@@ -195,7 +197,7 @@ def test_bf16_decode_from_synthetic_context():
 
 @pytest.mark.parametrize("cfg,b", [(MINI64, 32), (MINI64, 1), (MINI64, 2), (MINI128, 3), (MINI128, 16), (MINI128, 17),
                                    (MINI64, 31), (MINI2K, 3), (MINI2K, 4), (MINI2K, 8), (MINI2K, 9), (MINI128, 33),
-                                   (MINI64, 40)])
+                                   (MINI64, 40), (MINIG16, 2), (MINIG16, 5), (MINIG16, 34)])
 def test_bf16_decode_batch_sizes(cfg, b):
     """Decode across the row counts that switch kernels: 1-2 rows (one kernel per projection, operand in LDS),
     3-16 rows (split contraction, one token tile), 17-32 rows (two token tiles); MINI128's FFN has 44 k-tiles, so its
@@ -223,7 +225,7 @@ def test_bf16_decode_batch_sizes(cfg, b):
         assert row_rel_err(h, h_ref) < TOL["bf16"] and row_rel_err(p, p_ref) < TOL["bf16"]
 
 
-@pytest.mark.parametrize("cfg,ctx", [(MINI128, [1700, 40, 1537]), (MINI64, [2100]), (MINI64, [5, 1600])])
+@pytest.mark.parametrize("cfg,ctx", [(MINI128, [1700, 40, 1537]), (MINI64, [2100]), (MINI64, [5, 1600]), (MINIG16, [1800, 33])])
 def test_bf16_decode_long_context_split_over_blocks(cfg, ctx):
     """Few sequences with a long context: the attention of one (sequence, kv head) is split over several blocks and
     merged by the block that finishes last.  Ragged lengths leave the short sequences' later splits empty; the second

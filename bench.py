@@ -130,6 +130,9 @@ def main():
         ms, n = st.profile_read(slot)
         slots[name] = {"avg_us": ms / max(n, 1) * 1e3, "launches": n}
     st.profile_enable(False)
+    # the same kernel once more, all layers back to back between two events only (no per-launch events): its duration
+    # without the dispatch gap that an event pair around a single launch includes
+    b2b_ms, b2b_n = st.time_w13_decode(32)
 
     eb = 2
     H, Fl = cfg.hidden, cfg.ffn_l
@@ -161,7 +164,9 @@ def main():
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES, "bytes_per_launch": w13_bytes,
-                     "avg_launch_us": round(w13_us, 2), "launches_timed": w13_n},
+                     "avg_launch_us": round(w13_us, 2), "launches_timed": w13_n,
+                     "back_to_back": {"avg_launch_us": round(b2b_ms / b2b_n * 1e3, 2), "launches": b2b_n,
+                                      "frac": round(w13_bytes / (b2b_ms / b2b_n * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}},
     }
 
     if not args.no_cpu_baseline:

@@ -156,6 +156,14 @@ hexgen_status_t hexgen_stage_set_tap(hexgen_stage_t *st, int layer, void *h_dump
  */
 hexgen_status_t hexgen_stage_profile_enable(hexgen_stage_t *st, int slot_mask);
 hexgen_status_t hexgen_stage_profile_read(hexgen_stage_t *st, int slot, double *total_ms, int64_t *count);
+/* The W1/W3 (+SwiGLU) decode projection of every layer, back to back, `reps` times over, between two HIP events on
+ * `stream`: total_ms / launches is that kernel's duration without the per-launch event overhead of the slots above
+ * (every launch streams a different layer's weights, as in a decode step).  Runs on the operands the last decode call
+ * left in the workspace and overwrites only the workspace's FFN operand; HEXGEN_ERR_STATE before the first decode
+ * call of at most 32 rows or on an fp32 stage.  Synchronises the stream.
+ */
+hexgen_status_t hexgen_stage_time_w13_decode(hexgen_stage_t *st, int reps, double *total_ms, int64_t *launches,
+                                             void *stream);
 
 /* HBM calibration kernels of known size (used by the benchmark and to scale profiler byte counters):
  * copy moves `bytes` (multiple of 16) from src to dst; read streams `bytes` from src and writes at most one

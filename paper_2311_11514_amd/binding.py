@@ -65,6 +65,7 @@ SIGNATURES = {
     "hexgen_sched_group_can_hold": (_i, [_i, _vp, _vp, C.c_double]),
     "hexgen_stage_profile_enable": (_i, [_vp, _i]),
     "hexgen_stage_profile_read": (_i, [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64)]),
+    "hexgen_stage_time_w13_decode": (_i, [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64), _vp]),
 }
 
 
@@ -189,6 +190,13 @@ class Stage:
         ms, n = C.c_double(), C.c_int64()
         _check(lib.hexgen_stage_profile_read(self.handle, slot, C.byref(ms), C.byref(n)),
                "hexgen_stage_profile_read")
+        return ms.value, n.value
+
+    def time_w13_decode(self, reps: int, stream=None):
+        """(total milliseconds, launches) of the W1/W3 decode projection of every layer, back to back, reps times."""
+        ms, n = C.c_double(), C.c_int64()
+        _check(lib.hexgen_stage_time_w13_decode(self.handle, reps, C.byref(ms), C.byref(n), _stream_handle(stream)),
+               "hexgen_stage_time_w13_decode")
         return ms.value, n.value
 
     def weight_bytes(self) -> int:

@@ -97,6 +97,7 @@ struct hexgen_stage {
     std::vector<Layer> layers;
     std::vector<void *> taps;
     Workspace ws;
+    int last_decode_rows = 0;        // rows of the last decode call that ran on the weight-streaming kernels
     int ws_batch_cap = 0;
     int64_t weight_bytes = 0;
     Profiler prof;
@@ -873,6 +874,7 @@ hexgen_status_t hexgen_stage_decode(hexgen_stage_t *st, hexgen_kv_cache_t *kv, i
     st->prof.mark(PROF_CALL, s);
     if (st->dtype == HEXGEN_BF16) HX_TRY(forward_bf16(st, kv, r, hidden_in, out_partial, out_resid, s));
     else HX_TRY(forward_f32(st, kv, r, hidden_in, out_partial, out_resid, s));
+    if (r.decode && st->dtype == HEXGEN_BF16) st->last_decode_rows = r.T;
     if (!r.decode || st->dtype != HEXGEN_BF16) launch_advance_lens(kv->d_lens, kv->batch, s);   // else: the prologue did
     st->prof.mark(PROF_CALL, s);
     for (int i = 0; i < kv->batch; ++i) kv->lens[i] += 1;
@@ -933,6 +935,41 @@ hexgen_status_t hexgen_stage_profile_read(hexgen_stage_t *st, int slot, double *
     }
     *total_ms = tot;
     *count = n;
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_stage_time_w13_decode(hexgen_stage_t *st, int reps, double *total_ms, int64_t *launches,
+                                             void *stream) {
+    if (!st || !total_ms || !launches || reps <= 0) return HEXGEN_ERR_INVALID_ARG;
+    HX_TRY(check_loaded(st));
+    if (st->dtype != HEXGEN_BF16 || st->last_decode_rows <= 0) return HEXGEN_ERR_STATE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Workspace &w = st->ws;
+    Rows r;
+    r.T = st->last_decode_rows;
+    r.batch = r.T;
+    r.decode = true;
+    hipEvent_t e0, e1;
+    HX_HIP(hipEventCreate(&e0));
+    HX_HIP(hipEventCreate(&e1));
+    const unsigned saved = st->prof.mask;
+    st->prof.mask = 0;
+    DecodeEpi e = epi_base(st, DEC_SWIGLU);
+    e.ssq_in = w.ssq + (size_t)(st->H / 16) * DEC_SSQ_STRIDE;
+    e.u = w.xa_u;
+    e.F_l = st->F_l;
+    HX_HIP(hipEventRecord(e0, s));
+    for (int i = 0; i < reps; ++i)
+        for (int l = 0; l < st->L; ++l) decode_proj(st, r, st->layers[l].w13, w.xa_n, 2 * st->F_l, st->H, e, PROF_W13, s);
+    HX_HIP(hipEventRecord(e1, s));
+    HX_HIP(hipEventSynchronize(e1));
+    st->prof.mask = saved;
+    float ms = 0.f;
+    HX_HIP(hipEventElapsedTime(&ms, e0, e1));
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    *total_ms = ms;
+    *launches = (int64_t)reps * st->L;
     return HEXGEN_OK;
 }
 

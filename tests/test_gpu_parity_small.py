@@ -188,11 +188,17 @@ def test_bf16_decode_from_synthetic_context():
             oc.fill(layer, s, k, v)
             kv.fill(layer, s, k, v)
     kv.set_lengths(ctx)
+    import paper_2311_11514_amd as hx
+    with pytest.raises(hx.HexgenError):
+        st.time_w13_decode(1)                       # no decode call yet
     for step in range(3):
         x = generate.hidden_rows(cfg, len(ctx), stream_id=1 + step)
         p_ref, h_ref = ora.decode(oc, x)
         p, h = gpu_decode(st, kv, cfg, step, x)
         assert row_rel_err(h, h_ref) < TOL["bf16"] and row_rel_err(p, p_ref) < TOL["bf16"]
+        # the measurement pass of the FFN up-projection touches nothing the next step depends on
+        ms, n = st.time_w13_decode(2)
+        assert ms > 0 and n == 2 * cfg.n_layers
 
 
 @pytest.mark.parametrize("cfg,b", [(MINI64, 32), (MINI64, 1), (MINI64, 2), (MINI128, 3), (MINI128, 16), (MINI128, 17),

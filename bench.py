@@ -28,7 +28,7 @@ PROF_QKV, PROF_WO, PROF_W13, PROF_W2, PROF_ATTN, PROF_CALL = range(6)
 
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled
 # by a copy kernel of known size); see profiles/.  None until measured for the current kernel.
-MEASURED_TRAFFIC_BYTES = 470_663_000     # profiles/decode_l70_tp2_pmc_traffic.txt
+MEASURED_TRAFFIC_BYTES = 470_662_000     # profiles/decode_l70_tp2_pmc_traffic.txt
 
 
 def log(msg):

@@ -268,8 +268,9 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
         if (!XLDS) {
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                xq[i][b][0] = xv[b] ? xg[b][kt * 8] : zero;
-                xq[i][b][1] = xv[b] ? xg[b][kt * 8 + 4] : zero;
+                // unconditional (see above): lanes past the last row re-read row 0 and feed output columns nobody stores
+                xq[i][b][0] = xg[b][kt * 8];
+                xq[i][b][1] = xg[b][kt * 8 + 4];
             }
         }
 #pragma unroll
@@ -317,6 +318,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
             const int kt = wave + ((rd - 1) * UNROLL + i) * WAVES;
             contract(i, kt);
             request(i, kt + UNROLL * WAVES);
+            if (!XLDS) __builtin_amdgcn_sched_barrier(0);       // keep each refill right behind its slot's use
         }
     }
     if (rounds > 0) {
@@ -536,11 +538,11 @@ template <int UT, int MODE>
 void launch_mode(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, hipStream_t s) {
     const size_t xbytes = (size_t)T * k_tiles * 8 * sizeof(bf16x8);
     // staged operand: XR 16-byte pieces per thread (512 threads), 4 up to 32 KB, 8 up to 64 KB
-    // The residual projections (W_O, W2) have nothing to wait for before their main loop but the operand itself: with
-    // one or two rows each wave fetches its pieces through its request ring instead of the block staging the operand
-    // in LDS behind a barrier (measured at one row: W_O 17.9 -> 16.9 us, W2 44.0 -> 43.6; the projections that also
-    // derive rstd before the loop gain nothing, QKV loses).
-    if (MODE == DEC_RESID && T <= 2) {
+    // With one or two rows each wave of the residual projections (W_O, W2) and of W1/W3 fetches its operand pieces
+    // through its request ring instead of the block staging the operand in LDS behind a barrier (measured: W_O
+    // 17.9 -> 16.6 us and W2 44.0 -> 43.4 at one row, W1/W3 81.0 -> 77.9 at two rows and unchanged at one).  The
+    // QKV projection keeps the staged operand: through the ring it loses 3.5 us.
+    if ((MODE == DEC_RESID || MODE == DEC_SWIGLU) && T <= 2) {
         launch_one<1, UT, 8 / UT, MODE, false, 1>(Wp, Xa, N, k_tiles, T, e, s);
         return;
     }

@@ -533,3 +533,204 @@ def test_search_operators_follow_their_definitions():
     # early check: 2 x 80 GB + 1 x 24 GB hold a 140 GB model (184 >= 140), without the 24 GB card and one 80 GB card not
     assert sch.group_can_hold([2, 1], [80e9, 24e9], 140e9) and not sch.group_can_hold([1, 1], [80e9, 24e9], 140e9)
     assert sch.group_can_hold([0, 6], [80e9, 24e9], 144e9) and not sch.group_can_hold([0, 5], [80e9, 24e9], 144e9)
+
+
+# ---- SLO attainment simulator (Section 5.1) ----------------------------------------------------------------------
+def test_slo_simulator_hand_worked_traces():
+    from oracle import slo_oracle as slo
+    # two replicas needing 2 s and 3 s; worked by hand: request 0 -> A (done 2), 1 -> B (3), 2 -> A (4), 3 (t = 1):
+    # A would finish at 6, B at 6 -> tie, A; 4 (t = 5): A 8, B max(5, 3) + 3 = 8 -> tie, A
+    arrival = [0.0, 0.0, 0.0, 1.0, 5.0]
+    assert slo.simulate(arrival, [[2.0], [3.0]]) == [2.0, 3.0, 4.0, 6.0, 8.0]
+    assert slo.attainment(arrival, [[2.0], [3.0]], [3.0]) == 3 / 5          # response times 2, 3, 4, 5, 3
+    assert slo.attainment(arrival, [[2.0], [3.0]], [4.0]) == 4 / 5
+    # a burst of n requests on one replica of service time D: finish times D, 2D, ..: floor(deadline / D) of n in time
+    assert slo.simulate([0.0] * 7, [[1.5]]) == [1.5 * (i + 1) for i in range(7)]
+    assert slo.attainment([0.0] * 7, [[1.5]], [5.0]) == 3 / 7
+    # arrivals further apart than the service time never wait
+    assert slo.attainment([0.0, 2.0, 4.5, 7.0], [[1.9]], [1.9]) == 1.0
+    assert slo.attainment([0.0, 2.0, 4.5, 7.0], [[1.9]], [1.8]) == 0.0
+    # two request classes with their own latencies and deadlines (one replica): class 1 is served in 1 s, class 0 in 4 s
+    arrival, cls = [0.0, 0.5, 1.0], [0, 1, 1]
+    assert slo.simulate(arrival, [[4.0, 1.0]], cls) == [4.0, 5.0, 6.0]
+    assert slo.attainment(arrival, [[4.0, 1.0]], [4.0, 4.5], cls) == 2 / 3  # responses 4 (ok), 4.5 (ok), 5 (late)
+
+
+def test_slo_simulator_against_queueing_theory():
+    from oracle import slo_oracle as slo
+    from workloads import serving
+    # (a) c identical replicas with a constant service time D form a FCFS G/D/c queue, where requests leave in the
+    # order they came: request k starts at max(arrival_k, finish_{k-c})
+    arrival = serving.poisson_arrivals(2.0, 3000, 1)
+    for c, D in ((1, 0.4), (3, 1.3), (5, 2.6)):
+        fin = slo.simulate(arrival, [[D]] * c)
+        ref = []
+        for k, a in enumerate(arrival):
+            ref.append(max(a, ref[k - c] if k >= c else 0.0) + D)
+        assert np.allclose(fin, ref, rtol=0, atol=1e-9)
+    # (b) M/D/1: the mean wait in queue is rho D / (2 (1 - rho))  (Pollaczek-Khinchine)
+    lam, D = 0.5, 1.0
+    arrival = serving.poisson_arrivals(lam, 200_000, 2)
+    fin = slo.simulate(arrival, [[D]])
+    wait = np.mean(np.array(fin) - np.array(arrival) - D)
+    rho = lam * D
+    assert abs(wait - rho * D / (2 * (1 - rho))) < 0.03 * rho * D / (2 * (1 - rho))
+    # (c) ... and the share served within deadline t <= 2D follows the M/D/1 waiting-time law
+    #     P(W <= w) = (1 - rho) sum_{j=0..floor(w/D)} (lam (jD - w))^j / j! * exp(-lam (jD - w))
+    for t in (1.0, 1.5, 2.0, 2.7):
+        w = t - D
+        cdf = (1 - rho) * sum((lam * (j * D - w)) ** j / math.factorial(j) * math.exp(-lam * (j * D - w))
+                              for j in range(int(math.floor(w / D)) + 1))
+        assert abs(slo.attainment(arrival, [[D]], [t]) - cdf) < 0.01
+    # (d) attainment never falls when the deadline grows or an identical replica is added
+    arrival = serving.poisson_arrivals(1.2, 2000, 3)
+    prev = 0.0
+    for t in (1.0, 1.5, 2.0, 4.0, 8.0):
+        a = slo.attainment(arrival, [[1.0]], [t])
+        assert a >= prev
+        prev = a
+    assert slo.attainment(arrival, [[1.0]] * 2, [1.5]) >= slo.attainment(arrival, [[1.0]], [1.5])
+
+
+# ---- search over deployments (Section 4.3) --------------------------------------------------------------------------
+def test_search_random_draws_are_splitmix64():
+    from oracle import search_oracle as srch
+    # the published SplitMix64 sequence started at 0
+    assert [srch.draw(0, c) for c in range(3)] == [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+    assert all(0 <= srch.draw(12345, c) < 1 << 64 for c in range(100))
+    assert len({srch.draw(7, c) for c in range(1000)}) == 1000
+
+
+def test_search_kmeans_against_library_and_closed_forms():
+    from sklearn.cluster import KMeans
+
+    from oracle import search_oracle as srch
+    rng = np.random.default_rng(5)
+    for trial in range(10):
+        n, m, d = int(rng.integers(4, 9)), int(rng.integers(1, 4)), int(rng.integers(2, 7))
+        pts = rng.normal(size=(n, d)) + 4.0 * rng.integers(0, 3, size=(n, 1))
+        w = rng.integers(1, 9, size=n).astype(float)
+        assign, centres, inertia = srch.kmeans(pts.tolist(), w.tolist(), m)
+        # the same seeding handed to the library's Lloyd iteration converges to the same fixed point
+        first = max(range(n), key=lambda i: (w[i], -i))
+        seeds = [pts[first]]
+        while len(seeds) < m:
+            dist = np.min([np.sum((pts - s) ** 2, axis=1) for s in seeds], axis=0)
+            seeds.append(pts[int(np.argmax(dist))])
+        km = KMeans(n_clusters=m, init=np.array(seeds), n_init=1, algorithm="lloyd", tol=0.0, max_iter=100)
+        km.fit(pts, sample_weight=w)
+        assert list(km.labels_) == assign
+        assert abs(km.inertia_ - inertia) <= 1e-9 * max(1.0, inertia)
+    # one cluster: the centre is the weighted mean and the inertia the weighted scatter around it
+    pts = [[0.0, 0.0], [4.0, 0.0], [0.0, 2.0]]
+    assign, centres, inertia = srch.kmeans(pts, [1.0, 1.0, 2.0], 1)
+    assert np.allclose(centres[0], [1.0, 1.0]) and abs(inertia - (2 + 10 + 2 * 2)) < 1e-12
+    # as many clusters as points: nothing is left over
+    assert srch.kmeans(pts, [1.0, 1.0, 2.0], 3)[2] == 0.0
+    # two far-apart blobs are found
+    pts = [[0.0], [0.1], [10.0], [10.2], [0.05]]
+    assign, _, _ = srch.kmeans(pts, [1.0] * 5, 2)
+    assert assign[0] == assign[1] == assign[4] != assign[2] == assign[3]
+    # elbow of a curve with a sharp knee at 2; flat curves and single points give one cluster
+    assert srch.elbow([100.0, 10.0, 8.0, 6.0, 0.0]) == 2          # distances below the chord: 0, .65, .42, .19, 0
+    assert srch.elbow([100.0, 60.0, 5.0, 2.0, 0.0]) == 3
+    assert srch.elbow([0.0, 0.0, 0.0]) == 1 and srch.elbow([5.0]) == 1
+
+
+def test_search_initial_groups_follow_the_regions():
+    from oracle import search_oracle as srch
+    from workloads import serving
+    for kind in ("full_price", "half_price"):
+        pool = serving.hetero_pool(kind)
+        groups = srch.initial_groups(pool)
+        # a partition of the pool in which no GPU type is divided
+        assert [sum(g[k] for g in groups) for k in range(len(pool["count"]))] == pool["count"]
+        assert all(sum(1 for g in groups if g[k]) == 1 for k in range(len(pool["count"])))
+    # the three Illinois types (fast links among themselves, slow ones to everything else) stay together
+    groups = srch.initial_groups(serving.hetero_pool("full_price"))
+    (ill,) = [g for g in groups if g[3]]
+    assert ill[3:] == [16, 8, 4] and ill[:3] == [0, 0, 0]
+
+
+def _search_case(seed):
+    from oracle import search_oracle as srch
+    from workloads import serving
+    task = (4096, 12.0, 2, 1, 128, 32)
+    n_layers = 16
+    pool = serving.tiny_pool(seed, 3, 3)
+    pool["mem"] = [m / 8 for m in pool["mem"]]          # 3 - 10 GB cards against a 6.4 GB model
+    model_bytes = n_layers * 12 * 4096 ** 2 * 2
+    whole = srch.plan_group(pool, task, pool["count"], n_layers, 3)[0]
+    arrival = serving.poisson_arrivals(1.2 / whole, 150, seed)
+    return pool, task, n_layers, model_bytes, arrival, 2.5 * whole
+
+
+def test_search_group_plan_properties():
+    from oracle import sched_oracle as sch
+    from oracle import search_oracle as srch
+    for seed in (1, 2, 4):
+        pool, task, n_layers, _, _, _ = _search_case(seed)
+        tau = pool["count"]
+        cost, layers, stages = srch.plan_group(pool, task, tau, n_layers, 3)
+        assert cost < math.inf and sum(layers) == n_layers and len(layers) == len(stages) <= 3
+        # the plan is a feasible layout of the group and its cost is what the cost model gives for it
+        assert all(sum(n for k, n in stages if k == t) <= tau[t] for t in range(len(tau)))
+        total = sum(sch.stage_cost(pool, task, layers[j], k, n) for j, (k, n) in enumerate(stages))
+        total += sum(sch.hop_cost(pool, task, stages[j][0], stages[j + 1][0]) for j in range(len(stages) - 1))
+        assert abs(total - cost) <= 1e-12 * cost
+        # never worse than the even partition at any stage count, never better than the best over ALL partitions
+        sub = dict(pool, count=list(tau))
+        for s in (1, 2, 3):
+            even = [n_layers // s + (1 if j < n_layers % s else 0) for j in range(s)]
+            assert cost <= sch.best_layout_bruteforce(sub, task, even)[0]
+        best_any = min(sch.best_layout_bruteforce(sub, task, [a, n_layers - a])[0] for a in range(1, n_layers))
+        best_any = min(best_any, sch.best_layout_bruteforce(sub, task, [n_layers])[0])
+        if len(layers) <= 2:
+            assert cost >= best_any * (1 - 1e-12)
+    # one GPU type with ample memory: a single stage on one tensor-parallel group, priced by the cost model directly
+    pool = {"count": [2], "m": [2e12], "c": [4e14], "mem": [80e9], "tp_alpha": [1e-5], "tp_beta": [1e11],
+            "pp_alpha": [[1e-3]], "pp_beta": [[1e9]]}
+    cost, layers, stages = srch.plan_group(pool, (4096, 12.0, 2, 1, 128, 32), [2], 8, 1)
+    assert layers == [8] and stages[0][0] == 0
+    assert cost == min(sch.stage_cost(pool, (4096, 12.0, 2, 1, 128, 32), 8, 0, n) for n in (1, 2))
+
+
+def test_search_invariants_and_exhaustive_optimum():
+    import itertools
+
+    from oracle import search_oracle as srch
+    from oracle import slo_oracle as slo
+    reached = 0
+    for seed in (1, 2, 4, 5):
+        pool, task, n_layers, model_bytes, arrival, deadline = _search_case(seed)
+        res = srch.search(pool, task, n_layers, model_bytes, 3, arrival, deadline, seed, 80, 4)
+        groups = [g["tau"] for g in res["groups"]]
+        # the result is a partition of the pool; every group holds the model and has a plan of all the layers
+        assert [sum(g[k] for g in groups) for k in range(3)] == pool["count"]
+        for g in res["groups"]:
+            assert g["latency"] < math.inf and sum(g["layers"]) == n_layers
+            assert sum(t * m for t, m in zip(g["tau"], pool["mem"])) >= model_bytes
+        # the reported attainment is the simulator's for the reported latencies; the best-so-far curve never falls
+        assert res["attainment"] == slo.attainment(arrival, [[g["latency"]] for g in res["groups"]], [deadline])
+        assert all(b >= a for a, b in zip(res["history"], res["history"][1:])) and res["history"][-1] == res["attainment"]
+        start = srch.initial_groups(pool)
+        if all(srch.plan_group(pool, task, g, n_layers, 3)[0] < math.inf for g in start):
+            lat0 = [[srch.plan_group(pool, task, g, n_layers, 3)[0]] for g in start]
+            assert res["attainment"] >= slo.attainment(arrival, lat0, [deadline])
+        # exhaustive optimum over every partition of the (distinguishable) GPUs into groups
+        gpus = [k for k in range(3) for _ in range(pool["count"][k])]
+        seen, best = set(), 0.0
+        for labels in itertools.product(range(len(gpus)), repeat=len(gpus)):
+            part = {}
+            for g, lab in zip(gpus, labels):
+                part.setdefault(lab, [0, 0, 0])[g] += 1
+            key = tuple(sorted(tuple(t) for t in part.values()))
+            if key in seen:
+                continue
+            seen.add(key)
+            lats = [srch.plan_group(pool, task, list(t), n_layers, 3)[0] for t in key]
+            if all(x < math.inf for x in lats):
+                best = max(best, slo.attainment(arrival, [[x] for x in lats], [deadline]))
+        assert res["attainment"] <= best
+        reached += res["attainment"] == best
+    assert reached >= 2          # a local search: it finds the optimum on most of these small pools, not on all

@@ -281,6 +281,68 @@ int hexgen_sched_swap(int n_types, int *tau1, int *tau2, int type);
 int hexgen_sched_repartition_layers(int total_layers, int n_stages, const double *stage_mem, int *layers_out);
 int hexgen_sched_group_can_hold(int n_types, const int *tau, const double *mem_bytes, double model_bytes);
 
+/* ---- SLO attainment and the search over deployments (paper Section 5.1 "SLO attainment"; Section 4.3) -----------
+ * Host functions, no device work; all arrays are HOST arrays owned by the caller.
+ *
+ * hexgen_slo_attainment: the share of the requests of a trace that a deployment finishes in time.  arrival[n_req]:
+ * non-decreasing times >= 0 in seconds (a Poisson process in the paper's experiments); cls[n_req]: request class in
+ * [0, n_classes), NULL = all class 0; latency[n_replicas][n_classes] > 0: seconds replica r needs for a request of
+ * class c (the end-to-end cost of Section 4.2 of that pipeline group); deadline[n_classes].  The paper takes its task
+ * simulator from another system; the queue here: requests in arrival order, none dropped, one request at a time per
+ * replica, each request sent to the replica on which it finishes earliest (lowest index on ties); on time when
+ * finish <= arrival + deadline.  finish_out[n_req] (may be NULL) receives the finish times.  Returns the share in
+ * [0, 1]; NaN for invalid arguments (no request, unsorted or negative arrivals, a class out of range, a latency <= 0).
+ *
+ * hexgen_sched_draw: the search's counter-based random source: output counter + 1 of the SplitMix64 sequence started
+ * at seed.
+ *
+ * hexgen_sched_initial_groups: the start of the search (Section 4.3 "Initialization"): weighted K-means over the GPU
+ * types' rows of the hop matrices (latencies and per-byte times, each scaled by its largest entry), the number of
+ * groups from the elbow of the inertia curve; every cluster of types becomes one group.  groups[n_types][n_types]
+ * receives one count vector per group; returns the number of groups, 0 for invalid arguments or an empty pool.
+ *
+ * hexgen_sched_plan_group: the pipeline a group tau (tau[k] <= count[k]) would run (Section 4.3 "Determine the
+ * pipeline partitions"): for every stage count S <= min(max_stages, GPUs, layers) the even layer partition, the
+ * layout of Algorithm 1, the partition proportional to the stages' memory, the layout again, the cheaper of the two;
+ * over S the cheapest, fewest stages on ties.  Outputs (each may be NULL): *n_stages and layers / stage_type /
+ * stage_count[max_stages].  Returns the latency in seconds, +infinity (and *n_stages = 0) when the group can run no
+ * pipeline, NaN for invalid arguments.
+ *
+ * hexgen_sched_search: the iteration of Section 4.3 ("Put it together") for n_iter steps from the start above: pick a
+ * member of the population, one of merge / split / swap and its operand groups (for swap also the GPU type, among
+ * those the giving group holds) with draws 5 it .. 5 it + 4 modulo the number of choices; drop the offspring when the
+ * operator does not apply, a new group fails hexgen_sched_group_can_hold for model_bytes, has more than
+ * max_group_states layout states (product of tau[k] + 1) or no plan; score it by hexgen_slo_attainment over the trace
+ * with the groups' plan latencies (one class); let it join the population (pop_size members at most; it replaces the
+ * member of lowest score, oldest first, unless it scores lower).  A start that is not admissible is replaced by the
+ * whole pool as one group.  Outputs describe the first deployment that reached the best score: *n_groups,
+ * group_tau[max_groups][n_types], and (each may be NULL) group_latency[max_groups], group_n_stages[max_groups],
+ * stage_layers / stage_type / stage_count[max_groups][max_stages], history[n_iter] = best score after each step.
+ * Returns the best score; NaN for invalid arguments, when even the whole pool is not admissible, or when the result
+ * has more than max_groups groups (outputs then untouched).
+ */
+typedef struct {
+    int total_layers;
+    double model_bytes;
+    int max_stages;
+    int pow2_degrees_only;
+    unsigned long long seed;
+    int n_iter;
+    int pop_size;
+    long max_group_states;
+} hexgen_search_t;
+double hexgen_slo_attainment(int n_req, const double *arrival, const int *cls, int n_replicas, int n_classes,
+                             const double *latency, const double *deadline, double *finish_out);
+unsigned long long hexgen_sched_draw(unsigned long long seed, unsigned long long counter);
+int hexgen_sched_initial_groups(const hexgen_pool_t *pool, int *groups);
+double hexgen_sched_plan_group(const hexgen_pool_t *pool, const hexgen_task_t *task, const int *tau, int total_layers,
+                               int max_stages, int pow2_degrees_only, int *n_stages, int *layers, int *stage_type,
+                               int *stage_count);
+double hexgen_sched_search(const hexgen_pool_t *pool, const hexgen_task_t *task, const hexgen_search_t *cfg, int n_req,
+                           const double *arrival, double deadline, int max_groups, int *n_groups, int *group_tau,
+                           double *group_latency, int *group_n_stages, int *stage_layers, int *stage_type,
+                           int *stage_count, double *history);
+
 /* Measurement and test hook, process-wide: force one tile configuration of the prefill projection GEMM instead of
  * the choice by shape.  code = 10 * a + b names the block tile: 88 = 256 x 256 on 4 waves, 98 = 256 x 256 on 8 waves,
  * 84 = 256 x 128, 48 = 128 x 256, 94 / 49 = 128 x 256 on 8 waves (2 x 4 / 4 x 2 wave grid), 44 = 128 x 128,

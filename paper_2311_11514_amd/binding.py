@@ -63,6 +63,11 @@ SIGNATURES = {
     "hexgen_sched_swap": (_i, [_i, _vp, _vp, _i]),
     "hexgen_sched_repartition_layers": (_i, [_i, _i, _vp, _vp]),
     "hexgen_sched_group_can_hold": (_i, [_i, _vp, _vp, C.c_double]),
+    "hexgen_slo_attainment": (C.c_double, [_i, _vp, _vp, _i, _i, _vp, _vp, _vp]),
+    "hexgen_sched_draw": (C.c_ulonglong, [C.c_ulonglong, C.c_ulonglong]),
+    "hexgen_sched_initial_groups": (_i, [_vp, _vp]),
+    "hexgen_sched_plan_group": (C.c_double, [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp]),
+    "hexgen_sched_search": (C.c_double, [_vp, _vp, _vp, _i, _vp, C.c_double, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "hexgen_stage_profile_enable": (_i, [_vp, _i]),
     "hexgen_stage_profile_read": (_i, [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64)]),
     "hexgen_stage_time_w13_decode": (_i, [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64), _vp]),
@@ -349,6 +354,82 @@ def sched_pipeline_layout(pool: dict, task, layers, pow2_degrees_only: bool = Fa
     st, sc = (C.c_int * len(layers))(), (C.c_int * len(layers))()
     cost = lib.hexgen_sched_pipeline_layout(C.byref(p), C.byref(t), len(layers), ls, int(pow2_degrees_only), st, sc)
     return cost, [(st[j], sc[j]) for j in range(len(layers))]
+
+
+class _Search(C.Structure):
+    _fields_ = [("total_layers", C.c_int), ("model_bytes", C.c_double), ("max_stages", C.c_int),
+                ("pow2_degrees_only", C.c_int), ("seed", C.c_ulonglong), ("n_iter", C.c_int), ("pop_size", C.c_int),
+                ("max_group_states", C.c_long)]
+
+
+def _pool_struct(pool: dict):
+    keep = [_iarr(pool["count"]), _darr(pool["m"]), _darr(pool["c"]), _darr(pool["mem"]), _darr(pool["tp_alpha"]),
+            _darr(pool["tp_beta"]), _darr(pool["pp_alpha"]), _darr(pool["pp_beta"])]
+    return _Pool(len(pool["count"]), *keep), keep
+
+
+def _task_struct(task):
+    return _Task(int(task[0]), float(task[1]), int(task[2]), int(task[3]), int(task[4]), int(task[5]))
+
+
+def slo_attainment(arrival, latency, deadline, cls=None, return_finish: bool = False):
+    """hexgen_slo_attainment: latency[replica][class], deadline[class]; returns the share of requests served in time
+    (and the finish times when asked)."""
+    n, n_rep, n_cls = len(arrival), len(latency), len(deadline)
+    fin = (C.c_double * max(n, 1))() if return_finish else None
+    a = lib.hexgen_slo_attainment(n, _darr(arrival), None if cls is None else _iarr(cls), n_rep, n_cls,
+                                  _darr([list(r) for r in latency]), _darr(deadline), fin)
+    return (a, list(fin)[:n]) if return_finish else a
+
+
+def sched_draw(seed: int, counter: int) -> int:
+    return int(lib.hexgen_sched_draw(seed, counter))
+
+
+def sched_initial_groups(pool: dict):
+    """hexgen_sched_initial_groups: the K-means / elbow start of the search, a list of count vectors."""
+    p, _keep = _pool_struct(pool)
+    nt = len(pool["count"])
+    out = (C.c_int * (nt * nt))()
+    n = lib.hexgen_sched_initial_groups(C.byref(p), out)
+    return [[out[g * nt + k] for k in range(nt)] for g in range(n)]
+
+
+def sched_plan_group(pool: dict, task, tau, total_layers: int, max_stages: int, pow2_degrees_only: bool = False):
+    """hexgen_sched_plan_group: (latency, layers per stage, [(type, degree) per stage]) of the group's best pipeline."""
+    p, _keep = _pool_struct(pool)
+    t = _task_struct(task)
+    ns = C.c_int(0)
+    lay, ty, cn = (C.c_int * max_stages)(), (C.c_int * max_stages)(), (C.c_int * max_stages)()
+    cost = lib.hexgen_sched_plan_group(C.byref(p), C.byref(t), _iarr(tau), total_layers, max_stages, int(pow2_degrees_only),
+                                       C.byref(ns), lay, ty, cn)
+    return cost, [lay[j] for j in range(ns.value)], [(ty[j], cn[j]) for j in range(ns.value)]
+
+
+def sched_search(pool: dict, task, total_layers: int, model_bytes: float, max_stages: int, arrival, deadline: float,
+                 seed: int, n_iter: int, pop_size: int, pow2_degrees_only: bool = False, max_group_states: int = 1 << 14):
+    """hexgen_sched_search: returns {"attainment", "groups": [{"tau", "latency", "layers", "stages"}], "history"}."""
+    p, _keep = _pool_struct(pool)
+    t = _task_struct(task)
+    nt = len(pool["count"])
+    cfg = _Search(total_layers, float(model_bytes), max_stages, int(pow2_degrees_only), seed, n_iter, pop_size,
+                  max_group_states)
+    max_groups = max(1, sum(pool["count"]))
+    ng = C.c_int(0)
+    tau = (C.c_int * (max_groups * nt))()
+    lat = (C.c_double * max_groups)()
+    gs = (C.c_int * max_groups)()
+    lay, ty, cn = [(C.c_int * (max_groups * max_stages))() for _ in range(3)]
+    hist = (C.c_double * max(n_iter, 1))()
+    score = lib.hexgen_sched_search(C.byref(p), C.byref(t), C.byref(cfg), len(arrival), _darr(arrival), float(deadline),
+                                    max_groups, C.byref(ng), tau, lat, gs, lay, ty, cn, hist)
+    groups = []
+    for g in range(ng.value):
+        o = g * max_stages
+        groups.append({"tau": [tau[g * nt + k] for k in range(nt)], "latency": lat[g],
+                       "layers": [lay[o + j] for j in range(gs[g])],
+                       "stages": [(ty[o + j], cn[o + j]) for j in range(gs[g])]})
+    return {"attainment": score, "groups": groups, "history": list(hist)[:n_iter]}
 
 
 def sched_merge(t1, t2):

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhexgen.so")
 
-SOURCES = ["stage.hip", "cost_model.hip", "scheduler.hip", "kernels_layout.hip", "kernels_bf16_decode.hip", "kernels_bf16_gemm.hip",
+SOURCES = ["stage.hip", "cost_model.hip", "scheduler.hip", "search.hip", "kernels_layout.hip", "kernels_bf16_decode.hip", "kernels_bf16_gemm.hip",
            "kernels_bf16_attn.hip", "kernels_f32.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

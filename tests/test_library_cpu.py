@@ -221,3 +221,134 @@ def test_pipeline_layout_dp_at_sizes_enumeration_cannot_reach():
             c2 = sum(sch.stage_cost(pool, task, layers[j], k, n) for j, (k, n) in enumerate(cand))
             c2 += sum(sch.hop_cost(pool, task, cand[j][0], cand[j + 1][0]) for j in range(S - 1))
             assert c2 >= cost * (1 - 1e-12)
+
+
+# ---- SLO attainment and the search over deployments: product against the oracles -----------------------------------
+def test_slo_attainment_equals_oracle():
+    import numpy as np
+
+    from oracle import slo_oracle as slo
+    from workloads import serving
+    rng = np.random.default_rng(23)
+    for trial in range(30):
+        n, n_rep, n_cls = int(rng.integers(1, 400)), int(rng.integers(1, 7)), int(rng.integers(1, 4))
+        arrival = serving.poisson_arrivals(float(rng.uniform(0.2, 5.0)), n, trial)
+        if trial % 5 == 0:
+            arrival = sorted(float(round(a, 1)) for a in arrival)           # bursts: several requests at one instant
+        latency = rng.uniform(0.2, 3.0, (n_rep, n_cls)).tolist()
+        if trial % 3 == 0:
+            latency[-1] = list(latency[0])                                   # identical replicas: ties
+        deadline = rng.uniform(0.5, 6.0, n_cls).tolist()
+        cls = None if n_cls == 1 else [int(c) for c in rng.integers(0, n_cls, n)]
+        got, fin = hx.slo_attainment(arrival, latency, deadline, cls, return_finish=True)
+        assert fin == slo.simulate(arrival, latency, cls)                    # same sums in the same order: bit-identical
+        assert got == slo.attainment(arrival, latency, deadline, cls)
+
+
+def test_slo_attainment_rejects_invalid_arguments():
+    import math
+    assert math.isnan(hx.slo_attainment([], [[1.0]], [1.0]))
+    assert math.isnan(hx.slo_attainment([1.0, 0.5], [[1.0]], [1.0]))               # unsorted
+    assert math.isnan(hx.slo_attainment([-1.0], [[1.0]], [1.0]))
+    assert math.isnan(hx.slo_attainment([0.0], [[0.0]], [1.0]))                    # a latency of zero
+    assert math.isnan(hx.slo_attainment([0.0], [[1.0]], [1.0], cls=[1]))           # class out of range
+    assert math.isnan(hx.slo_attainment([float("nan")], [[1.0]], [1.0]))
+    assert hx.slo_attainment([0.0], [[1.0]], [1.0]) == 1.0
+
+
+def _check_plan(pool, task, tau, n_layers, cost, layers, stages, ref):
+    """The plan is the oracle's, or (two stages of equal cost swapped: several plans are optimal) another feasible plan
+    of the group that the oracle's cost functions price the same."""
+    from oracle import sched_oracle as sch
+    if layers == ref[1] and stages == [tuple(s) for s in ref[2]]:
+        return
+    assert sum(layers) == n_layers and min(layers) >= 1 and len(layers) == len(stages)
+    assert all(sum(n for k, n in stages if k == t) <= tau[t] for t in range(len(tau))) and all(n >= 1 for _, n in stages)
+    total = sum(sch.stage_cost(pool, task, layers[j], k, n) for j, (k, n) in enumerate(stages))
+    total += sum(sch.hop_cost(pool, task, stages[j][0], stages[j + 1][0]) for j in range(len(stages) - 1))
+    assert abs(total - ref[0]) <= 1e-12 * ref[0] and abs(total - cost) <= 1e-12 * cost
+
+
+def test_search_pieces_equal_oracle():
+    import math
+
+    import numpy as np
+
+    from oracle import search_oracle as srch
+    from workloads import serving
+    for seed in (0, 99, 12345, 2 ** 63 + 5):
+        assert [hx.sched_draw(seed, c) for c in range(50)] == [srch.draw(seed, c) for c in range(50)]
+    for kind in ("full_price", "half_price"):
+        pool = serving.hetero_pool(kind)
+        assert hx.sched_initial_groups(pool) == srch.initial_groups(pool)
+    rng = np.random.default_rng(3)
+    for seed in range(12):
+        pool = serving.tiny_pool(seed, int(rng.integers(1, 6)), 4, two_regions=bool(seed % 3))
+        assert hx.sched_initial_groups(pool) == srch.initial_groups(pool)
+    assert hx.sched_initial_groups(dict(serving.tiny_pool(1, 3), count=[0, 0, 0])) == []
+    task = (4096, 12.0, 2, 1, 128, 32)
+    for seed in range(6):
+        pool = serving.tiny_pool(seed, 3, 3)
+        pool["mem"] = [m / 8 for m in pool["mem"]]
+        for tau in (pool["count"], [1, 1, 0], [0, 1, 1], [pool["count"][0], 0, 1]):
+            for pow2 in (False, True):
+                ref = srch.plan_group(pool, task, tau, 16, 3, degrees={1, 2, 4} if pow2 else None)
+                cost, layers, stages = hx.sched_plan_group(pool, task, tau, 16, 3, pow2)
+                if ref[0] == math.inf:
+                    assert cost == math.inf and layers == []
+                    continue
+                assert abs(cost - ref[0]) <= 1e-12 * ref[0]
+                _check_plan(pool, task, tau, 16, cost, layers, stages, ref)
+
+
+def test_search_equals_oracle():
+    import math
+
+    from oracle import search_oracle as srch
+    from workloads import serving
+    task = (4096, 12.0, 2, 1, 128, 32)
+    n_layers = 16
+    model_bytes = n_layers * 12 * 4096 ** 2 * 2
+    improved = 0
+    for seed in (1, 2, 4, 5, 7):
+        pool = serving.tiny_pool(seed, 3, 3)
+        pool["mem"] = [m / 8 for m in pool["mem"]]
+        whole = hx.sched_plan_group(pool, task, pool["count"], n_layers, 3)[0]
+        arrival = serving.poisson_arrivals(1.2 / whole, 150, seed)
+        for pop in (1, 4):
+            ref = srch.search(pool, task, n_layers, model_bytes, 3, arrival, 2.5 * whole, seed, 60, pop)
+            got = hx.sched_search(pool, task, n_layers, model_bytes, 3, arrival, 2.5 * whole, seed, 60, pop)
+            assert got["history"] == ref["history"] and got["attainment"] == ref["attainment"]
+            assert [g["tau"] for g in got["groups"]] == [g["tau"] for g in ref["groups"]]
+            for a, b in zip(got["groups"], ref["groups"]):
+                assert abs(a["latency"] - b["latency"]) <= 1e-12 * b["latency"]
+                _check_plan(pool, task, a["tau"], n_layers, a["latency"], a["layers"], a["stages"],
+                            (b["latency"], b["layers"], b["stages"]))
+            improved += ref["history"][-1] > ref["history"][0] or ref["history"][0] == 1.0
+    assert improved >= 4
+    # a pool that cannot hold the model at all
+    pool = serving.tiny_pool(1, 2, 2)
+    assert math.isnan(hx.sched_search(pool, task, n_layers, 1e15, 3, [0.0, 1.0], 1.0, 0, 5, 2)["attainment"])
+
+
+def test_search_on_the_large_pool_keeps_its_invariants():
+    from workloads import serving
+    pool = serving.hetero_pool("half_price")
+    task = (8192, 12.0, 2, 1, 128, 32)
+    n_layers, model_bytes = 80, 80 * 12 * 8192 ** 2 * 2
+    start = hx.sched_initial_groups(pool)
+    lat0 = [hx.sched_plan_group(pool, task, g, n_layers, 8, True)[0] for g in start]
+    arrival = serving.poisson_arrivals(0.5, 300, 7)
+    res = hx.sched_search(pool, task, n_layers, model_bytes, 8, arrival, 5 * min(lat0), 11, 150, 8, True)
+    groups = [g["tau"] for g in res["groups"]]
+    assert [sum(g[k] for g in groups) for k in range(3)] == pool["count"]
+    assert all(b >= a for a, b in zip(res["history"], res["history"][1:]))
+    assert res["attainment"] == res["history"][-1] >= hx.slo_attainment(arrival, [[x] for x in lat0], [5 * min(lat0)])
+    for g in res["groups"]:
+        assert sum(g["layers"]) == n_layers and all(n in (1, 2, 4, 8) for _, n in g["stages"])
+        used = [sum(n for k, n in g["stages"] if k == t) for t in range(3)]
+        assert all(u <= c for u, c in zip(used, g["tau"]))
+        # the group's latency is what the layout routine gives for its plan
+        cost, _ = hx.sched_pipeline_layout(dict(pool, count=g["tau"]), task, g["layers"], True)
+        assert abs(cost - g["latency"]) <= 1e-12 * cost
+    assert res["attainment"] == hx.slo_attainment(arrival, [[g["latency"]] for g in res["groups"]], [5 * min(lat0)])

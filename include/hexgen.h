@@ -299,7 +299,8 @@ int hexgen_sched_group_can_hold(int n_types, const int *tau, const double *mem_b
  * hexgen_sched_initial_groups: the start of the search (Section 4.3 "Initialization"): weighted K-means over the GPU
  * types' rows of the hop matrices (latencies and per-byte times, each scaled by its largest entry), the number of
  * groups from the elbow of the inertia curve; every cluster of types becomes one group.  groups[n_types][n_types]
- * receives one count vector per group; returns the number of groups, 0 for invalid arguments or an empty pool.
+ * receives one count vector per group; returns the number of groups, 0 for invalid arguments (among them a hop
+ * latency < 0 or a hop bandwidth <= 0 between types that are present) or an empty pool.
  *
  * hexgen_sched_plan_group: the pipeline a group tau (tau[k] <= count[k]) would run (Section 4.3 "Determine the
  * pipeline partitions"): for every stage count S <= min(max_stages, GPUs, layers) the even layer partition, the

@@ -43,6 +43,17 @@ bool pool_ok(const hexgen_pool_t *p) {
     return true;
 }
 
+// the hop links between the GPU types that are present must be usable numbers: latency >= 0, bandwidth > 0
+bool links_ok(const hexgen_pool_t *p) {
+    for (int a = 0; a < p->n_types; ++a)
+        for (int b = 0; b < p->n_types; ++b) {
+            if (p->count[a] == 0 || p->count[b] == 0) continue;
+            const double al = p->pp_alpha[a * p->n_types + b], be = p->pp_beta[a * p->n_types + b];
+            if (!(al >= 0.0) || !(be > 0.0) || std::isinf(al) || std::isinf(be)) return false;
+        }
+    return true;
+}
+
 int total(const Tau &t) {
     int s = 0;
     for (int v : t) s += v;
@@ -246,7 +257,7 @@ double hexgen_slo_attainment(int n_req, const double *arrival, const int *cls, i
 unsigned long long hexgen_sched_draw(unsigned long long seed, unsigned long long counter) { return draw(seed, counter); }
 
 int hexgen_sched_initial_groups(const hexgen_pool_t *pool, int *groups) {
-    if (!pool_ok(pool) || !groups) return 0;
+    if (!pool_ok(pool) || !links_ok(pool) || !groups) return 0;
     const std::vector<Tau> g = initial_groups(pool);
     for (size_t i = 0; i < g.size(); ++i)
         for (int k = 0; k < pool->n_types; ++k) groups[i * pool->n_types + k] = g[i][k];
@@ -275,7 +286,7 @@ double hexgen_sched_search(const hexgen_pool_t *pool, const hexgen_task_t *task,
                            const double *arrival, double deadline, int max_groups, int *n_groups, int *group_tau,
                            double *group_latency, int *group_n_stages, int *stage_layers, int *stage_type,
                            int *stage_count, double *history) {
-    if (!pool_ok(pool) || !task || !cfg || n_req <= 0 || !arrival || !(deadline > 0.0) || max_groups <= 0 || !n_groups ||
+    if (!pool_ok(pool) || !links_ok(pool) || !task || !cfg || n_req <= 0 || !arrival || !(deadline > 0.0) || max_groups <= 0 || !n_groups ||
         !group_tau || cfg->total_layers <= 0 || cfg->max_stages <= 0 || cfg->max_stages > 64 || cfg->n_iter < 0 ||
         cfg->pop_size <= 0 || cfg->max_group_states <= 0)
         return kNaN;

@@ -326,6 +326,11 @@ def test_search_equals_oracle():
                             (b["latency"], b["layers"], b["stages"]))
             improved += ref["history"][-1] > ref["history"][0] or ref["history"][0] == 1.0
     assert improved >= 4
+    # unusable hop links are rejected (the K-means features would not be numbers)
+    bad = serving.tiny_pool(1, 2, 2)
+    bad["pp_beta"][0][1] = 0.0
+    assert hx.sched_initial_groups(bad) == []
+    assert math.isnan(hx.sched_search(bad, task, n_layers, model_bytes, 3, [0.0, 1.0], 1.0, 0, 5, 2)["attainment"])
     # a pool that cannot hold the model at all
     pool = serving.tiny_pool(1, 2, 2)
     assert math.isnan(hx.sched_search(pool, task, n_layers, 1e15, 3, [0.0, 1.0], 1.0, 0, 5, 2)["attainment"])

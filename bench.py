@@ -44,6 +44,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill leg (second workload)")
     ap.add_argument("--no-head", action="store_true", help="skip the LM-head leg (model end next to the last stage)")
+    ap.add_argument("--no-sched", action="store_true", help="skip the host-only scheduler-search leg")
     ap.add_argument("--calibrate", action="store_true",
                     help="measure what a plain streaming kernel and a register-resident MFMA loop sustain, then exit")
     args = ap.parse_args()
@@ -180,7 +181,32 @@ def main():
         result["lm_head"] = head_leg(torch, hx, generate)
     if "prefill" in result:
         result["cost_model"] = cost_model_alignment(torch, hx, cfg, result)
+    if not args.no_sched:
+        result["scheduler"] = scheduler_leg(hx)
     print(json.dumps(result), flush=True)
+
+
+def scheduler_leg(hx):
+    """Host-only leg: the search over deployments (Section 4.3) on a synthetic pool in the shape of the paper's
+    full-price rental (58 GPUs, 6 types), Llama-2-70B-sized task, 400 Poisson arrivals at 2 requests/s, deadline
+    5 x the fastest start group; wall time of the library call on one host core."""
+    import time
+
+    from workloads import serving
+    pool = serving.hetero_pool("full_price")
+    task, n_layers = (8192, 12.0, 2, 1, 128, 32), 80
+    model_bytes = n_layers * 12 * 8192 ** 2 * 2
+    start = hx.sched_initial_groups(pool)
+    lat0 = [hx.sched_plan_group(pool, task, g, n_layers, 8, True)[0] for g in start]
+    arrival = serving.poisson_arrivals(2.0, 400, 7)
+    deadline = 5 * min(lat0)
+    t0 = time.perf_counter()
+    res = hx.sched_search(pool, task, n_layers, model_bytes, 8, arrival, deadline, 11, 400, 8, True)
+    dt = time.perf_counter() - t0
+    return {"pool": "synthetic full-price shape, 58 GPUs of 6 types", "steps": 400, "population": 8,
+            "search_s": round(dt, 2), "start_groups": len(start),
+            "start_attainment": round(hx.slo_attainment(arrival, [[x] for x in lat0], [deadline]), 4),
+            "groups": len(res["groups"]), "attainment": round(res["attainment"], 4)}
 
 
 MFMA_PEAK_TFLOPS = 2516.6      # MI355X published dense bf16 rate

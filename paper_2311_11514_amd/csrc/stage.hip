@@ -559,8 +559,13 @@ hexgen_status_t hexgen_stage_create(int hidden, int n_heads, int n_kv_heads, int
     st->qw = hq_l * d;
     st->nqkv = (hq_l + 2 * hkv_l) * d;
     st->dtype = dtype;
-    st->layers.resize(n_layers);
-    st->taps.assign(n_layers, nullptr);
+    try {       // no exception may cross the C boundary
+        st->layers.resize(n_layers);
+        st->taps.assign(n_layers, nullptr);
+    } catch (...) {
+        delete st;
+        return HEXGEN_ERR_OOM;
+    }
     *out = st;
     return HEXGEN_OK;
 }

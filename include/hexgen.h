@@ -59,6 +59,8 @@ const char *hexgen_status_string(hexgen_status_t s);
 hexgen_status_t hexgen_stage_create(int hidden, int n_heads, int n_kv_heads, int ffn, int n_layers,
                                     int tp_degree, int tp_rank, hexgen_dtype_t dtype,
                                     hexgen_stage_t **out);
+/* Call set_params before hexgen_kv_cache_create: a cache carries rotation tables built for the rope_theta of that
+ * moment, and prefill / decode / run_sublayer return HEXGEN_ERR_STATE for a cache created under another rope_theta. */
 hexgen_status_t hexgen_stage_set_params(hexgen_stage_t *st, float rms_eps, float rope_theta);
 void            hexgen_stage_destroy(hexgen_stage_t *st);
 
@@ -146,39 +148,6 @@ hexgen_status_t hexgen_kv_cache_get_lengths(hexgen_kv_cache_t *kv, int32_t *lens
  * [rows, hidden] is copied to `h_dump` (device).  NULL removes the tap.
  */
 hexgen_status_t hexgen_stage_set_tap(hexgen_stage_t *st, int layer, void *h_dump);
-
-/* Measurement surface.  While enabled, prefill / decode record HIP events on the caller's stream
- * around each projection launch, so per-kernel time can be read without an external profiler
- * (this costs a few microseconds per timed launch: enable it for measurement passes only).
- * Slots: 0 QKV projection, 1 W_O, 2 W1/W3 (+SwiGLU), 3 W2, 4 attention, 5 the whole call.
- * enable(slot_mask): bit i selects slot i (0 = off, 63 = all); synchronises and clears earlier records.
- * read() synchronises and returns the summed time in milliseconds and the number of timed launches.
- */
-hexgen_status_t hexgen_stage_profile_enable(hexgen_stage_t *st, int slot_mask);
-hexgen_status_t hexgen_stage_profile_read(hexgen_stage_t *st, int slot, double *total_ms, int64_t *count);
-/* The W1/W3 (+SwiGLU) decode projection of every layer, back to back, `reps` times over, between two HIP events on
- * `stream`: total_ms / launches is that kernel's duration without the per-launch event overhead of the slots above
- * (every launch streams a different layer's weights, as in a decode step).  Runs on the operands the last decode call
- * left in the workspace and overwrites only the workspace's FFN operand; HEXGEN_ERR_STATE before the first decode
- * call of at most 32 rows or on an fp32 stage.  Synchronises the stream.
- */
-hexgen_status_t hexgen_stage_time_w13_decode(hexgen_stage_t *st, int reps, double *total_ms, int64_t *launches,
-                                             void *stream);
-
-/* HBM calibration kernels of known size (used by the benchmark and to scale profiler byte counters):
- * copy moves `bytes` (multiple of 16) from src to dst; read streams `bytes` from src and writes at most one
- * float per block to `sink` (device, >= blocks floats).  `blocks` = grid size (256-thread blocks).
- */
-hexgen_status_t hexgen_stream_copy(void *dst, const void *src, int64_t bytes, int blocks, void *stream);
-hexgen_status_t hexgen_stream_read(const void *src, void *sink, int64_t bytes, int blocks, void *stream);
-
-/* Matrix-core calibration: `blocks` 4-wave blocks each run `iters` k-steps of a 128 x 128 x 32 wave tile out of
- * registers (2^20 flop per wave and iteration).  variant 0: 16x16x32 bf16 MFMA, 1: 32x32x16 bf16 MFMA, 2 / 3: the
- * same plus the LDS fragment reads a GEMM issues; 4 .. 7: variants 0 .. 3 on operands with random signs and
- * mantissas instead of 1.0 (the power the matrix cores draw, and with it the clock the chip holds, depends on the
- * operand bits; run tens of milliseconds for a steady figure).  `sink`: device, >= 256 floats.  Time it with events.
- */
-hexgen_status_t hexgen_mfma_probe(int variant, void *sink, int iters, int blocks, void *stream);
 
 /* ---- the model's ends, adjacent to the first and the last stage -------------------------------------------
  * Paper Section 2: a request enters as prompt tokens and leaves as generated tokens, one per decode step.  These
@@ -343,15 +312,6 @@ double hexgen_sched_search(const hexgen_pool_t *pool, const hexgen_task_t *task,
                            const double *arrival, double deadline, int max_groups, int *n_groups, int *group_tau,
                            double *group_latency, int *group_n_stages, int *stage_layers, int *stage_type,
                            int *stage_count, double *history);
-
-/* Measurement and test hook, process-wide: force one tile configuration of the prefill projection GEMM instead of
- * the choice by shape.  code = 10 * a + b names the block tile: 88 = 256 x 256 on 4 waves, 98 = 256 x 256 on 8 waves,
- * 84 = 256 x 128, 48 = 128 x 256, 94 / 49 = 128 x 256 on 8 waves (2 x 4 / 4 x 2 wave grid), 44 = 128 x 128,
- * 72 = 448 features x 128 tokens on 4 waves; 0 restores the default.  (Residual-epilogue launches need 128 features
- * per wave and fall back to 84, from 72 to 98.)
- * HEXGEN_ERR_INVALID_ARG for any other code.
- */
-hexgen_status_t hexgen_set_gemm_tile(int code);
 
 /* Bytes of device memory the stage holds for weights (after repacking), for reporting. */
 int64_t hexgen_stage_weight_bytes(const hexgen_stage_t *st);

@@ -181,12 +181,13 @@ class OracleStage:
         return u @ W["w2"]
 
     # ---- one layer, chosen output rows only (full-size workloads) ------------------------------------
-    def layer_rows(self, layer: int, h_seq, rows: Sequence[int]):
+    def layer_rows(self, layer: int, h_seq, rows: Sequence[int], split_ffn: bool = False):
         """Solo-mode output of `layer` for ONE sequence given the residual stream h_seq [S,H] entering the
         layer (positions 0..S-1), evaluated only at the positions in `rows`.  Same definition as
         attn_partial / ffn_partial: K and V are formed for every position (they are needed by later rows),
         the query, attention, W_O, residual and FFN only for the chosen rows.  Returns (h_out [len(rows),H]
-        = residual stream after the layer, K [S,hkv_l,d] after rotation, V [S,hkv_l,d])."""
+        = residual stream after the layer, K [S,hkv_l,d] after rotation, V [S,hkv_l,d]); with split_ffn the
+        first element is the pair (h_mid, P_ffn) a stage returns for its last layer instead of their sum."""
         W = self.layers[layer]
         h = _f64(h_seq)
         S = h.shape[0]
@@ -204,7 +205,8 @@ class OracleStage:
                 w = softmax((K[: i + 1, c, :] @ q[a, j]) * scale)
                 o[a, j] = w @ V[: i + 1, c, :]
         h_mid = h[rows] + o.reshape(len(rows), self.hq_l * self.d) @ W["wo"]
-        return h_mid + self.ffn_partial(layer, h_mid), K, V
+        p = self.ffn_partial(layer, h_mid)
+        return ((h_mid, p) if split_ffn else h_mid + p), K, V
 
     # ---- solo mode: this rank alone ---------------------------------------------------
     def forward(self, cache: KVCache, hidden_in, seq_of_row: Sequence[int], taps: dict = None):

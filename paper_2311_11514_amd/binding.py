@@ -1,4 +1,5 @@
-"""ctypes binding of libhexgen.so: argument marshalling only, same names as include/hexgen.h.
+"""ctypes binding of libhexgen.so: argument marshalling only, same names as include/hexgen.h
+(the paper's calls) and include/hexgen_bench.h (measurement-only entry points).
 
 torch is used for device memory and streams; every step of the stage runs in the library's HIP
 kernels.  There is no fallback: if the shared library is missing, importing this module raises.
@@ -18,7 +19,7 @@ HEXGEN_F32, HEXGEN_BF16 = 0, 1
 STATUS_NAMES = {0: "HEXGEN_OK", 1: "HEXGEN_ERR_INVALID_ARG", 2: "HEXGEN_ERR_SHAPE", 3: "HEXGEN_ERR_STATE",
                 4: "HEXGEN_ERR_CAPACITY", 5: "HEXGEN_ERR_OOM", 6: "HEXGEN_ERR_DEVICE"}
 
-# every symbol include/hexgen.h declares: name -> (restype, argtypes)
+# every symbol include/*.h declares: name -> (restype, argtypes)
 _vp, _i, _i64, _f = C.c_void_p, C.c_int, C.c_int64, C.c_float
 _ip = C.POINTER(C.c_int32)
 _fp = C.POINTER(C.c_float)
@@ -191,7 +192,7 @@ class Stage:
         _check(lib.hexgen_stage_profile_enable(self.handle, mask), "hexgen_stage_profile_enable")
 
     def profile_read(self, slot: int):
-        """(total milliseconds, number of timed launches) of a slot; see include/hexgen.h."""
+        """(total milliseconds, number of timed launches) of a slot; see include/hexgen_bench.h."""
         ms, n = C.c_double(), C.c_int64()
         _check(lib.hexgen_stage_profile_read(self.handle, slot, C.byref(ms), C.byref(n)),
                "hexgen_stage_profile_read")

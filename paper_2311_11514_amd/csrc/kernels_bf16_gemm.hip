@@ -296,7 +296,10 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
     // offset, LDS destination in M0), which the compiler does not select for this instruction by itself: it
     // would spend a 64-bit vector add per load inside the MFMA stream.  The compiler does not see these
     // loads in its own vmcnt bookkeeping; every wait on them is explicit (HX_WAIT_VM), and vmcnt is drained
-    // before the epilogue issues ordinary loads.
+    // before the epilogue issues ordinary loads.  M0 is written here and cannot be named as clobbered: it is a
+    // reserved register (the compiler rejects it in a clobber list as undefined behaviour) that the compiler never
+    // allocates and only sets itself immediately in front of an instruction of its own that reads it; this kernel
+    // contains no such instruction (no LDS-direct builtin, no movrel, no message), so nothing relies on its value.
     const unsigned lane_bytes = (unsigned)lane * 16u;
     auto issue_one = [&](int kt, int x) {
         const int kc = min(kt, k_len - 1);

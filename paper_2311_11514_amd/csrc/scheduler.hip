@@ -39,7 +39,7 @@ double stage_cost(const hexgen_pool_t *p, const hexgen_task_t *t, int layers, in
 extern "C" {
 
 double hexgen_sched_pipeline_layout(const hexgen_pool_t *pool, const hexgen_task_t *task, int n_stages, const int *layers,
-                                    int pow2_degrees_only, int *stage_type, int *stage_count) {
+                                    int pow2_degrees_only, int *stage_type, int *stage_count) try {
     if (bad_pool(pool) || !task || n_stages <= 0 || n_stages > 64 || !layers) return kNaN;
     for (int j = 0; j < n_stages; ++j)
         if (layers[j] <= 0) return kNaN;
@@ -104,6 +104,8 @@ double hexgen_sched_pipeline_layout(const hexgen_pool_t *pool, const hexgen_task
         }
     }
     return best;
+} catch (...) {      // no exception (an allocation failure) may cross the C boundary
+    return kNaN;
 }
 
 int hexgen_sched_merge(int n_types, const int *tau1, const int *tau2, int *out) {
@@ -132,7 +134,7 @@ int hexgen_sched_group_can_hold(int n_types, const int *tau, const double *mem_b
     return total >= model_bytes ? 1 : 0;
 }
 
-int hexgen_sched_repartition_layers(int total_layers, int n_stages, const double *stage_mem, int *layers_out) {
+int hexgen_sched_repartition_layers(int total_layers, int n_stages, const double *stage_mem, int *layers_out) try {
     if (n_stages <= 0 || total_layers < n_stages || !stage_mem || !layers_out) return 0;
     double tot = 0.0;
     for (int j = 0; j < n_stages; ++j) {
@@ -157,6 +159,8 @@ int hexgen_sched_repartition_layers(int total_layers, int n_stages, const double
         frac[pick] = -1.0;
     }
     return 1;
+} catch (...) {      // no exception (an allocation failure) may cross the C boundary
+    return 0;
 }
 
 }  // extern "C"

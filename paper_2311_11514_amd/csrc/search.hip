@@ -243,7 +243,7 @@ uint64_t draw(uint64_t seed, uint64_t counter) {
 extern "C" {
 
 double hexgen_slo_attainment(int n_req, const double *arrival, const int *cls, int n_replicas, int n_classes,
-                             const double *latency, const double *deadline, double *finish_out) {
+                             const double *latency, const double *deadline, double *finish_out) try {
     if (n_req <= 0 || !arrival || n_replicas <= 0 || n_classes <= 0 || !latency || !deadline) return kNaN;
     for (int q = 0; q < n_req; ++q) {
         if (!(arrival[q] >= (q ? arrival[q - 1] : 0.0))) return kNaN;          // sorted, non-negative, no NaN
@@ -252,21 +252,25 @@ double hexgen_slo_attainment(int n_req, const double *arrival, const int *cls, i
     for (int i = 0; i < n_replicas * n_classes; ++i)
         if (!(latency[i] > 0.0)) return kNaN;
     return attainment(n_req, arrival, cls, n_replicas, n_classes, latency, deadline, finish_out);
+} catch (...) {      // no exception (an allocation failure) may cross the C boundary
+    return kNaN;
 }
 
 unsigned long long hexgen_sched_draw(unsigned long long seed, unsigned long long counter) { return draw(seed, counter); }
 
-int hexgen_sched_initial_groups(const hexgen_pool_t *pool, int *groups) {
+int hexgen_sched_initial_groups(const hexgen_pool_t *pool, int *groups) try {
     if (!pool_ok(pool) || !links_ok(pool) || !groups) return 0;
     const std::vector<Tau> g = initial_groups(pool);
     for (size_t i = 0; i < g.size(); ++i)
         for (int k = 0; k < pool->n_types; ++k) groups[i * pool->n_types + k] = g[i][k];
     return (int)g.size();
+} catch (...) {      // no exception (an allocation failure) may cross the C boundary
+    return 0;
 }
 
 double hexgen_sched_plan_group(const hexgen_pool_t *pool, const hexgen_task_t *task, const int *tau, int total_layers,
                                int max_stages, int pow2_degrees_only, int *n_stages, int *layers, int *stage_type,
-                               int *stage_count) {
+                               int *stage_count) try {
     if (!pool_ok(pool) || !task || !tau || total_layers <= 0 || max_stages <= 0 || max_stages > 64) return kNaN;
     Tau t(tau, tau + pool->n_types);
     for (int k = 0; k < pool->n_types; ++k)
@@ -280,12 +284,14 @@ double hexgen_sched_plan_group(const hexgen_pool_t *pool, const hexgen_task_t *t
         if (stage_count) stage_count[j] = p.count[j];
     }
     return p.latency;
+} catch (...) {      // no exception (an allocation failure) may cross the C boundary
+    return kNaN;
 }
 
 double hexgen_sched_search(const hexgen_pool_t *pool, const hexgen_task_t *task, const hexgen_search_t *cfg, int n_req,
                            const double *arrival, double deadline, int max_groups, int *n_groups, int *group_tau,
                            double *group_latency, int *group_n_stages, int *stage_layers, int *stage_type,
-                           int *stage_count, double *history) {
+                           int *stage_count, double *history) try {
     if (!pool_ok(pool) || !links_ok(pool) || !task || !cfg || n_req <= 0 || !arrival || !(deadline > 0.0) || max_groups <= 0 || !n_groups ||
         !group_tau || cfg->total_layers <= 0 || cfg->max_stages <= 0 || cfg->max_stages > 64 || cfg->n_iter < 0 ||
         cfg->pop_size <= 0 || cfg->max_group_states <= 0)
@@ -409,6 +415,8 @@ double hexgen_sched_search(const hexgen_pool_t *pool, const hexgen_task_t *task,
         }
     }
     return best.score;
+} catch (...) {      // no exception (an allocation failure) may cross the C boundary
+    return kNaN;
 }
 
 }  // extern "C"

@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/hexgen.h"
+#include "../../include/hexgen_bench.h"
 #include "kernels.h"
 
 #define HX_HIP(expr)                                                          \
@@ -194,6 +195,9 @@ hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
                          hipHostMallocDefault));
     w.cap_rows = rows;
     st->ws_batch_cap = batch;
+    // the zero fills above ran on the null stream; the caller's stream may be a non-blocking one that does not
+    // order itself behind it
+    HX_HIP(hipDeviceSynchronize());
     return HEXGEN_OK;
 }
 
@@ -504,6 +508,11 @@ hexgen_status_t check_loaded(const hexgen_stage *st) {
     for (const Layer &l : st->layers)
         if (!l.loaded) return HEXGEN_ERR_STATE;
     return HEXGEN_OK;
+}
+
+// the cache's rotation tables were built for the theta the stage had when the cache was created
+hexgen_status_t check_rope(const hexgen_stage *st, const hexgen_kv_cache *kv) {
+    return kv->rope_theta_built == st->theta ? HEXGEN_OK : HEXGEN_ERR_STATE;
 }
 
 hexgen_status_t upload_lens(hexgen_kv_cache *kv) {
@@ -849,7 +858,12 @@ hexgen_status_t hexgen_stage_prefill(hexgen_stage_t *st, hexgen_kv_cache_t *kv, 
         if (seq_lens[i] < 1) return HEXGEN_ERR_INVALID_ARG;
         if (seq_lens[i] > kv->max_seq) return HEXGEN_ERR_CAPACITY;
     }
+    HX_TRY(check_rope(st, kv));
     hipStream_t s = static_cast<hipStream_t>(stream);
+    long total = 0;
+    for (int i = 0; i < batch; ++i) total += seq_lens[i];
+    if (total > 0x3fffffff) return HEXGEN_ERR_CAPACITY;
+    HX_TRY(ensure_workspace(st, (int)total, batch));     // every check that can fail comes before the cache is touched
     HX_TRY(hexgen_kv_cache_reset(kv));
     Rows r;
     HX_TRY(setup_rows(st, kv, seq_lens, batch, false, s, &r));      // a prefill always takes the GEMM path
@@ -873,6 +887,7 @@ hexgen_status_t hexgen_stage_decode(hexgen_stage_t *st, hexgen_kv_cache_t *kv, i
     if (!st || !kv || !hidden_in || !out_partial || kv->st != st) return HEXGEN_ERR_INVALID_ARG;
     HX_TRY(check_loaded(st));
     if (!kv->prefilled || kv->batch <= 0 || step != kv->steps) return HEXGEN_ERR_STATE;
+    HX_TRY(check_rope(st, kv));
     hipStream_t s = static_cast<hipStream_t>(stream);
     Rows r;
     HX_TRY(setup_rows(st, kv, nullptr, kv->batch, true, s, &r));
@@ -894,6 +909,7 @@ hexgen_status_t hexgen_stage_run_sublayer(hexgen_stage_t *st, hexgen_kv_cache_t 
     if (!st || !kv || !h_in || !partial_out || kv->st != st) return HEXGEN_ERR_INVALID_ARG;
     if (layer < 0 || layer >= st->L || (which != 0 && which != 1)) return HEXGEN_ERR_INVALID_ARG;
     if (!st->layers[layer].loaded) return HEXGEN_ERR_STATE;
+    HX_TRY(check_rope(st, kv));
     hipStream_t s = static_cast<hipStream_t>(stream);
     Rows r;
     HX_TRY(setup_rows(st, kv, seq_lens, batch, true, s, &r));

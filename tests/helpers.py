@@ -28,6 +28,23 @@ def max_abs_over_l2(gpu, ref) -> float:
     return float(np.max(np.max(np.abs(g - r), axis=1) / np.linalg.norm(r, axis=1)))
 
 
+def check(label: str, gpu, ref, tol: float, per_row_l2: bool = True):
+    """THE gate of the GPU parity tests.  Prints both error metrics of one comparison and asserts
+      G1  max_abs_over_l2 < tol   always (the stated tolerance: largest error relative to the output row's L2 norm);
+      G2  row_rel_err     < tol   as well, unless per_row_l2=False.
+    per_row_l2=False is passed by exactly one family of comparisons: the END-TO-END outputs of the 20-layer
+    prefill workload, where rounding K and V to the bf16 the cache stores -- and nothing else -- already puts G2
+    beyond 2e-2 (tests/test_bf16_kv_floor.py, CPU, oracle only); there every layer is compared on its own,
+    fed the oracle's residual stream, with G2 on.  Returns (G2, G1)."""
+    e2, e1 = row_rel_err(gpu, ref), max_abs_over_l2(gpu, ref)
+    print(f"{label}: per-row L2 err {e2:.3e}, max-abs / row L2 {e1:.3e}"
+          + ("" if per_row_l2 else "  [gate: max-abs / row L2 only]"), flush=True)
+    assert e1 < tol, f"{label}: max-abs / row L2 {e1:.3e} >= {tol}"
+    if per_row_l2:
+        assert e2 < tol, f"{label}: per-row L2 err {e2:.3e} >= {tol}"
+    return e2, e1
+
+
 def torch_dtype(cfg):
     return torch.float32 if cfg.dtype == "f32" else torch.bfloat16
 

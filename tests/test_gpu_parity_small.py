@@ -304,3 +304,61 @@ def test_error_paths_on_device():
         st.decode(kv, 0, x, out)            # sequence 0 is full
     assert e.value.status == 4
     torch.cuda.synchronize()
+
+
+def test_bf16_prefill_and_decode_on_a_side_stream():
+    """A fresh stage used first on a non-default (non-blocking) torch stream: the workspace the first call allocates
+    is zero-filled before any kernel of the call can read it, whatever stream the caller launches on; covers the
+    batched decode path (split partial sums) and the split-KV attention (arrival counters) as well."""
+    cfg = MINI128
+    lens = [1700, 40, 1537]
+    w = _weights(cfg)
+    rank = cfg.tp_ranks[0]
+    ora = make_oracle(cfg, rank, w)
+    oc = ora.new_cache(len(lens))
+    st = make_gpu_stage(cfg, rank, w)
+    side = torch.cuda.Stream()
+    kv = st.kv_cache_create(len(lens), max(lens) + 8)
+    X = generate.hidden_rows(cfg, 77, stream_id=9)
+    p_ref, h_ref = ora.prefill(ora.new_cache(2), X, [50, 27])
+    xin = to_dev(X, cfg)
+    outp, outr = torch.empty_like(xin), torch.empty_like(xin)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        st.prefill(kv, xin, [50, 27], outp, outr, stream=side)
+    side.synchronize()
+    assert row_rel_err(outr.float().cpu().numpy(), h_ref) < TOL["bf16"]
+    assert row_rel_err(outp.float().cpu().numpy(), p_ref) < TOL["bf16"]
+    # decode from long synthetic contexts on the same side stream
+    for l in range(cfg.n_layers):
+        for s, n in enumerate(lens):
+            k, v = generate.synthetic_kv(cfg, l, s, n)
+            kv.fill(l, s, k, v)
+            oc.fill(l, s, k, v)
+    kv.set_lengths(lens)
+    for step in range(2):
+        x = generate.hidden_rows(cfg, len(lens), stream_id=1 + step)
+        p_ref, h_ref = ora.decode(oc, x)
+        xd = to_dev(x, cfg)
+        op, orr = torch.empty_like(xd), torch.empty_like(xd)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            st.decode(kv, step, xd, op, orr, stream=side)
+        side.synchronize()
+        assert row_rel_err(orr.float().cpu().numpy(), h_ref) < TOL["bf16"]
+        assert row_rel_err(op.float().cpu().numpy(), p_ref) < TOL["bf16"]
+
+
+def test_rope_theta_changed_after_cache_creation_is_refused():
+    import paper_2311_11514_amd as hx
+    cfg = MINI64
+    st = make_gpu_stage(cfg, 0, _weights(cfg))
+    kv = st.kv_cache_create(1, 64)
+    assert hx.lib.hexgen_stage_set_params(st.handle, 1e-5, 500000.0) == 0
+    x = to_dev(generate.hidden_rows(cfg, 8), cfg)
+    with pytest.raises(hx.HexgenError) as e:
+        st.prefill(kv, x, [8], torch.empty_like(x), torch.empty_like(x))
+    assert e.value.status == 3          # HEXGEN_ERR_STATE
+    kv2 = st.kv_cache_create(1, 64)     # a cache created under the new theta is accepted
+    st.prefill(kv2, x, [8], torch.empty_like(x), torch.empty_like(x))
+    torch.cuda.synchronize()

@@ -2,6 +2,7 @@
 shapes and arguments without touching a GPU."""
 import ctypes as C
 import os
+import math
 import re
 
 import pytest
@@ -12,9 +13,15 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "hexgen.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(hexgen_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for header in sorted(os.listdir(inc)):
+        if not header.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(hexgen_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported_and_bound():
@@ -22,7 +29,7 @@ def test_every_declared_symbol_is_exported_and_bound():
     assert len(names) >= 19
     raw = C.CDLL(hx.LIB_PATH)
     for n in names:
-        assert hasattr(raw, n), f"{n} declared in hexgen.h but not exported"
+        assert hasattr(raw, n), f"{n} declared in include/*.h but not exported"
         assert n in hx.SIGNATURES, f"{n} has no Python binding signature"
     assert sorted(hx.SIGNATURES) == names
 
@@ -99,6 +106,16 @@ def test_cost_model_functions_match_the_oracle():
     assert math.isnan(hx.cost_comp(8192, 2, 1, 1, 1, 1, [0.0], [1e14]))
     assert math.isnan(hx.cost_comm_tp(8192, 2, 1, 1, 1, 1, [[0, 1e-6], [1e-6, 0]], [[1, 0.0], [1e9, 1]]))
     assert hx.cost_comm_tp(8192, 2, 1, 1, 1, 1, [[0.0]], [[1.0]]) == 0.0
+
+
+def test_cost_model_library_on_the_hand_worked_comm_example():
+    """The library's Eq. 4 / Eq. 5 on the non-uniform links worked by hand (tests/golden/cost_model_comm_worked_example.txt)."""
+    from tests.test_oracle_pins import COMM_EXAMPLE as ex, _golden_cost
+    gold = _golden_cost("cost_model_comm_worked_example.txt")
+    t = ex["task"]
+    args = (t["H"], t["B_type"], t["b"], t["s_in"], t["s_out"])
+    assert math.isclose(hx.cost_comm_tp(*args, 3, ex["tp_alpha"], ex["tp_beta"]), gold["tp_total"], rel_tol=1e-12)
+    assert math.isclose(hx.cost_comm_pp(*args, ex["pp_alpha"], ex["pp_beta"]), gold["pp_total"], rel_tol=1e-12)
 
 
 # ---- pipeline layout DP and search operators against the oracle -------------------------------------------------

@@ -345,6 +345,8 @@ def test_layer_rows_matches_full_layer(tiny_weights):
     got, K, V = st.layer_rows(0, x, rows)
     assert rel(got, full[rows]) < 1e-13
     assert rel(K, cache.k[0][0]) < 1e-13 and rel(V, cache.v[0][0]) < 1e-13
+    (hm, p), _, _ = st.layer_rows(0, x, rows, split_ffn=True)          # the (resid, partial) pair of a last layer
+    assert rel(hm, h_mid[rows]) < 1e-13 and rel(p, st.ffn_partial(0, h_mid)[rows]) < 1e-13
 
 
 # ---- the model's ends: embedding gather and vocabulary-parallel greedy head -------------------------------------
@@ -398,10 +400,10 @@ def test_head_tie_rule_lowest_id_wins_across_ranks():
 
 
 # ---- the paper's cost model (Table 1, Eqs. 3-6) -------------------------------------------------------------------
-def _golden_cost():
+def _golden_cost(name="cost_model_worked_example.txt"):
     import os
     vals = {}
-    for line in open(os.path.join(os.path.dirname(__file__), "golden", "cost_model_worked_example.txt")):
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", name)):
         if line.strip() and not line.startswith("#"):
             k, v = line.split()
             vals[k] = float(v)
@@ -418,6 +420,32 @@ def test_cost_model_worked_example():
     assert math.isclose(co.comp_decode(**args), gold["decode"], rel_tol=1e-12)
     assert math.isclose(gold["scan_term"] + gold["flop_term"], gold["comp_total"], rel_tol=1e-12)
     assert math.isclose(co.mem(8192, 2, 1, 512, 64, 80, 8), gold["mem_bytes"], rel_tol=1e-15)
+
+
+COMM_EXAMPLE = dict(
+    task=dict(H=1024, B_type=2, b=2, s_in=100, s_out=10),
+    tp_alpha=[[7, 5e-5, 6e-5], [1e-5, 7, 2e-5], [4e-5, 2e-5, 7]],
+    tp_beta=[[1, 1e9, 4e9], [2e9, 1, 1e9], [5e8, 4e9, 1]],
+    pp_alpha=[[1e-3, 1e-5], [5e-5, 2e-4]],
+    pp_beta=[[1e10, 1e8], [2e9, 5e9]])
+
+
+def test_cost_model_comm_worked_example_on_non_uniform_links():
+    """Eqs. 4 and 5 by hand on links chosen so that a min instead of the max over devices, a sum that includes
+    d' = d, the same slowest device for both terms, or min alpha / max beta taken separately all give other numbers
+    (tests/golden/cost_model_comm_worked_example.txt)."""
+    from oracle import cost_oracle as co
+    gold = _golden_cost("cost_model_comm_worked_example.txt")
+    ex, t = COMM_EXAMPLE, COMM_EXAMPLE["task"]
+    assert math.isclose(gold["tp_prefill"] + gold["tp_decode"], gold["tp_total"], rel_tol=1e-12)
+    assert math.isclose(gold["pp_prefill"] + gold["pp_decode"], gold["pp_total"], rel_tol=1e-12)
+    assert math.isclose(co.comm_tp(l=3, alpha=ex["tp_alpha"], beta=ex["tp_beta"], **t), gold["tp_total"], rel_tol=1e-12)
+    # each term alone: no generated token / no prompt
+    only_prefill = co.comm_tp(l=3, alpha=ex["tp_alpha"], beta=ex["tp_beta"], **dict(t, s_out=0))
+    assert math.isclose(only_prefill, gold["tp_prefill"], rel_tol=1e-12)
+    assert math.isclose(co.comm_pp(alpha=ex["pp_alpha"], beta=ex["pp_beta"], **t), gold["pp_total"], rel_tol=1e-12)
+    assert math.isclose(co.comm_pp(alpha=ex["pp_alpha"], beta=ex["pp_beta"], **dict(t, s_out=0)), gold["pp_prefill"],
+                        rel_tol=1e-12)
 
 
 def test_cost_model_identities():

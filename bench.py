@@ -1,21 +1,27 @@
 #!/usr/bin/env python3
 """Benchmark of the stage hot path on one MI355X.
 
-Workload (N = 1): the Llama-2-70B-shaped shard at tensor-parallel degree 2, rank 0, 8-layer stage,
-batch-1 decode from a synthetic KV context of 1024 positions -- the configuration the headline metric
-(decode tokens/s per stage, fraction of HBM peak) is quoted on.  One "step" = one decode step of the whole
-stage (all layers: RMSNorm, QKV, RoPE + cache append, attention, W_O, RMSNorm, W1/W3 + SwiGLU, W2).
-Inputs and weights are synthetic (seeded normal draws) and resident in HBM before the timed region.
+Headline workload (N = 1): `l70_full`, the largest configuration that fits one GPU -- the full-width
+Llama-2-70B stage (TP degree 1, all 80 layers, 136.9 GB of bf16 weights), 32 ragged prompts of 128..4096 tokens
+prefilled, then decoded one token per sequence and step against the ragged KV cache.
+  * One timed "step" = one decode call of the whole stage for the batch of 32 (all 80 layers: RMSNorm, QKV, RoPE +
+    cache append, GQA attention, W_O, RMSNorm, W1/W3 + SwiGLU, W2).  `value` = decode tokens/s of the stage.
+  * The prefill of the 32 prompts that precedes the decode steps is timed on its own (it is one call of about nine
+    seconds) and reported next to it: `prefill_tokens_per_s`, and the `prefill` object (GEMMs against the bf16 MFMA peak).
+  * `configs` carries the same figures -- tokens/s, microseconds per layer, roofline fraction -- for every 70B-shaped
+    configuration of the task: TP2 batch-1 decode, TP4 prefill + decode, TP8 batch-16 decode, and the full stage.
+Inputs and weights are synthetic (seeded normal draws) and resident in HBM before any timed region.
 
 Prints ONE JSON line.  Besides the contract fields it carries
-  roofline     -- the dominant kernel (W1/W3 weight-streaming projection) against the 8 TB/s HBM peak,
-                  timed with HIP events on the launch stream in a second, instrumented pass;
-  cpu_baseline -- the float64 CPU oracle timed on a bounded sample (one layer, a few decode steps),
-                  scaled to the same unit.
+  roofline     -- the dominant kernel of the timed region (the W1/W3 weight-streaming decode projection) against the
+                  8 TB/s HBM peak, timed with HIP events on the launch stream in an instrumented pass of its own;
+  roofline_prefill -- the dominant kernel of the prefill (the W1/W3 GEMM) against the bf16 MFMA peak, same method;
+  cpu_baseline -- the float64 CPU oracle timed on a bounded sample of the same workload, scaled to the same unit.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -24,25 +30,180 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-PROF_QKV, PROF_WO, PROF_W13, PROF_W2, PROF_ATTN, PROF_CALL = range(6)
-
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled
-# by a copy kernel of known size); see profiles/.  None until measured for the current kernel.
-MEASURED_TRAFFIC_BYTES = 470_662_000     # profiles/decode_l70_tp2_pmc_traffic.txt
+MFMA_PEAK_TFLOPS = 2516.6      # MI355X published dense bf16 rate
+PROF_QKV, PROF_WO, PROF_W13, PROF_W2, PROF_ATTN, PROF_CALL, PROF_W13_MAIN = range(7)
+SLOT_NAMES = (("qkv", PROF_QKV), ("wo", PROF_WO), ("w13", PROF_W13), ("w2", PROF_W2), ("attn", PROF_ATTN))
 
 
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the dominant decode kernel as measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE
+    scaled by a copy of known size) in an EARLIER run, read from the committed summary of that run; (None, None)
+    when no summary for this workload exists.  The figure is not measured by this run: the source file is named
+    beside it in the JSON."""
+    path = os.path.join(ROOT, "profiles", f"decode_{workload}_pmc_traffic.txt")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch\s+(\S+)\s+(\d+)", open(path).read(), flags=re.M)
+    except OSError:
+        return None, None
+    return (int(m.group(2)), f"profiles/{os.path.basename(path)} ({m.group(1)})") if m else (None, None)
+
+
+# ------------------------------------------------------------------------------------------------------------------
+class Bench:
+    """One stage resident on the GPU with its cache; the legs below time it."""
+
+    def __init__(self, torch, hx, generate, cfg, max_decode_steps, keep_layers=()):
+        self.torch, self.hx, self.generate, self.cfg = torch, hx, generate, cfg
+        self.rank = cfg.tp_ranks[0]
+        t0 = time.time()
+        self.st = hx.Stage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, cfg.n_layers, cfg.tp_degree, self.rank,
+                           cfg.dtype, cfg.rms_eps, cfg.rope_theta)
+        self.host_layers = {}
+        for l in range(cfg.n_layers):
+            w = generate.layer_weights(cfg, l, device="cuda")
+            self.st.load_layer(l, *[w[k] for k in generate.LAYER_TENSOR_ORDER])
+            if l in keep_layers:
+                self.host_layers[l] = {k: v.cpu() for k, v in w.items()}
+            del w
+        self.b = cfg.batch
+        if cfg.kv_context is not None:
+            self.lens = [cfg.kv_context] * self.b
+        else:
+            self.lens = generate.prompt_lengths(cfg)
+        self.kv = self.st.kv_cache_create(self.b, max(self.lens) + max_decode_steps + 1)
+        if cfg.kv_context is not None:
+            for l in range(cfg.n_layers):
+                for s in range(self.b):
+                    k, v = generate.synthetic_kv(cfg, l, s, cfg.kv_context, device="cuda")
+                    self.kv.fill(l, s, k.cpu(), v.cpu())
+        n_x = max_decode_steps
+        self.X = torch.stack([generate.hidden_rows(cfg, self.b, stream_id=1 + i, device="cuda") for i in range(n_x)])
+        self.X = self.X.to(torch.bfloat16).contiguous()
+        self.outp = torch.empty(self.b, cfg.hidden, dtype=torch.bfloat16, device="cuda")
+        self.outr = torch.empty_like(self.outp)
+        torch.cuda.synchronize()
+        log(f"{cfg.name}: setup {time.time() - t0:.1f}s, weights {self.st.weight_bytes() / 1e9:.3f} GB")
+
+    # ---- prefill ---------------------------------------------------------------------------------------------
+    def prefill(self, reps, warm=1):
+        torch, cfg, st = self.torch, self.cfg, self.st
+        T = sum(self.lens)
+        Xp = self.generate.hidden_rows(cfg, T, device="cuda").to(torch.bfloat16).contiguous()
+        outp, outr = torch.empty_like(Xp), torch.empty_like(Xp)
+        for _ in range(warm):
+            st.prefill(self.kv, Xp, self.lens, outp, outr)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            st.prefill(self.kv, Xp, self.lens, outp, outr)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / reps
+        assert torch.isfinite(outp.float()).all() and torch.isfinite(outr.float()).all()
+        st.profile_enable(0b11111)
+        st.prefill(self.kv, Xp, self.lens, outp, outr)
+        H, d = cfg.hidden, cfg.head_dim
+        flops = {"qkv": 2 * T * H * (cfg.hq_l + 2 * cfg.hkv_l) * d, "wo": 2 * T * cfg.hq_l * d * H,
+                 "w13": 2 * T * H * 2 * cfg.ffn_l, "w2": 2 * T * cfg.ffn_l * H}
+        gemm, tot_f, tot_t = {}, 0.0, 0.0
+        for name, slot in SLOT_NAMES:
+            ms, n = st.profile_read(slot)
+            us = ms / max(n, 1) * 1e3
+            if name == "attn":
+                gemm["attn"] = {"avg_us": round(us, 1)}
+                continue
+            gemm[name] = {"avg_us": round(us, 1), "TFLOPs": round(flops[name] / us / 1e6, 1),
+                          "frac": round(flops[name] / us / 1e6 / MFMA_PEAK_TFLOPS, 4), "launches": n}
+            tot_f += flops[name]
+            tot_t += us
+        st.profile_enable(0)
+        del Xp, outp, outr
+        layer_flops = sum(flops.values()) + sum(2 * n * n * d * cfg.hq_l for n in self.lens)
+        self.prefill_w13 = (flops["w13"], gemm["w13"]["avg_us"], gemm["w13"]["launches"])
+        return {"rows": T, "sequences": self.b, "tokens_per_s": round(T / dt, 1), "ms_per_call": round(dt * 1e3, 3),
+                "us_per_layer": round(dt * 1e6 / cfg.n_layers, 1), "reps": reps,
+                "stage_mfma_frac": round(layer_flops * cfg.n_layers / dt / 1e12 / MFMA_PEAK_TFLOPS, 4),
+                "gemm_mfma_frac": round(tot_f / tot_t / 1e6 / MFMA_PEAK_TFLOPS, 4), "gemm": gemm}
+
+    # ---- decode ----------------------------------------------------------------------------------------------
+    def run_decode(self, n):
+        """n decode steps from the context the workload starts its decode phase with; returns seconds.
+        Bracketed by a device synchronisation on both sides (one process, one GPU: no rank barrier exists)."""
+        self.kv.set_lengths(self.lens)
+        self.torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            self.st.decode(self.kv, i, self.X[i], self.outp, self.outr)
+        self.torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    def decode(self, steps, warmup):
+        cfg = self.cfg
+        self.run_decode(warmup)
+        dt = self.run_decode(steps)
+        assert self.torch.isfinite(self.outp.float()).all() and self.torch.isfinite(self.outr.float()).all()
+        # algorithmic bytes of a step: every weight once + the K / V rows of every sequence's context (which grows
+        # by one position per step)
+        kv_pos = sum(n + (steps + 1) / 2.0 for n in self.lens)
+        step_bytes = cfg.n_layers * (cfg.weight_elems_per_layer_rank * 2 + cfg.kv_bytes_per_pos_layer() * kv_pos)
+        return dt, {"batch": self.b, "steps": steps, "tokens_per_s": round(self.b * steps / dt, 2),
+                    "ms_per_step": round(dt / steps * 1e3, 4),
+                    "us_per_layer": round(dt / steps * 1e6 / cfg.n_layers, 2),
+                    "hbm_frac": round(step_bytes / (dt / steps) / 1e9 / HBM_PEAK_GBS, 4),
+                    "GB_per_step": round(step_bytes / 1e9, 3)}
+
+    def decode_kernels(self, steps):
+        """Instrumented passes (HIP events recorded by the library on the launch stream): first the main kernel of
+        the W1/W3 projection alone, so that its figure carries no other event's overhead, then every projection."""
+        cfg, st = self.cfg, self.st
+        st.profile_enable(1 << PROF_W13_MAIN)
+        self.run_decode(steps)
+        w13_ms, w13_n = st.profile_read(PROF_W13_MAIN)
+        st.profile_enable(0b11111)
+        self.run_decode(steps)
+        H, Fl, eb = cfg.hidden, cfg.ffn_l, 2
+        nbytes = {"qkv": H * (cfg.hq_l + 2 * cfg.hkv_l) * cfg.head_dim * eb, "wo": cfg.hq_l * cfg.head_dim * H * eb,
+                  "w13": H * 2 * Fl * eb, "w2": Fl * H * eb}
+        per = {}
+        for name, slot in SLOT_NAMES:
+            ms, n = st.profile_read(slot)
+            us = ms / max(n, 1) * 1e3
+            per[name] = {"avg_us": round(us, 2)}
+            if name in nbytes:
+                per[name]["GBps"] = round(nbytes[name] / us / 1e3, 1)
+        st.profile_enable(0)
+        b2b_ms, b2b_n = st.time_w13_decode(max(1, 256 // cfg.n_layers))
+        # W1/W3 main kernel, algorithmic bytes: the weights + the rows' activation operand (hi and lo halves); the
+        # outputs (and, on the batched path, the fp32 partial sums handed to the finishing kernel) are not counted
+        w13_bytes = nbytes["w13"] + self.b * H * eb * 2
+        w13_us = w13_ms / max(w13_n, 1) * 1e3
+        return per, {"bytes_per_launch": w13_bytes, "avg_launch_us": round(w13_us, 2), "launches_timed": w13_n,
+                     "projection_back_to_back_us": round(b2b_ms / b2b_n * 1e3, 2)}
+
+
+def hbm_roofline(cfg, b, k):
+    achieved = k["bytes_per_launch"] / (k["avg_launch_us"] * 1e-6) / 1e9
+    name = ("decode_splitk_kernel<2> (W1/W3 projection, 17..32 rows; its finishing kernel with the SwiGLU epilogue "
+            "follows)" if b > 16 else
+            "decode_splitk_kernel<1> (W1/W3 projection, 3..16 rows; finishing kernel follows)" if b > 2 else
+            "decode_proj_kernel<1,2,8,4,SWIGLU> (W1/W3 projection + SwiGLU epilogue)")
+    traffic, src = measured_traffic(cfg.name)
+    return {"bound": "hbm", "kernel": name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": src, **k}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=256)
-    ap.add_argument("--warmup", type=int, default=16)
-    ap.add_argument("--workload", default="l70_tp2_decode")
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="l70_full", help="headline workload (a bf16 configuration)")
+    ap.add_argument("--prefill-reps", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-prefill", action="store_true", help="skip the prefill leg (second workload)")
+    ap.add_argument("--no-configs", action="store_true", help="skip the other configurations' legs")
     ap.add_argument("--no-head", action="store_true", help="skip the LM-head leg (model end next to the last stage)")
     ap.add_argument("--no-sched", action="store_true", help="skip the host-only scheduler-search leg")
     ap.add_argument("--calibrate", action="store_true",
@@ -55,143 +216,128 @@ def main():
 
     import torch
     import paper_2311_11514_amd as hx
-    from workloads import CONFIGS, generate
+    from workloads import CONFIGS, CONFIG_ORDER, generate
 
     if args.calibrate:
         calibrate(torch, hx)
         return
-
-    cfg = CONFIGS[args.workload]
-    assert cfg.kv_context is not None and cfg.dtype == "bf16", "bench workload must be a bf16 decode config"
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = "cuda"
-    rank = cfg.tp_ranks[0]
+    cfg = CONFIGS[args.workload]
+    assert cfg.dtype == "bf16", "the headline workload must be one of the bf16 configurations"
     K, W = args.steps, args.warmup
-    b, ctx = cfg.batch, cfg.kv_context
-
-    t_setup = time.time()
-    st = hx.Stage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, cfg.n_layers, cfg.tp_degree, rank, cfg.dtype,
-                  cfg.rms_eps, cfg.rope_theta)
-    layer0_host = None
-    for l in range(cfg.n_layers):
-        w = generate.layer_weights(cfg, l, device=dev)
-        st.load_layer(l, *[w[k] for k in generate.LAYER_TENSOR_ORDER])
-        if l == 0 and not args.no_cpu_baseline:
-            layer0_host = {k: v.cpu() for k, v in w.items()}
-        del w
-    kv = st.kv_cache_create(b, ctx + max(K, W) + 1)
-    kv_host = {}
-    for l in range(cfg.n_layers):
-        for s in range(b):
-            k, v = generate.synthetic_kv(cfg, l, s, ctx, device=dev)
-            k, v = k.cpu(), v.cpu()
-            kv.fill(l, s, k, v)
-            if l == 0:
-                kv_host[s] = (k, v)
-    X = torch.stack([generate.hidden_rows(cfg, b, stream_id=1 + i, device=dev) for i in range(max(K, W))])
-    X = X.to(torch.bfloat16).contiguous()
-    outp = torch.empty(b, cfg.hidden, dtype=torch.bfloat16, device=dev)
-    outr = torch.empty_like(outp)
-    torch.cuda.synchronize()
-    log(f"setup {time.time() - t_setup:.1f}s, weights {st.weight_bytes() / 1e9:.3f} GB")
-
-    def run(n):
-        kv.set_lengths([ctx] * b)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(n):
-            st.decode(kv, i, X[i], outp, outr)
-        torch.cuda.synchronize()
-        return time.perf_counter() - t0
+    nproc = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    log(f"host: nproc {nproc} (os.cpu_count {os.cpu_count()})")
 
     # three plain copies of known size: the yardstick the profiler's byte counters are scaled by
-    cal_src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+    cal_src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
     cal_dst = torch.empty_like(cal_src)
     for _ in range(3):
         hx.stream_copy(cal_dst, cal_src, blocks=512)
     torch.cuda.synchronize()
     del cal_src, cal_dst
 
-    run(W)
-    dt = run(K)
-    ms_per_step = dt / K * 1e3
-    tok_s = b * K / dt
-    assert torch.isfinite(outp.float()).all() and torch.isfinite(outr.float()).all()
+    be = Bench(torch, hx, generate, cfg, max(K, W), keep_layers=() if args.no_cpu_baseline else (0,))
+    pre = None
+    if cfg.kv_context is None:
+        pre = be.prefill(args.prefill_reps)          # leaves the prompts' K / V in the cache for the decode steps
+        log(f"prefill {pre['ms_per_call']:.1f} ms per call, {pre['tokens_per_s']:.0f} tokens/s, GEMMs "
+            f"{pre['gemm_mfma_frac']:.3f} of the MFMA peak")
+    dt, dec = be.decode(K, W)
+    per_kernel, w13 = be.decode_kernels(min(K, 32))
+    log(f"decode {dec['ms_per_step']:.3f} ms per step, {dec['tokens_per_s']:.1f} tokens/s, {dec['hbm_frac']:.3f} of HBM peak")
 
-    # instrumented passes: HIP events on the launch stream; first around the dominant kernel alone (so its
-    # figure carries no other events' overhead), then around every projection for the per-kernel table
-    st.profile_enable(1 << PROF_W13)
-    run(K)
-    w13_ms, w13_n = st.profile_read(PROF_W13)
-    st.profile_enable(True)
-    run(K)
-    slots = {}
-    for name, slot in (("qkv", PROF_QKV), ("wo", PROF_WO), ("w13", PROF_W13), ("w2", PROF_W2),
-                       ("attn", PROF_ATTN), ("call", PROF_CALL)):
-        ms, n = st.profile_read(slot)
-        slots[name] = {"avg_us": ms / max(n, 1) * 1e3, "launches": n}
-    st.profile_enable(False)
-    # the same kernel once more, all layers back to back between two events only (no per-launch events): its duration
-    # without the dispatch gap that an event pair around a single launch includes
-    b2b_ms, b2b_n = st.time_w13_decode(32)
-
-    eb = 2
-    H, Fl = cfg.hidden, cfg.ffn_l
-    w13_bytes = H * 2 * Fl * eb + b * H * eb * 2        # weights + hi/lo activation operand (outputs are negligible)
-    w13_us = w13_ms / max(w13_n, 1) * 1e3
-    achieved = w13_bytes / (w13_us * 1e-6) / 1e9
-    bytes_by_proj = {"qkv": H * (cfg.hq_l + 2 * cfg.hkv_l) * cfg.head_dim * eb, "wo": cfg.hq_l * cfg.head_dim * H * eb,
-                     "w13": H * 2 * Fl * eb, "w2": Fl * H * eb}
-    per_kernel = {k: {"avg_us": round(slots[k]["avg_us"], 2),
-                      "GBps": round(bytes_by_proj[k] / (slots[k]["avg_us"] * 1e-6) / 1e9, 1)} for k in bytes_by_proj}
-    per_kernel["attn_block"] = {"avg_us": round(slots["attn"]["avg_us"], 2)}
-    # whole-step algorithmic bytes: weights + KV read (context grows by one per step)
-    kv_bytes_avg = cfg.kv_bytes_per_pos_layer() * b * (ctx + (K + 1) / 2.0)
-    step_bytes = cfg.n_layers * (cfg.weight_elems_per_layer_rank * eb + kv_bytes_avg)
-    stage_frac = step_bytes / (dt / K) / 1e9 / HBM_PEAK_GBS
-
+    lens = be.lens
     result = {
-        "metric": "decode_tokens_per_s_per_stage", "value": round(tok_s, 2), "unit": "tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
+        "metric": "decode_tokens_per_s_per_stage", "value": dec["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": dec["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: Llama-2-70B-shaped shard, TP{cfg.tp_degree} rank {rank}, "
-                               f"{cfg.n_layers}-layer stage, batch {b} decode from KV context {ctx}",
-                   "hidden": H, "local_q_heads": cfg.hq_l, "local_kv_heads": cfg.hkv_l, "head_dim": cfg.head_dim,
-                   "local_ffn": Fl, "layers": cfg.n_layers, "batch": b, "kv_context": ctx},
-        "us_per_layer": round(ms_per_step * 1e3 / cfg.n_layers, 2),
-        "stage_hbm_frac": round(stage_frac, 4),
+        "config": {"workload": f"{cfg.name}: Llama-2-70B-shaped stage, TP{cfg.tp_degree} rank {be.rank}, "
+                               f"{cfg.n_layers} layers, batch {be.b}, "
+                               + (f"decode from a synthetic KV context of {cfg.kv_context}" if cfg.kv_context is not None
+                                  else f"prompts of {min(lens)}..{max(lens)} tokens ({sum(lens)} rows) prefilled, then "
+                                       f"one decode step per timed step against the ragged cache"),
+                   "hidden": cfg.hidden, "local_q_heads": cfg.hq_l, "local_kv_heads": cfg.hkv_l,
+                   "head_dim": cfg.head_dim, "local_ffn": cfg.ffn_l, "layers": cfg.n_layers, "batch": be.b,
+                   "weights_GB": round(be.st.weight_bytes() / 1e9, 1)},
+        "us_per_layer": dec["us_per_layer"], "stage_hbm_frac": dec["hbm_frac"],
+        "prefill_tokens_per_s": pre["tokens_per_s"] if pre else None,
         "per_kernel": per_kernel,
-        "roofline": {"bound": "hbm", "kernel": "decode_proj_kernel<1,2,8,4,SWIGLU> (W1/W3 projection + SwiGLU epilogue)",
-                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES, "bytes_per_launch": w13_bytes,
-                     "avg_launch_us": round(w13_us, 2), "launches_timed": w13_n,
-                     "back_to_back": {"avg_launch_us": round(b2b_ms / b2b_n * 1e3, 2), "launches": b2b_n,
-                                      "frac": round(w13_bytes / (b2b_ms / b2b_n * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}},
+        "roofline": hbm_roofline(cfg, be.b, w13),
+        "host": {"nproc": nproc, "os_cpu_count": os.cpu_count()},
     }
-
+    if pre:
+        result["prefill"] = pre
+        f, us, n = be.prefill_w13
+        result["roofline_prefill"] = {"bound": "mfma", "kernel": "gemm_mfma_kernel (W1/W3 GEMM + SwiGLU epilogue)",
+                                      "achieved": round(f / us / 1e6, 1), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                      "frac": round(f / us / 1e6 / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                                      "flops_per_launch": f, "avg_launch_us": us, "launches_timed": n}
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, rank, layer0_host, kv_host, X, ctx)
-    if not args.no_prefill:
-        del st, kv, X
-        torch.cuda.empty_cache()
-        result["prefill"] = prefill_leg(torch, hx, CONFIGS["l70_tp4_prefill"], generate)
+        result["cpu_baseline"] = cpu_baseline(torch, be, nproc)
+    summary = {cfg.name: {"decode": dec, **({"prefill": {k: v for k, v in pre.items() if k != "gemm"}} if pre else {})}}
+    del be
+    torch.cuda.empty_cache()
+
+    if not args.no_configs:
+        for name in CONFIG_ORDER:
+            c = CONFIGS[name]
+            if c.dtype != "bf16" or name == cfg.name:
+                continue
+            steps = c.decode_steps
+            ob = Bench(torch, hx, generate, c, steps)
+            entry = {}
+            if c.kv_context is None:
+                p = ob.prefill(5, warm=2)
+                entry["prefill"] = p
+                if name == "l70_tp4_prefill":
+                    entry["one_short_prompt"] = short_prompts(torch, ob)
+            _, d = ob.decode(steps, min(8, steps))
+            pk, k13 = ob.decode_kernels(min(steps, 64))
+            d["per_kernel"] = pk
+            d["w13_main_kernel"] = {**k13, "GBps": round(k13["bytes_per_launch"] / k13["avg_launch_us"] / 1e3, 1)}
+            entry["decode"] = d
+            summary[name] = entry
+            log(f"{name}: decode {d['us_per_layer']} us/layer, {d['hbm_frac']} of HBM peak"
+                + (f"; prefill GEMMs {entry['prefill']['gemm_mfma_frac']} of MFMA peak" if "prefill" in entry else ""))
+            del ob
+            torch.cuda.empty_cache()
+    result["configs"] = summary
     if not args.no_head:
-        torch.cuda.empty_cache()
         result["lm_head"] = head_leg(torch, hx, generate)
-    if "prefill" in result:
-        result["cost_model"] = cost_model_alignment(torch, hx, cfg, result)
+    if not args.no_configs and "l70_tp4_prefill" in summary and "l70_tp2_decode" in summary:
+        result["cost_model"] = cost_model_alignment(torch, hx, CONFIGS, summary)
     if not args.no_sched:
         result["scheduler"] = scheduler_leg(hx)
     print(json.dumps(result), flush=True)
+
+
+def short_prompts(torch, ob, reps=5):
+    """One short prompt on the TP4 stage: the regime of the split contraction and the skinny kernel (weight-streaming
+    bound: the floor is the stage's weight bytes at the HBM peak)."""
+    cfg, st = ob.cfg, ob.st
+    X = ob.generate.hidden_rows(cfg, 512, device="cuda").to(torch.bfloat16).contiguous()
+    outp, outr = torch.empty_like(X), torch.empty_like(X)
+    short = {}
+    for rows in (128, 512):
+        kv1 = st.kv_cache_create(1, rows + 8)
+        for _ in range(2):
+            st.prefill(kv1, X[:rows], [rows], outp[:rows], outr[:rows])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            st.prefill(kv1, X[:rows], [rows], outp[:rows], outr[:rows])
+        torch.cuda.synchronize()
+        dt1 = (time.perf_counter() - t0) / reps
+        short[str(rows)] = {"us_per_layer": round(dt1 * 1e6 / cfg.n_layers, 1), "tokens_per_s": round(rows / dt1, 1),
+                            "weights_at_hbm_peak_us_per_layer": round(st.weight_bytes() / cfg.n_layers / HBM_PEAK_GBS / 1e3, 1)}
+        del kv1
+    return short
 
 
 def scheduler_leg(hx):
     """Host-only leg: the search over deployments (Section 4.3) on a synthetic pool in the shape of the paper's
     full-price rental (58 GPUs, 6 types), Llama-2-70B-sized task, 400 Poisson arrivals at 2 requests/s, deadline
     5 x the fastest start group; wall time of the library call on one host core."""
-    import time
-
     from workloads import serving
     pool = serving.hetero_pool("full_price")
     task, n_layers = (8192, 12.0, 2, 1, 128, 32), 80
@@ -207,72 +353,6 @@ def scheduler_leg(hx):
             "search_s": round(dt, 2), "start_groups": len(start),
             "start_attainment": round(hx.slo_attainment(arrival, [[x] for x in lat0], [deadline]), 4),
             "groups": len(res["groups"]), "attainment": round(res["attainment"], 4)}
-
-
-MFMA_PEAK_TFLOPS = 2516.6      # MI355X published dense bf16 rate
-
-
-def prefill_leg(torch, hx, cfg, generate, reps=5):
-    """Second half of the headline metric: prefill tokens/s of the asymmetric TP4 shard (20 layers, 4 x 512 rows)
-    and the projection GEMMs against the bf16 MFMA peak.  Reported beside the decode figure, not as `value`."""
-    dev, rank = "cuda", cfg.tp_ranks[0]
-    st = hx.Stage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, cfg.n_layers, cfg.tp_degree, rank, cfg.dtype,
-                  cfg.rms_eps, cfg.rope_theta)
-    for l in range(cfg.n_layers):
-        w = generate.layer_weights(cfg, l, device=dev)
-        st.load_layer(l, *[w[k] for k in generate.LAYER_TENSOR_ORDER])
-        del w
-    lens = generate.prompt_lengths(cfg)
-    T = sum(lens)
-    kv = st.kv_cache_create(cfg.batch, max(lens) + 8)
-    X = generate.hidden_rows(cfg, T, device=dev).to(torch.bfloat16).contiguous()
-    outp, outr = torch.empty_like(X), torch.empty_like(X)
-    for _ in range(2):
-        st.prefill(kv, X, lens, outp, outr)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        st.prefill(kv, X, lens, outp, outr)
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / reps
-    assert torch.isfinite(outp.float()).all()
-    st.profile_enable(0b1111)
-    st.prefill(kv, X, lens, outp, outr)
-    H, d = cfg.hidden, cfg.head_dim
-    flops = {"qkv": 2 * T * H * (cfg.hq_l + 2 * cfg.hkv_l) * d, "wo": 2 * T * cfg.hq_l * d * H,
-             "w13": 2 * T * H * 2 * cfg.ffn_l, "w2": 2 * T * cfg.ffn_l * H}
-    gemm = {}
-    tot_f, tot_t = 0.0, 0.0
-    for slot, name in enumerate(("qkv", "wo", "w13", "w2")):
-        ms, n = st.profile_read(slot)
-        us = ms / max(n, 1) * 1e3
-        gemm[name] = {"avg_us": round(us, 1), "TFLOPs": round(flops[name] / us / 1e6, 1)}
-        tot_f += flops[name]
-        tot_t += us
-    st.profile_enable(0)
-    # one short prompt on the same stage: the regime of the split contraction and the skinny kernel (weight-streaming
-    # bound: the floor is the stage's weight bytes at the HBM peak)
-    short = {}
-    for rows in (128, 512):
-        kv1 = st.kv_cache_create(1, rows + 8)
-        for _ in range(2):
-            st.prefill(kv1, X[:rows], [rows], outp[:rows], outr[:rows])
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            st.prefill(kv1, X[:rows], [rows], outp[:rows], outr[:rows])
-        torch.cuda.synchronize()
-        dt1 = (time.perf_counter() - t0) / reps
-        short[str(rows)] = {"us_per_layer": round(dt1 * 1e6 / cfg.n_layers, 1), "tokens_per_s": round(rows / dt1, 1),
-                            "weights_at_hbm_peak_us_per_layer": round(st.weight_bytes() / cfg.n_layers / HBM_PEAK_GBS / 1e3, 1)}
-        del kv1
-    layer_flops = sum(flops.values()) + sum(2 * n * n * d * cfg.hq_l for n in lens)
-    return {"workload": f"{cfg.name}: TP{cfg.tp_degree} rank {rank}, {cfg.n_layers} layers, {cfg.batch} x {lens[0]} rows",
-            "tokens_per_s": round(T / dt, 1), "ms_per_call": round(dt * 1e3, 3),
-            "us_per_layer": round(dt * 1e6 / cfg.n_layers, 1),
-            "stage_mfma_frac": round(layer_flops * cfg.n_layers / dt / 1e12 / MFMA_PEAK_TFLOPS, 4),
-            "gemm_mfma_frac": round(tot_f / tot_t / 1e6 / MFMA_PEAK_TFLOPS, 4), "gemm": gemm,
-            "peak_TFLOPs": MFMA_PEAK_TFLOPS, "one_short_prompt": short}
 
 
 def head_leg(torch, hx, generate, reps=50):
@@ -301,11 +381,11 @@ def head_leg(torch, hx, generate, reps=50):
             "token": int(tok.item())}
 
 
-def cost_model_alignment(torch, hx, cfg, result):
+def cost_model_alignment(torch, hx, CONFIGS, summary):
     """The paper's computation-cost formula (Eq. 3, with Llama-2-70B's 12.75 H^2 parameters per layer) fed with this
     machine's MEASURED rates -- m_d: a cold 470 MB streaming read, c_d: the rate of the largest prefill GEMM -- against
-    the measured times of the two workloads above (the paper's own alignment table compares the same two columns)."""
-    from workloads import CONFIGS
+    the measured times of the TP2 decode and TP4 prefill workloads (the paper's own alignment table compares the same
+    two columns)."""
     big = torch.empty(1880 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
     sink = torch.zeros(1 << 16, dtype=torch.float32, device="cuda")
     n = 470 << 20
@@ -318,14 +398,16 @@ def cost_model_alignment(torch, hx, cfg, result):
     e1.record()
     torch.cuda.synchronize()
     m_d = 4 * n / (e0.elapsed_time(e1) * 1e-3)
-    c_d = result["prefill"]["gemm"]["w13"]["TFLOPs"] * 1e12
-    pc = CONFIGS["l70_tp4_prefill"]
-    dec = hx.cost_comp(cfg.hidden, 2, cfg.batch, 0, 1, cfg.n_layers, [m_d] * cfg.tp_degree, [c_d] * cfg.tp_degree, 12.75, "decode")
-    pre = hx.cost_comp(pc.hidden, 2, pc.batch, pc.prompt_len, 0, pc.n_layers, [m_d] * pc.tp_degree, [c_d] * pc.tp_degree,
+    pre = summary["l70_tp4_prefill"]["prefill"]
+    c_d = pre["gemm"]["w13"]["TFLOPs"] * 1e12
+    dc, pc = CONFIGS["l70_tp2_decode"], CONFIGS["l70_tp4_prefill"]
+    dec = hx.cost_comp(dc.hidden, 2, dc.batch, 0, 1, dc.n_layers, [m_d] * dc.tp_degree, [c_d] * dc.tp_degree, 12.75, "decode")
+    est = hx.cost_comp(pc.hidden, 2, pc.batch, pc.prompt_len, 0, pc.n_layers, [m_d] * pc.tp_degree, [c_d] * pc.tp_degree,
                        12.75, "prefill")
     return {"m_d_GBps": round(m_d / 1e9, 1), "c_d_TFLOPs": round(c_d / 1e12, 1),
-            "decode_ms_per_token": {"estimated": round(dec * 1e3, 4), "measured": result["ms_per_step"]},
-            "prefill_ms_per_call": {"estimated": round(pre * 1e3, 3), "measured": result["prefill"]["ms_per_call"]}}
+            "decode_ms_per_token": {"estimated": round(dec * 1e3, 4),
+                                    "measured": summary["l70_tp2_decode"]["decode"]["ms_per_step"]},
+            "prefill_ms_per_call": {"estimated": round(est * 1e3, 3), "measured": pre["ms_per_call"]}}
 
 
 def calibrate(torch, hx):
@@ -366,34 +448,52 @@ def calibrate(torch, hx):
         print(f"  {name:58s} {tf:8.1f} {tf / 2516.6:6.3f}")
 
 
-def cpu_baseline(cfg, rank, layer0, kv_host, X, ctx):
-    """The oracle as it stands, on the host cores: ONE layer of the same shard, a few decode steps from
-    the same synthetic context; tokens/s of the stage = batch / (per-layer step time * layers)."""
+def cpu_baseline(torch, be, nproc):
+    """The oracle as it stands, on the host cores, on a bounded sample of the headline workload: ONE layer (layer 0) of
+    the same stage -- a few decode steps of the whole batch from the GPU-prefilled context of that layer, and (when
+    the workload has prompts) the prefill of one of the batch's prompts -- scaled to the stage by the layer count."""
     from oracle import stage_oracle as so
     from workloads import generate
+    cfg = be.cfg
     try:
         from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        blas = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
-        cores = os.cpu_count() or 1
-    ora = so.OracleStage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, 1, cfg.tp_degree, rank, cfg.rms_eps,
+        blas = nproc
+    ora = so.OracleStage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, 1, cfg.tp_degree, be.rank, cfg.rms_eps,
                          cfg.rope_theta)
-    ora.load_layer(0, *[layer0[k] for k in generate.LAYER_TENSOR_ORDER])
-    oc = ora.new_cache(cfg.batch)
-    for s, (k, v) in kv_host.items():
+    ora.load_layer(0, *[be.host_layers[0][k] for k in generate.LAYER_TENSOR_ORDER])
+    oc = ora.new_cache(be.b)
+    for s in range(be.b):                                  # layer 0's context as the GPU holds it
+        k, v = be.kv.read(0, s, 0, be.lens[s])
         oc.fill(0, s, k, v)
-    xs = X.float().cpu()
+    xs = be.X.float().cpu()
     ora.decode(oc, xs[0])                       # untimed first touch
     n, t0 = 0, time.perf_counter()
-    while n < 64 and time.perf_counter() - t0 < 15.0:
-        ora.decode(oc, xs[1 + n % (xs.shape[0] - 1)])
+    while n < 32 and time.perf_counter() - t0 < 12.0:
+        ora.decode(oc, xs[(1 + n) % xs.shape[0]])
         n += 1
     per_layer_step = (time.perf_counter() - t0) / n
-    value = cfg.batch / (per_layer_step * cfg.n_layers)
-    log(f"cpu oracle: {per_layer_step * 1e3:.1f} ms per layer-step on {cores} threads")
-    return {"value": round(value, 4), "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"1 of {cfg.n_layers} layers, {n} decode steps at context {ctx}+, float64 numpy; "
-                      f"stage rate = batch / (layer-step time x {cfg.n_layers})"}
+    value = be.b / (per_layer_step * cfg.n_layers)
+    out = {"value": round(value, 4), "unit": "tokens/s", "cores": blas, "kind": "oracle",
+           "sample": f"1 of {cfg.n_layers} layers, {n} decode steps of the batch of {be.b} at its "
+                     f"{'ragged ' if cfg.kv_context is None else ''}context, float64 numpy; "
+                     f"stage rate = batch / (layer-step time x {cfg.n_layers}); projections on {blas} BLAS threads, "
+                     f"the attention loop on 1 (nproc {nproc})"}
+    log(f"cpu oracle: decode {per_layer_step * 1e3:.1f} ms per layer-step on {blas} BLAS threads (nproc {nproc})")
+    if cfg.kv_context is None:
+        # prefill of ONE prompt of the batch (the one closest to 1024 rows) through the same layer
+        s = min(range(be.b), key=lambda i: abs(be.lens[i] - 1024))
+        rows = be.lens[s]
+        x = generate.hidden_rows(cfg, sum(be.lens), device="cuda")[sum(be.lens[:s]): sum(be.lens[:s]) + rows].cpu()
+        t0 = time.perf_counter()
+        ora.prefill(ora.new_cache(1), x, [rows])
+        dtp = time.perf_counter() - t0
+        out["prefill"] = {"value": round(rows / (dtp * cfg.n_layers), 4), "unit": "tokens/s",
+                          "sample": f"1 of {cfg.n_layers} layers, one prompt of {rows} rows ({dtp:.1f} s); "
+                                    f"stage rate = rows / (layer time x {cfg.n_layers})"}
+        log(f"cpu oracle: prefill of {rows} rows through one layer {dtp:.1f} s")
+    return out
 
 
 if __name__ == "__main__":

@@ -17,8 +17,10 @@ extern "C" {
 /* Per-slot timing.  While enabled, prefill / decode record HIP events on the caller's stream
  * around each projection launch, so per-kernel time can be read without an external profiler
  * (this costs a few microseconds per timed launch: enable it for measurement passes only).
- * Slots: 0 QKV projection, 1 W_O, 2 W1/W3 (+SwiGLU), 3 W2, 4 attention, 5 the whole call.
- * enable(slot_mask): bit i selects slot i (0 = off, 63 = all); synchronises and clears earlier records.
+ * Slots: 0 QKV projection, 1 W_O, 2 W1/W3 (+SwiGLU), 3 W2, 4 attention, 5 the whole call, 6 (decode calls of at most
+ * 32 rows only) the first kernel of the W1/W3 projection alone: with 3 or more rows that projection is a split kernel
+ * followed by a finishing kernel, and slot 2 brackets the pair.
+ * enable(slot_mask): bit i selects slot i (0 = off, 127 = all); synchronises and clears earlier records.
  * read() synchronises and returns the summed time in milliseconds and the number of timed launches.
  */
 hexgen_status_t hexgen_stage_profile_enable(hexgen_stage_t *st, int slot_mask);

@@ -187,8 +187,8 @@ class Stage:
         _check(lib.hexgen_stage_set_tap(self.handle, layer, _ptr(h_dump)), "hexgen_stage_set_tap")
 
     def profile_enable(self, slot_mask):
-        """slot_mask: bit i times slot i (True = all six slots, False / 0 = off)."""
-        mask = 63 if slot_mask is True else int(slot_mask)
+        """slot_mask: bit i times slot i (True = all seven slots, False / 0 = off)."""
+        mask = 127 if slot_mask is True else int(slot_mask)
         _check(lib.hexgen_stage_profile_enable(self.handle, mask), "hexgen_stage_profile_enable")
 
     def profile_read(self, slot: int):

@@ -77,8 +77,10 @@ struct DecodeEpi {
 // Wp . Xa for T <= 32 rows (Xa: compact hi/lo operand [T][K]), one block per output unit, then the
 // epilogue of e.mode
 // `scratch` (device, scratch_floats floats, may be NULL) holds the split partial sums of the batched path (T > 2)
+// `mid` (measurement, may be NULL): recorded on `s` right behind the projection's first kernel, i.e. between the
+// split kernel and the finishing kernel of the batched path
 void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T, const DecodeEpi &e, float *scratch,
-                        size_t scratch_floats, hipStream_t s);
+                        size_t scratch_floats, hipStream_t s, hipEvent_t mid = nullptr);
 // stage input rows (+ optional second addend in2) -> h (optional), (x * g) hi/lo planes, sums of squares; block 0
 // publishes row positions from the committed lengths and optionally advances them
 void launch_decode_prologue(const void *in, const void *in2, int in_is_bf16, float *h_out, const float *g, bf16_t *hg,

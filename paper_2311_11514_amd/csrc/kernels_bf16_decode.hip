@@ -556,7 +556,7 @@ void launch_mode(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, 
 namespace {
 template <int MODE, int UT>
 void launch_splitk(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, float *scratch,
-                   size_t scratch_floats, hipStream_t s) {
+                   size_t scratch_floats, hipStream_t s, hipEvent_t mid) {
     const int n_tiles = N / 16, groups = (n_tiles + 7) / 8;
     // Two blocks fit a CU (registers), 512 on the chip.  The number of splits (at most 8: the finishing kernel walks
     // them one after the other; partials within the scratch) minimises rounds of blocks x chunks per block, the time
@@ -587,6 +587,7 @@ void launch_splitk(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T
         hipLaunchKernelGGL(decode_splitk_kernel<1>, grid, dim3(512), lds, s, Wp, Xa, n_tiles, k_tiles, T, scratch, e.ssq_in,
                            e.ssq_units, e.norm_dim, e.eps, rstd);
     }
+    if (mid) (void)hipEventRecord(mid, s);
     const int n_units = n_tiles / UT, nbt = (T + 15) / 16;
     hipLaunchKernelGGL((decode_finish_kernel<MODE, UT>), dim3((n_units * nbt + 3) / 4), dim3(256), 0, s, scratch, splits, N, T,
                        n_units, e, rstd);
@@ -594,7 +595,7 @@ void launch_splitk(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T
 }  // namespace
 
 void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T, const DecodeEpi &e, float *scratch,
-                        size_t scratch_floats, hipStream_t s) {
+                        size_t scratch_floats, hipStream_t s, hipEvent_t mid) {
     const int k_tiles = K / 32;
     // one or two rows: one kernel, complete dot products per block; more: shared operand, split contraction
     // A small matrix (launch-bound) with a handful of rows is better off without the second kernel: each block then
@@ -603,10 +604,10 @@ void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T,
     const bool small = (size_t)N * K * sizeof(bf16_t) <= ((size_t)72 << 20) && k_tiles >= 64 && T <= (K <= 4096 ? 8 : 4);
     if (T > 2 && !small && scratch != nullptr && scratch_floats >= (size_t)T * N + 32 && k_tiles >= SK_CH) {
         switch (e.mode) {
-            case DEC_RAW: launch_splitk<DEC_RAW, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s); break;
-            case DEC_QKV: launch_splitk<DEC_QKV, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s); break;
-            case DEC_RESID: launch_splitk<DEC_RESID, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s); break;
-            case DEC_SWIGLU: launch_splitk<DEC_SWIGLU, 2>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s); break;
+            case DEC_RAW: launch_splitk<DEC_RAW, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s, mid); break;
+            case DEC_QKV: launch_splitk<DEC_QKV, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s, mid); break;
+            case DEC_RESID: launch_splitk<DEC_RESID, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s, mid); break;
+            case DEC_SWIGLU: launch_splitk<DEC_SWIGLU, 2>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s, mid); break;
         }
         return;
     }
@@ -620,6 +621,7 @@ void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T,
         case DEC_RESID: launch_mode<1, DEC_RESID>(Wp, Xa, N, k_tiles, T, e, s); break;
         case DEC_SWIGLU: launch_mode<2, DEC_SWIGLU>(Wp, Xa, N, k_tiles, T, e, s); break;
     }
+    if (mid) (void)hipEventRecord(mid, s);
 }
 
 // -------------------------------------------------------------------------------------------------

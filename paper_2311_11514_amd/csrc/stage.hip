@@ -43,7 +43,7 @@ struct Layer {
 };
 
 // Optional per-slot timing with HIP events recorded on the caller's stream (measurement surface).
-enum { PROF_QKV = 0, PROF_WO = 1, PROF_W13 = 2, PROF_W2 = 3, PROF_ATTN = 4, PROF_CALL = 5, PROF_SLOTS = 6 };
+enum { PROF_QKV = 0, PROF_WO = 1, PROF_W13 = 2, PROF_W2 = 3, PROF_ATTN = 4, PROF_CALL = 5, PROF_W13_MAIN = 6, PROF_SLOTS = 7 };
 struct Profiler {
     unsigned mask = 0;                          // bit i set: slot i is timed
     std::vector<hipEvent_t> ev[PROF_SLOTS];     // start, stop, start, stop, ...
@@ -383,7 +383,20 @@ DecodeEpi epi_base(hexgen_stage *st, int mode) {
 void decode_proj(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xa, int N, int K, const DecodeEpi &e,
                  int slot, hipStream_t s) {
     st->prof.mark(slot, s);
-    launch_decode_proj(static_cast<const bf16_t *>(Wp), Xa, N, K, r.T, e, st->ws.dec_part, st->ws.dec_part_floats, s);
+    // slot 6: the first kernel of the W1/W3 projection alone (the batched path adds a finishing kernel behind it)
+    hipEvent_t mid = nullptr;
+    if (slot == PROF_W13 && (st->prof.mask >> PROF_W13_MAIN & 1u)) {
+        std::vector<hipEvent_t> &v = st->prof.ev[PROF_W13_MAIN];
+        const size_t before = v.size();
+        st->prof.mark(PROF_W13_MAIN, s);
+        if (v.size() == before + 1 && hipEventCreate(&mid) != hipSuccess) {     // keep start / stop pairs whole
+            (void)hipEventDestroy(v.back());
+            v.pop_back();
+            mid = nullptr;
+        }
+    }
+    launch_decode_proj(static_cast<const bf16_t *>(Wp), Xa, N, K, r.T, e, st->ws.dec_part, st->ws.dec_part_floats, s, mid);
+    if (mid) st->prof.ev[PROF_W13_MAIN].push_back(mid);
     st->prof.mark(slot, s);
 }
 

@@ -246,7 +246,12 @@ def test_full_width_80_layer_stage_sampled_layers():
                 check(f"{tag}, resid", outr[sl].float().cpu().numpy()[rows], ref[0], BF)
                 check(f"{tag}, partial", outp[sl].float().cpu().numpy()[rows], ref[1], BF)
             else:
-                check(tag, taps[l + 1][sl].cpu().numpy()[rows], ref, BF)
+                out = taps[l + 1][sl].cpu().numpy()[rows]
+                check(tag, out, ref, BF)
+                # what the layer ADDED to the residual stream (deep in the stage the stream itself is large, and an error
+                # of the layer would hide in it)
+                h_rows = h_in[sl].cpu().numpy().astype(np.float64)[rows]
+                check(f"{tag}: the layer's contribution", out - h_rows, ref - h_rows, BF)
             kk, vv = kv.read(l, s, 0, n)
             check(f"{tag}: cached K", kk.numpy().reshape(-1, d), K.reshape(-1, d), BF)
             check(f"{tag}: cached V", vv.numpy().reshape(-1, d), V.reshape(-1, d), BF)
@@ -283,7 +288,9 @@ def test_full_width_80_layer_stage_sampled_layers():
                 check(f"{tag}, resid", hg, h_mid, BF)
                 check(f"{tag}, partial", pg, p_ffn, BF)
             else:
-                check(tag, dtaps[l + 1].cpu().numpy(), h_mid + p_ffn, BF)
+                out = dtaps[l + 1].cpu().numpy()
+                check(tag, out, h_mid + p_ffn, BF)
+                check(f"{tag}: the layer's contribution", out - h_in, h_mid + p_ffn - h_in, BF)
             # the row the GPU appended in this layer is the oracle's
             s = longest
             kk, vv = kv.read(l, s, lens[s] + step, 1)

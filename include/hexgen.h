@@ -112,6 +112,31 @@ hexgen_status_t hexgen_stage_decode(hexgen_stage_t *st, hexgen_kv_cache_t *kv, i
                                     const void *hidden_in, void *out_partial, void *out_resid,
                                     void *stream);
 
+/* ---- decode for callers that cannot allocate ------------------------------------------------------------------
+ * For callers that may not call hipMalloc while they run: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation.  Same step, same kernels and same results as hexgen_stage_decode, but the call allocates
+ * nothing and frees nothing (no device memory, no host memory, no events): the workspace of the step -- residual
+ * stream, projection operands, split partial sums of the batched projections, split-attention partials and arrival
+ * counters, sums of squares, row positions -- is laid out in one file-scope device array of
+ * HEXGEN_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process ends.
+ *   - bf16 stages only (HEXGEN_ERR_SHAPE otherwise); at most 32 sequences in the batch, and the workspace of the
+ *     call (hexgen_stage_decode_static_bytes(st, batch)) must fit the array: HEXGEN_ERR_CAPACITY otherwise, nothing
+ *     is launched.  Every 70B-shaped configuration up to the full-width stage at batch 32 (39 MB) fits.
+ *   - the cache must have been prefilled (or set_lengths called) as for hexgen_stage_decode; `step` as there; the
+ *     cache, the lengths and the step count advance exactly as there, and the two calls may be mixed step by step.
+ *   - all calls on one GPU share that GPU's array, which keeps the last call's contents; the call clears (with a
+ *     kernel on `stream`) what has to start at zero.  Calls that overlap in time on one GPU -- two streams, two
+ *     stages, two threads -- race on it: serialise them.
+ *   - the timing slots of hexgen_stage_profile_enable are not recorded for this call; taps are.
+ * hexgen_stage_decode_static_bytes: bytes of the array a call with `batch` sequences uses; -1 for invalid arguments
+ * or an fp32 stage.
+ */
+#define HEXGEN_STATIC_SCRATCH_BYTES (64u << 20)
+hexgen_status_t hexgen_stage_decode_static(hexgen_stage_t *st, hexgen_kv_cache_t *kv, int step,
+                                           const void *hidden_in, void *out_partial, void *out_resid,
+                                           void *stream);
+int64_t hexgen_stage_decode_static_bytes(const hexgen_stage_t *st, int batch);
+
 /* ---- validation surface ("group" mode: all t ranks of a stage run one after another on the same
  * GPU and their partials are summed, standing in for the all-reduce of paper Section 2) ----------
  * hexgen_stage_run_sublayer: one sub-layer of one layer for this rank.

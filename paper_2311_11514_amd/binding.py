@@ -34,6 +34,8 @@ SIGNATURES = {
     "hexgen_kv_cache_reset": (_i, [_vp]),
     "hexgen_stage_prefill": (_i, [_vp, _vp, _vp, _ip, _i, _vp, _vp, _vp]),
     "hexgen_stage_decode": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _vp]),
+    "hexgen_stage_decode_static": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _vp]),
+    "hexgen_stage_decode_static_bytes": (_i64, [_vp, _i]),
     "hexgen_stage_run_sublayer": (_i, [_vp, _vp, _i, _i, _vp, _ip, _i, _vp, _vp]),
     "hexgen_kv_cache_commit": (_i, [_vp, _ip, _i]),
     "hexgen_accumulate_f32": (_i, [_vp, _vp, _i64, _vp]),
@@ -175,6 +177,15 @@ class Stage:
                out_resid: Optional[torch.Tensor] = None, stream=None):
         _check(lib.hexgen_stage_decode(self.handle, kv.handle, step, _ptr(hidden_in), _ptr(out_partial),
                                        _ptr(out_resid), _stream_handle(stream)), "hexgen_stage_decode")
+
+    def decode_static(self, kv: "KVCache", step: int, hidden_in: torch.Tensor, out_partial: torch.Tensor,
+                      out_resid: Optional[torch.Tensor] = None, stream=None):
+        """hexgen_stage_decode_static: the decode step for callers that cannot allocate."""
+        _check(lib.hexgen_stage_decode_static(self.handle, kv.handle, step, _ptr(hidden_in), _ptr(out_partial),
+                                              _ptr(out_resid), _stream_handle(stream)), "hexgen_stage_decode_static")
+
+    def decode_static_bytes(self, batch: int) -> int:
+        return int(lib.hexgen_stage_decode_static_bytes(self.handle, batch))
 
     def run_sublayer(self, kv: "KVCache", layer: int, which: int, h_in: torch.Tensor,
                      seq_lens: Optional[Sequence[int]], batch: int, partial_out: torch.Tensor, stream=None):

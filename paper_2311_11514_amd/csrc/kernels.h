@@ -151,6 +151,8 @@ void launch_embed_rows(const void *table, int64_t row_bytes, int vocab, const in
                        hipStream_t s);
 
 void launch_store_out(const float *src, void *dst, int dst_is_bf16, int64_t n, hipStream_t s);
+// p[0 .. bytes) = 0 with a kernel; p 4-byte aligned, bytes a multiple of 4
+void launch_fill_zero(void *p, size_t bytes, hipStream_t s);
 
 // ---- fp32 path (kernels_f32.hip): plain layouts, vector ALU -----------------------------------
 void f32_launch_rmsnorm(const float *in, const float *g, float *out, int T, int H, float eps, hipStream_t s);

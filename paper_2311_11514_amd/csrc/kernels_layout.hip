@@ -88,6 +88,19 @@ void launch_store_out(const float *src, void *dst, int dst_is_bf16, int64_t n, h
     hipLaunchKernelGGL(store_out_kernel, dim3(blocks), dim3(256), 0, s, src, dst, dst_is_bf16, n);
 }
 
+// zero fill as a kernel (a memset node recorded into a captured graph is avoided on purpose)
+__global__ void fill_zero_kernel(uint32_t *__restrict__ p, size_t n_words) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n_words; i += stride) p[i] = 0u;
+}
+void launch_fill_zero(void *p, size_t bytes, hipStream_t s) {
+    const size_t n = bytes / 4;
+    if (n == 0) return;
+    const int blocks = (int)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, static_cast<uint32_t *>(p), n);
+}
+
 // staging [n][hkv_l][d] fp32  <->  packed cache slabs of sequence `seq`
 __global__ void kv_scatter_kernel(const float *__restrict__ k, const float *__restrict__ v, bf16_t *__restrict__ kc,
                                   bf16_t *__restrict__ vc, KvGeom kg, int seq, int pos0, int n) {

@@ -98,6 +98,7 @@ struct hexgen_stage {
     std::vector<Layer> layers;
     std::vector<void *> taps;
     Workspace ws;
+    Workspace *cur = nullptr;        // the workspace the decode flow runs on: &ws, or a view of the static scratch array
     int last_decode_rows = 0;        // rows of the last decode call that ran on the weight-streaming kernels
     int ws_batch_cap = 0;
     int64_t weight_bytes = 0;
@@ -395,7 +396,7 @@ void decode_proj(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *
             mid = nullptr;
         }
     }
-    launch_decode_proj(static_cast<const bf16_t *>(Wp), Xa, N, K, r.T, e, st->ws.dec_part, st->ws.dec_part_floats, s, mid);
+    launch_decode_proj(static_cast<const bf16_t *>(Wp), Xa, N, K, r.T, e, st->cur->dec_part, st->cur->dec_part_floats, s, mid);
     if (mid) st->prof.ev[PROF_W13_MAIN].push_back(mid);
     st->prof.mark(slot, s);
 }
@@ -403,7 +404,7 @@ void decode_proj(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *
 // QKV (+RoPE, cache append) and attention; leaves o (hi/lo) in the workspace
 void attn_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Rows &r, const float *ssq_in,
                       hipStream_t s) {
-    Workspace &w = st->ws;
+    Workspace &w = *st->cur;
     const Layer &ly = st->layers[layer];
     const KvGeom kg = geom(st, kv);
     bf16_t *kc = static_cast<bf16_t *>(kv->k) + (size_t)layer * kv->layer_stride;
@@ -421,7 +422,7 @@ void attn_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Ro
 
 hexgen_status_t forward_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
                                     void *out_partial, void *out_resid, hipStream_t s) {
-    Workspace &w = st->ws;
+    Workspace &w = *st->cur;
     float *ssq_a = w.ssq, *ssq_f = w.ssq + (size_t)(st->H / 16) * DEC_SSQ_STRIDE;
     launch_decode_prologue(hidden_in, nullptr, 1, w.h, st->layers[0].g_attn, w.xa_n, ssq_a, r.T, st->H, kv->d_lens,
                            w.row_pos, 1, s);
@@ -540,6 +541,71 @@ void free_layer(Layer &l) {
     l = Layer();
 }
 
+
+// ---- the allocation-free decode step: its whole workspace lives in one file-scope device array ------------------
+constexpr size_t kStaticScratchBytes = (size_t)HEXGEN_STATIC_SCRATCH_BYTES;
+constexpr int kStaticMaxDevices = 64;
+constexpr int kStaticAttnSplit = 8;          // pick_attn_split never returns more
+
+}  // namespace
+
+// Every GPU the library runs on holds its own copy of this array, at its own address, until the process ends.  In
+// host code the name below is only a handle for hipGetSymbolAddress: the device address is looked up once per
+// device (static_scratch_ptr) and that pointer is what kernels and fills receive.
+static __device__ __align__(256) unsigned char hexgen_static_scratch[kStaticScratchBytes];
+
+namespace {
+
+void *g_static_scratch_ptr[kStaticMaxDevices];          // per device, nullptr until looked up
+
+hexgen_status_t static_scratch_ptr(unsigned char **out) {
+    int dev = -1;
+    HX_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kStaticMaxDevices) return HEXGEN_ERR_DEVICE;
+    if (!g_static_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HX_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(hexgen_static_scratch)));
+        if (!p) return HEXGEN_ERR_DEVICE;
+        g_static_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<unsigned char *>(g_static_scratch_ptr[dev]);
+    return HEXGEN_OK;
+}
+
+// Lays the buffers of one decode call of `rows` rows out behind `base` (256-byte aligned pieces) and returns the bytes
+// used; with base == nullptr only the size is computed.  Same buffers, sizes per row and roles as ensure_workspace's
+// decode part; the attention partials are sized for the 8 splits the split rule allows.
+size_t carve_decode_workspace(const hexgen_stage *st, int rows, unsigned char *base, Workspace *w) {
+    size_t off = 0;
+    auto take = [&](size_t bytes) -> void * {
+        off = (off + 255) / 256 * 256;
+        void *p = base ? base + off : nullptr;
+        off += bytes;
+        return p;
+    };
+    const size_t T = (size_t)rows;
+    const size_t nmax = (size_t)std::max(std::max(st->nqkv, st->H), 2 * st->F_l);
+    Workspace v;
+    v.cap_rows = rows;
+    v.h = static_cast<float *>(take(T * st->H * sizeof(float)));
+    v.xa_n = static_cast<bf16_t *>(take(2 * T * st->H * sizeof(bf16_t)));
+    v.xa_o = static_cast<bf16_t *>(take(2 * T * st->qw * sizeof(bf16_t)));
+    v.xa_u = static_cast<bf16_t *>(take(2 * T * st->F_l * sizeof(bf16_t)));
+    v.q = static_cast<bf16_t *>(take(T * st->qw * sizeof(bf16_t)));
+    v.q_lo = static_cast<bf16_t *>(take(T * st->qw * sizeof(bf16_t)));
+    if (rows > 2) {
+        v.dec_part_floats = T * ((size_t)512 * 128 + 2 * nmax);
+        v.dec_part = static_cast<float *>(take(v.dec_part_floats * sizeof(float)));
+    }
+    v.att_o = static_cast<float *>(take(T * st->hq_l * kStaticAttnSplit * st->d * sizeof(float)));
+    v.att_ml = static_cast<float *>(take(T * st->hq_l * kStaticAttnSplit * 2 * sizeof(float)));
+    v.att_arrived = static_cast<unsigned int *>(take(T * st->hkv_l * sizeof(unsigned int)));
+    v.ssq = static_cast<float *>(take(2 * (size_t)(st->H / 16) * DEC_SSQ_STRIDE * sizeof(float)));
+    v.row_pos = static_cast<int32_t *>(take(T * sizeof(int32_t)));
+    if (w) *w = v;
+    return off;
+}
+
 }  // namespace
 
 // =================================================================================================
@@ -581,6 +647,7 @@ hexgen_status_t hexgen_stage_create(int hidden, int n_heads, int n_kv_heads, int
     st->qw = hq_l * d;
     st->nqkv = (hq_l + 2 * hkv_l) * d;
     st->dtype = dtype;
+    st->cur = &st->ws;
     try {       // no exception may cross the C boundary
         st->layers.resize(n_layers);
         st->taps.assign(n_layers, nullptr);
@@ -913,6 +980,52 @@ hexgen_status_t hexgen_stage_decode(hexgen_stage_t *st, hexgen_kv_cache_t *kv, i
     for (int i = 0; i < kv->batch; ++i) kv->lens[i] += 1;
     kv->steps += 1;
     return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_stage_decode_static(hexgen_stage_t *st, hexgen_kv_cache_t *kv, int step, const void *hidden_in,
+                                           void *out_partial, void *out_resid, void *stream) {
+    if (!st || !kv || !hidden_in || !out_partial || kv->st != st) return HEXGEN_ERR_INVALID_ARG;
+    HX_TRY(check_loaded(st));
+    if (st->dtype != HEXGEN_BF16) return HEXGEN_ERR_SHAPE;
+    if (!kv->prefilled || kv->batch <= 0 || step != kv->steps) return HEXGEN_ERR_STATE;
+    HX_TRY(check_rope(st, kv));
+    const int batch = kv->batch;
+    if (batch > kDecodeMaxRows) return HEXGEN_ERR_CAPACITY;
+    for (int i = 0; i < batch; ++i)
+        if ((long)kv->lens[i] + 1 > kv->max_seq) return HEXGEN_ERR_CAPACITY;
+    if (carve_decode_workspace(st, batch, nullptr, nullptr) > kStaticScratchBytes) return HEXGEN_ERR_CAPACITY;
+    unsigned char *base = nullptr;
+    HX_TRY(static_scratch_ptr(&base));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Workspace view;
+    (void)carve_decode_workspace(st, batch, base, &view);
+    // what must start at zero: the arrival counters of the split attention and the sums of squares (a fill kernel,
+    // not a memset node, so that the call can be captured into a graph)
+    launch_fill_zero(view.att_arrived, (size_t)batch * st->hkv_l * sizeof(unsigned int), s);
+    launch_fill_zero(view.ssq, 2 * (size_t)(st->H / 16) * DEC_SSQ_STRIDE * sizeof(float), s);
+    Rows r;
+    r.T = batch;
+    r.batch = batch;
+    r.max_new = 1;
+    r.decode = true;
+    r.rm.row_seq = nullptr;        // the bf16 decode kernels take positions only (published by the prologue)
+    r.rm.row_pos = view.row_pos;
+    const unsigned saved_mask = st->prof.mask;
+    st->prof.mask = 0;             // the timing slots create events: not in a call that allocates nothing
+    st->cur = &view;
+    const hexgen_status_t rc = forward_decode_bf16(st, kv, r, hidden_in, out_partial, out_resid, s);
+    st->cur = &st->ws;
+    st->prof.mask = saved_mask;
+    HX_TRY(rc);
+    HX_HIP(hipGetLastError());
+    for (int i = 0; i < batch; ++i) kv->lens[i] += 1;
+    kv->steps += 1;
+    return HEXGEN_OK;
+}
+
+int64_t hexgen_stage_decode_static_bytes(const hexgen_stage_t *st, int batch) {
+    if (!st || batch <= 0 || st->dtype != HEXGEN_BF16) return -1;
+    return (int64_t)carve_decode_workspace(st, batch, nullptr, nullptr);
 }
 
 // ---- validation surface ----------------------------------------------------------------------------

@@ -232,17 +232,38 @@ __device__ __forceinline__ void gemm_epilogue(const floatx16 (&acc)[FM][FT], int
     }
 }
 
+// Linear tile id -> (feature block bm, token block bt).  Ids are dealt out patch by patch: a patch is pm_h feature
+// blocks x pt_w token blocks (lower / narrower at the edges), patches run along the token blocks first, and inside a
+// patch the feature block varies fastest.  pm_h = 1, pt_w = t_blocks is the plain row-major order.
+__device__ __forceinline__ void gemm_tile_of_id(int id, int n_blocks, int t_blocks, int pm_h, int pt_w, int &bm, int &bt) {
+    const int row = pm_h * t_blocks;                       // tiles of a full patch row
+    const int pm = id / row, rem = id - pm * row;
+    const int hm = min(pm_h, n_blocks - pm * pm_h);        // height of this patch row (the last one may be lower)
+    const int pt = rem / (hm * pt_w), rem2 = rem - pt * hm * pt_w;
+    bm = pm * pm_h + rem2 % hm;
+    bt = pt * pt_w + rem2 / hm;
+}
+
 // Operand tiles travel HBM -> LDS with direct-to-LDS loads (no registers in between): a wave copies one
 // 1 KB fragment tile per instruction, lane l's 16 bytes landing at tile base + 16 l.  S stages of the k-loop
 // are resident; the wait before a step only covers that step's loads (vmcnt counts the rest).
 //
 // Block = WM x WT waves; each wave owns FM x FT tiles of 32 features x 32 tokens, so the block tile is
 // (32 FM WM) features x (32 FT WT) tokens.
-template <int FM, int FT, int WM, int WT, int S, int MODE>
+//
+// PP = true (8 waves, two per SIMD): the two waves of a SIMD run the k-loop half a step out of phase.  Every wave
+// alternates a MEMORY phase (all operand fragments of one 32-deep k-step from LDS into registers, its share of the
+// direct-to-LDS loads of a later stage) and a COMPUTE phase (the k-step's MFMAs back to back, nothing else in the
+// stream), each closed by a workgroup barrier; waves 4..7 pass one extra barrier before their loop, waves 0..3 one
+// after it.  So while one wave of a SIMD waits for LDS data, for its loads or at a barrier, the other one is inside
+// its MFMA run: the barriers and waits that idle the matrix core in the lock-stepped loop below fall into the
+// shadow of the other wave's MFMAs.
+template <int FM, int FT, int WM, int WT, int S, int MODE, bool PP = false>
 __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *__restrict__ Wp,
                                                                  const bf16_t *__restrict__ Xp, int N, int k_tiles,
                                                                  int n_tiles, int t_tiles, int T, int n_blocks,
-                                                                 int t_blocks, GemmEpi e, float *__restrict__ part) {
+                                                                 int t_blocks, GemmEpi e, float *__restrict__ part,
+                                                                 int pm_h, int pt_w) {
     constexpr int NW = WM * WT, NT = 64 * NW;
     constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT;   // 16-row operand tiles per block and k-step
     constexpr int LA = TA / NW, LB = TB / NW;         // direct-to-LDS loads per wave and stage, per operand
@@ -258,7 +279,10 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
     const int per_xcd = (total + 7) / 8;
     id = (id & 7) * per_xcd + (id >> 3);
     if (id >= total) return;                     // only when total is not a multiple of 8
-    const int bm = id / t_blocks, bt = id - bm * t_blocks;
+    // Consecutive ids (the blocks one XCD runs at the same time) form a patch of pm_h feature blocks x pt_w token
+    // blocks: per k-step the patch fetches (pm_h + pt_w) operand slices into that XCD's L2 for pm_h x pt_w tiles.
+    int bm, bt;
+    gemm_tile_of_id(id, n_blocks, t_blocks, pm_h, pt_w, bm, bt);
     // the wave index is made provably uniform: tile addresses and LDS destinations then stay in scalar registers
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int wm = wave % WM, wt = wave / WM;
@@ -319,6 +343,75 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
     // kt + 1, whose first half is then fetched under the second half of stage kt, and frees the buffer of
     // stage kt - 1.  (3) The loads of stage kt + S - 1 into that buffer are spread over one whole step, half
     // behind the barrier of step kt and half in front of the barrier of step kt + 1, one load every few MFMAs.
+    if constexpr (PP) {
+        static_assert(NW == 8 && S >= 3, "ping-pong: two waves per SIMD");
+        const int grp = wave >> 2;                 // waves w and w + 4 share a SIMD
+#pragma unroll
+        for (int p2 = 0; p2 < S - 1; ++p2)
+#pragma unroll
+            for (int x = 0; x < LPT; ++x) issue_one(p2, x);
+        if (MODE != DEC_RESID && e.ssq_in != nullptr && part == nullptr) {
+            const int groups = e.norm_dim / GEMM_SSQ_COLS;
+            for (int t = tid; t < NTOK; t += NT) {
+                const int token = bt * NTOK + t;
+                float ss = 0.f;
+                if (token < T) {
+#pragma unroll 16
+                    for (int gI = 0; gI < groups; ++gI) ss += e.ssq_in[(size_t)gI * T + token];
+                }
+                rstd_s[t] = 1.0f / sqrtf(ss / (float)e.norm_dim + e.eps);
+            }
+        }
+        HX_WAIT_VM((S - 2) * LPT);                 // stage 0 has landed (this wave's share of it)
+        HX_LDS_BARRIER();                          // ... and everybody's
+        if (grp == 1) asm volatile("s_barrier" ::: "memory");       // half a step behind waves 0..3 from here on
+        bf16x8 pa[2][FM], pb[2][FT];
+        for (int kt = 0; kt < k_len; ++kt) {
+            // memory phase: the whole k-step's operands, then this wave's loads of stage kt + S - 1 into the buffer
+            // of stage kt - 1, which both halves of the block have finished reading (barriers below)
+            const bf16x8 *sa = smem + (size_t)(kt % S) * STAGE + (wm * FM * 2) * 64 + frag;
+            const bf16x8 *sb = smem + (size_t)(kt % S) * STAGE + (TA + wt * FT * 2) * 64 + frag;
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh) {
+#pragma unroll
+                for (int x = 0; x < FT; ++x) pb[kh][x] = sb[x * 128 + kh * 32];
+#pragma unroll
+                for (int x = 0; x < FM; ++x) pa[kh][x] = sa[x * 128 + kh * 32];
+            }
+#pragma unroll
+            for (int x = 0; x < LPT; ++x) issue_one(kt + S - 1, x);
+            __builtin_amdgcn_sched_barrier(0);
+            HX_WAIT_VM((S - 2) * LPT);             // this wave's loads of stage kt + 1 have landed
+            HX_LDS_BARRIER();                      // operands in registers; barrier
+            __builtin_amdgcn_sched_barrier(0);
+            // compute phase
+            __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+                for (int m = 0; m < FM * FT; ++m)
+                    acc[m / FT][m % FT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[kh][m / FT], pb[kh][m % FT], acc[m / FT][m % FT], 0, 0, 0);
+            __builtin_amdgcn_s_setprio(0);
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_barrier" ::: "memory");
+        }
+        if (grp == 0) asm volatile("s_barrier" ::: "memory");       // the barrier waves 4..7 passed ahead of their loop
+        HX_WAIT_VM(0);
+        if (part != nullptr) {
+            float *dst = part + ((((size_t)blockIdx.y * total + id) * NW + wave) * (FM * FT)) * 1024 + lane * 4;
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FT; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        *reinterpret_cast<floatx4 *>(dst + (i * FT + j) * 1024 + q * 256) =
+                            floatx4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+            return;
+        }
+        gemm_epilogue<FM, FT, WM, WT, MODE>(acc, bm, bt, wm, wt, lane, N, n_tiles, T, e, rstd_s);
+        return;
+    }
     constexpr int H1 = (LPT + 1) / 2, H2 = LPT / 2;  // loads issued behind / in front of the barrier
     constexpr int HL = H1;
     // MFMA slots of a half step: the first FM + FT also carry an LDS fetch; the loads go behind them when
@@ -424,12 +517,14 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
 // tiles up over the splits, in split order, and runs the epilogue.
 template <int FM, int FT, int WM, int WT, int MODE>
 __global__ __launch_bounds__(64 * WM * WT) void gemm_finish_kernel(const float *__restrict__ part, int splits, int N,
-                                                                   int n_tiles, int T, int total, int t_blocks, GemmEpi e) {
+                                                                   int n_tiles, int T, int total, int t_blocks, GemmEpi e,
+                                                                   int pm_h, int pt_w) {
     constexpr int NW = WM * WT, NT = 64 * NW, TB = 2 * FT * WT, NTOK = TB * 16;
     __shared__ float rstd_s[NTOK];
     __shared__ float ssq_lds[(MODE == DEC_RESID && 32 * FM != GEMM_SSQ_COLS) ? WM * NTOK : 1];
     const int id = blockIdx.x;
-    const int bm = id / t_blocks, bt = id - bm * t_blocks;
+    int bm, bt;
+    gemm_tile_of_id(id, total / t_blocks, t_blocks, pm_h, pt_w, bm, bt);      // as in the pass that wrote the partials
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int wm = wave % WM, wt = wave / WM;
     if (MODE != DEC_RESID && e.ssq_in != nullptr) {
@@ -569,14 +664,15 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t *__restri
                 floatx4{acc[j][4 * q], acc[j][4 * q + 1], acc[j][4 * q + 2], acc[j][4 * q + 3]};
 }
 
-template <int FM, int FT, int WM, int WT, int S, int MODE>
+template <int FM, int FT, int WM, int WT, int S, int MODE, bool PP = false>
 static void launch_cfg(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles, int n_tiles, int t_tiles, int T,
                        const GemmEpi &e, float *part, size_t part_floats, hipStream_t s) {
     constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT;
     const int n_blocks = (n_tiles + TA - 1) / TA, t_blocks = (t_tiles + TB - 1) / TB;
     const int total = n_blocks * t_blocks;
     const int grid = (total + 7) / 8 * 8;
-    auto kern = gemm_mfma_kernel<FM, FT, WM, WT, S, MODE>;
+    auto kern = gemm_mfma_kernel<FM, FT, WM, WT, S, MODE, PP>;
+    const int pm_h = 4, pt_w = 8;         // patch of tiles one XCD works on at a time: 4 feature blocks x 8 token blocks
     const size_t dyn = (size_t)S * (TA + TB) * 64 * sizeof(bf16x8) + (size_t)TB * 16 * sizeof(float);
     static bool raised = false;           // more than the default 64 KB of LDS per block
     if (!raised) {
@@ -595,16 +691,16 @@ static void launch_cfg(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles, i
         while (splits > 1 && (size_t)splits * total * tile_floats > part_floats) --splits;
     }
     hipLaunchKernelGGL(kern, dim3(grid, splits), dim3(64 * WM * WT), dyn, s, Wp, Xp, N, k_tiles, n_tiles, t_tiles, T,
-                       n_blocks, t_blocks, e, splits > 1 ? part : nullptr);
+                       n_blocks, t_blocks, e, splits > 1 ? part : nullptr, pm_h, std::min(pt_w, t_blocks));
     if (splits > 1)
         hipLaunchKernelGGL((gemm_finish_kernel<FM, FT, WM, WT, MODE>), dim3(total), dim3(64 * WM * WT), 0, s, part, splits, N,
-                           n_tiles, T, total, t_blocks, e);
+                           n_tiles, T, total, t_blocks, e, pm_h, std::min(pt_w, t_blocks));
 }
 
 // tile configuration forced for every GEMM launch of the process (0 = choose by shape); a measurement and test hook
 static std::atomic<int> g_force_tile{0};
 bool set_gemm_tile(int code) {
-    for (int ok : {0, 44, 48, 84, 88, 94, 49, 98, 72})
+    for (int ok : {0, 44, 48, 84, 88, 94, 49, 98, 72, 198})
         if (code == ok) { g_force_tile.store(code, std::memory_order_relaxed); return true; }
     return false;
 }
@@ -623,7 +719,7 @@ static bool launch_skinny(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles
     hipLaunchKernelGGL(gemm_skinny_kernel, dim3(n_blocks, splits), dim3(256), 0, s, Wp, Xp, k_tiles, n_tiles, t_tiles,
                        n_blocks, part);
     hipLaunchKernelGGL((gemm_finish_kernel<1, 1, 4, 1, MODE>), dim3(n_blocks * 4), dim3(256), 0, s, part, splits, N, n_tiles,
-                       T, n_blocks * 4, 4, e);
+                       T, n_blocks * 4, 4, e, 1, 4);
     return true;
 }
 
@@ -634,7 +730,8 @@ static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T,
     const int force = g_force_tile.load(std::memory_order_relaxed);
     // tiles of 256 x 256 once they fill the chip; 128 features x 256 tokens for smaller problems
     const long big = (long)((n_tiles + 15) / 16) * ((t_tiles + 15) / 16);
-    int cfg = big >= 200 ? 98 : 94;       // (128 x 256 also beats 128 x 128 on the few-tile launches that split)
+    // 198 = 256 x 256 on 8 waves with the two waves of a SIMD half a k-step out of phase (98: the same tile, lock-stepped)
+    int cfg = big >= 200 ? 198 : 94;      // (128 x 256 also beats 128 x 128 on the few-tile launches that split)
     if (cfg == 94 && part != nullptr && k_tiles >= 32) {
         // 128 x 256 tiles that neither fill the chip nor are few enough to split (129 .. 223 blocks): 256 x 256 tiles
         // with a split contraction instead, when that fills it (QKV of the TP4 shard at 2048 rows: 3 x 80 blocks
@@ -642,20 +739,12 @@ static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T,
         const long t94 = (long)((n_tiles + 7) / 8) * ((t_tiles + 15) / 16);
         if (t94 > 128 && t94 < 224 && 2 * big <= 256) {
             const long sp = std::min<long>({8, 256 / big, k_tiles / 16});
-            if (big * sp >= 230) cfg = 98;
+            if (big * sp >= 230) cfg = 198;
         }
-    }
-    if (cfg == 98 && MODE != DEC_RESID && big >= 200) {
-        // a launch of a few rounds of blocks loses the idle part of its last round: 448 x 128 tiles (4 waves of
-        // 224 x 64) when they fill the rounds markedly better (W1/W3 of the TP4 shard at 2048 rows: 512 blocks instead
-        // of 448 on 256 CUs; measured 3 % faster)
-        const long b98 = big, b72 = (long)((n_tiles + 27) / 28) * ((t_tiles + 7) / 8);
-        const double fill98 = (double)b98 / (double)((b98 + 255) / 256 * 256), fill72 = (double)b72 / (double)((b72 + 255) / 256 * 256);
-        if (fill72 > fill98 + 0.08) cfg = 72;
     }
     if (force) cfg = force;
     // the RESID epilogue emits one sum-of-squares partial per wave: its 32 FM features must be 128
-    if (MODE == DEC_RESID && cfg != 88 && cfg != 84 && cfg != 98) cfg = cfg == 72 ? 98 : 84;
+    if (MODE == DEC_RESID && cfg != 88 && cfg != 84 && cfg != 98 && cfg != 198) cfg = cfg == 72 ? 198 : 84;
     // one 128-token tile (a short prompt): 128-token block tiles; the split contraction then runs a short k-loop per
     // block with the weights coming from HBM, so the 256 x 128 tile of RESID keeps six stages in flight instead of four
     const bool short_prompt = !force && t_tiles <= 8;
@@ -664,6 +753,7 @@ static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T,
 #define HX_G(FM, FT, WM, WT, S) launch_cfg<FM, FT, WM, WT, S, MODE>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s)
     if (cfg == 88) HX_G(4, 4, 2, 2, 4);
     else if (cfg == 98) HX_G(4, 2, 2, 4, 4);
+    else if (cfg == 198) launch_cfg<4, 2, 2, 4, 4, MODE, true>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s);
     else if (cfg == 94) { if constexpr (MODE != DEC_RESID) HX_G(2, 2, 2, 4, 4); }
     else if (cfg == 49) { if constexpr (MODE != DEC_RESID) HX_G(2, 2, 4, 2, 4); }
     else if (cfg == 84) HX_G(4, 2, 2, 2, 4);

@@ -220,6 +220,7 @@ def main():
 
     if args.calibrate:
         calibrate(torch, hx)
+        calibrate_gemm(torch, hx)
         return
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cfg = CONFIGS[args.workload]
@@ -446,6 +447,85 @@ def calibrate(torch, hx):
         us = timed(lambda i: hx.mfma_probe(v, sink, iters, blocks), 1)
         tf = blocks * 4 * iters * (1 << 20) / us / 1e6
         print(f"  {name:58s} {tf:8.1f} {tf / 2516.6:6.3f}")
+
+
+class _PowerMeter:
+    """Socket power from the amdgpu hwmon file, sampled every 50 ms by a thread (None when the file is absent)."""
+
+    def __init__(self):
+        import glob
+        files = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") +
+                       glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average"))
+        self.path = files[0] if files else None
+
+    def run(self, torch, fn, secs):
+        """Calls fn() back to back for `secs` seconds; returns (calls per second, mean watts of the second half)."""
+        import threading
+        samples, stop = [], []
+
+        def sample():
+            while not stop:
+                try:
+                    samples.append(int(open(self.path).read()) / 1e6)
+                except Exception:
+                    pass
+                time.sleep(0.05)
+        th = threading.Thread(target=sample, daemon=True)
+        fn()
+        torch.cuda.synchronize()
+        if self.path:
+            th.start()
+        t0, n = time.perf_counter(), 0
+        while time.perf_counter() - t0 < secs:
+            for _ in range(4):
+                fn()
+            torch.cuda.synchronize()
+            n += 4
+        dt = time.perf_counter() - t0
+        stop.append(1)
+        if self.path:
+            th.join()
+        half = samples[len(samples) // 2:]
+        return n / dt, (sum(half) / len(half) if half else None)
+
+
+def calibrate_gemm(torch, hx):
+    """What bounds the prefill GEMM on this machine, as a table: sustained rate and socket power of
+      * the vendor library's bf16 GEMM (torch.nn.functional.linear -> hipBLASLt) on the W1/W3 shapes of the workloads --
+        a yardstick only, never part of the product path;
+      * this library's FFN sub-layer (W1/W3 + SwiGLU and W2 + residual GEMMs) on the same rows, with the default
+        tile and with the k-loop ablations of include/hexgen_bench.h (loads removed / cache-hit loads / no LDS reads)."""
+    from workloads import CONFIGS, generate
+    pm = _PowerMeter()
+    print(f"power file: {pm.path}")
+    print("vendor bf16 GEMM (hipBLASLt through torch), x ~ N(0,1), w ~ N(0, 0.02^2): rows x 8192 x features, TFLOP/s, fraction of 2516.6, W")
+    for T, N in ((2048, 14336), (16384, 14336), (65536, 14336), (71102, 57344)):
+        x = torch.randn(T, 8192, device="cuda", dtype=torch.bfloat16)
+        w = (torch.randn(N, 8192, device="cuda") * 0.02).to(torch.bfloat16)
+        rate, watts = pm.run(torch, lambda: torch.nn.functional.linear(x, w), 2.0)
+        tf = 2.0 * T * 8192 * N * rate / 1e12
+        print(f"  {T:6d} x 8192 x {N:6d}   {tf:8.1f}  {tf / MFMA_PEAK_TFLOPS:6.3f}  {watts if watts is None else round(watts):>6}")
+        del x, w
+    cfg = CONFIGS["l70_tp4_prefill"].scaled(n_layers=1)
+    st = hx.Stage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, 1, cfg.tp_degree, cfg.tp_ranks[0], "bf16")
+    w = generate.layer_weights(cfg, 0, device="cuda")
+    st.load_layer(0, *[w[k] for k in generate.LAYER_TENSOR_ORDER])
+    del w
+    print("this library, FFN sub-layer of the TP4 shard (W1/W3 2 x 7168 features + W2), rows, tile code, TFLOP/s of the two GEMMs, fraction, W")
+    names = {0: "default", 1198: "ablation: no loads in the k-loop", 2198: "ablation: loads hit in cache",
+             3198: "ablation: no LDS operand reads"}
+    for T in (2048, 16384, 65536):
+        kv = st.kv_cache_create(1, T)             # the FFN sub-layer leaves the cache alone; the call validates rows against it
+        h = torch.randn(T, cfg.hidden, device="cuda", dtype=torch.float32)
+        out = torch.empty_like(h)
+        flop = 2.0 * T * cfg.hidden * 3 * cfg.ffn_l
+        for code in (0, 1198, 2198, 3198):
+            hx.set_gemm_tile(code)
+            rate, watts = pm.run(torch, lambda: st.run_sublayer(kv, 0, 1, h, [T], 1, out), 2.0)
+            hx.set_gemm_tile(0)
+            tf = flop * rate / 1e12
+            print(f"  {T:6d}  {names[code]:36s} {tf:8.1f}  {tf / MFMA_PEAK_TFLOPS:6.3f}  {watts if watts is None else round(watts):>6}")
+        del kv, h, out
 
 
 def cpu_baseline(torch, be, nproc):

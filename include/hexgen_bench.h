@@ -55,6 +55,9 @@ hexgen_status_t hexgen_mfma_probe(int variant, void *sink, int iters, int blocks
  * 48 = 128 x 256, 94 / 49 = 128 x 256 on 8 waves (2 x 4 / 4 x 2 wave grid), 44 = 128 x 128, 72 = 448 features x 128
  * tokens on 4 waves; 0 restores the default.  (Residual-epilogue launches need 128 features per wave and fall back to
  * 84, from 72 to 198.)  HEXGEN_ERR_INVALID_ARG for any other code.
+ * Codes 1198 / 2198 / 3198 are ABLATIONS of 198 for power measurements -- the same kernel without its direct-to-LDS loads
+ * inside the k-loop / with loads that only re-read the first k-step (cache hits) / without its LDS operand reads.  They
+ * compute garbage (all accesses in bounds): never leave one of them set.
  */
 hexgen_status_t hexgen_set_gemm_tile(int code);
 

@@ -258,7 +258,13 @@ __device__ __forceinline__ void gemm_tile_of_id(int id, int n_blocks, int t_bloc
 // after it.  So while one wave of a SIMD waits for LDS data, for its loads or at a barrier, the other one is inside
 // its MFMA run: the barriers and waits that idle the matrix core in the lock-stepped loop below fall into the
 // shadow of the other wave's MFMAs.
-template <int FM, int FT, int WM, int WT, int S, int MODE, bool PP = false>
+//
+// ABL (measurement only; results are garbage, every access stays in bounds and every barrier is kept): the same kernel
+// with one activity of its k-loop taken out, to price that activity on a power-limited chip.  1: no direct-to-LDS
+// loads inside the loop (the MFMAs run on the stages the prologue fetched); 2: the loads are issued but every k-step
+// re-reads the block's first k-step (cache hits, no new bytes from HBM); 3: the operand fragments are read from LDS
+// for the first k-step only.
+template <int FM, int FT, int WM, int WT, int S, int MODE, bool PP = false, int ABL = 0>
 __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *__restrict__ Wp,
                                                                  const bf16_t *__restrict__ Xp, int N, int k_tiles,
                                                                  int n_tiles, int t_tiles, int T, int n_blocks,
@@ -326,7 +332,7 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
     // contains no such instruction (no LDS-direct builtin, no movrel, no message), so nothing relies on its value.
     const unsigned lane_bytes = (unsigned)lane * 16u;
     auto issue_one = [&](int kt, int x) {
-        const int kc = min(kt, k_len - 1);
+        const int kc = ABL == 2 ? 0 : min(kt, k_len - 1);
         bf16x8 *st = smem + (size_t)(kt % S) * STAGE;
         const bf16x8 *src = x < LA ? asrc[x] + kc * astep : bsrc[x - LA] + (size_t)kc * 64;
         bf16x8 *dst = x < LA ? st + (wave + NW * x) * 64 : st + (TA + wave + NW * (x - LA)) * 64;
@@ -371,17 +377,21 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
             // of stage kt - 1, which both halves of the block have finished reading (barriers below)
             const bf16x8 *sa = smem + (size_t)(kt % S) * STAGE + (wm * FM * 2) * 64 + frag;
             const bf16x8 *sb = smem + (size_t)(kt % S) * STAGE + (TA + wt * FT * 2) * 64 + frag;
+            if (ABL != 3 || kt == 0) {
 #pragma unroll
-            for (int kh = 0; kh < 2; ++kh) {
+                for (int kh = 0; kh < 2; ++kh) {
 #pragma unroll
-                for (int x = 0; x < FT; ++x) pb[kh][x] = sb[x * 128 + kh * 32];
+                    for (int x = 0; x < FT; ++x) pb[kh][x] = sb[x * 128 + kh * 32];
 #pragma unroll
-                for (int x = 0; x < FM; ++x) pa[kh][x] = sa[x * 128 + kh * 32];
+                    for (int x = 0; x < FM; ++x) pa[kh][x] = sa[x * 128 + kh * 32];
+                }
             }
+            if (ABL != 1) {
 #pragma unroll
-            for (int x = 0; x < LPT; ++x) issue_one(kt + S - 1, x);
+                for (int x = 0; x < LPT; ++x) issue_one(kt + S - 1, x);
+            }
             __builtin_amdgcn_sched_barrier(0);
-            HX_WAIT_VM((S - 2) * LPT);             // this wave's loads of stage kt + 1 have landed
+            HX_WAIT_VM(ABL == 1 ? 0 : (S - 2) * LPT);      // this wave's loads of stage kt + 1 have landed
             HX_LDS_BARRIER();                      // operands in registers; barrier
             __builtin_amdgcn_sched_barrier(0);
             // compute phase
@@ -664,14 +674,14 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t *__restri
                 floatx4{acc[j][4 * q], acc[j][4 * q + 1], acc[j][4 * q + 2], acc[j][4 * q + 3]};
 }
 
-template <int FM, int FT, int WM, int WT, int S, int MODE, bool PP = false>
+template <int FM, int FT, int WM, int WT, int S, int MODE, bool PP = false, int ABL = 0>
 static void launch_cfg(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles, int n_tiles, int t_tiles, int T,
                        const GemmEpi &e, float *part, size_t part_floats, hipStream_t s) {
     constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT;
     const int n_blocks = (n_tiles + TA - 1) / TA, t_blocks = (t_tiles + TB - 1) / TB;
     const int total = n_blocks * t_blocks;
     const int grid = (total + 7) / 8 * 8;
-    auto kern = gemm_mfma_kernel<FM, FT, WM, WT, S, MODE, PP>;
+    auto kern = gemm_mfma_kernel<FM, FT, WM, WT, S, MODE, PP, ABL>;
     const int pm_h = 4, pt_w = 8;         // patch of tiles one XCD works on at a time: 4 feature blocks x 8 token blocks
     const size_t dyn = (size_t)S * (TA + TB) * 64 * sizeof(bf16x8) + (size_t)TB * 16 * sizeof(float);
     static bool raised = false;           // more than the default 64 KB of LDS per block
@@ -700,7 +710,7 @@ static void launch_cfg(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles, i
 // tile configuration forced for every GEMM launch of the process (0 = choose by shape); a measurement and test hook
 static std::atomic<int> g_force_tile{0};
 bool set_gemm_tile(int code) {
-    for (int ok : {0, 44, 48, 84, 88, 94, 49, 98, 72, 198})
+    for (int ok : {0, 44, 48, 84, 88, 94, 49, 98, 72, 198, 1198, 2198, 3198})
         if (code == ok) { g_force_tile.store(code, std::memory_order_relaxed); return true; }
     return false;
 }
@@ -744,7 +754,7 @@ static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T,
     }
     if (force) cfg = force;
     // the RESID epilogue emits one sum-of-squares partial per wave: its 32 FM features must be 128
-    if (MODE == DEC_RESID && cfg != 88 && cfg != 84 && cfg != 98 && cfg != 198) cfg = cfg == 72 ? 198 : 84;
+    if (MODE == DEC_RESID && cfg != 88 && cfg != 84 && cfg != 98 && cfg % 1000 != 198) cfg = cfg == 72 ? 198 : 84;
     // one 128-token tile (a short prompt): 128-token block tiles; the split contraction then runs a short k-loop per
     // block with the weights coming from HBM, so the 256 x 128 tile of RESID keeps six stages in flight instead of four
     const bool short_prompt = !force && t_tiles <= 8;
@@ -754,6 +764,9 @@ static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T,
     if (cfg == 88) HX_G(4, 4, 2, 2, 4);
     else if (cfg == 98) HX_G(4, 2, 2, 4, 4);
     else if (cfg == 198) launch_cfg<4, 2, 2, 4, 4, MODE, true>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s);
+    else if (cfg == 1198) launch_cfg<4, 2, 2, 4, 4, MODE, true, 1>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s);
+    else if (cfg == 2198) launch_cfg<4, 2, 2, 4, 4, MODE, true, 2>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s);
+    else if (cfg == 3198) launch_cfg<4, 2, 2, 4, 4, MODE, true, 3>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s);
     else if (cfg == 94) { if constexpr (MODE != DEC_RESID) HX_G(2, 2, 2, 4, 4); }
     else if (cfg == 49) { if constexpr (MODE != DEC_RESID) HX_G(2, 2, 4, 2, 4); }
     else if (cfg == 84) HX_G(4, 2, 2, 2, 4);

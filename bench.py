@@ -202,6 +202,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="l70_full", help="headline workload (a bf16 configuration)")
     ap.add_argument("--prefill-reps", type=int, default=2)
+    ap.add_argument("--layers", type=int, default=0,
+                    help="measurement aid for profiler passes: run the headline stage with this many layers instead of the "
+                         "workload's (per-layer and per-kernel figures are unchanged; the JSON line says so)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the other configurations' legs")
     ap.add_argument("--no-head", action="store_true", help="skip the LM-head leg (model end next to the last stage)")
@@ -225,6 +228,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cfg = CONFIGS[args.workload]
     assert cfg.dtype == "bf16", "the headline workload must be one of the bf16 configurations"
+    if args.layers > 0:
+        cfg = cfg.scaled(n_layers=args.layers)
     K, W = args.steps, args.warmup
     nproc = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
     log(f"host: nproc {nproc} (os.cpu_count {os.cpu_count()})")
@@ -258,7 +263,8 @@ def main():
                                   else f"prompts of {min(lens)}..{max(lens)} tokens ({sum(lens)} rows) prefilled, then "
                                        f"one decode step per timed step against the ragged cache"),
                    "hidden": cfg.hidden, "local_q_heads": cfg.hq_l, "local_kv_heads": cfg.hkv_l,
-                   "head_dim": cfg.head_dim, "local_ffn": cfg.ffn_l, "layers": cfg.n_layers, "batch": be.b,
+                   "head_dim": cfg.head_dim, "local_ffn": cfg.ffn_l, "layers": cfg.n_layers,
+                   "layers_of_the_workload": CONFIGS[args.workload].n_layers, "batch": be.b,
                    "weights_GB": round(be.st.weight_bytes() / 1e9, 1)},
         "us_per_layer": dec["us_per_layer"], "stage_hbm_frac": dec["hbm_frac"],
         "prefill_tokens_per_s": pre["tokens_per_s"] if pre else None,

@@ -41,9 +41,10 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 // features 8 q + 4 (l / 32) .. + 3 of the 32-feature block, i.e. of the 16-row tile q / 2 its rows
 // (q % 2) * 8 + 4 (l / 32) .. + 3.  Rotary pairs (tile rows r, r + 8) and gate / up pairs (tiles 2m, 2m + 1)
 // therefore sit in the same lane, in quads q and q ^ 1 respectively q and q + 2: no cross-lane traffic.
-// acc: the wave's FM x FT result tiles of block (bm, bt), wave (wm, wt); rstd_s: 1 / rms of the block's token columns.
-template <int FM, int FT, int WM, int WT, int MODE>
-__device__ __forceinline__ void gemm_epilogue(const floatx16 (&acc)[FM][FT], int bm, int bt, int wm, int wt, int lane, int N,
+// acc_of(i, j): the wave's result tile (i, j) of its FM x FT tiles of block (bm, bt), wave (wm, wt), each asked for once
+// (the two-phase loop converts its 16 x 16 results tile by tile on demand); rstd_s: 1 / rms of the block's token columns.
+template <int FM, int FT, int WM, int WT, int MODE, typename AccF>
+__device__ __forceinline__ void gemm_epilogue(AccF acc_of, int bm, int bt, int wm, int wt, int lane, int N,
                                               int n_tiles, int T, const GemmEpi &e, const float *rstd_s,
                                               float *ssq_lds = nullptr) {
     constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT, NTOK = TB * 16;
@@ -85,7 +86,7 @@ __device__ __forceinline__ void gemm_epilogue(const floatx16 (&acc)[FM][FT], int
             if (i + 1 < FM) load_h(hv[(i + 1) & 1], i + 1);
 #pragma unroll
             for (int j = 0; j < FT; ++j) {
-                const floatx16 &c = acc[i][j];
+                const floatx16 c = acc_of(i, j);
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int n = (bm * TA + (wm * FM + i) * 2) * 16 + 8 * q + 4 * hl;
@@ -159,7 +160,7 @@ __device__ __forceinline__ void gemm_epilogue(const floatx16 (&acc)[FM][FT], int
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
             const int t16 = bm * TA + (wm * FM + i) * 2;        // first 16-row tile of this 32-feature block
-            const floatx16 &c = acc[i][j];
+            const floatx16 c = acc_of(i, j);
             if (MODE == DEC_RAW) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -371,20 +372,28 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
         HX_WAIT_VM((S - 2) * LPT);                 // stage 0 has landed (this wave's share of it)
         HX_LDS_BARRIER();                          // ... and everybody's
         if (grp == 1) asm volatile("s_barrier" ::: "memory");       // half a step behind waves 0..3 from here on
-        bf16x8 pa[2][FM], pb[2][FT];
+        // The MFMAs of this loop are v_mfma_f32_16x16x32_bf16 on the fragment tiles as they lie in LDS (one 128-bit read per
+        // 16-row tile and k-step, lane l reads entry l): on operands whose bits toggle the chip is power-limited, and this
+        // form sustains about 12 % more flops than 32x32x16 at the same socket power (register-only probe,
+        // profiles/hbm_mfma_calibration.txt).  Same LDS traffic and MFMA cycles per k-step as the 32x32x16 form: 12 reads,
+        // 32 x 16 cycles.  a16[i][j] = features 16 i .. + 15 of the wave tile x tokens 16 j .. + 15; lane l holds token
+        // l % 16 and features 4 (l / 16) .. + 3.
+        floatx4 a16[2 * FM][2 * FT];
+#pragma unroll
+        for (int i = 0; i < 2 * FM; ++i)
+#pragma unroll
+            for (int j = 0; j < 2 * FT; ++j) a16[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        bf16x8 pa[2 * FM], pb[2 * FT];
         for (int kt = 0; kt < k_len; ++kt) {
             // memory phase: the whole k-step's operands, then this wave's loads of stage kt + S - 1 into the buffer
             // of stage kt - 1, which both halves of the block have finished reading (barriers below)
-            const bf16x8 *sa = smem + (size_t)(kt % S) * STAGE + (wm * FM * 2) * 64 + frag;
-            const bf16x8 *sb = smem + (size_t)(kt % S) * STAGE + (TA + wt * FT * 2) * 64 + frag;
+            const bf16x8 *sa = smem + (size_t)(kt % S) * STAGE + (wm * FM * 2) * 64 + lane;
+            const bf16x8 *sb = smem + (size_t)(kt % S) * STAGE + (TA + wt * FT * 2) * 64 + lane;
             if (ABL != 3 || kt == 0) {
 #pragma unroll
-                for (int kh = 0; kh < 2; ++kh) {
+                for (int x = 0; x < 2 * FT; ++x) pb[x] = sb[x * 64];
 #pragma unroll
-                    for (int x = 0; x < FT; ++x) pb[kh][x] = sb[x * 128 + kh * 32];
-#pragma unroll
-                    for (int x = 0; x < FM; ++x) pa[kh][x] = sa[x * 128 + kh * 32];
-                }
+                for (int x = 0; x < 2 * FM; ++x) pa[x] = sa[x * 64];
             }
             if (ABL != 1) {
 #pragma unroll
@@ -397,29 +406,48 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
             // compute phase
             __builtin_amdgcn_s_setprio(1);
 #pragma unroll
-            for (int kh = 0; kh < 2; ++kh)
+            for (int i = 0; i < 2 * FM; ++i)
 #pragma unroll
-                for (int m = 0; m < FM * FT; ++m)
-                    acc[m / FT][m % FT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[kh][m / FT], pb[kh][m % FT], acc[m / FT][m % FT], 0, 0, 0);
+                for (int j = 0; j < 2 * FT; ++j)
+                    a16[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa[i], pb[j], a16[i][j], 0, 0, 0);
             __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
             asm volatile("s_barrier" ::: "memory");
         }
         if (grp == 0) asm volatile("s_barrier" ::: "memory");       // the barrier waves 4..7 passed ahead of their loop
         HX_WAIT_VM(0);
+        // Into the register layout of a 32 x 32 MFMA result, which the epilogues are written for: lane L holds token
+        // L % 32 and, in register 4 q + r, feature 8 q + 4 (L / 32) + r of the 32 x 32 block.  That value sits in the
+        // 16 x 16 tile (q / 2, (L % 32) / 16) of the block, register r, lane 16 (2 (q % 2) + L / 32) + L % 16.  Converted
+        // tile by tile when the epilogue asks for it, so that the two layouts never hold the whole wave tile at once.
+        auto acc_of = [&](int i, int j) {
+            floatx16 c;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int src = 16 * (2 * (q & 1) + (lane >> 5)) + (lane & 15);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float v0 = __shfl(a16[2 * i + (q >> 1)][2 * j][r], src, 64);
+                    const float v1 = __shfl(a16[2 * i + (q >> 1)][2 * j + 1][r], src, 64);
+                    c[4 * q + r] = (lane & 16) ? v1 : v0;
+                }
+            }
+            return c;
+        };
         if (part != nullptr) {
             float *dst = part + ((((size_t)blockIdx.y * total + id) * NW + wave) * (FM * FT)) * 1024 + lane * 4;
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int j = 0; j < FT; ++j)
+                for (int j = 0; j < FT; ++j) {
+                    const floatx16 c = acc_of(i, j);
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
-                        *reinterpret_cast<floatx4 *>(dst + (i * FT + j) * 1024 + q * 256) =
-                            floatx4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                        *reinterpret_cast<floatx4 *>(dst + (i * FT + j) * 1024 + q * 256) = floatx4{c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]};
+                }
             return;
         }
-        gemm_epilogue<FM, FT, WM, WT, MODE>(acc, bm, bt, wm, wt, lane, N, n_tiles, T, e, rstd_s);
+        gemm_epilogue<FM, FT, WM, WT, MODE>(acc_of, bm, bt, wm, wt, lane, N, n_tiles, T, e, rstd_s);
         return;
     }
     constexpr int H1 = (LPT + 1) / 2, H2 = LPT / 2;  // loads issued behind / in front of the barrier
@@ -520,7 +548,7 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
                         floatx4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
         return;
     }
-    gemm_epilogue<FM, FT, WM, WT, MODE>(acc, bm, bt, wm, wt, lane, N, n_tiles, T, e, rstd_s);
+    gemm_epilogue<FM, FT, WM, WT, MODE>([&](int i, int j) { return acc[i][j]; }, bm, bt, wm, wt, lane, N, n_tiles, T, e, rstd_s);
 }
 
 // Second pass of a split contraction: block `id` (the same tile and wave layout as gemm_mfma_kernel) adds its result
@@ -570,7 +598,7 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_finish_kernel(const float *
                 }
     }
     __syncthreads();
-    gemm_epilogue<FM, FT, WM, WT, MODE>(acc, bm, bt, wm, wt, lane, N, n_tiles, T, e, rstd_s, ssq_lds);
+    gemm_epilogue<FM, FT, WM, WT, MODE>([&](int i, int j) { return acc[i][j]; }, bm, bt, wm, wt, lane, N, n_tiles, T, e, rstd_s, ssq_lds);
 }
 
 // -------------------------------------------------------------------------------------------------

@@ -287,7 +287,8 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *sink, int iters)
             for (int i = 0; i < 8; ++i) {
                 if (LDS) a[i] = sm[(i + it + wave) & 31][lane];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < 8; ++j)      // written as asm: the builtin form makes the compiler shuffle accumulator registers in this loop
+                    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(a[i]), "v"(b[j]));
             }
         }
 #pragma unroll
@@ -316,7 +317,8 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *sink, int iters)
                 for (int i = 0; i < 4; ++i) {
                     if (LDS) a[i] = sm[(i + it + wave + kh * 4) & 31][lane];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < 4; ++j)
+                        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(a[i]), "v"(b[j]));
                 }
             }
         }

@@ -44,7 +44,7 @@ def measured_traffic(workload):
     scaled by a copy of known size) in an EARLIER run, read from the committed summary of that run; (None, None)
     when no summary for this workload exists.  The figure is not measured by this run: the source file is named
     beside it in the JSON."""
-    path = os.path.join(ROOT, "profiles", f"decode_{workload}_pmc_traffic.txt")
+    path = os.path.join(ROOT, "profiles", f"{workload}_pmc_traffic.txt")
     try:
         m = re.search(r"^traffic_bytes_per_launch\s+(\S+)\s+(\d+)", open(path).read(), flags=re.M)
     except OSError:

@@ -59,6 +59,7 @@ class Bench:
     def __init__(self, torch, hx, generate, cfg, max_decode_steps, keep_layers=()):
         self.torch, self.hx, self.generate, self.cfg = torch, hx, generate, cfg
         self.rank = cfg.tp_ranks[0]
+        self.td = {"bf16": torch.bfloat16, "f16": torch.float16}[cfg.dtype]
         t0 = time.time()
         self.st = hx.Stage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, cfg.n_layers, cfg.tp_degree, self.rank,
                            cfg.dtype, cfg.rms_eps, cfg.rope_theta)
@@ -82,8 +83,8 @@ class Bench:
                     self.kv.fill(l, s, k.cpu(), v.cpu())
         n_x = max_decode_steps
         self.X = torch.stack([generate.hidden_rows(cfg, self.b, stream_id=1 + i, device="cuda") for i in range(n_x)])
-        self.X = self.X.to(torch.bfloat16).contiguous()
-        self.outp = torch.empty(self.b, cfg.hidden, dtype=torch.bfloat16, device="cuda")
+        self.X = self.X.to(self.td).contiguous()
+        self.outp = torch.empty(self.b, cfg.hidden, dtype=self.td, device="cuda")
         self.outr = torch.empty_like(self.outp)
         torch.cuda.synchronize()
         log(f"{cfg.name}: setup {time.time() - t0:.1f}s, weights {self.st.weight_bytes() / 1e9:.3f} GB")
@@ -92,7 +93,7 @@ class Bench:
     def prefill(self, reps, warm=1):
         torch, cfg, st = self.torch, self.cfg, self.st
         T = sum(self.lens)
-        Xp = self.generate.hidden_rows(cfg, T, device="cuda").to(torch.bfloat16).contiguous()
+        Xp = self.generate.hidden_rows(cfg, T, device="cuda").to(self.td).contiguous()
         outp, outr = torch.empty_like(Xp), torch.empty_like(Xp)
         for _ in range(warm):
             st.prefill(self.kv, Xp, self.lens, outp, outr)
@@ -201,6 +202,9 @@ def main():
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="l70_full", help="headline workload (a bf16 configuration)")
+    ap.add_argument("--dtype", default="bf16", choices=("bf16", "f16"),
+                    help="16-bit storage type of the headline workload (the configurations name bf16; f16 runs the "
+                         "same shapes through the fp16 build of the kernels)")
     ap.add_argument("--prefill-reps", type=int, default=2)
     ap.add_argument("--layers", type=int, default=0,
                     help="measurement aid for profiler passes: run the headline stage with this many layers instead of the "
@@ -228,6 +232,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cfg = CONFIGS[args.workload]
     assert cfg.dtype == "bf16", "the headline workload must be one of the bf16 configurations"
+    if args.dtype != cfg.dtype:
+        cfg = cfg.scaled(dtype=args.dtype)         # same shapes and draws, stored in the other 16-bit format
     if args.layers > 0:
         cfg = cfg.scaled(n_layers=args.layers)
     K, W = args.steps, args.warmup
@@ -256,7 +262,7 @@ def main():
     result = {
         "metric": "decode_tokens_per_s_per_stage", "value": dec["tokens_per_s"], "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": dec["ms_per_step"],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: Llama-2-70B-shaped stage, TP{cfg.tp_degree} rank {be.rank}, "
                                f"{cfg.n_layers} layers, batch {be.b}, "
                                + (f"decode from a synthetic KV context of {cfg.kv_context}" if cfg.kv_context is not None

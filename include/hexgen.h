@@ -33,7 +33,10 @@ extern "C" {
 typedef struct hexgen_stage    hexgen_stage_t;     /* opaque, library-owned */
 typedef struct hexgen_kv_cache hexgen_kv_cache_t;  /* opaque, library-owned */
 
-typedef enum { HEXGEN_F32 = 0, HEXGEN_BF16 = 1 } hexgen_dtype_t;
+/* Storage / operand type of weights, activations handed to the matrix cores and the KV cache; accumulation, norms,
+ * softmax and the residual stream are fp32 for every value.  HEXGEN_F16 is the 2-byte precision the cost model's
+ * B_type example names (Section 4.1 / Appendix B); HEXGEN_BF16 is the same path with the other 16-bit format. */
+typedef enum { HEXGEN_F32 = 0, HEXGEN_BF16 = 1, HEXGEN_F16 = 2 } hexgen_dtype_t;
 
 typedef enum {
     HEXGEN_OK = 0,
@@ -53,7 +56,7 @@ const char *hexgen_status_string(hexgen_status_t s);
  * library derives head_dim = hidden / n_heads and rank `tp_rank`'s shard: query heads
  * [r*hq/t, (r+1)*hq/t), KV heads [r*hkv/t, (r+1)*hkv/t), FFN columns [r*F/t, (r+1)*F/t).
  * HEXGEN_ERR_SHAPE unless hidden % n_heads == 0, n_heads % n_kv_heads == 0, n_heads, n_kv_heads
- * and ffn divisible by tp_degree, 0 <= tp_rank < tp_degree, head_dim in {64, 128}, and (bf16)
+ * and ffn divisible by tp_degree, 0 <= tp_rank < tp_degree, head_dim in {64, 128}, and (bf16, fp16)
  * hidden a multiple of 128, local q width and local ffn multiples of 32.  Defaults: rms_eps 1e-5, rope_theta 1e4.
  */
 hexgen_status_t hexgen_stage_create(int hidden, int n_heads, int n_kv_heads, int ffn, int n_layers,
@@ -67,7 +70,7 @@ void            hexgen_stage_destroy(hexgen_stage_t *st);
 /* Full (unsharded) matrices of one layer, row-major [in, out]:
  *   g_attn [H], wq [H, hq*d], wk [H, hkv*d], wv [H, hkv*d], wo [hq*d, H], g_ffn [H],
  *   w1 [H, F] (gate), w3 [H, F] (up), w2 [F, H] (down); element type = the stage's dtype
- *   (fp32, or bf16 as raw 16-bit values).  Pointers may be host or device memory (detected).
+ *   (fp32, or bf16 / fp16 as raw 16-bit values).  Pointers may be host or device memory (detected).
  * The library copies rank r's shard (columns of wq/wk/wv/w1/w3, rows of wo/w2) and repacks it;
  * the call synchronises the device before returning, the sources may be freed afterwards.
  */
@@ -119,7 +122,7 @@ hexgen_status_t hexgen_stage_decode(hexgen_stage_t *st, hexgen_kv_cache_t *kv, i
  * stream, projection operands, split partial sums of the batched projections, split-attention partials and arrival
  * counters, sums of squares, row positions -- is laid out in one file-scope device array of
  * HEXGEN_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process ends.
- *   - bf16 stages only (HEXGEN_ERR_SHAPE otherwise); at most 32 sequences in the batch, and the workspace of the
+ *   - bf16 and fp16 stages only (HEXGEN_ERR_SHAPE otherwise); at most 32 sequences in the batch, and the workspace of the
  *     call (hexgen_stage_decode_static_bytes(st, batch)) must fit the array: HEXGEN_ERR_CAPACITY otherwise, nothing
  *     is launched.  Every 70B-shaped configuration up to the full-width stage at batch 32 (39 MB) fits.
  *   - the cache must have been prefilled (or set_lengths called) as for hexgen_stage_decode; `step` as there; the
@@ -184,7 +187,7 @@ hexgen_status_t hexgen_stage_set_tap(hexgen_stage_t *st, int layer, void *h_dump
  * device int32 [n] (ids outside [0, vocab) are clamped); rows_out: device [n, hidden] in `dtype`, caller-owned.
  *
  * hexgen_head: vocabulary-parallel over tp_degree ranks (vocab divisible by it, else HEXGEN_ERR_SHAPE); rank tp_rank
- * holds columns [r V/t, (r+1) V/t) of the untied LM head.  hidden: multiple of 128 (bf16) or 4 (f32).
+ * holds columns [r V/t, (r+1) V/t) of the untied LM head.  hidden: multiple of 128 (bf16, fp16) or 4 (f32).
  * hexgen_head_load: g_final [hidden] and the FULL matrix w_lm [hidden, vocab], row-major, host or device, in the head's
  * dtype; the library copies and repacks its shard, the caller keeps its buffers.
  * hexgen_head_greedy: x = hidden_a (+ hidden_b when not NULL: e.g. a stage's out_resid and out_partial), device

@@ -15,7 +15,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhexgen.so")
 
-HEXGEN_F32, HEXGEN_BF16 = 0, 1
+HEXGEN_F32, HEXGEN_BF16, HEXGEN_F16 = 0, 1, 2
+_DTYPE_CODE = {"f32": HEXGEN_F32, "bf16": HEXGEN_BF16, "f16": HEXGEN_F16}
 STATUS_NAMES = {0: "HEXGEN_OK", 1: "HEXGEN_ERR_INVALID_ARG", 2: "HEXGEN_ERR_SHAPE", 3: "HEXGEN_ERR_STATE",
                 4: "HEXGEN_ERR_CAPACITY", 5: "HEXGEN_ERR_OOM", 6: "HEXGEN_ERR_DEVICE"}
 
@@ -122,23 +123,23 @@ def _stream_handle(stream: Optional[torch.cuda.Stream]) -> Optional[int]:
 
 
 def _torch_dtype(dtype: int):
-    return torch.float32 if dtype == HEXGEN_F32 else torch.bfloat16
+    return {HEXGEN_F32: torch.float32, HEXGEN_BF16: torch.bfloat16, HEXGEN_F16: torch.float16}[dtype]
 
 
 def _dtype_code(dtype) -> int:
     if isinstance(dtype, str):
-        return {"f32": HEXGEN_F32, "bf16": HEXGEN_BF16}[dtype]
+        return _DTYPE_CODE[dtype]
     if isinstance(dtype, torch.dtype):
-        return {torch.float32: HEXGEN_F32, torch.bfloat16: HEXGEN_BF16}[dtype]
+        return {torch.float32: HEXGEN_F32, torch.bfloat16: HEXGEN_BF16, torch.float16: HEXGEN_F16}[dtype]
     return int(dtype)
 
 
 class Stage:
-    """Owns a hexgen_stage_t.  dtype: "f32" | "bf16"."""
+    """Owns a hexgen_stage_t.  dtype: "f32" | "bf16" | "f16"."""
 
     def __init__(self, hidden, n_heads, n_kv_heads, ffn, n_layers, tp_degree, tp_rank, dtype,
                  rms_eps: float = 1e-5, rope_theta: float = 10000.0):
-        self.dtype = {"f32": HEXGEN_F32, "bf16": HEXGEN_BF16}[dtype] if isinstance(dtype, str) else int(dtype)
+        self.dtype = _DTYPE_CODE[dtype] if isinstance(dtype, str) else int(dtype)
         h = C.c_void_p()
         _check(lib.hexgen_stage_create(hidden, n_heads, n_kv_heads, ffn, n_layers, tp_degree, tp_rank,
                                        self.dtype, C.byref(h)), "hexgen_stage_create")

@@ -12,7 +12,8 @@ BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhexgen.so")
 
 SOURCES = ["stage.hip", "cost_model.hip", "scheduler.hip", "search.hip", "kernels_layout.hip", "kernels_bf16_decode.hip", "kernels_bf16_gemm.hip",
-           "kernels_bf16_attn.hip", "kernels_f32.hip"]
+           "kernels_bf16_attn.hip", "kernels_bf16_convert.hip", "kernels_f16_decode.hip", "kernels_f16_gemm.hip", "kernels_f16_attn.hip",
+           "kernels_f16_convert.hip", "kernels_f32.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -13,9 +13,23 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
-typedef uint16_t bf16_t;   // raw storage
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float hx_floatx16;
+typedef uint16_t h16_t;    // raw storage of one 16-bit element (bf16 or fp16)
+
+// ---- the 16-bit element type of this translation unit -------------------------------------------------------------
+// The bf16 and the fp16 stage share every kernel: layouts, indexing and schedules only know "16-bit element".  What
+// differs -- the MFMA opcode, fp32 <-> element conversion -- sits in the few functions below, and each kernel source
+// is compiled once per element type (HX_ELEM_F16 defined or not) into its own namespace HX_NS (bf16 / f16).
+// h16x8 = the 8 elements one lane contributes to an MFMA operand.
+#ifdef HX_ELEM_F16
+#define HX_NS f16
+typedef _Float16 hx_elem;
+#else
+#define HX_NS bf16
+typedef __bf16 hx_elem;
+#endif
+typedef __attribute__((__vector_size__(8 * sizeof(hx_elem)))) hx_elem h16x8;
 
 #define HX_WAVE 64
 
@@ -42,31 +56,66 @@ __host__ __device__ inline size_t frag_offset(int idx, int k, int k_tiles) {
     return ((size_t)(it * (size_t)k_tiles + kt) * 64 + lane) * 8 + (k & 7);
 }
 
-__device__ inline float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
-
-// fp32 -> bf16, round-to-nearest-even, with the hardware's packed conversion (v_cvt_pk_bf16_f32: one instruction
-// per pair instead of half a dozen integer operations per value; the epilogues and the softmax are full of these)
-typedef __bf16 hx_bf16x2 __attribute__((ext_vector_type(2)));
+typedef hx_elem hx_elemx2 __attribute__((ext_vector_type(2)));
 typedef float hx_floatx2 __attribute__((ext_vector_type(2)));
-__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+#ifdef HX_ELEM_F16
+__device__ inline float h16_to_f32(h16_t v) {
+    _Float16 h;
+    __builtin_memcpy(&h, &v, 2);
+    return (float)h;
+}
+#else
+__device__ inline float h16_to_f32(h16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+#endif
+// the two elements of a packed pair (low half first)
+__device__ inline void h16x2_to_f32(uint32_t raw, float &a, float &b) {
+#ifdef HX_ELEM_F16
+    a = h16_to_f32((h16_t)(raw & 0xffffu));
+    b = h16_to_f32((h16_t)(raw >> 16));
+#else
+    a = __uint_as_float(raw << 16);
+    b = __uint_as_float(raw & 0xffff0000u);
+#endif
+}
+
+// fp32 -> element, round-to-nearest-even, with the hardware's packed conversion (one instruction per pair instead of
+// half a dozen integer operations per value; the epilogues and the softmax are full of these).  fp16: values beyond
+// 65504 become infinite, as the format has it.
+__device__ inline uint32_t pack_h16x2(float lo, float hi) {
     const hx_floatx2 v = {lo, hi};
-    const hx_bf16x2 h = __builtin_convertvector(v, hx_bf16x2);
+    const hx_elemx2 h = __builtin_convertvector(v, hx_elemx2);
     return *reinterpret_cast<const uint32_t *>(&h);
 }
-__device__ inline bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
+__device__ inline h16_t f32_to_h16(float f) { return (h16_t)(pack_h16x2(f, 0.f) & 0xffffu); }
 
-// x = hi + lo with both parts bf16: the pair carries ~16 mantissa bits of an fp32 activation.
+// the two MFMA forms of the kernels, on this translation unit's element type
+__device__ __forceinline__ floatx4 hx_mfma16(h16x8 a, h16x8 b, floatx4 c) {
+#ifdef HX_ELEM_F16
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+#else
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+#endif
+}
+__device__ __forceinline__ hx_floatx16 hx_mfma32(h16x8 a, h16x8 b, hx_floatx16 c) {
+#ifdef HX_ELEM_F16
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+#else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+#endif
+}
+
+// x = hi + lo with both parts 16-bit: the pair carries ~16 (bf16) / ~21 (fp16) mantissa bits of an fp32 activation.
 // Decode kernels are HBM-bound, so feeding hi and lo through two MFMAs costs nothing and removes the
 // bf16 rounding of activations from the error budget of deep stages.
-__device__ inline void split_bf16(float x, bf16_t &hi, bf16_t &lo) {
-    hi = f32_to_bf16(x);
-    lo = f32_to_bf16(x - bf16_to_f32(hi));
+__device__ inline void split_h16(float x, h16_t &hi, h16_t &lo) {
+    hi = f32_to_h16(x);
+    lo = f32_to_h16(x - h16_to_f32(hi));
 }
 // packs hi parts of (a, b) into *phi and lo parts into *plo
 __device__ inline void split_pack2(float a, float b, uint32_t &phi, uint32_t &plo) {
-    bf16_t ah, al, bh, bl;
-    split_bf16(a, ah, al);
-    split_bf16(b, bh, bl);
+    h16_t ah, al, bh, bl;
+    split_h16(a, ah, al);
+    split_h16(b, bh, bl);
     phi = (uint32_t)ah | ((uint32_t)bh << 16);
     plo = (uint32_t)al | ((uint32_t)bl << 16);
 }

@@ -30,9 +30,8 @@ struct KvGeom {
 // rope_d > 0 (fused QKV weight): columns are heads of width rope_d; each 16-row tile of a head holds 8
 // rotary pairs (rows 0-7 = head columns 8*tl .. 8*tl+7, rows 8-15 = those + rope_d/2), so one MFMA tile is
 // self-contained for RoPE.  The QKV projection output is in this permuted column order.
-void launch_pack_weight(const bf16_t *src, int64_t ld, int k0, int c0, int K, int N, bf16_t *dst,
+void launch_pack_weight(const h16_t *src, int64_t ld, int k0, int c0, int K, int N, h16_t *dst,
                         int dst_tile0, int dst_tile_stride, int dst_n_tiles, int rope_d, hipStream_t s);
-void launch_cvt_bf16_to_f32(const bf16_t *src, float *dst, int64_t n, hipStream_t s);
 void launch_accumulate_f32(float *dst, const float *src, int64_t n, hipStream_t s);
 // decode row map: row i -> (seq i, pos lens[i])
 void launch_decode_rowmap(const int32_t *lens, int32_t *row_seq, int32_t *row_pos, int b, hipStream_t s);
@@ -44,7 +43,7 @@ void launch_stream_read(const void *src, float *sink, int64_t bytes, int blocks,
 // register-resident MFMA loops: 4 waves per block, per wave and iteration 2^20 flop (one 128 x 128 x 32 k-step)
 void launch_mfma_probe(int variant, float *sink, int iters, int blocks, hipStream_t s);
 
-// ---- bf16 path (kernels_bf16_*.hip) ---------------------------------------------------------
+// ---- 16-bit path (kernels_bf16_*.hip, compiled once per element type: namespaces bf16 and f16) --------------------
 
 // ---- decode projections with fused epilogues (kernels_bf16_decode.hip) ---------------------------
 enum { DEC_RAW = 0, DEC_QKV = 1, DEC_RESID = 2, DEC_SWIGLU = 3 };
@@ -62,29 +61,18 @@ struct DecodeEpi {
     KvGeom kg;
     const int32_t *row_pos;
     const float *cos_tab, *sin_tab;
-    bf16_t *q_hi, *q_lo, *kc, *vc;
+    h16_t *q_hi, *q_lo, *kc, *vc;
     // RESID
     float *h;                  // residual stream [T][N] fp32, updated in place
     const float *g_next;       // gain of the next RMSNorm
-    bf16_t *hg;                // (h * g_next) as compact hi/lo decode operand (dec_act_offset)
+    h16_t *hg;                // (h * g_next) as compact hi/lo decode operand (dec_act_offset)
     float *ssq_out;
     int last_layer;            // 1: write out_partial / out_resid (bf16 [T][N]) instead of updating h
-    bf16_t *out_partial, *out_resid;
+    h16_t *out_partial, *out_resid;
     // SWIGLU
-    bf16_t *u;                 // compact hi/lo decode operand [T][F_l]
+    h16_t *u;                 // compact hi/lo decode operand [T][F_l]
     int F_l;
 };
-// Wp . Xa for T <= 32 rows (Xa: compact hi/lo operand [T][K]), one block per output unit, then the
-// epilogue of e.mode
-// `scratch` (device, scratch_floats floats, may be NULL) holds the split partial sums of the batched path (T > 2)
-// `mid` (measurement, may be NULL): recorded on `s` right behind the projection's first kernel, i.e. between the
-// split kernel and the finishing kernel of the batched path
-void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T, const DecodeEpi &e, float *scratch,
-                        size_t scratch_floats, hipStream_t s, hipEvent_t mid = nullptr);
-// stage input rows (+ optional second addend in2) -> h (optional), (x * g) hi/lo planes, sums of squares; block 0
-// publishes row positions from the committed lengths and optionally advances them
-void launch_decode_prologue(const void *in, const void *in2, int in_is_bf16, float *h_out, const float *g, bf16_t *hg,
-                            float *ssq_out, int T, int H, int32_t *lens, int32_t *row_pos, int advance, hipStream_t s);
 // ---- prefill projections with fused epilogues (kernels_bf16_gemm.hip) ----------------------------
 // Same epilogue roles as in decode (DEC_* modes), on packed operands: the input Xp is (h * gain) in
 // fragment tiles, RMSNorm enters as the per-token scale rstd derived from `ssq_in`.
@@ -100,49 +88,18 @@ struct GemmEpi {
     KvGeom kg;
     RowMap rm;
     const float *cos_tab, *sin_tab;
-    bf16_t *q, *kc, *vc;       // q: fragment tiles [T/16][hq_l * d / 32]
+    h16_t *q, *kc, *vc;       // q: fragment tiles [T/16][hq_l * d / 32]
     // RESID
     float *h;                  // residual stream, fp32, 32 x 32 tiled (h_tile_offset), updated in place
     const float *g_next;
-    bf16_t *hg;                // (h * g_next) in fragment tiles [T/16][N/32]
+    h16_t *hg;                // (h * g_next) in fragment tiles [T/16][N/32]
     float *ssq_out;            // [N / 128][T]
     int last_layer;
-    bf16_t *out_partial, *out_resid;
+    h16_t *out_partial, *out_resid;
     // SWIGLU
-    bf16_t *u;                 // fragment tiles [T/16][F_l/32]
+    h16_t *u;                 // fragment tiles [T/16][F_l/32]
     int F_l;
 };
-// `part` (device, part_floats floats, may be NULL): scratch for the fp32 partial tiles of a split contraction, which
-// short prompts use (few token tiles); without it the contraction is never split
-void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, float *part,
-                      size_t part_floats, hipStream_t s);
-// stage input rows -> h (optional), (x * g) in fragment tiles, sums of squares [H / 128][T]
-void launch_untile_h(const float *h_tiled, float *out, int T, int H, hipStream_t s);
-// force a tile configuration of the prefill GEMM (see launch_mode); false for an unknown code
-bool set_gemm_tile(int code);
-void launch_prefill_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg, float *ssq_out,
-                             int T, int H, hipStream_t s);
-
-// row_pos[seq] = position of the new row (= cached context length)
-// o_act: compact hi/lo decode operand [b][hq_l*d] of the W_O projection
-void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, const bf16_t *vc, KvGeom kg,
-                        int hq_l, const int32_t *row_pos, int b, int nsplit, float *part_o, float *part_ml,
-                        unsigned int *arrived, bf16_t *o_act, hipStream_t s);
-// decode attention on the prefill path's layouts, for calls with one new row per sequence: q and o_packed in
-// fragment tiles with row = sequence; row_pos[seq] = position of the new row
-void launch_attn_decode_rows(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,
-                             const int32_t *row_pos, int b, bf16_t *o_packed, hipStream_t s);
-// prefill attention over packed ragged rows (q in fragment tiles); K, V are read from the cache
-void launch_attn_prefill(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,
-                         const int32_t *cu_rows, const int32_t *pos0, int batch, int max_new,
-                         bf16_t *o_packed, hipStream_t s);
-
-// cache <-> host-format fp32 [n][hkv_l][d] staging (device buffers)
-void launch_kv_scatter(const float *k, const float *v, bf16_t *kc, bf16_t *vc, KvGeom kg, int seq,
-                       int pos0, int n, hipStream_t s);
-void launch_kv_gather(const bf16_t *kc, const bf16_t *vc, KvGeom kg, int seq, int pos0, int n, float *k,
-                      float *v, hipStream_t s);
-
 // per row of logits [n][ld]: the largest of the first `valid` entries and its index + id0 (lowest index wins ties)
 void launch_row_argmax(const float *logits, int64_t ld, int valid, int n, int id0, int32_t *token_out, float *logit_out,
                        hipStream_t s);
@@ -150,9 +107,9 @@ void launch_row_argmax(const float *logits, int64_t ld, int valid, int n, int id
 void launch_embed_rows(const void *table, int64_t row_bytes, int vocab, const int32_t *tokens, int n, void *rows_out,
                        hipStream_t s);
 
-void launch_store_out(const float *src, void *dst, int dst_is_bf16, int64_t n, hipStream_t s);
 // p[0 .. bytes) = 0 with a kernel; p 4-byte aligned, bytes a multiple of 4
 void launch_fill_zero(void *p, size_t bytes, hipStream_t s);
+
 
 // ---- fp32 path (kernels_f32.hip): plain layouts, vector ALU -----------------------------------
 void f32_launch_rmsnorm(const float *in, const float *g, float *out, int T, int H, float eps, hipStream_t s);
@@ -165,3 +122,11 @@ void f32_launch_attn(const float *q, const float *kc, const float *vc, int T, in
 void f32_launch_swiglu(const float *ab, float *u, int T, int F_l, hipStream_t s);
 void f32_launch_kv_copy(float *kc, float *vc, float *k, float *v, int hkv_l, int d, int smax, int seq,
                         int pos0, int n, int to_cache, hipStream_t s);
+
+// ---- launchers that depend on the 16-bit element type: the same declarations in namespace bf16 and in namespace f16 ----
+#define HX_DECL_NS bf16
+#include "kernels_h16.inc"
+#undef HX_DECL_NS
+#define HX_DECL_NS f16
+#include "kernels_h16.inc"
+#undef HX_DECL_NS

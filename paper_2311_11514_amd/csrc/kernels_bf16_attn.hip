@@ -13,18 +13,21 @@
 
 #define NEG_INF (-INFINITY)
 
+namespace HX_NS {
+
+
 // One 8-wave block per (sequence, kv head); the waves interleave over the 32-position tiles of the context and
 // their (m, l, o) triples are merged through LDS in wave order.
 // Used when there are enough (sequence, kv head) pairs to fill the chip or the context is short.
 // PF: the layouts of the prefill path on both ends (used when more than 32 sequences decode one row each, which the
 // prefill kernels otherwise serve): q is read from fragment tiles (row = sequence, no lo part), o is written to them.
 template <int D, bool PF>
-__global__ __launch_bounds__(512) void attn_decode_block_kernel(const bf16_t *__restrict__ q,
-                                                               const bf16_t *__restrict__ q_lo,
-                                                               const bf16_t *__restrict__ kc,
-                                                               const bf16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
+__global__ __launch_bounds__(512) void attn_decode_block_kernel(const h16_t *__restrict__ q,
+                                                               const h16_t *__restrict__ q_lo,
+                                                               const h16_t *__restrict__ kc,
+                                                               const h16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
                                                                const int32_t *__restrict__ row_pos,
-                                                               bf16_t *__restrict__ o_act, float scale_log2e) {
+                                                               h16_t *__restrict__ o_act, float scale_log2e) {
     constexpr int KT = D / 32, DT = D / 16, W = 8;
     __shared__ float s_m[W][16], s_l[W][16];
     __shared__ float s_o[W][16][D];
@@ -35,26 +38,26 @@ __global__ __launch_bounds__(512) void attn_decode_block_kernel(const bf16_t *__
     const int head = c * G + j;
     const bool hv = j < G;
 
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    bf16x8 qf[KT], ql[KT];
+    const h16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    h16x8 qf[KT], ql[KT];
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
         const size_t qo = PF ? frag_offset(sq, head * D + kt * 32 + 8 * g, (hq_l * D) >> 5)
                              : ((size_t)sq * hq_l + head) * D + kt * 32 + 8 * g;
-        qf[kt] = hv ? *reinterpret_cast<const bf16x8 *>(q + qo) : zero;
-        ql[kt] = (hv && !PF) ? *reinterpret_cast<const bf16x8 *>(q_lo + qo) : zero;
+        qf[kt] = hv ? *reinterpret_cast<const h16x8 *>(q + qo) : zero;
+        ql[kt] = (hv && !PF) ? *reinterpret_cast<const h16x8 *>(q_lo + qo) : zero;
     }
     floatx4 oacc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) oacc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
     float m = NEG_INF, lsum = 0.f;
     const size_t slab = (size_t)sq * kg.seq_stride + (size_t)c * kg.smax * D;
-    const bf16x8 *ks = reinterpret_cast<const bf16x8 *>(kc + slab) + lane;
-    const bf16x8 *vs = reinterpret_cast<const bf16x8 *>(vc + slab) + lane;
+    const h16x8 *ks = reinterpret_cast<const h16x8 *>(kc + slab) + lane;
+    const h16x8 *vs = reinterpret_cast<const h16x8 *>(vc + slab) + lane;
 
     for (int t = wave; t < n_t32; t += W) {
         floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-        bf16x8 ka[KT], kb[KT], va[DT];
+        h16x8 ka[KT], kb[KT], va[DT];
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) {
             ka[kt] = ks[(size_t)((2 * t) * KT + kt) * 64];
@@ -64,10 +67,10 @@ __global__ __launch_bounds__(512) void attn_decode_block_kernel(const bf16_t *__
         for (int dt = 0; dt < DT; ++dt) va[dt] = vs[(size_t)(t * DT + dt) * 64];
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) {
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt], ql[kt], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[kt], ql[kt], s1, 0, 0, 0);
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt], qf[kt], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[kt], qf[kt], s1, 0, 0, 0);
+            s0 = hx_mfma16(ka[kt], ql[kt], s0);
+            s1 = hx_mfma16(kb[kt], ql[kt], s1);
+            s0 = hx_mfma16(ka[kt], qf[kt], s0);
+            s1 = hx_mfma16(kb[kt], qf[kt], s1);
         }
         const int pbase = t * 32 + 4 * g;
         float mx = NEG_INF;
@@ -90,14 +93,14 @@ __global__ __launch_bounds__(512) void attn_decode_block_kernel(const bf16_t *__
             ps += p0[r] + p1[r];
         }
         lsum = lsum * alpha + ps;
-        union { uint32_t u[4]; bf16x8 v; } pb, pl;
+        union { uint32_t u[4]; h16x8 v; } pb, pl;
         split_pack2(p0[0], p0[1], pb.u[0], pl.u[0]); split_pack2(p0[2], p0[3], pb.u[1], pl.u[1]);
         split_pack2(p1[0], p1[1], pb.u[2], pl.u[2]); split_pack2(p1[2], p1[3], pb.u[3], pl.u[3]);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             oacc[dt] *= alpha;
-            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pl.v, oacc[dt], 0, 0, 0);
-            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb.v, oacc[dt], 0, 0, 0);
+            oacc[dt] = hx_mfma16(va[dt], pl.v, oacc[dt]);
+            oacc[dt] = hx_mfma16(va[dt], pb.v, oacc[dt]);
         }
     }
     lsum += __shfl_xor(lsum, 16, 64);
@@ -144,13 +147,13 @@ __global__ __launch_bounds__(512) void attn_decode_block_kernel(const bf16_t *__
 // The partials cross the chip's L2 slices: after a block barrier one wave publishes the block's stores with a
 // device-scope fence before it counts the block, and the merging block fences again before it reads.
 template <int D>
-__global__ __launch_bounds__(512) void attn_decode_split_kernel(const bf16_t *__restrict__ q,
-                                                               const bf16_t *__restrict__ q_lo,
-                                                               const bf16_t *__restrict__ kc,
-                                                               const bf16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
+__global__ __launch_bounds__(512) void attn_decode_split_kernel(const h16_t *__restrict__ q,
+                                                               const h16_t *__restrict__ q_lo,
+                                                               const h16_t *__restrict__ kc,
+                                                               const h16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
                                                                const int32_t *__restrict__ row_pos, int nsplit,
                                                                float *part_o, float *part_ml, unsigned int *arrived,
-                                                               bf16_t *__restrict__ o_act, float scale_log2e) {
+                                                               h16_t *__restrict__ o_act, float scale_log2e) {
     constexpr int KT = D / 32, DT = D / 16, W = 8;
     __shared__ float s_m[W][16], s_l[W][16];
     __shared__ float s_o[W][16][D];
@@ -164,25 +167,25 @@ __global__ __launch_bounds__(512) void attn_decode_split_kernel(const bf16_t *__
     const int head = c * G + j;
     const bool hv = j < G;
 
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    bf16x8 qf[KT], ql[KT];
+    const h16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    h16x8 qf[KT], ql[KT];
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
         const size_t qo = ((size_t)sq * hq_l + head) * D + kt * 32 + 8 * g;
-        qf[kt] = hv ? *reinterpret_cast<const bf16x8 *>(q + qo) : zero;
-        ql[kt] = hv ? *reinterpret_cast<const bf16x8 *>(q_lo + qo) : zero;
+        qf[kt] = hv ? *reinterpret_cast<const h16x8 *>(q + qo) : zero;
+        ql[kt] = hv ? *reinterpret_cast<const h16x8 *>(q_lo + qo) : zero;
     }
     floatx4 oacc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) oacc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
     float m = NEG_INF, lsum = 0.f;
     const size_t slab = (size_t)sq * kg.seq_stride + (size_t)c * kg.smax * D;
-    const bf16x8 *ks = reinterpret_cast<const bf16x8 *>(kc + slab) + lane;
-    const bf16x8 *vs = reinterpret_cast<const bf16x8 *>(vc + slab) + lane;
+    const h16x8 *ks = reinterpret_cast<const h16x8 *>(kc + slab) + lane;
+    const h16x8 *vs = reinterpret_cast<const h16x8 *>(vc + slab) + lane;
 
     for (int t = t0 + wave; t < t1; t += W) {
         floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-        bf16x8 ka[KT], kb[KT], va[DT];
+        h16x8 ka[KT], kb[KT], va[DT];
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) {
             ka[kt] = ks[(size_t)((2 * t) * KT + kt) * 64];
@@ -192,10 +195,10 @@ __global__ __launch_bounds__(512) void attn_decode_split_kernel(const bf16_t *__
         for (int dt = 0; dt < DT; ++dt) va[dt] = vs[(size_t)(t * DT + dt) * 64];
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) {
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt], ql[kt], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[kt], ql[kt], s1, 0, 0, 0);
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt], qf[kt], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[kt], qf[kt], s1, 0, 0, 0);
+            s0 = hx_mfma16(ka[kt], ql[kt], s0);
+            s1 = hx_mfma16(kb[kt], ql[kt], s1);
+            s0 = hx_mfma16(ka[kt], qf[kt], s0);
+            s1 = hx_mfma16(kb[kt], qf[kt], s1);
         }
         const int pbase = t * 32 + 4 * g;
         float mx = NEG_INF;
@@ -218,14 +221,14 @@ __global__ __launch_bounds__(512) void attn_decode_split_kernel(const bf16_t *__
             ps += p0[r] + p1[r];
         }
         lsum = lsum * alpha + ps;
-        union { uint32_t u[4]; bf16x8 v; } pb, pl;
+        union { uint32_t u[4]; h16x8 v; } pb, pl;
         split_pack2(p0[0], p0[1], pb.u[0], pl.u[0]); split_pack2(p0[2], p0[3], pb.u[1], pl.u[1]);
         split_pack2(p1[0], p1[1], pb.u[2], pl.u[2]); split_pack2(p1[2], p1[3], pb.u[3], pl.u[3]);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             oacc[dt] *= alpha;
-            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pl.v, oacc[dt], 0, 0, 0);
-            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb.v, oacc[dt], 0, 0, 0);
+            oacc[dt] = hx_mfma16(va[dt], pl.v, oacc[dt]);
+            oacc[dt] = hx_mfma16(va[dt], pb.v, oacc[dt]);
         }
     }
     lsum += __shfl_xor(lsum, 16, 64);
@@ -287,9 +290,9 @@ __global__ __launch_bounds__(512) void attn_decode_split_kernel(const bf16_t *__
     }
 }
 
-void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, const bf16_t *vc, KvGeom kg,
+void launch_attn_decode(const h16_t *q, const h16_t *q_lo, const h16_t *kc, const h16_t *vc, KvGeom kg,
                         int hq_l, const int32_t *row_pos, int b, int nsplit, float *part_o, float *part_ml,
-                        unsigned int *arrived, bf16_t *o_act, hipStream_t s) {
+                        unsigned int *arrived, h16_t *o_act, hipStream_t s) {
     const int G = hq_l / kg.hkv_l;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)kg.d);
     if (nsplit <= 1) {       // one block per (sequence, kv head), LDS merge
@@ -312,8 +315,8 @@ void launch_attn_decode(const bf16_t *q, const bf16_t *q_lo, const bf16_t *kc, c
 }
 
 // one new row per sequence on the prefill path's layouts: q and o in fragment tiles (row = sequence)
-void launch_attn_decode_rows(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,
-                             const int32_t *row_pos, int b, bf16_t *o_packed, hipStream_t s) {
+void launch_attn_decode_rows(const h16_t *q, const h16_t *kc, const h16_t *vc, KvGeom kg, int hq_l,
+                             const int32_t *row_pos, int b, h16_t *o_packed, hipStream_t s) {
     const int G = hq_l / kg.hkv_l;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)kg.d);
     dim3 grid(kg.hkv_l, b);
@@ -345,18 +348,18 @@ void launch_attn_decode_rows(const bf16_t *q, const bf16_t *kc, const bf16_t *vc
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
 template <int D, int NWV>
-__global__ __launch_bounds__(64 * NWV, 2) void attn_prefill_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc,
-                                                             const bf16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
+__global__ __launch_bounds__(64 * NWV, 2) void attn_prefill_kernel(const h16_t *__restrict__ q, const h16_t *__restrict__ kc,
+                                                             const h16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
                                                              const int32_t *__restrict__ cu_rows,
                                                              const int32_t *__restrict__ pos0,
-                                                             bf16_t *__restrict__ o_packed, float scale_log2e) {
+                                                             h16_t *__restrict__ o_packed, float scale_log2e) {
     constexpr int KT = D / 32, DT = D / 16, DB = D / 32;     // K d-tiles, V^T d-tiles, 32-wide output blocks
     constexpr int TILES = 2 * KT + DT;                       // 1 KB tiles per 32-position step: K then V^T
     constexpr int LPT = TILES / NWV;                         // loads per wave and step
     constexpr int ROWS = 32 * NWV;                           // query rows per block
     constexpr int S = 3;
     static_assert(TILES % NWV == 0, "tiles must divide over the waves");
-    __shared__ bf16x8 smem[S][TILES][64];
+    __shared__ h16x8 smem[S][TILES][64];
     const int seq = blockIdx.z, head = blockIdx.y;
     const int rb = gridDim.x - 1 - blockIdx.x;               // longest walks first
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -376,13 +379,13 @@ __global__ __launch_bounds__(64 * NWV, 2) void attn_prefill_kernel(const bf16_t 
     const int sub = (lane & 31) >> 4;                        // which tile of the pair
     const int fl = (lane & 15) + 16 * hl;                    // lane slot inside the tile for kh = 0 (+ 32 for kh = 1)
     const int qkt = (hq_l * D) >> 5;
-    bf16x8 qf[2 * KT];
+    h16x8 qf[2 * KT];
     {
-        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+        const h16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
         const int qr = row0 + min(ri, n_new - 1);
 #pragma unroll
         for (int kk = 0; kk < 2 * KT; ++kk)
-            qf[kk] = qbase < n_new ? *reinterpret_cast<const bf16x8 *>(
+            qf[kk] = qbase < n_new ? *reinterpret_cast<const h16x8 *>(
                                           q + frag_offset(qr, head * D + (kk >> 1) * 32 + 8 * (2 * (kk & 1) + hl), qkt))
                                     : zero;
     }
@@ -394,8 +397,8 @@ __global__ __launch_bounds__(64 * NWV, 2) void attn_prefill_kernel(const bf16_t 
     float m = NEG_INF, lsum = 0.f;
 
     const size_t slab = (size_t)seq * kg.seq_stride + (size_t)c * kg.smax * D;
-    const bf16x8 *ks = reinterpret_cast<const bf16x8 *>(kc + slab);
-    const bf16x8 *vs = reinterpret_cast<const bf16x8 *>(vc + slab);
+    const h16x8 *ks = reinterpret_cast<const h16x8 *>(kc + slab);
+    const h16x8 *vs = reinterpret_cast<const h16x8 *>(vc + slab);
     // tiles of step t: K tiles (2 t) KT .. (2 t + 2) KT - 1 and V^T tiles t DT .. (t + 1) DT - 1, both contiguous.
     // The loads are written in their scalar-base form as asm: besides saving a vector add per load, that keeps
     // them out of the compiler's memory model, which would otherwise drain vmcnt to 0 in front of every LDS
@@ -405,7 +408,7 @@ __global__ __launch_bounds__(64 * NWV, 2) void attn_prefill_kernel(const bf16_t 
 #pragma unroll
         for (int x = 0; x < LPT; ++x) {
             const int tile = wave + NWV * x;
-            const bf16x8 *src = tile < 2 * KT ? ks + (size_t)(2 * t * KT + tile) * 64 : vs + (size_t)(t * DT + tile - 2 * KT) * 64;
+            const h16x8 *src = tile < 2 * KT ? ks + (size_t)(2 * t * KT + tile) * 64 : vs + (size_t)(t * DT + tile - 2 * KT) * 64;
             const unsigned lds_addr = (unsigned)reinterpret_cast<uintptr_t>(HX_AS3(&smem[t % S][tile][0]));
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
@@ -425,13 +428,13 @@ __global__ __launch_bounds__(64 * NWV, 2) void attn_prefill_kernel(const bf16_t 
         asm volatile("s_barrier" ::: "memory");
         if (t + 2 < nt) issue(t + 2);         // into the buffer of step t - 1, which every wave has left
         if (t >= nt_w) continue;              // this wave's rows end before the tile (it still feeds the others)
-        const bf16x8(*st)[64] = smem[t % S];
+        const h16x8(*st)[64] = smem[t % S];
         floatx16 sc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) sc[r] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < 2 * KT; ++kk)
-            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st[sub * KT + (kk >> 1)][fl + 32 * (kk & 1)], qf[kk], sc, 0, 0, 0);
+            sc = hx_mfma32(st[sub * KT + (kk >> 1)][fl + 32 * (kk & 1)], qf[kk], sc);
         // causal mask (only tiles that reach a row's own position) and running max on the raw scores; the softmax
         // scale is folded into the exponent's multiply-add (scale > 0, so the max commutes with it)
         float mx = NEG_INF;
@@ -456,11 +459,11 @@ __global__ __launch_bounds__(64 * NWV, 2) void attn_prefill_kernel(const bf16_t 
             ps += sc[r];
         }
         lsum = lsum * alpha + ps;
-        union { uint32_t u[4]; bf16x8 v; } pb0, pb1;      // P for k-groups hl (quads 0, 2) and 2 + hl (quads 1, 3)
-        pb0.u[0] = pack_bf16x2(sc[0], sc[1]);   pb0.u[1] = pack_bf16x2(sc[2], sc[3]);
-        pb0.u[2] = pack_bf16x2(sc[8], sc[9]);   pb0.u[3] = pack_bf16x2(sc[10], sc[11]);
-        pb1.u[0] = pack_bf16x2(sc[4], sc[5]);   pb1.u[1] = pack_bf16x2(sc[6], sc[7]);
-        pb1.u[2] = pack_bf16x2(sc[12], sc[13]); pb1.u[3] = pack_bf16x2(sc[14], sc[15]);
+        union { uint32_t u[4]; h16x8 v; } pb0, pb1;      // P for k-groups hl (quads 0, 2) and 2 + hl (quads 1, 3)
+        pb0.u[0] = pack_h16x2(sc[0], sc[1]);   pb0.u[1] = pack_h16x2(sc[2], sc[3]);
+        pb0.u[2] = pack_h16x2(sc[8], sc[9]);   pb0.u[3] = pack_h16x2(sc[10], sc[11]);
+        pb1.u[0] = pack_h16x2(sc[4], sc[5]);   pb1.u[1] = pack_h16x2(sc[6], sc[7]);
+        pb1.u[2] = pack_h16x2(sc[12], sc[13]); pb1.u[3] = pack_h16x2(sc[14], sc[15]);
         // rescale the running output only when some row's maximum moved (rare after the first tiles)
         if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
@@ -470,8 +473,8 @@ __global__ __launch_bounds__(64 * NWV, 2) void attn_prefill_kernel(const bf16_t 
         }
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st[2 * KT + 2 * db + sub][fl], pb0.v, oacc[db], 0, 0, 0);
-            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st[2 * KT + 2 * db + sub][fl + 32], pb1.v, oacc[db], 0, 0, 0);
+            oacc[db] = hx_mfma32(st[2 * KT + 2 * db + sub][fl], pb0.v, oacc[db]);
+            oacc[db] = hx_mfma32(st[2 * KT + 2 * db + sub][fl + 32], pb1.v, oacc[db]);
         }
     }
     lsum += __shfl_xor(lsum, 32, 64);
@@ -482,15 +485,15 @@ __global__ __launch_bounds__(64 * NWV, 2) void attn_prefill_kernel(const bf16_t 
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 uint2 o;
-                o.x = pack_bf16x2(oacc[db][4 * qd] * inv, oacc[db][4 * qd + 1] * inv);
-                o.y = pack_bf16x2(oacc[db][4 * qd + 2] * inv, oacc[db][4 * qd + 3] * inv);
+                o.x = pack_h16x2(oacc[db][4 * qd] * inv, oacc[db][4 * qd + 1] * inv);
+                o.y = pack_h16x2(oacc[db][4 * qd + 2] * inv, oacc[db][4 * qd + 3] * inv);
                 *reinterpret_cast<uint2 *>(o_packed + frag_offset(row0 + ri, head * D + 32 * db + 8 * qd + 4 * hl, qkt)) = o;
             }
     }
 }
 
-void launch_attn_prefill(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, KvGeom kg, int hq_l,
-                         const int32_t *cu_rows, const int32_t *pos0, int batch, int max_new, bf16_t *o_packed,
+void launch_attn_prefill(const h16_t *q, const h16_t *kc, const h16_t *vc, KvGeom kg, int hq_l,
+                         const int32_t *cu_rows, const int32_t *pos0, int batch, int max_new, h16_t *o_packed,
                          hipStream_t s) {
     if (batch <= 0 || max_new <= 0) return;
     const int G = hq_l / kg.hkv_l;
@@ -512,3 +515,5 @@ void launch_attn_prefill(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, Kv
     }
 #undef HX_A
 }
+
+}  // namespace HX_NS

@@ -24,6 +24,9 @@
 #include "kernels.h"
 #include "kvlayout.h"
 
+namespace HX_NS {
+
+
 // rstd of a token row from the per-unit sums of squares of the residual stream
 __device__ inline void rstd_row(const DecodeEpi &e, int t, int lane, float *s_rstd) {
     float r = 1.0f;
@@ -56,7 +59,7 @@ __device__ inline void rstd_finish(const DecodeEpi &e, int t, int lane, const fl
     if (lane == 0) s_rstd[t] = 1.0f / sqrtf(ss / (float)e.norm_dim + e.eps);
 }
 
-__device__ inline void store_split4(const float x[4], bf16_t *hi, bf16_t *lo, size_t off) {
+__device__ inline void store_split4(const float x[4], h16_t *hi, h16_t *lo, size_t off) {
     uint2 o, ol;
     split_pack2(x[0], x[1], o.x, ol.x);
     split_pack2(x[2], x[3], o.y, ol.y);
@@ -64,7 +67,7 @@ __device__ inline void store_split4(const float x[4], bf16_t *hi, bf16_t *lo, si
     *reinterpret_cast<uint2 *>(lo + off) = ol;
 }
 // 4 consecutive features k..k+3 of one token into a compact decode operand (hi and lo planes)
-__device__ inline void store_act4(const float x[4], bf16_t *xa, int token, int k, int k_tiles) {
+__device__ inline void store_act4(const float x[4], h16_t *xa, int token, int k, int k_tiles) {
     const size_t off = dec_act_offset(token, k, k_tiles, 0);
     uint2 o, ol;
     split_pack2(x[0], x[1], o.x, ol.x);
@@ -129,13 +132,13 @@ __device__ inline void decode_epilogue(const floatx4 (&v)[UT], int unit, int b, 
             if (e.last_layer) {
                 // stage output: the partial without residual, and the residual it belongs to
                 uint2 po;
-                po.x = pack_bf16x2(v[0][0], v[0][1]);
-                po.y = pack_bf16x2(v[0][2], v[0][3]);
+                po.x = pack_h16x2(v[0][0], v[0][1]);
+                po.y = pack_h16x2(v[0][2], v[0][3]);
                 *reinterpret_cast<uint2 *>(e.out_partial + (size_t)token * N + n0) = po;
                 if (e.out_resid) {
                     uint2 ro;
-                    ro.x = pack_bf16x2(h4[0], h4[1]);
-                    ro.y = pack_bf16x2(h4[2], h4[3]);
+                    ro.x = pack_h16x2(h4[0], h4[1]);
+                    ro.y = pack_h16x2(h4[2], h4[3]);
                     *reinterpret_cast<uint2 *>(e.out_resid + (size_t)token * N + n0) = ro;
                 }
             } else {
@@ -192,14 +195,14 @@ __device__ inline void decode_epilogue(const floatx4 (&v)[UT], int unit, int b, 
             } else if (head < e.hq_l + e.kg.hkv_l) {
                 const size_t slab = (size_t)token * e.kg.seq_stride + (size_t)(head - e.hq_l) * e.kg.smax * d;
                 uint2 o;
-                o.x = pack_bf16x2(out[0], out[1]);
-                o.y = pack_bf16x2(out[2], out[3]);
+                o.x = pack_h16x2(out[0], out[1]);
+                o.y = pack_h16x2(out[2], out[3]);
                 *reinterpret_cast<uint2 *>(e.kc + slab + kv_k_offset(pos, e0, d)) = o;
             } else {
                 const size_t slab =
                     (size_t)token * e.kg.seq_stride + (size_t)(head - e.hq_l - e.kg.hkv_l) * e.kg.smax * d;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) e.vc[slab + kv_v_offset(pos, e0 + j, d)] = f32_to_bf16(out[j]);
+                for (int j = 0; j < 4; ++j) e.vc[slab + kv_v_offset(pos, e0 + j, d)] = f32_to_h16(out[j]);
             }
         }
     }
@@ -210,12 +213,12 @@ constexpr int kXldsMaxBytes = 64 * 1024;      // activation operand staged in LD
 // XLDS: the whole activation operand (T <= 2 rows) is staged once per block in LDS, so the main loop
 // issues nothing but weight loads; otherwise each lane fetches its 16-byte pieces per k-tile (L2 hits).
 template <int NB, int UT, int WAVES, int UNROLL, int MODE, bool XLDS, int XR>
-__global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *__restrict__ Wp,
-                                                                const bf16_t *__restrict__ Xa, int N, int k_tiles,
+__global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const h16_t *__restrict__ Wp,
+                                                                const h16_t *__restrict__ Xa, int N, int k_tiles,
                                                                 int T, DecodeEpi e) {
     __shared__ floatx4 red[WAVES][UT * NB][64];
     __shared__ float s_rstd[32];
-    extern __shared__ bf16x8 xs[];          // XLDS: copy of Xa, [token][k_tile][plane][lane group]
+    extern __shared__ h16x8 xs[];          // XLDS: copy of Xa, [token][k_tile][plane][lane group]
     const int unit = blockIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
 
@@ -225,21 +228,21 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
 #pragma unroll
         for (int b = 0; b < NB; ++b) acc[u][b] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    const bf16x8 *wp[UT];
+    const h16x8 *wp[UT];
 #pragma unroll
     for (int u = 0; u < UT; ++u)
-        wp[u] = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)(unit * UT + u) * 64 + lane;
+        wp[u] = reinterpret_cast<const h16x8 *>(Wp) + (size_t)(unit * UT + u) * 64 + lane;
     const size_t kstride = (size_t)(N >> 4) * 64;          // k-tile-major weights: one k-tile of all features
     // operand B of lane (token j, group g) for k-tile kt: hi at x[b][kt * 8], lo at x[b][kt * 8 + 4]
-    const bf16x8 *xg[NB];
+    const h16x8 *xg[NB];
     bool xv[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const int token = (lane & 15) + 16 * b;
         xv[b] = token < T;
-        xg[b] = (XLDS ? xs : reinterpret_cast<const bf16x8 *>(Xa)) + (size_t)(xv[b] ? token : 0) * k_tiles * 8 + (lane >> 4);
+        xg[b] = (XLDS ? xs : reinterpret_cast<const h16x8 *>(Xa)) + (size_t)(xv[b] ? token : 0) * k_tiles * 8 + (lane >> 4);
     }
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    const h16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     // Wave w owns k-tiles w, w + WAVES, ...; it holds a ring of UNROLL of them per feature tile in registers.  The
     // first ring round is requested before anything else, so the weights are already on their way while the block
     // stages the activation operand and derives the rows' rstd.
@@ -251,19 +254,19 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
     EpiPre pre;
     const bool finisher = wave < NB;          // wave b finishes token tile b
     if (finisher) epi_request_first<MODE>(pre, unit, wave, lane, N, T, e);
-    bf16x8 xr[XLDS ? XR : 1];
+    h16x8 xr[XLDS ? XR : 1];
     const int n16 = T * k_tiles * 8;
     if (XLDS) {
 #pragma unroll
         for (int j = 0; j < XR; ++j)
-            xr[j] = reinterpret_cast<const bf16x8 *>(Xa)[min((int)threadIdx.x + j * WAVES * 64, n16 - 1)];
+            xr[j] = reinterpret_cast<const h16x8 *>(Xa)[min((int)threadIdx.x + j * WAVES * 64, n16 - 1)];
     }
     float sv[RSTD_REGS];
     const bool rstd_wave = MODE != DEC_RESID && wave < T && e.ssq_in != nullptr;       // wave t derives rstd of row t
     if (rstd_wave) rstd_request(e, wave, lane, sv);
     // ring slot = the weight tiles of one k-tile and, when the operand is not staged in LDS, its hi / lo pieces too
     // (requested together, so that no wait for an operand piece ever drains the weight requests behind it)
-    bf16x8 a[UNROLL][UT], xq[XLDS ? 1 : UNROLL][NB][2];
+    h16x8 a[UNROLL][UT], xq[XLDS ? 1 : UNROLL][NB][2];
     auto request = [&](int i, int kt) {
         if (!XLDS) {
 #pragma unroll
@@ -295,7 +298,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
     auto contract = [&](int i, int kt) {
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            bf16x8 x, y;
+            h16x8 x, y;
             if (XLDS) {
                 x = xv[b] ? xg[b][kt * 8] : zero;
                 y = xv[b] ? xg[b][kt * 8 + 4] : zero;
@@ -305,8 +308,8 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const bf16_t *_
             }
 #pragma unroll
             for (int u = 0; u < UT; ++u) {
-                acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], y, acc[u][b], 0, 0, 0);
-                acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][u], x, acc[u][b], 0, 0, 0);
+                acc[u][b] = hx_mfma16(a[i][u], y, acc[u][b]);
+                acc[u][b] = hx_mfma16(a[i][u], x, acc[u][b]);
             }
         }
     };
@@ -363,7 +366,7 @@ constexpr int SK_CH = 8;                       // k-tiles per chunk: 1 KB of one
 constexpr int SK_TOK_STRIDE = 1024 + 16;       // LDS bytes per token and chunk; the pad spreads tokens over the banks
 
 template <int NB>
-__global__ __launch_bounds__(512) void decode_splitk_kernel(const bf16_t *__restrict__ Wp, const bf16_t *__restrict__ Xa,
+__global__ __launch_bounds__(512) void decode_splitk_kernel(const h16_t *__restrict__ Wp, const h16_t *__restrict__ Xa,
                                                            int n_tiles, int k_tiles, int T,
                                                            float *__restrict__ part, const float *__restrict__ ssq_in,
                                                            int ssq_units, int norm_dim, float eps,
@@ -382,28 +385,28 @@ __global__ __launch_bounds__(512) void decode_splitk_kernel(const bf16_t *__rest
     const int N = n_tiles * 16;
 
     // chunk c of the operand rows this wave copies: lane l carries bytes 16 l .. 16 l + 15 of the row's 1 KB
-    const bf16x8 *xsrc[LPW];
+    const h16x8 *xsrc[LPW];
 #pragma unroll
     for (int i = 0; i < LPW; ++i)
-        xsrc[i] = reinterpret_cast<const bf16x8 *>(Xa) + (size_t)min(wave + 8 * i, T - 1) * k_tiles * 8 + lane;
-    auto load_x = [&](int c, bf16x8(&x)[LPW]) {
+        xsrc[i] = reinterpret_cast<const h16x8 *>(Xa) + (size_t)min(wave + 8 * i, T - 1) * k_tiles * 8 + lane;
+    auto load_x = [&](int c, h16x8(&x)[LPW]) {
         const int kc = kt0 + c * SK_CH;
         const bool ok = c < n_chunks && kc + (lane >> 3) < kt1;         // 8 lanes per k-tile line
 #pragma unroll
         for (int i = 0; i < LPW; ++i)
             if (ok) x[i] = xsrc[i][(size_t)kc * 8];
     };
-    auto store_x = [&](int c, const bf16x8(&x)[LPW]) {
+    auto store_x = [&](int c, const h16x8(&x)[LPW]) {
         unsigned char *buf = sk_lds + (c & 1) * BUF;
 #pragma unroll
         for (int i = 0; i < LPW; ++i)
-            *reinterpret_cast<bf16x8 *>(buf + (wave + 8 * i) * SK_TOK_STRIDE + lane * 16) = x[i];
+            *reinterpret_cast<h16x8 *>(buf + (wave + 8 * i) * SK_TOK_STRIDE + lane * 16) = x[i];
     };
     // this wave's weight tile for the k-tiles of chunk c
-    const bf16x8 *wsrc = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)min(tile, n_tiles - 1) * 64 + lane;
+    const h16x8 *wsrc = reinterpret_cast<const h16x8 *>(Wp) + (size_t)min(tile, n_tiles - 1) * 64 + lane;
     const size_t kstride = (size_t)n_tiles * 64;
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    auto load_w = [&](int c, bf16x8(&w)[SK_CH]) {
+    const h16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    auto load_w = [&](int c, h16x8(&w)[SK_CH]) {
         const int kc = kt0 + c * SK_CH;
 #pragma unroll
         for (int i = 0; i < SK_CH; ++i)
@@ -424,7 +427,7 @@ __global__ __launch_bounds__(512) void decode_splitk_kernel(const bf16_t *__rest
     floatx4 acc[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
-    bf16x8 xr[LPW], wc[SK_CH], wn[SK_CH];
+    h16x8 xr[LPW], wc[SK_CH], wn[SK_CH];
 #pragma unroll
     for (int i = 0; i < LPW; ++i) xr[i] = zero;
     load_x(0, xr);
@@ -447,10 +450,10 @@ __global__ __launch_bounds__(512) void decode_splitk_kernel(const bf16_t *__rest
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
                     const unsigned char *row = buf + (j + 16 * b) * SK_TOK_STRIDE + i * 128 + g * 16;
-                    const bf16x8 x = *reinterpret_cast<const bf16x8 *>(row);
-                    const bf16x8 y = *reinterpret_cast<const bf16x8 *>(row + 64);
-                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wc[i], y, acc[b], 0, 0, 0);
-                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wc[i], x, acc[b], 0, 0, 0);
+                    const h16x8 x = *reinterpret_cast<const h16x8 *>(row);
+                    const h16x8 y = *reinterpret_cast<const h16x8 *>(row + 64);
+                    acc[b] = hx_mfma16(wc[i], y, acc[b]);
+                    acc[b] = hx_mfma16(wc[i], x, acc[b]);
                 }
             }
         }
@@ -518,12 +521,12 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(const float *__restr
 namespace {
 
 template <int NB, int UT, int UNR, int MODE, bool XLDS, int XR>
-void launch_one(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, hipStream_t s) {
+void launch_one(const h16_t *Wp, const h16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, hipStream_t s) {
     constexpr int WAVES = 8;
     auto kern = decode_proj_kernel<NB, UT, WAVES, UNR, MODE, XLDS, XR>;
     size_t dyn = 0;
     if (XLDS) {
-        dyn = (size_t)T * k_tiles * 8 * sizeof(bf16x8);
+        dyn = (size_t)T * k_tiles * 8 * sizeof(h16x8);
         static bool raised = false;       // static + dynamic LDS may exceed the default 64 KB per block
         if (!raised) {
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -535,8 +538,8 @@ void launch_one(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, c
 }
 
 template <int UT, int MODE>
-void launch_mode(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, hipStream_t s) {
-    const size_t xbytes = (size_t)T * k_tiles * 8 * sizeof(bf16x8);
+void launch_mode(const h16_t *Wp, const h16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, hipStream_t s) {
+    const size_t xbytes = (size_t)T * k_tiles * 8 * sizeof(h16x8);
     // staged operand: XR 16-byte pieces per thread (512 threads), 4 up to 32 KB, 8 up to 64 KB
     // With one or two rows each wave of the residual projections (W_O, W2) and of W1/W3 fetches its operand pieces
     // through its request ring instead of the block staging the operand in LDS behind a barrier (measured: W_O
@@ -555,7 +558,7 @@ void launch_mode(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, 
 
 namespace {
 template <int MODE, int UT>
-void launch_splitk(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, float *scratch,
+void launch_splitk(const h16_t *Wp, const h16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, float *scratch,
                    size_t scratch_floats, hipStream_t s, hipEvent_t mid) {
     const int n_tiles = N / 16, groups = (n_tiles + 7) / 8;
     // Two blocks fit a CU (registers), 512 on the chip.  The number of splits (at most 8: the finishing kernel walks
@@ -594,14 +597,14 @@ void launch_splitk(const bf16_t *Wp, const bf16_t *Xa, int N, int k_tiles, int T
 }
 }  // namespace
 
-void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T, const DecodeEpi &e, float *scratch,
+void launch_decode_proj(const h16_t *Wp, const h16_t *Xa, int N, int K, int T, const DecodeEpi &e, float *scratch,
                         size_t scratch_floats, hipStream_t s, hipEvent_t mid) {
     const int k_tiles = K / 32;
     // one or two rows: one kernel, complete dot products per block; more: shared operand, split contraction
     // A small matrix (launch-bound) with a handful of rows is better off without the second kernel: each block then
     // fetches the rows' operand pieces itself (an L2 read of T x K x 4 bytes per block, which is what limits this to
     // few rows, fewer when the contraction is long), and needs enough k-tiles per wave to fill its request ring.
-    const bool small = (size_t)N * K * sizeof(bf16_t) <= ((size_t)72 << 20) && k_tiles >= 64 && T <= (K <= 4096 ? 8 : 4);
+    const bool small = (size_t)N * K * sizeof(h16_t) <= ((size_t)72 << 20) && k_tiles >= 64 && T <= (K <= 4096 ? 8 : 4);
     if (T > 2 && !small && scratch != nullptr && scratch_floats >= (size_t)T * N + 32 && k_tiles >= SK_CH) {
         switch (e.mode) {
             case DEC_RAW: launch_splitk<DEC_RAW, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s, mid); break;
@@ -631,10 +634,10 @@ void launch_decode_proj(const bf16_t *Wp, const bf16_t *Xa, int N, int K, int T,
 // sequence's committed length) and, when asked, advances the lengths.
 // grid = H / 128 blocks of 512 threads; thread = (token, 4-column group).
 // -------------------------------------------------------------------------------------------------
-template <bool IN_BF16>
+template <bool IN_H16>
 __global__ __launch_bounds__(512) void decode_prologue_kernel(const void *__restrict__ in, const void *__restrict__ in2,
                                                              float *__restrict__ h_out,
-                                                             const float *__restrict__ g, bf16_t *__restrict__ hg,
+                                                             const float *__restrict__ g, h16_t *__restrict__ hg,
                                                              float *__restrict__ ssq_out,
                                                              int T, int H, int32_t *lens, int32_t *row_pos,
                                                              int advance) {
@@ -650,14 +653,16 @@ __global__ __launch_bounds__(512) void decode_prologue_kernel(const void *__rest
         float ss = 0.f;
         if (col < H) {
             float x[4];
-            if (IN_BF16) {
-                uint2 raw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(in) + (size_t)t * H + col);
-                x[0] = bf16_to_f32((bf16_t)(raw.x & 0xffff)); x[1] = bf16_to_f32((bf16_t)(raw.x >> 16));
-                x[2] = bf16_to_f32((bf16_t)(raw.y & 0xffff)); x[3] = bf16_to_f32((bf16_t)(raw.y >> 16));
+            if (IN_H16) {
+                uint2 raw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const h16_t *>(in) + (size_t)t * H + col);
+                h16x2_to_f32(raw.x, x[0], x[1]);
+                h16x2_to_f32(raw.y, x[2], x[3]);
                 if (in2) {      // second addend (e.g. a stage's partial on top of its residual stream)
-                    raw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(in2) + (size_t)t * H + col);
-                    x[0] += bf16_to_f32((bf16_t)(raw.x & 0xffff)); x[1] += bf16_to_f32((bf16_t)(raw.x >> 16));
-                    x[2] += bf16_to_f32((bf16_t)(raw.y & 0xffff)); x[3] += bf16_to_f32((bf16_t)(raw.y >> 16));
+                    raw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const h16_t *>(in2) + (size_t)t * H + col);
+                    float y0, y1, y2, y3;
+                    h16x2_to_f32(raw.x, y0, y1);
+                    h16x2_to_f32(raw.y, y2, y3);
+                    x[0] += y0; x[1] += y1; x[2] += y2; x[3] += y3;
                 }
             } else {
                 const floatx4 a = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const float *>(in) + (size_t)t * H + col);
@@ -680,13 +685,15 @@ __global__ __launch_bounds__(512) void decode_prologue_kernel(const void *__rest
     }
 }
 
-void launch_decode_prologue(const void *in, const void *in2, int in_is_bf16, float *h_out, const float *g, bf16_t *hg,
+void launch_decode_prologue(const void *in, const void *in2, int in_is_h16, float *h_out, const float *g, h16_t *hg,
                             float *ssq_out, int T, int H, int32_t *lens, int32_t *row_pos, int advance, hipStream_t s) {
     const int blocks = (H + 127) / 128;
-    if (in_is_bf16)
+    if (in_is_h16)
         hipLaunchKernelGGL(decode_prologue_kernel<true>, dim3(blocks), dim3(512), 0, s, in, in2, h_out, g, hg, ssq_out, T, H,
                            lens, row_pos, advance);
     else
         hipLaunchKernelGGL(decode_prologue_kernel<false>, dim3(blocks), dim3(512), 0, s, in, in2, h_out, g, hg, ssq_out, T, H,
                            lens, row_pos, advance);
 }
+
+}  // namespace HX_NS

@@ -37,6 +37,9 @@
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
+namespace HX_NS {
+
+
 // ---- epilogue, in registers.  32 x 32 result: lane l holds token column l % 32 and, per register quad q,
 // features 8 q + 4 (l / 32) .. + 3 of the 32-feature block, i.e. of the 16-row tile q / 2 its rows
 // (q % 2) * 8 + 4 (l / 32) .. + 3.  Rotary pairs (tile rows r, r + 8) and gate / up pairs (tiles 2m, 2m + 1)
@@ -95,13 +98,13 @@ __device__ __forceinline__ void gemm_epilogue(AccF acc_of, int bm, int bt, int w
                     const floatx4 v = {c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]};
                     if (e.last_layer) {
                         uint2 po;
-                        po.x = pack_bf16x2(v[0], v[1]);
-                        po.y = pack_bf16x2(v[2], v[3]);
+                        po.x = pack_h16x2(v[0], v[1]);
+                        po.y = pack_h16x2(v[2], v[3]);
                         *reinterpret_cast<uint2 *>(e.out_partial + (size_t)token[j] * N + n) = po;
                         if (e.out_resid) {
                             uint2 ro;
-                            ro.x = pack_bf16x2(h4[0], h4[1]);
-                            ro.y = pack_bf16x2(h4[2], h4[3]);
+                            ro.x = pack_h16x2(h4[0], h4[1]);
+                            ro.y = pack_h16x2(h4[2], h4[3]);
                             *reinterpret_cast<uint2 *>(e.out_resid + (size_t)token[j] * N + n) = ro;
                         }
                     } else {
@@ -109,8 +112,8 @@ __device__ __forceinline__ void gemm_epilogue(AccF acc_of, int bm, int bt, int w
                         *reinterpret_cast<floatx4 *>(e.h + h_tile_offset(token[j], n, N)) = hn;
                         const floatx4 g4 = gv[q];
                         uint2 o;
-                        o.x = pack_bf16x2(hn[0] * g4[0], hn[1] * g4[1]);
-                        o.y = pack_bf16x2(hn[2] * g4[2], hn[3] * g4[3]);
+                        o.x = pack_h16x2(hn[0] * g4[0], hn[1] * g4[1]);
+                        o.y = pack_h16x2(hn[2] * g4[2], hn[3] * g4[3]);
                         *reinterpret_cast<uint2 *>(e.hg + frag_offset(token[j], n, N >> 5)) = o;
                         ssq[j] += hn[0] * hn[0] + hn[1] * hn[1] + hn[2] * hn[2] + hn[3] * hn[3];
                     }
@@ -182,8 +185,8 @@ __device__ __forceinline__ void gemm_epilogue(AccF acc_of, int bm, int bt, int w
                         u[x] = aa / (1.0f + __expf(-aa)) * (c[4 * (q + 2) + x] * r);
                     }
                     uint2 o;
-                    o.x = pack_bf16x2(u[0], u[1]);
-                    o.y = pack_bf16x2(u[2], u[3]);
+                    o.x = pack_h16x2(u[0], u[1]);
+                    o.y = pack_h16x2(u[2], u[3]);
                     *reinterpret_cast<uint2 *>(e.u + frag_offset(token, f, e.F_l >> 5)) = o;
                 }
             } else {   // DEC_QKV: each 16-row tile holds 8 rotary pairs (rows r, r + 8)
@@ -208,8 +211,8 @@ __device__ __forceinline__ void gemm_epilogue(AccF acc_of, int bm, int bt, int w
                         }
                     }
                     uint2 plo, phi;
-                    plo.x = pack_bf16x2(lo[0], lo[1]); plo.y = pack_bf16x2(lo[2], lo[3]);
-                    phi.x = pack_bf16x2(hi[0], hi[1]); phi.y = pack_bf16x2(hi[2], hi[3]);
+                    plo.x = pack_h16x2(lo[0], lo[1]); plo.y = pack_h16x2(lo[2], lo[3]);
+                    phi.x = pack_h16x2(hi[0], hi[1]); phi.y = pack_h16x2(hi[2], hi[3]);
                     if (head < e.hq_l) {
                         const int qkt = (e.hq_l * d) >> 5;
                         *reinterpret_cast<uint2 *>(e.q + frag_offset(token, head * d + i0, qkt)) = plo;
@@ -223,8 +226,8 @@ __device__ __forceinline__ void gemm_epilogue(AccF acc_of, int bm, int bt, int w
                             (size_t)seq * e.kg.seq_stride + (size_t)(head - e.hq_l - e.kg.hkv_l) * e.kg.smax * d;
 #pragma unroll
                         for (int x = 0; x < 4; ++x) {
-                            e.vc[slab + kv_v_offset(pos, i0 + x, d)] = f32_to_bf16(lo[x]);
-                            e.vc[slab + kv_v_offset(pos, i0 + half + x, d)] = f32_to_bf16(hi[x]);
+                            e.vc[slab + kv_v_offset(pos, i0 + x, d)] = f32_to_h16(lo[x]);
+                            e.vc[slab + kv_v_offset(pos, i0 + half + x, d)] = f32_to_h16(hi[x]);
                         }
                     }
                 }
@@ -266,8 +269,8 @@ __device__ __forceinline__ void gemm_tile_of_id(int id, int n_blocks, int t_bloc
 // re-reads the block's first k-step (cache hits, no new bytes from HBM); 3: the operand fragments are read from LDS
 // for the first k-step only.
 template <int FM, int FT, int WM, int WT, int S, int MODE, bool PP = false, int ABL = 0>
-__global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *__restrict__ Wp,
-                                                                 const bf16_t *__restrict__ Xp, int N, int k_tiles,
+__global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const h16_t *__restrict__ Wp,
+                                                                 const h16_t *__restrict__ Xp, int N, int k_tiles,
                                                                  int n_tiles, int t_tiles, int T, int n_blocks,
                                                                  int t_blocks, GemmEpi e, float *__restrict__ part,
                                                                  int pm_h, int pt_w) {
@@ -275,10 +278,10 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
     constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT;   // 16-row operand tiles per block and k-step
     constexpr int LA = TA / NW, LB = TB / NW;         // direct-to-LDS loads per wave and stage, per operand
     constexpr int LPT = LA + LB;
-    constexpr int STAGE = (TA + TB) * 64;            // bf16x8 elements per stage
+    constexpr int STAGE = (TA + TB) * 64;            // h16x8 elements per stage
     constexpr int NTOK = TB * 16;                    // token columns of the block tile
     static_assert(TA % NW == 0 && TB % NW == 0, "operand tiles must divide evenly over the waves");
-    extern __shared__ bf16x8 smem[];                 // [S][TA + TB][64], then NTOK floats
+    extern __shared__ h16x8 smem[];                 // [S][TA + TB][64], then NTOK floats
     float *rstd_s = reinterpret_cast<float *>(smem + (size_t)S * STAGE);
     // XCD-aware remap of the linear block id
     const int total = n_blocks * t_blocks;
@@ -306,12 +309,12 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const bf16x8 *A = reinterpret_cast<const bf16x8 *>(Wp);
-    const bf16x8 *B = reinterpret_cast<const bf16x8 *>(Xp);
+    const h16x8 *A = reinterpret_cast<const h16x8 *>(Wp);
+    const h16x8 *B = reinterpret_cast<const h16x8 *>(Xp);
     // this wave copies tiles wave, wave + NW, ... of both operands; out-of-range tiles are clamped to the last
     // valid tile (their products are never stored) so that every wave issues LPT loads per stage.  Tile bases
     // are uniform (scalar registers); the lane adds its 16-byte slot as a 32-bit offset.
-    const bf16x8 *asrc[LA], *bsrc[LB];
+    const h16x8 *asrc[LA], *bsrc[LB];
 #pragma unroll
     for (int i = 0; i < LA; ++i) asrc[i] = A + (size_t)min(bm * TA + wave + NW * i, n_tiles - 1) * 64 + (size_t)k0 * n_tiles * 64;
 #pragma unroll
@@ -334,9 +337,9 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
     const unsigned lane_bytes = (unsigned)lane * 16u;
     auto issue_one = [&](int kt, int x) {
         const int kc = ABL == 2 ? 0 : min(kt, k_len - 1);
-        bf16x8 *st = smem + (size_t)(kt % S) * STAGE;
-        const bf16x8 *src = x < LA ? asrc[x] + kc * astep : bsrc[x - LA] + (size_t)kc * 64;
-        bf16x8 *dst = x < LA ? st + (wave + NW * x) * 64 : st + (TA + wave + NW * (x - LA)) * 64;
+        h16x8 *st = smem + (size_t)(kt % S) * STAGE;
+        const h16x8 *src = x < LA ? asrc[x] + kc * astep : bsrc[x - LA] + (size_t)kc * 64;
+        h16x8 *dst = x < LA ? st + (wave + NW * x) * 64 : st + (TA + wave + NW * (x - LA)) * 64;
         const unsigned lds_addr = (unsigned)reinterpret_cast<uintptr_t>(HX_AS3(dst));
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      :
@@ -383,12 +386,12 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
         for (int i = 0; i < 2 * FM; ++i)
 #pragma unroll
             for (int j = 0; j < 2 * FT; ++j) a16[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-        bf16x8 pa[2 * FM], pb[2 * FT];
+        h16x8 pa[2 * FM], pb[2 * FT];
         for (int kt = 0; kt < k_len; ++kt) {
             // memory phase: the whole k-step's operands, then this wave's loads of stage kt + S - 1 into the buffer
             // of stage kt - 1, which both halves of the block have finished reading (barriers below)
-            const bf16x8 *sa = smem + (size_t)(kt % S) * STAGE + (wm * FM * 2) * 64 + lane;
-            const bf16x8 *sb = smem + (size_t)(kt % S) * STAGE + (TA + wt * FT * 2) * 64 + lane;
+            const h16x8 *sa = smem + (size_t)(kt % S) * STAGE + (wm * FM * 2) * 64 + lane;
+            const h16x8 *sb = smem + (size_t)(kt % S) * STAGE + (TA + wt * FT * 2) * 64 + lane;
             if (ABL != 3 || kt == 0) {
 #pragma unroll
                 for (int x = 0; x < 2 * FT; ++x) pb[x] = sb[x * 64];
@@ -409,7 +412,7 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
             for (int i = 0; i < 2 * FM; ++i)
 #pragma unroll
                 for (int j = 0; j < 2 * FT; ++j)
-                    a16[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa[i], pb[j], a16[i][j], 0, 0, 0);
+                    a16[i][j] = hx_mfma16(pa[i], pb[j], a16[i][j]);
             __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
             asm volatile("s_barrier" ::: "memory");
@@ -478,15 +481,15 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
             rstd_s[t] = 1.0f / sqrtf(ss / (float)e.norm_dim + e.eps);
         }
     }
-    bf16x8 fa0[FM], fb0[FT], fa1[FM], fb1[FT];
+    h16x8 fa0[FM], fb0[FT], fa1[FM], fb1[FT];
     // x-th operand fetch of a half step: the FT token operands first, then the FM feature operands
-    auto fetch_one = [&](bf16x8(&fa)[FM], bf16x8(&fb)[FT], int kt, int kh, int x) {
-        const bf16x8 *sa = smem + (size_t)(kt % S) * STAGE + (wm * FM * 2) * 64 + frag + kh * 32;
-        const bf16x8 *sb = smem + (size_t)(kt % S) * STAGE + (TA + wt * FT * 2) * 64 + frag + kh * 32;
+    auto fetch_one = [&](h16x8(&fa)[FM], h16x8(&fb)[FT], int kt, int kh, int x) {
+        const h16x8 *sa = smem + (size_t)(kt % S) * STAGE + (wm * FM * 2) * 64 + frag + kh * 32;
+        const h16x8 *sb = smem + (size_t)(kt % S) * STAGE + (TA + wt * FT * 2) * 64 + frag + kh * 32;
         if (x < FT) fb[x] = sb[x * 128];
         else fa[x - FT] = sa[(x - FT) * 128];
     };
-    auto fetch = [&](bf16x8(&fa)[FM], bf16x8(&fb)[FT], int kt, int kh) {
+    auto fetch = [&](h16x8(&fa)[FM], h16x8(&fb)[FT], int kt, int kh) {
 #pragma unroll
         for (int x = 0; x < FM + FT; ++x) fetch_one(fa, fb, kt, kh, x);
     };
@@ -506,7 +509,7 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
         // slots are fenced so that the order below is the order in the instruction stream
 #pragma unroll
         for (int m = 0; m < FM * FT; ++m) {
-            acc[m / FT][m % FT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[m / FT], fb0[m % FT], acc[m / FT][m % FT], 0, 0, 0);
+            acc[m / FT][m % FT] = hx_mfma32(fa0[m / FT], fb0[m % FT], acc[m / FT][m % FT]);
             if (m < FM + FT) fetch_one(fa1, fb1, kt, 1, m);
             if (m >= LOAD0 && (m - LOAD0) % GAP == OFF && (m - LOAD0) / GAP < H2) issue_one(kt + S - 2, H1 + (m - LOAD0) / GAP);
             __builtin_amdgcn_sched_barrier(0);
@@ -516,7 +519,7 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const bf16_t *_
         HX_LDS_BARRIER();
 #pragma unroll
         for (int m = 0; m < FM * FT; ++m) {
-            acc[m / FT][m % FT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[m / FT], fb1[m % FT], acc[m / FT][m % FT], 0, 0, 0);
+            acc[m / FT][m % FT] = hx_mfma32(fa1[m / FT], fb1[m % FT], acc[m / FT][m % FT]);
             if (m < FM + FT) fetch_one(fa0, fb0, kt + 1, 0, m);
             if (m >= LOAD0 && (m - LOAD0) % GAP == OFF && (m - LOAD0) / GAP < H1) issue_one(kt + S - 1, (m - LOAD0) / GAP);
             __builtin_amdgcn_sched_barrier(0);
@@ -611,11 +614,11 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_finish_kernel(const float *
 // tiles go to `part` in the layout gemm_finish_kernel<1, 1, 4, 1> reads (four 32-token blocks per feature block).
 // -------------------------------------------------------------------------------------------------
 constexpr int SKINNY_RING = 6;          // measured: 4, 6 and 8 run alike (the CU's load issue rate paces the kernel)
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t *__restrict__ Wp, const bf16_t *__restrict__ Xp,
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t *__restrict__ Wp, const h16_t *__restrict__ Xp,
                                                          int k_tiles, int n_tiles, int t_tiles, int total,
                                                          float *__restrict__ part) {
     constexpr int RING = SKINNY_RING;
-    __shared__ bf16x8 xs[2][8 * 64];                 // two k-steps of the 8 token tiles
+    __shared__ h16x8 xs[2][8 * 64];                 // two k-steps of the 8 token tiles
     const int id = blockIdx.x;                       // 128-feature block
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int k0 = (int)((long)blockIdx.y * k_tiles / gridDim.y);
@@ -623,13 +626,13 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t *__restri
 
     // weights: lane l of k-half kh takes slot (l % 16) + 16 (l / 32) + 32 kh of tile t16 + (l % 32) / 16
     const int t16 = min(id * 8 + wave * 2 + ((lane & 31) >> 4), n_tiles - 1);
-    const bf16x8 *wsrc = reinterpret_cast<const bf16x8 *>(Wp) + ((size_t)k0 * n_tiles + t16) * 64 + (lane & 15) + 16 * (lane >> 5);
+    const h16x8 *wsrc = reinterpret_cast<const h16x8 *>(Wp) + ((size_t)k0 * n_tiles + t16) * 64 + (lane & 15) + 16 * (lane >> 5);
     const size_t wstep = (size_t)n_tiles * 64;
     // activations: wave w copies token tiles 2 w and 2 w + 1 of each k-step (clamped to the last valid tile)
-    const bf16x8 *xsrc[2];
+    const h16x8 *xsrc[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
-        xsrc[i] = reinterpret_cast<const bf16x8 *>(Xp) + ((size_t)min(wave * 2 + i, t_tiles - 1) * k_tiles + k0) * 64 + lane;
+        xsrc[i] = reinterpret_cast<const h16x8 *>(Xp) + ((size_t)min(wave * 2 + i, t_tiles - 1) * k_tiles + k0) * 64 + lane;
     const int frag = ((lane & 31) >> 4) * 64 + (lane & 15) + 16 * (lane >> 5);
 
     floatx16 acc[4];
@@ -642,12 +645,12 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t *__restri
     // unconditional (k-steps past the end re-read the last one, an L2 hit, unused), so the compiler counts requests in
     // flight exactly; because loads return in order, a piece of the activations must not be requested later than the
     // weights it is used with, or the wait for it would drain the weight requests behind which it sits.
-    bf16x8 a[RING][2], xq[RING][2];
+    h16x8 a[RING][2], xq[RING][2];
     auto request = [&](int slot, int kt) {
         const int kc = min(kt, k_len - 1);
         xq[slot][0] = xsrc[0][(size_t)kc * 64];
         xq[slot][1] = xsrc[1][(size_t)kc * 64];
-        const bf16x8 *src = wsrc + (size_t)kc * wstep;
+        const h16x8 *src = wsrc + (size_t)kc * wstep;
         a[slot][0] = __builtin_nontemporal_load(src);
         a[slot][1] = __builtin_nontemporal_load(src + 32);
     };
@@ -656,12 +659,12 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t *__restri
         xs[kt & 1][(wave * 2 + 1) * 64 + lane] = xq[slot][1];
     };
     auto step = [&](int slot, int kt) {
-        const bf16x8 *sb = xs[kt & 1] + frag;
+        const h16x8 *sb = xs[kt & 1] + frag;
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[slot][kh], sb[j * 128 + kh * 32], acc[j], 0, 0, 0);
+                acc[j] = hx_mfma32(a[slot][kh], sb[j * 128 + kh * 32], acc[j]);
     };
     // the barrier of a k-step waits for the LDS stores only: __syncthreads() would also drain the requests in flight
     auto lds_barrier = [&]() {
@@ -703,7 +706,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t *__restri
 }
 
 template <int FM, int FT, int WM, int WT, int S, int MODE, bool PP = false, int ABL = 0>
-static void launch_cfg(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles, int n_tiles, int t_tiles, int T,
+static void launch_cfg(const h16_t *Wp, const h16_t *Xp, int N, int k_tiles, int n_tiles, int t_tiles, int T,
                        const GemmEpi &e, float *part, size_t part_floats, hipStream_t s) {
     constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT;
     const int n_blocks = (n_tiles + TA - 1) / TA, t_blocks = (t_tiles + TB - 1) / TB;
@@ -711,7 +714,7 @@ static void launch_cfg(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles, i
     const int grid = (total + 7) / 8 * 8;
     auto kern = gemm_mfma_kernel<FM, FT, WM, WT, S, MODE, PP, ABL>;
     const int pm_h = 4, pt_w = 8;         // patch of tiles one XCD works on at a time: 4 feature blocks x 8 token blocks
-    const size_t dyn = (size_t)S * (TA + TB) * 64 * sizeof(bf16x8) + (size_t)TB * 16 * sizeof(float);
+    const size_t dyn = (size_t)S * (TA + TB) * 64 * sizeof(h16x8) + (size_t)TB * 16 * sizeof(float);
     static bool raised = false;           // more than the default 64 KB of LDS per block
     if (!raised) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -745,7 +748,7 @@ bool set_gemm_tile(int code) {
 
 // one 128-token tile, at least 32 k-tiles: skinny kernel + finishing pass; returns false when it does not apply
 template <int MODE>
-static bool launch_skinny(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles, int n_tiles, int t_tiles, int T,
+static bool launch_skinny(const h16_t *Wp, const h16_t *Xp, int N, int k_tiles, int n_tiles, int t_tiles, int T,
                           const GemmEpi &e, float *part, size_t part_floats, hipStream_t s) {
     if (part == nullptr || t_tiles > 8 || k_tiles < 32) return false;
     const int n_blocks = (n_tiles + 7) / 8;
@@ -762,7 +765,7 @@ static bool launch_skinny(const bf16_t *Wp, const bf16_t *Xp, int N, int k_tiles
 }
 
 template <int MODE>
-static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, float *part,
+static void launch_mode(const h16_t *Wp, const h16_t *Xp, int N, int K, int T, const GemmEpi &e, float *part,
                         size_t part_floats, hipStream_t s) {
     const int k_tiles = K / 32, n_tiles = N / 16, t_tiles = (T + 15) / 16;
     const int force = g_force_tile.load(std::memory_order_relaxed);
@@ -808,7 +811,7 @@ static void launch_mode(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T,
 #undef HX_G
 }
 
-void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, const GemmEpi &e, float *part,
+void launch_gemm_mfma(const h16_t *Wp, const h16_t *Xp, int N, int K, int T, const GemmEpi &e, float *part,
                       size_t part_floats, hipStream_t s) {
     switch (e.mode) {
         case DEC_RAW: launch_mode<DEC_RAW>(Wp, Xp, N, K, T, e, part, part_floats, s); break;
@@ -825,9 +828,9 @@ void launch_gemm_mfma(const bf16_t *Wp, const bf16_t *Xp, int N, int K, int T, c
 // 32 * half, four consecutive features per lane and quad): every store of the residual stream is one contiguous
 // 1 KB, every store of the operand two runs of 256 B, and the 64-byte row pieces it reads are fetched once.
 // -------------------------------------------------------------------------------------------------
-template <bool IN_BF16>
+template <bool IN_H16>
 __global__ __launch_bounds__(256) void prefill_prologue_kernel(const void *__restrict__ in, float *__restrict__ h_out,
-                                                              const float *__restrict__ g, bf16_t *__restrict__ hg,
+                                                              const float *__restrict__ g, h16_t *__restrict__ hg,
                                                               float *__restrict__ ssq_out, int T, int H) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int token = blockIdx.x * 32 + (lane & 31), hl = lane >> 5;
@@ -842,10 +845,10 @@ __global__ __launch_bounds__(256) void prefill_prologue_kernel(const void *__res
             const int n = col0 + fb * 32 + 8 * q + 4 * hl;
             float x[4] = {0.f, 0.f, 0.f, 0.f};
             if (tv) {
-                if (IN_BF16) {
-                    const uint2 raw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(in) + (size_t)token * H + n);
-                    x[0] = __uint_as_float(raw.x << 16); x[1] = __uint_as_float(raw.x & 0xffff0000u);
-                    x[2] = __uint_as_float(raw.y << 16); x[3] = __uint_as_float(raw.y & 0xffff0000u);
+                if (IN_H16) {
+                    const uint2 raw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const h16_t *>(in) + (size_t)token * H + n);
+                    h16x2_to_f32(raw.x, x[0], x[1]);
+                    h16x2_to_f32(raw.y, x[2], x[3]);
                 } else {
                     const float4 v = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(in) + (size_t)token * H + n);
                     x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
@@ -853,8 +856,8 @@ __global__ __launch_bounds__(256) void prefill_prologue_kernel(const void *__res
                 if (h_out) *reinterpret_cast<float4 *>(h_out + h_tile_offset(token, n, H)) = make_float4(x[0], x[1], x[2], x[3]);
                 const float4 g4 = *reinterpret_cast<const float4 *>(g + n);
                 uint2 o;
-                o.x = pack_bf16x2(x[0] * g4.x, x[1] * g4.y);
-                o.y = pack_bf16x2(x[2] * g4.z, x[3] * g4.w);
+                o.x = pack_h16x2(x[0] * g4.x, x[1] * g4.y);
+                o.y = pack_h16x2(x[2] * g4.z, x[3] * g4.w);
                 *reinterpret_cast<uint2 *>(hg + frag_offset(token, n, H >> 5)) = o;
             }
             ss += x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
@@ -864,11 +867,11 @@ __global__ __launch_bounds__(256) void prefill_prologue_kernel(const void *__res
     if (hl == 0 && tv) ssq_out[(size_t)(col0 / GEMM_SSQ_COLS) * T + token] = ss;
 }
 
-void launch_prefill_prologue(const void *in, int in_is_bf16, float *h_out, const float *g, bf16_t *hg, float *ssq_out,
+void launch_prefill_prologue(const void *in, int in_is_h16, float *h_out, const float *g, h16_t *hg, float *ssq_out,
                              int T, int H, hipStream_t s) {
     if (T <= 0) return;
     const dim3 grid((T + 31) / 32, (H / GEMM_SSQ_COLS + 3) / 4);
-    if (in_is_bf16)
+    if (in_is_h16)
         hipLaunchKernelGGL(prefill_prologue_kernel<true>, grid, dim3(256), 0, s, in, h_out, g, hg, ssq_out, T, H);
     else
         hipLaunchKernelGGL(prefill_prologue_kernel<false>, grid, dim3(256), 0, s, in, h_out, g, hg, ssq_out, T, H);
@@ -886,3 +889,5 @@ void launch_untile_h(const float *h_tiled, float *out, int T, int H, hipStream_t
     if (n4 <= 0) return;
     hipLaunchKernelGGL(untile_h_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, h_tiled, out, T, H);
 }
+
+}  // namespace HX_NS

@@ -1,0 +1,3 @@
+// The fp16 instance of kernels_bf16_attn.hip: same source, element type fp16 (v_mfma_*_f16, fp16 conversions), namespace f16.
+#define HX_ELEM_F16 1
+#include "kernels_bf16_attn.hip"

@@ -5,8 +5,8 @@
 // One thread builds one 16-byte lane slot of the packed matrix.
 // rope_d > 0: the columns are heads of width rope_d and every 16-row tile of a head is filled with 8 rotary
 // pairs: tile rows 0-7 = head columns 8*tl .. 8*tl+7, rows 8-15 = the same columns + rope_d/2.
-__global__ void pack_weight_kernel(const bf16_t *__restrict__ src, int64_t ld, int k0, int c0, int k_tiles,
-                                   int n_tiles, bf16_t *__restrict__ dst, int dst_tile0, int dst_tile_stride,
+__global__ void pack_weight_kernel(const h16_t *__restrict__ src, int64_t ld, int k0, int c0, int k_tiles,
+                                   int n_tiles, h16_t *__restrict__ dst, int dst_tile0, int dst_tile_stride,
                                    int dst_n_tiles, int rope_d) {
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t total = (int64_t)n_tiles * k_tiles * 64;
@@ -20,14 +20,14 @@ __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, int64_t ld, i
         n = c0 + head * rope_d + tl * 8 + (i & 7) + (i >= 8 ? (rope_d >> 1) : 0);
     }
     int k = k0 + kt * 32 + 8 * (lane >> 4);
-    union { bf16_t e[8]; uint4 v; } u;
+    union { h16_t e[8]; uint4 v; } u;
 #pragma unroll
     for (int j = 0; j < 8; ++j) u.e[j] = src[(int64_t)(k + j) * ld + n];
     int64_t dt = (int64_t)dst_tile0 + (int64_t)nt * dst_tile_stride;
     *reinterpret_cast<uint4 *>(dst + (((int64_t)kt * dst_n_tiles + dt) * 64 + lane) * 8) = u.v;
 }
 
-void launch_pack_weight(const bf16_t *src, int64_t ld, int k0, int c0, int K, int N, bf16_t *dst,
+void launch_pack_weight(const h16_t *src, int64_t ld, int k0, int c0, int K, int N, h16_t *dst,
                         int dst_tile0, int dst_tile_stride, int dst_n_tiles, int rope_d, hipStream_t s) {
     int k_tiles = K / 32, n_tiles = N / 16;
     int64_t total = (int64_t)n_tiles * k_tiles * 64;
@@ -35,17 +35,6 @@ void launch_pack_weight(const bf16_t *src, int64_t ld, int k0, int c0, int K, in
     int blocks = (int)((total + 255) / 256);
     hipLaunchKernelGGL(pack_weight_kernel, dim3(blocks), dim3(256), 0, s, src, ld, k0, c0, k_tiles, n_tiles,
                        dst, dst_tile0, dst_tile_stride, dst_n_tiles, rope_d);
-}
-
-__global__ void cvt_bf16_to_f32_kernel(const bf16_t *__restrict__ src, float *__restrict__ dst, int64_t n) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) dst[i] = bf16_to_f32(src[i]);
-}
-void launch_cvt_bf16_to_f32(const bf16_t *src, float *dst, int64_t n, hipStream_t s) {
-    if (n <= 0) return;
-    int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
-    hipLaunchKernelGGL(cvt_bf16_to_f32_kernel, dim3(blocks), dim3(256), 0, s, src, dst, n);
 }
 
 __global__ void accumulate_f32_kernel(float *__restrict__ dst, const float *__restrict__ src, int64_t n) {
@@ -74,20 +63,6 @@ void launch_advance_lens(int32_t *lens, int b, hipStream_t s) {
     hipLaunchKernelGGL(advance_lens_kernel, dim3((b + 63) / 64), dim3(64), 0, s, lens, b);
 }
 
-__global__ void store_out_kernel(const float *__restrict__ src, void *__restrict__ dst, int dst_is_bf16, int64_t n) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) {
-        if (dst_is_bf16) reinterpret_cast<bf16_t *>(dst)[i] = f32_to_bf16(src[i]);
-        else reinterpret_cast<float *>(dst)[i] = src[i];
-    }
-}
-void launch_store_out(const float *src, void *dst, int dst_is_bf16, int64_t n, hipStream_t s) {
-    if (n <= 0) return;
-    int blocks = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
-    hipLaunchKernelGGL(store_out_kernel, dim3(blocks), dim3(256), 0, s, src, dst, dst_is_bf16, n);
-}
-
 // zero fill as a kernel (a memset node recorded into a captured graph is avoided on purpose)
 __global__ void fill_zero_kernel(uint32_t *__restrict__ p, size_t n_words) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -99,46 +74,6 @@ void launch_fill_zero(void *p, size_t bytes, hipStream_t s) {
     if (n == 0) return;
     const int blocks = (int)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
     hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, static_cast<uint32_t *>(p), n);
-}
-
-// staging [n][hkv_l][d] fp32  <->  packed cache slabs of sequence `seq`
-__global__ void kv_scatter_kernel(const float *__restrict__ k, const float *__restrict__ v, bf16_t *__restrict__ kc,
-                                  bf16_t *__restrict__ vc, KvGeom kg, int seq, int pos0, int n) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t total = (int64_t)n * kg.hkv_l * kg.d;
-    if (i >= total) return;
-    int dd = (int)(i % kg.d);
-    int c = (int)((i / kg.d) % kg.hkv_l);
-    int p = pos0 + (int)(i / ((int64_t)kg.d * kg.hkv_l));
-    size_t slab = (size_t)seq * kg.seq_stride + (size_t)c * kg.smax * kg.d;
-    kc[slab + kv_k_offset(p, dd, kg.d)] = f32_to_bf16(k[i]);
-    vc[slab + kv_v_offset(p, dd, kg.d)] = f32_to_bf16(v[i]);
-}
-void launch_kv_scatter(const float *k, const float *v, bf16_t *kc, bf16_t *vc, KvGeom kg, int seq, int pos0,
-                       int n, hipStream_t s) {
-    int64_t total = (int64_t)n * kg.hkv_l * kg.d;
-    if (total <= 0) return;
-    hipLaunchKernelGGL(kv_scatter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, k, v, kc, vc, kg,
-                       seq, pos0, n);
-}
-__global__ void kv_gather_kernel(const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vc, KvGeom kg, int seq,
-                                 int pos0, int n, float *__restrict__ k, float *__restrict__ v) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t total = (int64_t)n * kg.hkv_l * kg.d;
-    if (i >= total) return;
-    int dd = (int)(i % kg.d);
-    int c = (int)((i / kg.d) % kg.hkv_l);
-    int p = pos0 + (int)(i / ((int64_t)kg.d * kg.hkv_l));
-    size_t slab = (size_t)seq * kg.seq_stride + (size_t)c * kg.smax * kg.d;
-    k[i] = bf16_to_f32(kc[slab + kv_k_offset(p, dd, kg.d)]);
-    v[i] = bf16_to_f32(vc[slab + kv_v_offset(p, dd, kg.d)]);
-}
-void launch_kv_gather(const bf16_t *kc, const bf16_t *vc, KvGeom kg, int seq, int pos0, int n, float *k, float *v,
-                      hipStream_t s) {
-    int64_t total = (int64_t)n * kg.hkv_l * kg.d;
-    if (total <= 0) return;
-    hipLaunchKernelGGL(kv_gather_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, kc, vc, kg, seq,
-                       pos0, n, k, v);
 }
 
 // ---- measurement utilities: plain streaming kernels of known size ---------------------------------
@@ -255,7 +190,7 @@ void launch_embed_rows(const void *table, int64_t row_bytes, int vocab, const in
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 template <int VARIANT, bool RANDOM>
 __global__ __launch_bounds__(256) void mfma_probe_kernel(float *sink, int iters) {
-    __shared__ bf16x8 sm[32][64];
+    __shared__ h16x8 sm[32][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int i = threadIdx.x; i < 32 * 64; i += 256) {
         uint32_t h = (uint32_t)i * 2654435761u + blockIdx.x * 40503u;
@@ -264,7 +199,7 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *sink, int iters)
             h = h * 1664525u + 1013904223u;
             w[c] = RANDOM ? ((h & 0x807f807fu) | 0x3f003f00u) : 0x3f803f80u;      // +-[0.5, 1) or 1.0, twice
         }
-        sm[i >> 6][i & 63] = *reinterpret_cast<const bf16x8 *>(w);
+        sm[i >> 6][i & 63] = *reinterpret_cast<const h16x8 *>(w);
     }
     __syncthreads();
     constexpr bool LDS = VARIANT >= 2;
@@ -275,7 +210,7 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *sink, int iters)
         for (int i = 0; i < 8; ++i)
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-        bf16x8 a[8], b[8];
+        h16x8 a[8], b[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) { a[i] = sm[i][lane]; b[i] = sm[8 + i][lane]; }
         for (int it = 0; it < iters; ++it) {
@@ -303,7 +238,7 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *sink, int iters)
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-        bf16x8 a[4], b[4];
+        h16x8 a[4], b[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) { a[i] = sm[i][lane]; b[i] = sm[8 + i][lane]; }
         for (int it = 0; it < iters; ++it) {

@@ -68,13 +68,13 @@ struct Workspace {
     float *part = nullptr;     // projection outputs / split-K partials, fp32
     float *p32 = nullptr;      // reduced partial [T][H] fp32
     // bf16 path
-    bf16_t *n = nullptr, *o = nullptr, *u = nullptr, *q = nullptr;
+    h16_t *n = nullptr, *o = nullptr, *u = nullptr, *q = nullptr;
     float *dec_part = nullptr;       // split partial sums of the batched decode projections
     size_t dec_part_floats = 0;
     float *gemm_part = nullptr;      // fp32 partial tiles of a split prefill contraction (short prompts)
     size_t gemm_part_floats = 0;
-    bf16_t *xa_n = nullptr, *xa_o = nullptr, *xa_u = nullptr;   // decode operands, compact hi/lo layout [32][K][2]
-    bf16_t *q_lo = nullptr;
+    h16_t *xa_n = nullptr, *xa_o = nullptr, *xa_u = nullptr;   // decode operands, compact hi/lo layout [32][K][2]
+    h16_t *q_lo = nullptr;
     float *att_o = nullptr, *att_ml = nullptr;
     unsigned int *att_arrived = nullptr;      // per (sequence, kv head): split blocks that have finished; zero between launches
     float *ssq = nullptr;                       // decode: 2 x [H/16 units][DEC_SSQ_STRIDE] sums of squares
@@ -122,6 +122,10 @@ struct hexgen_kv_cache {
 namespace {
 
 size_t esize(hexgen_dtype_t dt) { return dt == HEXGEN_F32 ? 4 : 2; }
+bool is_h16(hexgen_dtype_t dt) { return dt == HEXGEN_BF16 || dt == HEXGEN_F16; }
+bool known_dtype(hexgen_dtype_t dt) { return dt == HEXGEN_F32 || is_h16(dt); }
+// The 16-bit kernels exist once per element type (namespaces bf16 and f16): pick by the stage's type.
+#define HX_K(dt, fn, ...) ((dt) == HEXGEN_F16 ? f16::fn(__VA_ARGS__) : bf16::fn(__VA_ARGS__))
 
 void free_ws(Workspace &w) {
     void *ptrs[] = {w.dec_part, w.gemm_part, w.h, w.part, w.p32, w.n, w.o, w.u, w.q, w.xa_n, w.xa_o, w.xa_u, w.q_lo, w.ssq, w.ssq_pf, w.att_o, w.att_ml, w.att_arrived, w.n32, w.q32, w.o32, w.u32,
@@ -156,7 +160,7 @@ hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
         HX_TRY(dmalloc(&w.part, T * nmax));
         HX_TRY(dmalloc(&w.p32, T * st->H));
     }
-    if (st->dtype == HEXGEN_BF16) {
+    if (is_h16(st->dtype)) {
         HX_TRY(dmalloc(&w.n, T16 * st->H));
         HX_TRY(dmalloc(&w.o, T16 * st->qw));
         HX_TRY(dmalloc(&w.u, T16 * st->F_l));
@@ -181,9 +185,9 @@ hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
         HX_TRY(dmalloc(&w.ssq_pf, 2 * (size_t)(st->H / GEMM_SSQ_COLS + 1) * T));
         HX_HIP(hipMemset(w.ssq, 0, ssq_n * sizeof(float)));
         // padded rows of the packed operands are read by the GEMM tiles: keep them finite
-        HX_HIP(hipMemset(w.n, 0, T16 * st->H * sizeof(bf16_t)));
-        HX_HIP(hipMemset(w.o, 0, T16 * st->qw * sizeof(bf16_t)));
-        HX_HIP(hipMemset(w.u, 0, T16 * st->F_l * sizeof(bf16_t)));
+        HX_HIP(hipMemset(w.n, 0, T16 * st->H * sizeof(h16_t)));
+        HX_HIP(hipMemset(w.o, 0, T16 * st->qw * sizeof(h16_t)));
+        HX_HIP(hipMemset(w.u, 0, T16 * st->F_l * sizeof(h16_t)));
     } else {
         HX_TRY(dmalloc(&w.n32, T * st->H));
         HX_TRY(dmalloc(&w.q32, T * st->qw));
@@ -234,7 +238,7 @@ hexgen_status_t setup_rows(hexgen_stage *st, hexgen_kv_cache *kv, const int32_t 
     w.pos0 = w.cu_rows + batch + 1;
     r.rm.row_seq = w.row_seq;
     r.rm.row_pos = w.row_pos;
-    if (r.decode && st->dtype == HEXGEN_BF16) {
+    if (r.decode && is_h16(st->dtype)) {
         // the decode prologue kernel publishes row positions from the committed lengths on the device
     } else if (r.decode) {
         launch_decode_rowmap(kv->d_lens, w.row_seq, w.row_pos, batch, s);
@@ -279,80 +283,80 @@ GemmEpi gemm_epi_base(hexgen_stage *st, int mode) {
     return e;
 }
 
-void gemm_bf16(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xp, int N, int K, const GemmEpi &e,
+void gemm_h16(hexgen_stage *st, const Rows &r, const void *Wp, const h16_t *Xp, int N, int K, const GemmEpi &e,
                int slot, hipStream_t s) {
     st->prof.mark(slot, s);
-    launch_gemm_mfma(static_cast<const bf16_t *>(Wp), Xp, N, K, r.T, e, st->ws.gemm_part, st->ws.gemm_part_floats, s);
+    HX_K(st->dtype, launch_gemm_mfma, static_cast<const h16_t *>(Wp), Xp, N, K, r.T, e, st->ws.gemm_part, st->ws.gemm_part_floats, s);
     st->prof.mark(slot, s);
 }
 
 // QKV projection (+RoPE, cache append) and causal attention; leaves o (fragment tiles) in the workspace
-void attn_prefill_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Rows &r, const float *ssq_in,
+void attn_prefill_h16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Rows &r, const float *ssq_in,
                        hipStream_t s) {
     Workspace &w = st->ws;
     const Layer &ly = st->layers[layer];
     const KvGeom kg = geom(st, kv);
-    bf16_t *kc = static_cast<bf16_t *>(kv->k) + (size_t)layer * kv->layer_stride;
-    bf16_t *vc = static_cast<bf16_t *>(kv->v) + (size_t)layer * kv->layer_stride;
+    h16_t *kc = static_cast<h16_t *>(kv->k) + (size_t)layer * kv->layer_stride;
+    h16_t *vc = static_cast<h16_t *>(kv->v) + (size_t)layer * kv->layer_stride;
     GemmEpi e = gemm_epi_base(st, DEC_QKV);
     e.ssq_in = ssq_in;
     e.hq_l = st->hq_l; e.kg = kg; e.rm = r.rm; e.cos_tab = kv->cos_tab; e.sin_tab = kv->sin_tab;
     e.q = w.q; e.kc = kc; e.vc = vc;
-    gemm_bf16(st, r, ly.wqkv, w.n, st->nqkv, st->H, e, PROF_QKV, s);
+    gemm_h16(st, r, ly.wqkv, w.n, st->nqkv, st->H, e, PROF_QKV, s);
     st->prof.mark(PROF_ATTN, s);
     // one new row per sequence (a decode step of more than 32 sequences): the decode attention kernel, which shares
     // every K / V fragment among the query heads of its kv head, on this path's layouts (row = sequence)
     if (r.max_new == 1 && st->hq_l / st->hkv_l <= 16)
-        launch_attn_decode_rows(w.q, kc, vc, kg, st->hq_l, w.pos0, r.batch, w.o, s);
+        HX_K(st->dtype, launch_attn_decode_rows, w.q, kc, vc, kg, st->hq_l, w.pos0, r.batch, w.o, s);
     else
-        launch_attn_prefill(w.q, kc, vc, kg, st->hq_l, w.cu_rows, w.pos0, r.batch, r.max_new, w.o, s);
+        HX_K(st->dtype, launch_attn_prefill, w.q, kc, vc, kg, st->hq_l, w.cu_rows, w.pos0, r.batch, r.max_new, w.o, s);
     st->prof.mark(PROF_ATTN, s);
 }
 
-hexgen_status_t forward_prefill_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
+hexgen_status_t forward_prefill_h16(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
                                      void *out_partial, void *out_resid, hipStream_t s) {
     Workspace &w = st->ws;
     float *ssq_a = w.ssq_pf, *ssq_f = w.ssq_pf + (size_t)(st->H / GEMM_SSQ_COLS) * r.T;
-    launch_prefill_prologue(hidden_in, 1, w.h, st->layers[0].g_attn, w.n, ssq_a, r.T, st->H, s);
+    HX_K(st->dtype, launch_prefill_prologue, hidden_in, 1, w.h, st->layers[0].g_attn, w.n, ssq_a, r.T, st->H, s);
     for (int l = 0; l < st->L; ++l) {
         const Layer &ly = st->layers[l];
         const bool last = l + 1 == st->L;
-        if (st->taps[l]) launch_untile_h(w.h, static_cast<float *>(st->taps[l]), r.T, st->H, s);
-        attn_prefill_bf16(st, kv, l, r, ssq_a, s);
+        if (st->taps[l]) HX_K(st->dtype, launch_untile_h, w.h, static_cast<float *>(st->taps[l]), r.T, st->H, s);
+        attn_prefill_h16(st, kv, l, r, ssq_a, s);
         GemmEpi e = gemm_epi_base(st, DEC_RESID);
         e.h = w.h; e.g_next = ly.g_ffn; e.hg = w.n; e.ssq_out = ssq_f;
-        gemm_bf16(st, r, ly.wo, w.o, st->H, st->qw, e, PROF_WO, s);
+        gemm_h16(st, r, ly.wo, w.o, st->H, st->qw, e, PROF_WO, s);
         e = gemm_epi_base(st, DEC_SWIGLU);
         e.ssq_in = ssq_f; e.u = w.u; e.F_l = st->F_l;
-        gemm_bf16(st, r, ly.w13, w.n, 2 * st->F_l, st->H, e, PROF_W13, s);
+        gemm_h16(st, r, ly.w13, w.n, 2 * st->F_l, st->H, e, PROF_W13, s);
         e = gemm_epi_base(st, DEC_RESID);
         e.h = w.h; e.hg = w.n; e.ssq_out = ssq_a;
         e.g_next = last ? nullptr : st->layers[l + 1].g_attn;
         e.last_layer = last ? 1 : 0;
-        e.out_partial = static_cast<bf16_t *>(out_partial);
-        e.out_resid = static_cast<bf16_t *>(out_resid);
-        gemm_bf16(st, r, ly.w2, w.u, st->H, st->F_l, e, PROF_W2, s);
+        e.out_partial = static_cast<h16_t *>(out_partial);
+        e.out_resid = static_cast<h16_t *>(out_resid);
+        gemm_h16(st, r, ly.w2, w.u, st->H, st->F_l, e, PROF_W2, s);
     }
     return HEXGEN_OK;
 }
 
 // one sub-layer for the validation surface, prefill kernels; h fp32 in, raw fp32 partial out
-void sublayer_prefill_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, int which, const Rows &r, const float *h,
+void sublayer_prefill_h16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, int which, const Rows &r, const float *h,
                            float *p_out, hipStream_t s) {
     Workspace &w = st->ws;
     const Layer &ly = st->layers[layer];
     float *ssq = w.ssq_pf;
     GemmEpi e = gemm_epi_base(st, DEC_RAW);
     e.raw_out = p_out;
-    launch_prefill_prologue(h, 0, nullptr, which == 0 ? ly.g_attn : ly.g_ffn, w.n, ssq, r.T, st->H, s);
+    HX_K(st->dtype, launch_prefill_prologue, h, 0, nullptr, which == 0 ? ly.g_attn : ly.g_ffn, w.n, ssq, r.T, st->H, s);
     if (which == 0) {
-        attn_prefill_bf16(st, kv, layer, r, ssq, s);
-        gemm_bf16(st, r, ly.wo, w.o, st->H, st->qw, e, PROF_WO, s);
+        attn_prefill_h16(st, kv, layer, r, ssq, s);
+        gemm_h16(st, r, ly.wo, w.o, st->H, st->qw, e, PROF_WO, s);
     } else {
         GemmEpi g = gemm_epi_base(st, DEC_SWIGLU);
         g.ssq_in = ssq; g.u = w.u; g.F_l = st->F_l;
-        gemm_bf16(st, r, ly.w13, w.n, 2 * st->F_l, st->H, g, PROF_W13, s);
-        gemm_bf16(st, r, ly.w2, w.u, st->H, st->F_l, e, PROF_W2, s);
+        gemm_h16(st, r, ly.w13, w.n, 2 * st->F_l, st->H, g, PROF_W13, s);
+        gemm_h16(st, r, ly.w2, w.u, st->H, st->F_l, e, PROF_W2, s);
     }
 }
 
@@ -381,7 +385,7 @@ DecodeEpi epi_base(hexgen_stage *st, int mode) {
     return e;
 }
 
-void decode_proj(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *Xa, int N, int K, const DecodeEpi &e,
+void decode_proj(hexgen_stage *st, const Rows &r, const void *Wp, const h16_t *Xa, int N, int K, const DecodeEpi &e,
                  int slot, hipStream_t s) {
     st->prof.mark(slot, s);
     // slot 6: the first kernel of the W1/W3 projection alone (the batched path adds a finishing kernel behind it)
@@ -396,42 +400,42 @@ void decode_proj(hexgen_stage *st, const Rows &r, const void *Wp, const bf16_t *
             mid = nullptr;
         }
     }
-    launch_decode_proj(static_cast<const bf16_t *>(Wp), Xa, N, K, r.T, e, st->cur->dec_part, st->cur->dec_part_floats, s, mid);
+    HX_K(st->dtype, launch_decode_proj, static_cast<const h16_t *>(Wp), Xa, N, K, r.T, e, st->cur->dec_part, st->cur->dec_part_floats, s, mid);
     if (mid) st->prof.ev[PROF_W13_MAIN].push_back(mid);
     st->prof.mark(slot, s);
 }
 
 // QKV (+RoPE, cache append) and attention; leaves o (hi/lo) in the workspace
-void attn_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Rows &r, const float *ssq_in,
+void attn_decode_h16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Rows &r, const float *ssq_in,
                       hipStream_t s) {
     Workspace &w = *st->cur;
     const Layer &ly = st->layers[layer];
     const KvGeom kg = geom(st, kv);
-    bf16_t *kc = static_cast<bf16_t *>(kv->k) + (size_t)layer * kv->layer_stride;
-    bf16_t *vc = static_cast<bf16_t *>(kv->v) + (size_t)layer * kv->layer_stride;
+    h16_t *kc = static_cast<h16_t *>(kv->k) + (size_t)layer * kv->layer_stride;
+    h16_t *vc = static_cast<h16_t *>(kv->v) + (size_t)layer * kv->layer_stride;
     DecodeEpi e = epi_base(st, DEC_QKV);
     e.ssq_in = ssq_in;
     e.hq_l = st->hq_l; e.kg = kg; e.row_pos = w.row_pos; e.cos_tab = kv->cos_tab; e.sin_tab = kv->sin_tab;
     e.q_hi = w.q; e.q_lo = w.q_lo; e.kc = kc; e.vc = vc;
     decode_proj(st, r, ly.wqkv, w.xa_n, st->nqkv, st->H, e, PROF_QKV, s);
     st->prof.mark(PROF_ATTN, s);
-    launch_attn_decode(w.q, w.q_lo, kc, vc, kg, st->hq_l, w.row_pos, r.batch, pick_attn_split(st, kv, r.batch), w.att_o,
+    HX_K(st->dtype, launch_attn_decode, w.q, w.q_lo, kc, vc, kg, st->hq_l, w.row_pos, r.batch, pick_attn_split(st, kv, r.batch), w.att_o,
                        w.att_ml, w.att_arrived, w.xa_o, s);
     st->prof.mark(PROF_ATTN, s);
 }
 
-hexgen_status_t forward_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
+hexgen_status_t forward_decode_h16(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
                                     void *out_partial, void *out_resid, hipStream_t s) {
     Workspace &w = *st->cur;
     float *ssq_a = w.ssq, *ssq_f = w.ssq + (size_t)(st->H / 16) * DEC_SSQ_STRIDE;
-    launch_decode_prologue(hidden_in, nullptr, 1, w.h, st->layers[0].g_attn, w.xa_n, ssq_a, r.T, st->H, kv->d_lens,
+    HX_K(st->dtype, launch_decode_prologue, hidden_in, nullptr, 1, w.h, st->layers[0].g_attn, w.xa_n, ssq_a, r.T, st->H, kv->d_lens,
                            w.row_pos, 1, s);
     for (int l = 0; l < st->L; ++l) {
         const Layer &ly = st->layers[l];
         const bool last = l + 1 == st->L;
         if (st->taps[l])
             HX_HIP(hipMemcpyAsync(st->taps[l], w.h, sizeof(float) * (size_t)r.T * st->H, hipMemcpyDeviceToDevice, s));
-        attn_decode_bf16(st, kv, l, r, ssq_a, s);
+        attn_decode_h16(st, kv, l, r, ssq_a, s);
         DecodeEpi e = epi_base(st, DEC_RESID);
         e.h = w.h; e.g_next = ly.g_ffn; e.hg = w.xa_n; e.ssq_out = ssq_f;
         decode_proj(st, r, ly.wo, w.xa_o, st->H, st->qw, e, PROF_WO, s);
@@ -442,15 +446,15 @@ hexgen_status_t forward_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const
         e.h = w.h; e.hg = w.xa_n; e.ssq_out = ssq_a;
         e.g_next = last ? nullptr : st->layers[l + 1].g_attn;
         e.last_layer = last ? 1 : 0;
-        e.out_partial = static_cast<bf16_t *>(out_partial);
-        e.out_resid = static_cast<bf16_t *>(out_resid);
+        e.out_partial = static_cast<h16_t *>(out_partial);
+        e.out_resid = static_cast<h16_t *>(out_resid);
         decode_proj(st, r, ly.w2, w.xa_u, st->H, st->F_l, e, PROF_W2, s);
     }
     return HEXGEN_OK;
 }
 
 // one sub-layer for the validation surface, decode kernels; h fp32 in, raw fp32 partial out
-void sublayer_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, int which, const Rows &r, const float *h,
+void sublayer_decode_h16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, int which, const Rows &r, const float *h,
                           float *p_out, hipStream_t s) {
     Workspace &w = st->ws;
     const Layer &ly = st->layers[layer];
@@ -458,11 +462,11 @@ void sublayer_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, int 
     DecodeEpi e = epi_base(st, DEC_RAW);
     e.raw_out = p_out;
     if (which == 0) {
-        launch_decode_prologue(h, nullptr, 0, nullptr, ly.g_attn, w.xa_n, ssq, r.T, st->H, kv->d_lens, w.row_pos, 0, s);
-        attn_decode_bf16(st, kv, layer, r, ssq, s);
+        HX_K(st->dtype, launch_decode_prologue, h, nullptr, 0, nullptr, ly.g_attn, w.xa_n, ssq, r.T, st->H, kv->d_lens, w.row_pos, 0, s);
+        attn_decode_h16(st, kv, layer, r, ssq, s);
         decode_proj(st, r, ly.wo, w.xa_o, st->H, st->qw, e, PROF_WO, s);
     } else {
-        launch_decode_prologue(h, nullptr, 0, nullptr, ly.g_ffn, w.xa_n, ssq, r.T, st->H, nullptr, nullptr, 0, s);
+        HX_K(st->dtype, launch_decode_prologue, h, nullptr, 0, nullptr, ly.g_ffn, w.xa_n, ssq, r.T, st->H, nullptr, nullptr, 0, s);
         DecodeEpi g = epi_base(st, DEC_SWIGLU);
         g.ssq_in = ssq; g.u = w.xa_u; g.F_l = st->F_l;
         decode_proj(st, r, ly.w13, w.xa_n, 2 * st->F_l, st->H, g, PROF_W13, s);
@@ -470,10 +474,10 @@ void sublayer_decode_bf16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, int 
     }
 }
 
-hexgen_status_t forward_bf16(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
+hexgen_status_t forward_h16(hexgen_stage *st, hexgen_kv_cache *kv, const Rows &r, const void *hidden_in,
                              void *out_partial, void *out_resid, hipStream_t s) {
-    if (r.decode) return forward_decode_bf16(st, kv, r, hidden_in, out_partial, out_resid, s);
-    return forward_prefill_bf16(st, kv, r, hidden_in, out_partial, out_resid, s);
+    if (r.decode) return forward_decode_h16(st, kv, r, hidden_in, out_partial, out_resid, s);
+    return forward_prefill_h16(st, kv, r, hidden_in, out_partial, out_resid, s);
 }
 
 // ---- fp32 path -------------------------------------------------------------------------------
@@ -588,11 +592,11 @@ size_t carve_decode_workspace(const hexgen_stage *st, int rows, unsigned char *b
     Workspace v;
     v.cap_rows = rows;
     v.h = static_cast<float *>(take(T * st->H * sizeof(float)));
-    v.xa_n = static_cast<bf16_t *>(take(2 * T * st->H * sizeof(bf16_t)));
-    v.xa_o = static_cast<bf16_t *>(take(2 * T * st->qw * sizeof(bf16_t)));
-    v.xa_u = static_cast<bf16_t *>(take(2 * T * st->F_l * sizeof(bf16_t)));
-    v.q = static_cast<bf16_t *>(take(T * st->qw * sizeof(bf16_t)));
-    v.q_lo = static_cast<bf16_t *>(take(T * st->qw * sizeof(bf16_t)));
+    v.xa_n = static_cast<h16_t *>(take(2 * T * st->H * sizeof(h16_t)));
+    v.xa_o = static_cast<h16_t *>(take(2 * T * st->qw * sizeof(h16_t)));
+    v.xa_u = static_cast<h16_t *>(take(2 * T * st->F_l * sizeof(h16_t)));
+    v.q = static_cast<h16_t *>(take(T * st->qw * sizeof(h16_t)));
+    v.q_lo = static_cast<h16_t *>(take(T * st->qw * sizeof(h16_t)));
     if (rows > 2) {
         v.dec_part_floats = T * ((size_t)512 * 128 + 2 * nmax);
         v.dec_part = static_cast<float *>(take(v.dec_part_floats * sizeof(float)));
@@ -629,7 +633,7 @@ hexgen_status_t hexgen_stage_create(int hidden, int n_heads, int n_kv_heads, int
     if (!out) return HEXGEN_ERR_INVALID_ARG;
     if (hidden <= 0 || n_heads <= 0 || n_kv_heads <= 0 || ffn <= 0 || n_layers <= 0 || tp_degree <= 0)
         return HEXGEN_ERR_INVALID_ARG;
-    if (dtype != HEXGEN_F32 && dtype != HEXGEN_BF16) return HEXGEN_ERR_INVALID_ARG;
+    if (!known_dtype(dtype)) return HEXGEN_ERR_INVALID_ARG;
     if (tp_rank < 0 || tp_rank >= tp_degree) return HEXGEN_ERR_SHAPE;
     if (hidden % n_heads || n_heads % n_kv_heads || n_heads % tp_degree || n_kv_heads % tp_degree ||
         ffn % tp_degree)
@@ -638,7 +642,7 @@ hexgen_status_t hexgen_stage_create(int hidden, int n_heads, int n_kv_heads, int
     if (d != 64 && d != 128) return HEXGEN_ERR_SHAPE;
     const int hq_l = n_heads / tp_degree, hkv_l = n_kv_heads / tp_degree, F_l = ffn / tp_degree;
     if (hq_l / hkv_l > 16) return HEXGEN_ERR_SHAPE;          // one MFMA column block per query group
-    if (dtype == HEXGEN_BF16 && (hidden % 128 || (hq_l * d) % 32 || F_l % 32)) return HEXGEN_ERR_SHAPE;
+    if (is_h16(dtype) && (hidden % 128 || (hq_l * d) % 32 || F_l % 32)) return HEXGEN_ERR_SHAPE;
     if (hidden % 8) return HEXGEN_ERR_SHAPE;
     hexgen_stage *st = new (std::nothrow) hexgen_stage();
     if (!st) return HEXGEN_ERR_OOM;
@@ -699,13 +703,13 @@ hexgen_status_t hexgen_stage_load_layer(hexgen_stage_t *st, int layer, const voi
         HX_HIP(hipMemcpy(ly.g_attn, g_attn, sizeof(float) * H, hipMemcpyDefault));
         HX_HIP(hipMemcpy(ly.g_ffn, g_ffn, sizeof(float) * H, hipMemcpyDefault));
     } else {
-        bf16_t *tmp = nullptr;
+        h16_t *tmp = nullptr;
         HX_TRY(dmalloc(&tmp, (size_t)2 * H));
-        hipError_t e1 = hipMemcpy(tmp, g_attn, sizeof(bf16_t) * H, hipMemcpyDefault);
-        hipError_t e2 = hipMemcpy(tmp + H, g_ffn, sizeof(bf16_t) * H, hipMemcpyDefault);
+        hipError_t e1 = hipMemcpy(tmp, g_attn, sizeof(h16_t) * H, hipMemcpyDefault);
+        hipError_t e2 = hipMemcpy(tmp + H, g_ffn, sizeof(h16_t) * H, hipMemcpyDefault);
         if (e1 == hipSuccess && e2 == hipSuccess) {
-            launch_cvt_bf16_to_f32(tmp, ly.g_attn, H, nullptr);
-            launch_cvt_bf16_to_f32(tmp + H, ly.g_ffn, H, nullptr);
+            HX_K(st->dtype, launch_cvt_h16_to_f32, tmp, ly.g_attn, H, nullptr);
+            HX_K(st->dtype, launch_cvt_h16_to_f32, tmp + H, ly.g_ffn, H, nullptr);
             e1 = hipDeviceSynchronize();
         }
         (void)hipFree(tmp);
@@ -743,7 +747,7 @@ hexgen_status_t hexgen_stage_load_layer(hexgen_stage_t *st, int layer, const voi
     } else {
         // stage each shard in a dense device buffer, then repack it into MFMA fragment order
         const size_t tmp_elems = std::max(std::max((size_t)H * st->qw, (size_t)H * st->F_l), n_wo);
-        bf16_t *tmp = nullptr;
+        h16_t *tmp = nullptr;
         HX_TRY(dmalloc(&tmp, tmp_elems));
         hexgen_status_t rc = HEXGEN_OK;
         auto col_shard = [&](const void *src, int c0, int gcols, int cols, void *dst, int tile0, int stride, int dst_tiles,
@@ -752,14 +756,14 @@ hexgen_status_t hexgen_stage_load_layer(hexgen_stage_t *st, int layer, const voi
             hipError_t e = hipMemcpy2D(tmp, cbytes(cols), src_at(src, 0, c0, gcols), cbytes(gcols), cbytes(cols), H,
                                        hipMemcpyDefault);
             if (e != hipSuccess) { rc = HEXGEN_ERR_DEVICE; return; }
-            launch_pack_weight(tmp, cols, 0, 0, H, cols, static_cast<bf16_t *>(dst), tile0, stride, dst_tiles, rope_d, nullptr);
+            launch_pack_weight(tmp, cols, 0, 0, H, cols, static_cast<h16_t *>(dst), tile0, stride, dst_tiles, rope_d, nullptr);
             if (hipDeviceSynchronize() != hipSuccess) rc = HEXGEN_ERR_DEVICE;
         };
         auto row_shard = [&](const void *src, int r0, int rows, void *dst) {
             if (rc != HEXGEN_OK) return;
             hipError_t e = hipMemcpy(tmp, src_at(src, r0, 0, H), (size_t)rows * H * es, hipMemcpyDefault);
             if (e != hipSuccess) { rc = HEXGEN_ERR_DEVICE; return; }
-            launch_pack_weight(tmp, H, 0, 0, rows, H, static_cast<bf16_t *>(dst), 0, 1, H / 16, 0, nullptr);
+            launch_pack_weight(tmp, H, 0, 0, rows, H, static_cast<h16_t *>(dst), 0, 1, H / 16, 0, nullptr);
             if (hipDeviceSynchronize() != hipSuccess) rc = HEXGEN_ERR_DEVICE;
         };
         col_shard(wq, q0, qcols, st->qw, ly.wqkv, 0, 1, st->nqkv / 16, d);        // q, k, v tiles hold rotary pairs
@@ -895,11 +899,11 @@ static hexgen_status_t kv_io(hexgen_kv_cache_t *kv, int layer, int seq, int pos0
         if (e == hipSuccess) e = hipMemcpy(dv, v, cnt * sizeof(float), hipMemcpyHostToDevice);
     }
     if (e == hipSuccess) {
-        if (st->dtype == HEXGEN_BF16) {
-            bf16_t *kc = static_cast<bf16_t *>(kv->k) + (size_t)layer * kv->layer_stride;
-            bf16_t *vc = static_cast<bf16_t *>(kv->v) + (size_t)layer * kv->layer_stride;
-            if (to_cache) launch_kv_scatter(dk, dv, kc, vc, geom(st, kv), seq, pos0, n, nullptr);
-            else launch_kv_gather(kc, vc, geom(st, kv), seq, pos0, n, dk, dv, nullptr);
+        if (is_h16(st->dtype)) {
+            h16_t *kc = static_cast<h16_t *>(kv->k) + (size_t)layer * kv->layer_stride;
+            h16_t *vc = static_cast<h16_t *>(kv->v) + (size_t)layer * kv->layer_stride;
+            if (to_cache) HX_K(st->dtype, launch_kv_scatter, dk, dv, kc, vc, geom(st, kv), seq, pos0, n, nullptr);
+            else HX_K(st->dtype, launch_kv_gather, kc, vc, geom(st, kv), seq, pos0, n, dk, dv, nullptr);
         } else {
             float *kc = static_cast<float *>(kv->k) + (size_t)layer * kv->layer_stride;
             float *vc = static_cast<float *>(kv->v) + (size_t)layer * kv->layer_stride;
@@ -948,7 +952,7 @@ hexgen_status_t hexgen_stage_prefill(hexgen_stage_t *st, hexgen_kv_cache_t *kv, 
     Rows r;
     HX_TRY(setup_rows(st, kv, seq_lens, batch, false, s, &r));      // a prefill always takes the GEMM path
     st->prof.mark(PROF_CALL, s);
-    if (st->dtype == HEXGEN_BF16) HX_TRY(forward_bf16(st, kv, r, hidden_in, out_partial, out_resid, s));
+    if (is_h16(st->dtype)) HX_TRY(forward_h16(st, kv, r, hidden_in, out_partial, out_resid, s));
     else HX_TRY(forward_f32(st, kv, r, hidden_in, out_partial, out_resid, s));
     st->prof.mark(PROF_CALL, s);
     for (int i = 0; i < batch; ++i) kv->lens[i] = seq_lens[i];
@@ -972,10 +976,10 @@ hexgen_status_t hexgen_stage_decode(hexgen_stage_t *st, hexgen_kv_cache_t *kv, i
     Rows r;
     HX_TRY(setup_rows(st, kv, nullptr, kv->batch, true, s, &r));
     st->prof.mark(PROF_CALL, s);
-    if (st->dtype == HEXGEN_BF16) HX_TRY(forward_bf16(st, kv, r, hidden_in, out_partial, out_resid, s));
+    if (is_h16(st->dtype)) HX_TRY(forward_h16(st, kv, r, hidden_in, out_partial, out_resid, s));
     else HX_TRY(forward_f32(st, kv, r, hidden_in, out_partial, out_resid, s));
-    if (r.decode && st->dtype == HEXGEN_BF16) st->last_decode_rows = r.T;
-    if (!r.decode || st->dtype != HEXGEN_BF16) launch_advance_lens(kv->d_lens, kv->batch, s);   // else: the prologue did
+    if (r.decode && is_h16(st->dtype)) st->last_decode_rows = r.T;
+    if (!r.decode || !is_h16(st->dtype)) launch_advance_lens(kv->d_lens, kv->batch, s);   // else: the prologue did
     st->prof.mark(PROF_CALL, s);
     for (int i = 0; i < kv->batch; ++i) kv->lens[i] += 1;
     kv->steps += 1;
@@ -986,7 +990,7 @@ hexgen_status_t hexgen_stage_decode_static(hexgen_stage_t *st, hexgen_kv_cache_t
                                            void *out_partial, void *out_resid, void *stream) {
     if (!st || !kv || !hidden_in || !out_partial || kv->st != st) return HEXGEN_ERR_INVALID_ARG;
     HX_TRY(check_loaded(st));
-    if (st->dtype != HEXGEN_BF16) return HEXGEN_ERR_SHAPE;
+    if (!is_h16(st->dtype)) return HEXGEN_ERR_SHAPE;
     if (!kv->prefilled || kv->batch <= 0 || step != kv->steps) return HEXGEN_ERR_STATE;
     HX_TRY(check_rope(st, kv));
     const int batch = kv->batch;
@@ -1013,7 +1017,7 @@ hexgen_status_t hexgen_stage_decode_static(hexgen_stage_t *st, hexgen_kv_cache_t
     const unsigned saved_mask = st->prof.mask;
     st->prof.mask = 0;             // the timing slots create events: not in a call that allocates nothing
     st->cur = &view;
-    const hexgen_status_t rc = forward_decode_bf16(st, kv, r, hidden_in, out_partial, out_resid, s);
+    const hexgen_status_t rc = forward_decode_h16(st, kv, r, hidden_in, out_partial, out_resid, s);
     st->cur = &st->ws;
     st->prof.mask = saved_mask;
     HX_TRY(rc);
@@ -1024,7 +1028,7 @@ hexgen_status_t hexgen_stage_decode_static(hexgen_stage_t *st, hexgen_kv_cache_t
 }
 
 int64_t hexgen_stage_decode_static_bytes(const hexgen_stage_t *st, int batch) {
-    if (!st || batch <= 0 || st->dtype != HEXGEN_BF16) return -1;
+    if (!st || batch <= 0 || !is_h16(st->dtype)) return -1;
     return (int64_t)carve_decode_workspace(st, batch, nullptr, nullptr);
 }
 
@@ -1041,11 +1045,11 @@ hexgen_status_t hexgen_stage_run_sublayer(hexgen_stage_t *st, hexgen_kv_cache_t 
     HX_TRY(setup_rows(st, kv, seq_lens, batch, true, s, &r));
     const float *h = static_cast<const float *>(h_in);
     float *p = static_cast<float *>(partial_out);
-    if (st->dtype == HEXGEN_BF16) {
+    if (is_h16(st->dtype)) {
         if (r.decode) {
-            sublayer_decode_bf16(st, kv, layer, which, r, h, p, s);
+            sublayer_decode_h16(st, kv, layer, which, r, h, p, s);
         } else {
-            sublayer_prefill_bf16(st, kv, layer, which, r, h, p, s);
+            sublayer_prefill_h16(st, kv, layer, which, r, h, p, s);
         }
     } else {
         if (which == 0) attn_f32(st, kv, layer, r, h, p, s);
@@ -1089,7 +1093,7 @@ hexgen_status_t hexgen_stage_time_w13_decode(hexgen_stage_t *st, int reps, doubl
                                              void *stream) {
     if (!st || !total_ms || !launches || reps <= 0) return HEXGEN_ERR_INVALID_ARG;
     HX_TRY(check_loaded(st));
-    if (st->dtype != HEXGEN_BF16 || st->last_decode_rows <= 0) return HEXGEN_ERR_STATE;
+    if (!is_h16(st->dtype) || st->last_decode_rows <= 0) return HEXGEN_ERR_STATE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     Workspace &w = st->ws;
     Rows r;
@@ -1147,7 +1151,7 @@ struct hexgen_head {
     void *w = nullptr;            // bf16: fragment tiles, k-tile-major [H/32][Vpad/16][64][8]; f32: [H][Vl]
     float *g = nullptr;           // final norm gain, fp32 [H]
     // workspace for one chunk of up to kDecodeMaxRows rows
-    bf16_t *xa = nullptr;         // bf16: (x * g) as compact hi/lo operand
+    h16_t *xa = nullptr;         // bf16: (x * g) as compact hi/lo operand
     float *ssq = nullptr;         // bf16: sums of squares per 16 columns
     float *x32 = nullptr, *n32 = nullptr;      // f32: x = a + b, normalised rows
     float *logits = nullptr;      // [rows][Vpad]
@@ -1168,9 +1172,9 @@ hexgen_status_t hexgen_head_create(int hidden, int vocab, int tp_degree, int tp_
     if (!out) return HEXGEN_ERR_INVALID_ARG;
     *out = nullptr;
     if (hidden <= 0 || vocab <= 0 || tp_degree <= 0 || !(rms_eps >= 0.f)) return HEXGEN_ERR_INVALID_ARG;
-    if (dtype != HEXGEN_F32 && dtype != HEXGEN_BF16) return HEXGEN_ERR_INVALID_ARG;
+    if (!known_dtype(dtype)) return HEXGEN_ERR_INVALID_ARG;
     if (tp_rank < 0 || tp_rank >= tp_degree || vocab % tp_degree) return HEXGEN_ERR_SHAPE;
-    if (dtype == HEXGEN_BF16 && hidden % 128) return HEXGEN_ERR_SHAPE;
+    if (is_h16(dtype) && hidden % 128) return HEXGEN_ERR_SHAPE;
     if (dtype == HEXGEN_F32 && hidden % 4) return HEXGEN_ERR_SHAPE;
     hexgen_head *hd = new (std::nothrow) hexgen_head();
     if (!hd) return HEXGEN_ERR_OOM;
@@ -1180,7 +1184,7 @@ hexgen_status_t hexgen_head_create(int hidden, int vocab, int tp_degree, int tp_
     const size_t rows = kDecodeMaxRows;
     hexgen_status_t rc = dmalloc(&hd->g, (size_t)hidden);
     if (rc == HEXGEN_OK) rc = dmalloc(&hd->logits, rows * hd->Vpad);
-    if (rc == HEXGEN_OK && dtype == HEXGEN_BF16) {
+    if (rc == HEXGEN_OK && is_h16(dtype)) {
         rc = dmalloc(&hd->xa, 2 * rows * hidden);
         if (rc == HEXGEN_OK) rc = dmalloc(&hd->ssq, (size_t)(hidden / 16) * DEC_SSQ_STRIDE);
         hd->scratch_floats = rows * ((size_t)512 * 128 + 2 * (size_t)hd->Vpad);
@@ -1215,7 +1219,7 @@ hexgen_status_t hexgen_head_load(hexgen_head_t *hd, const void *g_final, const v
                            (size_t)hd->Vl * es, H, hipMemcpyDefault));
     } else {
         // gain -> fp32; the rank's columns -> a dense zero-padded device matrix -> MFMA fragment tiles
-        bf16_t *tmp = nullptr;
+        h16_t *tmp = nullptr;
         HX_TRY(dmalloc(&tmp, (size_t)H * hd->Vpad + H));
         hipError_t e = hipMemset(tmp, 0, ((size_t)H * hd->Vpad + H) * es);
         if (e == hipSuccess) e = hipMemcpy(tmp + (size_t)H * hd->Vpad, g_final, (size_t)H * es, hipMemcpyDefault);
@@ -1224,8 +1228,8 @@ hexgen_status_t hexgen_head_load(hexgen_head_t *hd, const void *g_final, const v
                             (size_t)hd->Vl * es, H, hipMemcpyDefault);
         if (e == hipSuccess) e = hipMalloc(&hd->w, (size_t)H * hd->Vpad * es);
         if (e == hipSuccess) {
-            launch_cvt_bf16_to_f32(tmp + (size_t)H * hd->Vpad, hd->g, H, nullptr);
-            launch_pack_weight(tmp, hd->Vpad, 0, 0, H, hd->Vpad, static_cast<bf16_t *>(hd->w), 0, 1, hd->Vpad / 16, 0, nullptr);
+            HX_K(hd->dtype, launch_cvt_h16_to_f32, tmp + (size_t)H * hd->Vpad, hd->g, H, nullptr);
+            launch_pack_weight(tmp, hd->Vpad, 0, 0, H, hd->Vpad, static_cast<h16_t *>(hd->w), 0, 1, hd->Vpad / 16, 0, nullptr);
             e = hipDeviceSynchronize();
         }
         (void)hipFree(tmp);
@@ -1247,10 +1251,10 @@ hexgen_status_t hexgen_head_greedy(hexgen_head_t *hd, const void *hidden_a, cons
         const char *a = static_cast<const char *>(hidden_a) + (size_t)r0 * H * es;
         const char *b = hidden_b ? static_cast<const char *>(hidden_b) + (size_t)r0 * H * es : nullptr;
         int64_t ld = hd->Vpad;
-        if (hd->dtype == HEXGEN_BF16) {
+        if (is_h16(hd->dtype)) {
             // same kernels as a decode projection: prologue (x = a + b, x * g as hi/lo operand, sums of squares),
             // weight-streaming projection with 1 / rms applied after the contraction, fp32 logits
-            launch_decode_prologue(a, b, 1, nullptr, hd->g, hd->xa, hd->ssq, n, H, nullptr, nullptr, 0, s);
+            HX_K(hd->dtype, launch_decode_prologue, a, b, 1, nullptr, hd->g, hd->xa, hd->ssq, n, H, nullptr, nullptr, 0, s);
             DecodeEpi e;
             std::memset(&e, 0, sizeof(e));
             e.mode = DEC_RAW;
@@ -1259,7 +1263,7 @@ hexgen_status_t hexgen_head_greedy(hexgen_head_t *hd, const void *hidden_a, cons
             e.norm_dim = H;
             e.eps = hd->eps;
             e.raw_out = hd->logits;
-            launch_decode_proj(static_cast<const bf16_t *>(hd->w), hd->xa, hd->Vpad, H, n, e, hd->scratch, hd->scratch_floats, s);
+            HX_K(hd->dtype, launch_decode_proj, static_cast<const h16_t *>(hd->w), hd->xa, hd->Vpad, H, n, e, hd->scratch, hd->scratch_floats, s);
         } else {
             HX_HIP(hipMemcpyAsync(hd->x32, a, (size_t)n * H * es, hipMemcpyDeviceToDevice, s));
             if (b) launch_accumulate_f32(hd->x32, reinterpret_cast<const float *>(b), (int64_t)n * H, s);
@@ -1276,7 +1280,7 @@ hexgen_status_t hexgen_head_greedy(hexgen_head_t *hd, const void *hidden_a, cons
 hexgen_status_t hexgen_embed_rows(const void *table, hexgen_dtype_t dtype, int hidden, int vocab, const int32_t *tokens,
                                   int n, void *rows_out, void *stream) {
     if (!table || !tokens || !rows_out || hidden <= 0 || vocab <= 0 || n < 0) return HEXGEN_ERR_INVALID_ARG;
-    if (dtype != HEXGEN_F32 && dtype != HEXGEN_BF16) return HEXGEN_ERR_INVALID_ARG;
+    if (!known_dtype(dtype)) return HEXGEN_ERR_INVALID_ARG;
     const int64_t row_bytes = (int64_t)hidden * (int64_t)esize(dtype);
     if (row_bytes % 4) return HEXGEN_ERR_SHAPE;
     launch_embed_rows(table, row_bytes, vocab, tokens, n, rows_out, static_cast<hipStream_t>(stream));
@@ -1284,7 +1288,10 @@ hexgen_status_t hexgen_embed_rows(const void *table, hexgen_dtype_t dtype, int h
     return HEXGEN_OK;
 }
 
-hexgen_status_t hexgen_set_gemm_tile(int code) { return set_gemm_tile(code) ? HEXGEN_OK : HEXGEN_ERR_INVALID_ARG; }
+hexgen_status_t hexgen_set_gemm_tile(int code) {
+    const bool a = bf16::set_gemm_tile(code), b = f16::set_gemm_tile(code);
+    return a && b ? HEXGEN_OK : HEXGEN_ERR_INVALID_ARG;
+}
 
 hexgen_status_t hexgen_stage_set_tap(hexgen_stage_t *st, int layer, void *h_dump) {
     if (!st || layer < 0 || layer >= st->L) return HEXGEN_ERR_INVALID_ARG;

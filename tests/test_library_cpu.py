@@ -56,6 +56,9 @@ def _create(*a):
     ((512, 8, 2, 1408, 0, 2, 0, 0), 1),      # no layers
     ((512, 8, 2, 1408, 2, 2, 0, 7), 1),      # unknown dtype
     ((1024, 8, 2, 1424, 2, 2, 0, 1), 2),     # bf16: local ffn 712 not a multiple of 32
+    ((8192, 64, 8, 28672, 8, 4, 1, 2), 0),   # fp16 stage
+    ((1024, 8, 2, 1424, 2, 2, 0, 2), 2),     # fp16: same alignment rules as bf16
+    ((512, 8, 2, 1408, 2, 2, 0, 3), 1),      # first code past the enum
 ])
 def test_stage_create_validation(args, status):
     assert _create(*args) == status
@@ -71,6 +74,19 @@ def test_null_and_range_arguments():
     assert hx.lib.hexgen_status_string(4) == b"capacity exceeded"
     assert hx.lib.hexgen_accumulate_f32(None, None, 4, None) == 1
     st.close()
+
+
+def test_fp16_workload_values_survive_the_storage_type():
+    """Inputs drawn for an fp16 stage are fp16 values already, so the oracle (float64) and the stage (fp16 storage)
+    start from identical numbers."""
+    import torch
+    from workloads import StageConfig, generate
+    cfg = StageConfig("f16_probe", "f16", 512, 8, 4, 1408, 1, 1, (0,), batch=2, seed=42)
+    for name, v in generate.layer_weights(cfg, 0).items():
+        assert torch.equal(v, v.to(torch.float16).to(torch.float32)), name
+    x = generate.hidden_rows(cfg, 7)
+    assert torch.equal(x, x.to(torch.float16).to(torch.float32))
+    assert hx.binding._dtype_code("f16") == hx.binding._dtype_code(torch.float16) == 2
 
 
 # ---- cost model (host functions of the library) against the oracle ------------------------------------------------

@@ -33,6 +33,8 @@ def round_to_dtype(x: torch.Tensor, dtype: str) -> torch.Tensor:
     """fp32 tensor whose values are exactly representable in `dtype`."""
     if dtype == "bf16":
         return x.to(torch.bfloat16).to(torch.float32)
+    if dtype == "f16":
+        return x.to(torch.float16).to(torch.float32)
     if dtype == "f32":
         return x.to(torch.float32)
     raise ValueError(dtype)

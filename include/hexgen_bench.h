@@ -61,6 +61,11 @@ hexgen_status_t hexgen_mfma_probe(int variant, void *sink, int iters, int blocks
  */
 hexgen_status_t hexgen_set_gemm_tile(int code);
 
+/* Measurement and test hook, process-wide: force the number of blocks one (sequence, kv head) pair's context is split
+ * over in the decode attention (1 = one block per pair, 2..8 = split with the last block merging) instead of the
+ * choice by batch and context lengths; 0 restores the default.  HEXGEN_ERR_INVALID_ARG outside 0..8. */
+hexgen_status_t hexgen_set_attn_split(int nsplit);
+
 #ifdef __cplusplus
 }
 #endif

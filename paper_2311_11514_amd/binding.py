@@ -50,6 +50,7 @@ SIGNATURES = {
     "hexgen_stream_read": (_i, [_vp, _vp, _i64, _i, _vp]),
     "hexgen_mfma_probe": (_i, [_i, _vp, _i, _i, _vp]),
     "hexgen_set_gemm_tile": (_i, [_i]),
+    "hexgen_set_attn_split": (_i, [_i]),
     "hexgen_embed_rows": (_i, [_vp, _i, _i, _i, _vp, _i, _vp, _vp]),
     "hexgen_head_create": (_i, [_i, _i, _i, _i, _i, C.c_float, C.POINTER(_vp)]),
     "hexgen_head_load": (_i, [_vp, _vp, _vp]),
@@ -477,6 +478,10 @@ def sched_repartition_layers(total_layers, stage_mem):
 
 def set_gemm_tile(code: int):
     _check(lib.hexgen_set_gemm_tile(code), "hexgen_set_gemm_tile")
+
+
+def set_attn_split(nsplit: int):
+    _check(lib.hexgen_set_attn_split(nsplit), "hexgen_set_attn_split")
 
 
 def mfma_probe(variant: int, sink: torch.Tensor, iters: int, blocks: int, stream=None):

@@ -120,6 +120,14 @@ __device__ inline void split_pack2(float a, float b, uint32_t &phi, uint32_t &pl
     plo = (uint32_t)al | ((uint32_t)bl << 16);
 }
 
+// Device-scope accesses for data that blocks of one launch hand to each other (the split attention's partials): stores
+// that go through to where every compute die of the GPU sees them -- complete, for the issuing lane, once its store
+// counter has drained -- and loads that read from there instead of a line the reader's own L2 may still hold.  Such
+// data is a few KB per block, so nothing is lost by not caching it, and no block needs a device-wide fence, which
+// writes the die's whole L2 back (about 0.8 us each, one after the other per die: more than the kernel itself once
+// a launch has a few hundred blocks).
+__device__ __forceinline__ void dev_store(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float dev_load(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ inline float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

@@ -154,7 +154,7 @@ __global__ __launch_bounds__(512) void attn_decode_split_kernel(const h16_t *__r
                                                                const int32_t *__restrict__ row_pos, int nsplit,
                                                                float *part_o, float *part_ml, unsigned int *arrived,
                                                                h16_t *__restrict__ o_act, float scale_log2e) {
-    constexpr int KT = D / 32, DT = D / 16, W = 8;
+    constexpr int KT = D / 32, DT = D / 16, W = 8, NT = 64 * W;
     __shared__ float s_m[W][16], s_l[W][16];
     __shared__ float s_o[W][16][D];
     __shared__ int s_last;
@@ -162,8 +162,12 @@ __global__ __launch_bounds__(512) void attn_decode_split_kernel(const h16_t *__r
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 15, g = lane >> 4;
     const int n_pos = row_pos[sq] + 1;
     const int n_t32 = (n_pos + 31) >> 5;
+    // tiles per block: the sequence's own even share; nb = blocks of this (sequence, kv head) that have tiles -- the
+    // others (short contexts in a ragged batch) leave at once and are never counted
     const int per = (n_t32 + nsplit - 1) / nsplit;
-    const int t0 = split * per, t1 = min(n_t32, t0 + per);
+    const int nb = min(nsplit, (n_t32 + per - 1) / per);
+    if (split >= nb) return;
+    const int t0 = split * per, t1 = (split == nb - 1) ? n_t32 : t0 + per;
     const int head = c * G + j;
     const bool hv = j < G;
 
@@ -237,11 +241,10 @@ __global__ __launch_bounds__(512) void attn_decode_split_kernel(const h16_t *__r
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<floatx4 *>(&s_o[wave][j][dt * 16 + 4 * g]) = oacc[dt];
     __syncthreads();
-    // the block's partial per query head: waves merged in wave order (a block with no tiles writes m = -inf, l = 0)
-    const int hh = (threadIdx.x * 4) / D, dd = (threadIdx.x * 4) % D;      // G * D / 4 <= 512 work items, one per thread
-    const bool item = threadIdx.x * 4 < G * D;
-    const size_t e0 = ((size_t)sq * hq_l + c * G + (item ? hh : 0)) * nsplit;
-    if (item) {
+    // the block's result per query head: waves merged in wave order
+    for (int idx = threadIdx.x * 4; idx < G * D; idx += NT * 4) {
+        const int hh = idx / D, dd = idx % D;
+        const size_t e = ((size_t)sq * hq_l + c * G + hh) * nsplit + split;
         float M = NEG_INF;
 #pragma unroll
         for (int w = 0; w < W; ++w) M = fmaxf(M, s_m[w][hh]);
@@ -254,31 +257,46 @@ __global__ __launch_bounds__(512) void attn_decode_split_kernel(const h16_t *__r
             L += s_l[w][hh] * wt;
             o += *reinterpret_cast<const floatx4 *>(&s_o[w][hh][dd]) * wt;
         }
-        *reinterpret_cast<floatx4 *>(part_o + (e0 + split) * D + dd) = o;
-        if (dd == 0) { part_ml[(e0 + split) * 2] = M; part_ml[(e0 + split) * 2 + 1] = L; }
-    }
-    __syncthreads();                       // the block's stores have been issued and waited for ...
-    if (threadIdx.x == 0) {
-        __threadfence();                   // ... one wave publishes them device-wide (the fence is cumulative) ...
-        const unsigned int before = atomicAdd(&arrived[sq * gridDim.y + c], 1u);       // ... before the block counts itself
-        s_last = before + 1 == (unsigned int)nsplit;
-        if (s_last) {
-            atomicExch(&arrived[sq * gridDim.y + c], 0u);      // all blocks have counted: ready for the next launch
-            __threadfence();               // read what the other blocks published, not a stale cached line
+        if (nb == 1) {          // the whole context was this block's: final result, as in the one-block kernel
+            const float inv = 1.0f / L;
+            uint2 ph, pl;
+            split_pack2(o[0] * inv, o[1] * inv, ph.x, pl.x);
+            split_pack2(o[2] * inv, o[3] * inv, ph.y, pl.y);
+            const size_t off = dec_act_offset(sq, (c * G + hh) * D + dd, (hq_l * D) >> 5, 0);
+            *reinterpret_cast<uint2 *>(o_act + off) = ph;
+            *reinterpret_cast<uint2 *>(o_act + off + 32) = pl;
+            continue;
         }
+        float *po = part_o + e * D + dd;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dev_store(po + r, o[r]);
+        if (dd == 0) { dev_store(part_ml + e * 2, M); dev_store(part_ml + e * 2 + 1, L); }
+    }
+    if (nb == 1) return;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this lane's device-scope stores have completed ...
+    __syncthreads();                                      // ... and so have every other lane's of the block ...
+    if (threadIdx.x == 0) {                               // ... before the block counts itself
+        const unsigned int before = __hip_atomic_fetch_add(&arrived[sq * gridDim.y + c], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = before + 1 == (unsigned int)nb;
+        // all blocks have counted: ready for the next launch
+        if (s_last) __hip_atomic_store(&arrived[sq * gridDim.y + c], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (!s_last) return;
-    if (item) {
+    for (int idx = threadIdx.x * 4; idx < G * D; idx += NT * 4) {
+        const int hh = idx / D, dd = idx % D;
+        const size_t e0 = ((size_t)sq * hq_l + c * G + hh) * nsplit;
         float M = NEG_INF;
-        for (int sp = 0; sp < nsplit; ++sp) M = fmaxf(M, __builtin_nontemporal_load(part_ml + (e0 + sp) * 2));
+        for (int sp = 0; sp < nb; ++sp) M = fmaxf(M, dev_load(part_ml + (e0 + sp) * 2));
         float L = 0.f;
         floatx4 o = {0.f, 0.f, 0.f, 0.f};
-        for (int sp = 0; sp < nsplit; ++sp) {
-            const float ms = __builtin_nontemporal_load(part_ml + (e0 + sp) * 2);
+        for (int sp = 0; sp < nb; ++sp) {
+            const float ms = dev_load(part_ml + (e0 + sp) * 2);
             const float wt = (ms == NEG_INF) ? 0.f : exp2f(ms - M);
-            L += __builtin_nontemporal_load(part_ml + (e0 + sp) * 2 + 1) * wt;
-            o += __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(part_o + (e0 + sp) * D + dd)) * wt;
+            L += dev_load(part_ml + (e0 + sp) * 2 + 1) * wt;
+            const float *po = part_o + (e0 + sp) * D + dd;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] += dev_load(po + r) * wt;
         }
         const float inv = 1.0f / L;
         uint2 ph, pl;

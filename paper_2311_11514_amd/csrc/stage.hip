@@ -32,7 +32,8 @@
 namespace {
 
 constexpr int kDecodeMaxRows = 32;      // rows handled by the weight-streaming decode kernels
-constexpr int kMaxAttnSplit = 32;
+constexpr int kMaxAttnSplit = 32;         // blocks per (sequence, kv head) the workspace has partials for
+constexpr int kStaticAttnSplit = 8;       // what pick_attn_split chooses at most, and what the static scratch is laid out for
 
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
@@ -361,18 +362,25 @@ void sublayer_prefill_h16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, int 
 }
 
 // ---- bf16 decode flow (T <= 32 rows): five kernels per layer, everything else fused into their tails ----
+int g_attn_split_forced = 0;      // measurement and test hook (hexgen_set_attn_split); 0 = choose
+
 int pick_attn_split(const hexgen_stage *st, const hexgen_kv_cache *kv, int batch) {
+    if (g_attn_split_forced > 0) return g_attn_split_forced;
     int mx = 0;
     for (int i = 0; i < batch; ++i) mx = std::max(mx, kv->lens[i] + 1);
     const int n_t32 = (mx + 31) / 32;
     // Enough (sequence, kv head) pairs to fill the chip, or a context short enough that one block's eight waves walk it
-    // in a few steps: one block per pair.  Otherwise the context is split: a block's time falls with the number of
-    // splits (one CU's load path delivers about 150 GB/s), while every block adds a device-scope fence whose cost
-    // grows with the number of blocks in the launch; the measured optimum sits near sqrt(4 tiles / pairs).
+    // in a few steps: one block per pair.  (Measured on a ragged batch of 32 x 8 pairs, contexts 240..4027: the launch
+    // ends 11 us after the same bytes in equal contexts would, but every way of cutting the long contexts -- evenly, or
+    // only those above the even share per CU -- costs more than that: a block's fixed part, query load and the merge of
+    // its waves, is about 7 us and a CU holds one 8-wave block at a time.)
+    // Otherwise every context is split evenly: a block's time falls with the number of splits (one CU's load path
+    // delivers about 150 GB/s), while every block adds its own tail (partials written through, the count, the merge);
+    // the measured optimum sits near sqrt(4 tiles / pairs).
     const int pairs = batch * st->hkv_l;
     if (pairs >= 32 || n_t32 <= 48) return 1;
     const int s = (int)std::lround(std::sqrt(4.0 * n_t32 / pairs));
-    return std::max(2, std::min({s, 8, (n_t32 + 7) / 8}));
+    return std::max(2, std::min({s, kStaticAttnSplit, (n_t32 + 7) / 8}));
 }
 
 DecodeEpi epi_base(hexgen_stage *st, int mode) {
@@ -549,7 +557,6 @@ void free_layer(Layer &l) {
 // ---- the allocation-free decode step: its whole workspace lives in one file-scope device array ------------------
 constexpr size_t kStaticScratchBytes = (size_t)HEXGEN_STATIC_SCRATCH_BYTES;
 constexpr int kStaticMaxDevices = 64;
-constexpr int kStaticAttnSplit = 8;          // pick_attn_split never returns more
 
 }  // namespace
 
@@ -1285,6 +1292,12 @@ hexgen_status_t hexgen_embed_rows(const void *table, hexgen_dtype_t dtype, int h
     if (row_bytes % 4) return HEXGEN_ERR_SHAPE;
     launch_embed_rows(table, row_bytes, vocab, tokens, n, rows_out, static_cast<hipStream_t>(stream));
     HX_HIP(hipGetLastError());
+    return HEXGEN_OK;
+}
+
+hexgen_status_t hexgen_set_attn_split(int nsplit) {
+    if (nsplit < 0 || nsplit > kStaticAttnSplit) return HEXGEN_ERR_INVALID_ARG;
+    g_attn_split_forced = nsplit;
     return HEXGEN_OK;
 }
 

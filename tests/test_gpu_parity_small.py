@@ -263,6 +263,44 @@ def test_bf16_decode_long_context_split_over_blocks(cfg, ctx):
         assert np.array_equal(p0, p1) and np.array_equal(h0, h1)
 
 
+@pytest.mark.parametrize("nsplit", [1, 2, 3, 5, 8])
+def test_bf16_decode_attention_with_a_forced_split(nsplit):
+    """Any split of the decode attention gives the same result to rounding: forced through the library's hook on a ragged
+    batch whose short sequences have fewer 32-position tiles than splits (their surplus blocks leave at once and must
+    not be waited for), on both the ordinary and the allocation-free entry point."""
+    import paper_2311_11514_amd as hx
+    cfg = MINI128
+    ctx = [70, 1, 33, 300, 31]
+    w = _weights(cfg)
+    rank = cfg.tp_ranks[0]
+    ora = make_oracle(cfg, rank, w)
+    st = make_gpu_stage(cfg, rank, w)
+    hx.set_attn_split(nsplit)
+    try:
+        for static in (False, True):
+            oc = ora.new_cache(len(ctx))
+            kv = st.kv_cache_create(len(ctx), 320)
+            for layer in range(cfg.n_layers):
+                for s, n in enumerate(ctx):
+                    k, v = generate.synthetic_kv(cfg, layer, s, n)
+                    oc.fill(layer, s, k, v)
+                    kv.fill(layer, s, k, v)
+            kv.set_lengths(ctx)
+            for step in range(3):
+                x = generate.hidden_rows(cfg, len(ctx), stream_id=1 + step)
+                p_ref, h_ref = ora.decode(oc, x)
+                xin = to_dev(x, cfg)
+                p, h = torch.empty_like(xin), torch.empty_like(xin)
+                (st.decode_static if static else st.decode)(kv, step, xin, p, h)
+                torch.cuda.synchronize()
+                assert row_rel_err(h.float().cpu().numpy(), h_ref) < TOL["bf16"]
+                assert row_rel_err(p.float().cpu().numpy(), p_ref) < TOL["bf16"]
+    finally:
+        hx.set_attn_split(0)
+    with pytest.raises(hx.HexgenError):
+        hx.set_attn_split(9)
+
+
 def test_run_to_run_determinism_bf16():
     cfg = MINI128
     w = _weights(cfg)

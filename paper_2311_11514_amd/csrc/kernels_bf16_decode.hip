@@ -561,15 +561,16 @@ template <int MODE, int UT>
 void launch_splitk(const h16_t *Wp, const h16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, float *scratch,
                    size_t scratch_floats, hipStream_t s, hipEvent_t mid) {
     const int n_tiles = N / 16, groups = (n_tiles + 7) / 8;
-    // Two blocks fit a CU (registers), 512 on the chip.  The number of splits (at most 8: the finishing kernel walks
-    // them one after the other; partials within the scratch) minimises rounds of blocks x chunks per block, the time
+    // Two blocks fit a CU (registers), 512 on the chip.  The number of splits (at most 8, or 16 for a matrix of fewer than 64
+    // feature groups: the finishing kernel walks them one after the other; partials within the scratch) minimises rounds of blocks x chunks per block, the time
     // of the launch in units of one chunk per block; on a tie the fewer splits (less partial-sum traffic) win.
     const int chunks = (k_tiles + SK_CH - 1) / SK_CH;
     const size_t part_floats = scratch_floats - 32;      // the last 32 floats of the scratch carry the rows' rstd
     float *rstd = scratch + part_floats;
     int splits = 1;
     long best = -1;
-    for (int c = 1; c <= std::min(8, chunks); ++c) {
+    const int cap = groups * 8 < 512 ? 16 : 8;      // a narrow matrix (TP8 QKV: 10 groups) fills more of the chip with 16
+    for (int c = 1; c <= std::min(cap, chunks); ++c) {
         if (c > 1 && (size_t)c * T * N > part_floats) break;
         const long cost = (long)((groups * c + 511) / 512) * ((chunks + c - 1) / c) * 16 + c;
         if (best < 0 || cost < best) { best = cost; splits = c; }

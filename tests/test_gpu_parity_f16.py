@@ -183,3 +183,40 @@ def test_f16_head_greedy_vocab_parallel(t, n_rows):
         decisive += int(np.sum(clear))
         assert np.array_equal(tok[clear], ids_ref[clear])
     assert decisive >= 0.8 * t * n_rows, "too many near-ties: the token comparison would be vacuous"
+
+
+def test_f16_full_width_shards_decode_and_prefill():
+    """The 70B shard shapes in fp16 at reduced depth (the oracle's cost is per layer): TP8 batch-16 decode from a
+    context of 2048 (split projections, 16 splits on the narrow QKV matrix, split attention) and a TP4 prompt batch of
+    4 x 512 rows (the large GEMM tiles), two layers each, every row compared."""
+    from tests.test_gpu_parity_full import build_both, install_context
+    from workloads import CONFIGS
+    cfg = CONFIGS["l70_tp8_decode"].scaled(dtype="f16", n_layers=2, name="f16_tp8")
+    st, ora = build_both(cfg, cfg.tp_ranks[0])
+    b, ctx = cfg.batch, cfg.kv_context
+    kv = st.kv_cache_create(b, ctx + 8)
+    oc = ora.new_cache(b)
+    install_context(cfg, kv, oc, range(b), ctx)
+    kv.set_lengths([ctx] * b)
+    for step in range(3):
+        x = generate.hidden_rows(cfg, b, stream_id=1 + step)
+        p_ref, h_ref = ora.decode(oc, x)
+        p, h = gpu_decode(st, kv, cfg, step, x)
+        check(f"f16 TP8 decode step {step} resid", h, h_ref, TOLF)
+        check(f"f16 TP8 decode step {step} partial", p, p_ref, TOLF)
+    del st, kv
+    cfg = CONFIGS["l70_tp4_prefill"].scaled(dtype="f16", n_layers=2, name="f16_tp4")
+    st, ora = build_both(cfg, cfg.tp_ranks[0])
+    lens = generate.prompt_lengths(cfg)
+    X = generate.hidden_rows(cfg, sum(lens))
+    kv = st.kv_cache_create(len(lens), max(lens) + 8)
+    oc = ora.new_cache(len(lens))
+    p_ref, h_ref = ora.prefill(oc, X, lens)
+    p, h = gpu_prefill(st, kv, cfg, X, lens)
+    check("f16 TP4 prefill resid", h, h_ref, TOLF)
+    check("f16 TP4 prefill partial", p, p_ref, TOLF)
+    x = generate.hidden_rows(cfg, len(lens), stream_id=1)
+    p_ref, h_ref = ora.decode(oc, x)
+    p, h = gpu_decode(st, kv, cfg, 0, x)
+    check("f16 TP4 decode after prefill resid", h, h_ref, TOLF)
+    check("f16 TP4 decode after prefill partial", p, p_ref, TOLF)

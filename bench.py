@@ -538,6 +538,28 @@ def calibrate_gemm(torch, hx):
             tf = flop * rate / 1e12
             print(f"  {T:6d}  {names[code]:36s} {tf:8.1f}  {tf / MFMA_PEAK_TFLOPS:6.3f}  {watts if watts is None else round(watts):>6}")
         del kv, h, out
+    st.close()
+    # The same comparison on the headline workload's own shape and over its own duration: the headline prefill keeps the
+    # matrix cores busy for many seconds, and what the part sustains at its power limit falls as it warms up.
+    print("sustained, 12 s each, 71102 rows (the headline workload's prompt batch), full-width FFN 8192 <-> 28672: TFLOP/s, fraction, W")
+    T = 71102
+    x = torch.randn(T, 8192, device="cuda", dtype=torch.bfloat16)
+    w = (torch.randn(57344, 8192, device="cuda") * 0.02).to(torch.bfloat16)
+    rate, watts = pm.run(torch, lambda: torch.nn.functional.linear(x, w), 12.0)
+    tf = 2.0 * T * 8192 * 57344 * rate / 1e12
+    print(f"  vendor bf16 GEMM, rows x 8192 x 57344 (W1/W3's shape, no epilogue)   {tf:8.1f}  {tf / MFMA_PEAK_TFLOPS:6.3f}  {watts if watts is None else round(watts):>6}")
+    del x, w
+    cfg = CONFIGS["l70_full"].scaled(n_layers=1)
+    st = hx.Stage(cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.ffn, 1, 1, 0, "bf16")
+    w = generate.layer_weights(cfg, 0, device="cuda")
+    st.load_layer(0, *[w[k] for k in generate.LAYER_TENSOR_ORDER])
+    del w
+    kv = st.kv_cache_create(1, T)
+    h = torch.randn(T, cfg.hidden, device="cuda", dtype=torch.float32)
+    out = torch.empty_like(h)
+    rate, watts = pm.run(torch, lambda: st.run_sublayer(kv, 0, 1, h, [T], 1, out), 12.0)
+    tf = 2.0 * T * cfg.hidden * 3 * cfg.ffn_l * rate / 1e12
+    print(f"  this library, FFN sub-layer (W1/W3 + SwiGLU, W2 + residual)           {tf:8.1f}  {tf / MFMA_PEAK_TFLOPS:6.3f}  {watts if watts is None else round(watts):>6}")
 
 
 def cpu_baseline(torch, be, nproc):

@@ -104,6 +104,10 @@ class Bench:
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / reps
         assert torch.isfinite(outp.float()).all() and torch.isfinite(outr.float()).all()
+        # the instrumented pass follows at least 0.2 s of the same work: after a pause the part takes some tens of
+        # milliseconds to reach the clocks it then sustains, and a short call measured right away reads 10 % slow
+        for _ in range(min(32, int(0.2 / dt)) if dt * (reps + warm) < 0.2 else 0):
+            st.prefill(self.kv, Xp, self.lens, outp, outr)
         st.profile_enable(0b11111)
         st.prefill(self.kv, Xp, self.lens, outp, outr)
         H, d = cfg.hidden, cfg.head_dim

@@ -347,9 +347,11 @@ void launch_attn_decode_rows(const h16_t *q, const h16_t *kc, const h16_t *vc, K
 }
 
 // -------------------------------------------------------------------------------------------------
-// Prefill: grid (ceil(max_new / (32 NWV)), hq_l, batch), NWV = 4 or 2 waves per block; a block owns 32 NWV query rows
-// of one head of one sequence, a wave 32 of them, and walks the cache in 32-position tiles up to its last row's position (causal:
-// later tiles are never touched).  Rows of the call sit at positions pos0[seq] + i.
+// Prefill: grid (G n_items, kv heads); a block of 4 waves owns 128 query rows of one head of one sequence, a wave 32 of
+// them, and walks the cache in 32-position tiles up to its last row's position (causal: later tiles are never
+// touched).  Rows of the call sit at positions pos0[seq] + i.  The (sequence, row block) pairs come from a work list
+// built on the host, longest walks first; the G query heads of a kv head run next to each other on one XCD, so the
+// blocks that walk the same K and V do so at the same time and share them in that XCD's L2.
 //
 // Everything runs on v_mfma_f32_32x32x16_bf16.  S^T (32 positions x 32 query rows) = K . Q^T: operand A is gathered
 // from the two 16-position K tiles, operand B is the wave's query block, held in registers for the whole walk.
@@ -370,6 +372,7 @@ __global__ __launch_bounds__(64 * NWV, 2) void attn_prefill_kernel(const h16_t *
                                                              const h16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
                                                              const int32_t *__restrict__ cu_rows,
                                                              const int32_t *__restrict__ pos0,
+                                                             const int32_t *__restrict__ items, int n_items,
                                                              h16_t *__restrict__ o_packed, float scale_log2e) {
     constexpr int KT = D / 32, DT = D / 16, DB = D / 32;     // K d-tiles, V^T d-tiles, 32-wide output blocks
     constexpr int TILES = 2 * KT + DT;                       // 1 KB tiles per 32-position step: K then V^T
@@ -378,8 +381,12 @@ __global__ __launch_bounds__(64 * NWV, 2) void attn_prefill_kernel(const h16_t *
     constexpr int S = 3;
     static_assert(TILES % NWV == 0, "tiles must divide over the waves");
     __shared__ h16x8 smem[S][TILES][64];
-    const int seq = blockIdx.z, head = blockIdx.y;
-    const int rb = gridDim.x - 1 - blockIdx.x;               // longest walks first
+    // Consecutive block ids are dealt to the 8 XCDs in turn, each with its own L2: block id = 8 slot + xcd.  An XCD takes
+    // every eighth item, and the G heads of an item occupy consecutive slots of that XCD.
+    const int slot = blockIdx.x >> 3, xcd = blockIdx.x & 7;
+    const int item = (slot / G) * 8 + xcd, c = blockIdx.y, head = c * G + slot % G;
+    if (item >= n_items) return;                             // the whole block leaves
+    const int seq = items[2 * item], rb = items[2 * item + 1];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int row0 = cu_rows[seq], n_new = cu_rows[seq + 1] - row0, p0s = pos0[seq];
     if (rb * ROWS >= n_new) return;                          // the whole block leaves
@@ -391,7 +398,6 @@ __global__ __launch_bounds__(64 * NWV, 2) void attn_prefill_kernel(const h16_t *
     const int nt = ((p0s + min(rb * ROWS + ROWS - 1, n_new - 1)) >> 5) + 1;                      // steps of the block
     const int nt_w = qbase < n_new ? ((p0s + min(qbase + 31, n_new - 1)) >> 5) + 1 : 0;    // steps this wave computes
     const int first_masked = (p0s + qbase) >> 5;             // tiles before it lie wholly in every row's past
-    const int c = head / G;
 
     // 32x32x16 operand gather from a pair of 16-row fragment tiles: lane l takes row l % 32, k-group 2 kh + l / 32
     const int sub = (lane & 31) >> 4;                        // which tile of the pair
@@ -511,27 +517,18 @@ __global__ __launch_bounds__(64 * NWV, 2) void attn_prefill_kernel(const h16_t *
 }
 
 void launch_attn_prefill(const h16_t *q, const h16_t *kc, const h16_t *vc, KvGeom kg, int hq_l,
-                         const int32_t *cu_rows, const int32_t *pos0, int batch, int max_new, h16_t *o_packed,
+                         const int32_t *cu_rows, const int32_t *pos0, const int32_t *items, int n_items, h16_t *o_packed,
                          hipStream_t s) {
-    if (batch <= 0 || max_new <= 0) return;
+    if (n_items <= 0) return;
     const int G = hq_l / kg.hkv_l;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)kg.d);
-    // 128-row blocks (4 waves) share each K/V tile among more rows; 64-row blocks (2 waves) when those would leave
-    // the chip with fewer than two blocks per CU
-    const long blocks128 = (long)((max_new + 127) / 128) * hq_l * batch;
-    const bool small = false && blocks128 < 512;
-    dim3 grid(small ? (max_new + 63) / 64 : (max_new + 127) / 128, hq_l, batch);
-#define HX_A(DD, NW)                                                                                              \
-    hipLaunchKernelGGL((attn_prefill_kernel<DD, NW>), grid, dim3(64 * NW), 0, s, q, kc, vc, kg, hq_l, G, cu_rows, pos0, \
-                       o_packed, scale_log2e)
-    if (kg.d == 128) {
-        if (small) HX_A(128, 2);
-        else HX_A(128, 4);
-    } else {
-        if (small) HX_A(64, 2);
-        else HX_A(64, 4);
-    }
-#undef HX_A
+    dim3 grid((unsigned)G * ((n_items + 7) / 8 * 8), kg.hkv_l);
+    if (kg.d == 128)
+        hipLaunchKernelGGL((attn_prefill_kernel<128, 4>), grid, dim3(256), 0, s, q, kc, vc, kg, hq_l, G, cu_rows, pos0, items,
+                           n_items, o_packed, scale_log2e);
+    else
+        hipLaunchKernelGGL((attn_prefill_kernel<64, 4>), grid, dim3(256), 0, s, q, kc, vc, kg, hq_l, G, cu_rows, pos0, items,
+                           n_items, o_packed, scale_log2e);
 }
 
 }  // namespace HX_NS

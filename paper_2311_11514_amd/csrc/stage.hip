@@ -32,6 +32,7 @@
 namespace {
 
 constexpr int kDecodeMaxRows = 32;      // rows handled by the weight-streaming decode kernels
+constexpr int kAttnRows = 128;            // new rows per block of the prefill attention (4 waves x 32)
 constexpr int kMaxAttnSplit = 32;         // blocks per (sequence, kv head) the workspace has partials for
 constexpr int kStaticAttnSplit = 8;       // what pick_attn_split chooses at most, and what the static scratch is laid out for
 
@@ -85,6 +86,7 @@ struct Workspace {
     // row bookkeeping
     int32_t *rowmap = nullptr;       // one block: row_seq | row_pos | cu_rows | pos0, packed by the sizes of the call
     int32_t *row_seq = nullptr, *row_pos = nullptr, *cu_rows = nullptr, *pos0 = nullptr;   // views into rowmap
+    int32_t *items = nullptr;        // view into rowmap: the prefill attention's work list, (sequence, 128-row block) pairs
     int32_t *host_stage = nullptr;   // pinned staging for the arrays above
     int host_stage_cap = 0;
 };
@@ -195,8 +197,9 @@ hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
         HX_TRY(dmalloc(&w.o32, T * st->qw));
         HX_TRY(dmalloc(&w.u32, T * st->F_l));
     }
-    HX_TRY(dmalloc(&w.rowmap, 2 * T + 2 * (size_t)batch + 1));
-    w.host_stage_cap = 2 * rows + 3 * batch + 1;     // row_seq, row_pos, cu_rows, pos0, new lengths
+    // row_seq, row_pos, cu_rows, pos0, new lengths, attention work list (at most rows / 128 + batch pairs)
+    w.host_stage_cap = 2 * rows + 3 * batch + 1 + 2 * (rows / kAttnRows + batch);
+    HX_TRY(dmalloc(&w.rowmap, (size_t)w.host_stage_cap));
     HX_HIP(hipHostMalloc(reinterpret_cast<void **>(&w.host_stage), (size_t)w.host_stage_cap * sizeof(int32_t),
                          hipHostMallocDefault));
     w.cap_rows = rows;
@@ -208,7 +211,7 @@ hexgen_status_t ensure_workspace(hexgen_stage *st, int rows, int batch) {
 }
 
 struct Rows {
-    int T = 0, batch = 0, max_new = 0;
+    int T = 0, batch = 0, max_new = 0, n_items = 0;
     bool decode = false;
     RowMap rm{};
 };
@@ -256,9 +259,32 @@ hexgen_status_t setup_rows(hexgen_stage *st, hexgen_kv_cache *kv, const int32_t 
             for (int jn = 0; jn < n; ++jn, ++row) { h_seq[row] = i; h_pos[row] = kv->lens[i] + jn; }
         }
         h_cu[batch] = row;
-        // host staging and device block share one packing: a single copy moves all four arrays
-        HX_HIP(hipMemcpyAsync(w.rowmap, hs, sizeof(int32_t) * (2 * (size_t)r.T + 2 * (size_t)batch + 1),
-                              hipMemcpyHostToDevice, s));
+        // The prefill attention's work list: one entry per (sequence, block of 128 new rows), the longest walks over
+        // the cache first.  A ragged batch thus launches no empty blocks (a grid over the longest prompt's blocks
+        // would: 45 % of it at lengths 128..4096) and its long walks do not end up alone at the tail of the launch.
+        const size_t items_off = 2 * (size_t)r.T + 3 * (size_t)batch + 1;
+        int32_t *h_items = hs + items_off;
+        std::vector<std::pair<int, int>> order;         // (-last position of the block, index)
+        int n_items = 0;
+        for (int i = 0; i < batch; ++i) {
+            const int n = seq_lens ? seq_lens[i] : 1;
+            for (int rb = 0; rb * kAttnRows < n; ++rb, ++n_items) {
+                h_items[2 * n_items] = i;
+                h_items[2 * n_items + 1] = rb;
+                order.emplace_back(-(kv->lens[i] + std::min((rb + 1) * kAttnRows, n)), n_items);
+            }
+        }
+        std::stable_sort(order.begin(), order.end());
+        std::vector<int32_t> sorted(2 * (size_t)n_items);
+        for (int k = 0; k < n_items; ++k) {
+            sorted[2 * k] = h_items[2 * order[k].second];
+            sorted[2 * k + 1] = h_items[2 * order[k].second + 1];
+        }
+        std::copy(sorted.begin(), sorted.end(), h_items);
+        r.n_items = n_items;
+        w.items = w.rowmap + items_off;
+        // host staging and device block share one packing: a single copy moves all the arrays
+        HX_HIP(hipMemcpyAsync(w.rowmap, hs, sizeof(int32_t) * (items_off + 2 * (size_t)n_items), hipMemcpyHostToDevice, s));
     }
     *out = r;
     return HEXGEN_OK;
@@ -310,7 +336,7 @@ void attn_prefill_h16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Ro
     if (r.max_new == 1 && st->hq_l / st->hkv_l <= 16)
         HX_K(st->dtype, launch_attn_decode_rows, w.q, kc, vc, kg, st->hq_l, w.pos0, r.batch, w.o, s);
     else
-        HX_K(st->dtype, launch_attn_prefill, w.q, kc, vc, kg, st->hq_l, w.cu_rows, w.pos0, r.batch, r.max_new, w.o, s);
+        HX_K(st->dtype, launch_attn_prefill, w.q, kc, vc, kg, st->hq_l, w.cu_rows, w.pos0, w.items, r.n_items, w.o, s);
     st->prof.mark(PROF_ATTN, s);
 }
 

@@ -463,6 +463,13 @@ def calibrate(torch, hx):
         us = timed(lambda i: hx.mfma_probe(v, sink, iters, blocks), 1)
         tf = blocks * 4 * iters * (1 << 20) / us / 1e6
         print(f"  {name:58s} {tf:8.1f} {tf / 2516.6:6.3f}")
+    names2 = {8: "results in accumulation registers, row by row", 9: "results in vector registers, row by row",
+              10: "results in accumulation registers, serpentine", 11: "results in vector registers, serpentine"}
+    for v in (8, 9, 10, 11, 8, 9):
+        iters = 100000
+        us = timed(lambda i: hx.mfma_probe(v, sink, iters, blocks), 1)
+        tf = blocks * 4 * iters * (1 << 20) / us / 1e6
+        print(f"  16x16x32, random bits, 128 result registers: {names2[v]:46s} {tf:8.1f} {tf / 2516.6:6.3f}")
 
 
 class _PowerMeter:

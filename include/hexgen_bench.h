@@ -45,7 +45,10 @@ hexgen_status_t hexgen_stream_read(const void *src, void *sink, int64_t bytes, i
  * registers (2^20 flop per wave and iteration).  variant 0: 16x16x32 bf16 MFMA, 1: 32x32x16 bf16 MFMA, 2 / 3: the
  * same plus the LDS fragment reads a GEMM issues; 4 .. 7: variants 0 .. 3 on operands with random signs and
  * mantissas instead of 1.0 (the power the matrix cores draw, and with it the clock the chip holds, depends on the
- * operand bits; run tens of milliseconds for a steady figure).  `sink`: device, >= 256 floats.  Time it with events.
+ * operand bits; run tens of milliseconds for a steady figure).  8 .. 11: 16x16x32 on random bits with 128 result
+ * registers per wave (a 64 x 128 wave tile, as the two-phase GEMM loop holds): results in accumulation registers (8, 10)
+ * or in ordinary vector registers (9, 11), issued row by row (8, 9) or in a serpentine that changes one operand per
+ * instruction (10, 11).  `sink`: device, >= 256 floats.  Time it with events.
  */
 hexgen_status_t hexgen_mfma_probe(int variant, void *sink, int iters, int blocks, void *stream);
 

@@ -264,7 +264,64 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *sink, int iters)
     }
     if (total == 123.456f) sink[threadIdx.x] = total;      // practically never: keeps the math alive
 }
+// Variants 8..11: v_mfma_f32_16x16x32_bf16 on random operand bits with the 128 accumulator registers per wave that the
+// two-phase GEMM loop holds (4 x 8 results), in accumulation registers (8, 10) or in ordinary vector registers (9, 11),
+// issued row by row (8, 9) or in a serpentine that changes only one operand from one instruction to the next (10, 11):
+// whether register class or operand order moves the energy per flop.
+template <bool VACC, bool SNAKE>
+__global__ __launch_bounds__(256) void mfma_probe2_kernel(float *sink, int iters) {
+    __shared__ h16x8 sm[32][64];
+    const int lane = threadIdx.x & 63;
+    for (int i = threadIdx.x; i < 32 * 64; i += 256) {
+        uint32_t h = (uint32_t)i * 2654435761u + blockIdx.x * 40503u;
+        uint32_t w[4];
+        for (int c = 0; c < 4; ++c) {
+            h = h * 1664525u + 1013904223u;
+            w[c] = (h & 0x807f807fu) | 0x3f003f00u;
+        }
+        sm[i >> 6][i & 63] = *reinterpret_cast<const h16x8 *>(w);
+    }
+    __syncthreads();
+    floatx4 acc[4][8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    h16x8 a[4], b[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] = sm[i][lane];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) b[j] = sm[8 + j][lane];
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int rep = 0; rep < 2; ++rep)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) {
+                    const int j = (SNAKE && (i & 1)) ? 7 - jj : jj;
+                    if (VACC) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc[i][j]) : "v"(a[i]), "v"(b[j]));
+                    else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(a[i]), "v"(b[j]));
+                }
+    }
+    float total = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) total += acc[i][j][0] + acc[i][j][3];
+    if (total == 123.456f) sink[threadIdx.x] = total;
+}
+
 void launch_mfma_probe(int variant, float *sink, int iters, int blocks, hipStream_t s) {
+    if (variant >= 8 && variant <= 11) {       // per k-step: 64 MFMAs of 16384 flop = 2^20 flop per wave, as in the variants above
+        switch (variant) {
+            case 8: hipLaunchKernelGGL((mfma_probe2_kernel<false, false>), dim3(blocks), dim3(256), 0, s, sink, iters); break;
+            case 9: hipLaunchKernelGGL((mfma_probe2_kernel<true, false>), dim3(blocks), dim3(256), 0, s, sink, iters); break;
+            case 10: hipLaunchKernelGGL((mfma_probe2_kernel<false, true>), dim3(blocks), dim3(256), 0, s, sink, iters); break;
+            default: hipLaunchKernelGGL((mfma_probe2_kernel<true, true>), dim3(blocks), dim3(256), 0, s, sink, iters); break;
+        }
+        return;
+    }
 #define HX_P(V, R) hipLaunchKernelGGL((mfma_probe_kernel<V, R>), dim3(blocks), dim3(256), 0, s, sink, iters)
     switch (variant) {
         case 0: HX_P(0, false); break;

@@ -1170,7 +1170,7 @@ hexgen_status_t hexgen_stream_read(const void *src, void *sink, int64_t bytes, i
 }
 
 hexgen_status_t hexgen_mfma_probe(int variant, void *sink, int iters, int blocks, void *stream) {
-    if (!sink || variant < 0 || variant > 7 || iters <= 0 || blocks <= 0) return HEXGEN_ERR_INVALID_ARG;
+    if (!sink || variant < 0 || variant > 11 || iters <= 0 || blocks <= 0) return HEXGEN_ERR_INVALID_ARG;
     launch_mfma_probe(variant, static_cast<float *>(sink), iters, blocks, static_cast<hipStream_t>(stream));
     return HEXGEN_OK;
 }

@@ -421,10 +421,28 @@ def cost_model_alignment(torch, hx, CONFIGS, summary):
     dec = hx.cost_comp(dc.hidden, 2, dc.batch, 0, 1, dc.n_layers, [m_d] * dc.tp_degree, [c_d] * dc.tp_degree, 12.75, "decode")
     est = hx.cost_comp(pc.hidden, 2, pc.batch, pc.prompt_len, 0, pc.n_layers, [m_d] * pc.tp_degree, [c_d] * pc.tp_degree,
                        12.75, "prefill")
+    # the same two columns for every workload of the run: where the two-parameter model holds (weight-streaming decode of
+    # large shards, long prefills) and where it does not (small shards: launch-bound; ragged long prompts: attention)
+    table = []
+    for name, entry in summary.items():
+        c = CONFIGS[name]
+        m, cc = [m_d] * c.tp_degree, [c_d] * c.tp_degree
+        if "decode" in entry:
+            e = hx.cost_comp(c.hidden, 2, entry["decode"]["batch"], 0, 1, c.n_layers, m, cc, 12.75, "decode")
+            table.append({"workload": name, "phase": "decode step", "estimated_ms": round(e * 1e3, 4),
+                          "measured_ms": entry["decode"]["ms_per_step"],
+                          "measured_over_estimated": round(entry["decode"]["ms_per_step"] / (e * 1e3), 3)})
+        if "prefill" in entry:
+            pr = entry["prefill"]
+            e = hx.cost_comp(c.hidden, 2, pr["sequences"], int(round(pr["rows"] / pr["sequences"])), 0, c.n_layers, m, cc,
+                             12.75, "prefill")
+            table.append({"workload": name, "phase": "prefill call", "estimated_ms": round(e * 1e3, 3),
+                          "measured_ms": pr["ms_per_call"], "measured_over_estimated": round(pr["ms_per_call"] / (e * 1e3), 3)})
     return {"m_d_GBps": round(m_d / 1e9, 1), "c_d_TFLOPs": round(c_d / 1e12, 1),
             "decode_ms_per_token": {"estimated": round(dec * 1e3, 4),
                                     "measured": summary["l70_tp2_decode"]["decode"]["ms_per_step"]},
-            "prefill_ms_per_call": {"estimated": round(est * 1e3, 3), "measured": pre["ms_per_call"]}}
+            "prefill_ms_per_call": {"estimated": round(est * 1e3, 3), "measured": pre["ms_per_call"]},
+            "table": table}
 
 
 def calibrate(torch, hx):

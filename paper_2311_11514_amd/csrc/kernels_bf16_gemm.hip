@@ -746,6 +746,29 @@ bool set_gemm_tile(int code) {
     return false;
 }
 
+// Estimated time in microseconds of one projection with block tiles of tm features x tt tokens (both multiples of 16),
+// `step_us` per 32-deep k-step of a block; constants fitted to this chip (TP4-shaped projections at 128 .. 2048 rows):
+//   * a block walks its k-steps and pays a fixed 11 us (pipeline fill, epilogue; 15 more when the epilogue is the
+//     residual read-modify-write); the chip holds 256 such blocks at once (their LDS fills a CU), and a launch takes
+//     whole rounds of them;
+//   * launch_cfg splits the contraction when the tiles fill less than half of the chip: the partial sums are written
+//     (about 5 TB/s) and a finishing pass reads them back (about 2.5 TB/s) behind a second launch.
+static double gemm_estimate_us(int tm, int tt, double step_us, int n_tiles, int t_tiles, int k_tiles, bool resid, bool can_split) {
+    const int resident = 256;
+    const long total = (long)((n_tiles * 16 + tm - 1) / tm) * ((t_tiles * 16 + tt - 1) / tt);
+    int splits = 1;
+    if (can_split && 2 * total <= resident && k_tiles >= 32)
+        splits = (int)std::max<long>(1, std::min<long>({8, resident / total, k_tiles / 16}));
+    const long rounds = (total * splits + resident - 1) / resident;
+    const double ksteps = (double)((k_tiles + splits - 1) / splits);
+    double us = rounds * (ksteps * step_us + 11.0 + (resid && splits == 1 ? 15.0 : 0.0));
+    if (splits > 1) {
+        const double part_mb = (double)splits * total * tm * tt * 4.0 / 1e6;
+        us += part_mb / 5.0 + 8.0 + part_mb / 2.5 + (resid ? 15.0 : 0.0);
+    }
+    return us;
+}
+
 // one 128-token tile, at least 32 k-tiles: skinny kernel + finishing pass; returns false when it does not apply
 template <int MODE>
 static bool launch_skinny(const h16_t *Wp, const h16_t *Xp, int N, int k_tiles, int n_tiles, int t_tiles, int T,
@@ -769,20 +792,13 @@ static void launch_mode(const h16_t *Wp, const h16_t *Xp, int N, int K, int T, c
                         size_t part_floats, hipStream_t s) {
     const int k_tiles = K / 32, n_tiles = N / 16, t_tiles = (T + 15) / 16;
     const int force = g_force_tile.load(std::memory_order_relaxed);
-    // tiles of 256 x 256 once they fill the chip; 128 features x 256 tokens for smaller problems
-    const long big = (long)((n_tiles + 15) / 16) * ((t_tiles + 15) / 16);
-    // 198 = 256 x 256 on 8 waves with the two waves of a SIMD half a k-step out of phase (98: the same tile, lock-stepped)
-    int cfg = big >= 200 ? 198 : 94;      // (128 x 256 also beats 128 x 128 on the few-tile launches that split)
-    if (cfg == 94 && part != nullptr && k_tiles >= 32) {
-        // 128 x 256 tiles that neither fill the chip nor are few enough to split (129 .. 223 blocks): 256 x 256 tiles
-        // with a split contraction instead, when that fills it (QKV of the TP4 shard at 2048 rows: 3 x 80 blocks
-        // instead of 160; measured 8 % faster including the finishing pass)
-        const long t94 = (long)((n_tiles + 7) / 8) * ((t_tiles + 15) / 16);
-        if (t94 > 128 && t94 < 224 && 2 * big <= 256) {
-            const long sp = std::min<long>({8, 256 / big, k_tiles / 16});
-            if (big * sp >= 230) cfg = 198;
-        }
-    }
+    // 198 = 256 x 256 on 8 waves with the two waves of a SIMD half a k-step out of phase; the smaller tile is 128 x 256
+    // (94), or 256 x 128 (84) for the residual epilogue.  Which one: the shorter of two estimates (gemm_estimate_us),
+    // i.e. rounds of blocks over the chip x a block's time, plus what a split contraction costs in partial sums.
+    const bool resid = MODE == DEC_RESID;
+    const double t198 = gemm_estimate_us(256, 256, 0.55, n_tiles, t_tiles, k_tiles, resid, part != nullptr);
+    const double tsml = gemm_estimate_us(resid ? 256 : 128, resid ? 128 : 256, 0.40, n_tiles, t_tiles, k_tiles, resid, part != nullptr);
+    int cfg = t198 <= tsml ? 198 : 94;
     if (force) cfg = force;
     // the RESID epilogue emits one sum-of-squares partial per wave: its 32 FM features must be 128
     if (MODE == DEC_RESID && cfg != 88 && cfg != 84 && cfg != 98 && cfg % 1000 != 198) cfg = cfg == 72 ? 198 : 84;

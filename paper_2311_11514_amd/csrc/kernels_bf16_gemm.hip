@@ -273,7 +273,7 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const h16_t *__
                                                                  const h16_t *__restrict__ Xp, int N, int k_tiles,
                                                                  int n_tiles, int t_tiles, int T, int n_blocks,
                                                                  int t_blocks, GemmEpi e, float *__restrict__ part,
-                                                                 int pm_h, int pt_w) {
+                                                                 int pm_h, int pt_w, int nb0) {
     constexpr int NW = WM * WT, NT = 64 * NW;
     constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT;   // 16-row operand tiles per block and k-step
     constexpr int LA = TA / NW, LB = TB / NW;         // direct-to-LDS loads per wave and stage, per operand
@@ -293,6 +293,7 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const h16_t *__
     // blocks: per k-step the patch fetches (pm_h + pt_w) operand slices into that XCD's L2 for pm_h x pt_w tiles.
     int bm, bt;
     gemm_tile_of_id(id, n_blocks, t_blocks, pm_h, pt_w, bm, bt);
+    bm += nb0;               // the launch covers feature blocks nb0 .. nb0 + n_blocks - 1 of the matrix
     // the wave index is made provably uniform: tile addresses and LDS destinations then stay in scalar registers
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int wm = wave % WM, wt = wave / WM;
@@ -559,13 +560,14 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const h16_t *__
 template <int FM, int FT, int WM, int WT, int MODE>
 __global__ __launch_bounds__(64 * WM * WT) void gemm_finish_kernel(const float *__restrict__ part, int splits, int N,
                                                                    int n_tiles, int T, int total, int t_blocks, GemmEpi e,
-                                                                   int pm_h, int pt_w) {
+                                                                   int pm_h, int pt_w, int nb0) {
     constexpr int NW = WM * WT, NT = 64 * NW, TB = 2 * FT * WT, NTOK = TB * 16;
     __shared__ float rstd_s[NTOK];
     __shared__ float ssq_lds[(MODE == DEC_RESID && 32 * FM != GEMM_SSQ_COLS) ? WM * NTOK : 1];
     const int id = blockIdx.x;
     int bm, bt;
     gemm_tile_of_id(id, total / t_blocks, t_blocks, pm_h, pt_w, bm, bt);      // as in the pass that wrote the partials
+    bm += nb0;
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int wm = wave % WM, wt = wave / WM;
     if (MODE != DEC_RESID && e.ssq_in != nullptr) {
@@ -707,9 +709,10 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t *__restric
 
 template <int FM, int FT, int WM, int WT, int S, int MODE, bool PP = false, int ABL = 0>
 static void launch_cfg(const h16_t *Wp, const h16_t *Xp, int N, int k_tiles, int n_tiles, int t_tiles, int T,
-                       const GemmEpi &e, float *part, size_t part_floats, hipStream_t s) {
+                       const GemmEpi &e, float *part, size_t part_floats, hipStream_t s, int nb0 = 0, int nb_count = -1) {
     constexpr int TA = 2 * FM * WM, TB = 2 * FT * WT;
-    const int n_blocks = (n_tiles + TA - 1) / TA, t_blocks = (t_tiles + TB - 1) / TB;
+    // feature blocks nb0 .. nb0 + nb_count - 1 of the matrix (all of them by default)
+    const int n_blocks = nb_count >= 0 ? nb_count : (n_tiles + TA - 1) / TA, t_blocks = (t_tiles + TB - 1) / TB;
     const int total = n_blocks * t_blocks;
     const int grid = (total + 7) / 8 * 8;
     auto kern = gemm_mfma_kernel<FM, FT, WM, WT, S, MODE, PP, ABL>;
@@ -732,10 +735,10 @@ static void launch_cfg(const h16_t *Wp, const h16_t *Xp, int N, int k_tiles, int
         while (splits > 1 && (size_t)splits * total * tile_floats > part_floats) --splits;
     }
     hipLaunchKernelGGL(kern, dim3(grid, splits), dim3(64 * WM * WT), dyn, s, Wp, Xp, N, k_tiles, n_tiles, t_tiles, T,
-                       n_blocks, t_blocks, e, splits > 1 ? part : nullptr, pm_h, std::min(pt_w, t_blocks));
+                       n_blocks, t_blocks, e, splits > 1 ? part : nullptr, pm_h, std::min(pt_w, t_blocks), nb0);
     if (splits > 1)
         hipLaunchKernelGGL((gemm_finish_kernel<FM, FT, WM, WT, MODE>), dim3(total), dim3(64 * WM * WT), 0, s, part, splits, N,
-                           n_tiles, T, total, t_blocks, e, pm_h, std::min(pt_w, t_blocks));
+                           n_tiles, T, total, t_blocks, e, pm_h, std::min(pt_w, t_blocks), nb0);
 }
 
 // tile configuration forced for every GEMM launch of the process (0 = choose by shape); a measurement and test hook
@@ -783,7 +786,7 @@ static bool launch_skinny(const h16_t *Wp, const h16_t *Xp, int N, int k_tiles, 
     hipLaunchKernelGGL(gemm_skinny_kernel, dim3(n_blocks, splits), dim3(256), 0, s, Wp, Xp, k_tiles, n_tiles, t_tiles,
                        n_blocks, part);
     hipLaunchKernelGGL((gemm_finish_kernel<1, 1, 4, 1, MODE>), dim3(n_blocks * 4), dim3(256), 0, s, part, splits, N, n_tiles,
-                       T, n_blocks * 4, 4, e, 1, 4);
+                       T, n_blocks * 4, 4, e, 1, 4, 0);
     return true;
 }
 
@@ -810,7 +813,23 @@ static void launch_mode(const h16_t *Wp, const h16_t *Xp, int N, int K, int T, c
 #define HX_G(FM, FT, WM, WT, S) launch_cfg<FM, FT, WM, WT, S, MODE>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s)
     if (cfg == 88) HX_G(4, 4, 2, 2, 4);
     else if (cfg == 98) HX_G(4, 2, 2, 4, 4);
-    else if (cfg == 198) launch_cfg<4, 2, 2, 4, 4, MODE, true>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s);
+    else if (cfg == 198) {
+        // The chip holds 256 of these blocks; a launch of a few more than a multiple of 256 would run its last round
+        // nearly empty (1280 rows x 14336 features: 280 tiles, two rounds for 1.09 rounds of work).  Then the feature
+        // blocks whose tiles fill whole rounds go first, and the few that remain follow as a launch of their own, which
+        // launch_cfg splits along the contraction so that it fills the chip as well.
+        const int nb = (n_tiles + 15) / 16, tb = (t_tiles + 15) / 16, total = nb * tb, rem = total % 256;
+        const int nA = (total - rem) / tb;
+        if (!force && total > 256 && rem > 0 && rem <= 128 && part != nullptr && k_tiles >= 32 && nA >= 1 && nA < nb &&
+            gemm_estimate_us(256, 256, 0.55, nA * 16, t_tiles, k_tiles, resid, true) +
+                    gemm_estimate_us(256, 256, 0.55, (nb - nA) * 16, t_tiles, k_tiles, resid, true) <
+                t198) {
+            launch_cfg<4, 2, 2, 4, 4, MODE, true>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s, 0, nA);
+            launch_cfg<4, 2, 2, 4, 4, MODE, true>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s, nA, nb - nA);
+        } else {
+            launch_cfg<4, 2, 2, 4, 4, MODE, true>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s);
+        }
+    }
     else if (cfg == 1198) launch_cfg<4, 2, 2, 4, 4, MODE, true, 1>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s);
     else if (cfg == 2198) launch_cfg<4, 2, 2, 4, 4, MODE, true, 2>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s);
     else if (cfg == 3198) launch_cfg<4, 2, 2, 4, 4, MODE, true, 3>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s);

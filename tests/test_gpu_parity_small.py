@@ -175,6 +175,33 @@ def test_bf16_prefill_every_gemm_tile_configuration(tile):
         hx.set_gemm_tile(17)
 
 
+# a launch of a few more than a multiple of 256 large GEMM tiles: the feature blocks that fill whole rounds of the chip go
+# first, the remaining one follows as a launch of its own with a split contraction.  MINIREM13: W1/W3 has 17 x 16 = 272
+# tiles at 4096 rows (SwiGLU epilogue on a feature range); MINIREMO: W_O has 8 x 33 = 264 tiles at 8448 rows (residual
+# epilogue, its sums of squares indexed by feature block).
+MINIREM13 = StageConfig("minirem13", "bf16", 1024, 8, 2, 2176, 1, 1, (0,), batch=16, seed=16)
+MINIREMO = StageConfig("miniremo", "bf16", 2048, 16, 2, 256, 1, 1, (0,), batch=33, seed=17)
+
+
+@pytest.mark.parametrize("cfg,lens", [(MINIREM13, [256] * 16), (MINIREMO, [256] * 33)])
+def test_bf16_prefill_launch_with_a_nearly_empty_last_round(cfg, lens):
+    w = _weights(cfg)
+    rank = cfg.tp_ranks[0]
+    X = generate.hidden_rows(cfg, sum(lens))
+    ora = make_oracle(cfg, rank, w)
+    oc = ora.new_cache(len(lens))
+    p_ref, h_ref = ora.prefill(oc, X, lens)
+    st = make_gpu_stage(cfg, rank, w)
+    kv = st.kv_cache_create(len(lens), max(lens) + 8)
+    p, h = gpu_prefill(st, kv, cfg, X, lens)
+    assert row_rel_err(h, h_ref) < TOL["bf16"]
+    assert row_rel_err(p, p_ref) < TOL["bf16"]
+    x = generate.hidden_rows(cfg, len(lens), stream_id=1)
+    p_ref, h_ref = ora.decode(oc, x)
+    p, h = gpu_decode(st, kv, cfg, 0, x)
+    assert row_rel_err(h, h_ref) < TOL["bf16"] and row_rel_err(p, p_ref) < TOL["bf16"]
+
+
 def test_bf16_decode_from_synthetic_context():
     """Decode-only workloads start from an installed synthetic KV context (ragged lengths here)."""
     cfg = MINI128

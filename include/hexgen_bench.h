@@ -54,10 +54,11 @@ hexgen_status_t hexgen_mfma_probe(int variant, void *sink, int iters, int blocks
 
 /* Measurement and test hook, process-wide: force one tile configuration of the prefill projection GEMM instead of
  * the choice by shape.  code names the block tile: 88 = 256 x 256 on 4 waves, 98 = 256 x 256 on 8 waves, 198 = the same
- * with the two waves of each SIMD half a k-step out of phase (the default for large launches), 84 = 256 x 128,
+ * with the two waves of each SIMD half a k-step out of phase (the default for large launches), 194 / 184 = 128 x 256 /
+ * 256 x 128 on the same two-phase loop (the defaults for launches that do not fill the chip with 198), 84 = 256 x 128,
  * 48 = 128 x 256, 94 / 49 = 128 x 256 on 8 waves (2 x 4 / 4 x 2 wave grid), 44 = 128 x 128, 72 = 448 features x 128
  * tokens on 4 waves; 0 restores the default.  (Residual-epilogue launches need 128 features per wave and fall back to
- * 84, from 72 to 198.)  HEXGEN_ERR_INVALID_ARG for any other code.
+ * 84, from 194 to 184, from 72 to 198.)  HEXGEN_ERR_INVALID_ARG for any other code.
  * Codes 1198 / 2198 / 3198 are ABLATIONS of 198 for power measurements -- the same kernel without its direct-to-LDS loads
  * inside the k-loop / with loads that only re-read the first k-step (cache hits) / without its LDS operand reads.  They
  * compute garbage (all accesses in bounds): never leave one of them set.

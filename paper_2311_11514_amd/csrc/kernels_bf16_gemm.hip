@@ -494,7 +494,7 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_mfma_kernel(const h16_t *__
 #pragma unroll
         for (int x = 0; x < FM + FT; ++x) fetch_one(fa, fb, kt, kh, x);
     };
-    static_assert(FM + FT <= FM * FT, "one operand fetch per MFMA slot");
+    static_assert(PP || FM + FT <= FM * FT, "one operand fetch per MFMA slot");
     HX_WAIT_VM((S - 3) * LPT + H1);
     HX_LDS_BARRIER();
     fetch(fa0, fb0, 0, 0);
@@ -744,7 +744,7 @@ static void launch_cfg(const h16_t *Wp, const h16_t *Xp, int N, int k_tiles, int
 // tile configuration forced for every GEMM launch of the process (0 = choose by shape); a measurement and test hook
 static std::atomic<int> g_force_tile{0};
 bool set_gemm_tile(int code) {
-    for (int ok : {0, 44, 48, 84, 88, 94, 49, 98, 72, 198, 1198, 2198, 3198})
+    for (int ok : {0, 44, 48, 84, 88, 94, 49, 98, 72, 198, 194, 184, 1198, 2198, 3198})
         if (code == ok) { g_force_tile.store(code, std::memory_order_relaxed); return true; }
     return false;
 }
@@ -795,16 +795,17 @@ static void launch_mode(const h16_t *Wp, const h16_t *Xp, int N, int K, int T, c
                         size_t part_floats, hipStream_t s) {
     const int k_tiles = K / 32, n_tiles = N / 16, t_tiles = (T + 15) / 16;
     const int force = g_force_tile.load(std::memory_order_relaxed);
-    // 198 = 256 x 256 on 8 waves with the two waves of a SIMD half a k-step out of phase; the smaller tile is 128 x 256
-    // (94), or 256 x 128 (84) for the residual epilogue.  Which one: the shorter of two estimates (gemm_estimate_us),
-    // i.e. rounds of blocks over the chip x a block's time, plus what a split contraction costs in partial sums.
+    // 198 = 256 x 256 on 8 waves with the two waves of a SIMD half a k-step out of phase; the smaller tile, on the same
+    // loop, is 128 x 256 (194), or 256 x 128 (184) for the residual epilogue.  Which one: the shorter of two estimates
+    // (gemm_estimate_us), i.e. rounds of blocks over the chip x a block's time, plus what a split contraction costs in
+    // partial sums.
     const bool resid = MODE == DEC_RESID;
     const double t198 = gemm_estimate_us(256, 256, 0.55, n_tiles, t_tiles, k_tiles, resid, part != nullptr);
-    const double tsml = gemm_estimate_us(resid ? 256 : 128, resid ? 128 : 256, 0.40, n_tiles, t_tiles, k_tiles, resid, part != nullptr);
-    int cfg = t198 <= tsml ? 198 : 94;
+    const double tsml = gemm_estimate_us(resid ? 256 : 128, resid ? 128 : 256, 0.37, n_tiles, t_tiles, k_tiles, resid, part != nullptr);
+    int cfg = t198 <= tsml ? 198 : 194;
     if (force) cfg = force;
     // the RESID epilogue emits one sum-of-squares partial per wave: its 32 FM features must be 128
-    if (MODE == DEC_RESID && cfg != 88 && cfg != 84 && cfg != 98 && cfg % 1000 != 198) cfg = cfg == 72 ? 198 : 84;
+    if (MODE == DEC_RESID && cfg != 88 && cfg != 84 && cfg != 184 && cfg != 98 && cfg % 1000 != 198) cfg = cfg == 72 ? 198 : (cfg == 194 ? 184 : 84);
     // one 128-token tile (a short prompt): 128-token block tiles; the split contraction then runs a short k-loop per
     // block with the weights coming from HBM, so the 256 x 128 tile of RESID keeps six stages in flight instead of four
     const bool short_prompt = !force && t_tiles <= 8;
@@ -833,6 +834,8 @@ static void launch_mode(const h16_t *Wp, const h16_t *Xp, int N, int K, int T, c
     else if (cfg == 1198) launch_cfg<4, 2, 2, 4, 4, MODE, true, 1>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s);
     else if (cfg == 2198) launch_cfg<4, 2, 2, 4, 4, MODE, true, 2>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s);
     else if (cfg == 3198) launch_cfg<4, 2, 2, 4, 4, MODE, true, 3>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s);
+    else if (cfg == 194) { if constexpr (MODE != DEC_RESID) launch_cfg<2, 2, 2, 4, 4, MODE, true>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s); }
+    else if (cfg == 184) launch_cfg<4, 1, 2, 4, 4, MODE, true>(Wp, Xp, N, k_tiles, n_tiles, t_tiles, T, e, part, part_floats, s);
     else if (cfg == 94) { if constexpr (MODE != DEC_RESID) HX_G(2, 2, 2, 4, 4); }
     else if (cfg == 49) { if constexpr (MODE != DEC_RESID) HX_G(2, 2, 4, 2, 4); }
     else if (cfg == 84) HX_G(4, 2, 2, 2, 4);

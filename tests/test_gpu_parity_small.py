@@ -149,7 +149,7 @@ def test_bf16_small_prefill_then_decode(cfg, lens):
             assert row_rel_err(vv.numpy().reshape(-1, cfg.head_dim), oc.v[layer][s].reshape(-1, cfg.head_dim)) < TOL["bf16"]
 
 
-@pytest.mark.parametrize("tile", [88, 98, 198, 84, 48, 94, 49, 44, 72])
+@pytest.mark.parametrize("tile", [88, 98, 198, 194, 184, 84, 48, 94, 49, 44, 72])
 def test_bf16_prefill_every_gemm_tile_configuration(tile):
     """Every instantiation of the prefill projection GEMM (4- and 8-wave blocks, 256/128-wide tiles, odd and even
     load counts per stage), forced through the library's tile hook, on a ragged prompt batch that spans several

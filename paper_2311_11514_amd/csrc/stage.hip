@@ -264,23 +264,27 @@ hexgen_status_t setup_rows(hexgen_stage *st, hexgen_kv_cache *kv, const int32_t 
         // would: 45 % of it at lengths 128..4096) and its long walks do not end up alone at the tail of the launch.
         const size_t items_off = 2 * (size_t)r.T + 3 * (size_t)batch + 1;
         int32_t *h_items = hs + items_off;
-        std::vector<std::pair<int, int>> order;         // (-last position of the block, index)
         int n_items = 0;
-        for (int i = 0; i < batch; ++i) {
-            const int n = seq_lens ? seq_lens[i] : 1;
-            for (int rb = 0; rb * kAttnRows < n; ++rb, ++n_items) {
-                h_items[2 * n_items] = i;
-                h_items[2 * n_items + 1] = rb;
-                order.emplace_back(-(kv->lens[i] + std::min((rb + 1) * kAttnRows, n)), n_items);
+        try {
+            std::vector<std::pair<int, int>> order;         // (-last position of the block, index)
+            for (int i = 0; i < batch; ++i) {
+                const int n = seq_lens ? seq_lens[i] : 1;
+                for (int rb = 0; rb * kAttnRows < n; ++rb, ++n_items) {
+                    h_items[2 * n_items] = i;
+                    h_items[2 * n_items + 1] = rb;
+                    order.emplace_back(-(kv->lens[i] + std::min((rb + 1) * kAttnRows, n)), n_items);
+                }
             }
+            std::stable_sort(order.begin(), order.end());
+            std::vector<int32_t> sorted(2 * (size_t)n_items);
+            for (int k = 0; k < n_items; ++k) {
+                sorted[2 * k] = h_items[2 * order[k].second];
+                sorted[2 * k + 1] = h_items[2 * order[k].second + 1];
+            }
+            std::copy(sorted.begin(), sorted.end(), h_items);
+        } catch (...) {                                     // no exception crosses the C boundary
+            return HEXGEN_ERR_OOM;
         }
-        std::stable_sort(order.begin(), order.end());
-        std::vector<int32_t> sorted(2 * (size_t)n_items);
-        for (int k = 0; k < n_items; ++k) {
-            sorted[2 * k] = h_items[2 * order[k].second];
-            sorted[2 * k + 1] = h_items[2 * order[k].second + 1];
-        }
-        std::copy(sorted.begin(), sorted.end(), h_items);
         r.n_items = n_items;
         w.items = w.rowmap + items_off;
         // host staging and device block share one packing: a single copy moves all the arrays

@@ -179,6 +179,11 @@ class Bench:
             per[name] = {"avg_us": round(us, 2)}
             if name in nbytes:
                 per[name]["GBps"] = round(nbytes[name] / us / 1e3, 1)
+        # the four projections together (weight bytes over the time of their launches, finishing kernels included)
+        tot_b = sum(nbytes.values())
+        tot_us = sum(per[k]["avg_us"] for k in nbytes)
+        per["projections"] = {"avg_us": round(tot_us, 2), "GBps": round(tot_b / tot_us / 1e3, 1),
+                              "hbm_frac": round(tot_b / tot_us / 1e3 / HBM_PEAK_GBS, 4)}
         st.profile_enable(0)
         b2b_ms, b2b_n = st.time_w13_decode(max(1, 256 // cfg.n_layers))
         # W1/W3 main kernel, algorithmic bytes: the weights + the rows' activation operand (hi and lo halves); the

@@ -73,6 +73,15 @@ struct DecodeEpi {
     h16_t *u;                 // compact hi/lo decode operand [T][F_l]
     int F_l;
 };
+// What the decode attention needs to finish a QKV projection whose contraction was split over blocks: it adds up the
+// partial sums of its own heads, applies 1/rms and the rotary embedding, appends the new K / V row to the cache and
+// goes on with q in registers -- the projection then needs no finishing launch (launch_decode_qkv, launch_attn_decode).
+struct QkvTail {
+    const float *part;         // [splits][T][N] partial sums; NULL: q and the cache rows are complete already
+    int splits, T, N;
+    const float *rstd;         // [T] 1/rms of the rows, left by the split kernel
+    const float *cos_tab, *sin_tab;
+};
 // ---- prefill projections with fused epilogues (kernels_bf16_gemm.hip) ----------------------------
 // Same epilogue roles as in decode (DEC_* modes), on packed operands: the input Xp is (h * gain) in
 // fragment tiles, RMSNorm enters as the per-token scale rstd derived from `ssq_in`.

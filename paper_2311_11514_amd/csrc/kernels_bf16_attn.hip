@@ -16,21 +16,145 @@
 namespace HX_NS {
 
 
+
+// ---- finishing a split QKV projection inside the decode attention (QkvTail) ---------------------------------------
+// LDS staging of what a block computes for its own (sequence, kv head): the G query heads as the MFMA's B operand
+// (hi and lo parts, heads beyond G zero) and the new K / V row.
+template <int D>
+struct QkvStage {
+    h16_t qh[16][D], ql[16][D];
+    h16_t kn[D], vn[D];
+};
+
+// Every thread of the block: adds up the split partial sums of the block's G query heads and of its K and V head for
+// row `sq` (in split order), applies 1/rms and the rotary embedding at position `pos`, and leaves q (hi + lo) and the
+// new K / V row in LDS; `append` blocks also write the row to the cache.  The QKV weight tiles are packed so that a
+// 16-feature tile holds 8 rotary pairs: features 0..7 of the tile are elements 8 tl .. 8 tl + 7 of the head, features
+// 8..15 the elements half a head further (the layout decode_epilogue<DEC_QKV> reads as well).  Ends with a barrier.
+template <int D, int NT>
+__device__ __forceinline__ void qkv_tail_stage(const QkvTail &tail, QkvStage<D> &st, int sq, int c, int G, int hq_l,
+                                               const KvGeom &kg, int pos, bool append, h16_t *kc, h16_t *vc) {
+    constexpr int TPH = D / 16, HALF = D / 2;
+    const float r = tail.rstd[sq];
+    const size_t slab = (size_t)sq * kg.seq_stride + (size_t)c * kg.smax * D;
+    for (int idx = threadIdx.x; idx < (G + 2) * TPH * 2; idx += NT) {
+        const int hh = idx / (TPH * 2), rem = idx - hh * TPH * 2, tl = rem >> 1, q2 = rem & 1;
+        const int head_g = hh < G ? c * G + hh : (hh == G ? hq_l + c : hq_l + kg.hkv_l + c);
+        const size_t col = ((size_t)head_g * TPH + tl) * 16 + 4 * q2;
+        floatx4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+        for (int ks0 = 0; ks0 < tail.splits; ks0 += 8) {         // eight splits' partials in flight at a time
+            floatx4 pl[8], ph[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float *p = tail.part + ((size_t)min(ks0 + u, tail.splits - 1) * tail.T + sq) * tail.N + col;
+                pl[u] = *reinterpret_cast<const floatx4 *>(p);
+                ph[u] = *reinterpret_cast<const floatx4 *>(p + 8);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)                           // added in split order
+                if (ks0 + u < tail.splits) { lo += pl[u]; hi += ph[u]; }
+        }
+        lo *= r;
+        hi *= r;
+        const int i0 = tl * 8 + 4 * q2;              // first of this thread's four rotary pairs
+        float ol[4], oh[4];
+        if (hh <= G) {
+            const floatx4 c4 = *reinterpret_cast<const floatx4 *>(tail.cos_tab + (size_t)pos * HALF + i0);
+            const floatx4 s4 = *reinterpret_cast<const floatx4 *>(tail.sin_tab + (size_t)pos * HALF + i0);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                ol[x] = lo[x] * c4[x] - hi[x] * s4[x];
+                oh[x] = hi[x] * c4[x] + lo[x] * s4[x];
+            }
+        } else {
+#pragma unroll
+            for (int x = 0; x < 4; ++x) { ol[x] = lo[x]; oh[x] = hi[x]; }
+        }
+        if (hh < G) {
+            uint2 a, al, b, bl;
+            split_pack2(ol[0], ol[1], a.x, al.x); split_pack2(ol[2], ol[3], a.y, al.y);
+            split_pack2(oh[0], oh[1], b.x, bl.x); split_pack2(oh[2], oh[3], b.y, bl.y);
+            *reinterpret_cast<uint2 *>(&st.qh[hh][i0]) = a;
+            *reinterpret_cast<uint2 *>(&st.ql[hh][i0]) = al;
+            *reinterpret_cast<uint2 *>(&st.qh[hh][HALF + i0]) = b;
+            *reinterpret_cast<uint2 *>(&st.ql[hh][HALF + i0]) = bl;
+        } else {
+            uint2 a, b;
+            a.x = pack_h16x2(ol[0], ol[1]); a.y = pack_h16x2(ol[2], ol[3]);
+            b.x = pack_h16x2(oh[0], oh[1]); b.y = pack_h16x2(oh[2], oh[3]);
+            h16_t *dst = hh == G ? st.kn : st.vn;
+            *reinterpret_cast<uint2 *>(dst + i0) = a;
+            *reinterpret_cast<uint2 *>(dst + HALF + i0) = b;
+            if (append) {
+                if (hh == G) {
+                    *reinterpret_cast<uint2 *>(kc + slab + kv_k_offset(pos, i0, D)) = a;
+                    *reinterpret_cast<uint2 *>(kc + slab + kv_k_offset(pos, HALF + i0, D)) = b;
+                } else {
+                    const h16_t *av = reinterpret_cast<const h16_t *>(&a), *bv = reinterpret_cast<const h16_t *>(&b);
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        vc[slab + kv_v_offset(pos, i0 + x, D)] = av[x];
+                        vc[slab + kv_v_offset(pos, HALF + i0 + x, D)] = bv[x];
+                    }
+                }
+            }
+        }
+    }
+    for (int idx = threadIdx.x; idx < (16 - G) * (D / 8); idx += NT) {      // operand columns beyond the group: zero
+        const int hh = G + idx / (D / 8), e8 = (idx % (D / 8)) * 8;
+        *reinterpret_cast<uint4 *>(&st.qh[hh][e8]) = uint4{0u, 0u, 0u, 0u};
+        *reinterpret_cast<uint4 *>(&st.ql[hh][e8]) = uint4{0u, 0u, 0u, 0u};
+    }
+    __syncthreads();
+}
+
+// The tile that holds the new row's position takes that row from LDS instead of the cache (the row is being written
+// by this very block): K fragments hold position 32 t + 16 sub + lane % 16, V^T fragments positions 4 g .. 4 g + 3 and
+// 16 + 4 g .. + 3 of the tile (kvlayout.h).
+template <int D>
+__device__ __forceinline__ void qkv_tail_patch(const QkvStage<D> &st, int p32, int j, int g, h16x8 (&ka)[D / 32],
+                                               h16x8 (&kb)[D / 32], h16x8 (&va)[D / 16]) {
+    const int sub = p32 >> 4, jp = p32 & 15;
+    if (j == jp) {
+#pragma unroll
+        for (int kt = 0; kt < D / 32; ++kt) {
+            const h16x8 nk = *reinterpret_cast<const h16x8 *>(&st.kn[kt * 32 + 8 * g]);
+            if (sub) kb[kt] = nk;
+            else ka[kt] = nk;
+        }
+    }
+    const int gp = (p32 & 15) >> 2, ep = (p32 & 3) + 4 * (p32 >> 4);
+    if (g == gp) {
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) {
+            union { h16x8 v; h16_t e[8]; } u;
+            u.v = va[dt];
+            const h16_t nv = st.vn[dt * 16 + j];
+#pragma unroll
+            for (int x = 0; x < 8; ++x) u.e[x] = x == ep ? nv : u.e[x];
+            va[dt] = u.v;
+        }
+    }
+}
+
 // One 8-wave block per (sequence, kv head); the waves interleave over the 32-position tiles of the context and
 // their (m, l, o) triples are merged through LDS in wave order.
 // Used when there are enough (sequence, kv head) pairs to fill the chip or the context is short.
 // PF: the layouts of the prefill path on both ends (used when more than 32 sequences decode one row each, which the
 // prefill kernels otherwise serve): q is read from fragment tiles (row = sequence, no lo part), o is written to them.
-template <int D, bool PF>
+// FUSE: the QKV projection of this step left split partial sums (QkvTail): the block finishes them for its own heads
+// first, appends the new K / V row to the cache and takes q and that row from LDS.
+template <int D, bool PF, bool FUSE>
 __global__ __launch_bounds__(512) void attn_decode_block_kernel(const h16_t *__restrict__ q,
-                                                               const h16_t *__restrict__ q_lo,
-                                                               const h16_t *__restrict__ kc,
-                                                               const h16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
+                                                               const h16_t *__restrict__ q_lo, h16_t *kc, h16_t *vc,
+                                                               KvGeom kg, int hq_l, int G,
                                                                const int32_t *__restrict__ row_pos,
-                                                               h16_t *__restrict__ o_act, float scale_log2e) {
+                                                               h16_t *__restrict__ o_act, float scale_log2e, QkvTail tail) {
     constexpr int KT = D / 32, DT = D / 16, W = 8;
+    static_assert(!(PF && FUSE), "the prefill path finishes its projections in their own epilogues");
     __shared__ float s_m[W][16], s_l[W][16];
     __shared__ float s_o[W][16][D];
+    __shared__ __align__(16) QkvStage<FUSE ? D : 8> s_qkv;
     const int c = blockIdx.x, sq = blockIdx.y;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 15, g = lane >> 4;
     const int n_pos = row_pos[sq] + 1;
@@ -40,24 +164,11 @@ __global__ __launch_bounds__(512) void attn_decode_block_kernel(const h16_t *__r
 
     const h16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     h16x8 qf[KT], ql[KT];
-#pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
-        const size_t qo = PF ? frag_offset(sq, head * D + kt * 32 + 8 * g, (hq_l * D) >> 5)
-                             : ((size_t)sq * hq_l + head) * D + kt * 32 + 8 * g;
-        qf[kt] = hv ? *reinterpret_cast<const h16x8 *>(q + qo) : zero;
-        ql[kt] = (hv && !PF) ? *reinterpret_cast<const h16x8 *>(q_lo + qo) : zero;
-    }
-    floatx4 oacc[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) oacc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    float m = NEG_INF, lsum = 0.f;
     const size_t slab = (size_t)sq * kg.seq_stride + (size_t)c * kg.smax * D;
     const h16x8 *ks = reinterpret_cast<const h16x8 *>(kc + slab) + lane;
     const h16x8 *vs = reinterpret_cast<const h16x8 *>(vc + slab) + lane;
-
-    for (int t = wave; t < n_t32; t += W) {
-        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-        h16x8 ka[KT], kb[KT], va[DT];
+    h16x8 ka[KT], kb[KT], va[DT];
+    auto load_tile = [&](int t) {
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) {
             ka[kt] = ks[(size_t)((2 * t) * KT + kt) * 64];
@@ -65,6 +176,36 @@ __global__ __launch_bounds__(512) void attn_decode_block_kernel(const h16_t *__r
         }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) va[dt] = vs[(size_t)(t * DT + dt) * 64];
+    };
+    if constexpr (FUSE) {
+        // the wave's first tile is requested before the projection's tail is finished: the two wait side by side
+        if (wave < n_t32) load_tile(wave);
+        qkv_tail_stage<D, 512>(tail, reinterpret_cast<QkvStage<D> &>(s_qkv), sq, c, G, hq_l, kg, n_pos - 1, true, kc, vc);
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+            qf[kt] = *reinterpret_cast<const h16x8 *>(&reinterpret_cast<QkvStage<D> &>(s_qkv).qh[j][kt * 32 + 8 * g]);
+            ql[kt] = *reinterpret_cast<const h16x8 *>(&reinterpret_cast<QkvStage<D> &>(s_qkv).ql[j][kt * 32 + 8 * g]);
+        }
+    } else {
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+            const size_t qo = PF ? frag_offset(sq, head * D + kt * 32 + 8 * g, (hq_l * D) >> 5)
+                                 : ((size_t)sq * hq_l + head) * D + kt * 32 + 8 * g;
+            qf[kt] = hv ? *reinterpret_cast<const h16x8 *>(q + qo) : zero;
+            ql[kt] = (hv && !PF) ? *reinterpret_cast<const h16x8 *>(q_lo + qo) : zero;
+        }
+    }
+    floatx4 oacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) oacc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float m = NEG_INF, lsum = 0.f;
+
+    for (int t = wave; t < n_t32; t += W) {
+        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+        if (!FUSE || t != wave) load_tile(t);
+        if constexpr (FUSE) {
+            if (t == n_t32 - 1) qkv_tail_patch<D>(reinterpret_cast<const QkvStage<D> &>(s_qkv), (n_pos - 1) & 31, j, g, ka, kb, va);
+        }
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) {
             s0 = hx_mfma16(ka[kt], ql[kt], s0);
@@ -146,18 +287,18 @@ __global__ __launch_bounds__(512) void attn_decode_block_kernel(const h16_t *__r
 // next launch.  Nobody waits for anybody: every block runs straight to its end.
 // The partials cross the chip's L2 slices: after a block barrier one wave publishes the block's stores with a
 // device-scope fence before it counts the block, and the merging block fences again before it reads.
-template <int D>
+template <int D, bool FUSE>
 __global__ __launch_bounds__(512) void attn_decode_split_kernel(const h16_t *__restrict__ q,
-                                                               const h16_t *__restrict__ q_lo,
-                                                               const h16_t *__restrict__ kc,
-                                                               const h16_t *__restrict__ vc, KvGeom kg, int hq_l, int G,
+                                                               const h16_t *__restrict__ q_lo, h16_t *kc, h16_t *vc,
+                                                               KvGeom kg, int hq_l, int G,
                                                                const int32_t *__restrict__ row_pos, int nsplit,
                                                                float *part_o, float *part_ml, unsigned int *arrived,
-                                                               h16_t *__restrict__ o_act, float scale_log2e) {
+                                                               h16_t *__restrict__ o_act, float scale_log2e, QkvTail tail) {
     constexpr int KT = D / 32, DT = D / 16, W = 8, NT = 64 * W;
     __shared__ float s_m[W][16], s_l[W][16];
     __shared__ float s_o[W][16][D];
     __shared__ int s_last;
+    __shared__ __align__(16) QkvStage<FUSE ? D : 8> s_qkv;
     const int split = blockIdx.x, c = blockIdx.y, sq = blockIdx.z;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 15, g = lane >> 4;
     const int n_pos = row_pos[sq] + 1;
@@ -173,23 +314,11 @@ __global__ __launch_bounds__(512) void attn_decode_split_kernel(const h16_t *__r
 
     const h16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     h16x8 qf[KT], ql[KT];
-#pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
-        const size_t qo = ((size_t)sq * hq_l + head) * D + kt * 32 + 8 * g;
-        qf[kt] = hv ? *reinterpret_cast<const h16x8 *>(q + qo) : zero;
-        ql[kt] = hv ? *reinterpret_cast<const h16x8 *>(q_lo + qo) : zero;
-    }
-    floatx4 oacc[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) oacc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    float m = NEG_INF, lsum = 0.f;
     const size_t slab = (size_t)sq * kg.seq_stride + (size_t)c * kg.smax * D;
     const h16x8 *ks = reinterpret_cast<const h16x8 *>(kc + slab) + lane;
     const h16x8 *vs = reinterpret_cast<const h16x8 *>(vc + slab) + lane;
-
-    for (int t = t0 + wave; t < t1; t += W) {
-        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-        h16x8 ka[KT], kb[KT], va[DT];
+    h16x8 ka[KT], kb[KT], va[DT];
+    auto load_tile = [&](int t) {
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) {
             ka[kt] = ks[(size_t)((2 * t) * KT + kt) * 64];
@@ -197,6 +326,36 @@ __global__ __launch_bounds__(512) void attn_decode_split_kernel(const h16_t *__r
         }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) va[dt] = vs[(size_t)(t * DT + dt) * 64];
+    };
+    if constexpr (FUSE) {
+        // every block of the pair finishes q for itself; the block that holds the last tile appends the new row; the
+        // wave's first tile is requested before that, so that the two wait side by side
+        if (t0 + wave < t1) load_tile(t0 + wave);
+        qkv_tail_stage<D, 512>(tail, reinterpret_cast<QkvStage<D> &>(s_qkv), sq, c, G, hq_l, kg, n_pos - 1, split == nb - 1, kc, vc);
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+            qf[kt] = *reinterpret_cast<const h16x8 *>(&reinterpret_cast<QkvStage<D> &>(s_qkv).qh[j][kt * 32 + 8 * g]);
+            ql[kt] = *reinterpret_cast<const h16x8 *>(&reinterpret_cast<QkvStage<D> &>(s_qkv).ql[j][kt * 32 + 8 * g]);
+        }
+    } else {
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+            const size_t qo = ((size_t)sq * hq_l + head) * D + kt * 32 + 8 * g;
+            qf[kt] = hv ? *reinterpret_cast<const h16x8 *>(q + qo) : zero;
+            ql[kt] = hv ? *reinterpret_cast<const h16x8 *>(q_lo + qo) : zero;
+        }
+    }
+    floatx4 oacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) oacc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float m = NEG_INF, lsum = 0.f;
+
+    for (int t = t0 + wave; t < t1; t += W) {
+        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+        if (!FUSE || t != t0 + wave) load_tile(t);
+        if constexpr (FUSE) {
+            if (t == n_t32 - 1) qkv_tail_patch<D>(reinterpret_cast<const QkvStage<D> &>(s_qkv), (n_pos - 1) & 31, j, g, ka, kb, va);
+        }
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) {
             s0 = hx_mfma16(ka[kt], ql[kt], s0);
@@ -308,28 +467,29 @@ __global__ __launch_bounds__(512) void attn_decode_split_kernel(const h16_t *__r
     }
 }
 
-void launch_attn_decode(const h16_t *q, const h16_t *q_lo, const h16_t *kc, const h16_t *vc, KvGeom kg,
+void launch_attn_decode(const h16_t *q, const h16_t *q_lo, h16_t *kc, h16_t *vc, KvGeom kg,
                         int hq_l, const int32_t *row_pos, int b, int nsplit, float *part_o, float *part_ml,
-                        unsigned int *arrived, h16_t *o_act, hipStream_t s) {
+                        unsigned int *arrived, h16_t *o_act, const QkvTail &tail, hipStream_t s) {
     const int G = hq_l / kg.hkv_l;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)kg.d);
+    const bool fuse = tail.part != nullptr;
+#define HX_BLK(DD, FF)                                                                                                   \
+    hipLaunchKernelGGL((attn_decode_block_kernel<DD, false, FF>), grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G, row_pos, \
+                       o_act, scale_log2e, tail)
+#define HX_SPL(DD, FF)                                                                                                   \
+    hipLaunchKernelGGL((attn_decode_split_kernel<DD, FF>), grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G, row_pos, nsplit, \
+                       part_o, part_ml, arrived, o_act, scale_log2e, tail)
     if (nsplit <= 1) {       // one block per (sequence, kv head), LDS merge
         dim3 grid(kg.hkv_l, b);
-        if (kg.d == 128)
-            hipLaunchKernelGGL((attn_decode_block_kernel<128, false>), grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G,
-                               row_pos, o_act, scale_log2e);
-        else
-            hipLaunchKernelGGL((attn_decode_block_kernel<64, false>), grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G,
-                               row_pos, o_act, scale_log2e);
+        if (kg.d == 128) { if (fuse) HX_BLK(128, true); else HX_BLK(128, false); }
+        else { if (fuse) HX_BLK(64, true); else HX_BLK(64, false); }
         return;
     }
     dim3 grid(nsplit, kg.hkv_l, b);
-    if (kg.d == 128)
-        hipLaunchKernelGGL(attn_decode_split_kernel<128>, grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G, row_pos,
-                           nsplit, part_o, part_ml, arrived, o_act, scale_log2e);
-    else
-        hipLaunchKernelGGL(attn_decode_split_kernel<64>, grid, dim3(512), 0, s, q, q_lo, kc, vc, kg, hq_l, G, row_pos,
-                           nsplit, part_o, part_ml, arrived, o_act, scale_log2e);
+    if (kg.d == 128) { if (fuse) HX_SPL(128, true); else HX_SPL(128, false); }
+    else { if (fuse) HX_SPL(64, true); else HX_SPL(64, false); }
+#undef HX_BLK
+#undef HX_SPL
 }
 
 // one new row per sequence on the prefill path's layouts: q and o in fragment tiles (row = sequence)
@@ -337,13 +497,15 @@ void launch_attn_decode_rows(const h16_t *q, const h16_t *kc, const h16_t *vc, K
                              const int32_t *row_pos, int b, h16_t *o_packed, hipStream_t s) {
     const int G = hq_l / kg.hkv_l;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)kg.d);
+    const QkvTail none{nullptr, 0, 0, 0, nullptr, nullptr, nullptr};
+    h16_t *kw = const_cast<h16_t *>(kc), *vw = const_cast<h16_t *>(vc);       // read only without a QkvTail
     dim3 grid(kg.hkv_l, b);
     if (kg.d == 128)
-        hipLaunchKernelGGL((attn_decode_block_kernel<128, true>), grid, dim3(512), 0, s, q, q, kc, vc, kg, hq_l, G, row_pos,
-                           o_packed, scale_log2e);
+        hipLaunchKernelGGL((attn_decode_block_kernel<128, true, false>), grid, dim3(512), 0, s, q, q, kw, vw, kg, hq_l, G, row_pos,
+                           o_packed, scale_log2e, none);
     else
-        hipLaunchKernelGGL((attn_decode_block_kernel<64, true>), grid, dim3(512), 0, s, q, q, kc, vc, kg, hq_l, G, row_pos,
-                           o_packed, scale_log2e);
+        hipLaunchKernelGGL((attn_decode_block_kernel<64, true, false>), grid, dim3(512), 0, s, q, q, kw, vw, kg, hq_l, G, row_pos,
+                           o_packed, scale_log2e, none);
 }
 
 // -------------------------------------------------------------------------------------------------

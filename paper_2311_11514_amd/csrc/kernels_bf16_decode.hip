@@ -559,7 +559,7 @@ void launch_mode(const h16_t *Wp, const h16_t *Xa, int N, int k_tiles, int T, co
 namespace {
 template <int MODE, int UT>
 void launch_splitk(const h16_t *Wp, const h16_t *Xa, int N, int k_tiles, int T, const DecodeEpi &e, float *scratch,
-                   size_t scratch_floats, hipStream_t s, hipEvent_t mid) {
+                   size_t scratch_floats, hipStream_t s, hipEvent_t mid, QkvTail *tail = nullptr) {
     const int n_tiles = N / 16, groups = (n_tiles + 7) / 8;
     // Two blocks fit a CU (registers), 512 on the chip.  The number of splits (at most 8, or 16 for a matrix of fewer than 64
     // feature groups: the finishing kernel walks them one after the other; partials within the scratch) minimises rounds of blocks x chunks per block, the time
@@ -592,6 +592,10 @@ void launch_splitk(const h16_t *Wp, const h16_t *Xa, int N, int k_tiles, int T, 
                            e.ssq_units, e.norm_dim, e.eps, rstd);
     }
     if (mid) (void)hipEventRecord(mid, s);
+    if (tail != nullptr) {          // the consumer finishes the projection (QKV -> decode attention)
+        *tail = QkvTail{scratch, splits, T, N, rstd, e.cos_tab, e.sin_tab};
+        return;
+    }
     const int n_units = n_tiles / UT, nbt = (T + 15) / 16;
     hipLaunchKernelGGL((decode_finish_kernel<MODE, UT>), dim3((n_units * nbt + 3) / 4), dim3(256), 0, s, scratch, splits, N, T,
                        n_units, e, rstd);
@@ -626,6 +630,18 @@ void launch_decode_proj(const h16_t *Wp, const h16_t *Xa, int N, int K, int T, c
         case DEC_SWIGLU: launch_mode<2, DEC_SWIGLU>(Wp, Xa, N, k_tiles, T, e, s); break;
     }
     if (mid) (void)hipEventRecord(mid, s);
+}
+
+void launch_decode_qkv(const h16_t *Wp, const h16_t *Xa, int N, int K, int T, const DecodeEpi &e, float *scratch,
+                       size_t scratch_floats, QkvTail *tail, hipStream_t s) {
+    *tail = QkvTail{nullptr, 0, T, N, nullptr, e.cos_tab, e.sin_tab};
+    const int k_tiles = K / 32;
+    // the same choice between the single-kernel and the split path as launch_decode_proj makes
+    const bool small = (size_t)N * K * sizeof(h16_t) <= ((size_t)72 << 20) && k_tiles >= 64 && T <= (K <= 4096 ? 8 : 4);
+    if (e.mode == DEC_QKV && T > 2 && !small && scratch != nullptr && scratch_floats >= (size_t)T * N + 32 && k_tiles >= SK_CH)
+        launch_splitk<DEC_QKV, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s, nullptr, tail);
+    else
+        launch_decode_proj(Wp, Xa, N, K, T, e, scratch, scratch_floats, s, nullptr);
 }
 
 // -------------------------------------------------------------------------------------------------

@@ -455,10 +455,16 @@ void attn_decode_h16(hexgen_stage *st, hexgen_kv_cache *kv, int layer, const Row
     e.ssq_in = ssq_in;
     e.hq_l = st->hq_l; e.kg = kg; e.row_pos = w.row_pos; e.cos_tab = kv->cos_tab; e.sin_tab = kv->sin_tab;
     e.q_hi = w.q; e.q_lo = w.q_lo; e.kc = kc; e.vc = vc;
-    decode_proj(st, r, ly.wqkv, w.xa_n, st->nqkv, st->H, e, PROF_QKV, s);
+    // a QKV projection with a split contraction leaves its finishing pass (sum of the partials, 1/rms, rotary
+    // embedding, cache append) to the attention kernel, whose blocks own whole heads: one launch less per layer
+    QkvTail tail{};
+    st->prof.mark(PROF_QKV, s);
+    HX_K(st->dtype, launch_decode_qkv, static_cast<const h16_t *>(ly.wqkv), w.xa_n, st->nqkv, st->H, r.T, e, st->cur->dec_part,
+         st->cur->dec_part_floats, &tail, s);
+    st->prof.mark(PROF_QKV, s);
     st->prof.mark(PROF_ATTN, s);
     HX_K(st->dtype, launch_attn_decode, w.q, w.q_lo, kc, vc, kg, st->hq_l, w.row_pos, r.batch, pick_attn_split(st, kv, r.batch), w.att_o,
-                       w.att_ml, w.att_arrived, w.xa_o, s);
+                       w.att_ml, w.att_arrived, w.xa_o, tail, s);
     st->prof.mark(PROF_ATTN, s);
 }
 

@@ -285,8 +285,9 @@ __global__ __launch_bounds__(512) void attn_decode_block_kernel(const h16_t *__r
 // head.  Blocks of one (sequence, kv head) then count themselves on a device counter; whichever arrives LAST merges
 // the partials -- in split order, so the result does not depend on who that was -- and resets the counter for the
 // next launch.  Nobody waits for anybody: every block runs straight to its end.
-// The partials cross the chip's L2 slices: after a block barrier one wave publishes the block's stores with a
-// device-scope fence before it counts the block, and the merging block fences again before it reads.
+// The partials cross the chip's L2 slices: they are written with device-scope stores and read with device-scope
+// loads (no fence: a fence would write back and invalidate the die's whole L2); a block counts itself once every
+// lane's store counter has drained.
 template <int D, bool FUSE>
 __global__ __launch_bounds__(512) void attn_decode_split_kernel(const h16_t *__restrict__ q,
                                                                const h16_t *__restrict__ q_lo, h16_t *kc, h16_t *vc,

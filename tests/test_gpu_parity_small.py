@@ -261,7 +261,8 @@ def test_bf16_decode_batch_sizes(cfg, b):
         assert row_rel_err(h, h_ref) < TOL["bf16"] and row_rel_err(p, p_ref) < TOL["bf16"]
 
 
-@pytest.mark.parametrize("cfg,ctx", [(MINI128, [1700, 40, 1537]), (MINI64, [2100]), (MINI64, [5, 1600]), (MINIG16, [1800, 33])])
+@pytest.mark.parametrize("cfg,ctx", [(MINI128, [1700, 40, 1537]), (MINI64, [2100]), (MINI64, [5, 1600]), (MINIG16, [1800, 33]),
+                                     (MINI64, [16500]), (MINI128, [9001, 300])])
 def test_bf16_decode_long_context_split_over_blocks(cfg, ctx):
     """Few sequences with a long context: the attention of one (sequence, kv head) is split over several blocks and
     merged by the block that finishes last.  Ragged lengths leave the short sequences' later splits empty; the second

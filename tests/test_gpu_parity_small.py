@@ -115,14 +115,17 @@ def test_tiny_f32_group_mode_greedy_tokens():
 
 @pytest.mark.parametrize("cfg,lens", [(MINI128, [37, 5, 64]), (MINI64, [16, 33]), (MINI2K, [70]), (MINI2K, [100, 29, 150]),
                                       (MINIRAG, [90]), (MINIRAG, [128]), (MINIRAG, [129, 3]),
-                                      (MINI64, [1, 128, 129, 256, 5, 127, 130, 64, 33, 257, 2])])
+                                      (MINI64, [1, 128, 129, 256, 5, 127, 130, 64, 33, 257, 2]),
+                                      (MINI2K, [300, 212]), (MINI2K, [520, 500])])
 def test_bf16_small_prefill_then_decode(cfg, lens):
     """Short prompts: few token tiles, so the projections with at least 32 k-tiles split their contraction over
     several blocks and finish in a second pass: up to 128 rows through the skinny kernel (weights in a register ring),
     beyond through the LDS-staged kernel; MINI64 (16 k-tiles) does neither.  MINIRAG has a ragged last feature block
     and an odd number of k-tiles; 128 and 129 + 3 rows sit on either side of the one-token-tile limit.  The batch of
     eleven prompts around the 128-row block size gives the prefill attention a work list of 16 (sequence, block) pairs
-    in an order that differs from the batch order (longest walks first, dealt over the XCDs)."""
+    in an order that differs from the batch order (longest walks first, dealt over the XCDs).  512 and 1020 rows on
+    MINI2K: split launches of 12 to 88 tiles, whose second pass finishes a tile with four blocks (up to 64 tiles) or
+    two (W1/W3 at 1020 rows), each with its share of the tile's waves."""
     w = _weights(cfg)
     rank = cfg.tp_ranks[0]
     X = generate.hidden_rows(cfg, sum(lens))

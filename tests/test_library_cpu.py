@@ -390,3 +390,19 @@ def test_search_on_the_large_pool_keeps_its_invariants():
         cost, _ = hx.sched_pipeline_layout(dict(pool, count=g["tau"]), task, g["layers"], True)
         assert abs(cost - g["latency"]) <= 1e-12 * cost
     assert res["attainment"] == hx.slo_attainment(arrival, [[g["latency"]] for g in res["groups"]], [5 * min(lat0)])
+
+
+def test_bench_refuses_more_than_one_gpu_and_a_missing_gpu():
+    """bench.py measures one GPU: `--gpus 2` ends with a message and a non-zero status before anything is imported, and
+    without a GPU the default run fails loudly instead of timing anything on the CPU."""
+    import os
+    import subprocess
+    import sys
+    import torch
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, cwd=root)
+    assert p.returncode != 0 and "ONE GPU" in p.stderr and p.stdout.strip() == ""
+    if not torch.cuda.is_available():
+        p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "1", "--warmup", "0"], capture_output=True,
+                           text=True, cwd=root)
+        assert p.returncode != 0 and "needs a GPU" in p.stderr and p.stdout.strip() == ""

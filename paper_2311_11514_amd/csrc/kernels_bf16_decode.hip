@@ -610,6 +610,23 @@ void launch_decode_proj(const h16_t *Wp, const h16_t *Xa, int N, int K, int T, c
     // fetches the rows' operand pieces itself (an L2 read of T x K x 4 bytes per block, which is what limits this to
     // few rows, fewer when the contraction is long), and needs enough k-tiles per wave to fill its request ring.
     const bool small = (size_t)N * K * sizeof(h16_t) <= ((size_t)72 << 20) && k_tiles >= 64 && T <= (K <= 4096 ? 8 : 4);
+    // A residual projection with a short contraction (W_O of a narrow shard: 1024 or 2048 long) is one kernel as well:
+    // a block holds complete dot products after 4 (8) k-tiles per wave, its ring sized to exactly that, and what the
+    // split path adds -- partial sums, a second launch -- costs more than the rows' operand pieces fetched per block.
+    // Measured on 70B shards, W_O per layer: TP8 (32 k-tiles) 3 / 8 / 16 / 17 / 32 rows 11.3 / 12.0 / 12.3 / 12.9 / 13.0 ->
+    // 8.1 / 8.5 / 9.7 / 10.8 / 12.8 us; TP4 (64 k-tiles) 9 / 16 rows 15.3 / 15.9 -> 12.6 / 14.4, but 32 rows 17.7 -> 21.8.
+    const bool short_k = e.mode == DEC_RESID && T > 2 && !small && k_tiles >= 8 &&
+                         ((k_tiles <= 32 && T <= 32) || (k_tiles <= 64 && T <= 16));
+    if (short_k) {
+        if (k_tiles <= 32) {
+            if (T <= 16) launch_one<1, 1, 4, DEC_RESID, false, 1>(Wp, Xa, N, k_tiles, T, e, s);
+            else launch_one<2, 1, 4, DEC_RESID, false, 1>(Wp, Xa, N, k_tiles, T, e, s);
+        } else {
+            launch_one<1, 1, 8, DEC_RESID, false, 1>(Wp, Xa, N, k_tiles, T, e, s);
+        }
+        if (mid) (void)hipEventRecord(mid, s);
+        return;
+    }
     if (T > 2 && !small && scratch != nullptr && scratch_floats >= (size_t)T * N + 32 && k_tiles >= SK_CH) {
         switch (e.mode) {
             case DEC_RAW: launch_splitk<DEC_RAW, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s, mid); break;
@@ -637,7 +654,9 @@ void launch_decode_qkv(const h16_t *Wp, const h16_t *Xa, int N, int K, int T, co
     *tail = QkvTail{nullptr, 0, T, N, nullptr, e.cos_tab, e.sin_tab};
     const int k_tiles = K / 32;
     // the same choice between the single-kernel and the split path as launch_decode_proj makes
-    const bool small = (size_t)N * K * sizeof(h16_t) <= ((size_t)72 << 20) && k_tiles >= 64 && T <= (K <= 4096 ? 8 : 4);
+    // (a matrix of fewer than 128 feature tiles would run the single kernel on that many blocks: TP8's 80 tiles with
+    // 3 / 4 rows took 14.8 / 15.0 us against 10.0 / 10.4 split, 2.5 us per layer after the attention's longer start)
+    const bool small = (size_t)N * K * sizeof(h16_t) <= ((size_t)72 << 20) && k_tiles >= 64 && T <= (K <= 4096 ? 8 : 4) && N / 16 >= 128;
     if (e.mode == DEC_QKV && T > 2 && !small && scratch != nullptr && scratch_floats >= (size_t)T * N + 32 && k_tiles >= SK_CH)
         launch_splitk<DEC_QKV, 1>(Wp, Xa, N, k_tiles, T, e, scratch, scratch_floats, s, nullptr, tail);
     else

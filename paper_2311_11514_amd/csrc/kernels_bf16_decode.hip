@@ -324,13 +324,28 @@ __global__ __launch_bounds__(WAVES * 64) void decode_proj_kernel(const h16_t *__
             if (!XLDS) __builtin_amdgcn_sched_barrier(0);       // keep each refill right behind its slot's use
         }
     }
+    // The last full round is refilled as well, with the wave's remaining (fewer than UNROLL) k-tiles, so that those are
+    // in flight while the round is consumed instead of being fetched one by one behind it; slots past the last k-tile
+    // re-read it (unconditional requests, see above) and are not used.  With no full round at all the first ring round,
+    // requested at kernel start, already is this remainder.
+    const int kt_rem = wave + rounds * UNROLL * WAVES;       // the wave's first k-tile beyond its full rounds
     if (rounds > 0) {
+        if (kt_rem < k_tiles) {       // (uniform over the wave; a wave without remainder issues no request it does not use)
 #pragma unroll
-        for (int i = 0; i < UNROLL; ++i) contract(i, wave + ((rounds - 1) * UNROLL + i) * WAVES);
+            for (int i = 0; i < UNROLL; ++i) {
+                contract(i, wave + ((rounds - 1) * UNROLL + i) * WAVES);
+                request(i, min(kt_rem + i * WAVES, k_tiles - 1));
+                if (!XLDS) __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < UNROLL; ++i) contract(i, wave + ((rounds - 1) * UNROLL + i) * WAVES);
+        }
     }
-    for (int kt = wave + rounds * UNROLL * WAVES; kt < k_tiles; kt += WAVES) {       // fewer than UNROLL tiles left
-        request(0, kt);
-        contract(0, kt);
+#pragma unroll
+    for (int i = 0; i < UNROLL; ++i) {
+        const int kt = kt_rem + i * WAVES;       // uniform over the wave
+        if (kt < k_tiles) contract(i, kt);
     }
 
 #pragma unroll
@@ -546,6 +561,10 @@ void launch_mode(const h16_t *Wp, const h16_t *Xa, int N, int k_tiles, int T, co
     // 17.9 -> 16.6 us and W2 44.0 -> 43.4 at one row, W1/W3 81.0 -> 77.9 at two rows and unchanged at one).  The
     // QKV projection keeps the staged operand: through the ring it loses 3.5 us.
     if ((MODE == DEC_RESID || MODE == DEC_SWIGLU) && T <= 2) {
+        // (a contraction of at most 32 k-tiles gives a wave 4 of them: a ring of 4 requests nothing it does not use)
+        if constexpr (UT == 1) {
+            if (k_tiles <= 32) { launch_one<1, 1, 4, MODE, false, 1>(Wp, Xa, N, k_tiles, T, e, s); return; }
+        }
         launch_one<1, UT, 8 / UT, MODE, false, 1>(Wp, Xa, N, k_tiles, T, e, s);
         return;
     }

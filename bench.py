@@ -222,6 +222,9 @@ def main():
     ap.add_argument("--no-configs", action="store_true", help="skip the other configurations' legs")
     ap.add_argument("--no-head", action="store_true", help="skip the LM-head leg (model end next to the last stage)")
     ap.add_argument("--no-sched", action="store_true", help="skip the host-only scheduler-search leg")
+    ap.add_argument("--short-prompts", action="store_true",
+                    help="also time one prompt of 128 and of 512 rows on the headline stage (the split-contraction and skinny-kernel "
+                         "regime; the configurations leg does this for l70_tp4_prefill)")
     ap.add_argument("--calibrate", action="store_true",
                     help="measure what a plain streaming kernel and a register-resident MFMA loop sustain, then exit")
     args = ap.parse_args()
@@ -296,6 +299,8 @@ def main():
                                       "flops_per_launch": f, "avg_launch_us": us, "launches_timed": n}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(torch, be, nproc)
+    if args.short_prompts:
+        result["one_short_prompt"] = short_prompts(torch, be)
     summary = {cfg.name: {"decode": dec, **({"prefill": {k: v for k, v in pre.items() if k != "gemm"}} if pre else {})}}
     del be
     torch.cuda.empty_cache()

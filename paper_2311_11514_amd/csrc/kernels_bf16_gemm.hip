@@ -621,25 +621,33 @@ __global__ __launch_bounds__(64 * WM * WT) void gemm_finish_kernel(const float *
 // tiles go to `part` in the layout gemm_finish_kernel<1, 1, 4, 1> reads (four 32-token blocks per feature block).
 // -------------------------------------------------------------------------------------------------
 constexpr int SKINNY_RING = 6;          // measured: 4, 6 and 8 run alike (the CU's load issue rate paces the kernel)
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t *__restrict__ Wp, const h16_t *__restrict__ Xp,
-                                                         int k_tiles, int n_tiles, int t_tiles, int total,
-                                                         float *__restrict__ part) {
+// KG = 2: a block of 8 waves = two groups of 4, each group walking one half of the block's share of the contraction
+// in step with the other (one barrier serves both) and the second group's results added to the first's through LDS
+// before anything is stored: as many waves and k-steps per wave as two blocks of 4 on two splits, half the partial sums.
+template <int KG>
+__global__ __launch_bounds__(256 * KG) void gemm_skinny_kernel(const h16_t *__restrict__ Wp, const h16_t *__restrict__ Xp,
+                                                              int k_tiles, int n_tiles, int t_tiles, int total,
+                                                              float *__restrict__ part) {
     constexpr int RING = SKINNY_RING;
-    __shared__ h16x8 xs[2][8 * 64];                 // two k-steps of the 8 token tiles
+    __shared__ h16x8 xs[KG][2][8 * 64];             // per group: two k-steps of the 8 token tiles
     const int id = blockIdx.x;                       // 128-feature block
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int k0 = (int)((long)blockIdx.y * k_tiles / gridDim.y);
-    const int k_len = (int)((long)(blockIdx.y + 1) * k_tiles / gridDim.y) - k0;
+    const int kg = wave >> 2, w4 = wave & 3;         // k-group, wave inside the group (32 features each)
+    const int b0 = (int)((long)blockIdx.y * k_tiles / gridDim.y);
+    const int b_len = (int)((long)(blockIdx.y + 1) * k_tiles / gridDim.y) - b0;       // the block's k-steps ...
+    const int g0 = (int)((long)kg * b_len / KG);
+    const int k0 = b0 + g0, k_len = (int)((long)(kg + 1) * b_len / KG) - g0;          // ... and this group's
+    const int steps = (b_len + KG - 1) / KG;         // k-steps every wave of the block walks (the longer group's)
 
     // weights: lane l of k-half kh takes slot (l % 16) + 16 (l / 32) + 32 kh of tile t16 + (l % 32) / 16
-    const int t16 = min(id * 8 + wave * 2 + ((lane & 31) >> 4), n_tiles - 1);
+    const int t16 = min(id * 8 + w4 * 2 + ((lane & 31) >> 4), n_tiles - 1);
     const h16x8 *wsrc = reinterpret_cast<const h16x8 *>(Wp) + ((size_t)k0 * n_tiles + t16) * 64 + (lane & 15) + 16 * (lane >> 5);
     const size_t wstep = (size_t)n_tiles * 64;
-    // activations: wave w copies token tiles 2 w and 2 w + 1 of each k-step (clamped to the last valid tile)
+    // activations: wave w of a group copies token tiles 2 w and 2 w + 1 of each k-step (clamped to the last valid tile)
     const h16x8 *xsrc[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
-        xsrc[i] = reinterpret_cast<const h16x8 *>(Xp) + ((size_t)min(wave * 2 + i, t_tiles - 1) * k_tiles + k0) * 64 + lane;
+        xsrc[i] = reinterpret_cast<const h16x8 *>(Xp) + ((size_t)min(w4 * 2 + i, t_tiles - 1) * k_tiles + k0) * 64 + lane;
     const int frag = ((lane & 31) >> 4) * 64 + (lane & 15) + 16 * (lane >> 5);
 
     floatx16 acc[4];
@@ -662,11 +670,12 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t *__restric
         a[slot][1] = __builtin_nontemporal_load(src + 32);
     };
     auto store_x = [&](int slot, int kt) {
-        xs[kt & 1][(wave * 2) * 64 + lane] = xq[slot][0];
-        xs[kt & 1][(wave * 2 + 1) * 64 + lane] = xq[slot][1];
+        xs[kg][kt & 1][(w4 * 2) * 64 + lane] = xq[slot][0];
+        xs[kg][kt & 1][(w4 * 2 + 1) * 64 + lane] = xq[slot][1];
     };
     auto step = [&](int slot, int kt) {
-        const h16x8 *sb = xs[kt & 1] + frag;
+        if (KG > 1 && kt >= k_len) return;          // the shorter group's last k-step (uniform over the wave)
+        const h16x8 *sb = xs[kg][kt & 1] + frag;
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
@@ -681,7 +690,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t *__restric
 #pragma unroll
     for (int i = 0; i < RING; ++i) request(i, i);
     store_x(0, 0);
-    const int rounds = k_len / RING;
+    const int rounds = steps / RING;
     for (int rd = 0; rd < rounds; ++rd) {
 #pragma unroll
         for (int i = 0; i < RING; ++i) {
@@ -696,11 +705,34 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t *__restric
 #pragma unroll
     for (int i = 0; i < RING; ++i) {
         const int kt = rounds * RING + i;
-        if (kt < k_len) {                 // uniform over the block
+        if (kt < steps) {                 // uniform over the block
             lds_barrier();
             store_x((i + 1) % RING, kt + 1);
             step(i, kt);
         }
+    }
+    if constexpr (KG == 2) {
+        // group 1 hands its results to group 0, two of the four token blocks at a time, through the 32 KB of the staging
+        // buffers (4 waves x 2 tiles x 16 registers x 64 lanes of fp32); group 0 + group 1, in that order, every time
+        float *red = reinterpret_cast<float *>(&xs[0][0][0]);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            __syncthreads();              // the staging buffers (first pass) or the previous pass's values are no longer read
+            if (kg == 1) {
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) red[((w4 * 2 + jj) * 16 + r) * 64 + lane] = acc[2 * half + jj][r];
+            }
+            __syncthreads();
+            if (kg == 0) {
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[2 * half + jj][r] += red[((w4 * 2 + jj) * 16 + r) * 64 + lane];
+            }
+        }
+        if (kg != 0) return;
     }
     // result tile (32 features x token block j) of this wave, in the layout gemm_finish_kernel<1, 1, 4, 1> reads with
     // four token blocks per feature block: the finishing pass then has four times as many (smaller) blocks
@@ -708,7 +740,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t *__restric
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            *reinterpret_cast<floatx4 *>(part + ((((size_t)blockIdx.y * total + id) * 4 + j) * 4 + wave) * 1024 + q * 256 + lane * 4) =
+            *reinterpret_cast<floatx4 *>(part + ((((size_t)blockIdx.y * total + id) * 4 + j) * 4 + w4) * 1024 + q * 256 + lane * 4) =
                 floatx4{acc[j][4 * q], acc[j][4 * q + 1], acc[j][4 * q + 2], acc[j][4 * q + 3]};
 }
 
@@ -797,8 +829,19 @@ static bool launch_skinny(const h16_t *Wp, const h16_t *Xp, int N, int k_tiles, 
     int splits = std::max(1, std::min({8, 512 / n_blocks, k_tiles / 16}));
     while (splits > 1 && (size_t)splits * n_blocks * tile_floats > part_floats) --splits;
     if ((size_t)splits * n_blocks * tile_floats > part_floats) return false;
-    hipLaunchKernelGGL(gemm_skinny_kernel, dim3(n_blocks, splits), dim3(256), 0, s, Wp, Xp, k_tiles, n_tiles, t_tiles,
-                       n_blocks, part);
+    // An even number of splits over enough blocks runs as half as many splits of 8-wave blocks, the pairs of splits summed
+    // inside the block: half the partial sums written, and read by the finishing pass.  Measured on the TP4 shard of the
+    // 70B shape at 128 rows: W1/W3 (112 blocks x 4 -> x 2) 64.8 -> 59.4 us, W2 (64 x 8 -> x 4) 43.0 -> 38.5, 158.9 -> 149.8 us
+    // per layer; with fewer than 160 blocks left the CUs that stay empty cost more (W_O 64 x 4 -> x 2: 22.1 -> 25.9,
+    // QKV 20 x 8 -> x 4: 25.6 -> 32.4), and 8-wave blocks at an unchanged number of splits gain nothing there either.
+    if (splits % 2 == 0 && n_blocks * (splits / 2) >= 160) {
+        splits /= 2;
+        hipLaunchKernelGGL(gemm_skinny_kernel<2>, dim3(n_blocks, splits), dim3(512), 0, s, Wp, Xp, k_tiles, n_tiles, t_tiles,
+                           n_blocks, part);
+    } else {
+        hipLaunchKernelGGL(gemm_skinny_kernel<1>, dim3(n_blocks, splits), dim3(256), 0, s, Wp, Xp, k_tiles, n_tiles, t_tiles,
+                           n_blocks, part);
+    }
     hipLaunchKernelGGL((gemm_finish_kernel<1, 1, 4, 1, MODE>), dim3(n_blocks * 4), dim3(256), 0, s, part, splits, N, n_tiles,
                        T, n_blocks * 4, 4, e, 1, 4, 0, 1);
     return true;

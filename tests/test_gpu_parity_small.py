@@ -19,6 +19,9 @@ MINI2K = StageConfig("mini2k", "bf16", 2048, 16, 4, 5632, 2, 2, (1,), batch=4, s
 MINIRAG = StageConfig("minirag", "bf16", 1024, 8, 2, 2880, 2, 2, (0,), batch=2, seed=14)
 # 16 query heads on one kv head: every column of the decode attention's 16-column MFMA results is a live head
 MINIG16 = StageConfig("minig16", "bf16", 1024, 16, 1, 2816, 2, 1, (0,), batch=2, seed=15)
+# wide enough (40 to 64 feature blocks, 128 to 160 k-tiles) that a short prompt's skinny launches pair their splits inside
+# 8-wave blocks, in all four epilogues
+MINI5K = StageConfig("mini5k", "bf16", 5120, 40, 8, 4096, 1, 1, (0,), batch=1, seed=16)
 
 
 def _weights(cfg, n_layers=None):
@@ -116,7 +119,7 @@ def test_tiny_f32_group_mode_greedy_tokens():
 @pytest.mark.parametrize("cfg,lens", [(MINI128, [37, 5, 64]), (MINI64, [16, 33]), (MINI2K, [70]), (MINI2K, [100, 29, 150]),
                                       (MINIRAG, [90]), (MINIRAG, [128]), (MINIRAG, [129, 3]),
                                       (MINI64, [1, 128, 129, 256, 5, 127, 130, 64, 33, 257, 2]),
-                                      (MINI2K, [300, 212]), (MINI2K, [520, 500])])
+                                      (MINI2K, [300, 212]), (MINI2K, [520, 500]), (MINI5K, [128]), (MINI5K, [61, 40])])
 def test_bf16_small_prefill_then_decode(cfg, lens):
     """Short prompts: few token tiles, so the projections with at least 32 k-tiles split their contraction over
     several blocks and finish in a second pass: up to 128 rows through the skinny kernel (weights in a register ring),
@@ -125,7 +128,8 @@ def test_bf16_small_prefill_then_decode(cfg, lens):
     eleven prompts around the 128-row block size gives the prefill attention a work list of 16 (sequence, block) pairs
     in an order that differs from the batch order (longest walks first, dealt over the XCDs).  512 and 1020 rows on
     MINI2K: split launches of 12 to 88 tiles, whose second pass finishes a tile with four blocks (up to 64 tiles) or
-    two (W1/W3 at 1020 rows), each with its share of the tile's waves."""
+    two (W1/W3 at 1020 rows), each with its share of the tile's waves.  MINI5K: the skinny kernel's 8-wave form (two
+    groups of waves on two halves of a block's contraction, summed through LDS) in every epilogue, full and ragged tile."""
     w = _weights(cfg)
     rank = cfg.tp_ranks[0]
     X = generate.hidden_rows(cfg, sum(lens))

@@ -302,8 +302,10 @@ def main():
     if args.short_prompts:
         result["one_short_prompt"] = short_prompts(torch, be)
     summary = {cfg.name: {"decode": dec, **({"prefill": {k: v for k, v in pre.items() if k != "gemm"}} if pre else {})}}
-    del be
-    torch.cuda.empty_cache()
+    # The headline's stage stays allocated while the other configurations run (they need a few GB each): on this driver a
+    # process that has just freed a large allocation runs the same kernels on the same buffers a few percent slower (the
+    # TP2 batch-1 leg 165-166 us per layer behind the freed 137 GB stage, 160-162 with it still resident or in a process
+    # of its own).
 
     if not args.no_configs:
         for name in CONFIG_ORDER:

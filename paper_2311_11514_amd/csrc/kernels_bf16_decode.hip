@@ -1,7 +1,10 @@
-// Decode projections (T <= 32 token rows): a weight-streaming skinny GEMM on the matrix cores with the
-// whole sub-layer glue fused into its tail.  No scratch buffers, no atomics, no second kernel.
+// Decode projections (T <= 32 token rows): weight-streaming skinny GEMMs on the matrix cores with the
+// whole sub-layer glue fused into their tails.  Two forms: decode_proj_kernel (one or two rows, small or short
+// matrices: one kernel, complete dot products per block, no scratch buffers, no atomics) and, further down,
+// decode_splitk_kernel + decode_finish_kernel (3 to 32 rows: operand shared through LDS, contraction split over
+// blocks); launch_decode_proj chooses.
 //
-// Main loop.  Each wave streams 1 KB weight tiles with one 128-bit load per lane (fully coalesced,
+// Main loop of decode_proj_kernel.  Each wave streams 1 KB weight tiles with one 128-bit load per lane (fully coalesced,
 // non-temporal) and feeds them to v_mfma_f32_16x16x32_bf16 against a 16-token activation tile: 16 MFMA
 // cycles per KB, a quarter of what unpacking bf16 on the vector ALU would cost, so the kernel stays
 // HBM-bound up to 32 rows.  Activations arrive as hi + lo bf16 pairs (two MFMAs per tile, free here).

@@ -22,6 +22,8 @@ MINIG16 = StageConfig("minig16", "bf16", 1024, 16, 1, 2816, 2, 1, (0,), batch=2,
 # wide enough (40 to 64 feature blocks, 128 to 160 k-tiles) that a short prompt's skinny launches pair their splits inside
 # 8-wave blocks, in all four epilogues
 MINI5K = StageConfig("mini5k", "bf16", 5120, 40, 8, 4096, 1, 1, (0,), batch=1, seed=16)
+# 140 k-tiles in 4 splits of 35: the two wave groups of an 8-wave skinny block walk 17 and 18 k-steps (QKV, 45 feature blocks)
+MINIODD = StageConfig("miniodd", "bf16", 4480, 35, 5, 4480, 1, 1, (0,), batch=1, seed=17)
 
 
 def _weights(cfg, n_layers=None):
@@ -119,7 +121,7 @@ def test_tiny_f32_group_mode_greedy_tokens():
 @pytest.mark.parametrize("cfg,lens", [(MINI128, [37, 5, 64]), (MINI64, [16, 33]), (MINI2K, [70]), (MINI2K, [100, 29, 150]),
                                       (MINIRAG, [90]), (MINIRAG, [128]), (MINIRAG, [129, 3]),
                                       (MINI64, [1, 128, 129, 256, 5, 127, 130, 64, 33, 257, 2]),
-                                      (MINI2K, [300, 212]), (MINI2K, [520, 500]), (MINI5K, [128]), (MINI5K, [61, 40])])
+                                      (MINI2K, [300, 212]), (MINI2K, [520, 500]), (MINI5K, [128]), (MINI5K, [61, 40]), (MINIODD, [128]), (MINIODD, [77])])
 def test_bf16_small_prefill_then_decode(cfg, lens):
     """Short prompts: few token tiles, so the projections with at least 32 k-tiles split their contraction over
     several blocks and finish in a second pass: up to 128 rows through the skinny kernel (weights in a register ring),
@@ -129,7 +131,8 @@ def test_bf16_small_prefill_then_decode(cfg, lens):
     in an order that differs from the batch order (longest walks first, dealt over the XCDs).  512 and 1020 rows on
     MINI2K: split launches of 12 to 88 tiles, whose second pass finishes a tile with four blocks (up to 64 tiles) or
     two (W1/W3 at 1020 rows), each with its share of the tile's waves.  MINI5K: the skinny kernel's 8-wave form (two
-    groups of waves on two halves of a block's contraction, summed through LDS) in every epilogue, full and ragged tile."""
+    groups of waves on two halves of a block's contraction, summed through LDS) in every epilogue, full and ragged tile;
+    MINIODD: halves of unequal length."""
     w = _weights(cfg)
     rank = cfg.tp_ranks[0]
     X = generate.hidden_rows(cfg, sum(lens))
